@@ -1,0 +1,170 @@
+"""CPU oracle for the TAO per-operator tolerance engine -- TEST INFRASTRUCTURE.
+
+Thin ctypes/numpy front end of oracle/tao_oracle.c (plain C, binary64 with
+directed rounding).  Only tests, the smoke check and the benchmark's
+cpu_baseline leg may import this package; the product path never does, and
+this package imports nothing from the GPU library.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+NBINS = 2048
+
+LAYERNORM, RMSNORM, BN_AFFINE, SUM, MEAN = 0, 1, 2, 3, 4
+GELU_ERF, SILU, MUL, ADD, RELU = 0, 1, 2, 3, 4
+UNDERFLOW_TERMS = 1
+
+
+class Model(ctypes.Structure):
+    """Floating-point model (App. A.1) and intrinsic accuracy constants (Sec. 3.1)."""
+    _fields_ = [("u", ctypes.c_double), ("mode", ctypes.c_int), ("lam", ctypes.c_double),
+                ("c_exp", ctypes.c_double), ("c_erf", ctypes.c_double),
+                ("c_rsqrt", ctypes.c_double), ("c_div", ctypes.c_double),
+                ("flags", ctypes.c_uint)]
+
+    def __init__(self, u=2.0 ** -24, mode=0, lam=4.0, c_exp=2.0, c_erf=2.0, c_rsqrt=2.0,
+                 c_div=2.0, flags=0):
+        super().__init__(u, mode, lam, c_exp, c_erf, c_rsqrt, c_div, flags)
+
+
+class Profile(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_uint64), ("violations", ctypes.c_uint64),
+                ("nan_count", ctypes.c_uint64), ("max_rel", ctypes.c_float),
+                ("accept", ctypes.c_uint32), ("p50_bin", ctypes.c_uint32),
+                ("p99_bin", ctypes.c_uint32), ("p999_bin", ctypes.c_uint32),
+                ("p50", ctypes.c_float), ("p99", ctypes.c_float), ("p999", ctypes.c_float),
+                ("pad_", ctypes.c_uint32), ("hist", ctypes.c_uint64 * NBINS)]
+
+    def as_dict(self):
+        return {"n": int(self.n), "violations": int(self.violations),
+                "nan_count": int(self.nan_count), "max_rel": float(self.max_rel),
+                "accept": int(self.accept), "p50_bin": int(self.p50_bin),
+                "p99_bin": int(self.p99_bin), "p999_bin": int(self.p999_bin),
+                "p50": float(self.p50), "p99": float(self.p99), "p999": float(self.p999),
+                "hist": np.ctypeslib.as_array(self.hist).copy()}
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        L = ctypes.CDLL(path)
+        fp = ctypes.POINTER(ctypes.c_float)
+        mp = ctypes.POINTER(Model)
+        L.taoo_gamma.restype = ctypes.c_double
+        L.taoo_gamma.argtypes = [ctypes.c_long, mp]
+        L.taoo_bound_linear.argtypes = [fp, fp, fp, fp] + [ctypes.c_long] * 6 + [ctypes.c_int] + \
+            [ctypes.c_long] * 4 + [mp]
+        L.taoo_bound_softmax.argtypes = [fp, fp, fp, ctypes.c_long, ctypes.c_long, ctypes.c_long, mp]
+        L.taoo_bound_norm.argtypes = [ctypes.c_int, fp, fp, fp, fp, ctypes.c_double, fp,
+                                      ctypes.c_long, ctypes.c_long, ctypes.c_long, mp]
+        L.taoo_bound_act.argtypes = [ctypes.c_int, fp, fp, fp, fp, ctypes.c_long, mp]
+        L.taoo_check_and_profile.argtypes = [fp, fp, fp, ctypes.c_long, ctypes.c_double,
+                                             ctypes.c_double, ctypes.POINTER(Profile)]
+        L.taoo_rel_errors.argtypes = [fp, fp, ctypes.c_long, ctypes.c_double, fp]
+        L.taoo_num_threads.restype = ctypes.c_int
+        L.taoo_profile_size.restype = ctypes.c_size_t
+        assert L.taoo_profile_size() == ctypes.sizeof(Profile)
+        _lib = L
+    return _lib
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _chk(rc):
+    if rc != 0:
+        raise ValueError("oracle status %d" % rc)
+
+
+def gamma(k, model=None):
+    """Gamma(k) rounded up in binary64 (App. A.1 Eq. gamma-def; Sec. 3.1 probabilistic form)."""
+    model = model or Model()
+    return lib().taoo_gamma(int(k), ctypes.byref(model))
+
+
+def bound_linear(A, W, bias=None, trans_w=False, model=None):
+    """tau[..., M, N] for A[..., M, K] and W[..., N, K] (or [..., K, N] with trans_w)."""
+    model = model or Model()
+    A = _f32(A); W = _f32(W)
+    batched = A.ndim == 3
+    A3 = A if batched else A[None]
+    W3 = W if W.ndim == 3 else W[None]
+    B, M, K = A3.shape
+    N = W3.shape[2] if trans_w else W3.shape[1]
+    assert (W3.shape[1] if trans_w else W3.shape[2]) == K
+    assert W3.shape[0] in (1, B)
+    bias = None if bias is None else _f32(bias)
+    tau = np.empty((B, M, N), dtype=np.float32)
+    sW = 0 if W3.shape[0] == 1 else W3.shape[1] * W3.shape[2]
+    _chk(lib().taoo_bound_linear(_p(A3), _p(W3), _p(bias), _p(tau), M, N, K, K, W3.shape[2], N,
+                                 int(bool(trans_w)), B, M * K, sW, M * N, ctypes.byref(model)))
+    return tau if batched else tau[0]
+
+
+def bound_softmax(x, y, model=None):
+    model = model or Model()
+    x = _f32(x); y = _f32(y)
+    cols = x.shape[-1]; rows = x.size // cols
+    tau = np.empty_like(x)
+    _chk(lib().taoo_bound_softmax(_p(x), _p(y), _p(tau), rows, cols, cols, ctypes.byref(model)))
+    return tau
+
+
+def bound_norm(kind, x, y=None, g=None, b=None, eps=0.0, model=None):
+    model = model or Model()
+    x = _f32(x)
+    cols = x.shape[-1]; rows = x.size // cols
+    y = None if y is None else _f32(y)
+    g = None if g is None else _f32(g)
+    b = None if b is None else _f32(b)
+    if kind in (SUM, MEAN):
+        tau = np.empty(x.shape[:-1], dtype=np.float32)
+    else:
+        tau = np.empty_like(x)
+    _chk(lib().taoo_bound_norm(kind, _p(x), _p(y), _p(g), _p(b), float(eps), _p(tau), rows, cols,
+                               cols, ctypes.byref(model)))
+    return tau
+
+
+def bound_act(kind, x, y, x2=None, model=None):
+    model = model or Model()
+    y = _f32(y)
+    x = None if x is None else _f32(x)
+    x2 = None if x2 is None else _f32(x2)
+    tau = np.empty_like(y)
+    _chk(lib().taoo_bound_act(kind, _p(x), _p(x2), _p(y), _p(tau), y.size, ctypes.byref(model)))
+    return tau
+
+
+def check_and_profile(claimed, ref, tau, alpha=1.0, eps_rel=1e-12):
+    claimed = _f32(claimed); ref = _f32(ref); tau = _f32(tau)
+    assert claimed.size == ref.size == tau.size
+    out = Profile()
+    _chk(lib().taoo_check_and_profile(_p(claimed), _p(ref), _p(tau), claimed.size, float(alpha),
+                                      float(eps_rel), ctypes.byref(out)))
+    return out.as_dict()
+
+
+def rel_errors(claimed, ref, eps_rel=1e-12):
+    claimed = _f32(claimed); ref = _f32(ref)
+    out = np.empty(claimed.shape, dtype=np.float32)
+    _chk(lib().taoo_rel_errors(_p(claimed), _p(ref), claimed.size, float(eps_rel), _p(out)))
+    return out
+
+
+def num_threads():
+    return lib().taoo_num_threads()
