@@ -1,0 +1,191 @@
+/*
+ * tao.h -- C ABI of the MI355X (gfx950) per-operator tolerance engine.
+ *
+ * For one traced FP32 operator the engine computes the element-wise worst-case
+ * IEEE-754 acceptance bound tau (same shape as the operator's output) and
+ * checks a claimed output against a locally re-executed one, element by
+ * element, also producing a relative-error percentile profile.  The method is
+ * that of "TAO: Tolerance-Aware Optimistic Verification for Floating-Point
+ * Neural Networks": bound templates of Sec. 3.1 with the constants of
+ * App. A.1-A.2, the error profile of Sec. 3.2 Eq. (2) / Sec. 5.3, the leaf
+ * check of Sec. 5.4.
+ *
+ * Conventions for every entry point
+ *  - All tensor pointers are DEVICE pointers to binary32 data owned by the
+ *    caller; row-major; leading dimensions are in elements.  `tau` buffers are
+ *    written, everything else is read only.  Nothing is retained after return.
+ *  - `stream` is the caller's hipStream_t passed as void* (NULL = the null
+ *    stream).  All work is enqueued asynchronously on it; no entry point
+ *    synchronises and none allocates device memory.
+ *  - `model` is a HOST pointer (NULL selects tao_default_model()).
+ *  - Return value: TAO_OK or a negative TAO_ERR_* code; on error nothing has
+ *    been enqueued.  Data-dependent failures (a row for which a template has
+ *    no finite bound, NaN/+inf inputs) are not status codes: the affected tau
+ *    elements are written as NaN, which the check counts as violations.
+ *  - Every bound is evaluated so that it never falls below the real-number
+ *    value of its formula: sums are inflated by a proven bound on their own
+ *    rounding error and the final binary64 value is rounded up to binary32.
+ */
+#ifndef TAO_H
+#define TAO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TAO_NBINS 2048
+
+enum {
+    TAO_OK = 0,
+    TAO_ERR_NULL = -1,      /* a required pointer is NULL */
+    TAO_ERR_SHAPE = -2,     /* negative size, leading dimension smaller than the row, bad stride */
+    TAO_ERR_ALIGN = -3,     /* pointer not aligned to 4 bytes (8 for tao_profile) */
+    TAO_ERR_K_RANGE = -4,   /* reduction depth k with k*u >= 1: gamma_k undefined (App. A.1) */
+    TAO_ERR_MODEL = -5,     /* tao_fp_model field out of range */
+    TAO_ERR_KIND = -6,      /* unknown operator kind */
+    TAO_ERR_LAUNCH = -7,    /* HIP reported an error; see tao_last_hip_error() */
+    TAO_ERR_WORKSPACE = -8  /* workspace missing, misaligned (256 bytes) or too small */
+};
+
+/* Floating-point model (App. A.1) and intrinsic accuracies (Sec. 3.1 uses the
+ * math library's documented maximum errors; the printed softmax template has
+ * 2u for exp).  c_* are relative errors in units of u. */
+typedef struct tao_fp_model {
+    double u;        /* unit roundoff; 2^-24 for binary32 */
+    int mode;        /* TAO_MODE_DETERMINISTIC: gamma_k; TAO_MODE_PROBABILISTIC: gamma~_k(lambda) */
+    double lambda;   /* confidence parameter of the probabilistic constant (4 in Sec. 3.1) */
+    double c_exp;    /* exp   (default 2) */
+    double c_erf;    /* erf   (default 2) */
+    double c_rsqrt;  /* rsqrt, or sqrt followed by a division (default 2) */
+    double c_div;    /* division by n, or multiplication by a rounded 1/n (default 2) */
+    unsigned flags;  /* TAO_FLAG_* */
+} tao_fp_model;
+
+enum { TAO_MODE_DETERMINISTIC = 0, TAO_MODE_PROBABILISTIC = 1 };
+enum {
+    TAO_FLAG_UNDERFLOW_TERMS = 1u,  /* linear: add K'*2^-149 for gradual underflow (App. A.1 excludes it) */
+    TAO_FLAG_FAST_ACCUM = 2u        /* linear: one FP32 accumulation chain over K; still an upper
+                                       bound, but looser than the default by about 2*K*u relative */
+};
+
+/* Result of tao_check_and_profile (lives in DEVICE memory, 8-byte aligned). */
+typedef struct tao_profile {
+    uint64_t n;            /* elements examined */
+    uint64_t violations;   /* elements with !(|c - r| <= alpha*tau) */
+    uint64_t nan_count;    /* elements whose relative error is NaN */
+    float max_rel;         /* largest non-NaN relative error (binary32), 0 if none */
+    uint32_t accept;       /* 1 iff violations == 0 (Sec. 5.4: any element outside rejects) */
+    uint32_t p50_bin, p99_bin, p999_bin;   /* histogram bin holding the nearest-rank percentile */
+    float p50, p99, p999;  /* upper edge of that bin (+inf / NaN for the inf / NaN bins) */
+    uint32_t pad_;
+    uint64_t hist[TAO_NBINS];   /* bin b counts errors e with bits(e) >> 20 == b; NaN -> 2047 */
+} tao_profile;
+
+/* Operator kinds of tao_bound_norm and tao_bound_act (operator list of App. A.3). */
+enum { TAO_NORM_LAYERNORM = 0, TAO_NORM_RMSNORM = 1, TAO_NORM_BN_AFFINE = 2,
+       TAO_NORM_SUM = 3, TAO_NORM_MEAN = 4 };
+enum { TAO_ACT_GELU_ERF = 0, TAO_ACT_SILU = 1, TAO_ACT_MUL = 2, TAO_ACT_ADD = 3, TAO_ACT_RELU = 4 };
+
+/* Fills *m with u = 2^-24, deterministic mode, lambda = 4, c_exp = c_erf =
+ * c_rsqrt = c_div = 2, flags = 0. */
+void tao_default_model(tao_fp_model *m);
+
+/* Gamma(k) on the host, rounded up in binary64: gamma_k = k u/(1 - k u)
+ * (App. A.1 Eq. gamma-def) or gamma~_k(lambda) = exp(lambda sqrt(k) u + k u^2/(1-u)) - 1
+ * (Sec. 3.1).  Returns NaN when undefined (k u >= 1); 0 for k <= 0. */
+double tao_gamma(long k, const tao_fp_model *model);
+
+/* Linear / matmul / bmm / convolution-as-GEMM bound (Sec. 3.1: reductions use
+ * gamma_k with the k of the output element; App. A.2 Eq. det-sum):
+ *     tau[b][i][j] = Gamma(K') * ( sum_k |A[b][i][k]| |W[b][j][k]| + |bias[j]| ),
+ *     K' = K, or K + 1 when bias != NULL.
+ * A: [batch][M][K] with row stride lda and batch stride strideA.
+ * W: trans_w == 0: [batch][N][K] (row j = weights of output j, the layout of a
+ *    Linear layer); trans_w != 0: [batch][K][N].  Row stride ldw, batch stride
+ *    strideW (0 shares one W across the batch).
+ * bias: [N] or NULL, shared across the batch.  tau: [batch][M][N], ldt, strideT.
+ * The product |A||W| runs on the FP32 matrix cores in chains of at most 6
+ * k-steps whose partial sums are folded into a binary64 accumulator; the result
+ * is inflated by the proven rounding error of that scheme, so
+ * exact <= tau <= exact * (1 + 1e-6).  M, N or batch equal to 0 is a no-op;
+ * K == 0 gives tau = Gamma(K') |bias| (0 without bias). */
+int tao_bound_linear(const float *A, const float *W, const float *bias, float *tau,
+                     long M, long N, long K, long lda, long ldw, long ldt, int trans_w,
+                     long batch, long strideA, long strideW, long strideT,
+                     const tao_fp_model *model, void *stream);
+
+/* Softmax over the last dimension (Sec. 3.1 "Minimal example: softmax", closed
+ * to second order).  x, y_ref, tau: [rows][cols] with row stride ld; y_ref is
+ * the verifier's own binary32 softmax output.  Per row, with n = cols:
+ *     a_j = u(|x_j| + |max x|), rho_j = (a_j(1+a_j) + c_exp u)/(1 - c_exp u), q_j = y_j/(1-u),
+ *     sigma = Gamma(n-1) sum q + (1 + Gamma(n-1)) sum rho q,
+ *     tau_i = q_i rho_i + q_i (1 + rho_i) sigma/(1 - sigma) + u y_i.
+ * Entries with x = -inf are masked: tau = 0 and they are left out of the sums.
+ * A row that is fully masked, contains NaN or +inf, or has sigma >= 1 gets NaN. */
+int tao_bound_softmax(const float *x, const float *y_ref, float *tau, long rows, long cols, long ld,
+                      const tao_fp_model *model, void *stream);
+
+/* Row-wise normalisations and reductions over the last dimension (operators of
+ * App. A.3; templates follow the primitive rule of Sec. 3.1).  x: [rows][cols],
+ * row stride ld.  y_ref: the verifier's binary32 output ([rows][cols] with row
+ * stride ld; [rows] for MEAN; unused and may be NULL for SUM).
+ *  LAYERNORM  y = (x - mean) rsqrt(var + eps) g + b; g = gamma_or_scale[cols] or NULL (= 1),
+ *             b = beta_or_shift[cols] or NULL (never enters the bound); two-pass algorithm.
+ *  RMSNORM    y = g (x rsqrt(mean(x^2) + eps)); g as above.
+ *  BN_AFFINE  y = x s_c + t_c per column c; s = gamma_or_scale (required), t = beta_or_shift.
+ *  SUM, MEAN  tau: [rows];  Gamma(cols-1) sum|x|  (/cols + |y| c_div u/(1 - c_div u) for MEAN).
+ * eps is rounded to binary32 first, as the operator does.  A row whose bound is
+ * not finite (lower end of var + eps not positive) gets NaN. */
+int tao_bound_norm(int kind, const float *x, const float *y_ref,
+                   const float *gamma_or_scale, const float *beta_or_shift, double eps,
+                   float *tau, long rows, long cols, long ld,
+                   const tao_fp_model *model, void *stream);
+
+/* Element-wise operators (App. A.3), flat length n.  y_ref is the verifier's
+ * binary32 output and is always required.
+ *  GELU_ERF  y = 0.5 x (1 + erf(x/sqrt 2)); needs x.
+ *            tau = |x|/2 ((2/sqrt pi) e^{-t_lo^2} E_t + c_erf u min(1, (2/sqrt pi)|t|(1+4u)))
+ *                  + u |y| (1 + 1/(1-u)),  t = x/sqrt 2, E_t = (2u+u^2)|t|, t_lo = max(0,|t|-E_t).
+ *  SILU      y = x/(1 + exp(-x)): tau = |y| (w/(1-u) + u), w = (c_exp u/(1-c_exp u) + u)/(1-u).
+ *  MUL, ADD  one rounding: tau = u |y|.     RELU  exact: tau = 0.
+ * x and x2 (the operands) are ignored except by GELU_ERF and may be NULL there. */
+int tao_bound_act(int kind, const float *x, const float *x2, const float *y_ref, float *tau, long n,
+                  const tao_fp_model *model, void *stream);
+
+/* Leaf check (Sec. 5.4) and relative-error profile (Sec. 5.3; Sec. 3.2 Eq. 2)
+ * of n elements, in IEEE binary64 per element:
+ *     d = |claimed - ref|;  violation iff !(d <= alpha * tau);
+ *     e = d / (|ref| + eps_rel), cast to binary32;  bin = NaN ? 2047 : bits(e) >> 20.
+ * Percentiles p50, p99, p99.9 by nearest rank, rank = max(1, ceil(n p)), on the
+ * histogram; alpha is the bound scale factor of Sec. 4.5 (1 = the paper's check).
+ * out: DEVICE pointer, fully overwritten; valid once the stream has drained.
+ * ws / ws_bytes: DEVICE scratch of at least tao_check_workspace_bytes(n). */
+int tao_check_and_profile(const float *claimed, const float *ref, const float *tau, long n,
+                          double alpha, double eps_rel, tao_profile *out,
+                          void *ws, size_t ws_bytes, void *stream);
+
+/* Bytes of DEVICE workspace tao_check_and_profile needs for n elements (per-
+ * workgroup partial histograms and counters).  The workspace must be 256-byte
+ * aligned; its contents on entry do not matter and are garbage afterwards.
+ * Calls that share a workspace must be ordered on one stream. */
+size_t tao_check_workspace_bytes(long n);
+
+/* Runs crafted inputs through the FP32 matrix-core instruction and reports, as
+ * a bit mask in *report (HOST pointer), which modelling assumptions of the
+ * linear bound's inflation hold on this device: bit 0 accumulation rounds to
+ * nearest-even; bit 1 subnormal products are kept (no flush); bit 2 a 6-step
+ * chain on random non-negative data stays within gamma_6 of the exact sum.
+ * Synchronises the stream.  For callers that want to verify the device once. */
+int tao_selftest_matrix_core(unsigned *report, void *stream);
+
+/* hipError_t of the most recent TAO_ERR_LAUNCH on this thread (0 if none). */
+int tao_last_hip_error(void);
+const char *tao_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TAO_H */

@@ -1,0 +1,322 @@
+"""Python binding of libtao.so, the MI355X per-operator tolerance engine.
+
+Argument marshalling only: every function below hands device pointers, sizes
+and the current HIP stream to the C entry point of the same name (declared in
+include/tao.h); all arithmetic runs in the library's kernels.  PyTorch is used
+for device memory and streams.  There is no CPU fallback: if the shared
+library is missing or no GPU is present, calls raise.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+NBINS = 2048
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtao.so")
+
+OK = 0
+ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_K_RANGE, ERR_MODEL, ERR_KIND, ERR_LAUNCH, ERR_WORKSPACE = \
+    -1, -2, -3, -4, -5, -6, -7, -8
+MODE_DETERMINISTIC, MODE_PROBABILISTIC = 0, 1
+FLAG_UNDERFLOW_TERMS, FLAG_FAST_ACCUM = 1, 2
+NORM_LAYERNORM, NORM_RMSNORM, NORM_BN_AFFINE, NORM_SUM, NORM_MEAN = 0, 1, 2, 3, 4
+ACT_GELU_ERF, ACT_SILU, ACT_MUL, ACT_ADD, ACT_RELU = 0, 1, 2, 3, 4
+
+
+class FpModel(ctypes.Structure):
+    """tao_fp_model: unit roundoff, deterministic/probabilistic constant, intrinsic accuracies."""
+    _fields_ = [("u", ctypes.c_double), ("mode", ctypes.c_int), ("lam", ctypes.c_double),
+                ("c_exp", ctypes.c_double), ("c_erf", ctypes.c_double),
+                ("c_rsqrt", ctypes.c_double), ("c_div", ctypes.c_double),
+                ("flags", ctypes.c_uint)]
+
+    def __init__(self, u=2.0 ** -24, mode=0, lam=4.0, c_exp=2.0, c_erf=2.0, c_rsqrt=2.0,
+                 c_div=2.0, flags=0):
+        super().__init__(u, mode, lam, c_exp, c_erf, c_rsqrt, c_div, flags)
+
+
+class Profile(ctypes.Structure):
+    """tao_profile as laid out in device memory."""
+    _fields_ = [("n", ctypes.c_uint64), ("violations", ctypes.c_uint64),
+                ("nan_count", ctypes.c_uint64), ("max_rel", ctypes.c_float),
+                ("accept", ctypes.c_uint32), ("p50_bin", ctypes.c_uint32),
+                ("p99_bin", ctypes.c_uint32), ("p999_bin", ctypes.c_uint32),
+                ("p50", ctypes.c_float), ("p99", ctypes.c_float), ("p999", ctypes.c_float),
+                ("pad_", ctypes.c_uint32), ("hist", ctypes.c_uint64 * NBINS)]
+
+    def as_dict(self):
+        return {"n": int(self.n), "violations": int(self.violations),
+                "nan_count": int(self.nan_count), "max_rel": float(self.max_rel),
+                "accept": int(self.accept), "p50_bin": int(self.p50_bin),
+                "p99_bin": int(self.p99_bin), "p999_bin": int(self.p999_bin),
+                "p50": float(self.p50), "p99": float(self.p99), "p999": float(self.p999),
+                "hist": np.ctypeslib.as_array(self.hist).copy()}
+
+
+class TaoError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = lib().tao_status_string(status).decode()
+        extra = ""
+        if status == ERR_LAUNCH:
+            extra = " (hipError %d)" % lib().tao_last_hip_error()
+        super().__init__("%s: %s%s" % (where, msg, extra))
+
+
+EXPORTS = ["tao_default_model", "tao_gamma", "tao_bound_linear", "tao_bound_softmax",
+           "tao_bound_norm", "tao_bound_act", "tao_check_and_profile",
+           "tao_check_workspace_bytes", "tao_selftest_matrix_core", "tao_last_hip_error",
+           "tao_status_string"]
+
+_lib = None
+
+
+def lib():
+    """Load libtao.so (built by `python -m paper_2510_16028_amd.build`); raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError("libtao.so not built: run `python -m paper_2510_16028_amd.build` "
+                           "(there is no CPU fallback)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, lg, dbl = ctypes.c_void_p, ctypes.c_long, ctypes.c_double
+    mp = ctypes.POINTER(FpModel)
+    L.tao_default_model.argtypes = [mp]
+    L.tao_default_model.restype = None
+    L.tao_gamma.argtypes = [lg, mp]
+    L.tao_gamma.restype = dbl
+    L.tao_bound_linear.argtypes = [vp, vp, vp, vp, lg, lg, lg, lg, lg, lg, ctypes.c_int,
+                                   lg, lg, lg, lg, mp, vp]
+    L.tao_bound_softmax.argtypes = [vp, vp, vp, lg, lg, lg, mp, vp]
+    L.tao_bound_norm.argtypes = [ctypes.c_int, vp, vp, vp, vp, dbl, vp, lg, lg, lg, mp, vp]
+    L.tao_bound_act.argtypes = [ctypes.c_int, vp, vp, vp, vp, lg, mp, vp]
+    L.tao_check_and_profile.argtypes = [vp, vp, vp, lg, dbl, dbl, vp, vp, ctypes.c_size_t, vp]
+    L.tao_check_workspace_bytes.argtypes = [lg]
+    L.tao_check_workspace_bytes.restype = ctypes.c_size_t
+    L.tao_selftest_matrix_core.argtypes = [ctypes.POINTER(ctypes.c_uint), vp]
+    L.tao_last_hip_error.restype = ctypes.c_int
+    L.tao_status_string.argtypes = [ctypes.c_int]
+    L.tao_status_string.restype = ctypes.c_char_p
+    _lib = L
+    return L
+
+
+def _torch():
+    import torch
+    if not torch.cuda.is_available():
+        raise RuntimeError("paper_2510_16028_amd needs a GPU: no CPU fallback exists")
+    return torch
+
+
+def _stream():
+    return ctypes.c_void_p(_torch().cuda.current_stream().cuda_stream)
+
+
+def _dev(t, name):
+    torch = _torch()
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32):
+        raise TypeError("%s must be a float32 CUDA tensor" % name)
+    return t
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _mref(model):
+    return None if model is None else ctypes.byref(model)
+
+
+def _check(status, where):
+    if status != OK:
+        raise TaoError(status, where)
+
+
+def _rows_view(t, name):
+    """(rows, cols, ld) of a tensor whose last dimension is contiguous and whose
+    leading dimensions collapse to one uniform row stride."""
+    if t.dim() == 0:
+        raise ValueError("%s: need at least one dimension" % name)
+    cols = t.shape[-1]
+    if t.dim() == 1:
+        return 1, cols, cols
+    if cols > 1 and t.stride(-1) != 1:
+        raise ValueError("%s: last dimension must be contiguous" % name)
+    t2 = t if t.is_contiguous() else None
+    if t2 is not None:
+        return t.numel() // max(cols, 1), cols, cols
+    if t.dim() == 2:
+        return t.shape[0], cols, t.stride(0)
+    raise ValueError("%s: only 2-D tensors may have a padded row stride" % name)
+
+
+# ------------------------------------------------------------------ entry points
+
+def tao_default_model():
+    m = FpModel()
+    lib().tao_default_model(ctypes.byref(m))
+    return m
+
+
+def tao_gamma(k, model=None):
+    return lib().tao_gamma(int(k), _mref(model))
+
+
+def tao_bound_linear(A, W, bias=None, trans_w=False, model=None, out=None):
+    """tau[..., M, N] for A[..., M, K] and W[N, K] / [B, N, K] (trans_w: [K, N] / [B, K, N])."""
+    torch = _torch()
+    A = _dev(A, "A"); W = _dev(W, "W"); bias = _dev(bias, "bias")
+    if A.dim() not in (2, 3) or W.dim() not in (2, 3):
+        raise ValueError("A and W must be 2-D or 3-D")
+    for t, nm in ((A, "A"), (W, "W")):
+        if t.shape[-1] > 1 and t.stride(-1) != 1:
+            raise ValueError("%s: last dimension must be contiguous" % nm)
+    batch = A.shape[0] if A.dim() == 3 else 1
+    M, K = A.shape[-2], A.shape[-1]
+    N = W.shape[-1] if trans_w else W.shape[-2]
+    if (W.shape[-2] if trans_w else W.shape[-1]) != K:
+        raise ValueError("reduction sizes of A and W differ")
+    if W.dim() == 3 and W.shape[0] != batch:
+        raise ValueError("batch sizes of A and W differ")
+    if bias is not None and (bias.dim() != 1 or bias.shape[0] != N or not bias.is_contiguous()):
+        raise ValueError("bias must be a contiguous [N] tensor")
+    shape = (batch, M, N) if A.dim() == 3 else (M, N)
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float32, device=A.device)
+    elif tuple(out.shape) != shape or not out.is_contiguous() or out.dtype != torch.float32:
+        raise ValueError("out must be a contiguous float32 tensor of shape %s" % (shape,))
+    lda = A.stride(-2) if M > 1 else max(K, 1)
+    ldw = W.stride(-2) if W.shape[-2] > 1 else max(W.shape[-1], 1)
+    sA = A.stride(0) if A.dim() == 3 and batch > 1 else M * lda
+    sW = (W.stride(0) if W.shape[0] > 1 else 0) if W.dim() == 3 else 0
+    rc = lib().tao_bound_linear(_ptr(A), _ptr(W), _ptr(bias), _ptr(out), M, N, K, lda, ldw, N,
+                                int(bool(trans_w)), batch, sA, sW, M * N, _mref(model), _stream())
+    _check(rc, "tao_bound_linear")
+    return out
+
+
+def tao_bound_softmax(x, y_ref, model=None, out=None):
+    torch = _torch()
+    x = _dev(x, "x"); y_ref = _dev(y_ref, "y_ref")
+    if x.shape != y_ref.shape or x.stride() != y_ref.stride():
+        raise ValueError("x and y_ref must have the same shape and strides")
+    rows, cols, ld = _rows_view(x, "x")
+    if out is None:
+        out = torch.empty_strided(x.shape, x.stride(), dtype=torch.float32, device=x.device)
+    elif out.shape != x.shape or out.stride() != x.stride():
+        raise ValueError("out must match x in shape and strides")
+    rc = lib().tao_bound_softmax(_ptr(x), _ptr(y_ref), _ptr(out), rows, cols, ld, _mref(model), _stream())
+    _check(rc, "tao_bound_softmax")
+    return out
+
+
+def tao_bound_norm(kind, x, y_ref=None, gamma_or_scale=None, beta_or_shift=None, eps=0.0,
+                   model=None, out=None):
+    torch = _torch()
+    x = _dev(x, "x"); y_ref = _dev(y_ref, "y_ref")
+    g = _dev(gamma_or_scale, "gamma_or_scale"); b = _dev(beta_or_shift, "beta_or_shift")
+    rows, cols, ld = _rows_view(x, "x")
+    reduces = kind in (NORM_SUM, NORM_MEAN)
+    for t, nm in ((g, "gamma_or_scale"), (b, "beta_or_shift")):
+        if t is not None and (t.dim() != 1 or t.shape[0] != cols or not t.is_contiguous()):
+            raise ValueError("%s must be a contiguous [cols] tensor" % nm)
+    if reduces:
+        if y_ref is not None and (y_ref.numel() != rows or not y_ref.is_contiguous()):
+            raise ValueError("y_ref must be a contiguous tensor with one value per row")
+        oshape = x.shape[:-1]
+        if out is None:
+            out = torch.empty(oshape, dtype=torch.float32, device=x.device)
+        elif out.numel() != rows or not out.is_contiguous():
+            raise ValueError("out must be contiguous with one value per row")
+    else:
+        if y_ref is not None and (y_ref.shape != x.shape or y_ref.stride() != x.stride()):
+            raise ValueError("x and y_ref must have the same shape and strides")
+        if out is None:
+            out = torch.empty_strided(x.shape, x.stride(), dtype=torch.float32, device=x.device)
+        elif out.shape != x.shape or out.stride() != x.stride():
+            raise ValueError("out must match x in shape and strides")
+    rc = lib().tao_bound_norm(int(kind), _ptr(x), _ptr(y_ref), _ptr(g), _ptr(b), float(eps), _ptr(out),
+                              rows, cols, ld, _mref(model), _stream())
+    _check(rc, "tao_bound_norm")
+    return out
+
+
+def tao_bound_act(kind, x, y_ref, x2=None, model=None, out=None):
+    torch = _torch()
+    x = _dev(x, "x"); x2 = _dev(x2, "x2"); y_ref = _dev(y_ref, "y_ref")
+    for t, nm in ((x, "x"), (x2, "x2"), (y_ref, "y_ref")):
+        if t is not None and not t.is_contiguous():
+            raise ValueError("%s must be contiguous" % nm)
+        if t is not None and t.numel() != y_ref.numel():
+            raise ValueError("%s must have as many elements as y_ref" % nm)
+    if out is None:
+        out = torch.empty_like(y_ref)
+    elif out.shape != y_ref.shape or not out.is_contiguous():
+        raise ValueError("out must be contiguous and shaped like y_ref")
+    rc = lib().tao_bound_act(int(kind), _ptr(x), _ptr(x2), _ptr(y_ref), _ptr(out), y_ref.numel(),
+                             _mref(model), _stream())
+    _check(rc, "tao_bound_act")
+    return out
+
+
+_ws_cache = {}
+
+
+def _workspace(device, n):
+    """One scratch tensor per (device, stream); calls on one stream are ordered, so sharing is safe."""
+    torch = _torch()
+    need = lib().tao_check_workspace_bytes(int(n))
+    key = (device.index if device.index is not None else torch.cuda.current_device(),
+           torch.cuda.current_stream().cuda_stream)
+    ws = _ws_cache.get(key)
+    if ws is None or ws.numel() < need:
+        ws = torch.empty(need, dtype=torch.uint8, device=device)
+        _ws_cache[key] = ws
+    return ws
+
+
+def new_profile_buffer(device):
+    """Device buffer able to hold one tao_profile."""
+    return _torch().empty(ctypes.sizeof(Profile), dtype=_torch().uint8, device=device)
+
+
+def read_profile(buf):
+    """Copy a tao_profile back from the device (synchronises) and return it as a dict."""
+    raw = buf.cpu().numpy().tobytes()
+    return Profile.from_buffer_copy(raw).as_dict()
+
+
+def tao_check_and_profile(claimed, ref, tau, alpha=1.0, eps_rel=1e-12, out=None, ws=None,
+                          readback=True):
+    """Enqueue the check; with readback=True (default) wait for it and return the profile dict,
+    otherwise return the device buffer holding the tao_profile without synchronising."""
+    claimed = _dev(claimed, "claimed"); ref = _dev(ref, "ref"); tau = _dev(tau, "tau")
+    for t, nm in ((claimed, "claimed"), (ref, "ref"), (tau, "tau")):
+        if not t.is_contiguous():
+            raise ValueError("%s must be contiguous" % nm)
+    n = claimed.numel()
+    if ref.numel() != n or tau.numel() != n:
+        raise ValueError("claimed, ref and tau must have the same number of elements")
+    if out is None:
+        out = new_profile_buffer(claimed.device)
+    if ws is None:
+        ws = _workspace(claimed.device, n)
+    rc = lib().tao_check_and_profile(_ptr(claimed), _ptr(ref), _ptr(tau), n, float(alpha),
+                                     float(eps_rel), _ptr(out), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "tao_check_and_profile")
+    return read_profile(out) if readback else out
+
+
+def tao_check_workspace_bytes(n):
+    return lib().tao_check_workspace_bytes(int(n))
+
+
+def tao_selftest_matrix_core():
+    """Bit mask: 1 accumulation rounds to nearest-even, 2 subnormals kept, 4 chain within gamma_6."""
+    rep = ctypes.c_uint(0)
+    _check(lib().tao_selftest_matrix_core(ctypes.byref(rep), _stream()), "tao_selftest_matrix_core")
+    return int(rep.value)

@@ -1,0 +1,236 @@
+// tao_check_and_profile: the leaf check of Sec. 5.4 and the relative-error
+// profile of Sec. 5.3 / Sec. 3.2 Eq. (2) as one streaming pass over
+// (claimed, ref, tau) plus a small finalising kernel.
+//
+// Pass 1 (check_pass): grid-stride over 16-byte vectors of the three inputs;
+// per element IEEE binary64 arithmetic (no contraction); each workgroup keeps a
+// lane-replicated 2048-bin histogram in LDS and writes its partial histogram
+// and counters to the workspace -- no global atomics, so the result does not
+// depend on scheduling.
+// Pass 2 (profile_reduce): one workgroup per 16 bins sums the partials into the
+// 64-bit histogram; the last workgroup to finish (device-scope counter in the
+// result struct, zeroed by pass 1) scans the 2048 bins for the nearest-rank
+// percentiles and writes the scalar fields.
+#include "tao_device.hpp"
+#include "tao_host.hpp"
+
+namespace tao {
+
+constexpr int kBins = TAO_NBINS;
+constexpr int kCheckThreads = 256;
+constexpr int kReplicas = 4;                 // LDS copies of each bin, selected by lane & 3
+constexpr int kMaxCheckBlocks = 1024;
+constexpr int kBinsPerReduceBlock = 16;
+constexpr int kReduceBlocks = kBins / kBinsPerReduceBlock;
+
+struct BlockStats {          // one per pass-1 workgroup, in the workspace after the histograms
+    unsigned long long violations;
+    unsigned long long nans;
+    unsigned int max_bits;   // bit pattern of the largest non-NaN error (errors are >= 0)
+    unsigned int pad;
+};
+
+struct ThreadAcc {
+    unsigned int violations = 0, nans = 0, max_bits = 0;
+};
+
+__device__ __forceinline__ void check_one(float c, float r, float t, double alpha, double eps_rel,
+                                          unsigned int* hist, int rep, ThreadAcc& acc) {
+    const double cd = (double)c, rd = (double)r;
+    const double d = fabs(cd - rd);
+    const double T = alpha * (double)t;
+    acc.violations += !(d <= T);
+    const double den = fabs(rd) + eps_rel;
+    const double e = d / den;
+    const float e32 = (float)e;
+    const bool isn = e32 != e32;
+    const unsigned int bits = __float_as_uint(e32);
+    const unsigned int bin = isn ? (unsigned)(kBins - 1) : (bits >> 20);
+    acc.nans += isn;
+    if (!isn) acc.max_bits = max(acc.max_bits, bits);
+    atomicAdd(&hist[bin * kReplicas + rep], 1u);
+}
+
+__global__ __launch_bounds__(kCheckThreads) void check_pass(
+    const float* __restrict__ claimed, const float* __restrict__ ref, const float* __restrict__ tau,
+    long n, int vec_ok, double alpha, double eps_rel,
+    unsigned int* __restrict__ ws_hist, BlockStats* __restrict__ ws_stats, tao_profile* out) {
+    __shared__ unsigned int hist[kBins * kReplicas];
+    __shared__ unsigned int red[3 * (kCheckThreads / kWave)];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < kBins * kReplicas; i += kCheckThreads) hist[i] = 0;
+    if (blockIdx.x == 0 && tid == 0) out->pad_ = 0;      // completion counter of pass 2
+    __syncthreads();
+
+    ThreadAcc acc;
+    const int rep = tid & (kReplicas - 1);
+    const long nvec = vec_ok ? (n >> 2) : 0;
+    const long stride = (long)gridDim.x * kCheckThreads;
+    for (long i = (long)blockIdx.x * kCheckThreads + tid; i < nvec; i += stride) {
+        const float4 c4 = reinterpret_cast<const float4*>(claimed)[i];
+        const float4 r4 = reinterpret_cast<const float4*>(ref)[i];
+        const float4 t4 = reinterpret_cast<const float4*>(tau)[i];
+        check_one(c4.x, r4.x, t4.x, alpha, eps_rel, hist, rep, acc);
+        check_one(c4.y, r4.y, t4.y, alpha, eps_rel, hist, rep, acc);
+        check_one(c4.z, r4.z, t4.z, alpha, eps_rel, hist, rep, acc);
+        check_one(c4.w, r4.w, t4.w, alpha, eps_rel, hist, rep, acc);
+    }
+    // scalar remainder (everything when the inputs are not 16-byte aligned)
+    for (long i = (nvec << 2) + (long)blockIdx.x * kCheckThreads + tid; i < n; i += stride)
+        check_one(claimed[i], ref[i], tau[i], alpha, eps_rel, hist, rep, acc);
+
+    // workgroup totals of the three counters
+    unsigned int v = acc.violations, q = acc.nans, m = acc.max_bits;
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+        v += __shfl_xor(v, o, kWave);
+        q += __shfl_xor(q, o, kWave);
+        m = max(m, (unsigned int)__shfl_xor(m, o, kWave));
+    }
+    const int wave = tid / kWave;
+    if ((tid & (kWave - 1)) == 0) { red[wave * 3] = v; red[wave * 3 + 1] = q; red[wave * 3 + 2] = m; }
+    __syncthreads();
+    if (tid == 0) {
+        BlockStats s{0, 0, 0, 0};
+        for (int w = 0; w < kCheckThreads / kWave; ++w) {
+            s.violations += red[w * 3]; s.nans += red[w * 3 + 1];
+            s.max_bits = max(s.max_bits, red[w * 3 + 2]);
+        }
+        ws_stats[blockIdx.x] = s;
+    }
+    unsigned int* dst = ws_hist + (size_t)blockIdx.x * kBins;
+    for (int b = tid; b < kBins; b += kCheckThreads) {
+        unsigned int s = 0;
+#pragma unroll
+        for (int r = 0; r < kReplicas; ++r) s += hist[b * kReplicas + r];
+        dst[b] = s;
+    }
+}
+
+__device__ __forceinline__ float bin_upper_edge(unsigned int b) {
+    if (b >= (unsigned)(kBins - 1)) return __uint_as_float(0x7fc00000u);
+    if (b >= 2039u) return __uint_as_float(0x7f800000u);
+    return __uint_as_float((b + 1u) << 20);
+}
+
+// rank = max(1, ceil(n * num / den)); n < 2^53 and num <= 999 keep the product in 64 bits.
+__device__ __forceinline__ unsigned long long rank_of(unsigned long long n, unsigned long long num,
+                                                       unsigned long long den) {
+    unsigned long long r = (n * num + den - 1) / den;
+    return r < 1 ? 1 : r;
+}
+
+__global__ __launch_bounds__(256) void profile_reduce(
+    const unsigned int* __restrict__ ws_hist, const BlockStats* __restrict__ ws_stats, int nblocks,
+    unsigned long long n, tao_profile* out) {
+    __shared__ unsigned long long part[256];
+    __shared__ unsigned long long scan[kBins / 8];
+    __shared__ int is_last;
+    const int tid = threadIdx.x;
+    // 16 bins x 16 slices of the partial histograms
+    const int b = tid & (kBinsPerReduceBlock - 1);
+    const int slice = tid / kBinsPerReduceBlock;
+    const int bin = blockIdx.x * kBinsPerReduceBlock + b;
+    unsigned long long s = 0;
+    for (int k = slice; k < nblocks; k += 256 / kBinsPerReduceBlock) s += ws_hist[(size_t)k * kBins + bin];
+    part[tid] = s;
+    __syncthreads();
+    if (tid < kBinsPerReduceBlock) {
+        unsigned long long t = 0;
+        for (int k = 0; k < 256 / kBinsPerReduceBlock; ++k) t += part[k * kBinsPerReduceBlock + tid];
+        out->hist[blockIdx.x * kBinsPerReduceBlock + tid] = t;
+    }
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) is_last = (atomicAdd(&out->pad_, 1u) == (unsigned)(gridDim.x - 1));
+    __syncthreads();
+    if (!is_last) return;
+    __threadfence();
+
+    // Finalise: each thread owns 8 consecutive bins.
+    unsigned long long h[8], local = 0;
+    const volatile uint64_t* gh = out->hist;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) { h[k] = gh[tid * 8 + k]; local += h[k]; }
+    scan[tid] = local;
+    __syncthreads();
+    if (tid == 0) {
+        unsigned long long run = 0;
+        for (int k = 0; k < kBins / 8; ++k) { unsigned long long t = scan[k]; scan[k] = run; run += t; }
+    }
+    __syncthreads();
+    const unsigned long long before = scan[tid];          // exclusive prefix of this thread's bins
+    const unsigned long long ranks[3] = {rank_of(n, 1, 2), rank_of(n, 99, 100), rank_of(n, 999, 1000)};
+    unsigned int* bins_out[3] = {&out->p50_bin, &out->p99_bin, &out->p999_bin};
+    float* vals_out[3] = {&out->p50, &out->p99, &out->p999};
+    if (n > 0) {
+        unsigned long long cum = before;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const unsigned long long lo = cum;
+            cum += h[k];
+            for (int p = 0; p < 3; ++p)
+                if (lo < ranks[p] && ranks[p] <= cum) {
+                    *bins_out[p] = tid * 8 + k;
+                    *vals_out[p] = bin_upper_edge(tid * 8 + k);
+                }
+        }
+    }
+    // counters
+    unsigned long long v = 0, q = 0; unsigned int m = 0;
+    for (int k = tid; k < nblocks; k += 256) {
+        v += ws_stats[k].violations; q += ws_stats[k].nans; m = max(m, ws_stats[k].max_bits);
+    }
+    __shared__ unsigned long long rv[256], rq[256];
+    __shared__ unsigned int rm[256];
+    rv[tid] = v; rq[tid] = q; rm[tid] = m;
+    __syncthreads();
+    if (tid == 0) {
+        v = 0; q = 0; m = 0;
+        for (int k = 0; k < 256; ++k) { v += rv[k]; q += rq[k]; m = max(m, rm[k]); }
+        out->n = n;
+        out->violations = v;
+        out->nan_count = q;
+        out->max_rel = __uint_as_float(m);
+        out->accept = (v == 0) ? 1u : 0u;
+        if (n == 0) {
+            out->p50_bin = out->p99_bin = out->p999_bin = 0;
+            out->p50 = out->p99 = out->p999 = bin_upper_edge(0);
+        }
+    }
+}
+
+}  // namespace tao
+
+extern "C" {
+
+size_t tao_check_workspace_bytes(long n) {
+    (void)n;
+    return (size_t)tao::kMaxCheckBlocks * (tao::kBins * sizeof(unsigned int) + sizeof(tao::BlockStats));
+}
+
+int tao_check_and_profile(const float* claimed, const float* ref, const float* tau, long n,
+                          double alpha, double eps_rel, tao_profile* out,
+                          void* ws, size_t ws_bytes, void* stream) {
+    using namespace tao;
+    if (!out || !ws) return out ? TAO_ERR_WORKSPACE : TAO_ERR_NULL;
+    if (n < 0) return TAO_ERR_SHAPE;
+    if (n > 0 && (!claimed || !ref || !tau)) return TAO_ERR_NULL;
+    if (!aligned(claimed, 4) || !aligned(ref, 4) || !aligned(tau, 4) || !aligned(out, 8)) return TAO_ERR_ALIGN;
+    if (!aligned(ws, 256) || ws_bytes < tao_check_workspace_bytes(n)) return TAO_ERR_WORKSPACE;
+    if (n >= (1L << 53)) return TAO_ERR_SHAPE;
+    hipStream_t st = (hipStream_t)stream;
+    const int vec_ok = aligned(claimed, 16) && aligned(ref, 16) && aligned(tau, 16);
+    // 16 elements (four 16-byte vectors) per thread before another workgroup is worth it
+    long want = (n + (long)kCheckThreads * 16 - 1) / ((long)kCheckThreads * 16);
+    int nblocks = (int)(want < 1 ? 1 : (want > kMaxCheckBlocks ? kMaxCheckBlocks : want));
+    unsigned int* ws_hist = (unsigned int*)ws;
+    BlockStats* ws_stats = (BlockStats*)((char*)ws + (size_t)kMaxCheckBlocks * kBins * sizeof(unsigned int));
+    hipLaunchKernelGGL(check_pass, dim3(nblocks), dim3(kCheckThreads), 0, st, claimed, ref, tau, n,
+                       vec_ok, alpha, eps_rel, ws_hist, ws_stats, out);
+    hipLaunchKernelGGL(profile_reduce, dim3(kReduceBlocks), dim3(256), 0, st, ws_hist, ws_stats,
+                       nblocks, (unsigned long long)n, out);
+    return launch_status();
+}
+
+}  // extern "C"

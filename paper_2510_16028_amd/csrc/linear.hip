@@ -1,0 +1,325 @@
+// tao_bound_linear: tau = Gamma(K') (|A| |W|^T + |bias|) on the FP32 matrix cores
+// of gfx950 (Sec. 3.1: reductions take gamma_k with the k of the output element;
+// App. A.2 Eq. det-sum extended by one rounding per product).
+//
+// The bound has to be an upper bound of the real-number value and must stay
+// within 1e-6 of it, so a plain FP32 accumulation over K (error up to K*u) is
+// not usable.  Scheme: v_mfma_f32_32x32x2_f32 accumulates chains of 3
+// instructions (6 k-steps) from a zero accumulator; two such chains are added
+// in binary32 and the sum is folded into a binary64 accumulator on the vector
+// ALU.  Every term is non-negative, so the computed sum S~ satisfies
+//   S (1-u)^7 (1-2^-53)^(K/12+1) <= S~ <= S (1+u)^7 (1+2^-53)^(K/12+1)
+// under the rounding model of App. A.1 (6 k-steps of at most one product and
+// one addition rounding each, the first addition to zero being exact, plus the
+// pair addition).  The epilogue multiplies by the reciprocal of the lower
+// factor, by Gamma and by the guard factor and rounds up to binary32:
+// exact <= tau <= exact (1 + 16u + ...) < exact (1 + 1e-6).
+//
+// Tiling: 128x128 output tile per 256-thread workgroup, four wavefronts in a
+// 2x2 arrangement, each owning 2x2 MFMA tiles of 32x32.  K advances in slabs of
+// 48 (four chain pairs); |A| and |W| slabs are staged through LDS with the sign
+// bit cleared on the way in; the next slab is prefetched into registers while
+// the current one is consumed.
+#include "tao_device.hpp"
+#include "tao_host.hpp"
+
+namespace tao {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128, BN = 128, BK = 48;
+constexpr int SA = BK + 2;          // LDS row stride (floats) of a k-contiguous slab: 8-byte reads
+                                    // of 32 consecutive rows fall in distinct bank pairs
+constexpr int SWT = BN + 16;        // LDS row stride of a [k][n] slab (trans_w): the two k-halves
+                                    // of a wavefront read disjoint bank halves
+constexpr int kLinThreads = 256;
+constexpr int kVecPerThread = (BM * BK / 4) / kLinThreads;   // 6 float4 per operand per slab
+
+struct LinArgs {
+    const float* A; const float* W; const float* bias; float* tau;
+    long M, N, K, lda, ldw, ldt, strideA, strideW, strideT;
+    int vecA, vecW;            // 16-byte global loads allowed
+    double c;                  // Gamma(K'), upper
+    double infl;               // reciprocal of the lower rounding factor of the accumulation
+    double uflow;              // optional absolute underflow term
+};
+
+__device__ __forceinline__ float4 abs4(float4 v) {
+    return make_float4(fabsf(v.x), fabsf(v.y), fabsf(v.z), fabsf(v.w));
+}
+
+// Load one float4 of row `r` (global row index, < nrows) at column k (< K), zero beyond the edges.
+__device__ __forceinline__ float4 gload(const float* __restrict__ base, long r, long nrows, long ld,
+                                        long k, long K, int vec) {
+    if (r >= nrows || k >= K) return make_float4(0.f, 0.f, 0.f, 0.f);
+    const float* p = base + r * ld + k;
+    if (vec && k + 3 < K) return *reinterpret_cast<const float4*>(p);
+    float4 v;
+    v.x = p[0];
+    v.y = (k + 1 < K) ? p[1] : 0.f;
+    v.z = (k + 2 < K) ? p[2] : 0.f;
+    v.w = (k + 3 < K) ? p[3] : 0.f;
+    return v;
+}
+
+template <bool TRANS_W, bool FAST>
+__global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
+    __shared__ __attribute__((aligned(16))) float As[BM * SA];
+    __shared__ __attribute__((aligned(16))) float Ws[TRANS_W ? BK * SWT : BN * SA];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int r32 = lane & 31, h = lane >> 5;
+    const long m0 = (long)blockIdx.y * BM, n0 = (long)blockIdx.x * BN;
+    const float* __restrict__ A = p.A + (long)blockIdx.z * p.strideA;
+    const float* __restrict__ W = p.W + (long)blockIdx.z * p.strideW;
+    float* __restrict__ T = p.tau + (long)blockIdx.z * p.strideT;
+
+    float4 pa[kVecPerThread], pw[kVecPerThread];
+    auto prefetch = [&](long k0) {
+#pragma unroll
+        for (int i = 0; i < kVecPerThread; ++i) {
+            const int f = tid + kLinThreads * i;
+            const int row = f / (BK / 4), k = (f % (BK / 4)) * 4;
+            pa[i] = gload(A, m0 + row, p.M, p.lda, k0 + k, p.K, p.vecA);
+            if (!TRANS_W) {
+                pw[i] = gload(W, n0 + row, p.N, p.ldw, k0 + k, p.K, p.vecW);
+            } else {
+                const int kr = f / (BN / 4), n = (f % (BN / 4)) * 4;
+                // rows of W are k here, columns are n
+                pw[i] = gload(W, k0 + kr, p.K, p.ldw, n0 + n, p.N, p.vecW);
+            }
+        }
+    };
+    auto commit = [&]() {
+#pragma unroll
+        for (int i = 0; i < kVecPerThread; ++i) {
+            const int f = tid + kLinThreads * i;
+            const int row = f / (BK / 4), k = (f % (BK / 4)) * 4;
+            const float4 a = abs4(pa[i]);
+            float2* da = reinterpret_cast<float2*>(&As[row * SA + k]);
+            da[0] = make_float2(a.x, a.y); da[1] = make_float2(a.z, a.w);
+            const float4 w = abs4(pw[i]);
+            if (!TRANS_W) {
+                float2* dw = reinterpret_cast<float2*>(&Ws[row * SA + k]);
+                dw[0] = make_float2(w.x, w.y); dw[1] = make_float2(w.z, w.w);
+            } else {
+                const int kr = f / (BN / 4), n = (f % (BN / 4)) * 4;
+                *reinterpret_cast<float4*>(&Ws[kr * SWT + n]) = w;
+            }
+        }
+    };
+
+    double S[2][2][16];
+    floatx16 chain[2][2];
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+        for (int tj = 0; tj < 2; ++tj) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) { S[ti][tj][v] = 0.0; chain[ti][tj][v] = 0.f; }
+        }
+
+    const long nslab = (p.K + BK - 1) / BK;
+    if (nslab > 0) { prefetch(0); commit(); }
+    __syncthreads();
+    for (long s = 0; s < nslab; ++s) {
+        const bool more = s + 1 < nslab;
+        if (more) prefetch((s + 1) * BK);
+#pragma unroll 1
+        for (int pr = 0; pr < BK / 12; ++pr) {
+            const int kb = pr * 12 + 6 * h;           // this half-wavefront's six k indices
+            float a[2][6], b[2][6];
+#pragma unroll
+            for (int ti = 0; ti < 2; ++ti) {
+                const float2* src = reinterpret_cast<const float2*>(&As[(wm * 64 + ti * 32 + r32) * SA + kb]);
+                const float2 v0 = src[0], v1 = src[1], v2 = src[2];
+                a[ti][0] = v0.x; a[ti][1] = v0.y; a[ti][2] = v1.x; a[ti][3] = v1.y; a[ti][4] = v2.x; a[ti][5] = v2.y;
+            }
+#pragma unroll
+            for (int tj = 0; tj < 2; ++tj) {
+                if (!TRANS_W) {
+                    const float2* src = reinterpret_cast<const float2*>(&Ws[(wn * 64 + tj * 32 + r32) * SA + kb]);
+                    const float2 v0 = src[0], v1 = src[1], v2 = src[2];
+                    b[tj][0] = v0.x; b[tj][1] = v0.y; b[tj][2] = v1.x; b[tj][3] = v1.y; b[tj][4] = v2.x; b[tj][5] = v2.y;
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 6; ++j) b[tj][j] = Ws[(kb + j) * SWT + wn * 64 + tj * 32 + r32];
+                }
+            }
+#pragma unroll
+            for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+                for (int tj = 0; tj < 2; ++tj) {
+                    if (FAST) {
+                        floatx16 c = chain[ti][tj];
+#pragma unroll
+                        for (int j = 0; j < 6; ++j)
+                            c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ti][j], b[tj][j], c, 0, 0, 0);
+                        chain[ti][tj] = c;
+                    } else {
+                        floatx16 z;
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) z[v] = 0.f;
+                        floatx16 c0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ti][0], b[tj][0], z, 0, 0, 0);
+                        c0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ti][1], b[tj][1], c0, 0, 0, 0);
+                        c0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ti][2], b[tj][2], c0, 0, 0, 0);
+                        floatx16 c1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ti][3], b[tj][3], z, 0, 0, 0);
+                        c1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ti][4], b[tj][4], c1, 0, 0, 0);
+                        c1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ti][5], b[tj][5], c1, 0, 0, 0);
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) S[ti][tj][v] += (double)(c0[v] + c1[v]);
+                    }
+                }
+        }
+        __syncthreads();
+        if (more) { commit(); __syncthreads(); }
+    }
+
+    // epilogue: D[i][j] of a 32x32 tile sits in lane (j + 32*((i/4)%2)), register 4*(i/8) + i%4
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+        for (int tj = 0; tj < 2; ++tj) {
+            const long col = n0 + wn * 64 + tj * 32 + r32;
+            const double ab = (p.bias && col < p.N) ? fabs((double)p.bias[col]) : 0.0;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const long row = m0 + wm * 64 + ti * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                if (row < p.M && col < p.N) {
+                    const double s = FAST ? (double)chain[ti][tj][v] : S[ti][tj][v];
+                    const double t = p.c * (s * p.infl + ab) * kGuard + p.uflow;
+                    T[row * p.ldt + col] = up32(t);
+                }
+            }
+        }
+}
+
+// ---- matrix-core self test ----------------------------------------------------------------
+// out[v*64 + lane] = register v of the accumulator after `steps` chained MFMAs from zero.
+__global__ void mfma_probe(const float* __restrict__ a, const float* __restrict__ b, int steps,
+                           float* __restrict__ out) {
+    const int lane = threadIdx.x;
+    floatx16 c;
+    for (int v = 0; v < 16; ++v) c[v] = 0.f;
+    for (int s = 0; s < steps; ++s)
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s * 64 + lane], b[s * 64 + lane], c, 0, 0, 0);
+    for (int v = 0; v < 16; ++v) out[v * 64 + lane] = c[v];
+}
+
+}  // namespace tao
+
+extern "C" {
+
+int tao_bound_linear(const float* A, const float* W, const float* bias, float* tau,
+                     long M, long N, long K, long lda, long ldw, long ldt, int trans_w,
+                     long batch, long strideA, long strideW, long strideT,
+                     const tao_fp_model* model, void* stream) {
+    using namespace tao;
+    tao_fp_model md;
+    int rc = resolve_model(model, &md);
+    if (rc != TAO_OK) return rc;
+    if (M < 0 || N < 0 || K < 0 || batch < 0) return TAO_ERR_SHAPE;
+    if (lda < K || ldt < N || ldw < (trans_w ? N : K)) return TAO_ERR_SHAPE;
+    if (strideA < 0 || strideW < 0 || strideT < 0) return TAO_ERR_SHAPE;
+    if (batch > 1 && strideT < M * ldt - (ldt - N)) return TAO_ERR_SHAPE;   // outputs would overlap
+    if (batch > 65535) return TAO_ERR_SHAPE;
+    const long Kp = K + (bias ? 1 : 0);
+    const double c = gamma_up(Kp, md);
+    if (!(c == c)) return TAO_ERR_K_RANGE;
+    if (M == 0 || N == 0 || batch == 0) return TAO_OK;
+    if (!tau || (K > 0 && (!A || !W))) return TAO_ERR_NULL;
+    if (!aligned(A, 4) || !aligned(W, 4) || !aligned(bias, 4) || !aligned(tau, 4)) return TAO_ERR_ALIGN;
+
+    LinArgs p;
+    p.A = A; p.W = W; p.bias = bias; p.tau = tau;
+    p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldw = ldw; p.ldt = ldt;
+    p.strideA = strideA; p.strideW = strideW; p.strideT = strideT;
+    p.vecA = aligned(A, 16) && (lda % 4 == 0) && (strideA % 4 == 0);
+    p.vecW = aligned(W, 16) && (ldw % 4 == 0) && (strideW % 4 == 0);
+    p.c = c;
+    const bool fast = (md.flags & TAO_FLAG_FAST_ACCUM) != 0;
+    const double u = md.u;
+    // lower rounding factor: (1-u)^r (1-2^-53)^f with r roundings in binary32, f in binary64
+    const double r32 = fast ? (double)(K > 0 ? K : 1) : 7.0;
+    const double f64 = (double)(K / 12 + 2);
+    if (!(r32 * u < 0.5)) return TAO_ERR_K_RANGE;
+    const double lower = (1.0 - r32 * u) * (1.0 - f64 * 0x1p-53);   // <= (1-u)^r (1-2^-53)^f
+    p.infl = widen(1.0 / (lower * (1.0 - 0x1p-52)));
+    p.uflow = (md.flags & TAO_FLAG_UNDERFLOW_TERMS) ? (double)Kp * 0x1p-149 : 0.0;
+
+    dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM), (unsigned)batch);
+    if (grid.y > 65535u) return TAO_ERR_SHAPE;
+    hipStream_t st = (hipStream_t)stream;
+    if (trans_w) {
+        if (fast) hipLaunchKernelGGL((absgemm_bound<true, true>), grid, dim3(kLinThreads), 0, st, p);
+        else      hipLaunchKernelGGL((absgemm_bound<true, false>), grid, dim3(kLinThreads), 0, st, p);
+    } else {
+        if (fast) hipLaunchKernelGGL((absgemm_bound<false, true>), grid, dim3(kLinThreads), 0, st, p);
+        else      hipLaunchKernelGGL((absgemm_bound<false, false>), grid, dim3(kLinThreads), 0, st, p);
+    }
+    return launch_status();
+}
+
+int tao_selftest_matrix_core(unsigned* report, void* stream) {
+    using namespace tao;
+    if (!report) return TAO_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    const int kSteps = 3;
+    float ha[kSteps * 64], hb[kSteps * 64], hout[16 * 64];
+    float *da = nullptr, *db = nullptr, *dout = nullptr;
+    auto fail = [&](hipError_t e) { g_last_hip_error = (int)e; (void)hipFree(da); (void)hipFree(db); (void)hipFree(dout); return TAO_ERR_LAUNCH; };
+    hipError_t e;
+    if ((e = hipMalloc(&da, sizeof(ha))) != hipSuccess) return fail(e);
+    if ((e = hipMalloc(&db, sizeof(hb))) != hipSuccess) return fail(e);
+    if ((e = hipMalloc(&dout, sizeof(hout))) != hipSuccess) return fail(e);
+    auto run = [&](int steps) -> hipError_t {
+        hipError_t r;
+        if ((r = hipMemcpyAsync(da, ha, sizeof(ha), hipMemcpyHostToDevice, st)) != hipSuccess) return r;
+        if ((r = hipMemcpyAsync(db, hb, sizeof(hb), hipMemcpyHostToDevice, st)) != hipSuccess) return r;
+        hipLaunchKernelGGL(mfma_probe, dim3(1), dim3(64), 0, st, da, db, steps, dout);
+        if ((r = hipGetLastError()) != hipSuccess) return r;
+        if ((r = hipMemcpyAsync(hout, dout, sizeof(hout), hipMemcpyDeviceToHost, st)) != hipSuccess) return r;
+        return hipStreamSynchronize(st);
+    };
+    // operand element (i, k) of A lives in lane i + 32 k; element (k, j) of B in lane j + 32 k
+    auto D = [&](int i, int j) { return hout[(4 * (i / 8) + i % 4) * 64 + j + 32 * ((i / 4) % 2)]; };
+    unsigned rep = 0;
+
+    // (a) rounding of the accumulation and subnormals: one instruction, D[i][0] = x_i * 1 + y_i * 1
+    for (int k = 0; k < kSteps * 64; ++k) { ha[k] = 0.f; hb[k] = 0.f; }
+    hb[0] = 1.f;             // B[0][0]
+    hb[32] = 1.f;            // B[1][0]
+    hb[1] = 0x1p-100f;       // B[0][1]
+    ha[0] = 1.f;              ha[32 + 0] = 0x1p-24f;       // tie, even below: stays 1
+    ha[1] = 1.f + 0x1p-23f;   ha[32 + 1] = 0x1p-24f;       // tie, even above: 1 + 2^-22
+    ha[2] = 1.f;              ha[32 + 2] = 0x1.8p-24f;     // above the tie: 1 + 2^-23
+    ha[3] = 0x1p-40f;                                       // times 2^-100: subnormal product
+    ha[4] = 0x1p-130f;                                      // subnormal operand
+    if ((e = run(1)) != hipSuccess) return fail(e);
+    if (D(0, 0) == 1.f && D(1, 0) == 1.f + 0x1p-22f && D(2, 0) == 1.f + 0x1p-23f) rep |= 1u;
+    if (D(3, 1) == 0x1p-140f && D(4, 0) == 0x1p-130f) rep |= 2u;
+
+    // (b) three chained instructions on pseudo-random non-negative data vs the exact sum
+    unsigned long long lcg = 0x9E3779B97F4A7C15ull;
+    auto rnd = [&]() { lcg = lcg * 6364136223846793005ull + 1442695040888963407ull; return (float)((lcg >> 40) + 1) * 0x1p-24f; };
+    for (int k = 0; k < kSteps * 64; ++k) { ha[k] = rnd(); hb[k] = rnd() * 4.f; }
+    if ((e = run(kSteps)) != hipSuccess) return fail(e);
+    bool within = true;
+    const double g6 = 6.0 * 0x1p-24 / (1.0 - 6.0 * 0x1p-24);
+    for (int i = 0; i < 32 && within; ++i)
+        for (int j = 0; j < 32; ++j) {
+            double s = 0.0;
+            for (int st3 = 0; st3 < kSteps; ++st3)
+                for (int kk = 0; kk < 2; ++kk)
+                    s += (double)ha[st3 * 64 + i + 32 * kk] * (double)hb[st3 * 64 + j + 32 * kk];
+            if (!(std::fabs((double)D(i, j) - s) <= g6 * s)) { within = false; break; }
+        }
+    if (within) rep |= 4u;
+    (void)hipFree(da); (void)hipFree(db); (void)hipFree(dout);
+    *report = rep;
+    return TAO_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,399 @@
+// Row-wise bound kernels: tao_bound_softmax and tao_bound_norm.
+//
+// One "row group" of TPR threads (a wavefront, or a whole 256-thread workgroup
+// for long rows) owns one row.  The row is read once with 16-byte loads and
+// kept in registers (V vectors per thread); row statistics are accumulated in
+// binary64 and combined with wavefront shuffles (plus one LDS exchange when the
+// group spans four wavefronts); the bound is written once.  HBM traffic is the
+// algorithmic minimum: each input element read once, each tau written once.
+// Rows longer than 8192 columns take the V == 0 variant, which re-reads the row
+// from global memory in each pass instead of caching it.
+//
+// Formulas: Sec. 3.1 softmax template closed to second order; LayerNorm,
+// RMSNorm, BatchNorm-affine, sum and mean (operators of App. A.3) from the
+// primitive rule of Sec. 3.1 with Gamma(n-1) for the reductions (App. A.2).
+#include "tao_device.hpp"
+#include "tao_host.hpp"
+
+namespace tao {
+
+constexpr int kRowThreads = 256;
+
+struct RowConsts {
+    double u;          // unit roundoff
+    double G;          // Gamma(cols - 1), upper
+    double inv1mu;     // >= 1/(1-u)
+    double ce_u;       // c_exp * u
+    double inv1mce;    // >= 1/(1 - c_exp u)
+    double cd_u;       // c_div * u
+    double inv1mcd;    // >= 1/(1 - c_div u)
+    double cr_u;       // c_rsqrt * u
+    double eps;        // (double)(float)eps
+    double inv_n;      // 1/cols (nearest; covered by the guard factor)
+    double mean_f;     // c_div u / (1 - c_div u), upper
+};
+
+// ---- reductions over the TPR threads of a row group (result in every thread) ----
+template <int TPR>
+__device__ __forceinline__ void group_sum(double* v, int count, double* smem) {
+    for (int i = 0; i < count; ++i) v[i] = wave_sum(v[i]);
+    if (TPR > kWave) {
+        const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+        __syncthreads();                         // smem may still be read from a previous call
+        if (lane == 0) for (int i = 0; i < count; ++i) smem[wave * 4 + i] = v[i];
+        __syncthreads();
+        for (int i = 0; i < count; ++i) {
+            double s = 0;
+            for (int w = 0; w < TPR / kWave; ++w) s += smem[w * 4 + i];
+            v[i] = s;
+        }
+    }
+}
+template <int TPR>
+__device__ __forceinline__ void group_max_or(float& m, int& flag, double* smem) {
+    m = wave_max(m);
+    flag = wave_or(flag);
+    if (TPR > kWave) {
+        const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+        __syncthreads();
+        if (lane == 0) { smem[wave * 4] = (double)m; smem[wave * 4 + 1] = (double)flag; }
+        __syncthreads();
+        float mm = -INFINITY; int ff = 0;
+        for (int w = 0; w < TPR / kWave; ++w) { mm = fmaxf(mm, (float)smem[w * 4]); ff |= (int)smem[w * 4 + 1]; }
+        m = mm; flag = ff;
+    }
+}
+
+#define TAO_ROW_PROLOGUE                                                              \
+    constexpr int RPB = kRowThreads / TPR;                                            \
+    constexpr bool CACHED = (V > 0);                                                  \
+    __shared__ double smem[16];                                                       \
+    const int lt = threadIdx.x % TPR;                                                 \
+    const long row = (long)blockIdx.x * RPB + threadIdx.x / TPR;                      \
+    const bool active = row < rows;                                                   \
+    const long limit = active ? cols : 0; /* idle groups see an empty row */          \
+    const long roff = active ? row * ld : 0;                                          \
+    const int nv = CACHED ? V : (int)((cols + TPR * 4 - 1) / (TPR * 4));              \
+    (void)smem;
+
+#define TAO_VEC_INDEX(v) (((long)(v) * TPR + lt) * 4)
+
+// ------------------------------------------------------------------ softmax
+template <int TPR, int V>
+__global__ __launch_bounds__(kRowThreads) void softmax_bound(
+    const float* __restrict__ x, const float* __restrict__ y, float* __restrict__ tau,
+    long rows, long cols, long ld, int vec_ok, RowConsts k) {
+    TAO_ROW_PROLOGUE
+    float4 xv[CACHED ? V : 1], yv[CACHED ? V : 1];
+    float m = -INFINITY; int bad = 0;
+    for (int v = 0; v < nv; ++v) {
+        const float4 X = load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, -INFINITY);
+        if (CACHED) { xv[v] = X; yv[v] = load4(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f); }
+        const float e[4] = {X.x, X.y, X.z, X.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { bad |= (e[c] != e[c]) | (e[c] == INFINITY); m = fmaxf(m, e[c]); }
+    }
+    group_max_or<TPR>(m, bad, smem);
+    if (m == -INFINITY) bad = 1;
+    const double am = fabs((double)m);
+    double acc[2] = {0.0, 0.0};                                  // sum q, sum rho q
+    for (int v = 0; v < nv; ++v) {
+        const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, -INFINITY);
+        const float4 Y = CACHED ? yv[v] : load4(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (xe[c] == -INFINITY) continue;
+            const double a = k.u * (fabs((double)xe[c]) + am);
+            const double rho = (a * (1.0 + a) + k.ce_u) * k.inv1mce;
+            const double q = fabs((double)ye[c]) * k.inv1mu;
+            acc[0] += q; acc[1] += rho * q;
+        }
+    }
+    group_sum<TPR>(acc, 2, smem);
+    const double sigma = k.G * acc[0] + (1.0 + k.G) * acc[1];
+    if (!(sigma < 1.0)) bad = 1;
+    const double sfac = sigma / (1.0 - sigma);
+    for (int v = 0; v < nv; ++v) {
+        const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, -INFINITY);
+        const float4 Y = CACHED ? yv[v] : load4(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w};
+        float te[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const double a = k.u * (fabs((double)xe[c]) + am);
+            const double rho = (a * (1.0 + a) + k.ce_u) * k.inv1mce;
+            const double ay = fabs((double)ye[c]);
+            const double q = ay * k.inv1mu;
+            const double t = q * rho + q * (1.0 + rho) * sfac + k.u * ay;
+            te[c] = bad ? NAN : (xe[c] == -INFINITY ? 0.f : up32(t * kGuard));
+        }
+        store4(tau + roff, TAO_VEC_INDEX(v), limit, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
+    }
+}
+
+// tail shared by LayerNorm and RMSNorm: from v*, E_v to (r*, E_r, R); ok = finite bound
+__device__ __forceinline__ bool rsqrt_tail(double vstar, double E_v, const RowConsts& k,
+                                           double& rs, double& E_r, double& R) {
+    const double w = vstar + k.eps;
+    const double E_w = (E_v + k.u * w) * k.inv1mu;
+    const double w_lo = w - E_w;
+    const bool ok = w_lo > 0.0;
+    const double inv_s = 1.0 / sqrt(w_lo);
+    const double inv_s3 = inv_s / w_lo;
+    E_r = 0.5 * E_w * inv_s3 + k.cr_u * inv_s;
+    rs = 1.0 / sqrt(w);
+    R = rs + E_r;
+    return ok;
+}
+
+// ------------------------------------------------------------------ LayerNorm
+template <int TPR, int V>
+__global__ __launch_bounds__(kRowThreads) void layernorm_bound(
+    const float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ g,
+    float* __restrict__ tau, long rows, long cols, long ld, int vec_ok, int vec_g, RowConsts k) {
+    TAO_ROW_PROLOGUE
+    float4 xv[CACHED ? V : 1];
+    double a1[2] = {0.0, 0.0};                                   // sum x, sum |x|
+    for (int v = 0; v < nv; ++v) {
+        const float4 X = load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        if (CACHED) xv[v] = X;
+        const float e[4] = {X.x, X.y, X.z, X.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { a1[0] += (double)e[c]; a1[1] += fabs((double)e[c]); }
+    }
+    group_sum<TPR>(a1, 2, smem);
+    const double mu = a1[0] * k.inv_n;
+    const double E_mu = ((k.G * a1[1]) * k.inv_n + k.cd_u * fabs(mu)) * k.inv1mcd;
+    double a2[3] = {0.0, 0.0, 0.0};                              // sum Q, sum E_q, sum d^2
+    for (int v = 0; v < nv; ++v) {
+        const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        const float e[4] = {X.x, X.y, X.z, X.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (TAO_VEC_INDEX(v) + c >= limit) continue;
+            const double ad = fabs((double)e[c] - mu);
+            const double E_d = (E_mu + k.u * ad) * k.inv1mu;
+            const double D = ad + E_d;
+            a2[0] += D * D * (1.0 + k.u);
+            a2[1] += E_d * (ad + D) + k.u * D * D;
+            a2[2] += ad * ad;
+        }
+    }
+    group_sum<TPR>(a2, 3, smem);
+    const double E_t = k.G * a2[0] + a2[1];
+    const double vstar = a2[2] * k.inv_n;
+    const double E_v = (E_t * k.inv_n + k.cd_u * vstar) * k.inv1mcd;
+    double rs, E_r, R;
+    const bool ok = rsqrt_tail(vstar, E_v, k, rs, E_r, R);
+    for (int v = 0; v < nv; ++v) {
+        const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        const float4 Y = load4(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        const float4 Gv = g ? load4(g, TAO_VEC_INDEX(v), limit, vec_g, 1.f) : make_float4(1.f, 1.f, 1.f, 1.f);
+        const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w};
+        const float ge[4] = {Gv.x, Gv.y, Gv.z, Gv.w};
+        float te[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const double ad = fabs((double)xe[c] - mu);
+            const double E_d = (E_mu + k.u * ad) * k.inv1mu;
+            const double D = ad + E_d;
+            const double E_h = D * E_r + rs * E_d + k.u * D * R;
+            const double H = ad * rs + E_h;
+            const double ag = fabs((double)ge[c]);
+            const double E_p = ag * E_h + k.u * ag * H;
+            const double t = E_p + k.u * fabs((double)ye[c]);
+            te[c] = ok ? up32(t * kGuard) : NAN;
+        }
+        store4(tau + roff, TAO_VEC_INDEX(v), limit, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
+    }
+}
+
+// ------------------------------------------------------------------ RMSNorm
+template <int TPR, int V>
+__global__ __launch_bounds__(kRowThreads) void rmsnorm_bound(
+    const float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ g,
+    float* __restrict__ tau, long rows, long cols, long ld, int vec_ok, int vec_g, RowConsts k) {
+    TAO_ROW_PROLOGUE
+    float4 xv[CACHED ? V : 1];
+    double a1[1] = {0.0};
+    for (int v = 0; v < nv; ++v) {
+        const float4 X = load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        if (CACHED) xv[v] = X;
+        const float e[4] = {X.x, X.y, X.z, X.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) a1[0] += (double)e[c] * (double)e[c];
+    }
+    group_sum<TPR>(a1, 1, smem);
+    const double E_t = (k.G * (1.0 + k.u) + k.u) * a1[0];
+    const double vstar = a1[0] * k.inv_n;
+    const double E_v = (E_t * k.inv_n + k.cd_u * vstar) * k.inv1mcd;
+    double rs, E_r, R;
+    const bool ok = rsqrt_tail(vstar, E_v, k, rs, E_r, R);
+    const double f = E_r + k.u * R;
+    for (int v = 0; v < nv; ++v) {
+        const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        const float4 Y = load4(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        const float4 Gv = g ? load4(g, TAO_VEC_INDEX(v), limit, vec_g, 1.f) : make_float4(1.f, 1.f, 1.f, 1.f);
+        const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w};
+        const float ge[4] = {Gv.x, Gv.y, Gv.z, Gv.w};
+        float te[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const double xg = fabs((double)xe[c] * (double)ge[c]);
+            const double t = xg * f + k.u * fabs((double)ye[c]);
+            te[c] = ok ? up32(t * kGuard) : NAN;
+        }
+        store4(tau + roff, TAO_VEC_INDEX(v), limit, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
+    }
+}
+
+// ------------------------------------------------------------------ sum / mean
+template <int TPR, int V>
+__global__ __launch_bounds__(kRowThreads) void summean_bound(
+    const float* __restrict__ x, const float* __restrict__ y, float* __restrict__ tau,
+    long rows, long cols, long ld, int vec_ok, int is_mean, RowConsts k) {
+    TAO_ROW_PROLOGUE
+    double a1[1] = {0.0};
+    for (int v = 0; v < nv; ++v) {
+        const float4 X = load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        a1[0] += fabs((double)X.x) + fabs((double)X.y) + fabs((double)X.z) + fabs((double)X.w);
+    }
+    group_sum<TPR>(a1, 1, smem);
+    if (active && lt == 0) {
+        double t = k.G * a1[0];
+        if (is_mean) t = t * k.inv_n + fabs((double)y[row]) * k.mean_f;
+        tau[row] = up32(t * kGuard);
+    }
+}
+
+// ------------------------------------------------------------------ BatchNorm-affine
+// tau = u |x s_c| (1+u) + u |y|, column c = flat index mod cols; one thread per 4 columns.
+__global__ __launch_bounds__(kRowThreads) void bn_affine_bound(
+    const float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ s,
+    float* __restrict__ tau, long rows, long cols, long ld, int vec_ok, int vec_s, double u) {
+    const long vpr = (cols + 3) / 4;                       // vectors per row
+    const long total = rows * vpr;
+    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
+        const long row = i / vpr, j = (i - row * vpr) * 4;
+        const float4 X = load4(x + row * ld, j, cols, vec_ok, 0.f);
+        const float4 Y = load4(y + row * ld, j, cols, vec_ok, 0.f);
+        const float4 S = load4(s, j, cols, vec_s, 0.f);
+        const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w}, se[4] = {S.x, S.y, S.z, S.w};
+        float te[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const double xs = fabs((double)xe[c] * (double)se[c]);
+            const double t = u * xs * (1.0 + u) + u * fabs((double)ye[c]);
+            te[c] = up32(t * kGuard);
+        }
+        store4(tau + row * ld, j, cols, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
+    }
+}
+
+// Pick the row-group shape for a row length and launch KERNEL<TPR, V>.
+#define TAO_DISPATCH_ROWS(KERNEL, rows, cols, stream, ...)                                          \
+    do {                                                                                            \
+        const long c_ = (cols);                                                                     \
+        auto grid_ = [&](int tpr) { return dim3((unsigned)(((rows) + (kRowThreads / tpr) - 1) / (kRowThreads / tpr))); }; \
+        if (c_ <= 256)       hipLaunchKernelGGL((KERNEL<64, 1>), grid_(64), dim3(kRowThreads), 0, stream, __VA_ARGS__);   \
+        else if (c_ <= 512)  hipLaunchKernelGGL((KERNEL<64, 2>), grid_(64), dim3(kRowThreads), 0, stream, __VA_ARGS__);   \
+        else if (c_ <= 1024) hipLaunchKernelGGL((KERNEL<64, 4>), grid_(64), dim3(kRowThreads), 0, stream, __VA_ARGS__);   \
+        else if (c_ <= 2048) hipLaunchKernelGGL((KERNEL<256, 2>), grid_(256), dim3(kRowThreads), 0, stream, __VA_ARGS__); \
+        else if (c_ <= 4096) hipLaunchKernelGGL((KERNEL<256, 4>), grid_(256), dim3(kRowThreads), 0, stream, __VA_ARGS__); \
+        else if (c_ <= 8192) hipLaunchKernelGGL((KERNEL<256, 8>), grid_(256), dim3(kRowThreads), 0, stream, __VA_ARGS__); \
+        else                 hipLaunchKernelGGL((KERNEL<256, 0>), grid_(256), dim3(kRowThreads), 0, stream, __VA_ARGS__); \
+    } while (0)
+
+static int make_consts(const tao_fp_model& md, long cols, double eps, RowConsts* k) {
+    const double G = gamma_up(cols - 1, md);
+    if (!(G == G)) return TAO_ERR_K_RANGE;
+    const double u = md.u;
+    k->u = u; k->G = G;
+    k->inv1mu = widen(1.0 / (1.0 - u));
+    k->ce_u = md.c_exp * u;
+    k->inv1mce = widen(1.0 / (1.0 - md.c_exp * u));
+    k->cd_u = md.c_div * u;
+    k->inv1mcd = widen(1.0 / (1.0 - md.c_div * u));
+    k->cr_u = md.c_rsqrt * u;
+    k->eps = (double)(float)eps;
+    k->inv_n = 1.0 / (double)cols;
+    k->mean_f = widen(k->cd_u * k->inv1mcd);
+    if (!(md.c_exp * u < 0.5) || !(md.c_div * u < 0.5)) return TAO_ERR_MODEL;
+    return TAO_OK;
+}
+
+}  // namespace tao
+
+extern "C" {
+
+int tao_bound_softmax(const float* x, const float* y_ref, float* tau, long rows, long cols, long ld,
+                      const tao_fp_model* model, void* stream) {
+    using namespace tao;
+    tao_fp_model md;
+    int rc = resolve_model(model, &md);
+    if (rc != TAO_OK) return rc;
+    if (rows < 0 || cols < 0 || ld < cols) return TAO_ERR_SHAPE;
+    if (rows == 0 || cols == 0) return TAO_OK;
+    if (!x || !y_ref || !tau) return TAO_ERR_NULL;
+    if (!aligned(x, 4) || !aligned(y_ref, 4) || !aligned(tau, 4)) return TAO_ERR_ALIGN;
+    RowConsts k;
+    rc = make_consts(md, cols, 0.0, &k);
+    if (rc != TAO_OK) return rc;
+    const int vec_ok = aligned(x, 16) && aligned(y_ref, 16) && aligned(tau, 16) && (ld % 4 == 0);
+    hipStream_t st = (hipStream_t)stream;
+    TAO_DISPATCH_ROWS(softmax_bound, rows, cols, st, x, y_ref, tau, rows, cols, ld, vec_ok, k);
+    return launch_status();
+}
+
+int tao_bound_norm(int kind, const float* x, const float* y_ref, const float* gamma_or_scale,
+                   const float* beta_or_shift, double eps, float* tau, long rows, long cols, long ld,
+                   const tao_fp_model* model, void* stream) {
+    using namespace tao;
+    (void)beta_or_shift;
+    tao_fp_model md;
+    int rc = resolve_model(model, &md);
+    if (rc != TAO_OK) return rc;
+    if (kind < TAO_NORM_LAYERNORM || kind > TAO_NORM_MEAN) return TAO_ERR_KIND;
+    if (rows < 0 || cols < 0 || ld < cols) return TAO_ERR_SHAPE;
+    if (rows == 0) return TAO_OK;
+    if (cols == 0 && kind != TAO_NORM_SUM && kind != TAO_NORM_MEAN) return TAO_OK;
+    if (cols == 0) return TAO_ERR_SHAPE;
+    if (!x || !tau) return TAO_ERR_NULL;
+    if (kind != TAO_NORM_SUM && !y_ref) return TAO_ERR_NULL;
+    if (kind == TAO_NORM_BN_AFFINE && !gamma_or_scale) return TAO_ERR_NULL;
+    if (!aligned(x, 4) || !aligned(y_ref, 4) || !aligned(tau, 4) || !aligned(gamma_or_scale, 4)) return TAO_ERR_ALIGN;
+    if (!(eps >= 0.0) || !std::isfinite(eps)) return TAO_ERR_SHAPE;
+    RowConsts k;
+    rc = make_consts(md, cols, eps, &k);
+    if (rc != TAO_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const int vec_x = aligned(x, 16) && (ld % 4 == 0);
+    const int vec_ok = vec_x && aligned(y_ref, 16) && aligned(tau, 16);
+    const int vec_g = aligned(gamma_or_scale, 16);
+    const float* g = gamma_or_scale;
+    switch (kind) {
+        case TAO_NORM_LAYERNORM:
+            TAO_DISPATCH_ROWS(layernorm_bound, rows, cols, st, x, y_ref, g, tau, rows, cols, ld, vec_ok, vec_g, k);
+            break;
+        case TAO_NORM_RMSNORM:
+            TAO_DISPATCH_ROWS(rmsnorm_bound, rows, cols, st, x, y_ref, g, tau, rows, cols, ld, vec_ok, vec_g, k);
+            break;
+        case TAO_NORM_BN_AFFINE: {
+            const long total = rows * ((cols + 3) / 4);
+            long blocks = (total + kRowThreads - 1) / kRowThreads;
+            if (blocks > 256L * 16) blocks = 256L * 16;
+            hipLaunchKernelGGL(bn_affine_bound, dim3((unsigned)blocks), dim3(kRowThreads), 0, st, x, y_ref, g,
+                               tau, rows, cols, ld, vec_ok, vec_g, md.u);
+            break;
+        }
+        default: {
+            const int is_mean = (kind == TAO_NORM_MEAN);
+            TAO_DISPATCH_ROWS(summean_bound, rows, cols, st, x, y_ref, tau, rows, cols, ld, vec_x, is_mean, k);
+            break;
+        }
+    }
+    return launch_status();
+}
+
+}  // extern "C"

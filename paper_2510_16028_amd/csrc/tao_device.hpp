@@ -1,0 +1,61 @@
+// Device-side helpers shared by the gfx950 kernels of the tolerance engine.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tao {
+
+constexpr int kWave = 64;
+
+// Smallest binary32 value >= v, for v >= 0 (NaN and +inf pass through).  The
+// conversion itself rounds to nearest; one step up repairs a round-down.
+__device__ __forceinline__ float up32(double v) {
+    float f = (float)v;
+    if ((double)f < v) f = __uint_as_float(__float_as_uint(f) + 1u);
+    return f;
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+__device__ __forceinline__ int wave_or(int v) {
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) v |= __shfl_xor(v, o, kWave);
+    return v;
+}
+
+// 16-byte global load when the caller has established alignment, else four
+// guarded scalar loads; elements at or beyond `limit` read as `fill`.
+__device__ __forceinline__ float4 load4(const float* __restrict__ p, long idx, long limit,
+                                        bool vec_ok, float fill) {
+    float4 r;
+    if (vec_ok && idx + 3 < limit) {
+        r = *reinterpret_cast<const float4*>(p + idx);
+    } else {
+        r.x = (idx + 0 < limit) ? p[idx + 0] : fill;
+        r.y = (idx + 1 < limit) ? p[idx + 1] : fill;
+        r.z = (idx + 2 < limit) ? p[idx + 2] : fill;
+        r.w = (idx + 3 < limit) ? p[idx + 3] : fill;
+    }
+    return r;
+}
+__device__ __forceinline__ void store4(float* __restrict__ p, long idx, long limit, bool vec_ok,
+                                       float4 v) {
+    if (vec_ok && idx + 3 < limit) {
+        *reinterpret_cast<float4*>(p + idx) = v;
+    } else {
+        if (idx + 0 < limit) p[idx + 0] = v.x;
+        if (idx + 1 < limit) p[idx + 1] = v.y;
+        if (idx + 2 < limit) p[idx + 2] = v.z;
+        if (idx + 3 < limit) p[idx + 3] = v.w;
+    }
+}
+
+}  // namespace tao

@@ -1,0 +1,34 @@
+// Host-side helpers of the C ABI: status handling, model validation and the
+// scalar constants (Gamma, guard factors) that the kernels take as arguments.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cmath>
+#include <cstdint>
+#include "tao.h"
+
+namespace tao {
+
+extern thread_local int g_last_hip_error;
+
+inline int launch_status() {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { g_last_hip_error = (int)e; return TAO_ERR_LAUNCH; }
+    return TAO_OK;
+}
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+// Returns TAO_OK and fills *out with the validated model (defaults when m == NULL).
+int resolve_model(const tao_fp_model* m, tao_fp_model* out);
+
+// Upper enclosures in binary64 (round-to-nearest evaluation widened by a few ulps).
+double gamma_up(long k, const tao_fp_model& m);            // NaN when undefined
+inline double widen(double v) { return v * (1.0 + 0x1p-49); }   // for v >= 0
+
+// Every kernel evaluates its formula in round-to-nearest binary64 and multiplies
+// the result by this factor before rounding up to binary32; it dominates the
+// accumulated binary64 rounding (at most ~2^-52 per operation, rows up to 2^19
+// elements) so the emitted bound is never below the real-number value.
+constexpr double kGuard = 1.0 + 0x1p-32;
+
+}  // namespace tao

@@ -1,0 +1,247 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by
+element, on the benchmark configurations at sizes the oracle finishes in seconds, plus
+edge cases.  Bounds: oracle <= gpu <= oracle (1 + 1e-6).  Check/profile: bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+import tao_inputs
+from opmap import assert_bound_parity, assert_profile_equal, gpu_tau, oracle_tau
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tao():
+    import paper_2510_16028_amd as t
+    t.lib()
+    assert torch.cuda.is_available()
+    return t
+
+
+def _np(t):
+    return t.detach().cpu().numpy()
+
+
+def _run_ops(tao, oracle_mod, ops, expect_zero_violations=True):
+    for op in ops:
+        print("op", op.name, op.kind, tuple(op.y_ref.shape), flush=True)
+        t_or = oracle_tau(oracle_mod, op)
+        t_gpu = gpu_tau(tao, op)
+        torch.cuda.synchronize()
+        worst = assert_bound_parity(_np(t_gpu), t_or, op.name)
+        print("   max tau_gpu/tau_oracle - 1 = %.3e" % worst, flush=True)
+        # check + profile on identical inputs (the oracle's tau on both sides): bit-exact
+        tau_dev = torch.from_numpy(np.ascontiguousarray(t_or)).cuda()
+        pg = tao.tao_check_and_profile(op.claimed.cuda().contiguous(), op.y_ref.cuda().contiguous(), tau_dev)
+        po = oracle_mod.check_and_profile(_np(op.claimed), _np(op.y_ref), t_or)
+        assert_profile_equal(pg, po, op.name)
+        if expect_zero_violations:
+            assert pg["violations"] == 0 and pg["accept"] == 1, op.name
+            # and the GPU's own bound accepts the honest claim as well
+            pe = tao.tao_check_and_profile(op.claimed.cuda().contiguous(), op.y_ref.cuda().contiguous(),
+                                           t_gpu.contiguous())
+            assert pe["violations"] == 0, op.name
+
+
+def test_matrix_core_selftest(tao):
+    rep = tao.tao_selftest_matrix_core()
+    print("matrix-core self test report:", rep, flush=True)
+    assert rep & 1, "accumulation is not round-to-nearest-even"
+    assert rep & 4, "6-step chain exceeds gamma_6"
+
+
+def test_config1_linear_and_softmax(tao, oracle_mod):
+    ops = tao_inputs.config1("cpu")
+    _run_ops(tao, oracle_mod, ops)
+    # closed form of the workload: +-{0..3} ulp noise => max relative error <= 3 * 2^-23
+    p = tao.tao_check_and_profile(ops[0].claimed.cuda(), ops[0].y_ref.cuda(),
+                                  gpu_tau(tao, ops[0]), eps_rel=0.0)
+    assert p["violations"] == 0 and 0 < p["max_rel"] <= np.float32(3 * 2.0 ** -23)
+
+
+def test_config2_bert_block_scaled(tao, oracle_mod):
+    _run_ops(tao, oracle_mod, tao_inputs.config2("cpu", scale=4))
+
+
+def test_config3_qwen_layer_scaled(tao, oracle_mod):
+    _run_ops(tao, oracle_mod, tao_inputs.config3("cpu", scale=16))
+
+
+def test_config4_conv_stage_scaled(tao, oracle_mod):
+    _run_ops(tao, oracle_mod, tao_inputs.config4("cpu", scale=32))
+
+
+def test_config5_stress_scaled(tao, oracle_mod):
+    g, A, W = tao_inputs.config5_operands("cpu", size=384)
+    ref = A @ W.t()
+    t_or = oracle_mod.bound_linear(_np(A), _np(W))
+    t_gpu = tao.tao_bound_linear(A.cuda(), W.cuda())
+    assert_bound_parity(_np(t_gpu), t_or, "c5 linear")
+    claimed, cls = tao_inputs.config5_claimed(g, ref, torch.from_numpy(t_or))
+    po = oracle_mod.check_and_profile(_np(claimed), _np(ref), t_or)
+    assert po["violations"] == int((cls == 2).sum())            # the 1.01x class, known from the seed
+    pg = tao.tao_check_and_profile(claimed.cuda(), ref.cuda(), torch.from_numpy(t_or).cuda())
+    assert_profile_equal(pg, po, "c5 check")
+    # the GPU's own bound gives the same verdict counts: 1 % margins >> 1e-6 tolerance
+    pe = tao.tao_check_and_profile(claimed.cuda(), ref.cuda(), t_gpu)
+    assert pe["violations"] == po["violations"]
+
+
+@pytest.mark.parametrize("M,N,K,bias,trans_w,batch", [
+    (1, 1, 1, False, False, 1), (1, 5, 7, True, False, 1), (129, 257, 49, True, False, 1),
+    (130, 64, 601, False, True, 1), (33, 200, 48, True, True, 3), (256, 128, 96, False, False, 2),
+    (5, 3, 0, True, False, 1), (70, 130, 13, False, False, 1)])
+def test_linear_shapes(tao, oracle_mod, M, N, K, bias, trans_w, batch):
+    g = torch.Generator().manual_seed(M * 1000 + N * 10 + K)
+    A = torch.randn((batch, M, K), generator=g)
+    W = torch.randn((batch, K, N) if trans_w else (batch, N, K), generator=g)
+    b = torch.randn((N,), generator=g) if bias else None
+    if batch == 1:
+        A, W = A[0], W[0]
+    t_or = oracle_mod.bound_linear(_np(A), _np(W), None if b is None else _np(b), trans_w=trans_w)
+    t_gpu = tao.tao_bound_linear(A.cuda(), W.cuda(), None if b is None else b.cuda(), trans_w=trans_w)
+    assert_bound_parity(_np(t_gpu), t_or, "linear %s" % ((M, N, K, bias, trans_w, batch),))
+
+
+def test_linear_unaligned_views_and_modes(tao, oracle_mod):
+    g = torch.Generator().manual_seed(77)
+    Abig = torch.randn((150, 203), generator=g).cuda()
+    Wbig = torch.randn((90, 203), generator=g).cuda()
+    A = Abig[:, 1:200]            # row stride 203, base misaligned by 4 bytes
+    W = Wbig[:, 3:202]
+    t_or = oracle_mod.bound_linear(_np(A), _np(W))
+    assert_bound_parity(_np(tao.tao_bound_linear(A, W)), t_or, "strided views")
+    # probabilistic constant (Sec. 3.1, lambda = 4)
+    mo, mg = oracle_mod.Model(mode=1), tao.FpModel(mode=1)
+    assert_bound_parity(_np(tao.tao_bound_linear(A, W, model=mg)),
+                        oracle_mod.bound_linear(_np(A), _np(W), model=mo), "probabilistic")
+    # underflow term
+    mo, mg = oracle_mod.Model(flags=1), tao.FpModel(flags=tao.FLAG_UNDERFLOW_TERMS)
+    tiny = (A * 1e-30, W * 1e-12)
+    assert_bound_parity(_np(tao.tao_bound_linear(tiny[0], tiny[1], model=mg)),
+                        oracle_mod.bound_linear(_np(tiny[0]), _np(tiny[1]), model=mo), "underflow term")
+    # single-chain accumulation: still never below the oracle, looser by at most ~2 K u
+    fast = _np(tao.tao_bound_linear(A, W, model=tao.FpModel(flags=tao.FLAG_FAST_ACCUM)))
+    K = A.shape[1]
+    assert_bound_parity(fast, t_or, "fast accumulation", rel_tol=2.5 * K * 2.0 ** -24)
+
+
+@pytest.mark.parametrize("rows,cols", [(1, 1), (3, 2), (64, 128), (7, 257), (33, 512), (5, 1000),
+                                       (9, 2048), (4, 4100), (3, 8192), (2, 9001)])
+def test_softmax_shapes(tao, oracle_mod, rows, cols):
+    g = torch.Generator().manual_seed(rows * 100003 + cols)
+    x = torch.randn((rows, cols), generator=g) * 3
+    if cols > 2:
+        x[0, cols // 2:] = float("-inf")                   # partly masked row
+    if rows > 2:
+        x[1, :] = float("-inf")                            # fully masked row -> NaN
+        x[2, 0] = float("nan")                             # poisoned row -> NaN
+    y = tao_inputs.softmax_f32(x)
+    y = torch.nan_to_num(y, nan=0.0)
+    t_or = oracle_mod.bound_softmax(_np(x), _np(y))
+    t_gpu = tao.tao_bound_softmax(x.cuda(), y.cuda())
+    assert_bound_parity(_np(t_gpu), t_or, "softmax %dx%d" % (rows, cols))
+
+
+def test_softmax_padded_rows_and_probabilistic(tao, oracle_mod):
+    g = torch.Generator().manual_seed(5)
+    big = torch.randn((20, 301), generator=g)
+    x = big[:, :299]
+    y = tao_inputs.softmax_f32(x.contiguous())
+    ybig = torch.zeros_like(big); ybig[:, :299] = y
+    t_gpu = tao.tao_bound_softmax(big.cuda()[:, :299], ybig.cuda()[:, :299])
+    assert_bound_parity(_np(t_gpu), oracle_mod.bound_softmax(_np(x.contiguous()), _np(y)), "padded softmax")
+    t_p = tao.tao_bound_softmax(x.contiguous().cuda(), y.cuda(), model=tao.FpModel(mode=1, c_exp=3.0))
+    assert_bound_parity(_np(t_p), oracle_mod.bound_softmax(_np(x.contiguous()), _np(y),
+                                                          model=oracle_mod.Model(mode=1, c_exp=3.0)), "prob softmax")
+
+
+@pytest.mark.parametrize("kind", ["layernorm", "rmsnorm", "bn_affine", "sum", "mean"])
+@pytest.mark.parametrize("rows,cols", [(1, 1), (5, 3), (16, 256), (7, 768), (3, 1030), (4, 4096), (2, 8200)])
+def test_norm_shapes(tao, oracle_mod, kind, rows, cols):
+    if kind in ("layernorm",) and cols == 1:
+        pytest.skip("variance of a single element is zero: NaN row by construction, covered below")
+    g = torch.Generator().manual_seed(rows * 7919 + cols)
+    x = torch.randn((rows, cols), generator=g) * 2 + 0.5
+    gam = 1 + 0.1 * torch.randn((cols,), generator=g)
+    bet = 0.1 * torch.randn((cols,), generator=g)
+    code = {"layernorm": 0, "rmsnorm": 1, "bn_affine": 2, "sum": 3, "mean": 4}[kind]
+    eps = 1e-5
+    if kind == "layernorm":
+        y = tao_inputs.layernorm_f32(x, gam, bet, eps)
+    elif kind == "rmsnorm":
+        y = tao_inputs.rmsnorm_f32(x, gam, eps)
+    elif kind == "bn_affine":
+        y = x * gam + bet
+    elif kind == "sum":
+        y = None
+    else:
+        y = x.sum(-1) / cols
+    t_or = oracle_mod.bound_norm(code, _np(x), y=None if y is None else _np(y), g=_np(gam), b=_np(bet), eps=eps)
+    t_gpu = tao.tao_bound_norm(code, x.cuda(), None if y is None else y.cuda(), gam.cuda(), bet.cuda(), eps=eps)
+    assert_bound_parity(_np(t_gpu), t_or, "%s %dx%d" % (kind, rows, cols))
+
+
+def test_norm_failure_rows_and_no_gamma(tao, oracle_mod):
+    x = torch.full((3, 64), 3.0); x[1] = torch.arange(64.0); x[2, 5] = float("nan")
+    y = torch.zeros((3, 64))
+    t_or = oracle_mod.bound_norm(0, _np(x), y=_np(y), eps=1e-12)
+    t_gpu = tao.tao_bound_norm(0, x.cuda(), y.cuda(), eps=1e-12)
+    assert np.all(np.isnan(t_or[0])) and np.all(np.isnan(t_or[2]))
+    assert_bound_parity(_np(t_gpu), t_or, "layernorm failure rows")
+    t_or = oracle_mod.bound_norm(1, _np(x[1:2]), y=_np(y[1:2]), eps=1e-6)
+    assert_bound_parity(_np(tao.tao_bound_norm(1, x[1:2].cuda(), y[1:2].cuda(), eps=1e-6)), t_or, "rmsnorm g=1")
+
+
+@pytest.mark.parametrize("kind", ["gelu", "silu", "mul", "add", "relu"])
+@pytest.mark.parametrize("n,offset", [(1, 0), (1023, 0), (4096, 1), ((1 << 20) + 3, 0)])
+def test_act_shapes(tao, oracle_mod, kind, n, offset):
+    g = torch.Generator().manual_seed(n + offset)
+    x = (torch.randn((n + offset,), generator=g) * 4)[offset:]
+    x2 = torch.randn((n + offset,), generator=g)[offset:]
+    y = {"gelu": tao_inputs.gelu_f32, "silu": tao_inputs.silu_f32, "relu": torch.relu}.get(kind, None)
+    y = y(x) if y else (x * x2 if kind == "mul" else x + x2)
+    code = {"gelu": 0, "silu": 1, "mul": 2, "add": 3, "relu": 4}[kind]
+    xg = x.cuda() if offset == 0 else torch.cat([torch.zeros(offset), x]).cuda()[offset:]
+    yg = y.cuda() if offset == 0 else torch.cat([torch.zeros(offset), y]).cuda()[offset:]
+    t_or = oracle_mod.bound_act(code, _np(x), _np(y), x2=_np(x2))
+    t_gpu = tao.tao_bound_act(code, xg, yg, x2=x2.cuda())
+    assert_bound_parity(_np(t_gpu), t_or, "%s n=%d" % (kind, n))
+
+
+def test_gelu_wide_range(tao, oracle_mod):
+    x = torch.cat([torch.linspace(-40, 40, 200001), torch.tensor([0.0, -0.0, 1e-30, -1e-30, 38.5, -38.5])])
+    y = tao_inputs.gelu_f32(x)
+    assert_bound_parity(_np(tao.tao_bound_act(0, x.cuda(), y.cuda())), oracle_mod.bound_act(0, _np(x), _np(y)), "gelu range")
+
+
+@pytest.mark.parametrize("n,offset", [(0, 0), (1, 0), (5, 0), (1000, 1), ((1 << 20) + 3, 0), (300001, 3)])
+def test_check_sizes(tao, oracle_mod, n, offset):
+    c, r, t = tao_inputs.check_triplet("cpu", seed=1000 + n, n=n + offset)
+    c, r, t = c[offset:], r[offset:], t[offset:]
+    cg, rg, tg = [torch.cat([torch.zeros(offset), v]).cuda()[offset:] if offset else v.cuda() for v in (c, r, t)]
+    for alpha, eps in ((1.0, 1e-12), (0.5, 0.0), (3.0, 1e-3)):
+        pg = tao.tao_check_and_profile(cg, rg, tg, alpha=alpha, eps_rel=eps)
+        po = oracle_mod.check_and_profile(_np(c), _np(r), _np(t), alpha=alpha, eps_rel=eps)
+        assert_profile_equal(pg, po, "check n=%d alpha=%g" % (n, alpha))
+    if n > 1000:
+        assert 0 < po["violations"] < n
+
+
+def test_check_special_values_and_clusters(tao, oracle_mod):
+    ref = torch.tensor([1.0, 0.0, 0.0, float("nan"), 1.0, float("inf"), 3e38, 1e-40, -2.0])
+    claimed = torch.tensor([1.0, 0.0, 1.0, 1.0, float("nan"), float("inf"), -3e38, 0.0, -2.0000002])
+    tau = torch.tensor([0.0, 0.0, 2.0, 1.0, 1.0, 1.0, float("inf"), 1e-38, float("nan")])
+    for eps in (0.0, 1e-12, 1e10):
+        pg = tao.tao_check_and_profile(claimed.cuda(), ref.cuda(), tau.cuda(), eps_rel=eps)
+        po = oracle_mod.check_and_profile(_np(claimed), _np(ref), _np(tau), eps_rel=eps)
+        assert_profile_equal(pg, po, "special eps=%g" % eps)
+    # every element in one bin (worst case for the LDS histogram), and two-call reuse of buffers
+    n = 1 << 18
+    ref = torch.ones(n); claimed = torch.full((n,), 1.0 + 2.0 ** -12); tau = torch.full((n,), 1e-3)
+    for _ in range(2):
+        pg = tao.tao_check_and_profile(claimed.cuda(), ref.cuda(), tau.cuda(), eps_rel=0.0)
+        po = oracle_mod.check_and_profile(_np(claimed), _np(ref), _np(tau), eps_rel=0.0)
+        assert_profile_equal(pg, po, "single bin")
+    assert po["hist"][(127 - 12) << 3] == n
