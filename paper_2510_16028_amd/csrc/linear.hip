@@ -15,11 +15,12 @@
 // factor, by Gamma and by the guard factor and rounds up to binary32:
 // exact <= tau <= exact (1 + 16u + ...) < exact (1 + 1e-6).
 //
-// Tiling: 128x128 output tile per 256-thread workgroup, four wavefronts in a
-// 2x2 arrangement, each owning 2x2 MFMA tiles of 32x32.  K advances in slabs of
-// 48 (four chain pairs); |A| and |W| slabs are staged through LDS with the sign
-// bit cleared on the way in; the next slab is prefetched into registers while
-// the current one is consumed.
+// Tiling: 128x128 output tile per 512-thread workgroup: eight wavefronts (4 along
+// M, 2 along N), each owning two 32x32 MFMA tiles.  Two wavefronts share a SIMD,
+// so one can fold its partial sums on the vector ALU while the other feeds the
+// matrix core.  K advances in slabs of 48 (four chain pairs); |A| and |W| slabs
+// are staged through LDS with the sign bit cleared on the way in; the next slab
+// is prefetched into registers while the current one is consumed.
 #include "tao_device.hpp"
 #include "tao_host.hpp"
 
@@ -32,8 +33,8 @@ constexpr int SA = BK + 2;          // LDS row stride (floats) of a k-contiguous
                                     // of 32 consecutive rows fall in distinct bank pairs
 constexpr int SWT = BN + 16;        // LDS row stride of a [k][n] slab (trans_w): the two k-halves
                                     // of a wavefront read disjoint bank halves
-constexpr int kLinThreads = 256;
-constexpr int kVecPerThread = (BM * BK / 4) / kLinThreads;   // 6 float4 per operand per slab
+constexpr int kLinThreads = 512;    // 8 wavefronts: 4 along M x 2 along N, each 32 x 64 outputs
+constexpr int kVecPerThread = (BM * BK / 4) / kLinThreads;   // 3 float4 per operand per slab
 
 struct LinArgs {
     const float* A; const float* W; const float* bias; float* tau;
@@ -75,20 +76,25 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
     const float* __restrict__ A = p.A + (long)blockIdx.z * p.strideA;
     const float* __restrict__ W = p.W + (long)blockIdx.z * p.strideW;
     float* __restrict__ T = p.tau + (long)blockIdx.z * p.strideT;
+    // interior tiles with aligned operands take unguarded 16-byte loads
+    const bool full_mn = (m0 + BM <= p.M) && (n0 + BN <= p.N) && p.vecA && p.vecW;
 
     float4 pa[kVecPerThread], pw[kVecPerThread];
     auto prefetch = [&](long k0) {
+        const bool fast_slab = full_mn && (k0 + BK <= p.K);
 #pragma unroll
         for (int i = 0; i < kVecPerThread; ++i) {
             const int f = tid + kLinThreads * i;
             const int row = f / (BK / 4), k = (f % (BK / 4)) * 4;
-            pa[i] = gload(A, m0 + row, p.M, p.lda, k0 + k, p.K, p.vecA);
-            if (!TRANS_W) {
-                pw[i] = gload(W, n0 + row, p.N, p.ldw, k0 + k, p.K, p.vecW);
+            const int kr = f / (BN / 4), n = (f % (BN / 4)) * 4;     // [k][n] slab of a transposed W
+            if (fast_slab) {
+                pa[i] = *reinterpret_cast<const float4*>(A + (m0 + row) * p.lda + k0 + k);
+                pw[i] = TRANS_W ? *reinterpret_cast<const float4*>(W + (k0 + kr) * p.ldw + n0 + n)
+                                : *reinterpret_cast<const float4*>(W + (n0 + row) * p.ldw + k0 + k);
             } else {
-                const int kr = f / (BN / 4), n = (f % (BN / 4)) * 4;
-                // rows of W are k here, columns are n
-                pw[i] = gload(W, k0 + kr, p.K, p.ldw, n0 + n, p.N, p.vecW);
+                pa[i] = gload(A, m0 + row, p.M, p.lda, k0 + k, p.K, p.vecA);
+                pw[i] = TRANS_W ? gload(W, k0 + kr, p.K, p.ldw, n0 + n, p.N, p.vecW)
+                                : gload(W, n0 + row, p.N, p.ldw, k0 + k, p.K, p.vecW);
             }
         }
     };
@@ -111,15 +117,13 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
         }
     };
 
-    double S[2][2][16];
-    floatx16 chain[2][2];
+    double S[2][16];
+    floatx16 chain[2];
 #pragma unroll
-    for (int ti = 0; ti < 2; ++ti)
+    for (int tj = 0; tj < 2; ++tj) {
 #pragma unroll
-        for (int tj = 0; tj < 2; ++tj) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) { S[ti][tj][v] = 0.0; chain[ti][tj][v] = 0.f; }
-        }
+        for (int v = 0; v < 16; ++v) { S[tj][v] = 0.0; chain[tj][v] = 0.f; }
+    }
 
     const long nslab = (p.K + BK - 1) / BK;
     if (nslab > 0) { prefetch(0); commit(); }
@@ -130,12 +134,11 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
 #pragma unroll 1
         for (int pr = 0; pr < BK / 12; ++pr) {
             const int kb = pr * 12 + 6 * h;           // this half-wavefront's six k indices
-            float a[2][6], b[2][6];
-#pragma unroll
-            for (int ti = 0; ti < 2; ++ti) {
-                const float2* src = reinterpret_cast<const float2*>(&As[(wm * 64 + ti * 32 + r32) * SA + kb]);
+            float a[6], b[2][6];
+            {
+                const float2* src = reinterpret_cast<const float2*>(&As[(wm * 32 + r32) * SA + kb]);
                 const float2 v0 = src[0], v1 = src[1], v2 = src[2];
-                a[ti][0] = v0.x; a[ti][1] = v0.y; a[ti][2] = v1.x; a[ti][3] = v1.y; a[ti][4] = v2.x; a[ti][5] = v2.y;
+                a[0] = v0.x; a[1] = v0.y; a[2] = v1.x; a[3] = v1.y; a[4] = v2.x; a[5] = v2.y;
             }
 #pragma unroll
             for (int tj = 0; tj < 2; ++tj) {
@@ -148,30 +151,41 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
                     for (int j = 0; j < 6; ++j) b[tj][j] = Ws[(kb + j) * SWT + wn * 64 + tj * 32 + r32];
                 }
             }
-#pragma unroll
-            for (int ti = 0; ti < 2; ++ti)
+            if (FAST) {
 #pragma unroll
                 for (int tj = 0; tj < 2; ++tj) {
-                    if (FAST) {
-                        floatx16 c = chain[ti][tj];
+                    floatx16 c = chain[tj];
 #pragma unroll
-                        for (int j = 0; j < 6; ++j)
-                            c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ti][j], b[tj][j], c, 0, 0, 0);
-                        chain[ti][tj] = c;
-                    } else {
-                        floatx16 z;
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) z[v] = 0.f;
-                        floatx16 c0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ti][0], b[tj][0], z, 0, 0, 0);
-                        c0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ti][1], b[tj][1], c0, 0, 0, 0);
-                        c0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ti][2], b[tj][2], c0, 0, 0, 0);
-                        floatx16 c1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ti][3], b[tj][3], z, 0, 0, 0);
-                        c1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ti][4], b[tj][4], c1, 0, 0, 0);
-                        c1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a[ti][5], b[tj][5], c1, 0, 0, 0);
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) S[ti][tj][v] += (double)(c0[v] + c1[v]);
-                    }
+                    for (int j = 0; j < 6; ++j)
+                        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j], b[tj][j], c, 0, 0, 0);
+                    chain[tj] = c;
                 }
+            } else {
+                floatx16 z;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) z[v] = 0.f;
+                floatx16 c0[2], c1[2];
+#pragma unroll
+                for (int tj = 0; tj < 2; ++tj) {
+                    c0[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[tj][0], z, 0, 0, 0);
+                    c1[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[tj][3], z, 0, 0, 0);
+                }
+#pragma unroll
+                for (int tj = 0; tj < 2; ++tj) {
+                    c0[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[tj][1], c0[tj], 0, 0, 0);
+                    c1[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[4], b[tj][4], c1[tj], 0, 0, 0);
+                }
+#pragma unroll
+                for (int tj = 0; tj < 2; ++tj) {
+                    c0[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[2], b[tj][2], c0[tj], 0, 0, 0);
+                    c1[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[5], b[tj][5], c1[tj], 0, 0, 0);
+                }
+#pragma unroll
+                for (int tj = 0; tj < 2; ++tj) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) S[tj][v] += (double)(c0[tj][v] + c1[tj][v]);
+                }
+            }
         }
         __syncthreads();
         if (more) { commit(); __syncthreads(); }
@@ -179,21 +193,19 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
 
     // epilogue: D[i][j] of a 32x32 tile sits in lane (j + 32*((i/4)%2)), register 4*(i/8) + i%4
 #pragma unroll
-    for (int ti = 0; ti < 2; ++ti)
+    for (int tj = 0; tj < 2; ++tj) {
+        const long col = n0 + wn * 64 + tj * 32 + r32;
+        const double ab = (p.bias && col < p.N) ? fabs((double)p.bias[col]) : 0.0;
 #pragma unroll
-        for (int tj = 0; tj < 2; ++tj) {
-            const long col = n0 + wn * 64 + tj * 32 + r32;
-            const double ab = (p.bias && col < p.N) ? fabs((double)p.bias[col]) : 0.0;
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const long row = m0 + wm * 64 + ti * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-                if (row < p.M && col < p.N) {
-                    const double s = FAST ? (double)chain[ti][tj][v] : S[ti][tj][v];
-                    const double t = p.c * (s * p.infl + ab) * kGuard + p.uflow;
-                    T[row * p.ldt + col] = up32(t);
-                }
+        for (int v = 0; v < 16; ++v) {
+            const long row = m0 + wm * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+            if (row < p.M && col < p.N) {
+                const double s = FAST ? (double)chain[tj][v] : S[tj][v];
+                const double t = p.c * (s * p.infl + ab) * kGuard + p.uflow;
+                T[row * p.ldt + col] = up32(t);
             }
         }
+    }
 }
 
 // ---- matrix-core self test ----------------------------------------------------------------
