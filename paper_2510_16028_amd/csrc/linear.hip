@@ -63,10 +63,17 @@ __device__ __forceinline__ float4 gload(const float* __restrict__ base, long r, 
     return v;
 }
 
+// One LDS stage holds a 128 x 48 slab of |A| and one of |W|.
+constexpr int kStageFloats = BM * SA + (BN * SA > BK * SWT ? BN * SA : BK * SWT);
+constexpr int kStages = 2;
+constexpr size_t kLinLdsBytes = (size_t)kStages * kStageFloats * sizeof(float);
+
+// Scheduling hint: the next `n` instructions of class `mask` (8 = MFMA, 2 = VALU) form a group.
+#define TAO_SCHED_GROUP(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+
 template <bool TRANS_W, bool FAST>
 __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
-    __shared__ __attribute__((aligned(16))) float As[BM * SA];
-    __shared__ __attribute__((aligned(16))) float Ws[TRANS_W ? BK * SWT : BN * SA];
+    extern __shared__ __attribute__((aligned(16))) float lds[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -98,7 +105,9 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
             }
         }
     };
-    auto commit = [&]() {
+    auto commit = [&](int stage) {
+        float* As = lds + stage * kStageFloats;
+        float* Ws = As + BM * SA;
 #pragma unroll
         for (int i = 0; i < kVecPerThread; ++i) {
             const int f = tid + kLinThreads * i;
@@ -117,20 +126,27 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
         }
     };
 
+    // S: binary64 running sums; c0/c1: the two 6-step chains of each tile.  The fold of tile 1
+    // is deferred by one step so that it overlaps the MFMAs of tile 0 of the next chain pair.
     double S[2][16];
-    floatx16 chain[2];
+    floatx16 c0[2], c1[2];
 #pragma unroll
     for (int tj = 0; tj < 2; ++tj) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { S[tj][v] = 0.0; chain[tj][v] = 0.f; }
+        for (int v = 0; v < 16; ++v) { S[tj][v] = 0.0; c0[tj][v] = 0.f; c1[tj][v] = 0.f; }
     }
+    floatx16 zero;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) zero[v] = 0.f;
 
     const long nslab = (p.K + BK - 1) / BK;
-    if (nslab > 0) { prefetch(0); commit(); }
+    if (nslab > 0) { prefetch(0); commit(0); }
     __syncthreads();
     for (long s = 0; s < nslab; ++s) {
         const bool more = s + 1 < nslab;
         if (more) prefetch((s + 1) * BK);
+        const float* As = lds + (int)(s & 1) * kStageFloats;
+        const float* Ws = As + BM * SA;
 #pragma unroll 1
         for (int pr = 0; pr < BK / 12; ++pr) {
             const int kb = pr * 12 + 6 * h;           // this half-wavefront's six k indices
@@ -154,41 +170,42 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
             if (FAST) {
 #pragma unroll
                 for (int tj = 0; tj < 2; ++tj) {
-                    floatx16 c = chain[tj];
 #pragma unroll
                     for (int j = 0; j < 6; ++j)
-                        c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j], b[tj][j], c, 0, 0, 0);
-                    chain[tj] = c;
+                        c0[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j], b[tj][j], c0[tj], 0, 0, 0);
                 }
             } else {
-                floatx16 z;
+                // step A: fold tile 1 (previous chain pair) under the MFMAs of tile 0
 #pragma unroll
-                for (int v = 0; v < 16; ++v) z[v] = 0.f;
-                floatx16 c0[2], c1[2];
+                for (int v = 0; v < 16; ++v) S[1][v] += (double)(c0[1][v] + c1[1][v]);
+                c0[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0][0], zero, 0, 0, 0);
+                c1[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[0][3], zero, 0, 0, 0);
+                c0[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[0][1], c0[0], 0, 0, 0);
+                c1[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[4], b[0][4], c1[0], 0, 0, 0);
+                c0[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[2], b[0][2], c0[0], 0, 0, 0);
+                c1[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[5], b[0][5], c1[0], 0, 0, 0);
 #pragma unroll
-                for (int tj = 0; tj < 2; ++tj) {
-                    c0[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[tj][0], z, 0, 0, 0);
-                    c1[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[tj][3], z, 0, 0, 0);
-                }
+                for (int g = 0; g < 6; ++g) { TAO_SCHED_GROUP(0x008, 1); TAO_SCHED_GROUP(0x002, 8); }
+                // step B: fold tile 0 under the MFMAs of tile 1
 #pragma unroll
-                for (int tj = 0; tj < 2; ++tj) {
-                    c0[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[tj][1], c0[tj], 0, 0, 0);
-                    c1[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[4], b[tj][4], c1[tj], 0, 0, 0);
-                }
+                for (int v = 0; v < 16; ++v) S[0][v] += (double)(c0[0][v] + c1[0][v]);
+                c0[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[1][0], zero, 0, 0, 0);
+                c1[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[1][3], zero, 0, 0, 0);
+                c0[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[1][1], c0[1], 0, 0, 0);
+                c1[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[4], b[1][4], c1[1], 0, 0, 0);
+                c0[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[2], b[1][2], c0[1], 0, 0, 0);
+                c1[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[5], b[1][5], c1[1], 0, 0, 0);
 #pragma unroll
-                for (int tj = 0; tj < 2; ++tj) {
-                    c0[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[2], b[tj][2], c0[tj], 0, 0, 0);
-                    c1[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[5], b[tj][5], c1[tj], 0, 0, 0);
-                }
-#pragma unroll
-                for (int tj = 0; tj < 2; ++tj) {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) S[tj][v] += (double)(c0[tj][v] + c1[tj][v]);
-                }
+                for (int g = 0; g < 6; ++g) { TAO_SCHED_GROUP(0x008, 1); TAO_SCHED_GROUP(0x002, 8); }
             }
         }
+        // the other stage was last read before the previous barrier: safe to refill now
+        if (more) commit((int)((s + 1) & 1));
         __syncthreads();
-        if (more) { commit(); __syncthreads(); }
+    }
+    if (!FAST) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) S[1][v] += (double)(c0[1][v] + c1[1][v]);
     }
 
     // epilogue: D[i][j] of a 32x32 tile sits in lane (j + 32*((i/4)%2)), register 4*(i/8) + i%4
@@ -200,12 +217,25 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
         for (int v = 0; v < 16; ++v) {
             const long row = m0 + wm * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
             if (row < p.M && col < p.N) {
-                const double s = FAST ? (double)chain[tj][v] : S[tj][v];
+                const double s = FAST ? (double)c0[tj][v] : S[tj][v];
                 const double t = p.c * (s * p.infl + ab) * kGuard + p.uflow;
                 T[row * p.ldt + col] = up32(t);
             }
         }
     }
+}
+
+template <bool TRANS_W, bool FAST>
+static hipError_t launch_absgemm(dim3 grid, hipStream_t st, const LinArgs& p) {
+    static bool configured = false;      // raise the dynamic LDS limit once per instantiation
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_bound<TRANS_W, FAST>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLinLdsBytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL((absgemm_bound<TRANS_W, FAST>), grid, dim3(kLinThreads), kLinLdsBytes, st, p);
+    return hipSuccess;
 }
 
 // ---- matrix-core self test ----------------------------------------------------------------
@@ -264,13 +294,10 @@ int tao_bound_linear(const float* A, const float* W, const float* bias, float* t
     dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM), (unsigned)batch);
     if (grid.y > 65535u) return TAO_ERR_SHAPE;
     hipStream_t st = (hipStream_t)stream;
-    if (trans_w) {
-        if (fast) hipLaunchKernelGGL((absgemm_bound<true, true>), grid, dim3(kLinThreads), 0, st, p);
-        else      hipLaunchKernelGGL((absgemm_bound<true, false>), grid, dim3(kLinThreads), 0, st, p);
-    } else {
-        if (fast) hipLaunchKernelGGL((absgemm_bound<false, true>), grid, dim3(kLinThreads), 0, st, p);
-        else      hipLaunchKernelGGL((absgemm_bound<false, false>), grid, dim3(kLinThreads), 0, st, p);
-    }
+    hipError_t e;
+    if (trans_w) e = fast ? launch_absgemm<true, true>(grid, st, p) : launch_absgemm<true, false>(grid, st, p);
+    else         e = fast ? launch_absgemm<false, true>(grid, st, p) : launch_absgemm<false, false>(grid, st, p);
+    if (e != hipSuccess) { g_last_hip_error = (int)e; return TAO_ERR_LAUNCH; }
     return launch_status();
 }
 
