@@ -1,0 +1,252 @@
+#!/usr/bin/env python3
+"""Benchmark of the tolerance engine's hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input: for
+every traced operator of a Qwen3-8B-shaped decoder layer (hidden 4096,
+intermediate 12288, 32 q / 8 kv heads, head_dim 128, seq 2048) compute the
+bound tensor tau (linear, softmax, RMSNorm, SiLU, Mul, Add kinds) and run the
+check + relative-error profile of the claimed output against the re-executed
+one.  All inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` = bytes of claimed operator output verified per
+second (4 bytes per element that went through bound + check).  `roofline` is for
+the dominant kernel (the MFMA |A||W| bound), from HIP events recorded around its
+launches inside the timed region.  `cpu_baseline` times the CPU oracle on a row
+sample of the same workload.  Extra key `kernels` lists the other kernels and
+the 8192^3 / 67M-element stress shapes.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+_NORM = {"layernorm": 0, "rmsnorm": 1, "bn_affine": 2, "sum": 3, "mean": 4}
+_ACT = {"gelu": 0, "silu": 1, "mul": 2, "add": 3, "relu": 4}
+# algorithmic HBM bytes per output element of the streaming bound kernels (inputs read once,
+# tau written once)
+_STREAM_BYTES = {"softmax": 12, "layernorm": 12, "rmsnorm": 12, "bn_affine": 12, "gelu": 12,
+                 "silu": 8, "mul": 8, "add": 8}
+
+
+class PlannedOp:
+    """One operator with every buffer preallocated; run() only enqueues kernels."""
+
+    def __init__(self, tao, torch, op):
+        self.tao, self.op, self.kind, self.name = tao, op, op.kind, op.name
+        self.claimed = op.claimed.contiguous()
+        self.y_ref = op.y_ref.contiguous()
+        self.tau = torch.empty_like(self.y_ref)
+        self.prof = tao.new_profile_buffer(self.y_ref.device)
+        self.n = self.y_ref.numel()
+        a = op.args
+        if self.kind == "linear":
+            A, W = a["A"], a["W"]
+            K = A.shape[-1]
+            self.flops = 2.0 * self.n * K
+        else:
+            self.flops = 0.0
+        self.bound_events, self.check_events = [], []
+
+    def bound(self):
+        tao, a, op = self.tao, self.op.args, self.op
+        if self.kind == "linear":
+            tao.tao_bound_linear(a["A"], a["W"], a.get("bias"), trans_w=bool(op.attrs.get("trans_w", 0)), out=self.tau)
+        elif self.kind == "softmax":
+            tao.tao_bound_softmax(a["x"], self.y_ref, out=self.tau)
+        elif self.kind in ("layernorm", "rmsnorm"):
+            tao.tao_bound_norm(_NORM[self.kind], a["x"], self.y_ref, a.get("gamma"), a.get("beta"),
+                               eps=op.attrs["eps"], out=self.tau)
+        elif self.kind == "bn_affine":
+            tao.tao_bound_norm(2, a["x"], self.y_ref, a["scale"], a["shift"], out=self.tau)
+        else:
+            tao.tao_bound_act(_ACT[self.kind], a.get("x"), self.y_ref, x2=a.get("x2"), out=self.tau)
+
+    def check(self):
+        self.tao.tao_check_and_profile(self.claimed, self.y_ref, self.tau, out=self.prof, readback=False)
+
+    def run(self, torch, record):
+        if record:
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            e[0].record(); self.bound(); e[1].record(); self.check(); e[2].record()
+            self.bound_events.append((e[0], e[1])); self.check_events.append((e[1], e[2]))
+        else:
+            self.bound(); self.check()
+
+
+def _ms(pairs):
+    return [a.elapsed_time(b) for a, b in pairs]
+
+
+def _event_time(torch, fn, reps, warm=2):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in ev:
+        a.record(); fn(); b.record()
+    torch.cuda.synchronize()
+    return sum(_ms(ev)) / reps
+
+
+def cpu_baseline(ops, rows_per_op):
+    """The oracle, as it stands, on the first `rows_per_op` output rows of every operator."""
+    import numpy as np
+    import oracle
+    import tao_inputs
+    from opmap import oracle_tau
+    sample = []
+    for op in ops:
+        y = op.y_ref
+        lead = y.shape[0] if y.dim() > 1 else 1
+        if op.kind == "linear":
+            A = op.args["A"]
+            if A.dim() == 3:          # batched: take rows of the first batch entry
+                args = {"A": A[0, :rows_per_op], "W": op.args["W"][0], "bias": None}
+                sub = tao_inputs.Op(op.name, op.kind, args, y[0, :rows_per_op], op.claimed[0, :rows_per_op], op.attrs)
+            else:
+                args = {"A": A[:rows_per_op], "W": op.args["W"], "bias": op.args.get("bias")}
+                sub = tao_inputs.Op(op.name, op.kind, args, y[:rows_per_op], op.claimed[:rows_per_op], op.attrs)
+        else:
+            def cut(t):
+                if t is None or t.dim() == 1 and t.shape[0] != lead:
+                    return t
+                return t.reshape(-1, t.shape[-1])[:rows_per_op] if t.dim() > 1 else t
+            args = {k: (cut(v) if k in ("x", "x2") else v) for k, v in op.args.items()}
+            sub = tao_inputs.Op(op.name, op.kind, args, cut(y), cut(op.claimed), op.attrs)
+        # move to host before timing: the baseline is CPU work only
+        sub.args = {k: (None if v is None else v.detach().cpu().contiguous()) for k, v in sub.args.items()}
+        sub.y_ref = sub.y_ref.detach().cpu().contiguous()
+        sub.claimed = sub.claimed.detach().cpu().contiguous()
+        sample.append(sub)
+    oracle.lib()
+    t0 = time.perf_counter()
+    elems = 0
+    for sub in sample:
+        tau = oracle_tau(oracle, sub)
+        oracle.check_and_profile(sub.claimed.numpy(), sub.y_ref.numpy(), tau)
+        elems += sub.y_ref.numel()
+    dt = time.perf_counter() - t0
+    return {"value": elems * 4 / dt / 1e9, "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": "first %d output rows of each of the %d operators (%d elements, %.1f s)" %
+                      (rows_per_op, len(sample), elems, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--scale", type=int, default=1, help="shrink the workload (1 = full size)")
+    ap.add_argument("--cpu-rows", type=int, default=2048, help="output rows per operator for the CPU oracle baseline")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-stress", action="store_true", help="skip the 8192^3 / 67M-element side measurements")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); got --gpus %d" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2510_16028_amd as tao
+    import tao_inputs
+    tao.lib()
+    assert torch.cuda.is_available(), "bench.py needs a GPU (no CPU fallback)"
+    dev = "cuda"
+    torch.cuda.set_device(0)
+
+    ops = tao_inputs.config3(dev, scale=args.scale)
+    plan = [PlannedOp(tao, torch, op) for op in ops]
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        for p in plan:
+            p.run(torch, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        for p in plan:
+            p.run(torch, True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    elems = sum(p.n for p in plan)
+    violations = sum(tao.read_profile(p.prof)["violations"] for p in plan)
+    value = elems * 4 / (ms_per_step * 1e-3) / 1e9
+
+    # dominant kernel: the MFMA bound, all its launches in the timed region
+    lin = [p for p in plan if p.kind == "linear"]
+    lin_ms = sum(sum(_ms(p.bound_events)) for p in lin)
+    lin_launches = sum(len(p.bound_events) for p in lin)
+    lin_flops = sum(p.flops * len(p.bound_events) for p in lin)
+    achieved = lin_flops / (lin_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "absgemm_bound", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                "launches": lin_launches, "avg_launch_ms": lin_ms / lin_launches,
+                "flop_per_launch": lin_flops / lin_launches,
+                "share_of_step": lin_ms / args.steps / ms_per_step}
+
+    kernels = {}
+    chk_ms = sum(sum(_ms(p.check_events)) for p in plan)
+    chk_bytes = sum(12.0 * p.n * len(p.check_events) for p in plan)
+    kernels["check_and_profile"] = {"GB/s": chk_bytes / (chk_ms * 1e-3) / 1e9,
+                                    "frac_hbm": chk_bytes / (chk_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                    "avg_launch_ms": chk_ms / sum(len(p.check_events) for p in plan)}
+    for kind in sorted({p.kind for p in plan if p.kind != "linear"}):
+        sel = [p for p in plan if p.kind == kind]
+        ms = sum(sum(_ms(p.bound_events)) for p in sel)
+        by = sum(_STREAM_BYTES[kind] * p.n * len(p.bound_events) for p in sel)
+        kernels["bound_" + kind] = {"GB/s": by / (ms * 1e-3) / 1e9, "frac_hbm": by / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                    "avg_launch_ms": ms / sum(len(p.bound_events) for p in sel)}
+    for p in lin:
+        ms = sum(_ms(p.bound_events)) / len(p.bound_events)
+        kernels["linear_" + p.name] = {"shape": list(p.op.args["A"].shape) + [p.op.y_ref.shape[-1]],
+                                       "TFLOP/s": p.flops / (ms * 1e-3) / 1e12, "ms": ms}
+
+    if not args.no_stress:
+        # side measurements on the stress shapes (not part of `value`)
+        g, A, W = tao_inputs.config5_operands(dev, size=8192)
+        out = torch.empty((8192, 8192), device=dev)
+        for flags, nm in ((0, "linear_8192^3"), (tao.FLAG_FAST_ACCUM, "linear_8192^3_fast_accum")):
+            md = tao.FpModel(flags=flags)
+            ms = _event_time(torch, lambda: tao.tao_bound_linear(A, W, model=md, out=out), 5, 1)
+            tf = 2.0 * 8192 ** 3 / (ms * 1e-3) / 1e12
+            kernels[nm] = {"ms": ms, "TFLOP/s": tf, "frac_mfma": tf / PEAK_FP32_MFMA_TFLOPS}
+        ref = A @ W.t()
+        claimed, cls = tao_inputs.config5_claimed(g, ref, out)
+        buf = tao.new_profile_buffer(ref.device)
+        ms = _event_time(torch, lambda: tao.tao_check_and_profile(claimed, ref, out, out=buf, readback=False), 20, 2)
+        prof = tao.read_profile(buf)
+        kernels["check_67M"] = {"ms": ms, "GB/s": 12.0 * ref.numel() / (ms * 1e-3) / 1e9,
+                                "frac_hbm": 12.0 * ref.numel() / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                "violations": prof["violations"], "expected_violations": int((cls == 2).sum()),
+                                "p50": prof["p50"], "p99": prof["p99"], "p999": prof["p999"], "max_rel": prof["max_rel"]}
+        del A, W, out, ref, claimed, cls
+
+    result = {
+        "metric": "traced-operator GB/s verified (bound+check) & % FP32 MFMA/HBM peak, 1 GPU",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 (MFMA) + f64 (accumulation, scalars, check)", "data": "synthetic",
+        "config": {"workload": "config 3: Qwen3-8B-shaped decoder layer ops, FP32, seq %d: %d traced operators, "
+                               "%d output elements verified per step" % (ops[0].y_ref.shape[0], len(plan), elems),
+                   "scale": args.scale},
+        "violations": violations,
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(ops, args.cpu_rows)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

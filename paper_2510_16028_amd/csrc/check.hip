@@ -7,21 +7,26 @@
 // lane-replicated 2048-bin histogram in LDS and writes its partial histogram
 // and counters to the workspace -- no global atomics, so the result does not
 // depend on scheduling.
-// Pass 2 (profile_reduce): one workgroup per 16 bins sums the partials into the
-// 64-bit histogram; the last workgroup to finish (device-scope counter in the
-// result struct, zeroed by pass 1) scans the 2048 bins for the nearest-rank
-// percentiles and writes the scalar fields.
+// Pass 2 (profile_reduce): one workgroup per 64 bins sums the partials (256-byte
+// contiguous reads) into the 64-bit histogram; the last workgroup to finish
+// (device-scope counter in the result struct, zeroed by pass 1) scans the 2048
+// bins for the nearest-rank percentiles and writes the scalar fields.
 #include "tao_device.hpp"
 #include "tao_host.hpp"
 
 namespace tao {
 
 constexpr int kBins = TAO_NBINS;
-constexpr int kCheckThreads = 256;
+constexpr int kCheckThreads = 1024;          // one workgroup per CU: one partial histogram per CU
 constexpr int kReplicas = 4;                 // LDS copies of each bin, selected by lane & 3
-constexpr int kMaxCheckBlocks = 1024;
-constexpr int kBinsPerReduceBlock = 16;
+constexpr int kMaxCheckBlocks = 256;
+constexpr int kBinsPerReduceBlock = 64;
 constexpr int kReduceBlocks = kBins / kBinsPerReduceBlock;
+constexpr int kReduceThreads = 1024;
+constexpr int kReduceSlices = kReduceThreads / kBinsPerReduceBlock;      // 16
+constexpr int kPartialsPerThread = kMaxCheckBlocks / kReduceSlices;      // 16 independent loads
+constexpr int kBinsPerThread = kBins / kReduceThreads;                    // 2, in the final scan
+constexpr int kReduceWaves = kReduceThreads / kWave;
 
 struct BlockStats {          // one per pass-1 workgroup, in the workspace after the histograms
     unsigned long long violations;
@@ -120,24 +125,34 @@ __device__ __forceinline__ unsigned long long rank_of(unsigned long long n, unsi
     return r < 1 ? 1 : r;
 }
 
-__global__ __launch_bounds__(256) void profile_reduce(
+__global__ __launch_bounds__(kReduceThreads) void profile_reduce(
     const unsigned int* __restrict__ ws_hist, const BlockStats* __restrict__ ws_stats, int nblocks,
     unsigned long long n, tao_profile* out) {
-    __shared__ unsigned long long part[256];
-    __shared__ unsigned long long scan[kBins / 8];
+    __shared__ unsigned long long part[kReduceThreads];
+    __shared__ unsigned long long wtot[kReduceWaves], wv[kReduceWaves], wq[kReduceWaves];
+    __shared__ unsigned int wm[kReduceWaves];
     __shared__ int is_last;
     const int tid = threadIdx.x;
-    // 16 bins x 16 slices of the partial histograms
+    const int lane = tid & (kWave - 1), wave = tid / kWave;
+    // 64 bins x 16 slices of the partial histograms; all loads of a thread are independent
     const int b = tid & (kBinsPerReduceBlock - 1);
     const int slice = tid / kBinsPerReduceBlock;
     const int bin = blockIdx.x * kBinsPerReduceBlock + b;
+    unsigned int vals[kPartialsPerThread];
+#pragma unroll
+    for (int j = 0; j < kPartialsPerThread; ++j) {
+        const int k = slice + kReduceSlices * j;
+        vals[j] = (k < nblocks) ? ws_hist[(size_t)k * kBins + bin] : 0u;
+    }
     unsigned long long s = 0;
-    for (int k = slice; k < nblocks; k += 256 / kBinsPerReduceBlock) s += ws_hist[(size_t)k * kBins + bin];
+#pragma unroll
+    for (int j = 0; j < kPartialsPerThread; ++j) s += vals[j];
     part[tid] = s;
     __syncthreads();
     if (tid < kBinsPerReduceBlock) {
         unsigned long long t = 0;
-        for (int k = 0; k < 256 / kBinsPerReduceBlock; ++k) t += part[k * kBinsPerReduceBlock + tid];
+#pragma unroll
+        for (int k = 0; k < kReduceSlices; ++k) t += part[k * kBinsPerReduceBlock + tid];
         out->hist[blockIdx.x * kBinsPerReduceBlock + tid] = t;
     }
     __threadfence();
@@ -147,47 +162,53 @@ __global__ __launch_bounds__(256) void profile_reduce(
     if (!is_last) return;
     __threadfence();
 
-    // Finalise: each thread owns 8 consecutive bins.
-    unsigned long long h[8], local = 0;
+    // Finalise: each thread owns 2 consecutive bins; exclusive prefix over threads by a
+    // shuffle scan inside each wavefront plus the wavefront totals.
+    unsigned long long h[kBinsPerThread], local = 0;
     const volatile uint64_t* gh = out->hist;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) { h[k] = gh[tid * 8 + k]; local += h[k]; }
-    scan[tid] = local;
-    __syncthreads();
-    if (tid == 0) {
-        unsigned long long run = 0;
-        for (int k = 0; k < kBins / 8; ++k) { unsigned long long t = scan[k]; scan[k] = run; run += t; }
+    for (int k = 0; k < kBinsPerThread; ++k) { h[k] = gh[tid * kBinsPerThread + k]; local += h[k]; }
+    unsigned long long incl = local;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const unsigned long long up = __shfl_up(incl, o, kWave);
+        if (lane >= o) incl += up;
     }
+    if (lane == kWave - 1) wtot[wave] = incl;
+    // counters of pass 1 (at most one workgroup's record per thread)
+    unsigned long long v = 0, q = 0; unsigned int m = 0;
+    for (int k = tid; k < nblocks; k += kReduceThreads) {
+        v += ws_stats[k].violations; q += ws_stats[k].nans; m = max(m, ws_stats[k].max_bits);
+    }
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+        v += __shfl_xor(v, o, kWave); q += __shfl_xor(q, o, kWave);
+        m = max(m, (unsigned int)__shfl_xor(m, o, kWave));
+    }
+    if (lane == 0) { wv[wave] = v; wq[wave] = q; wm[wave] = m; }
     __syncthreads();
-    const unsigned long long before = scan[tid];          // exclusive prefix of this thread's bins
+    unsigned long long before = incl - local;                 // exclusive prefix inside the wavefront
+    for (int w = 0; w < wave; ++w) before += wtot[w];
     const unsigned long long ranks[3] = {rank_of(n, 1, 2), rank_of(n, 99, 100), rank_of(n, 999, 1000)};
     unsigned int* bins_out[3] = {&out->p50_bin, &out->p99_bin, &out->p999_bin};
     float* vals_out[3] = {&out->p50, &out->p99, &out->p999};
     if (n > 0) {
         unsigned long long cum = before;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
+        for (int k = 0; k < kBinsPerThread; ++k) {
             const unsigned long long lo = cum;
             cum += h[k];
+#pragma unroll
             for (int p = 0; p < 3; ++p)
                 if (lo < ranks[p] && ranks[p] <= cum) {
-                    *bins_out[p] = tid * 8 + k;
-                    *vals_out[p] = bin_upper_edge(tid * 8 + k);
+                    *bins_out[p] = tid * kBinsPerThread + k;
+                    *vals_out[p] = bin_upper_edge(tid * kBinsPerThread + k);
                 }
         }
     }
-    // counters
-    unsigned long long v = 0, q = 0; unsigned int m = 0;
-    for (int k = tid; k < nblocks; k += 256) {
-        v += ws_stats[k].violations; q += ws_stats[k].nans; m = max(m, ws_stats[k].max_bits);
-    }
-    __shared__ unsigned long long rv[256], rq[256];
-    __shared__ unsigned int rm[256];
-    rv[tid] = v; rq[tid] = q; rm[tid] = m;
-    __syncthreads();
     if (tid == 0) {
         v = 0; q = 0; m = 0;
-        for (int k = 0; k < 256; ++k) { v += rv[k]; q += rq[k]; m = max(m, rm[k]); }
+        for (int w = 0; w < kReduceWaves; ++w) { v += wv[w]; q += wq[w]; m = max(m, wm[w]); }
         out->n = n;
         out->violations = v;
         out->nan_count = q;
@@ -218,7 +239,7 @@ int tao_check_and_profile(const float* claimed, const float* ref, const float* t
     if (n > 0 && (!claimed || !ref || !tau)) return TAO_ERR_NULL;
     if (!aligned(claimed, 4) || !aligned(ref, 4) || !aligned(tau, 4) || !aligned(out, 8)) return TAO_ERR_ALIGN;
     if (!aligned(ws, 256) || ws_bytes < tao_check_workspace_bytes(n)) return TAO_ERR_WORKSPACE;
-    if (n >= (1L << 53)) return TAO_ERR_SHAPE;
+    if (n >= (1L << 36)) return TAO_ERR_SHAPE;   // 32-bit per-workgroup counters
     hipStream_t st = (hipStream_t)stream;
     const int vec_ok = aligned(claimed, 16) && aligned(ref, 16) && aligned(tau, 16);
     // 16 elements (four 16-byte vectors) per thread before another workgroup is worth it
@@ -228,7 +249,7 @@ int tao_check_and_profile(const float* claimed, const float* ref, const float* t
     BlockStats* ws_stats = (BlockStats*)((char*)ws + (size_t)kMaxCheckBlocks * kBins * sizeof(unsigned int));
     hipLaunchKernelGGL(check_pass, dim3(nblocks), dim3(kCheckThreads), 0, st, claimed, ref, tau, n,
                        vec_ok, alpha, eps_rel, ws_hist, ws_stats, out);
-    hipLaunchKernelGGL(profile_reduce, dim3(kReduceBlocks), dim3(256), 0, st, ws_hist, ws_stats,
+    hipLaunchKernelGGL(profile_reduce, dim3(kReduceBlocks), dim3(kReduceThreads), 0, st, ws_hist, ws_stats,
                        nblocks, (unsigned long long)n, out);
     return launch_status();
 }
