@@ -8,9 +8,11 @@
 // and counters to the workspace -- no global atomics, so the result does not
 // depend on scheduling.
 // Pass 2 (profile_reduce): one workgroup per 64 bins sums the partials (256-byte
-// contiguous reads) into the 64-bit histogram; the last workgroup to finish
-// (device-scope counter in the result struct, zeroed by pass 1) scans the 2048
-// bins for the nearest-rank percentiles and writes the scalar fields.
+// contiguous reads) into the 64-bit histogram.  Pass 1 also leaves per-workgroup
+// counts of each 64-bin group, from which every pass-2 workgroup derives the
+// number of elements below its own bins; it can then decide by itself whether a
+// nearest-rank percentile falls into one of its bins -- no cross-workgroup
+// ordering, fences or atomics.  Workgroup 0 also writes the scalar fields.
 #include "tao_device.hpp"
 #include "tao_host.hpp"
 
@@ -25,8 +27,8 @@ constexpr int kReduceBlocks = kBins / kBinsPerReduceBlock;
 constexpr int kReduceThreads = 1024;
 constexpr int kReduceSlices = kReduceThreads / kBinsPerReduceBlock;      // 16
 constexpr int kPartialsPerThread = kMaxCheckBlocks / kReduceSlices;      // 16 independent loads
-constexpr int kBinsPerThread = kBins / kReduceThreads;                    // 2, in the final scan
 constexpr int kReduceWaves = kReduceThreads / kWave;
+constexpr int kGroups = kBins / kBinsPerReduceBlock;                      // 32 coarse groups of 64 bins
 
 struct BlockStats {          // one per pass-1 workgroup, in the workspace after the histograms
     unsigned long long violations;
@@ -59,12 +61,12 @@ __device__ __forceinline__ void check_one(float c, float r, float t, double alph
 __global__ __launch_bounds__(kCheckThreads) void check_pass(
     const float* __restrict__ claimed, const float* __restrict__ ref, const float* __restrict__ tau,
     long n, int vec_ok, double alpha, double eps_rel,
-    unsigned int* __restrict__ ws_hist, BlockStats* __restrict__ ws_stats, tao_profile* out) {
+    unsigned int* __restrict__ ws_hist, unsigned int* __restrict__ ws_coarse,
+    BlockStats* __restrict__ ws_stats) {
     __shared__ unsigned int hist[kBins * kReplicas];
     __shared__ unsigned int red[3 * (kCheckThreads / kWave)];
     const int tid = threadIdx.x;
     for (int i = tid; i < kBins * kReplicas; i += kCheckThreads) hist[i] = 0;
-    if (blockIdx.x == 0 && tid == 0) out->pad_ = 0;      // completion counter of pass 2
     __syncthreads();
 
     ThreadAcc acc;
@@ -109,6 +111,11 @@ __global__ __launch_bounds__(kCheckThreads) void check_pass(
 #pragma unroll
         for (int r = 0; r < kReplicas; ++r) s += hist[b * kReplicas + r];
         dst[b] = s;
+        // a wavefront covers exactly one group of 64 consecutive bins
+        unsigned int g = s;
+#pragma unroll
+        for (int o = kWave / 2; o > 0; o >>= 1) g += __shfl_xor(g, o, kWave);
+        if ((tid & (kWave - 1)) == 0) ws_coarse[blockIdx.x * kGroups + b / kBinsPerReduceBlock] = g;
     }
 }
 
@@ -126,15 +133,14 @@ __device__ __forceinline__ unsigned long long rank_of(unsigned long long n, unsi
 }
 
 __global__ __launch_bounds__(kReduceThreads) void profile_reduce(
-    const unsigned int* __restrict__ ws_hist, const BlockStats* __restrict__ ws_stats, int nblocks,
-    unsigned long long n, tao_profile* out) {
+    const unsigned int* __restrict__ ws_hist, const unsigned int* __restrict__ ws_coarse,
+    const BlockStats* __restrict__ ws_stats, int nblocks, unsigned long long n, tao_profile* out) {
     __shared__ unsigned long long part[kReduceThreads];
-    __shared__ unsigned long long wtot[kReduceWaves], wv[kReduceWaves], wq[kReduceWaves];
+    __shared__ unsigned long long wsum[kReduceWaves], wv[kReduceWaves], wq[kReduceWaves];
     __shared__ unsigned int wm[kReduceWaves];
-    __shared__ int is_last;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = tid / kWave;
-    // 64 bins x 16 slices of the partial histograms; all loads of a thread are independent
+    // own bins: 64 bins x 16 slices of the partial histograms; all loads independent
     const int b = tid & (kBinsPerReduceBlock - 1);
     const int slice = tid / kBinsPerReduceBlock;
     const int bin = blockIdx.x * kBinsPerReduceBlock + b;
@@ -144,69 +150,58 @@ __global__ __launch_bounds__(kReduceThreads) void profile_reduce(
         const int k = slice + kReduceSlices * j;
         vals[j] = (k < nblocks) ? ws_hist[(size_t)k * kBins + bin] : 0u;
     }
+    // elements in all bins below this workgroup's: coarse counts of the groups g < blockIdx.x
+    unsigned long long below = 0;
+    const int total = nblocks * kGroups;
+#pragma unroll
+    for (int j = 0; j < (kMaxCheckBlocks * kGroups) / kReduceThreads; ++j) {
+        const int e = tid + kReduceThreads * j;
+        if (e < total && (e % kGroups) < (int)blockIdx.x) below += ws_coarse[e];
+    }
     unsigned long long s = 0;
 #pragma unroll
     for (int j = 0; j < kPartialsPerThread; ++j) s += vals[j];
     part[tid] = s;
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) below += __shfl_xor(below, o, kWave);
+    if (lane == 0) wsum[wave] = below;
+    // counters of pass 1 (workgroup 0 only; at most one record per thread)
+    unsigned long long v = 0, q = 0; unsigned int m = 0;
+    if (blockIdx.x == 0) {
+        for (int k = tid; k < nblocks; k += kReduceThreads) {
+            v += ws_stats[k].violations; q += ws_stats[k].nans; m = max(m, ws_stats[k].max_bits);
+        }
+#pragma unroll
+        for (int o = kWave / 2; o > 0; o >>= 1) {
+            v += __shfl_xor(v, o, kWave); q += __shfl_xor(q, o, kWave);
+            m = max(m, (unsigned int)__shfl_xor(m, o, kWave));
+        }
+        if (lane == 0) { wv[wave] = v; wq[wave] = q; wm[wave] = m; }
+    }
     __syncthreads();
-    if (tid < kBinsPerReduceBlock) {
+    if (tid < kBinsPerReduceBlock) {            // first wavefront: one lane per bin
         unsigned long long t = 0;
 #pragma unroll
         for (int k = 0; k < kReduceSlices; ++k) t += part[k * kBinsPerReduceBlock + tid];
-        out->hist[blockIdx.x * kBinsPerReduceBlock + tid] = t;
-    }
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) is_last = (atomicAdd(&out->pad_, 1u) == (unsigned)(gridDim.x - 1));
-    __syncthreads();
-    if (!is_last) return;
-    __threadfence();
-
-    // Finalise: each thread owns 2 consecutive bins; exclusive prefix over threads by a
-    // shuffle scan inside each wavefront plus the wavefront totals.
-    unsigned long long h[kBinsPerThread], local = 0;
-    const volatile uint64_t* gh = out->hist;
+        out->hist[bin] = t;
+        unsigned long long before = 0;
 #pragma unroll
-    for (int k = 0; k < kBinsPerThread; ++k) { h[k] = gh[tid * kBinsPerThread + k]; local += h[k]; }
-    unsigned long long incl = local;
+        for (int w = 0; w < kReduceWaves; ++w) before += wsum[w];
+        unsigned long long incl = t;
 #pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-        const unsigned long long up = __shfl_up(incl, o, kWave);
-        if (lane >= o) incl += up;
-    }
-    if (lane == kWave - 1) wtot[wave] = incl;
-    // counters of pass 1 (at most one workgroup's record per thread)
-    unsigned long long v = 0, q = 0; unsigned int m = 0;
-    for (int k = tid; k < nblocks; k += kReduceThreads) {
-        v += ws_stats[k].violations; q += ws_stats[k].nans; m = max(m, ws_stats[k].max_bits);
-    }
-#pragma unroll
-    for (int o = kWave / 2; o > 0; o >>= 1) {
-        v += __shfl_xor(v, o, kWave); q += __shfl_xor(q, o, kWave);
-        m = max(m, (unsigned int)__shfl_xor(m, o, kWave));
-    }
-    if (lane == 0) { wv[wave] = v; wq[wave] = q; wm[wave] = m; }
-    __syncthreads();
-    unsigned long long before = incl - local;                 // exclusive prefix inside the wavefront
-    for (int w = 0; w < wave; ++w) before += wtot[w];
-    const unsigned long long ranks[3] = {rank_of(n, 1, 2), rank_of(n, 99, 100), rank_of(n, 999, 1000)};
-    unsigned int* bins_out[3] = {&out->p50_bin, &out->p99_bin, &out->p999_bin};
-    float* vals_out[3] = {&out->p50, &out->p99, &out->p999};
-    if (n > 0) {
-        unsigned long long cum = before;
-#pragma unroll
-        for (int k = 0; k < kBinsPerThread; ++k) {
-            const unsigned long long lo = cum;
-            cum += h[k];
-#pragma unroll
-            for (int p = 0; p < 3; ++p)
-                if (lo < ranks[p] && ranks[p] <= cum) {
-                    *bins_out[p] = tid * kBinsPerThread + k;
-                    *vals_out[p] = bin_upper_edge(tid * kBinsPerThread + k);
-                }
+        for (int o = 1; o < kWave; o <<= 1) {
+            const unsigned long long up = __shfl_up(incl, o, kWave);
+            if (lane >= o) incl += up;
+        }
+        const unsigned long long hi = before + incl, lo = hi - t;      // ranks (lo, hi] fall in this bin
+        if (n > 0) {
+            const unsigned long long r50 = rank_of(n, 1, 2), r99 = rank_of(n, 99, 100), r999 = rank_of(n, 999, 1000);
+            if (lo < r50 && r50 <= hi) { out->p50_bin = bin; out->p50 = bin_upper_edge(bin); }
+            if (lo < r99 && r99 <= hi) { out->p99_bin = bin; out->p99 = bin_upper_edge(bin); }
+            if (lo < r999 && r999 <= hi) { out->p999_bin = bin; out->p999 = bin_upper_edge(bin); }
         }
     }
-    if (tid == 0) {
+    if (blockIdx.x == 0 && tid == 0) {
         v = 0; q = 0; m = 0;
         for (int w = 0; w < kReduceWaves; ++w) { v += wv[w]; q += wq[w]; m = max(m, wm[w]); }
         out->n = n;
@@ -214,6 +209,7 @@ __global__ __launch_bounds__(kReduceThreads) void profile_reduce(
         out->nan_count = q;
         out->max_rel = __uint_as_float(m);
         out->accept = (v == 0) ? 1u : 0u;
+        out->pad_ = 0;
         if (n == 0) {
             out->p50_bin = out->p99_bin = out->p999_bin = 0;
             out->p50 = out->p99 = out->p999 = bin_upper_edge(0);
@@ -227,7 +223,8 @@ extern "C" {
 
 size_t tao_check_workspace_bytes(long n) {
     (void)n;
-    return (size_t)tao::kMaxCheckBlocks * (tao::kBins * sizeof(unsigned int) + sizeof(tao::BlockStats));
+    return (size_t)tao::kMaxCheckBlocks *
+           ((tao::kBins + tao::kGroups) * sizeof(unsigned int) + sizeof(tao::BlockStats));
 }
 
 int tao_check_and_profile(const float* claimed, const float* ref, const float* tau, long n,
@@ -246,11 +243,12 @@ int tao_check_and_profile(const float* claimed, const float* ref, const float* t
     long want = (n + (long)kCheckThreads * 16 - 1) / ((long)kCheckThreads * 16);
     int nblocks = (int)(want < 1 ? 1 : (want > kMaxCheckBlocks ? kMaxCheckBlocks : want));
     unsigned int* ws_hist = (unsigned int*)ws;
-    BlockStats* ws_stats = (BlockStats*)((char*)ws + (size_t)kMaxCheckBlocks * kBins * sizeof(unsigned int));
+    unsigned int* ws_coarse = ws_hist + (size_t)kMaxCheckBlocks * kBins;
+    BlockStats* ws_stats = (BlockStats*)(ws_coarse + (size_t)kMaxCheckBlocks * kGroups);
     hipLaunchKernelGGL(check_pass, dim3(nblocks), dim3(kCheckThreads), 0, st, claimed, ref, tau, n,
-                       vec_ok, alpha, eps_rel, ws_hist, ws_stats, out);
-    hipLaunchKernelGGL(profile_reduce, dim3(kReduceBlocks), dim3(kReduceThreads), 0, st, ws_hist, ws_stats,
-                       nblocks, (unsigned long long)n, out);
+                       vec_ok, alpha, eps_rel, ws_hist, ws_coarse, ws_stats);
+    hipLaunchKernelGGL(profile_reduce, dim3(kReduceBlocks), dim3(kReduceThreads), 0, st, ws_hist, ws_coarse,
+                       ws_stats, nblocks, (unsigned long long)n, out);
     return launch_status();
 }
 
