@@ -16,11 +16,14 @@
 // exact <= tau <= exact (1 + 16u + ...) < exact (1 + 1e-6).
 //
 // Tiling: 128x128 output tile per 512-thread workgroup: eight wavefronts (4 along
-// M, 2 along N), each owning two 32x32 MFMA tiles.  Two wavefronts share a SIMD,
-// so one can fold its partial sums on the vector ALU while the other feeds the
-// matrix core.  K advances in slabs of 48 (four chain pairs); |A| and |W| slabs
-// are staged through LDS with the sign bit cleared on the way in; the next slab
-// is prefetched into registers while the current one is consumed.
+// M, 2 along N), each owning two 32x32 MFMA tiles.  K advances in slabs of 48
+// (four chain pairs); |A| and |W| slabs travel global -> registers -> LDS with
+// the sign bit cleared on the way in, through three LDS stages so that the
+// operands of the next chain pair are always fetched ahead of the barrier.  On
+// this hardware FP32 MFMA and vector-ALU instructions of a SIMD do not overlap,
+// so the fold (three VALU operations per output element and 12 k-steps) is the
+// price of the 1e-6 guarantee; TAO_FLAG_FAST_ACCUM skips it.
+#include <type_traits>
 #include "tao_device.hpp"
 #include "tao_host.hpp"
 
@@ -40,6 +43,7 @@ struct LinArgs {
     const float* A; const float* W; const float* bias; float* tau;
     long M, N, K, lda, ldw, ldt, strideA, strideW, strideT;
     int vecA, vecW;            // 16-byte global loads allowed
+    int fast_ok;               // vecA && vecW && per-thread slab offsets fit in 32 bits
     double c;                  // Gamma(K'), upper
     double infl;               // reciprocal of the lower rounding factor of the accumulation
     double uflow;              // optional absolute underflow term
@@ -65,11 +69,13 @@ __device__ __forceinline__ float4 gload(const float* __restrict__ base, long r, 
 
 // One LDS stage holds a 128 x 48 slab of |A| and one of |W|.
 constexpr int kStageFloats = BM * SA + (BN * SA > BK * SWT ? BN * SA : BK * SWT);
-constexpr int kStages = 2;
+constexpr int kStages = 3;
 constexpr size_t kLinLdsBytes = (size_t)kStages * kStageFloats * sizeof(float);
 
 // Scheduling hint: the next `n` instructions of class `mask` (8 = MFMA, 2 = VALU) form a group.
 #define TAO_SCHED_GROUP(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+
+struct Frags { float a[6]; float b[2][6]; };
 
 template <bool TRANS_W, bool FAST>
 __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
@@ -83,129 +89,154 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
     const float* __restrict__ A = p.A + (long)blockIdx.z * p.strideA;
     const float* __restrict__ W = p.W + (long)blockIdx.z * p.strideW;
     float* __restrict__ T = p.tau + (long)blockIdx.z * p.strideT;
-    // interior tiles with aligned operands take unguarded 16-byte loads
-    const bool full_mn = (m0 + BM <= p.M) && (n0 + BN <= p.N) && p.vecA && p.vecW;
+    // Interior tiles of aligned operands take unguarded 16-byte loads: a uniform slab base plus
+    // one 32-bit per-thread byte offset; the three vectors of a thread sit at constant strides.
+    const bool interior = (m0 + BM <= p.M) && (n0 + BN <= p.N) && p.fast_ok;
 
-    float4 pa[kVecPerThread], pw[kVecPerThread];
-    auto prefetch = [&](long k0) {
-        const bool fast_slab = full_mn && (k0 + BK <= p.K);
+    // global -> register -> LDS mapping.  k-contiguous slab [128 rows][48]: thread -> row tid/4,
+    // columns 4*(tid%4) + 16*i.  [k][n] slab of a transposed W: rows tid/32 + 16*i, columns 4*(tid%32).
+    const int ld_row = tid >> 2, ld_k = (tid & 3) * 4;
+    const int lt_kr = tid >> 5, lt_n = (tid & 31) * 4;
+    const unsigned offA = (unsigned)((ld_row * p.lda + ld_k) * 4);
+    const unsigned offW = TRANS_W ? (unsigned)((lt_kr * p.ldw + lt_n) * 4) : (unsigned)((ld_row * p.ldw + ld_k) * 4);
+    const long strideWi = TRANS_W ? 16 * p.ldw * 4 : 64;               // bytes between a thread's vectors
+    const int stA = ld_row * SA + ld_k;                                // + 16*i
+    const int stW = BM * SA + (TRANS_W ? lt_kr * SWT + lt_n : ld_row * SA + ld_k);   // + 16*SWT*i or 16*i
+    const char* baseA = reinterpret_cast<const char*>(A + m0 * p.lda);
+    const char* baseW = reinterpret_cast<const char*>(TRANS_W ? W + n0 : W + n0 * p.ldw);
+    const long slabW = TRANS_W ? (long)BK * p.ldw * 4 : (long)BK * 4;  // bytes per slab along K
+
+    float4 ra[kVecPerThread], rw[kVecPerThread];
+    auto load_slab = [&](long s) {
+        const long k0 = s * BK;
+        if (interior && k0 + BK <= p.K) {
+            const char* ba = baseA + k0 * 4 + offA;
+            const char* bw = baseW + s * slabW + offW;
 #pragma unroll
-        for (int i = 0; i < kVecPerThread; ++i) {
-            const int f = tid + kLinThreads * i;
-            const int row = f / (BK / 4), k = (f % (BK / 4)) * 4;
-            const int kr = f / (BN / 4), n = (f % (BN / 4)) * 4;     // [k][n] slab of a transposed W
-            if (fast_slab) {
-                pa[i] = *reinterpret_cast<const float4*>(A + (m0 + row) * p.lda + k0 + k);
-                pw[i] = TRANS_W ? *reinterpret_cast<const float4*>(W + (k0 + kr) * p.ldw + n0 + n)
-                                : *reinterpret_cast<const float4*>(W + (n0 + row) * p.ldw + k0 + k);
-            } else {
-                pa[i] = gload(A, m0 + row, p.M, p.lda, k0 + k, p.K, p.vecA);
-                pw[i] = TRANS_W ? gload(W, k0 + kr, p.K, p.ldw, n0 + n, p.N, p.vecW)
-                                : gload(W, n0 + row, p.N, p.ldw, k0 + k, p.K, p.vecW);
+            for (int i = 0; i < kVecPerThread; ++i) {
+                ra[i] = *reinterpret_cast<const float4*>(ba + 64 * i);
+                rw[i] = *reinterpret_cast<const float4*>(bw + strideWi * i);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < kVecPerThread; ++i) {
+                ra[i] = gload(A, m0 + ld_row, p.M, p.lda, k0 + ld_k + 16 * i, p.K, p.vecA);
+                rw[i] = TRANS_W ? gload(W, k0 + lt_kr + 16 * i, p.K, p.ldw, n0 + lt_n, p.N, p.vecW)
+                                : gload(W, n0 + ld_row, p.N, p.ldw, k0 + ld_k + 16 * i, p.K, p.vecW);
             }
         }
     };
-    auto commit = [&](int stage) {
-        float* As = lds + stage * kStageFloats;
-        float* Ws = As + BM * SA;
+    // registers -> LDS stage, sign bits cleared
+    auto commit = [&](float* stage) {
 #pragma unroll
         for (int i = 0; i < kVecPerThread; ++i) {
-            const int f = tid + kLinThreads * i;
-            const int row = f / (BK / 4), k = (f % (BK / 4)) * 4;
-            const float4 a = abs4(pa[i]);
-            float2* da = reinterpret_cast<float2*>(&As[row * SA + k]);
+            const float4 a = abs4(ra[i]);
+            float2* da = reinterpret_cast<float2*>(stage + stA + 16 * i);
             da[0] = make_float2(a.x, a.y); da[1] = make_float2(a.z, a.w);
-            const float4 w = abs4(pw[i]);
+            const float4 w = abs4(rw[i]);
             if (!TRANS_W) {
-                float2* dw = reinterpret_cast<float2*>(&Ws[row * SA + k]);
+                float2* dw = reinterpret_cast<float2*>(stage + stW + 16 * i);
                 dw[0] = make_float2(w.x, w.y); dw[1] = make_float2(w.z, w.w);
             } else {
-                const int kr = f / (BN / 4), n = (f % (BN / 4)) * 4;
-                *reinterpret_cast<float4*>(&Ws[kr * SWT + n]) = w;
+                *reinterpret_cast<float4*>(stage + stW + 16 * SWT * i) = w;
             }
         }
     };
 
-    // S: binary64 running sums; c0/c1: the two 6-step chains of each tile.  The fold of tile 1
-    // is deferred by one step so that it overlaps the MFMAs of tile 0 of the next chain pair.
+    // S: binary64 running sums (tight mode); c0: the single FP32 chain (fast mode)
     double S[2][16];
-    floatx16 c0[2], c1[2];
+    floatx16 c0[2];
 #pragma unroll
     for (int tj = 0; tj < 2; ++tj) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { S[tj][v] = 0.0; c0[tj][v] = 0.f; c1[tj][v] = 0.f; }
+        for (int v = 0; v < 16; ++v) { S[tj][v] = 0.0; c0[tj][v] = 0.f; }
     }
     floatx16 zero;
 #pragma unroll
     for (int v = 0; v < 16; ++v) zero[v] = 0.f;
 
-    const long nslab = (p.K + BK - 1) / BK;
-    if (nslab > 0) { prefetch(0); commit(0); }
-    __syncthreads();
-    for (long s = 0; s < nslab; ++s) {
-        const bool more = s + 1 < nslab;
-        if (more) prefetch((s + 1) * BK);
-        const float* As = lds + (int)(s & 1) * kStageFloats;
-        const float* Ws = As + BM * SA;
-#pragma unroll 1
-        for (int pr = 0; pr < BK / 12; ++pr) {
-            const int kb = pr * 12 + 6 * h;           // this half-wavefront's six k indices
-            float a[6], b[2][6];
-            {
-                const float2* src = reinterpret_cast<const float2*>(&As[(wm * 32 + r32) * SA + kb]);
+    const int fragA = (wm * 32 + r32) * SA + 6 * h;
+    const int fragW = BM * SA + (TRANS_W ? (6 * h) * SWT + wn * 64 + r32 : (wn * 64 + r32) * SA + 6 * h);
+
+    // operand registers of one chain pair (12 k-steps, both tiles) from LDS stage `st`
+    auto read_frags = [&](const float* st, int pr, Frags& f) {
+        {
+            const float2* src = reinterpret_cast<const float2*>(st + fragA + pr * 12);
+            const float2 v0 = src[0], v1 = src[1], v2 = src[2];
+            f.a[0] = v0.x; f.a[1] = v0.y; f.a[2] = v1.x; f.a[3] = v1.y; f.a[4] = v2.x; f.a[5] = v2.y;
+        }
+#pragma unroll
+        for (int tj = 0; tj < 2; ++tj) {
+            if (!TRANS_W) {
+                const float2* src = reinterpret_cast<const float2*>(st + fragW + tj * 32 * SA + pr * 12);
                 const float2 v0 = src[0], v1 = src[1], v2 = src[2];
-                a[0] = v0.x; a[1] = v0.y; a[2] = v1.x; a[3] = v1.y; a[4] = v2.x; a[5] = v2.y;
-            }
-#pragma unroll
-            for (int tj = 0; tj < 2; ++tj) {
-                if (!TRANS_W) {
-                    const float2* src = reinterpret_cast<const float2*>(&Ws[(wn * 64 + tj * 32 + r32) * SA + kb]);
-                    const float2 v0 = src[0], v1 = src[1], v2 = src[2];
-                    b[tj][0] = v0.x; b[tj][1] = v0.y; b[tj][2] = v1.x; b[tj][3] = v1.y; b[tj][4] = v2.x; b[tj][5] = v2.y;
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 6; ++j) b[tj][j] = Ws[(kb + j) * SWT + wn * 64 + tj * 32 + r32];
-                }
-            }
-            if (FAST) {
-#pragma unroll
-                for (int tj = 0; tj < 2; ++tj) {
-#pragma unroll
-                    for (int j = 0; j < 6; ++j)
-                        c0[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[j], b[tj][j], c0[tj], 0, 0, 0);
-                }
+                f.b[tj][0] = v0.x; f.b[tj][1] = v0.y; f.b[tj][2] = v1.x; f.b[tj][3] = v1.y;
+                f.b[tj][4] = v2.x; f.b[tj][5] = v2.y;
             } else {
-                // step A: fold tile 1 (previous chain pair) under the MFMAs of tile 0
 #pragma unroll
-                for (int v = 0; v < 16; ++v) S[1][v] += (double)(c0[1][v] + c1[1][v]);
-                c0[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[0][0], zero, 0, 0, 0);
-                c1[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[0][3], zero, 0, 0, 0);
-                c0[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[0][1], c0[0], 0, 0, 0);
-                c1[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[4], b[0][4], c1[0], 0, 0, 0);
-                c0[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[2], b[0][2], c0[0], 0, 0, 0);
-                c1[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[5], b[0][5], c1[0], 0, 0, 0);
-#pragma unroll
-                for (int g = 0; g < 6; ++g) { TAO_SCHED_GROUP(0x008, 1); TAO_SCHED_GROUP(0x002, 8); }
-                // step B: fold tile 0 under the MFMAs of tile 1
-#pragma unroll
-                for (int v = 0; v < 16; ++v) S[0][v] += (double)(c0[0][v] + c1[0][v]);
-                c0[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[0], b[1][0], zero, 0, 0, 0);
-                c1[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[3], b[1][3], zero, 0, 0, 0);
-                c0[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[1], b[1][1], c0[1], 0, 0, 0);
-                c1[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[4], b[1][4], c1[1], 0, 0, 0);
-                c0[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[2], b[1][2], c0[1], 0, 0, 0);
-                c1[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[5], b[1][5], c1[1], 0, 0, 0);
-#pragma unroll
-                for (int g = 0; g < 6; ++g) { TAO_SCHED_GROUP(0x008, 1); TAO_SCHED_GROUP(0x002, 8); }
+                for (int j = 0; j < 6; ++j) f.b[tj][j] = st[fragW + (pr * 12 + j) * SWT + tj * 32];
             }
         }
-        // the other stage was last read before the previous barrier: safe to refill now
-        if (more) commit((int)((s + 1) & 1));
-        __syncthreads();
-    }
-    if (!FAST) {
+    };
+    // Three LDS stages.  While slab s is consumed from stage s%3, slab s+1 already sits in the
+    // next stage (so its first operands can be fetched ahead of the barrier), slab s+2 moves from
+    // registers into the third stage at the start of slab s, and slab s+3 is requested from
+    // global memory right after.  One loop iteration is one chain pair: wait for its operands,
+    // issue the 12 MFMAs, request the operands of the next pair into the same registers (the
+    // matrix core has consumed them), then fold on the vector ALU while those reads are in flight.
+    const long nslab = (p.K + BK - 1) / BK;
+    float* rd = lds;
+    float* nx = lds + kStageFloats;
+    float* wr = lds + 2 * kStageFloats;
+    if (nslab > 0) { load_slab(0); commit(rd); }
+    if (nslab > 1) { load_slab(1); commit(nx); }
+    if (nslab > 2) load_slab(2);
+    __syncthreads();
+    Frags f;
+    if (nslab > 0) read_frags(rd, 0, f);
+    const long npair = nslab * (BK / 12);
+#pragma unroll 1
+    for (long q = 0; q < npair; ++q) {
+        const int pr = (int)(q & 3);
+        const long s = q >> 2;
+        if (pr == 0) {
+            if (s + 2 < nslab) commit(wr);
+            if (s + 3 < nslab) load_slab(s + 3);
+        }
+        floatx16 u0[2], u1[2];
+        if (FAST) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) S[1][v] += (double)(c0[1][v] + c1[1][v]);
+            for (int tj = 0; tj < 2; ++tj) {
+#pragma unroll
+                for (int j = 0; j < 6; ++j)
+                    c0[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[j], f.b[tj][j], c0[tj], 0, 0, 0);
+            }
+        } else {
+            // per tile: two 6-step chains from zero
+#pragma unroll
+            for (int tj = 0; tj < 2; ++tj) {
+                u0[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[0], f.b[tj][0], zero, 0, 0, 0);
+                u1[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[3], f.b[tj][3], zero, 0, 0, 0);
+                u0[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[1], f.b[tj][1], u0[tj], 0, 0, 0);
+                u1[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[4], f.b[tj][4], u1[tj], 0, 0, 0);
+                u0[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[2], f.b[tj][2], u0[tj], 0, 0, 0);
+                u1[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[5], f.b[tj][5], u1[tj], 0, 0, 0);
+            }
+        }
+        // operands of the next pair (same slab, or the first pair of the next slab's stage)
+        if (q + 1 < npair) read_frags(pr == 3 ? nx : rd, pr == 3 ? 0 : pr + 1, f);
+        if (!FAST) {
+            // chains added in binary32, folded into binary64
+#pragma unroll
+            for (int tj = 0; tj < 2; ++tj) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) S[tj][v] += (double)(u0[tj][v] + u1[tj][v]);
+            }
+        }
+        if (pr == 3) {
+            __syncthreads();
+            float* t = rd; rd = nx; nx = wr; wr = t;
+        }
     }
 
     // epilogue: D[i][j] of a 32x32 tile sits in lane (j + 32*((i/4)%2)), register 4*(i/8) + i%4
@@ -217,8 +248,8 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
         for (int v = 0; v < 16; ++v) {
             const long row = m0 + wm * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
             if (row < p.M && col < p.N) {
-                const double s = FAST ? (double)c0[tj][v] : S[tj][v];
-                const double t = p.c * (s * p.infl + ab) * kGuard + p.uflow;
+                const double sv = FAST ? (double)c0[tj][v] : S[tj][v];
+                const double t = p.c * (sv * p.infl + ab) * kGuard + p.uflow;
                 T[row * p.ldt + col] = up32(t);
             }
         }
@@ -280,6 +311,11 @@ int tao_bound_linear(const float* A, const float* W, const float* bias, float* t
     p.strideA = strideA; p.strideW = strideW; p.strideT = strideT;
     p.vecA = aligned(A, 16) && (lda % 4 == 0) && (strideA % 4 == 0);
     p.vecW = aligned(W, 16) && (ldw % 4 == 0) && (strideW % 4 == 0);
+    {   // byte offsets inside one slab must fit in 32 bits for the unguarded load path
+        const long spanA = ((long)(BM - 1) * lda + BK) * 4;
+        const long spanW = trans_w ? ((long)(BK - 1) * ldw + BN) * 4 : ((long)(BN - 1) * ldw + BK) * 4;
+        p.fast_ok = p.vecA && p.vecW && (K % 4 == 0) && spanA < (1L << 31) && spanW < (1L << 31);
+    }
     p.c = c;
     const bool fast = (md.flags & TAO_FLAG_FAST_ACCUM) != 0;
     const double u = md.u;
