@@ -1,0 +1,134 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
+The oracle cannot redo whole tensors of these sizes, so bounds are compared on sampled
+output rows (first, last, random) that the oracle computes one by one, the check/profile
+pass is compared bit-exactly on whole synthetic triplets (it is cheap on the CPU), and
+properties that hold at any size are asserted on the full outputs (no violation for an
+honest claim; violation count equal to the number of planted 1.01x elements)."""
+import numpy as np
+import pytest
+import torch
+
+import tao_inputs
+from opmap import assert_bound_parity, assert_profile_equal, gpu_tau, oracle_tau
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tao():
+    import paper_2510_16028_amd as t
+    t.lib()
+    assert torch.cuda.is_available()
+    return t
+
+
+def _np(t):
+    return t.detach().cpu().numpy()
+
+
+def _sample_rows(nrows, k, seed):
+    g = np.random.Generator(np.random.Philox(seed))
+    rows = {0, nrows - 1, nrows // 2} | set(g.integers(0, nrows, k).tolist())
+    return torch.tensor(sorted(rows), dtype=torch.long)
+
+
+def _sub_op(op, rows, batch=None):
+    """The operator restricted to some output rows (of one batch entry for batched matmuls)."""
+    dev_rows = rows.to(op.y_ref.device)
+    a = op.args
+    if op.kind == "linear":
+        if a["A"].dim() == 3:
+            args = {"A": a["A"][batch].index_select(0, dev_rows), "W": a["W"][batch], "bias": None}
+            y, c = op.y_ref[batch].index_select(0, dev_rows), op.claimed[batch].index_select(0, dev_rows)
+        else:
+            args = {"A": a["A"].index_select(0, dev_rows), "W": a["W"], "bias": a.get("bias")}
+            y, c = op.y_ref.index_select(0, dev_rows), op.claimed.index_select(0, dev_rows)
+    else:
+        cols = op.y_ref.shape[-1]
+
+        def cut(t):
+            return t.reshape(-1, cols).index_select(0, dev_rows)
+        args = {k: (cut(v) if k in ("x", "x2") and v is not None else v) for k, v in a.items()}
+        y, c = cut(op.y_ref), cut(op.claimed)
+    cpu = lambda t: None if t is None else t.detach().cpu().contiguous()
+    return tao_inputs.Op(op.name, op.kind, {k: cpu(v) for k, v in args.items()}, cpu(y), cpu(c), op.attrs)
+
+
+def _tau_rows(tau, op, rows, batch=None):
+    dev_rows = rows.to(tau.device)
+    if op.kind == "linear" and op.args["A"].dim() == 3:
+        return tau[batch].index_select(0, dev_rows)
+    return tau.reshape(-1, tau.shape[-1]).index_select(0, dev_rows)
+
+
+def _check_ops_sampled(tao, oracle_mod, ops, nsample, seed):
+    for idx, op in enumerate(ops):
+        print("op", op.name, op.kind, tuple(op.y_ref.shape), flush=True)
+        tau = gpu_tau(tao, op)
+        # property on the whole tensor: the honest claim is accepted by the GPU's own bound
+        p = tao.tao_check_and_profile(op.claimed.contiguous(), op.y_ref.contiguous(), tau.contiguous())
+        assert p["violations"] == 0 and p["n"] == op.y_ref.numel(), op.name
+        nrows = op.y_ref.shape[-2] if op.kind == "linear" else op.y_ref.numel() // op.y_ref.shape[-1]
+        rows = _sample_rows(nrows, nsample, seed + idx)
+        batch = (idx % op.args["A"].shape[0]) if (op.kind == "linear" and op.args["A"].dim() == 3) else None
+        sub = _sub_op(op, rows, batch)
+        t_or = oracle_tau(oracle_mod, sub)
+        worst = assert_bound_parity(_np(_tau_rows(tau, op, rows, batch)), t_or, op.name)
+        print("   sampled %d rows: max tau_gpu/tau_oracle - 1 = %.3e" % (len(rows), worst), flush=True)
+        # check/profile on the sampled rows with the oracle's bound on both sides: bit-exact
+        pg = tao.tao_check_and_profile(sub.claimed.cuda(), sub.y_ref.cuda(),
+                                       torch.from_numpy(np.ascontiguousarray(t_or)).cuda())
+        po = oracle_mod.check_and_profile(_np(sub.claimed), _np(sub.y_ref), t_or)
+        assert_profile_equal(pg, po, op.name)
+        del tau
+
+
+def test_config3_qwen_layer_full_size(tao, oracle_mod):
+    ops = tao_inputs.config3("cuda", scale=1)
+    _check_ops_sampled(tao, oracle_mod, ops, nsample=5, seed=300)
+
+
+def test_config2_bert_block_full_size(tao, oracle_mod):
+    ops = tao_inputs.config2("cuda", scale=1)
+    _check_ops_sampled(tao, oracle_mod, ops, nsample=13, seed=200)
+
+
+def test_config4_conv_stage_full_size(tao, oracle_mod):
+    ops = tao_inputs.config4("cuda", scale=1)
+    _check_ops_sampled(tao, oracle_mod, ops, nsample=13, seed=400)
+
+
+def test_config5_stress_full_size(tao, oracle_mod):
+    g, A, W = tao_inputs.config5_operands("cuda", size=8192)
+    ref = A @ W.t()
+    tau = tao.tao_bound_linear(A, W)
+    rows = _sample_rows(8192, 13, 500)
+    t_or = oracle_mod.bound_linear(_np(A.index_select(0, rows.cuda())), _np(W))
+    worst = assert_bound_parity(_np(tau.index_select(0, rows.cuda())), t_or, "c5 linear rows")
+    print("c5: max tau_gpu/tau_oracle - 1 on %d rows = %.3e" % (len(rows), worst), flush=True)
+    # whole-pipeline property: claims at 0.5x / 0.99x pass, those at 1.01x are all caught
+    claimed, cls = tao_inputs.config5_claimed(g, ref, tau)
+    p = tao.tao_check_and_profile(claimed, ref, tau)
+    assert p["n"] == 8192 * 8192
+    assert p["violations"] == int((cls == 2).sum())
+    # same planting built from the oracle's bound on the sampled rows: the oracle counts the
+    # same, and the GPU check on those rows is bit-identical to the oracle's
+    gs = torch.Generator().manual_seed(55)
+    ref_rows = ref.index_select(0, rows.cuda()).cpu()
+    claimed_o, cls_o = tao_inputs.config5_claimed(gs, ref_rows, torch.from_numpy(t_or))
+    po = oracle_mod.check_and_profile(_np(claimed_o), _np(ref_rows), t_or)
+    assert po["violations"] == int((cls_o == 2).sum())
+    pg = tao.tao_check_and_profile(claimed_o.cuda(), ref_rows.cuda(), torch.from_numpy(t_or).cuda())
+    assert_profile_equal(pg, po, "c5 check rows")
+    # the fast-accumulation variant stays an upper bound on the same rows
+    fast = tao.tao_bound_linear(A, W, model=tao.FpModel(flags=tao.FLAG_FAST_ACCUM))
+    assert_bound_parity(_np(fast.index_select(0, rows.cuda())), t_or, "c5 fast", rel_tol=2.5 * 8192 * 2.0 ** -24)
+
+
+def test_check_profile_67m_elements_bit_exact(tao, oracle_mod):
+    n = 8192 * 8192
+    c, r, t = tao_inputs.check_triplet("cpu", seed=67, n=n)
+    pg = tao.tao_check_and_profile(c.cuda(), r.cuda(), t.cuda())
+    po = oracle_mod.check_and_profile(_np(c), _np(r), _np(t))
+    assert_profile_equal(pg, po, "67M check")
+    assert 0 < po["violations"] < n
