@@ -148,6 +148,8 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=2048, help="output rows per operator for the CPU oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stress", action="store_true", help="skip the 8192^3 / 67M-element side measurements")
+    ap.add_argument("--copy-calib", action="store_true",
+                    help="also run three 1 GiB element-wise copy kernels (reference kernel for scaling FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); got --gpus %d" % args.gpus,
@@ -230,6 +232,14 @@ def main():
                                 "violations": prof["violations"], "expected_violations": int((cls == 2).sum()),
                                 "p50": prof["p50"], "p99": prof["p99"], "p999": prof["p999"], "max_rel": prof["max_rel"]}
         del A, W, out, ref, claimed, cls
+
+    if args.copy_calib:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)       # an element-wise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     result = {
         "metric": "traced-operator GB/s verified (bound+check) & % FP32 MFMA/HBM peak, 1 GPU",

@@ -1,0 +1,120 @@
+"""Host-side tests of the C ABI that need no GPU: the shared library loads, exports every
+function include/tao.h declares, and rejects bad arguments with the documented status
+codes before anything is enqueued."""
+import ctypes
+import math
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def tao():
+    import paper_2510_16028_amd as t
+    if not os.path.exists(t.LIB_PATH):
+        from paper_2510_16028_amd import build
+        build.build()
+    t.lib()
+    return t
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "tao.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tao_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function(tao):
+    names = _declared_functions()
+    assert len(names) >= 10
+    for n in names:
+        assert hasattr(tao.lib(), n), "libtao.so does not export %s" % n
+    assert set(names) == set(tao.EXPORTS)
+
+
+def test_struct_layouts_match_the_header(tao):
+    assert ctypes.sizeof(tao.Profile) == 8 * 3 + 4 * 10 + 8 * 2048
+    assert tao.Profile.hist.offset == 64
+    assert ctypes.sizeof(tao.FpModel) == 64
+    m = tao.tao_default_model()
+    assert (m.u, m.mode, m.lam, m.c_exp, m.c_erf, m.c_rsqrt, m.c_div, m.flags) == \
+        (2.0 ** -24, 0, 4.0, 2.0, 2.0, 2.0, 2.0, 0)
+
+
+def test_host_gamma(tao):
+    assert tao.tao_gamma(0) == 0.0
+    g = tao.tao_gamma(256)
+    assert 1 / 65535 <= g <= (1 / 65535) * (1 + 1e-14)
+    assert math.isnan(tao.tao_gamma(2 ** 24))
+    gp = tao.tao_gamma(256, tao.FpModel(mode=1))
+    assert abs(gp - 3.8147e-6) < 1e-9
+    assert math.isnan(tao.tao_gamma(10, tao.FpModel(mode=7)))
+
+
+def test_argument_validation_without_a_gpu(tao):
+    L = tao.lib()
+    p = ctypes.c_void_p(0x1000)        # aligned dummy pointer; never dereferenced on these paths
+    odd = ctypes.c_void_p(0x1002)
+    nul = ctypes.c_void_p(0)
+    # softmax
+    assert L.tao_bound_softmax(p, p, p, -1, 4, 4, None, None) == tao.ERR_SHAPE
+    assert L.tao_bound_softmax(p, p, p, 4, 8, 4, None, None) == tao.ERR_SHAPE          # ld < cols
+    assert L.tao_bound_softmax(nul, p, p, 4, 4, 4, None, None) == tao.ERR_NULL
+    assert L.tao_bound_softmax(odd, p, p, 4, 4, 4, None, None) == tao.ERR_ALIGN
+    assert L.tao_bound_softmax(p, p, p, 4, 2 ** 24 + 2, 2 ** 24 + 2, None, None) == tao.ERR_K_RANGE
+    assert L.tao_bound_softmax(nul, nul, nul, 0, 4, 4, None, None) == tao.OK             # empty: no-op
+    bad = tao.FpModel(u=0.5)
+    assert L.tao_bound_softmax(p, p, p, 4, 4, 4, ctypes.byref(bad), None) == tao.ERR_MODEL
+    # norm
+    assert L.tao_bound_norm(9, p, p, p, p, 1e-5, p, 4, 4, 4, None, None) == tao.ERR_KIND
+    assert L.tao_bound_norm(0, p, nul, p, p, 1e-5, p, 4, 4, 4, None, None) == tao.ERR_NULL   # y_ref required
+    assert L.tao_bound_norm(2, p, p, nul, p, 0.0, p, 4, 4, 4, None, None) == tao.ERR_NULL    # scale required
+    assert L.tao_bound_norm(0, p, p, p, p, -1.0, p, 4, 4, 4, None, None) == tao.ERR_SHAPE
+    # act
+    assert L.tao_bound_act(7, p, p, p, p, 4, None, None) == tao.ERR_KIND
+    assert L.tao_bound_act(0, nul, nul, p, p, 4, None, None) == tao.ERR_NULL                 # GELU needs x
+    assert L.tao_bound_act(1, nul, nul, p, p, -4, None, None) == tao.ERR_SHAPE
+    assert L.tao_bound_act(1, nul, nul, nul, nul, 0, None, None) == tao.OK
+    # linear
+    args = lambda M, N, K, lda, ldw, ldt, tw=0, batch=1: (M, N, K, lda, ldw, ldt, tw, batch, 0, 0, 0)
+    assert L.tao_bound_linear(p, p, nul, p, *args(4, 4, 8, 4, 8, 4), None, None) == tao.ERR_SHAPE   # lda < K
+    assert L.tao_bound_linear(p, p, nul, p, *args(4, 4, 8, 8, 8, 2), None, None) == tao.ERR_SHAPE   # ldt < N
+    assert L.tao_bound_linear(p, p, nul, p, *args(4, 4, 8, 8, 2, 4, 1), None, None) == tao.ERR_SHAPE  # trans: ldw < N
+    assert L.tao_bound_linear(p, p, nul, p, *args(-1, 4, 8, 8, 8, 4), None, None) == tao.ERR_SHAPE
+    K = 2 ** 24
+    assert L.tao_bound_linear(p, p, nul, p, *args(4, 4, K, K, K, 4), None, None) == tao.ERR_K_RANGE
+    assert L.tao_bound_linear(nul, p, nul, p, *args(4, 4, 8, 8, 8, 4), None, None) == tao.ERR_NULL
+    assert L.tao_bound_linear(p, odd, nul, p, *args(4, 4, 8, 8, 8, 4), None, None) == tao.ERR_ALIGN
+    assert L.tao_bound_linear(nul, nul, nul, nul, *args(0, 4, 8, 8, 8, 4), None, None) == tao.OK
+    # check
+    need = L.tao_check_workspace_bytes(1000)
+    assert need > 0
+    ws = ctypes.c_void_p(0x10000)
+    assert L.tao_check_and_profile(p, p, p, 10, 1.0, 0.0, nul, ws, need, None) == tao.ERR_NULL
+    assert L.tao_check_and_profile(p, p, p, 10, 1.0, 0.0, p, nul, need, None) == tao.ERR_WORKSPACE
+    assert L.tao_check_and_profile(p, p, p, 10, 1.0, 0.0, p, ws, need - 1, None) == tao.ERR_WORKSPACE
+    assert L.tao_check_and_profile(p, p, p, 10, 1.0, 0.0, p, ctypes.c_void_p(0x10010), need, None) == tao.ERR_WORKSPACE
+    assert L.tao_check_and_profile(p, p, p, -1, 1.0, 0.0, p, ws, need, None) == tao.ERR_SHAPE
+    assert L.tao_check_and_profile(nul, p, p, 10, 1.0, 0.0, p, ws, need, None) == tao.ERR_NULL
+    assert L.tao_check_and_profile(odd, p, p, 10, 1.0, 0.0, p, ws, need, None) == tao.ERR_ALIGN
+    for code in range(0, -9, -1):
+        assert L.tao_status_string(code)
+    assert L.tao_selftest_matrix_core(None, None) == tao.ERR_NULL
+
+
+def test_binding_refuses_to_run_without_a_gpu(tao):
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(RuntimeError):
+        tao.tao_bound_softmax(torch.zeros(2, 2), torch.zeros(2, 2))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr
