@@ -74,9 +74,9 @@ __global__ __launch_bounds__(kCheckThreads) void check_pass(
     const long nvec = vec_ok ? (n >> 2) : 0;
     const long stride = (long)gridDim.x * kCheckThreads;
     for (long i = (long)blockIdx.x * kCheckThreads + tid; i < nvec; i += stride) {
-        const float4 c4 = reinterpret_cast<const float4*>(claimed)[i];
-        const float4 r4 = reinterpret_cast<const float4*>(ref)[i];
-        const float4 t4 = reinterpret_cast<const float4*>(tau)[i];
+        const float4 c4 = ntload4(reinterpret_cast<const float4*>(claimed) + i);
+        const float4 r4 = ntload4(reinterpret_cast<const float4*>(ref) + i);
+        const float4 t4 = ntload4(reinterpret_cast<const float4*>(tau) + i);
         check_one(c4.x, r4.x, t4.x, alpha, eps_rel, hist, rep, acc);
         check_one(c4.y, r4.y, t4.y, alpha, eps_rel, hist, rep, acc);
         check_one(c4.z, r4.z, t4.z, alpha, eps_rel, hist, rep, acc);

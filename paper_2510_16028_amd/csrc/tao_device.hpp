@@ -31,6 +31,13 @@ __device__ __forceinline__ int wave_or(int v) {
     return v;
 }
 
+// Streaming 16-byte load: the data is used once, so it is marked non-temporal.
+__device__ __forceinline__ float4 ntload4(const float4* p) {
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    const v4f v = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+
 // 16-byte global load when the caller has established alignment, else four
 // guarded scalar loads; elements at or beyond `limit` read as `fill`.
 __device__ __forceinline__ float4 load4(const float* __restrict__ p, long idx, long limit,
