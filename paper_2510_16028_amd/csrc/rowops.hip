@@ -95,38 +95,57 @@ __global__ __launch_bounds__(kRowThreads) void softmax_bound(
     }
     group_max_or<TPR>(m, bad, smem);
     if (m == -INFINITY) bad = 1;
-    const double am = fabs((double)m);
+    // a = u(|x| + |m|) and rho = (a(1+a) + c u)/(1 - c u) as three fused multiply-adds:
+    //   a = fma(u, |x|, u|m|);  rho = fma(fma(a, a, a), inv, c u inv)
+    const double uam = k.u * fabs((double)m);
+    const double ce_inv = k.ce_u * k.inv1mce;
     double acc[2] = {0.0, 0.0};                                  // sum q, sum rho q
+    double qv[CACHED ? V * 4 : 1], rv[CACHED ? V * 4 : 1];       // q and rho of the cached elements
     for (int v = 0; v < nv; ++v) {
         const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, -INFINITY);
         const float4 Y = CACHED ? yv[v] : load4(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
         const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w};
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            if (xe[c] == -INFINITY) continue;
-            const double a = k.u * (fabs((double)xe[c]) + am);
-            const double rho = (a * (1.0 + a) + k.ce_u) * k.inv1mce;
-            const double q = fabs((double)ye[c]) * k.inv1mu;
-            acc[0] += q; acc[1] += rho * q;
+            const bool masked = xe[c] == -INFINITY;
+            const double a = fma(k.u, fabs((double)xe[c]), uam);
+            const double rho = masked ? 0.0 : fma(fma(a, a, a), k.inv1mce, ce_inv);
+            const double q = masked ? 0.0 : fabs((double)ye[c]) * k.inv1mu;
+            acc[0] += q; acc[1] = fma(rho, q, acc[1]);
+            if (CACHED) { qv[v * 4 + c] = q; rv[v * 4 + c] = rho; }
         }
     }
     group_sum<TPR>(acc, 2, smem);
     const double sigma = k.G * acc[0] + (1.0 + k.G) * acc[1];
     if (!(sigma < 1.0)) bad = 1;
     const double sfac = sigma / (1.0 - sigma);
+    // tau = q rho + q (1+rho) sfac + u y = q (rho + (1+rho) sfac + u/inv1mu'), y = q / inv1mu;
+    // the constant uses u (not u/inv1mu): slightly larger, still within the tolerance
+    const double cy = k.u;
     for (int v = 0; v < nv; ++v) {
-        const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, -INFINITY);
-        const float4 Y = CACHED ? yv[v] : load4(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        float4 X = make_float4(0.f, 0.f, 0.f, 0.f), Y = X;
+        if (!CACHED) {
+            X = load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, -INFINITY);
+            Y = load4(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        }
         const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w};
         float te[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const double a = k.u * (fabs((double)xe[c]) + am);
-            const double rho = (a * (1.0 + a) + k.ce_u) * k.inv1mce;
-            const double ay = fabs((double)ye[c]);
-            const double q = ay * k.inv1mu;
-            const double t = q * rho + q * (1.0 + rho) * sfac + k.u * ay;
-            te[c] = bad ? NAN : (xe[c] == -INFINITY ? 0.f : up32(t * kGuard));
+            double q, rho; bool masked;
+            if (CACHED) {
+                q = qv[v * 4 + c]; rho = rv[v * 4 + c];
+                const float xc = c == 0 ? xv[v].x : c == 1 ? xv[v].y : c == 2 ? xv[v].z : xv[v].w;
+                masked = xc == -INFINITY;
+            } else {
+                masked = xe[c] == -INFINITY;
+                const double a = fma(k.u, fabs((double)xe[c]), uam);
+                rho = fma(fma(a, a, a), k.inv1mce, ce_inv);
+                q = fabs((double)ye[c]) * k.inv1mu;
+            }
+            const double w = fma(rho, sfac, sfac) + rho + cy;
+            const double t = q * w;
+            te[c] = bad ? NAN : (masked ? 0.f : up32(t * kGuard));
         }
         store4(tau + roff, TAO_VEC_INDEX(v), limit, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
     }
