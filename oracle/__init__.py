@@ -48,6 +48,26 @@ class Profile(ctypes.Structure):
                 "hist": np.ctypeslib.as_array(self.hist).copy()}
 
 
+NGRID = 22
+GRID_PERCENT = [1] + [5 * g for g in range(1, 20)] + [99, 100]
+
+
+class ErrorProfile(ctypes.Structure):
+    _fields_ = [("n", ctypes.c_uint64), ("nan_count", ctypes.c_uint64),
+                ("max_abs", ctypes.c_float), ("max_rel", ctypes.c_float),
+                ("abs_p", ctypes.c_float * NGRID), ("rel_p", ctypes.c_float * NGRID),
+                ("abs_bin", ctypes.c_uint32 * NGRID), ("rel_bin", ctypes.c_uint32 * NGRID),
+                ("p_max", ctypes.c_double), ("offending", ctypes.c_uint32), ("pad_", ctypes.c_uint32),
+                ("hist_abs", ctypes.c_uint64 * NBINS), ("hist_rel", ctypes.c_uint64 * NBINS)]
+
+    def as_dict(self):
+        arr = lambda a: np.ctypeslib.as_array(a).copy()
+        return {"n": int(self.n), "nan_count": int(self.nan_count), "max_abs": float(self.max_abs),
+                "max_rel": float(self.max_rel), "abs_p": arr(self.abs_p), "rel_p": arr(self.rel_p),
+                "abs_bin": arr(self.abs_bin), "rel_bin": arr(self.rel_bin), "p_max": float(self.p_max),
+                "offending": int(self.offending), "hist_abs": arr(self.hist_abs), "hist_rel": arr(self.hist_rel)}
+
+
 _lib = None
 
 
@@ -69,6 +89,10 @@ def lib():
         L.taoo_check_and_profile.argtypes = [fp, fp, fp, ctypes.c_long, ctypes.c_double,
                                              ctypes.c_double, ctypes.POINTER(Profile)]
         L.taoo_rel_errors.argtypes = [fp, fp, ctypes.c_long, ctypes.c_double, fp]
+        L.taoo_profile_errors.argtypes = [fp, fp, ctypes.c_long, ctypes.c_double, fp, fp,
+                                          ctypes.POINTER(ErrorProfile)]
+        L.taoo_error_profile_size.restype = ctypes.c_size_t
+        assert L.taoo_error_profile_size() == ctypes.sizeof(ErrorProfile)
         L.taoo_num_threads.restype = ctypes.c_int
         L.taoo_profile_size.restype = ctypes.c_size_t
         assert L.taoo_profile_size() == ctypes.sizeof(Profile)
@@ -164,6 +188,21 @@ def rel_errors(claimed, ref, eps_rel=1e-12):
     out = np.empty(claimed.shape, dtype=np.float32)
     _chk(lib().taoo_rel_errors(_p(claimed), _p(ref), claimed.size, float(eps_rel), _p(out)))
     return out
+
+
+def profile_errors(claimed, ref, eps_rel=1e-12, thr_abs=None, thr_rel=None):
+    """Absolute / relative error profiles on the 22-point grid and the selection statistic (Sec. 5.3)."""
+    claimed = _f32(claimed); ref = _f32(ref)
+    assert claimed.size == ref.size
+    ta = None if thr_abs is None else _f32(thr_abs)
+    tr = None if thr_rel is None else _f32(thr_rel)
+    assert (ta is None) == (tr is None)
+    if ta is not None:
+        assert ta.size == NGRID and tr.size == NGRID
+    out = ErrorProfile()
+    _chk(lib().taoo_profile_errors(_p(claimed), _p(ref), claimed.size, float(eps_rel), _p(ta), _p(tr),
+                                   ctypes.byref(out)))
+    return out.as_dict()
 
 
 def num_threads():

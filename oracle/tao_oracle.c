@@ -515,6 +515,74 @@ int taoo_rel_errors(const float *claimed, const float *ref, long n, double eps_r
     return 0;
 }
 
+/* --------------------------------------------------- error profiles on the paper's grid */
+/* Sec. 5.3 (and Sec. 3.2 Eq. 1-2): absolute and relative element-wise errors between the
+ * proposer's and the challenger's output, their percentile profiles on the 22-point grid
+ * P = {1, 5, 10, ..., 95, 99, 100}, and the selection statistic
+ *   p_max = max_p { p_abs(p)/thr_abs(p), p_rel(p)/thr_rel(p) },  offending iff p_max > 1.
+ * Percentiles are nearest-rank on the fixed 2048-edge histogram (bin = bits(e32) >> 20, NaN ->
+ * 2047) and reported as the bin's upper edge, capped by the exact maximum (so p = 100 is the
+ * maximum itself).
+ * Ratios are binary64 quotients of the reported value and the threshold; NaN ratios (0/0) are
+ * skipped; without thresholds p_max = NaN and offending = 0. */
+#define TAOO_NGRID 22
+typedef struct {
+    uint64_t n;
+    uint64_t nan_count;
+    float max_abs, max_rel;
+    float abs_p[TAOO_NGRID], rel_p[TAOO_NGRID];
+    uint32_t abs_bin[TAOO_NGRID], rel_bin[TAOO_NGRID];
+    double p_max;
+    uint32_t offending;
+    uint32_t pad_;
+    uint64_t hist_abs[TAOO_NBINS], hist_rel[TAOO_NBINS];
+} taoo_error_profile;
+
+static int grid_percent(int g) { return g == 0 ? 1 : (g <= 19 ? 5 * g : (g == 20 ? 99 : 100)); }
+
+int taoo_profile_errors(const float *claimed, const float *ref, long n, double eps_rel,
+                        const float *thr_abs, const float *thr_rel, taoo_error_profile *out) {
+    int saved = fegetround(); fesetround(FE_TONEAREST);
+    memset(out, 0, sizeof(*out));
+    out->n = (uint64_t)n;
+    float mxa = 0.0f, mxr = 0.0f;
+    for (long i = 0; i < n; ++i) {
+        volatile double c = (double)claimed[i], r = (double)ref[i];
+        volatile double d = fabs(c - r);
+        volatile double den = fabs(r) + eps_rel;
+        volatile double e = d / den;
+        float a32 = (float)d, e32 = (float)e;
+        if (e32 != e32) out->nan_count++;
+        else if (e32 > mxr) mxr = e32;
+        if (a32 == a32 && a32 > mxa) mxa = a32;
+        out->hist_abs[bin_of(a32)]++;
+        out->hist_rel[bin_of(e32)]++;
+    }
+    out->max_abs = mxa; out->max_rel = mxr;
+    double pmax = NAN;
+    for (int g = 0; g < TAOO_NGRID; ++g) {
+        int pct = grid_percent(g);
+        out->abs_bin[g] = rank_bin(out->hist_abs, out->n, (uint64_t)pct, 100);
+        out->rel_bin[g] = rank_bin(out->hist_rel, out->n, (uint64_t)pct, 100);
+        out->abs_p[g] = bin_upper_edge(out->abs_bin[g]);
+        out->rel_p[g] = bin_upper_edge(out->rel_bin[g]);
+        /* a percentile cannot exceed the exact maximum (p = 100 is the maximum itself) */
+        if (n > 0 && out->abs_bin[g] < TAOO_NBINS - 1 && out->abs_p[g] > mxa) out->abs_p[g] = mxa;
+        if (n > 0 && out->rel_bin[g] < TAOO_NBINS - 1 && out->rel_p[g] > mxr) out->rel_p[g] = mxr;
+        if (thr_abs && thr_rel) {
+            volatile double ra = (double)out->abs_p[g] / (double)thr_abs[g];
+            volatile double rr = (double)out->rel_p[g] / (double)thr_rel[g];
+            if (ra == ra && !(pmax >= ra)) pmax = ra;
+            if (rr == rr && !(pmax >= rr)) pmax = rr;
+        }
+    }
+    out->p_max = pmax;
+    out->offending = (pmax > 1.0) ? 1u : 0u;
+    fesetround(saved);
+    return 0;
+}
+size_t taoo_error_profile_size(void) { return sizeof(taoo_error_profile); }
+
 int taoo_num_threads(void) {
 #ifdef _OPENMP
     return omp_get_max_threads();
