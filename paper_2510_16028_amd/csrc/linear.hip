@@ -4,25 +4,32 @@
 //
 // The bound has to be an upper bound of the real-number value and must stay
 // within 1e-6 of it, so a plain FP32 accumulation over K (error up to K*u) is
-// not usable.  Scheme: v_mfma_f32_32x32x2_f32 accumulates chains of 3
-// instructions (6 k-steps) from a zero accumulator; two such chains are added
-// in binary32 and the sum is folded into a binary64 accumulator on the vector
-// ALU.  Every term is non-negative, so the computed sum S~ satisfies
-//   S (1-u)^7 (1-2^-53)^(K/12+1) <= S~ <= S (1+u)^7 (1+2^-53)^(K/12+1)
-// under the rounding model of App. A.1 (6 k-steps of at most one product and
-// one addition rounding each, the first addition to zero being exact, plus the
-// pair addition).  The epilogue multiplies by the reciprocal of the lower
-// factor, by Gamma and by the guard factor and rounds up to binary32:
-// exact <= tau <= exact (1 + 16u + ...) < exact (1 + 1e-6).
+// not usable.  Scheme, per 32 k-steps of an output element:
+//   - v_mfma_f32_32x32x2_f32 accumulates eight chains of 2 instructions (4
+//     k-steps) from a zero accumulator: 4 roundings per chain;
+//   - the eight chain results are added as a binary32 tree of depth 3 on the
+//     vector ALU: 3 more roundings;
+//   - the tree's root is converted and added to a binary64 running sum.
+// Every term is non-negative and passes through at most 7 binary32 roundings, so
+// the computed sum S~ satisfies
+//   S (1-u)^7 (1-2^-53)^(K/32+1) <= S~ <= S (1+u)^7 (1+2^-53)^(K/32+1)
+// under the rounding model of App. A.1.  The epilogue multiplies by the
+// reciprocal of the lower factor, by Gamma and by the guard factor and rounds up
+// to binary32: exact <= tau <= exact (1 + 16u + ...) < exact (1 + 1e-6).
+//
+// On this hardware FP32 MFMA and vector-ALU instructions of a SIMD share one
+// pipe (neither overlaps the other, from the same or another wavefront), so the
+// vector-ALU work per k-step is what the 1e-6 guarantee costs.  The 8 x 4 tree
+// is the cheapest member of the family "chain length + tree depth <= 7": seven
+// binary32 additions, one conversion and one binary64 addition per 32 k-steps.
+// TAO_FLAG_FAST_ACCUM skips all of it (one FP32 chain over K).
 //
 // Tiling: 128x128 output tile per 512-thread workgroup: eight wavefronts (4 along
-// M, 2 along N), each owning two 32x32 MFMA tiles.  K advances in slabs of 48
-// (four chain pairs); |A| and |W| slabs travel global -> registers -> LDS with
-// the sign bit cleared on the way in, through three LDS stages so that the
-// operands of the next chain pair are always fetched ahead of the barrier.  On
-// this hardware FP32 MFMA and vector-ALU instructions of a SIMD do not overlap,
-// so the fold (three VALU operations per output element and 12 k-steps) is the
-// price of the 1e-6 guarantee; TAO_FLAG_FAST_ACCUM skips it.
+// M, 2 along N), each owning two 32x32 MFMA tiles.  K advances in groups of 32;
+// |A| and |W| slabs travel global -> registers -> LDS with the sign bit cleared
+// on the way in, through three LDS stages with one barrier per group; the
+// operand registers of the next group are requested from LDS as soon as the last
+// MFMA of the current group has been issued.
 #include <type_traits>
 #include "tao_device.hpp"
 #include "tao_host.hpp"
@@ -31,13 +38,13 @@ namespace tao {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 128, BN = 128, BK = 48;
-constexpr int SA = BK + 2;          // LDS row stride (floats) of a k-contiguous slab: 8-byte reads
-                                    // of 32 consecutive rows fall in distinct bank pairs
-constexpr int SWT = BN + 16;        // LDS row stride of a [k][n] slab (trans_w): the two k-halves
-                                    // of a wavefront read disjoint bank halves
+constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int SA = BK + 4;          // LDS row stride (floats) of a k-contiguous slab: 16-byte reads
+                                    // of 16 consecutive rows fall in distinct 16-byte bank groups
+constexpr int SWT = BN + 2;         // LDS row stride of a [k][n] slab (trans_w): the two k-halves
+                                    // of a wavefront (16 rows apart) read disjoint bank halves
 constexpr int kLinThreads = 512;    // 8 wavefronts: 4 along M x 2 along N, each 32 x 64 outputs
-constexpr int kVecPerThread = (BM * BK / 4) / kLinThreads;   // 3 float4 per operand per slab
+constexpr int kVecPerThread = (BM * BK / 4) / kLinThreads;   // 2 float4 per operand per group
 
 struct LinArgs {
     const float* A; const float* W; const float* bias; float* tau;
@@ -67,15 +74,12 @@ __device__ __forceinline__ float4 gload(const float* __restrict__ base, long r, 
     return v;
 }
 
-// One LDS stage holds a 128 x 48 slab of |A| and one of |W|.
+// One LDS stage holds a 128 x 32 slab of |A| and one of |W|.
 constexpr int kStageFloats = BM * SA + (BN * SA > BK * SWT ? BN * SA : BK * SWT);
 constexpr int kStages = 3;
 constexpr size_t kLinLdsBytes = (size_t)kStages * kStageFloats * sizeof(float);
 
-// Scheduling hint: the next `n` instructions of class `mask` (8 = MFMA, 2 = VALU) form a group.
-#define TAO_SCHED_GROUP(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
-
-struct Frags { float a[6]; float b[2][6]; };
+#define TAO_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0)
 
 template <bool TRANS_W, bool FAST>
 __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
@@ -90,55 +94,64 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
     const float* __restrict__ W = p.W + (long)blockIdx.z * p.strideW;
     float* __restrict__ T = p.tau + (long)blockIdx.z * p.strideT;
     // Interior tiles of aligned operands take unguarded 16-byte loads: a uniform slab base plus
-    // one 32-bit per-thread byte offset; the three vectors of a thread sit at constant strides.
+    // one 32-bit per-thread byte offset; the two vectors of a thread sit at a constant stride.
     const bool interior = (m0 + BM <= p.M) && (n0 + BN <= p.N) && p.fast_ok;
 
-    // global -> register -> LDS mapping.  k-contiguous slab [128 rows][48]: thread -> row tid/4,
-    // columns 4*(tid%4) + 16*i.  [k][n] slab of a transposed W: rows tid/32 + 16*i, columns 4*(tid%32).
-    const int ld_row = tid >> 2, ld_k = (tid & 3) * 4;
+    // global -> register -> LDS mapping.  k-contiguous slab [128 rows][32]: thread -> rows
+    // tid/8 + 64*i, columns 4*(tid%8): eight threads fetch 128 contiguous bytes of a row.
+    // [k][n] slab of a transposed W: rows tid/32 + 16*i, columns 4*(tid%32).
+    const int ld_row = tid >> 3, ld_k = (tid & 7) * 4;
     const int lt_kr = tid >> 5, lt_n = (tid & 31) * 4;
     const unsigned offA = (unsigned)((ld_row * p.lda + ld_k) * 4);
     const unsigned offW = TRANS_W ? (unsigned)((lt_kr * p.ldw + lt_n) * 4) : (unsigned)((ld_row * p.ldw + ld_k) * 4);
-    const long strideWi = TRANS_W ? 16 * p.ldw * 4 : 64;               // bytes between a thread's vectors
-    const int stA = ld_row * SA + ld_k;                                // + 16*i
-    const int stW = BM * SA + (TRANS_W ? lt_kr * SWT + lt_n : ld_row * SA + ld_k);   // + 16*SWT*i or 16*i
+    const long strideAi = 64 * p.lda * 4;                              // bytes between a thread's vectors
+    const long strideWi = (TRANS_W ? 16 : 64) * p.ldw * 4;
+    const int stA = ld_row * SA + ld_k;                                // + 64*SA*i
+    const int stW = BM * SA + (TRANS_W ? lt_kr * SWT + lt_n : ld_row * SA + ld_k);   // + 16*SWT*i or 64*SA*i
     const char* baseA = reinterpret_cast<const char*>(A + m0 * p.lda);
     const char* baseW = reinterpret_cast<const char*>(TRANS_W ? W + n0 : W + n0 * p.ldw);
-    const long slabW = TRANS_W ? (long)BK * p.ldw * 4 : (long)BK * 4;  // bytes per slab along K
+    const long slabW = TRANS_W ? (long)BK * p.ldw * 4 : (long)BK * 4;  // bytes per group along K
+    // bytes one group's slab spans from its first element (both below 2^31 when fast_ok)
+    const long spanA = ((long)(BM - 1) * p.lda + BK) * 4;
+    const long spanW = TRANS_W ? ((long)(BK - 1) * p.ldw + BN) * 4 : ((long)(BN - 1) * p.ldw + BK) * 4;
 
-    float4 ra[kVecPerThread], rw[kVecPerThread];
-    auto load_slab = [&](long s) {
-        const long k0 = s * BK;
+    // two register sets: the slab requested during group g is written to LDS during group g+2
+    float4 ra0[kVecPerThread], rw0[kVecPerThread], ra1[kVecPerThread], rw1[kVecPerThread];
+    auto load_slab = [&](long g, float4* ra, float4* rw) {
+        const long k0 = g * BK;
         if (interior && k0 + BK <= p.K) {
-            const char* ba = baseA + k0 * 4 + offA;
-            const char* bw = baseW + s * slabW + offW;
+            // Buffer loads: descriptor (uniform base of this group's slab) in SGPRs, one 32-bit
+            // per-thread offset, the vector index as a scalar offset.  Next to FP32 MFMA this
+            // form is nearly free, while loads with a 64-bit per-lane address stall the SIMD.
+            const __amdgpu_buffer_rsrc_t da = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<char*>(baseA + k0 * 4), 0, (int)spanA, 0x00020000);
+            const __amdgpu_buffer_rsrc_t dw = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<char*>(baseW + g * slabW), 0, (int)spanW, 0x00020000);
 #pragma unroll
             for (int i = 0; i < kVecPerThread; ++i) {
-                ra[i] = *reinterpret_cast<const float4*>(ba + 64 * i);
-                rw[i] = *reinterpret_cast<const float4*>(bw + strideWi * i);
+                ra[i] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(da, (int)offA, (int)(strideAi * i), 0));
+                rw[i] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(dw, (int)offW, (int)(strideWi * i), 0));
             }
         } else {
 #pragma unroll
             for (int i = 0; i < kVecPerThread; ++i) {
-                ra[i] = gload(A, m0 + ld_row, p.M, p.lda, k0 + ld_k + 16 * i, p.K, p.vecA);
+                ra[i] = gload(A, m0 + ld_row + 64 * i, p.M, p.lda, k0 + ld_k, p.K, p.vecA);
                 rw[i] = TRANS_W ? gload(W, k0 + lt_kr + 16 * i, p.K, p.ldw, n0 + lt_n, p.N, p.vecW)
-                                : gload(W, n0 + ld_row, p.N, p.ldw, k0 + ld_k + 16 * i, p.K, p.vecW);
+                                : gload(W, n0 + ld_row + 64 * i, p.N, p.ldw, k0 + ld_k, p.K, p.vecW);
             }
         }
     };
     // registers -> LDS stage, sign bits cleared
-    auto commit = [&](float* stage) {
+    auto commit = [&](float* stage, const float4* ra, const float4* rw) {
 #pragma unroll
         for (int i = 0; i < kVecPerThread; ++i) {
-            const float4 a = abs4(ra[i]);
-            float2* da = reinterpret_cast<float2*>(stage + stA + 16 * i);
-            da[0] = make_float2(a.x, a.y); da[1] = make_float2(a.z, a.w);
+            *reinterpret_cast<float4*>(stage + stA + 64 * SA * i) = abs4(ra[i]);
             const float4 w = abs4(rw[i]);
             if (!TRANS_W) {
-                float2* dw = reinterpret_cast<float2*>(stage + stW + 16 * i);
-                dw[0] = make_float2(w.x, w.y); dw[1] = make_float2(w.z, w.w);
+                *reinterpret_cast<float4*>(stage + stW + 64 * SA * i) = w;
             } else {
-                *reinterpret_cast<float4*>(stage + stW + 16 * SWT * i) = w;
+                float2* dw = reinterpret_cast<float2*>(stage + stW + 16 * SWT * i);
+                dw[0] = make_float2(w.x, w.y); dw[1] = make_float2(w.z, w.w);
             }
         }
     };
@@ -155,88 +168,104 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) zero[v] = 0.f;
 
-    const int fragA = (wm * 32 + r32) * SA + 6 * h;
-    const int fragW = BM * SA + (TRANS_W ? (6 * h) * SWT + wn * 64 + r32 : (wn * 64 + r32) * SA + 6 * h);
-
-    // operand registers of one chain pair (12 k-steps, both tiles) from LDS stage `st`
-    auto read_frags = [&](const float* st, int pr, Frags& f) {
-        {
-            const float2* src = reinterpret_cast<const float2*>(st + fragA + pr * 12);
-            const float2 v0 = src[0], v1 = src[1], v2 = src[2];
-            f.a[0] = v0.x; f.a[1] = v0.y; f.a[2] = v1.x; f.a[3] = v1.y; f.a[4] = v2.x; f.a[5] = v2.y;
+    // Operand registers of one group: lane (r32, h) holds k = 16h .. 16h+15 of its A row and of
+    // its W row in each tile; MFMA number i of the group multiplies element i of both.
+    const int fragA = (wm * 32 + r32) * SA + 16 * h;
+    const int fragW = BM * SA + (TRANS_W ? (16 * h) * SWT + wn * 64 + r32 : (wn * 64 + r32) * SA + 16 * h);
+    float fa[16], fb[2][16];
+    auto read_frags = [&](const float* st) {
+        const float4* sa = reinterpret_cast<const float4*>(st + fragA);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float4 v = sa[j];
+            fa[4 * j] = v.x; fa[4 * j + 1] = v.y; fa[4 * j + 2] = v.z; fa[4 * j + 3] = v.w;
         }
 #pragma unroll
         for (int tj = 0; tj < 2; ++tj) {
             if (!TRANS_W) {
-                const float2* src = reinterpret_cast<const float2*>(st + fragW + tj * 32 * SA + pr * 12);
-                const float2 v0 = src[0], v1 = src[1], v2 = src[2];
-                f.b[tj][0] = v0.x; f.b[tj][1] = v0.y; f.b[tj][2] = v1.x; f.b[tj][3] = v1.y;
-                f.b[tj][4] = v2.x; f.b[tj][5] = v2.y;
+                const float4* sw = reinterpret_cast<const float4*>(st + fragW + tj * 32 * SA);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float4 v = sw[j];
+                    fb[tj][4 * j] = v.x; fb[tj][4 * j + 1] = v.y; fb[tj][4 * j + 2] = v.z; fb[tj][4 * j + 3] = v.w;
+                }
             } else {
 #pragma unroll
-                for (int j = 0; j < 6; ++j) f.b[tj][j] = st[fragW + (pr * 12 + j) * SWT + tj * 32];
+                for (int j = 0; j < 16; ++j) fb[tj][j] = st[fragW + j * SWT + tj * 32];
             }
         }
     };
-    // Three LDS stages.  While slab s is consumed from stage s%3, slab s+1 already sits in the
-    // next stage (so its first operands can be fetched ahead of the barrier), slab s+2 moves from
-    // registers into the third stage at the start of slab s, and slab s+3 is requested from
-    // global memory right after.  One loop iteration is one chain pair: wait for its operands,
-    // issue the 12 MFMAs, request the operands of the next pair into the same registers (the
-    // matrix core has consumed them), then fold on the vector ALU while those reads are in flight.
-    const long nslab = (p.K + BK - 1) / BK;
-    float* rd = lds;
-    float* nx = lds + kStageFloats;
-    float* wr = lds + 2 * kStageFloats;
-    if (nslab > 0) { load_slab(0); commit(rd); }
-    if (nslab > 1) { load_slab(1); commit(nx); }
-    if (nslab > 2) load_slab(2);
+
+    // Three LDS stages and two register sets.  While group g is consumed (its operands already in
+    // registers), group g+1 sits complete in the next stage, group g+2 moves from registers into
+    // the third stage, and groups g+3 and g+4 are in flight from global memory (requested two
+    // groups before they are needed in registers, which covers the memory latency with one
+    // workgroup per CU).  The single barrier of a group, between its two tiles, orders the write of
+    // stage (g+2)%3 in group g after every read of it in group g-2 and before every read of it at
+    // the end of group g+1.
+    const long ngroup = (p.K + BK - 1) / BK;
+    float* nx = lds + kStageFloats;          // stage of group g+1
+    float* wr = lds + 2 * kStageFloats;      // stage receiving group g+2
+    float* fr = lds;                         // stage of group g (free for group g+3 afterwards)
+    if (ngroup > 0) { load_slab(0, ra0, rw0); commit(fr, ra0, rw0); }
+    if (ngroup > 1) { load_slab(1, ra1, rw1); commit(nx, ra1, rw1); }
+    if (ngroup > 2) load_slab(2, ra0, rw0);
+    if (ngroup > 3) load_slab(3, ra1, rw1);
     __syncthreads();
-    Frags f;
-    if (nslab > 0) read_frags(rd, 0, f);
-    const long npair = nslab * (BK / 12);
+    if (ngroup > 0) read_frags(fr);
+    // one group; (ra, rw) is the register set of the group's parity
+    auto group = [&](long g, float4* ra, float4* rw) {
+        if (g + 2 < ngroup) commit(wr, ra, rw);
+        if (g + 4 < ngroup) load_slab(g + 4, ra, rw);
+#pragma unroll
+        for (int tj = 0; tj < 2; ++tj) {
+            if (FAST) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) c0[tj] = TAO_MFMA(fa[i], fb[tj][i], c0[tj]);
+                if (tj == 1 && g + 1 < ngroup) read_frags(nx);
+            } else {
+                floatx16 x, z;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    // two chains of 4 k-steps from zero, interleaved
+                    floatx16 pc = TAO_MFMA(fa[4 * c], fb[tj][4 * c], zero);
+                    floatx16 qc = TAO_MFMA(fa[4 * c + 2], fb[tj][4 * c + 2], zero);
+                    pc = TAO_MFMA(fa[4 * c + 1], fb[tj][4 * c + 1], pc);
+                    qc = TAO_MFMA(fa[4 * c + 3], fb[tj][4 * c + 3], qc);
+                    // operands of the next group: requested once the last MFMA has been issued
+                    if (tj == 1 && c == 3 && g + 1 < ngroup) read_frags(nx);
+                    if (c == 0) {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) x[v] = pc[v] + qc[v];
+                    } else if (c == 1) {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) x[v] = x[v] + (pc[v] + qc[v]);
+                    } else if (c == 2) {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) z[v] = pc[v] + qc[v];
+                    } else {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) S[tj][v] += (double)(x[v] + (z[v] + (pc[v] + qc[v])));
+                    }
+                    // keep the chain pairs and their additions in program order, so that at most
+                    // two accumulators are live next to x and z
+                    if (c < 2) asm volatile("" : "+v"(x));
+                    if (c == 2) asm volatile("" : "+v"(z));
+                    if (c == 3) {
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(S[tj][v]));
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            if (tj == 0) __syncthreads();
+        }
+        float* t = fr; fr = nx; nx = wr; wr = t;
+    };
 #pragma unroll 1
-    for (long q = 0; q < npair; ++q) {
-        const int pr = (int)(q & 3);
-        const long s = q >> 2;
-        if (pr == 0) {
-            if (s + 2 < nslab) commit(wr);
-            if (s + 3 < nslab) load_slab(s + 3);
-        }
-        floatx16 u0[2], u1[2];
-        if (FAST) {
-#pragma unroll
-            for (int tj = 0; tj < 2; ++tj) {
-#pragma unroll
-                for (int j = 0; j < 6; ++j)
-                    c0[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[j], f.b[tj][j], c0[tj], 0, 0, 0);
-            }
-        } else {
-            // per tile: two 6-step chains from zero
-#pragma unroll
-            for (int tj = 0; tj < 2; ++tj) {
-                u0[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[0], f.b[tj][0], zero, 0, 0, 0);
-                u1[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[3], f.b[tj][3], zero, 0, 0, 0);
-                u0[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[1], f.b[tj][1], u0[tj], 0, 0, 0);
-                u1[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[4], f.b[tj][4], u1[tj], 0, 0, 0);
-                u0[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[2], f.b[tj][2], u0[tj], 0, 0, 0);
-                u1[tj] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.a[5], f.b[tj][5], u1[tj], 0, 0, 0);
-            }
-        }
-        // operands of the next pair (same slab, or the first pair of the next slab's stage)
-        if (q + 1 < npair) read_frags(pr == 3 ? nx : rd, pr == 3 ? 0 : pr + 1, f);
-        if (!FAST) {
-            // chains added in binary32, folded into binary64
-#pragma unroll
-            for (int tj = 0; tj < 2; ++tj) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) S[tj][v] += (double)(u0[tj][v] + u1[tj][v]);
-            }
-        }
-        if (pr == 3) {
-            __syncthreads();
-            float* t = rd; rd = nx; nx = wr; wr = t;
-        }
+    for (long g = 0; g < ngroup; g += 2) {
+        group(g, ra0, rw0);
+        if (g + 1 < ngroup) group(g + 1, ra1, rw1);
     }
 
     // epilogue: D[i][j] of a 32x32 tile sits in lane (j + 32*((i/4)%2)), register 4*(i/8) + i%4
@@ -321,7 +350,7 @@ int tao_bound_linear(const float* A, const float* W, const float* bias, float* t
     const double u = md.u;
     // lower rounding factor: (1-u)^r (1-2^-53)^f with r roundings in binary32, f in binary64
     const double r32 = fast ? (double)(K > 0 ? K : 1) : 7.0;
-    const double f64 = (double)(K / 12 + 2);
+    const double f64 = (double)(K / 32 + 2);
     if (!(r32 * u < 0.5)) return TAO_ERR_K_RANGE;
     const double lower = (1.0 - r32 * u) * (1.0 - f64 * 0x1p-53);   // <= (1-u)^r (1-2^-53)^f
     p.infl = widen(1.0 / (lower * (1.0 - 0x1p-52)));
