@@ -27,9 +27,9 @@
 // Tiling: 128x128 output tile per 512-thread workgroup: eight wavefronts (4 along
 // M, 2 along N), each owning two 32x32 MFMA tiles.  K advances in groups of 32;
 // |A| and |W| slabs travel global -> registers -> LDS with the sign bit cleared
-// on the way in, through three LDS stages with one barrier per group; the
-// operand registers of the next group are requested from LDS as soon as the last
-// MFMA of the current group has been issued.
+// on the way in, through four LDS stages with one barrier per two groups; the
+// operand registers of the next group are requested from LDS in three pieces
+// spread over the current group.
 #include <type_traits>
 #include "tao_device.hpp"
 #include "tao_host.hpp"
@@ -76,7 +76,7 @@ __device__ __forceinline__ float4 gload(const float* __restrict__ base, long r, 
 
 // One LDS stage holds a 128 x 32 slab of |A| and one of |W|.
 constexpr int kStageFloats = BM * SA + (BN * SA > BK * SWT ? BN * SA : BK * SWT);
-constexpr int kStages = 3;
+constexpr int kStages = 4;            // a power of two (stage index = group & 3)
 constexpr size_t kLinLdsBytes = (size_t)kStages * kStageFloats * sizeof(float);
 
 #define TAO_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0)
@@ -117,9 +117,11 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
 
     // two register sets: the slab requested during group g is written to LDS during group g+2
     float4 ra0[kVecPerThread], rw0[kVecPerThread], ra1[kVecPerThread], rw1[kVecPerThread];
-    auto load_slab = [&](long g, float4* ra, float4* rw) {
+    // CLEAN (a compile-time flag): the whole tile is interior and K is a multiple of the group
+    // size, so every group takes the buffer-load path and the loop holds no other load code.
+    auto load_slab = [&](auto clean, long g, float4* ra, float4* rw) __attribute__((always_inline)) {
         const long k0 = g * BK;
-        if (interior && k0 + BK <= p.K) {
+        if (decltype(clean)::value || (interior && k0 + BK <= p.K)) {
             // Buffer loads: descriptor (uniform base of this group's slab) in SGPRs, one 32-bit
             // per-thread offset, the vector index as a scalar offset.  Next to FP32 MFMA this
             // form is nearly free, while loads with a 64-bit per-lane address stall the SIMD.
@@ -142,7 +144,7 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
         }
     };
     // registers -> LDS stage, sign bits cleared
-    auto commit = [&](float* stage, const float4* ra, const float4* rw) {
+    auto commit = [&](float* stage, const float4* ra, const float4* rw) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < kVecPerThread; ++i) {
             *reinterpret_cast<float4*>(stage + stA + 64 * SA * i) = abs4(ra[i]);
@@ -173,56 +175,52 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
     const int fragA = (wm * 32 + r32) * SA + 16 * h;
     const int fragW = BM * SA + (TRANS_W ? (16 * h) * SWT + wn * 64 + r32 : (wn * 64 + r32) * SA + 16 * h);
     float fa[16], fb[2][16];
-    auto read_frags = [&](const float* st) {
+    auto read_a = [&](const float* st) __attribute__((always_inline)) {
         const float4* sa = reinterpret_cast<const float4*>(st + fragA);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const float4 v = sa[j];
             fa[4 * j] = v.x; fa[4 * j + 1] = v.y; fa[4 * j + 2] = v.z; fa[4 * j + 3] = v.w;
         }
+    };
+    auto read_b = [&](const float* st, int tj) __attribute__((always_inline)) {
+        if (!TRANS_W) {
+            const float4* sw = reinterpret_cast<const float4*>(st + fragW + tj * 32 * SA);
 #pragma unroll
-        for (int tj = 0; tj < 2; ++tj) {
-            if (!TRANS_W) {
-                const float4* sw = reinterpret_cast<const float4*>(st + fragW + tj * 32 * SA);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float4 v = sw[j];
-                    fb[tj][4 * j] = v.x; fb[tj][4 * j + 1] = v.y; fb[tj][4 * j + 2] = v.z; fb[tj][4 * j + 3] = v.w;
-                }
-            } else {
-#pragma unroll
-                for (int j = 0; j < 16; ++j) fb[tj][j] = st[fragW + j * SWT + tj * 32];
+            for (int j = 0; j < 4; ++j) {
+                const float4 v = sw[j];
+                fb[tj][4 * j] = v.x; fb[tj][4 * j + 1] = v.y; fb[tj][4 * j + 2] = v.z; fb[tj][4 * j + 3] = v.w;
             }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) fb[tj][j] = st[fragW + j * SWT + tj * 32];
         }
     };
 
-    // Three LDS stages and two register sets.  While group g is consumed (its operands already in
-    // registers), group g+1 sits complete in the next stage, group g+2 moves from registers into
-    // the third stage, and groups g+3 and g+4 are in flight from global memory (requested two
-    // groups before they are needed in registers, which covers the memory latency with one
-    // workgroup per CU).  The single barrier of a group, between its two tiles, orders the write of
-    // stage (g+2)%3 in group g after every read of it in group g-2 and before every read of it at
-    // the end of group g+1.
+    // Four LDS stages and two register sets.  Slab j (32 k-steps of both operands) is requested
+    // from global memory during group j-4, written to stage j%4 at the top of group j-2, and read
+    // into operand registers in three pieces: the W operands of tile 1 at the top of group j, the
+    // W operands of tile 0 in the middle of group j-1, the A operands at the end of group j-1.
+    // One barrier in the middle of every EVEN group is enough: between the write of a stage (top
+    // of group j-2) and its first read (middle of group j-1) lies the barrier of j-2 or of j-1,
+    // and between its last read as slab j-4 (top of group j-4) and that write lies the barrier of
+    // j-4 or of j-3.  Requests run two groups ahead of the registers' use, which covers the memory
+    // latency with a single workgroup per CU.
     const long ngroup = (p.K + BK - 1) / BK;
-    float* nx = lds + kStageFloats;          // stage of group g+1
-    float* wr = lds + 2 * kStageFloats;      // stage receiving group g+2
-    float* fr = lds;                         // stage of group g (free for group g+3 afterwards)
-    if (ngroup > 0) { load_slab(0, ra0, rw0); commit(fr, ra0, rw0); }
-    if (ngroup > 1) { load_slab(1, ra1, rw1); commit(nx, ra1, rw1); }
-    if (ngroup > 2) load_slab(2, ra0, rw0);
-    if (ngroup > 3) load_slab(3, ra1, rw1);
-    __syncthreads();
-    if (ngroup > 0) read_frags(fr);
+    auto stage = [&](long j) __attribute__((always_inline)) { return lds + (int)(j & (kStages - 1)) * kStageFloats; };
     // one group; (ra, rw) is the register set of the group's parity
-    auto group = [&](long g, float4* ra, float4* rw) {
-        if (g + 2 < ngroup) commit(wr, ra, rw);
-        if (g + 4 < ngroup) load_slab(g + 4, ra, rw);
+    auto group = [&](auto clean, auto steady, long g, float4* ra, float4* rw, bool even) __attribute__((always_inline)) {
+        // steady (compile time): groups g+1 .. g+4 exist, so nothing below is conditional
+        constexpr bool ST = decltype(steady)::value;
+        if (ST || g + 2 < ngroup) commit(stage(g + 2), ra, rw);
+        if (ST || g + 4 < ngroup) load_slab(clean, g + 4, ra, rw);
+        read_b(stage(g), 1);
 #pragma unroll
         for (int tj = 0; tj < 2; ++tj) {
             if (FAST) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) c0[tj] = TAO_MFMA(fa[i], fb[tj][i], c0[tj]);
-                if (tj == 1 && g + 1 < ngroup) read_frags(nx);
+                if (tj == 1 && (ST || g + 1 < ngroup)) read_a(stage(g + 1));
             } else {
                 floatx16 x, z;
 #pragma unroll
@@ -232,8 +230,8 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
                     floatx16 qc = TAO_MFMA(fa[4 * c + 2], fb[tj][4 * c + 2], zero);
                     pc = TAO_MFMA(fa[4 * c + 1], fb[tj][4 * c + 1], pc);
                     qc = TAO_MFMA(fa[4 * c + 3], fb[tj][4 * c + 3], qc);
-                    // operands of the next group: requested once the last MFMA has been issued
-                    if (tj == 1 && c == 3 && g + 1 < ngroup) read_frags(nx);
+                    // A operands of the next group: requested once the last MFMA has been issued
+                    if (tj == 1 && c == 3 && (ST || g + 1 < ngroup)) read_a(stage(g + 1));
                     if (c == 0) {
 #pragma unroll
                         for (int v = 0; v < 16; ++v) x[v] = pc[v] + qc[v];
@@ -258,15 +256,51 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            if (tj == 0) __syncthreads();
+            if (tj == 0) {
+                if (even) __syncthreads();
+                // W operands of tile 0 of the next group (its registers are free now)
+                if (ST || g + 1 < ngroup) read_b(stage(g + 1), 0);
+            }
         }
-        float* t = fr; fr = nx; nx = wr; wr = t;
     };
+    // Two copies of the whole pipeline: with the edge-handling loads in the same control flow
+    // the compiler's wait-count bookkeeping turns conservative and waits for the youngest
+    // requests as well, which would expose the memory latency in every group.
+    auto pipeline = [&](auto clean) __attribute__((always_inline)) {
+        long g = 0;
+        if (ngroup >= 6) {
+            // Steady state: every request, LDS write and LDS read is unconditional, from the
+            // prologue on, so the wait counts the compiler derives are exact (one conditional
+            // request on any path into the loop makes it wait for all outstanding requests,
+            // which halves the distance between a request and its use).
+            load_slab(clean, 0, ra0, rw0); commit(stage(0), ra0, rw0);
+            load_slab(clean, 1, ra1, rw1); commit(stage(1), ra1, rw1);
+            load_slab(clean, 2, ra0, rw0);
+            load_slab(clean, 3, ra1, rw1);
+            __syncthreads();
+            read_a(stage(0)); read_b(stage(0), 0);
 #pragma unroll 1
-    for (long g = 0; g < ngroup; g += 2) {
-        group(g, ra0, rw0);
-        if (g + 1 < ngroup) group(g + 1, ra1, rw1);
-    }
+            for (; g + 5 < ngroup; g += 2) {
+                group(clean, std::true_type(), g, ra0, rw0, true);
+                group(clean, std::true_type(), g + 1, ra1, rw1, false);
+            }
+        } else {
+            if (ngroup > 0) { load_slab(clean, 0, ra0, rw0); commit(stage(0), ra0, rw0); }
+            if (ngroup > 1) { load_slab(clean, 1, ra1, rw1); commit(stage(1), ra1, rw1); }
+            if (ngroup > 2) load_slab(clean, 2, ra0, rw0);
+            if (ngroup > 3) load_slab(clean, 3, ra1, rw1);
+            __syncthreads();
+            if (ngroup > 0) { read_a(stage(0)); read_b(stage(0), 0); }
+        }
+        // the last groups (all of them when there are fewer than six): conditional copy
+#pragma unroll 1
+        for (; g < ngroup; g += 2) {
+            group(clean, std::false_type(), g, ra0, rw0, true);
+            if (g + 1 < ngroup) group(clean, std::false_type(), g + 1, ra1, rw1, false);
+        }
+    };
+    if (interior && p.K % BK == 0) pipeline(std::true_type());
+    else pipeline(std::false_type());
 
     // epilogue: D[i][j] of a 32x32 tile sits in lane (j + 32*((i/4)%2)), register 4*(i/8) + i%4
 #pragma unroll
