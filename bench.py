@@ -27,6 +27,21 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_FP32_MFMA_TFLOPS = 157.3
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per launch of the dominant kernel, measured offline with two rocprofv3 counter passes
+# over this same command (FETCH_SIZE, WRITE_SIZE, scaled by a copy kernel); the summary is kept
+# as text next to the other profiles and only its one figure is read here.
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "bench_c3_hbm_traffic.md")
+
+
+def measured_traffic(kernel):
+    """Bytes per launch recorded in the committed counter summary, or None."""
+    import re
+    try:
+        text = open(TRAFFIC_SUMMARY).read()
+    except OSError:
+        return None
+    m = re.search(r"^%s traffic bytes per launch: (\d+)$" % re.escape(kernel), text, re.M)
+    return int(m.group(1)) if m else None
 
 _NORM = {"layernorm": 0, "rmsnorm": 1, "bn_affine": 2, "sum": 3, "mean": 4}
 _ACT = {"gelu": 0, "silu": 1, "mul": 2, "add": 3, "relu": 4}
@@ -51,8 +66,10 @@ class PlannedOp:
             A, W = a["A"], a["W"]
             K = A.shape[-1]
             self.flops = 2.0 * self.n * K
+            self.min_bytes = 4.0 * (A.numel() + W.numel() + self.n)
         else:
             self.flops = 0.0
+            self.min_bytes = 0.0
         self.bound_events, self.check_events = [], []
 
     def bound(self):
@@ -191,7 +208,9 @@ def main():
     lin_flops = sum(p.flops * len(p.bound_events) for p in lin)
     achieved = lin_flops / (lin_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "absgemm_bound", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "traffic": None,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                "traffic": measured_traffic("absgemm_bound") if args.scale == 1 else None,
+                "compulsory_bytes_per_launch": sum(p.min_bytes for p in lin) / len(lin),
                 "launches": lin_launches, "avg_launch_ms": lin_ms / lin_launches,
                 "flop_per_launch": lin_flops / lin_launches,
                 "share_of_step": lin_ms / args.steps / ms_per_step}
