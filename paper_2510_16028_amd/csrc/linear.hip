@@ -38,13 +38,25 @@ namespace tao {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int BK = 32;               // k-steps per group
+constexpr int BN = 128;              // output columns per workgroup (both tile shapes)
 constexpr int SA = BK + 4;          // LDS row stride (floats) of a k-contiguous slab: 16-byte reads
                                     // of 16 consecutive rows fall in distinct 16-byte bank groups
 constexpr int SWT = BN + 2;         // LDS row stride of a [k][n] slab (trans_w): the two k-halves
                                     // of a wavefront (16 rows apart) read disjoint bank halves
-constexpr int kLinThreads = 512;    // 8 wavefronts: 4 along M x 2 along N, each 32 x 64 outputs
-constexpr int kVecPerThread = (BM * BK / 4) / kLinThreads;   // 2 float4 per operand per group
+constexpr int kLinThreads = 512;    // 8 wavefronts
+// Two tile shapes, chosen by the host: WM = 4 wavefronts along M x 2 along N, each owning two
+// 32x32 MFMA tiles (128 x 128 outputs per workgroup), or, for problems with too few such tiles to
+// fill the chip, WM = 2 x 4 wavefronts of one MFMA tile each (64 x 128 outputs per workgroup).
+template <int WM> struct Shape {
+    static constexpr int kWN = 8 / WM;                 // wavefronts along N
+    static constexpr int kTN = BN / (32 * kWN);        // MFMA tiles per wavefront (along N)
+    static constexpr int kBM = 32 * WM;
+    static constexpr int kVecA = kBM * BK / 4 / kLinThreads;   // float4 per thread and group
+    static constexpr int kVecW = BN * BK / 4 / kLinThreads;
+    // one LDS stage holds a kBM x 32 slab of |A| and a 128 x 32 slab of |W|
+    static constexpr int kStageFloats = kBM * SA + (BN * SA > BK * SWT ? BN * SA : BK * SWT);
+};
 
 struct LinArgs {
     const float* A; const float* W; const float* bias; float* tau;
@@ -74,20 +86,20 @@ __device__ __forceinline__ float4 gload(const float* __restrict__ base, long r, 
     return v;
 }
 
-// One LDS stage holds a 128 x 32 slab of |A| and one of |W|.
-constexpr int kStageFloats = BM * SA + (BN * SA > BK * SWT ? BN * SA : BK * SWT);
 constexpr int kStages = 4;            // a power of two (stage index = group & 3)
-constexpr size_t kLinLdsBytes = (size_t)kStages * kStageFloats * sizeof(float);
 
 #define TAO_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0)
 
-template <bool TRANS_W, bool FAST>
+template <bool TRANS_W, bool FAST, int WM>
 __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
     extern __shared__ __attribute__((aligned(16))) float lds[];
+    constexpr int BM = Shape<WM>::kBM, WN = Shape<WM>::kWN, TN = Shape<WM>::kTN;
+    constexpr int kVecA = Shape<WM>::kVecA, kVecW = Shape<WM>::kVecW;
+    constexpr int kStageFloats = Shape<WM>::kStageFloats;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN, wn = wave % WN;
     const int r32 = lane & 31, h = lane >> 5;
     const long m0 = (long)blockIdx.y * BM, n0 = (long)blockIdx.x * BN;
     const float* __restrict__ A = p.A + (long)blockIdx.z * p.strideA;
@@ -116,7 +128,7 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
     const long spanW = TRANS_W ? ((long)(BK - 1) * p.ldw + BN) * 4 : ((long)(BN - 1) * p.ldw + BK) * 4;
 
     // two register sets: the slab requested during group g is written to LDS during group g+2
-    float4 ra0[kVecPerThread], rw0[kVecPerThread], ra1[kVecPerThread], rw1[kVecPerThread];
+    float4 ra0[kVecA], rw0[kVecW], ra1[kVecA], rw1[kVecW];
     // CLEAN (a compile-time flag): the whole tile is interior and K is a multiple of the group
     // size, so every group takes the buffer-load path and the loop holds no other load code.
     auto load_slab = [&](auto clean, long g, float4* ra, float4* rw) __attribute__((always_inline)) {
@@ -130,24 +142,27 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
             const __amdgpu_buffer_rsrc_t dw = __builtin_amdgcn_make_buffer_rsrc(
                 const_cast<char*>(baseW + g * slabW), 0, (int)spanW, 0x00020000);
 #pragma unroll
-            for (int i = 0; i < kVecPerThread; ++i) {
+            for (int i = 0; i < kVecA; ++i)
                 ra[i] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(da, (int)offA, (int)(strideAi * i), 0));
+#pragma unroll
+            for (int i = 0; i < kVecW; ++i)
                 rw[i] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(dw, (int)offW, (int)(strideWi * i), 0));
-            }
         } else {
 #pragma unroll
-            for (int i = 0; i < kVecPerThread; ++i) {
+            for (int i = 0; i < kVecA; ++i)
                 ra[i] = gload(A, m0 + ld_row + 64 * i, p.M, p.lda, k0 + ld_k, p.K, p.vecA);
+#pragma unroll
+            for (int i = 0; i < kVecW; ++i)
                 rw[i] = TRANS_W ? gload(W, k0 + lt_kr + 16 * i, p.K, p.ldw, n0 + lt_n, p.N, p.vecW)
                                 : gload(W, n0 + ld_row + 64 * i, p.N, p.ldw, k0 + ld_k, p.K, p.vecW);
-            }
         }
     };
     // registers -> LDS stage, sign bits cleared
     auto commit = [&](float* stage, const float4* ra, const float4* rw) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < kVecPerThread; ++i) {
-            *reinterpret_cast<float4*>(stage + stA + 64 * SA * i) = abs4(ra[i]);
+        for (int i = 0; i < kVecA; ++i) *reinterpret_cast<float4*>(stage + stA + 64 * SA * i) = abs4(ra[i]);
+#pragma unroll
+        for (int i = 0; i < kVecW; ++i) {
             const float4 w = abs4(rw[i]);
             if (!TRANS_W) {
                 *reinterpret_cast<float4*>(stage + stW + 64 * SA * i) = w;
@@ -159,10 +174,10 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
     };
 
     // S: binary64 running sums (tight mode); c0: the single FP32 chain (fast mode)
-    double S[2][16];
-    floatx16 c0[2];
+    double S[TN][16];
+    floatx16 c0[TN];
 #pragma unroll
-    for (int tj = 0; tj < 2; ++tj) {
+    for (int tj = 0; tj < TN; ++tj) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) { S[tj][v] = 0.0; c0[tj][v] = 0.f; }
     }
@@ -173,7 +188,9 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
     // Operand registers of one group: lane (r32, h) holds k = 16h .. 16h+15 of its A row and of
     // its W row in each tile; MFMA number i of the group multiplies element i of both.
     const int fragA = (wm * 32 + r32) * SA + 16 * h;
-    const int fragW = BM * SA + (TRANS_W ? (16 * h) * SWT + wn * 64 + r32 : (wn * 64 + r32) * SA + 16 * h);
+    const int fragW = BM * SA + (TRANS_W ? (16 * h) * SWT + wn * 32 * TN + r32 : (wn * 32 * TN + r32) * SA + 16 * h);
+    // fb[j]: with two tiles per wavefront the W operands of tile j; with one tile the two
+    // buffers alternate between groups (j = parity of the group)
     float fa[16], fb[2][16];
     auto read_a = [&](const float* st) __attribute__((always_inline)) {
         const float4* sa = reinterpret_cast<const float4*>(st + fragA);
@@ -183,17 +200,18 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
             fa[4 * j] = v.x; fa[4 * j + 1] = v.y; fa[4 * j + 2] = v.z; fa[4 * j + 3] = v.w;
         }
     };
-    auto read_b = [&](const float* st, int tj) __attribute__((always_inline)) {
+    auto read_b = [&](const float* st, int buf) __attribute__((always_inline)) {
+        const int tj = TN == 2 ? buf : 0;       // tile whose operands are read
         if (!TRANS_W) {
             const float4* sw = reinterpret_cast<const float4*>(st + fragW + tj * 32 * SA);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float4 v = sw[j];
-                fb[tj][4 * j] = v.x; fb[tj][4 * j + 1] = v.y; fb[tj][4 * j + 2] = v.z; fb[tj][4 * j + 3] = v.w;
+                fb[buf][4 * j] = v.x; fb[buf][4 * j + 1] = v.y; fb[buf][4 * j + 2] = v.z; fb[buf][4 * j + 3] = v.w;
             }
         } else {
 #pragma unroll
-            for (int j = 0; j < 16; ++j) fb[tj][j] = st[fragW + j * SWT + tj * 32];
+            for (int j = 0; j < 16; ++j) fb[buf][j] = st[fragW + j * SWT + tj * 32];
         }
     };
 
@@ -205,62 +223,75 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
     // of group j-2) and its first read (middle of group j-1) lies the barrier of j-2 or of j-1,
     // and between its last read as slab j-4 (top of group j-4) and that write lies the barrier of
     // j-4 or of j-3.  Requests run two groups ahead of the registers' use, which covers the memory
-    // latency with a single workgroup per CU.
+    // latency with a single workgroup per CU.  With one tile per wavefront (64-row workgroup
+    // tiles) the W operands of group j are read at the top of group j-1 into the buffer the
+    // current group does not use, and the barrier sits at the top of the even groups, right
+    // after the LDS write; the same two arguments hold.
     const long ngroup = (p.K + BK - 1) / BK;
     auto stage = [&](long j) __attribute__((always_inline)) { return lds + (int)(j & (kStages - 1)) * kStageFloats; };
-    // one group; (ra, rw) is the register set of the group's parity
-    auto group = [&](auto clean, auto steady, long g, float4* ra, float4* rw, bool even) __attribute__((always_inline)) {
+    // the MFMA / vector-ALU work of one 32x32 tile over one group: accumulator `acc`, W operands
+    // from fb[buf]; `last`: the group's last tile, which requests the next group's A operands
+    // as soon as its last MFMA has been issued
+    auto tile = [&](int acc, int buf, bool last, bool have_next, long g) __attribute__((always_inline)) {
+        if (FAST) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) c0[acc] = TAO_MFMA(fa[i], fb[buf][i], c0[acc]);
+            if (last && have_next) read_a(stage(g + 1));
+        } else {
+            floatx16 x, z;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                // two chains of 4 k-steps from zero, interleaved
+                floatx16 pc = TAO_MFMA(fa[4 * c], fb[buf][4 * c], zero);
+                floatx16 qc = TAO_MFMA(fa[4 * c + 2], fb[buf][4 * c + 2], zero);
+                pc = TAO_MFMA(fa[4 * c + 1], fb[buf][4 * c + 1], pc);
+                qc = TAO_MFMA(fa[4 * c + 3], fb[buf][4 * c + 3], qc);
+                if (last && c == 3 && have_next) read_a(stage(g + 1));
+                if (c == 0) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) x[v] = pc[v] + qc[v];
+                } else if (c == 1) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) x[v] = x[v] + (pc[v] + qc[v]);
+                } else if (c == 2) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) z[v] = pc[v] + qc[v];
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) S[acc][v] += (double)(x[v] + (z[v] + (pc[v] + qc[v])));
+                }
+                // keep the chain pairs and their additions in program order, so that at most
+                // two accumulators are live next to x and z
+                if (c < 2) asm volatile("" : "+v"(x));
+                if (c == 2) asm volatile("" : "+v"(z));
+                if (c == 3) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(S[acc][v]));
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+    // one group; (ra, rw) is the register set of the group's parity (`even`, compile time)
+    auto group = [&](auto clean, auto steady, auto even_t, long g, float4* ra, float4* rw) __attribute__((always_inline)) {
         // steady (compile time): groups g+1 .. g+4 exist, so nothing below is conditional
         constexpr bool ST = decltype(steady)::value;
+        constexpr bool even = decltype(even_t)::value;
+        const bool have_next = ST || g + 1 < ngroup;
         if (ST || g + 2 < ngroup) commit(stage(g + 2), ra, rw);
         if (ST || g + 4 < ngroup) load_slab(clean, g + 4, ra, rw);
-        read_b(stage(g), 1);
-#pragma unroll
-        for (int tj = 0; tj < 2; ++tj) {
-            if (FAST) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) c0[tj] = TAO_MFMA(fa[i], fb[tj][i], c0[tj]);
-                if (tj == 1 && (ST || g + 1 < ngroup)) read_a(stage(g + 1));
-            } else {
-                floatx16 x, z;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    // two chains of 4 k-steps from zero, interleaved
-                    floatx16 pc = TAO_MFMA(fa[4 * c], fb[tj][4 * c], zero);
-                    floatx16 qc = TAO_MFMA(fa[4 * c + 2], fb[tj][4 * c + 2], zero);
-                    pc = TAO_MFMA(fa[4 * c + 1], fb[tj][4 * c + 1], pc);
-                    qc = TAO_MFMA(fa[4 * c + 3], fb[tj][4 * c + 3], qc);
-                    // A operands of the next group: requested once the last MFMA has been issued
-                    if (tj == 1 && c == 3 && (ST || g + 1 < ngroup)) read_a(stage(g + 1));
-                    if (c == 0) {
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) x[v] = pc[v] + qc[v];
-                    } else if (c == 1) {
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) x[v] = x[v] + (pc[v] + qc[v]);
-                    } else if (c == 2) {
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) z[v] = pc[v] + qc[v];
-                    } else {
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) S[tj][v] += (double)(x[v] + (z[v] + (pc[v] + qc[v])));
-                    }
-                    // keep the chain pairs and their additions in program order, so that at most
-                    // two accumulators are live next to x and z
-                    if (c < 2) asm volatile("" : "+v"(x));
-                    if (c == 2) asm volatile("" : "+v"(z));
-                    if (c == 3) {
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) asm volatile("" : "+v"(S[tj][v]));
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
-            if (tj == 0) {
-                if (even) __syncthreads();
-                // W operands of tile 0 of the next group (its registers are free now)
-                if (ST || g + 1 < ngroup) read_b(stage(g + 1), 0);
-            }
+        if (TN == 2) {
+            read_b(stage(g), 1);                          // W operands of this group's tile 1
+            tile(0, 0, false, have_next, g);
+            if (even) __syncthreads();
+            if (have_next) read_b(stage(g + 1), 0);       // tile 0 of the next group (registers free now)
+            tile(1, 1, true, have_next, g);
+        } else {
+            // one tile per wavefront: the barrier sits at the top of the even groups (after the
+            // LDS write), and the W operands of the next group go to the other buffer
+            if (even) __syncthreads();
+            if (have_next) read_b(stage(g + 1), even ? 1 : 0);
+            tile(0, even ? 0 : 1, true, have_next, g);
         }
     };
     // Two copies of the whole pipeline: with the edge-handling loads in the same control flow
@@ -273,20 +304,22 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
             // prologue on, so the wait counts the compiler derives are exact (one conditional
             // request on any path into the loop makes it wait for all outstanding requests,
             // which halves the distance between a request and its use).
-            load_slab(clean, 0, ra0, rw0); commit(stage(0), ra0, rw0);
-            load_slab(clean, 1, ra1, rw1); commit(stage(1), ra1, rw1);
+            load_slab(clean, 0, ra0, rw0); load_slab(clean, 1, ra1, rw1);     // one round trip for both
+            commit(stage(0), ra0, rw0); commit(stage(1), ra1, rw1);
             load_slab(clean, 2, ra0, rw0);
             load_slab(clean, 3, ra1, rw1);
             __syncthreads();
             read_a(stage(0)); read_b(stage(0), 0);
 #pragma unroll 1
             for (; g + 5 < ngroup; g += 2) {
-                group(clean, std::true_type(), g, ra0, rw0, true);
-                group(clean, std::true_type(), g + 1, ra1, rw1, false);
+                group(clean, std::true_type(), std::true_type(), g, ra0, rw0);
+                group(clean, std::true_type(), std::false_type(), g + 1, ra1, rw1);
             }
         } else {
-            if (ngroup > 0) { load_slab(clean, 0, ra0, rw0); commit(stage(0), ra0, rw0); }
-            if (ngroup > 1) { load_slab(clean, 1, ra1, rw1); commit(stage(1), ra1, rw1); }
+            if (ngroup > 0) load_slab(clean, 0, ra0, rw0);
+            if (ngroup > 1) load_slab(clean, 1, ra1, rw1);
+            if (ngroup > 0) commit(stage(0), ra0, rw0);
+            if (ngroup > 1) commit(stage(1), ra1, rw1);
             if (ngroup > 2) load_slab(clean, 2, ra0, rw0);
             if (ngroup > 3) load_slab(clean, 3, ra1, rw1);
             __syncthreads();
@@ -295,8 +328,8 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
         // the last groups (all of them when there are fewer than six): conditional copy
 #pragma unroll 1
         for (; g < ngroup; g += 2) {
-            group(clean, std::false_type(), g, ra0, rw0, true);
-            if (g + 1 < ngroup) group(clean, std::false_type(), g + 1, ra1, rw1, false);
+            group(clean, std::false_type(), std::true_type(), g, ra0, rw0);
+            if (g + 1 < ngroup) group(clean, std::false_type(), std::false_type(), g + 1, ra1, rw1);
         }
     };
     if (interior && p.K % BK == 0) pipeline(std::true_type());
@@ -304,8 +337,8 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
 
     // epilogue: D[i][j] of a 32x32 tile sits in lane (j + 32*((i/4)%2)), register 4*(i/8) + i%4
 #pragma unroll
-    for (int tj = 0; tj < 2; ++tj) {
-        const long col = n0 + wn * 64 + tj * 32 + r32;
+    for (int tj = 0; tj < TN; ++tj) {
+        const long col = n0 + (wn * TN + tj) * 32 + r32;
         const double ab = (p.bias && col < p.N) ? fabs((double)p.bias[col]) : 0.0;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -319,17 +352,23 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
     }
 }
 
-template <bool TRANS_W, bool FAST>
+template <bool TRANS_W, bool FAST, int WM>
 static hipError_t launch_absgemm(dim3 grid, hipStream_t st, const LinArgs& p) {
+    constexpr size_t lds_bytes = (size_t)kStages * Shape<WM>::kStageFloats * sizeof(float);
     static bool configured = false;      // raise the dynamic LDS limit once per instantiation
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_bound<TRANS_W, FAST>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLinLdsBytes);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_bound<TRANS_W, FAST, WM>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((absgemm_bound<TRANS_W, FAST>), grid, dim3(kLinThreads), kLinLdsBytes, st, p);
+    hipLaunchKernelGGL((absgemm_bound<TRANS_W, FAST, WM>), grid, dim3(kLinThreads), lds_bytes, st, p);
     return hipSuccess;
+}
+template <int WM>
+static hipError_t launch_shape(bool trans_w, bool fast, dim3 grid, hipStream_t st, const LinArgs& p) {
+    if (trans_w) return fast ? launch_absgemm<true, true, WM>(grid, st, p) : launch_absgemm<true, false, WM>(grid, st, p);
+    return fast ? launch_absgemm<false, true, WM>(grid, st, p) : launch_absgemm<false, false, WM>(grid, st, p);
 }
 
 // ---- matrix-core self test ----------------------------------------------------------------
@@ -375,7 +414,7 @@ int tao_bound_linear(const float* A, const float* W, const float* bias, float* t
     p.vecA = aligned(A, 16) && (lda % 4 == 0) && (strideA % 4 == 0);
     p.vecW = aligned(W, 16) && (ldw % 4 == 0) && (strideW % 4 == 0);
     {   // byte offsets inside one slab must fit in 32 bits for the unguarded load path
-        const long spanA = ((long)(BM - 1) * lda + BK) * 4;
+        const long spanA = ((long)(128 - 1) * lda + BK) * 4;
         const long spanW = trans_w ? ((long)(BK - 1) * ldw + BN) * 4 : ((long)(BN - 1) * ldw + BK) * 4;
         p.fast_ok = p.vecA && p.vecW && (K % 4 == 0) && spanA < (1L << 31) && spanW < (1L << 31);
     }
@@ -390,12 +429,17 @@ int tao_bound_linear(const float* A, const float* W, const float* bias, float* t
     p.infl = widen(1.0 / (lower * (1.0 - 0x1p-52)));
     p.uflow = (md.flags & TAO_FLAG_UNDERFLOW_TERMS) ? (double)Kp * 0x1p-149 : 0.0;
 
-    dim3 grid((unsigned)((N + BN - 1) / BN), (unsigned)((M + BM - 1) / BM), (unsigned)batch);
+    // 128-row tiles unless they would leave a quarter or more of the 256 CUs without a
+    // workgroup while 64-row tiles would not
+    const long tiles_n = (N + BN - 1) / BN;
+    const long tiles128 = tiles_n * ((M + 127) / 128) * batch;
+    const bool small = tiles128 <= 192 && M > 64;
+    const long bm = small ? 64 : 128;
+    dim3 grid((unsigned)tiles_n, (unsigned)((M + bm - 1) / bm), (unsigned)batch);
     if (grid.y > 65535u) return TAO_ERR_SHAPE;
     hipStream_t st = (hipStream_t)stream;
-    hipError_t e;
-    if (trans_w) e = fast ? launch_absgemm<true, true>(grid, st, p) : launch_absgemm<true, false>(grid, st, p);
-    else         e = fast ? launch_absgemm<false, true>(grid, st, p) : launch_absgemm<false, false>(grid, st, p);
+    const hipError_t e = small ? launch_shape<2>(trans_w != 0, fast, grid, st, p)
+                               : launch_shape<4>(trans_w != 0, fast, grid, st, p);
     if (e != hipSuccess) { g_last_hip_error = (int)e; return TAO_ERR_LAUNCH; }
     return launch_status();
 }
