@@ -65,7 +65,7 @@ __device__ __forceinline__ float act_one(float x, float y, const ActConsts& k) {
     } else {
         return 0.f;
     }
-    return up32(t * kGuard);
+    return up32g(t);
 }
 
 template <int KIND>
@@ -77,12 +77,12 @@ __global__ __launch_bounds__(256) void act_bound(const float* __restrict__ x, co
     const long t0 = (long)blockIdx.x * blockDim.x + threadIdx.x;
     for (long i = t0; i < nvec; i += stride) {
         float4 X = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (NEEDS_X) X = reinterpret_cast<const float4*>(x)[i];
-        const float4 Y = reinterpret_cast<const float4*>(y)[i];
+        if (NEEDS_X) X = ntload4(reinterpret_cast<const float4*>(x) + i);
+        const float4 Y = ntload4(reinterpret_cast<const float4*>(y) + i);
         float4 T;
         T.x = act_one<KIND>(X.x, Y.x, k); T.y = act_one<KIND>(X.y, Y.y, k);
         T.z = act_one<KIND>(X.z, Y.z, k); T.w = act_one<KIND>(X.w, Y.w, k);
-        reinterpret_cast<float4*>(tau)[i] = T;
+        ntstore4(reinterpret_cast<float4*>(tau) + i, T);
     }
     for (long i = (nvec << 2) + t0; i < n; i += stride)
         tau[i] = act_one<KIND>(NEEDS_X ? x[i] : 0.f, y[i], k);
@@ -117,9 +117,11 @@ int tao_bound_act(int kind, const float* x, const float* x2, const float* y_ref,
     k.silu_f = widen(om * inv1mu + u);
     k.a_f = widen(kTwoRsqrtPiUp * (1.0 + 4.0 * u));
     const int vec_ok = aligned(y_ref, 16) && aligned(tau, 16) && (kind != TAO_ACT_GELU_ERF || aligned(x, 16));
+    // four 256-thread workgroups per CU, grid-stride: every wavefront of the chip walks one
+    // contiguous moving window of memory (the best of the launch shapes measured)
     long blocks = (n / 4 + 255) / 256;
     if (blocks < 1) blocks = 1;
-    if (blocks > 256L * 16) blocks = 256L * 16;
+    if (blocks > 256L * 4) blocks = 256L * 4;
     hipStream_t st = (hipStream_t)stream;
     dim3 grid((unsigned)blocks), blk(256);
     switch (kind) {

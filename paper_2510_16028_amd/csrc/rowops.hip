@@ -87,8 +87,8 @@ __global__ __launch_bounds__(kRowThreads) void softmax_bound(
     float4 xv[CACHED ? V : 1], yv[CACHED ? V : 1];
     float m = -INFINITY; int bad = 0;
     for (int v = 0; v < nv; ++v) {
-        const float4 X = load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, -INFINITY);
-        if (CACHED) { xv[v] = X; yv[v] = load4(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f); }
+        const float4 X = load4<CACHED>(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, -INFINITY);
+        if (CACHED) { xv[v] = X; yv[v] = load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f); }
         const float e[4] = {X.x, X.y, X.z, X.w};
 #pragma unroll
         for (int c = 0; c < 4; ++c) { bad |= (e[c] != e[c]) | (e[c] == INFINITY); m = fmaxf(m, e[c]); }
@@ -100,52 +100,56 @@ __global__ __launch_bounds__(kRowThreads) void softmax_bound(
     const double uam = k.u * fabs((double)m);
     const double ce_inv = k.ce_u * k.inv1mce;
     double acc[2] = {0.0, 0.0};                                  // sum q, sum rho q
-    double qv[CACHED ? V * 4 : 1], rv[CACHED ? V * 4 : 1];       // q and rho of the cached elements
+    // q and rho of the cached elements are kept for the last pass only while registers allow
+    // (a wavefront-wide row of 2048 columns recomputes them: six operations per element)
+    constexpr bool KEEP = CACHED && V <= 4;
+    double qv[KEEP ? V * 4 : 1], rv[KEEP ? V * 4 : 1];
+    // masked entries (x = -inf) take |x| = 0 and y = 0: then q = 0 drops them from both sums
+    // and from tau without a select on binary64 values
+    auto q_rho = [&](float xe, float ye, double& q, double& rho) __attribute__((always_inline)) {
+        const bool masked = xe == -INFINITY;
+        const double ax = (double)(masked ? 0.f : fabsf(xe));
+        const double a = fma(k.u, ax, uam);
+        rho = fma(fma(a, a, a), k.inv1mce, ce_inv);
+        q = (double)(masked ? 0.f : fabsf(ye)) * k.inv1mu;
+    };
     for (int v = 0; v < nv; ++v) {
         const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, -INFINITY);
         const float4 Y = CACHED ? yv[v] : load4(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
         const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w};
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const bool masked = xe[c] == -INFINITY;
-            const double a = fma(k.u, fabs((double)xe[c]), uam);
-            const double rho = masked ? 0.0 : fma(fma(a, a, a), k.inv1mce, ce_inv);
-            const double q = masked ? 0.0 : fabs((double)ye[c]) * k.inv1mu;
+            double q, rho;
+            q_rho(xe[c], ye[c], q, rho);
             acc[0] += q; acc[1] = fma(rho, q, acc[1]);
-            if (CACHED) { qv[v * 4 + c] = q; rv[v * 4 + c] = rho; }
+            if (KEEP) { qv[v * 4 + c] = q; rv[v * 4 + c] = rho; }
         }
     }
     group_sum<TPR>(acc, 2, smem);
     const double sigma = k.G * acc[0] + (1.0 + k.G) * acc[1];
     if (!(sigma < 1.0)) bad = 1;
+    // tau = q rho + q (1+rho) sfac + u y  with y = q (1-u) <= q:
+    //     = q (rho (1 + sfac) + (sfac + u)); a row without a finite bound gets NaN through the
+    // two row constants (0 * NaN = NaN also covers its masked entries)
     const double sfac = sigma / (1.0 - sigma);
-    // tau = q rho + q (1+rho) sfac + u y = q (rho + (1+rho) sfac + u/inv1mu'), y = q / inv1mu;
-    // the constant uses u (not u/inv1mu): slightly larger, still within the tolerance
-    const double cy = k.u;
+    const double w1 = bad ? NAN : 1.0 + sfac;
+    const double w0 = bad ? NAN : sfac + k.u;
     for (int v = 0; v < nv; ++v) {
         float4 X = make_float4(0.f, 0.f, 0.f, 0.f), Y = X;
         if (!CACHED) {
             X = load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, -INFINITY);
             Y = load4(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        } else if (!KEEP) {
+            X = xv[v]; Y = yv[v];
         }
         const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w};
         float te[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            double q, rho; bool masked;
-            if (CACHED) {
-                q = qv[v * 4 + c]; rho = rv[v * 4 + c];
-                const float xc = c == 0 ? xv[v].x : c == 1 ? xv[v].y : c == 2 ? xv[v].z : xv[v].w;
-                masked = xc == -INFINITY;
-            } else {
-                masked = xe[c] == -INFINITY;
-                const double a = fma(k.u, fabs((double)xe[c]), uam);
-                rho = fma(fma(a, a, a), k.inv1mce, ce_inv);
-                q = fabs((double)ye[c]) * k.inv1mu;
-            }
-            const double w = fma(rho, sfac, sfac) + rho + cy;
-            const double t = q * w;
-            te[c] = bad ? NAN : (masked ? 0.f : up32(t * kGuard));
+            double q, rho;
+            if (KEEP) { q = qv[v * 4 + c]; rho = rv[v * 4 + c]; }
+            else q_rho(xe[c], ye[c], q, rho);
+            te[c] = up32g(q * fma(rho, w1, w0));
         }
         store4(tau + roff, TAO_VEC_INDEX(v), limit, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
     }
@@ -167,6 +171,16 @@ __device__ __forceinline__ bool rsqrt_tail(double vstar, double E_v, const RowCo
 }
 
 // ------------------------------------------------------------------ LayerNorm
+// Chain of the template (E_s, E_mu, E_d, D, E_q, Q, E_t, E_v, E_w, w_lo, E_r, R, E_h, H, E_p).
+// Per element only |d| = |x - mu| varies, and everything downstream is a polynomial in it with
+// non-negative coefficients:
+//   E_d = u' |d| + E'      (u' = u/(1-u), E' = E_mu/(1-u));   D = |d| + E_d = (1+u')|d| + E'
+// so the two sums the variance bound needs,
+//   sum Q   = (1+u) sum D^2,   sum E_q = sum E_d(|d| + D) + u sum D^2,
+// follow from n, sum|d| and sum d^2, and the per-element tail
+//   E_p/|g| = (1+u) E_h + u r|d|,  E_h = D (E_r + u R) + r E_d
+// collapses to K1 |d| + K0.  Same real-number formula as the step-by-step chain; the different
+// binary64 rounding (a few 2^-53) is covered by the rounding margin of up32g.
 template <int TPR, int V>
 __global__ __launch_bounds__(kRowThreads) void layernorm_bound(
     const float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ g,
@@ -175,39 +189,45 @@ __global__ __launch_bounds__(kRowThreads) void layernorm_bound(
     float4 xv[CACHED ? V : 1];
     double a1[2] = {0.0, 0.0};                                   // sum x, sum |x|
     for (int v = 0; v < nv; ++v) {
-        const float4 X = load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        const float4 X = load4<CACHED>(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
         if (CACHED) xv[v] = X;
         const float e[4] = {X.x, X.y, X.z, X.w};
 #pragma unroll
-        for (int c = 0; c < 4; ++c) { a1[0] += (double)e[c]; a1[1] += fabs((double)e[c]); }
+        for (int c = 0; c < 4; ++c) { a1[0] += (double)e[c]; a1[1] += (double)fabsf(e[c]); }
     }
     group_sum<TPR>(a1, 2, smem);
+    const double n = (double)cols;
     const double mu = a1[0] * k.inv_n;
     const double E_mu = ((k.G * a1[1]) * k.inv_n + k.cd_u * fabs(mu)) * k.inv1mcd;
-    double a2[3] = {0.0, 0.0, 0.0};                              // sum Q, sum E_q, sum d^2
+    double a2[2] = {0.0, 0.0};                                   // sum |d|, sum d^2
     for (int v = 0; v < nv; ++v) {
         const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
         const float e[4] = {X.x, X.y, X.z, X.w};
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            if (TAO_VEC_INDEX(v) + c >= limit) continue;
-            const double ad = fabs((double)e[c] - mu);
-            const double E_d = (E_mu + k.u * ad) * k.inv1mu;
-            const double D = ad + E_d;
-            a2[0] += D * D * (1.0 + k.u);
-            a2[1] += E_d * (ad + D) + k.u * D * D;
-            a2[2] += ad * ad;
+            // padding lanes (beyond the row) hold x = 0 and must not count: d = 0 for them
+            const double d = (TAO_VEC_INDEX(v) + c < limit) ? (double)e[c] - mu : 0.0;
+            a2[0] += fabs(d);
+            a2[1] = fma(d, d, a2[1]);
         }
     }
-    group_sum<TPR>(a2, 3, smem);
-    const double E_t = k.G * a2[0] + a2[1];
-    const double vstar = a2[2] * k.inv_n;
+    group_sum<TPR>(a2, 2, smem);
+    const double up = k.u * k.inv1mu, Ep = E_mu * k.inv1mu;       // u', E'
+    const double c1 = 1.0 + up;
+    const double sD2 = c1 * c1 * a2[1] + 2.0 * c1 * Ep * a2[0] + n * Ep * Ep;           // sum D^2
+    const double sEdD = up * (1.0 + c1) * a2[1] + Ep * (up + 1.0 + c1) * a2[0] + n * Ep * Ep;  // sum E_d(|d|+D)
+    const double E_t = k.G * (1.0 + k.u) * sD2 + sEdD + k.u * sD2;
+    const double vstar = a2[1] * k.inv_n;
     const double E_v = (E_t * k.inv_n + k.cd_u * vstar) * k.inv1mcd;
     double rs, E_r, R;
     const bool ok = rsqrt_tail(vstar, E_v, k, rs, E_r, R);
+    // E_p/|g| = K1 |d| + K0
+    const double hc = E_r + k.u * R;                              // E_h = D hc + r E_d
+    const double K1 = (1.0 + k.u) * (c1 * hc + rs * up) + k.u * rs;
+    const double K0 = ok ? (1.0 + k.u) * Ep * (hc + rs) : NAN;    // NaN row when the bound is not finite
     for (int v = 0; v < nv; ++v) {
         const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
-        const float4 Y = load4(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        const float4 Y = load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
         const float4 Gv = g ? load4(g, TAO_VEC_INDEX(v), limit, vec_g, 1.f) : make_float4(1.f, 1.f, 1.f, 1.f);
         const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w};
         const float ge[4] = {Gv.x, Gv.y, Gv.z, Gv.w};
@@ -215,14 +235,8 @@ __global__ __launch_bounds__(kRowThreads) void layernorm_bound(
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const double ad = fabs((double)xe[c] - mu);
-            const double E_d = (E_mu + k.u * ad) * k.inv1mu;
-            const double D = ad + E_d;
-            const double E_h = D * E_r + rs * E_d + k.u * D * R;
-            const double H = ad * rs + E_h;
-            const double ag = fabs((double)ge[c]);
-            const double E_p = ag * E_h + k.u * ag * H;
-            const double t = E_p + k.u * fabs((double)ye[c]);
-            te[c] = ok ? up32(t * kGuard) : NAN;
+            const double ep = (double)fabsf(ge[c]) * fma(K1, ad, K0);
+            te[c] = up32g(fma(k.u, (double)fabsf(ye[c]), ep));
         }
         store4(tau + roff, TAO_VEC_INDEX(v), limit, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
     }
@@ -237,7 +251,7 @@ __global__ __launch_bounds__(kRowThreads) void rmsnorm_bound(
     float4 xv[CACHED ? V : 1];
     double a1[1] = {0.0};
     for (int v = 0; v < nv; ++v) {
-        const float4 X = load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        const float4 X = load4<CACHED>(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
         if (CACHED) xv[v] = X;
         const float e[4] = {X.x, X.y, X.z, X.w};
 #pragma unroll
@@ -252,7 +266,7 @@ __global__ __launch_bounds__(kRowThreads) void rmsnorm_bound(
     const double f = E_r + k.u * R;
     for (int v = 0; v < nv; ++v) {
         const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
-        const float4 Y = load4(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        const float4 Y = load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
         const float4 Gv = g ? load4(g, TAO_VEC_INDEX(v), limit, vec_g, 1.f) : make_float4(1.f, 1.f, 1.f, 1.f);
         const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w};
         const float ge[4] = {Gv.x, Gv.y, Gv.z, Gv.w};
@@ -261,7 +275,7 @@ __global__ __launch_bounds__(kRowThreads) void rmsnorm_bound(
         for (int c = 0; c < 4; ++c) {
             const double xg = fabs((double)xe[c] * (double)ge[c]);
             const double t = xg * f + k.u * fabs((double)ye[c]);
-            te[c] = ok ? up32(t * kGuard) : NAN;
+            te[c] = ok ? up32g(t) : NAN;
         }
         store4(tau + roff, TAO_VEC_INDEX(v), limit, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
     }
@@ -275,14 +289,14 @@ __global__ __launch_bounds__(kRowThreads) void summean_bound(
     TAO_ROW_PROLOGUE
     double a1[1] = {0.0};
     for (int v = 0; v < nv; ++v) {
-        const float4 X = load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        const float4 X = load4<true>(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
         a1[0] += fabs((double)X.x) + fabs((double)X.y) + fabs((double)X.z) + fabs((double)X.w);
     }
     group_sum<TPR>(a1, 1, smem);
     if (active && lt == 0) {
         double t = k.G * a1[0];
         if (is_mean) t = t * k.inv_n + fabs((double)y[row]) * k.mean_f;
-        tau[row] = up32(t * kGuard);
+        tau[row] = up32g(t);
     }
 }
 
@@ -293,10 +307,17 @@ __global__ __launch_bounds__(kRowThreads) void bn_affine_bound(
     float* __restrict__ tau, long rows, long cols, long ld, int vec_ok, int vec_s, double u) {
     const long vpr = (cols + 3) / 4;                       // vectors per row
     const long total = rows * vpr;
-    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (long)gridDim.x * blockDim.x) {
-        const long row = i / vpr, j = (i - row * vpr) * 4;
-        const float4 X = load4(x + row * ld, j, cols, vec_ok, 0.f);
-        const float4 Y = load4(y + row * ld, j, cols, vec_ok, 0.f);
+    // flat grid-stride walk over (row, vector) pairs; the pair is advanced by additions only
+    // (one division per thread, before the loop)
+    const long stride = (long)gridDim.x * blockDim.x;
+    const long srow = stride / vpr, sjv = stride - srow * vpr;
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    long row = i / vpr, jv = i - row * vpr;
+    for (; i < total; i += stride, row += srow, jv += sjv) {
+        if (jv >= vpr) { jv -= vpr; ++row; }
+        const long j = jv * 4;
+        const float4 X = load4<true>(x + row * ld, j, cols, vec_ok, 0.f);
+        const float4 Y = load4<true>(y + row * ld, j, cols, vec_ok, 0.f);
         const float4 S = load4(s, j, cols, vec_s, 0.f);
         const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w}, se[4] = {S.x, S.y, S.z, S.w};
         float te[4];
@@ -304,20 +325,25 @@ __global__ __launch_bounds__(kRowThreads) void bn_affine_bound(
         for (int c = 0; c < 4; ++c) {
             const double xs = fabs((double)xe[c] * (double)se[c]);
             const double t = u * xs * (1.0 + u) + u * fabs((double)ye[c]);
-            te[c] = up32(t * kGuard);
+            te[c] = up32g(t);
         }
         store4(tau + row * ld, j, cols, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
     }
 }
 
-// Pick the row-group shape for a row length and launch KERNEL<TPR, V>.
-#define TAO_DISPATCH_ROWS(KERNEL, rows, cols, stream, ...)                                          \
+// Pick the row-group shape for a row length and launch KERNEL<TPR, V>.  A single wavefront owns
+// a row of up to WMAX columns (no barrier, no LDS exchange); longer rows take a workgroup.
+// Measured: beyond 1024 columns the registers of a wavefront-wide cached row cut the occupancy
+// to two wavefronts per SIMD and the kernels lose a third of their bandwidth, so WMAX = 1024.
+#define TAO_DISPATCH_ROWS(KERNEL, WMAX, rows, cols, stream, ...)                                    \
     do {                                                                                            \
         const long c_ = (cols);                                                                     \
         auto grid_ = [&](int tpr) { return dim3((unsigned)(((rows) + (kRowThreads / tpr) - 1) / (kRowThreads / tpr))); }; \
         if (c_ <= 256)       hipLaunchKernelGGL((KERNEL<64, 1>), grid_(64), dim3(kRowThreads), 0, stream, __VA_ARGS__);   \
         else if (c_ <= 512)  hipLaunchKernelGGL((KERNEL<64, 2>), grid_(64), dim3(kRowThreads), 0, stream, __VA_ARGS__);   \
         else if (c_ <= 1024) hipLaunchKernelGGL((KERNEL<64, 4>), grid_(64), dim3(kRowThreads), 0, stream, __VA_ARGS__);   \
+        else if (c_ <= 2048 && WMAX >= 2048) hipLaunchKernelGGL((KERNEL<64, 8>), grid_(64), dim3(kRowThreads), 0, stream, __VA_ARGS__);  \
+        else if (c_ <= 4096 && WMAX >= 4096) hipLaunchKernelGGL((KERNEL<64, 16>), grid_(64), dim3(kRowThreads), 0, stream, __VA_ARGS__); \
         else if (c_ <= 2048) hipLaunchKernelGGL((KERNEL<256, 2>), grid_(256), dim3(kRowThreads), 0, stream, __VA_ARGS__); \
         else if (c_ <= 4096) hipLaunchKernelGGL((KERNEL<256, 4>), grid_(256), dim3(kRowThreads), 0, stream, __VA_ARGS__); \
         else if (c_ <= 8192) hipLaunchKernelGGL((KERNEL<256, 8>), grid_(256), dim3(kRowThreads), 0, stream, __VA_ARGS__); \
@@ -361,7 +387,7 @@ int tao_bound_softmax(const float* x, const float* y_ref, float* tau, long rows,
     if (rc != TAO_OK) return rc;
     const int vec_ok = aligned(x, 16) && aligned(y_ref, 16) && aligned(tau, 16) && (ld % 4 == 0);
     hipStream_t st = (hipStream_t)stream;
-    TAO_DISPATCH_ROWS(softmax_bound, rows, cols, st, x, y_ref, tau, rows, cols, ld, vec_ok, k);
+    TAO_DISPATCH_ROWS(softmax_bound, 1024, rows, cols, st, x, y_ref, tau, rows, cols, ld, vec_ok, k);
     return launch_status();
 }
 
@@ -393,22 +419,22 @@ int tao_bound_norm(int kind, const float* x, const float* y_ref, const float* ga
     const float* g = gamma_or_scale;
     switch (kind) {
         case TAO_NORM_LAYERNORM:
-            TAO_DISPATCH_ROWS(layernorm_bound, rows, cols, st, x, y_ref, g, tau, rows, cols, ld, vec_ok, vec_g, k);
+            TAO_DISPATCH_ROWS(layernorm_bound, 1024, rows, cols, st, x, y_ref, g, tau, rows, cols, ld, vec_ok, vec_g, k);
             break;
         case TAO_NORM_RMSNORM:
-            TAO_DISPATCH_ROWS(rmsnorm_bound, rows, cols, st, x, y_ref, g, tau, rows, cols, ld, vec_ok, vec_g, k);
+            TAO_DISPATCH_ROWS(rmsnorm_bound, 1024, rows, cols, st, x, y_ref, g, tau, rows, cols, ld, vec_ok, vec_g, k);
             break;
         case TAO_NORM_BN_AFFINE: {
             const long total = rows * ((cols + 3) / 4);
             long blocks = (total + kRowThreads - 1) / kRowThreads;
-            if (blocks > 256L * 16) blocks = 256L * 16;
+            if (blocks > 256L * 4) blocks = 256L * 4;      // four workgroups per CU, grid-stride
             hipLaunchKernelGGL(bn_affine_bound, dim3((unsigned)blocks), dim3(kRowThreads), 0, st, x, y_ref, g,
                                tau, rows, cols, ld, vec_ok, vec_g, md.u);
             break;
         }
         default: {
             const int is_mean = (kind == TAO_NORM_MEAN);
-            TAO_DISPATCH_ROWS(summean_bound, rows, cols, st, x, y_ref, tau, rows, cols, ld, vec_x, is_mean, k);
+            TAO_DISPATCH_ROWS(summean_bound, 1024, rows, cols, st, x, y_ref, tau, rows, cols, ld, vec_x, is_mean, k);
             break;
         }
     }

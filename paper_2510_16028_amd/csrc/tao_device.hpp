@@ -15,6 +15,16 @@ __device__ __forceinline__ float up32(double v) {
     return f;
 }
 
+// Cheaper upper rounding for the streaming kernels (two operations instead of five), which also
+// takes the place of the guard factor: for v >= 0 the result is a binary32 value >= v(1 + 2^-33)
+// and at most v(1 + 2^-23 + 2^-31) (three halves of that near the bottom of the normal range).
+// v(1 + 2^-24 + 2^-32) lies above the midpoint of the two binary32 neighbours of v, so round-to-
+// nearest moves it to the upper one; the 2^-150 keeps that true among subnormal results, where
+// rounding is absolute (0 stays 0: the tie goes to even).  NaN and +inf pass through.
+__device__ __forceinline__ float up32g(double v) {
+    return (float)fma(v, 1.0 + 0x1p-24 + 0x1p-32, 0x1p-150);
+}
+
 __device__ __forceinline__ double wave_sum(double v) {
 #pragma unroll
     for (int o = kWave / 2; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
@@ -38,13 +48,23 @@ __device__ __forceinline__ float4 ntload4(const float4* p) {
     return make_float4(v.x, v.y, v.z, v.w);
 }
 
+// Streaming 16-byte store of data that is not read again by this kernel.
+__device__ __forceinline__ void ntstore4(float4* p, float4 v) {
+    typedef float v4f __attribute__((ext_vector_type(4)));
+    const v4f t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<v4f*>(p));
+}
+
 // 16-byte global load when the caller has established alignment, else four
 // guarded scalar loads; elements at or beyond `limit` read as `fill`.
+// STREAM: the data is read once by the kernel (non-temporal load).
+template <bool STREAM = false>
 __device__ __forceinline__ float4 load4(const float* __restrict__ p, long idx, long limit,
                                         bool vec_ok, float fill) {
     float4 r;
     if (vec_ok && idx + 3 < limit) {
-        r = *reinterpret_cast<const float4*>(p + idx);
+        r = STREAM ? ntload4(reinterpret_cast<const float4*>(p + idx))
+                   : *reinterpret_cast<const float4*>(p + idx);
     } else {
         r.x = (idx + 0 < limit) ? p[idx + 0] : fill;
         r.y = (idx + 1 < limit) ? p[idx + 1] : fill;
@@ -56,7 +76,7 @@ __device__ __forceinline__ float4 load4(const float* __restrict__ p, long idx, l
 __device__ __forceinline__ void store4(float* __restrict__ p, long idx, long limit, bool vec_ok,
                                        float4 v) {
     if (vec_ok && idx + 3 < limit) {
-        *reinterpret_cast<float4*>(p + idx) = v;
+        ntstore4(reinterpret_cast<float4*>(p + idx), v);      // bounds are written once, never re-read here
     } else {
         if (idx + 0 < limit) p[idx + 0] = v.x;
         if (idx + 1 < limit) p[idx + 1] = v.y;
