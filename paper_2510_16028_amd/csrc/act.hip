@@ -117,11 +117,11 @@ int tao_bound_act(int kind, const float* x, const float* x2, const float* y_ref,
     k.silu_f = widen(om * inv1mu + u);
     k.a_f = widen(kTwoRsqrtPiUp * (1.0 + 4.0 * u));
     const int vec_ok = aligned(y_ref, 16) && aligned(tau, 16) && (kind != TAO_ACT_GELU_ERF || aligned(x, 16));
-    // four 256-thread workgroups per CU, grid-stride: every wavefront of the chip walks one
-    // contiguous moving window of memory (the best of the launch shapes measured)
+    // up to 64 workgroups of 256 threads per CU, grid-stride beyond that (sweeping 2 .. 128 per
+    // CU at 8 M .. 100 M elements: the kernels with more arithmetic keep gaining up to 32 - 64)
     long blocks = (n / 4 + 255) / 256;
     if (blocks < 1) blocks = 1;
-    if (blocks > 256L * 4) blocks = 256L * 4;
+    if (blocks > 256L * 64) blocks = 256L * 64;
     hipStream_t st = (hipStream_t)stream;
     dim3 grid((unsigned)blocks), blk(256);
     switch (kind) {

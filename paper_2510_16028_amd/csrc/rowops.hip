@@ -39,7 +39,7 @@ __device__ __forceinline__ void group_sum(double* v, int count, double* smem) {
     for (int i = 0; i < count; ++i) v[i] = wave_sum(v[i]);
     if (TPR > kWave) {
         const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-        __syncthreads();                         // smem may still be read from a previous call
+        // every reduction of a kernel has its own 16-double slot of smem, so one barrier is enough
         if (lane == 0) for (int i = 0; i < count; ++i) smem[wave * 4 + i] = v[i];
         __syncthreads();
         for (int i = 0; i < count; ++i) {
@@ -55,7 +55,6 @@ __device__ __forceinline__ void group_max_or(float& m, int& flag, double* smem) 
     flag = wave_or(flag);
     if (TPR > kWave) {
         const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-        __syncthreads();
         if (lane == 0) { smem[wave * 4] = (double)m; smem[wave * 4 + 1] = (double)flag; }
         __syncthreads();
         float mm = -INFINITY; int ff = 0;
@@ -67,7 +66,7 @@ __device__ __forceinline__ void group_max_or(float& m, int& flag, double* smem) 
 #define TAO_ROW_PROLOGUE                                                              \
     constexpr int RPB = kRowThreads / TPR;                                            \
     constexpr bool CACHED = (V > 0);                                                  \
-    __shared__ double smem[16];                                                       \
+    __shared__ double smem[2 * 16]; /* one slot per reduction of the kernel */        \
     const int lt = threadIdx.x % TPR;                                                 \
     const long row = (long)blockIdx.x * RPB + threadIdx.x / TPR;                      \
     const bool active = row < rows;                                                   \
@@ -125,7 +124,7 @@ __global__ __launch_bounds__(kRowThreads) void softmax_bound(
             if (KEEP) { qv[v * 4 + c] = q; rv[v * 4 + c] = rho; }
         }
     }
-    group_sum<TPR>(acc, 2, smem);
+    group_sum<TPR>(acc, 2, smem + 16);
     const double sigma = k.G * acc[0] + (1.0 + k.G) * acc[1];
     if (!(sigma < 1.0)) bad = 1;
     // tau = q rho + q (1+rho) sfac + u y  with y = q (1-u) <= q:
@@ -186,11 +185,16 @@ __global__ __launch_bounds__(kRowThreads) void layernorm_bound(
     const float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ g,
     float* __restrict__ tau, long rows, long cols, long ld, int vec_ok, int vec_g, RowConsts k) {
     TAO_ROW_PROLOGUE
-    float4 xv[CACHED ? V : 1];
+    // a cached row also requests y and g up front: their latency then overlaps the reductions
+    float4 xv[CACHED ? V : 1], yv[CACHED ? V : 1], gv[CACHED ? V : 1];
     double a1[2] = {0.0, 0.0};                                   // sum x, sum |x|
     for (int v = 0; v < nv; ++v) {
         const float4 X = load4<CACHED>(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
-        if (CACHED) xv[v] = X;
+        if (CACHED) {
+            xv[v] = X;
+            yv[v] = load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+            gv[v] = g ? load4(g, TAO_VEC_INDEX(v), limit, vec_g, 1.f) : make_float4(1.f, 1.f, 1.f, 1.f);
+        }
         const float e[4] = {X.x, X.y, X.z, X.w};
 #pragma unroll
         for (int c = 0; c < 4; ++c) { a1[0] += (double)e[c]; a1[1] += (double)fabsf(e[c]); }
@@ -211,7 +215,7 @@ __global__ __launch_bounds__(kRowThreads) void layernorm_bound(
             a2[1] = fma(d, d, a2[1]);
         }
     }
-    group_sum<TPR>(a2, 2, smem);
+    group_sum<TPR>(a2, 2, smem + 16);
     const double up = k.u * k.inv1mu, Ep = E_mu * k.inv1mu;       // u', E'
     const double c1 = 1.0 + up;
     const double sD2 = c1 * c1 * a2[1] + 2.0 * c1 * Ep * a2[0] + n * Ep * Ep;           // sum D^2
@@ -227,8 +231,8 @@ __global__ __launch_bounds__(kRowThreads) void layernorm_bound(
     const double K0 = ok ? (1.0 + k.u) * Ep * (hc + rs) : NAN;    // NaN row when the bound is not finite
     for (int v = 0; v < nv; ++v) {
         const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
-        const float4 Y = load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
-        const float4 Gv = g ? load4(g, TAO_VEC_INDEX(v), limit, vec_g, 1.f) : make_float4(1.f, 1.f, 1.f, 1.f);
+        const float4 Y = CACHED ? yv[v] : load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        const float4 Gv = CACHED ? gv[v] : (g ? load4(g, TAO_VEC_INDEX(v), limit, vec_g, 1.f) : make_float4(1.f, 1.f, 1.f, 1.f));
         const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w};
         const float ge[4] = {Gv.x, Gv.y, Gv.z, Gv.w};
         float te[4];
@@ -248,11 +252,15 @@ __global__ __launch_bounds__(kRowThreads) void rmsnorm_bound(
     const float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ g,
     float* __restrict__ tau, long rows, long cols, long ld, int vec_ok, int vec_g, RowConsts k) {
     TAO_ROW_PROLOGUE
-    float4 xv[CACHED ? V : 1];
+    float4 xv[CACHED ? V : 1], yv[CACHED ? V : 1], gv[CACHED ? V : 1];
     double a1[1] = {0.0};
     for (int v = 0; v < nv; ++v) {
         const float4 X = load4<CACHED>(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
-        if (CACHED) xv[v] = X;
+        if (CACHED) {
+            xv[v] = X;
+            yv[v] = load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+            gv[v] = g ? load4(g, TAO_VEC_INDEX(v), limit, vec_g, 1.f) : make_float4(1.f, 1.f, 1.f, 1.f);
+        }
         const float e[4] = {X.x, X.y, X.z, X.w};
 #pragma unroll
         for (int c = 0; c < 4; ++c) a1[0] += (double)e[c] * (double)e[c];
@@ -266,8 +274,8 @@ __global__ __launch_bounds__(kRowThreads) void rmsnorm_bound(
     const double f = E_r + k.u * R;
     for (int v = 0; v < nv; ++v) {
         const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
-        const float4 Y = load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
-        const float4 Gv = g ? load4(g, TAO_VEC_INDEX(v), limit, vec_g, 1.f) : make_float4(1.f, 1.f, 1.f, 1.f);
+        const float4 Y = CACHED ? yv[v] : load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        const float4 Gv = CACHED ? gv[v] : (g ? load4(g, TAO_VEC_INDEX(v), limit, vec_g, 1.f) : make_float4(1.f, 1.f, 1.f, 1.f));
         const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w};
         const float ge[4] = {Gv.x, Gv.y, Gv.z, Gv.w};
         float te[4];
@@ -427,7 +435,7 @@ int tao_bound_norm(int kind, const float* x, const float* y_ref, const float* ga
         case TAO_NORM_BN_AFFINE: {
             const long total = rows * ((cols + 3) / 4);
             long blocks = (total + kRowThreads - 1) / kRowThreads;
-            if (blocks > 256L * 4) blocks = 256L * 4;      // four workgroups per CU, grid-stride
+            if (blocks > 256L * 64) blocks = 256L * 64;    // grid-stride beyond 64 workgroups per CU
             hipLaunchKernelGGL(bn_affine_bound, dim3((unsigned)blocks), dim3(kRowThreads), 0, st, x, y_ref, g,
                                tau, rows, cols, ld, vec_ok, vec_g, md.u);
             break;
