@@ -107,9 +107,10 @@ double tao_gamma(long k, const tao_fp_model *model);
  *    Linear layer); trans_w != 0: [batch][K][N].  Row stride ldw, batch stride
  *    strideW (0 shares one W across the batch).
  * bias: [N] or NULL, shared across the batch.  tau: [batch][M][N], ldt, strideT.
- * The product |A||W| runs on the FP32 matrix cores in chains of at most 6
- * k-steps whose partial sums are folded into a binary64 accumulator; the result
- * is inflated by the proven rounding error of that scheme, so
+ * The product |A||W| runs on the FP32 matrix cores in chains of 4 k-steps from
+ * a zero accumulator; eight chain results are added as a binary32 tree and the
+ * root is folded into a binary64 accumulator (at most 7 binary32 roundings per
+ * term); the result is inflated by the proven rounding error of that scheme, so
  * exact <= tau <= exact * (1 + 1e-6).  M, N or batch equal to 0 is a no-op;
  * K == 0 gives tau = Gamma(K') |bias| (0 without bias). */
 int tao_bound_linear(const float *A, const float *W, const float *bias, float *tau,
@@ -172,6 +173,39 @@ int tao_check_and_profile(const float *claimed, const float *ref, const float *t
  * aligned; its contents on entry do not matter and are garbage afterwards.
  * Calls that share a workspace must be ordered on one stream. */
 size_t tao_check_workspace_bytes(long n);
+
+/* Error profile of tao_profile_errors (lives in DEVICE memory, 8-byte aligned). */
+#define TAO_NGRID 22   /* percentile grid P = {1, 5, 10, ..., 95, 99, 100} of Sec. 3.2 / Sec. 5.3 */
+typedef struct tao_error_profile {
+    uint64_t n;                 /* elements examined */
+    uint64_t nan_count;         /* elements whose relative error is NaN */
+    float max_abs, max_rel;     /* largest non-NaN absolute / relative error (binary32), 0 if none */
+    float abs_p[TAO_NGRID];     /* percentile values on the grid: upper edge of the bin holding the */
+    float rel_p[TAO_NGRID];     /*   nearest-rank element, capped by the exact maximum               */
+    uint32_t abs_bin[TAO_NGRID], rel_bin[TAO_NGRID];   /* that bin */
+    double p_max;               /* selection statistic; NaN without thresholds */
+    uint32_t offending;         /* 1 iff p_max > 1 */
+    uint32_t pad_;
+    uint64_t hist_abs[TAO_NBINS], hist_rel[TAO_NBINS];  /* bin = bits(error) >> 20; NaN -> 2047 */
+} tao_error_profile;
+
+/* Empirical error profile of two outputs of one operator, as used for calibration (Sec. 3.2
+ * Eq. 1-2) and for child selection in the dispute game (Sec. 5.3): per element, in IEEE binary64,
+ *     abs = |claimed - ref|,   rel = abs / (|ref| + eps_rel),   both cast to binary32;
+ * two histograms with the bin key of tao_check_and_profile; for each p of the 22-point grid the
+ * nearest-rank percentile (rank = max(1, ceil(n p / 100))) reported as its bin and that bin's
+ * upper edge, capped by the exact maximum, so p = 100 is the maximum itself; and, when the
+ * committed threshold tables thr_abs[22], thr_rel[22] (DEVICE pointers, both or neither) are
+ * given, the selection statistic
+ *     p_max = max over the grid of { abs_p / thr_abs, rel_p / thr_rel }  (binary64 quotients,
+ *     NaN quotients skipped),   offending = (p_max > 1).
+ * out: DEVICE pointer, fully overwritten; valid once the stream has drained.
+ * ws / ws_bytes: DEVICE scratch of at least tao_profile_workspace_bytes(n), 256-byte aligned;
+ * contents on entry do not matter; calls sharing a workspace must be ordered on one stream. */
+int tao_profile_errors(const float *claimed, const float *ref, long n, double eps_rel,
+                       const float *thr_abs, const float *thr_rel, tao_error_profile *out,
+                       void *ws, size_t ws_bytes, void *stream);
+size_t tao_profile_workspace_bytes(long n);
 
 /* Runs crafted inputs through the FP32 matrix-core instruction and reports, as
  * a bit mask in *report (HOST pointer), which modelling assumptions of the

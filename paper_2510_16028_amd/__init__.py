@@ -54,6 +54,28 @@ class Profile(ctypes.Structure):
                 "hist": np.ctypeslib.as_array(self.hist).copy()}
 
 
+NGRID = 22
+GRID_PERCENT = [1] + [5 * g for g in range(1, 20)] + [99, 100]
+
+
+class ErrorProfile(ctypes.Structure):
+    """tao_error_profile as laid out in device memory."""
+    _fields_ = [("n", ctypes.c_uint64), ("nan_count", ctypes.c_uint64),
+                ("max_abs", ctypes.c_float), ("max_rel", ctypes.c_float),
+                ("abs_p", ctypes.c_float * NGRID), ("rel_p", ctypes.c_float * NGRID),
+                ("abs_bin", ctypes.c_uint32 * NGRID), ("rel_bin", ctypes.c_uint32 * NGRID),
+                ("p_max", ctypes.c_double), ("offending", ctypes.c_uint32), ("pad_", ctypes.c_uint32),
+                ("hist_abs", ctypes.c_uint64 * NBINS), ("hist_rel", ctypes.c_uint64 * NBINS)]
+
+    def as_dict(self):
+        arr = lambda a: np.ctypeslib.as_array(a).copy()
+        return {"n": int(self.n), "nan_count": int(self.nan_count), "max_abs": float(self.max_abs),
+                "max_rel": float(self.max_rel), "abs_p": arr(self.abs_p), "rel_p": arr(self.rel_p),
+                "abs_bin": arr(self.abs_bin), "rel_bin": arr(self.rel_bin), "p_max": float(self.p_max),
+                "offending": int(self.offending), "hist_abs": arr(self.hist_abs),
+                "hist_rel": arr(self.hist_rel)}
+
+
 class TaoError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
@@ -66,8 +88,8 @@ class TaoError(RuntimeError):
 
 EXPORTS = ["tao_default_model", "tao_gamma", "tao_bound_linear", "tao_bound_softmax",
            "tao_bound_norm", "tao_bound_act", "tao_check_and_profile",
-           "tao_check_workspace_bytes", "tao_selftest_matrix_core", "tao_last_hip_error",
-           "tao_status_string"]
+           "tao_check_workspace_bytes", "tao_profile_errors", "tao_profile_workspace_bytes",
+           "tao_selftest_matrix_core", "tao_last_hip_error", "tao_status_string"]
 
 _lib = None
 
@@ -95,6 +117,9 @@ def lib():
     L.tao_check_and_profile.argtypes = [vp, vp, vp, lg, dbl, dbl, vp, vp, ctypes.c_size_t, vp]
     L.tao_check_workspace_bytes.argtypes = [lg]
     L.tao_check_workspace_bytes.restype = ctypes.c_size_t
+    L.tao_profile_errors.argtypes = [vp, vp, lg, dbl, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.tao_profile_workspace_bytes.argtypes = [lg]
+    L.tao_profile_workspace_bytes.restype = ctypes.c_size_t
     L.tao_selftest_matrix_core.argtypes = [ctypes.POINTER(ctypes.c_uint), vp]
     L.tao_last_hip_error.restype = ctypes.c_int
     L.tao_status_string.argtypes = [ctypes.c_int]
@@ -309,6 +334,46 @@ def tao_check_and_profile(claimed, ref, tau, alpha=1.0, eps_rel=1e-12, out=None,
                                      float(eps_rel), _ptr(out), _ptr(ws), ws.numel(), _stream())
     _check(rc, "tao_check_and_profile")
     return read_profile(out) if readback else out
+
+
+def tao_profile_errors(claimed, ref, eps_rel=1e-12, thr_abs=None, thr_rel=None, out=None, ws=None,
+                       readback=True):
+    """Absolute / relative error profiles on the 22-point grid and the selection statistic.
+    thr_abs, thr_rel: float32 CUDA tensors of 22 thresholds (both or neither)."""
+    torch = _torch()
+    claimed = _dev(claimed, "claimed"); ref = _dev(ref, "ref")
+    thr_abs = _dev(thr_abs, "thr_abs"); thr_rel = _dev(thr_rel, "thr_rel")
+    for t, nm in ((claimed, "claimed"), (ref, "ref")):
+        if not t.is_contiguous():
+            raise ValueError("%s must be contiguous" % nm)
+    n = claimed.numel()
+    if ref.numel() != n:
+        raise ValueError("claimed and ref must have the same number of elements")
+    if (thr_abs is None) != (thr_rel is None):
+        raise ValueError("thr_abs and thr_rel come together")
+    for t, nm in ((thr_abs, "thr_abs"), (thr_rel, "thr_rel")):
+        if t is not None and (t.numel() != NGRID or not t.is_contiguous()):
+            raise ValueError("%s must be a contiguous tensor of %d thresholds" % (nm, NGRID))
+    if out is None:
+        out = torch.empty(ctypes.sizeof(ErrorProfile), dtype=torch.uint8, device=claimed.device)
+    need = lib().tao_profile_workspace_bytes(int(n))
+    if ws is None:
+        key = ("errors", claimed.device.index if claimed.device.index is not None else torch.cuda.current_device(),
+               torch.cuda.current_stream().cuda_stream)
+        ws = _ws_cache.get(key)
+        if ws is None or ws.numel() < need:
+            ws = torch.empty(need, dtype=torch.uint8, device=claimed.device)
+            _ws_cache[key] = ws
+    rc = lib().tao_profile_errors(_ptr(claimed), _ptr(ref), n, float(eps_rel), _ptr(thr_abs), _ptr(thr_rel),
+                                  _ptr(out), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "tao_profile_errors")
+    if not readback:
+        return out
+    return ErrorProfile.from_buffer_copy(out.cpu().numpy().tobytes()).as_dict()
+
+
+def tao_profile_workspace_bytes(n):
+    return lib().tao_profile_workspace_bytes(int(n))
 
 
 def tao_check_workspace_bytes(n):

@@ -13,22 +13,14 @@
 // number of elements below its own bins; it can then decide by itself whether a
 // nearest-rank percentile falls into one of its bins -- no cross-workgroup
 // ordering, fences or atomics.  Workgroup 0 also writes the scalar fields.
-#include "tao_device.hpp"
+#include "tao_hist.hpp"
 #include "tao_host.hpp"
 
 namespace tao {
 
-constexpr int kBins = TAO_NBINS;
 constexpr int kCheckThreads = 1024;          // one workgroup per CU: one partial histogram per CU
-constexpr int kReplicas = 4;                 // LDS copies of each bin, selected by lane & 3
-constexpr int kMaxCheckBlocks = 256;
-constexpr int kBinsPerReduceBlock = 64;
-constexpr int kReduceBlocks = kBins / kBinsPerReduceBlock;
-constexpr int kReduceThreads = 1024;
-constexpr int kReduceSlices = kReduceThreads / kBinsPerReduceBlock;      // 16
-constexpr int kPartialsPerThread = kMaxCheckBlocks / kReduceSlices;      // 16 independent loads
-constexpr int kReduceWaves = kReduceThreads / kWave;
-constexpr int kGroups = kBins / kBinsPerReduceBlock;                      // 32 coarse groups of 64 bins
+constexpr int kMaxCheckBlocks = kMaxPartials;
+constexpr int kReduceBlocks = kGroups;
 
 struct BlockStats {          // one per pass-1 workgroup, in the workspace after the histograms
     unsigned long long violations;
@@ -50,9 +42,9 @@ __device__ __forceinline__ void check_one(float c, float r, float t, double alph
     const double den = fabs(rd) + eps_rel;
     const double e = d / den;
     const float e32 = (float)e;
-    const bool isn = e32 != e32;
+    bool isn;
+    const unsigned int bin = error_bin(e32, isn);
     const unsigned int bits = __float_as_uint(e32);
-    const unsigned int bin = isn ? (unsigned)(kBins - 1) : (bits >> 20);
     acc.nans += isn;
     if (!isn) acc.max_bits = max(acc.max_bits, bits);
     atomicAdd(&hist[bin * kReplicas + rep], 1u);
@@ -105,108 +97,40 @@ __global__ __launch_bounds__(kCheckThreads) void check_pass(
         }
         ws_stats[blockIdx.x] = s;
     }
-    unsigned int* dst = ws_hist + (size_t)blockIdx.x * kBins;
-    for (int b = tid; b < kBins; b += kCheckThreads) {
-        unsigned int s = 0;
-#pragma unroll
-        for (int r = 0; r < kReplicas; ++r) s += hist[b * kReplicas + r];
-        dst[b] = s;
-        // a wavefront covers exactly one group of 64 consecutive bins
-        unsigned int g = s;
-#pragma unroll
-        for (int o = kWave / 2; o > 0; o >>= 1) g += __shfl_xor(g, o, kWave);
-        if ((tid & (kWave - 1)) == 0) ws_coarse[blockIdx.x * kGroups + b / kBinsPerReduceBlock] = g;
-    }
-}
-
-__device__ __forceinline__ float bin_upper_edge(unsigned int b) {
-    if (b >= (unsigned)(kBins - 1)) return __uint_as_float(0x7fc00000u);
-    if (b >= 2039u) return __uint_as_float(0x7f800000u);
-    return __uint_as_float((b + 1u) << 20);
-}
-
-// rank = max(1, ceil(n * num / den)); n < 2^53 and num <= 999 keep the product in 64 bits.
-__device__ __forceinline__ unsigned long long rank_of(unsigned long long n, unsigned long long num,
-                                                       unsigned long long den) {
-    unsigned long long r = (n * num + den - 1) / den;
-    return r < 1 ? 1 : r;
+    flush_histogram(hist, ws_hist + (size_t)blockIdx.x * kBins, ws_coarse + blockIdx.x * kGroups);
 }
 
 __global__ __launch_bounds__(kReduceThreads) void profile_reduce(
     const unsigned int* __restrict__ ws_hist, const unsigned int* __restrict__ ws_coarse,
     const BlockStats* __restrict__ ws_stats, int nblocks, unsigned long long n, tao_profile* out) {
-    __shared__ unsigned long long part[kReduceThreads];
-    __shared__ unsigned long long wsum[kReduceWaves], wv[kReduceWaves], wq[kReduceWaves];
+    __shared__ unsigned long long smem[kReduceThreads + kReduceWaves];
+    __shared__ unsigned long long wv[kReduceWaves], wq[kReduceWaves];
     __shared__ unsigned int wm[kReduceWaves];
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1), wave = tid / kWave;
-    // own bins: 64 bins x 16 slices of the partial histograms; all loads independent
-    const int b = tid & (kBinsPerReduceBlock - 1);
-    const int slice = tid / kBinsPerReduceBlock;
-    const int bin = blockIdx.x * kBinsPerReduceBlock + b;
-    unsigned int vals[kPartialsPerThread];
-#pragma unroll
-    for (int j = 0; j < kPartialsPerThread; ++j) {
-        const int k = slice + kReduceSlices * j;
-        vals[j] = (k < nblocks) ? ws_hist[(size_t)k * kBins + bin] : 0u;
+    // nearest-rank percentiles p50, p99, p99.9; the three bin and three edge fields of tao_profile
+    // are consecutive
+    const RankQuery q[3] = {{1, 2}, {99, 100}, {999, 1000}};
+    reduce_group<3>(ws_hist, ws_coarse, nblocks, blockIdx.x, n, out->hist, q, &out->p50_bin, &out->p50, smem);
+    if (blockIdx.x != 0) return;
+    // counters of pass 1 (at most one record per thread)
+    unsigned long long v = 0, qn = 0; unsigned int m = 0;
+    for (int k = tid; k < nblocks; k += kReduceThreads) {
+        v += ws_stats[k].violations; qn += ws_stats[k].nans; m = max(m, ws_stats[k].max_bits);
     }
-    // elements in all bins below this workgroup's: coarse counts of the groups g < blockIdx.x
-    unsigned long long below = 0;
-    const int total = nblocks * kGroups;
 #pragma unroll
-    for (int j = 0; j < (kMaxCheckBlocks * kGroups) / kReduceThreads; ++j) {
-        const int e = tid + kReduceThreads * j;
-        if (e < total && (e % kGroups) < (int)blockIdx.x) below += ws_coarse[e];
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+        v += __shfl_xor(v, o, kWave); qn += __shfl_xor(qn, o, kWave);
+        m = max(m, (unsigned int)__shfl_xor(m, o, kWave));
     }
-    unsigned long long s = 0;
-#pragma unroll
-    for (int j = 0; j < kPartialsPerThread; ++j) s += vals[j];
-    part[tid] = s;
-#pragma unroll
-    for (int o = kWave / 2; o > 0; o >>= 1) below += __shfl_xor(below, o, kWave);
-    if (lane == 0) wsum[wave] = below;
-    // counters of pass 1 (workgroup 0 only; at most one record per thread)
-    unsigned long long v = 0, q = 0; unsigned int m = 0;
-    if (blockIdx.x == 0) {
-        for (int k = tid; k < nblocks; k += kReduceThreads) {
-            v += ws_stats[k].violations; q += ws_stats[k].nans; m = max(m, ws_stats[k].max_bits);
-        }
-#pragma unroll
-        for (int o = kWave / 2; o > 0; o >>= 1) {
-            v += __shfl_xor(v, o, kWave); q += __shfl_xor(q, o, kWave);
-            m = max(m, (unsigned int)__shfl_xor(m, o, kWave));
-        }
-        if (lane == 0) { wv[wave] = v; wq[wave] = q; wm[wave] = m; }
-    }
+    if (lane == 0) { wv[wave] = v; wq[wave] = qn; wm[wave] = m; }
     __syncthreads();
-    if (tid < kBinsPerReduceBlock) {            // first wavefront: one lane per bin
-        unsigned long long t = 0;
-#pragma unroll
-        for (int k = 0; k < kReduceSlices; ++k) t += part[k * kBinsPerReduceBlock + tid];
-        out->hist[bin] = t;
-        unsigned long long before = 0;
-#pragma unroll
-        for (int w = 0; w < kReduceWaves; ++w) before += wsum[w];
-        unsigned long long incl = t;
-#pragma unroll
-        for (int o = 1; o < kWave; o <<= 1) {
-            const unsigned long long up = __shfl_up(incl, o, kWave);
-            if (lane >= o) incl += up;
-        }
-        const unsigned long long hi = before + incl, lo = hi - t;      // ranks (lo, hi] fall in this bin
-        if (n > 0) {
-            const unsigned long long r50 = rank_of(n, 1, 2), r99 = rank_of(n, 99, 100), r999 = rank_of(n, 999, 1000);
-            if (lo < r50 && r50 <= hi) { out->p50_bin = bin; out->p50 = bin_upper_edge(bin); }
-            if (lo < r99 && r99 <= hi) { out->p99_bin = bin; out->p99 = bin_upper_edge(bin); }
-            if (lo < r999 && r999 <= hi) { out->p999_bin = bin; out->p999 = bin_upper_edge(bin); }
-        }
-    }
-    if (blockIdx.x == 0 && tid == 0) {
-        v = 0; q = 0; m = 0;
-        for (int w = 0; w < kReduceWaves; ++w) { v += wv[w]; q += wq[w]; m = max(m, wm[w]); }
+    if (tid == 0) {
+        v = 0; qn = 0; m = 0;
+        for (int w = 0; w < kReduceWaves; ++w) { v += wv[w]; qn += wq[w]; m = max(m, wm[w]); }
         out->n = n;
         out->violations = v;
-        out->nan_count = q;
+        out->nan_count = qn;
         out->max_rel = __uint_as_float(m);
         out->accept = (v == 0) ? 1u : 0u;
         out->pad_ = 0;

@@ -39,6 +39,10 @@ def test_struct_layouts_match_the_header(tao):
     assert ctypes.sizeof(tao.Profile) == 8 * 3 + 4 * 10 + 8 * 2048
     assert tao.Profile.hist.offset == 64
     assert ctypes.sizeof(tao.FpModel) == 64
+    assert ctypes.sizeof(tao.ErrorProfile) == 8 * 2 + 4 * 2 + 4 * 22 * 4 + 8 + 4 * 2 + 8 * 2048 * 2
+    assert tao.ErrorProfile.p_max.offset % 8 == 0 and tao.ErrorProfile.hist_abs.offset % 8 == 0
+    assert tao.GRID_PERCENT == [1, 5, 10, 15, 20, 25, 30, 35, 40, 45, 50, 55, 60, 65, 70, 75, 80, 85, 90,
+                                95, 99, 100]
     m = tao.tao_default_model()
     assert (m.u, m.mode, m.lam, m.c_exp, m.c_erf, m.c_rsqrt, m.c_div, m.flags) == \
         (2.0 ** -24, 0, 4.0, 2.0, 2.0, 2.0, 2.0, 0)
@@ -100,6 +104,16 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_check_and_profile(p, p, p, -1, 1.0, 0.0, p, ws, need, None) == tao.ERR_SHAPE
     assert L.tao_check_and_profile(nul, p, p, 10, 1.0, 0.0, p, ws, need, None) == tao.ERR_NULL
     assert L.tao_check_and_profile(odd, p, p, 10, 1.0, 0.0, p, ws, need, None) == tao.ERR_ALIGN
+    # error profiles
+    need = L.tao_profile_workspace_bytes(1000)
+    assert need > 0
+    assert L.tao_profile_errors(p, p, 10, 0.0, nul, nul, nul, ws, need, None) == tao.ERR_NULL
+    assert L.tao_profile_errors(p, p, 10, 0.0, nul, nul, p, nul, need, None) == tao.ERR_WORKSPACE
+    assert L.tao_profile_errors(p, p, 10, 0.0, nul, nul, p, ws, need - 1, None) == tao.ERR_WORKSPACE
+    assert L.tao_profile_errors(p, p, 10, 0.0, p, nul, p, ws, need, None) == tao.ERR_NULL      # one table only
+    assert L.tao_profile_errors(p, nul, 10, 0.0, nul, nul, p, ws, need, None) == tao.ERR_NULL
+    assert L.tao_profile_errors(p, p, -1, 0.0, nul, nul, p, ws, need, None) == tao.ERR_SHAPE
+    assert L.tao_profile_errors(odd, p, 10, 0.0, nul, nul, p, ws, need, None) == tao.ERR_ALIGN
     for code in range(0, -9, -1):
         assert L.tao_status_string(code)
     assert L.tao_selftest_matrix_core(None, None) == tao.ERR_NULL

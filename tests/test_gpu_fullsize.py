@@ -132,3 +132,22 @@ def test_check_profile_67m_elements_bit_exact(tao, oracle_mod):
     po = oracle_mod.check_and_profile(_np(c), _np(r), _np(t))
     assert_profile_equal(pg, po, "67M check")
     assert 0 < po["violations"] < n
+
+
+def test_profile_errors_67m_elements_bit_exact(tao, oracle_mod):
+    """Error profiles on the 22-point grid at the stress size: histograms, percentile bins and
+    values, maxima and the selection statistic identical to the oracle's."""
+    n = 8192 * 8192
+    c, r, _ = tao_inputs.check_triplet("cpu", seed=68, n=n)
+    base = oracle_mod.profile_errors(_np(c), _np(r))
+    ta = (3 * base["abs_p"]).astype(np.float32); tr = (3 * base["rel_p"]).astype(np.float32)
+    pg = tao.tao_profile_errors(c.cuda(), r.cuda(), thr_abs=torch.from_numpy(ta).cuda(), thr_rel=torch.from_numpy(tr).cuda())
+    po = oracle_mod.profile_errors(_np(c), _np(r), thr_abs=ta, thr_rel=tr)
+    for k in ("n", "nan_count", "offending"):
+        assert pg[k] == po[k], k
+    for k in ("hist_abs", "hist_rel", "abs_bin", "rel_bin"):
+        assert np.array_equal(pg[k], po[k]), k
+    for k in ("abs_p", "rel_p"):
+        assert np.array_equal(pg[k].view(np.uint32), po[k].view(np.uint32)), k
+    assert pg["max_abs"] == po["max_abs"] and pg["max_rel"] == po["max_rel"] and pg["p_max"] == po["p_max"]
+    assert pg["n"] == n and abs(pg["p_max"] - 1 / 3) < 1e-6

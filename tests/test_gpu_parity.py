@@ -245,3 +245,66 @@ def test_check_special_values_and_clusters(tao, oracle_mod):
         po = oracle_mod.check_and_profile(_np(claimed), _np(ref), _np(tau), eps_rel=0.0)
         assert_profile_equal(pg, po, "single bin")
     assert po["hist"][(127 - 12) << 3] == n
+
+
+def _assert_error_profile_equal(pg, po, what):
+    for k in ("n", "nan_count", "offending"):
+        assert pg[k] == po[k], (what, k, pg[k], po[k])
+    for k in ("hist_abs", "hist_rel", "abs_bin", "rel_bin"):
+        assert np.array_equal(pg[k], po[k]), (what, k)
+    for k in ("abs_p", "rel_p"):
+        assert np.array_equal(pg[k].view(np.uint32), po[k].view(np.uint32)), (what, k, pg[k], po[k])
+    for k in ("max_abs", "max_rel", "p_max"):
+        a, b = np.float64(pg[k]), np.float64(po[k])
+        assert (np.isnan(a) and np.isnan(b)) or a == b, (what, k, a, b)
+
+
+@pytest.mark.parametrize("n,offset", [(0, 0), (1, 0), (7, 0), (1000, 1), ((1 << 20) + 3, 0), (300001, 3)])
+def test_profile_errors_sizes(tao, oracle_mod, n, offset):
+    """Error profiles on the 22-point grid and the selection statistic: bit-exact against the oracle
+    (integer histograms and ranks, IEEE binary64 per element and for the threshold quotients)."""
+    c, r, _ = tao_inputs.check_triplet("cpu", seed=2000 + n, n=n + offset)
+    c, r = c[offset:], r[offset:]
+    cg, rg = [torch.cat([torch.zeros(offset), v]).cuda()[offset:] if offset else v.cuda() for v in (c, r)]
+    for eps in (1e-12, 0.0, 1e-3):
+        pg = tao.tao_profile_errors(cg, rg, eps_rel=eps)
+        po = oracle_mod.profile_errors(_np(c), _np(r), eps_rel=eps)
+        _assert_error_profile_equal(pg, po, "errors n=%d eps=%g" % (n, eps))
+        assert np.isnan(pg["p_max"]) and pg["offending"] == 0
+    if n == 0:
+        return
+    # thresholds = alpha x the profile itself (threshold construction of Sec. 3.2, alpha = 3), then one
+    # entry pushed below the observed percentile
+    base = oracle_mod.profile_errors(_np(c), _np(r))
+    ta = (3 * base["abs_p"]).astype(np.float32); tr = (3 * base["rel_p"]).astype(np.float32)
+    for tweak in (False, True):
+        if tweak:
+            tr[10] = base["rel_p"][10] / np.float32(2)
+        pg = tao.tao_profile_errors(cg, rg, thr_abs=torch.from_numpy(ta).cuda(), thr_rel=torch.from_numpy(tr).cuda())
+        po = oracle_mod.profile_errors(_np(c), _np(r), thr_abs=ta, thr_rel=tr)
+        _assert_error_profile_equal(pg, po, "errors n=%d thresholds tweak=%s" % (n, tweak))
+    if n > 1000 and base["rel_p"][10] > 0:
+        assert po["offending"] == 1 and po["p_max"] == 2.0
+
+
+def test_profile_errors_special_values(tao, oracle_mod):
+    ref = torch.tensor([1.0, 0.0, 0.0, float("nan"), 1.0, float("inf"), 3e38, 1e-40, -2.0, 2.0])
+    claimed = torch.tensor([1.0, 0.0, 1.0, 1.0, float("nan"), float("inf"), -3e38, 0.0, -2.0000002, float("inf")])
+    for eps in (0.0, 1e-12, 1e10):
+        pg = tao.tao_profile_errors(claimed.cuda(), ref.cuda(), eps_rel=eps)
+        po = oracle_mod.profile_errors(_np(claimed), _np(ref), eps_rel=eps)
+        _assert_error_profile_equal(pg, po, "special eps=%g" % eps)
+    # identical outputs with zero thresholds: every quotient is 0/0 or 0/thr
+    z = torch.randn(5000)
+    ta = np.zeros(22, np.float32); tr = np.ones(22, np.float32)
+    pg = tao.tao_profile_errors(z.cuda(), z.cuda(), thr_abs=torch.from_numpy(ta).cuda(), thr_rel=torch.from_numpy(tr).cuda())
+    po = oracle_mod.profile_errors(_np(z), _np(z), thr_abs=ta, thr_rel=tr)
+    _assert_error_profile_equal(pg, po, "identical")
+    assert pg["p_max"] == 0.0 and pg["max_abs"] == 0.0
+    # every element in one bin, twice with the same buffers
+    n = 1 << 18
+    ref = torch.ones(n); claimed = torch.full((n,), 1.0 + 2.0 ** -12)
+    for _ in range(2):
+        pg = tao.tao_profile_errors(claimed.cuda(), ref.cuda(), eps_rel=0.0)
+        po = oracle_mod.profile_errors(_np(claimed), _np(ref), eps_rel=0.0)
+        _assert_error_profile_equal(pg, po, "single bin")
