@@ -61,8 +61,10 @@ template <int WM> struct Shape {
 struct LinArgs {
     const float* A; const float* W; const float* bias; float* tau;
     long M, N, K, lda, ldw, ldt, strideA, strideW, strideT;
+    unsigned tiles_n, tiles_m, ntiles;   // output tiles along N, along M, in all (x batch)
     int vecA, vecW;            // 16-byte global loads allowed
     int fast_ok;               // vecA && vecW && per-thread slab offsets fit in 32 bits
+    int all_clean;             // every tile interior and K a multiple of the group size
     double c;                  // Gamma(K'), upper
     double infl;               // reciprocal of the lower rounding factor of the accumulation
     double uflow;              // optional absolute underflow term
@@ -90,7 +92,15 @@ constexpr int kStages = 4;            // a power of two (stage index = group & 3
 
 #define TAO_MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0)
 
-template <bool TRANS_W, bool FAST, int WM>
+// CLEAN: every tile is interior and K is a multiple of the group size (decided by the host), so
+// every group takes the buffer-load path and the kernel holds no edge-handling code at all; the
+// general kernel keeps both paths.  (Separate kernels rather than a branch: with the
+// edge-handling loads in the same control flow the compiler's wait-count bookkeeping turns
+// conservative and waits for the youngest requests as well, and the scalar registers overflow.)
+// PERSIST: a workgroup walks several tiles (short K loops, where the start-up and the epilogue of
+// a tile would otherwise stay exposed); without it one workgroup computes one tile and the steady
+// loop carries no tile bookkeeping (measured 2 - 3 % faster for long K loops).
+template <bool TRANS_W, bool FAST, int WM, bool CLEAN, bool PERSIST>
 __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
     extern __shared__ __attribute__((aligned(16))) float lds[];
     constexpr int BM = Shape<WM>::kBM, WN = Shape<WM>::kWN, TN = Shape<WM>::kTN;
@@ -101,15 +111,25 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int r32 = lane & 31, h = lane >> 5;
-    const long m0 = (long)blockIdx.y * BM, n0 = (long)blockIdx.x * BN;
-    const float* __restrict__ A = p.A + (long)blockIdx.z * p.strideA;
-    const float* __restrict__ W = p.W + (long)blockIdx.z * p.strideW;
-    float* __restrict__ T = p.tau + (long)blockIdx.z * p.strideT;
-    // Interior tiles of aligned operands take unguarded 16-byte loads: a uniform slab base plus
-    // one 32-bit per-thread byte offset; the two vectors of a thread sit at a constant stride.
-    const bool interior = (m0 + BM <= p.M) && (n0 + BN <= p.N) && p.fast_ok;
 
-    // global -> register -> LDS mapping.  k-contiguous slab [128 rows][32]: thread -> rows
+    // A workgroup walks the output tiles blockIdx.x, blockIdx.x + gridDim.x, ... (tile index:
+    // column tile fastest, then row tile, then batch entry).  Its K loops are concatenated into
+    // one stream of 32-k-step groups, so the software pipeline below runs across tile boundaries:
+    // the first slabs of the next tile are requested while the current tile still computes, and
+    // only the epilogue (the bound of one tile written out) sits between two tiles.
+    const unsigned nwg = gridDim.x;
+    const unsigned my_tiles = !PERSIST ? 1u : (blockIdx.x < p.ntiles ? (p.ntiles - 1 - blockIdx.x) / nwg + 1 : 0u);
+    const long ngroup = (p.K + BK - 1) / BK;
+    const long total = (long)my_tiles * ngroup;            // groups of this workgroup
+    struct Origin { long m0, n0, z; };
+    auto origin = [&](unsigned t) __attribute__((always_inline)) {
+        const unsigned x = t % p.tiles_n, yz = t / p.tiles_n;
+        Origin o;
+        o.n0 = (long)x * BN; o.m0 = (long)(yz % p.tiles_m) * BM; o.z = yz / p.tiles_m;
+        return o;
+    };
+
+    // global -> register -> LDS mapping.  k-contiguous slab [rows][32]: thread -> rows
     // tid/8 + 64*i, columns 4*(tid%8): eight threads fetch 128 contiguous bytes of a row.
     // [k][n] slab of a transposed W: rows tid/32 + 16*i, columns 4*(tid%32).
     const int ld_row = tid >> 3, ld_k = (tid & 7) * 4;
@@ -120,27 +140,39 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
     const long strideWi = (TRANS_W ? 16 : 64) * p.ldw * 4;
     const int stA = ld_row * SA + ld_k;                                // + 64*SA*i
     const int stW = BM * SA + (TRANS_W ? lt_kr * SWT + lt_n : ld_row * SA + ld_k);   // + 16*SWT*i or 64*SA*i
-    const char* baseA = reinterpret_cast<const char*>(A + m0 * p.lda);
-    const char* baseW = reinterpret_cast<const char*>(TRANS_W ? W + n0 : W + n0 * p.ldw);
     const long slabW = TRANS_W ? (long)BK * p.ldw * 4 : (long)BK * 4;  // bytes per group along K
     // bytes one group's slab spans from its first element (both below 2^31 when fast_ok)
     const long spanA = ((long)(BM - 1) * p.lda + BK) * 4;
     const long spanW = TRANS_W ? ((long)(BK - 1) * p.ldw + BN) * 4 : ((long)(BN - 1) * p.ldw + BK) * 4;
 
+    // Request side of the pipeline: the tile and group of the next slab to request.  Slabs are
+    // requested strictly in stream order, one call of load_slab each.
+    unsigned l_tile = blockIdx.x;
+    long l_g = 0, l_m0 = 0, l_n0 = 0;
+    const float* l_A = p.A; const float* l_W = p.W;     // batch entry (edge path)
+    const char* l_pa = nullptr; const char* l_pw = nullptr;   // first byte of the next slab of A / W
+    bool l_interior = false;
+    auto set_load_tile = [&](unsigned t) __attribute__((always_inline)) {
+        const Origin o = origin(t);
+        l_m0 = o.m0; l_n0 = o.n0;
+        l_A = p.A + o.z * p.strideA; l_W = p.W + o.z * p.strideW;
+        l_pa = reinterpret_cast<const char*>(l_A + o.m0 * p.lda);
+        l_pw = reinterpret_cast<const char*>(TRANS_W ? l_W + o.n0 : l_W + o.n0 * p.ldw);
+        // Interior tiles of aligned operands take unguarded 16-byte loads
+        l_interior = (o.m0 + BM <= p.M) && (o.n0 + BN <= p.N) && p.fast_ok;
+    };
+    if (my_tiles > 0) set_load_tile(l_tile);
+
     // two register sets: the slab requested during group g is written to LDS during group g+2
     float4 ra0[kVecA], rw0[kVecW], ra1[kVecA], rw1[kVecW];
-    // CLEAN (a compile-time flag): the whole tile is interior and K is a multiple of the group
-    // size, so every group takes the buffer-load path and the loop holds no other load code.
-    auto load_slab = [&](auto clean, long g, float4* ra, float4* rw) __attribute__((always_inline)) {
-        const long k0 = g * BK;
-        if (decltype(clean)::value || (interior && k0 + BK <= p.K)) {
+    auto load_slab = [&](float4* ra, float4* rw) __attribute__((always_inline)) {
+        const long k0 = l_g * BK;
+        if (CLEAN || (l_interior && k0 + BK <= p.K)) {
             // Buffer loads: descriptor (uniform base of this group's slab) in SGPRs, one 32-bit
             // per-thread offset, the vector index as a scalar offset.  Next to FP32 MFMA this
             // form is nearly free, while loads with a 64-bit per-lane address stall the SIMD.
-            const __amdgpu_buffer_rsrc_t da = __builtin_amdgcn_make_buffer_rsrc(
-                const_cast<char*>(baseA + k0 * 4), 0, (int)spanA, 0x00020000);
-            const __amdgpu_buffer_rsrc_t dw = __builtin_amdgcn_make_buffer_rsrc(
-                const_cast<char*>(baseW + g * slabW), 0, (int)spanW, 0x00020000);
+            const __amdgpu_buffer_rsrc_t da = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(l_pa), 0, (int)spanA, 0x00020000);
+            const __amdgpu_buffer_rsrc_t dw = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(l_pw), 0, (int)spanW, 0x00020000);
 #pragma unroll
             for (int i = 0; i < kVecA; ++i)
                 ra[i] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(da, (int)offA, (int)(strideAi * i), 0));
@@ -150,11 +182,18 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
         } else {
 #pragma unroll
             for (int i = 0; i < kVecA; ++i)
-                ra[i] = gload(A, m0 + ld_row + 64 * i, p.M, p.lda, k0 + ld_k, p.K, p.vecA);
+                ra[i] = gload(l_A, l_m0 + ld_row + 64 * i, p.M, p.lda, k0 + ld_k, p.K, p.vecA);
 #pragma unroll
             for (int i = 0; i < kVecW; ++i)
-                rw[i] = TRANS_W ? gload(W, k0 + lt_kr + 16 * i, p.K, p.ldw, n0 + lt_n, p.N, p.vecW)
-                                : gload(W, n0 + ld_row + 64 * i, p.N, p.ldw, k0 + ld_k, p.K, p.vecW);
+                rw[i] = TRANS_W ? gload(l_W, k0 + lt_kr + 16 * i, p.K, p.ldw, l_n0 + lt_n, p.N, p.vecW)
+                                : gload(l_W, l_n0 + ld_row + 64 * i, p.N, p.ldw, k0 + ld_k, p.K, p.vecW);
+        }
+        // advance to the next slab of the stream (no memory operation here)
+        l_pa += BK * 4; l_pw += slabW;
+        ++l_g;
+        if (PERSIST && l_g == ngroup) {
+            l_g = 0; l_tile += nwg;
+            if (l_tile < p.ntiles) set_load_tile(l_tile);
         }
     };
     // registers -> LDS stage, sign bits cleared
@@ -176,14 +215,42 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
     // S: binary64 running sums (tight mode); c0: the single FP32 chain (fast mode)
     double S[TN][16];
     floatx16 c0[TN];
+    auto clear_sums = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int tj = 0; tj < TN; ++tj) {
+        for (int tj = 0; tj < TN; ++tj) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { S[tj][v] = 0.0; c0[tj][v] = 0.f; }
-    }
+            for (int v = 0; v < 16; ++v) { S[tj][v] = 0.0; c0[tj][v] = 0.f; }
+        }
+    };
+    clear_sums();
     floatx16 zero;
 #pragma unroll
     for (int v = 0; v < 16; ++v) zero[v] = 0.f;
+
+    // The bound of one finished tile: D[i][j] of a 32x32 tile sits in lane (j + 32*((i/4)%2)),
+    // register 4*(i/8) + i%4.
+    auto epilogue = [&](unsigned t) __attribute__((always_inline)) {
+        const Origin o = origin(t);
+        float* __restrict__ T = p.tau + o.z * p.strideT;
+#pragma unroll
+        for (int tj = 0; tj < TN; ++tj) {
+            const long col = o.n0 + (wn * TN + tj) * 32 + r32;
+            const double ab = (p.bias && col < p.N) ? fabs((double)p.bias[col]) : 0.0;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const long row = o.m0 + wm * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                if (row < p.M && col < p.N) {
+                    const double sv = FAST ? (double)c0[tj][v] : S[tj][v];
+                    const double tt = p.c * (sv * p.infl + ab) * kGuard + p.uflow;
+                    T[row * p.ldt + col] = up32(tt);
+                }
+            }
+        }
+    };
+    if (ngroup == 0) {                       // K == 0: tau = Gamma |bias|
+        for (unsigned i = 0; i < my_tiles; ++i) epilogue(blockIdx.x + i * nwg);
+        return;
+    }
 
     // Operand registers of one group: lane (r32, h) holds k = 16h .. 16h+15 of its A row and of
     // its W row in each tile; MFMA number i of the group multiplies element i of both.
@@ -215,19 +282,18 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
         }
     };
 
-    // Four LDS stages and two register sets.  Slab j (32 k-steps of both operands) is requested
-    // from global memory during group j-4, written to stage j%4 at the top of group j-2, and read
-    // into operand registers in three pieces: the W operands of tile 1 at the top of group j, the
-    // W operands of tile 0 in the middle of group j-1, the A operands at the end of group j-1.
-    // One barrier in the middle of every EVEN group is enough: between the write of a stage (top
-    // of group j-2) and its first read (middle of group j-1) lies the barrier of j-2 or of j-1,
-    // and between its last read as slab j-4 (top of group j-4) and that write lies the barrier of
-    // j-4 or of j-3.  Requests run two groups ahead of the registers' use, which covers the memory
-    // latency with a single workgroup per CU.  With one tile per wavefront (64-row workgroup
-    // tiles) the W operands of group j are read at the top of group j-1 into the buffer the
-    // current group does not use, and the barrier sits at the top of the even groups, right
-    // after the LDS write; the same two arguments hold.
-    const long ngroup = (p.K + BK - 1) / BK;
+    // Four LDS stages and two register sets.  Slab j of the stream (32 k-steps of both operands)
+    // is requested from global memory during group j-4, written to stage j%4 at the top of group
+    // j-2, and read into operand registers in three pieces: the W operands of tile 1 at the top
+    // of group j, the W operands of tile 0 in the middle of group j-1, the A operands at the end
+    // of group j-1.  One barrier in the middle of every EVEN group is enough: between the write
+    // of a stage (top of group j-2) and its first read (middle of group j-1) lies the barrier of
+    // j-2 or of j-1, and between its last read as slab j-4 (top of group j-4) and that write lies
+    // the barrier of j-4 or of j-3.  Requests run two groups ahead of the registers' use, which
+    // covers the memory latency with a single workgroup per CU.  With one tile per wavefront
+    // (64-row workgroup tiles) the W operands of group j are read at the top of group j-1 into
+    // the buffer the current group does not use, and the barrier sits at the top of the even
+    // groups, right after the LDS write; the same two arguments hold.
     auto stage = [&](long j) __attribute__((always_inline)) { return lds + (int)(j & (kStages - 1)) * kStageFloats; };
     // the MFMA / vector-ALU work of one 32x32 tile over one group: accumulator `acc`, W operands
     // from fb[buf]; `last`: the group's last tile, which requests the next group's A operands
@@ -237,6 +303,7 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) c0[acc] = TAO_MFMA(fa[i], fb[buf][i], c0[acc]);
             if (last && have_next) read_a(stage(g + 1));
+            __builtin_amdgcn_sched_barrier(0);
         } else {
             floatx16 x, z;
 #pragma unroll
@@ -272,14 +339,17 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
             }
         }
     };
-    // one group; (ra, rw) is the register set of the group's parity (`even`, compile time)
-    auto group = [&](auto clean, auto steady, auto even_t, long g, float4* ra, float4* rw) __attribute__((always_inline)) {
+    // Compute side of the pipeline: tile and group of the group being consumed.
+    unsigned c_tile = blockIdx.x;
+    long c_g = 0;
+    // one group of the stream; (ra, rw) is the register set of the group's parity (`even`)
+    auto group = [&](auto steady, auto even_t, long g, float4* ra, float4* rw) __attribute__((always_inline)) {
         // steady (compile time): groups g+1 .. g+4 exist, so nothing below is conditional
         constexpr bool ST = decltype(steady)::value;
         constexpr bool even = decltype(even_t)::value;
-        const bool have_next = ST || g + 1 < ngroup;
-        if (ST || g + 2 < ngroup) commit(stage(g + 2), ra, rw);
-        if (ST || g + 4 < ngroup) load_slab(clean, g + 4, ra, rw);
+        const bool have_next = ST || g + 1 < total;
+        if (ST || g + 2 < total) commit(stage(g + 2), ra, rw);
+        if (ST || g + 4 < total) load_slab(ra, rw);
         if (TN == 2) {
             read_b(stage(g), 1);                          // W operands of this group's tile 1
             tile(0, 0, false, have_next, g);
@@ -293,82 +363,67 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
             if (have_next) read_b(stage(g + 1), even ? 1 : 0);
             tile(0, even ? 0 : 1, true, have_next, g);
         }
+        if (PERSIST && ++c_g == ngroup) {    // last group of an output tile
+            epilogue(c_tile);
+            clear_sums();
+            c_g = 0; c_tile += nwg;
+        }
     };
-    // Two copies of the whole pipeline: with the edge-handling loads in the same control flow
-    // the compiler's wait-count bookkeeping turns conservative and waits for the youngest
-    // requests as well, which would expose the memory latency in every group.
-    auto pipeline = [&](auto clean) __attribute__((always_inline)) {
+    {
         long g = 0;
-        if (ngroup >= 6) {
+        if (total >= 6) {
             // Steady state: every request, LDS write and LDS read is unconditional, from the
             // prologue on, so the wait counts the compiler derives are exact (one conditional
             // request on any path into the loop makes it wait for all outstanding requests,
             // which halves the distance between a request and its use).
-            load_slab(clean, 0, ra0, rw0); load_slab(clean, 1, ra1, rw1);     // one round trip for both
+            load_slab(ra0, rw0); load_slab(ra1, rw1);     // one round trip for both
             commit(stage(0), ra0, rw0); commit(stage(1), ra1, rw1);
-            load_slab(clean, 2, ra0, rw0);
-            load_slab(clean, 3, ra1, rw1);
+            load_slab(ra0, rw0);
+            load_slab(ra1, rw1);
             __syncthreads();
             read_a(stage(0)); read_b(stage(0), 0);
 #pragma unroll 1
-            for (; g + 5 < ngroup; g += 2) {
-                group(clean, std::true_type(), std::true_type(), g, ra0, rw0);
-                group(clean, std::true_type(), std::false_type(), g + 1, ra1, rw1);
+            for (; g + 5 < total; g += 2) {
+                group(std::true_type(), std::true_type(), g, ra0, rw0);
+                group(std::true_type(), std::false_type(), g + 1, ra1, rw1);
             }
         } else {
-            if (ngroup > 0) load_slab(clean, 0, ra0, rw0);
-            if (ngroup > 1) load_slab(clean, 1, ra1, rw1);
-            if (ngroup > 0) commit(stage(0), ra0, rw0);
-            if (ngroup > 1) commit(stage(1), ra1, rw1);
-            if (ngroup > 2) load_slab(clean, 2, ra0, rw0);
-            if (ngroup > 3) load_slab(clean, 3, ra1, rw1);
+            if (total > 0) load_slab(ra0, rw0);
+            if (total > 1) load_slab(ra1, rw1);
+            if (total > 0) commit(stage(0), ra0, rw0);
+            if (total > 1) commit(stage(1), ra1, rw1);
+            if (total > 2) load_slab(ra0, rw0);
+            if (total > 3) load_slab(ra1, rw1);
             __syncthreads();
-            if (ngroup > 0) { read_a(stage(0)); read_b(stage(0), 0); }
+            if (total > 0) { read_a(stage(0)); read_b(stage(0), 0); }
         }
         // the last groups (all of them when there are fewer than six): conditional copy
 #pragma unroll 1
-        for (; g < ngroup; g += 2) {
-            group(clean, std::false_type(), std::true_type(), g, ra0, rw0);
-            if (g + 1 < ngroup) group(clean, std::false_type(), std::false_type(), g + 1, ra1, rw1);
-        }
-    };
-    if (interior && p.K % BK == 0) pipeline(std::true_type());
-    else pipeline(std::false_type());
-
-    // epilogue: D[i][j] of a 32x32 tile sits in lane (j + 32*((i/4)%2)), register 4*(i/8) + i%4
-#pragma unroll
-    for (int tj = 0; tj < TN; ++tj) {
-        const long col = n0 + (wn * TN + tj) * 32 + r32;
-        const double ab = (p.bias && col < p.N) ? fabs((double)p.bias[col]) : 0.0;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const long row = m0 + wm * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-            if (row < p.M && col < p.N) {
-                const double sv = FAST ? (double)c0[tj][v] : S[tj][v];
-                const double t = p.c * (sv * p.infl + ab) * kGuard + p.uflow;
-                T[row * p.ldt + col] = up32(t);
-            }
+        for (; g < total; g += 2) {
+            group(std::false_type(), std::true_type(), g, ra0, rw0);
+            if (g + 1 < total) group(std::false_type(), std::false_type(), g + 1, ra1, rw1);
         }
     }
+    if (!PERSIST) epilogue(blockIdx.x);
 }
 
-template <bool TRANS_W, bool FAST, int WM>
+template <bool TRANS_W, bool FAST, int WM, bool CLEAN, bool PERSIST>
 static hipError_t launch_absgemm(dim3 grid, hipStream_t st, const LinArgs& p) {
     constexpr size_t lds_bytes = (size_t)kStages * Shape<WM>::kStageFloats * sizeof(float);
     static bool configured = false;      // raise the dynamic LDS limit once per instantiation
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_bound<TRANS_W, FAST, WM>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_bound<TRANS_W, FAST, WM, CLEAN, PERSIST>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((absgemm_bound<TRANS_W, FAST, WM>), grid, dim3(kLinThreads), lds_bytes, st, p);
+    hipLaunchKernelGGL((absgemm_bound<TRANS_W, FAST, WM, CLEAN, PERSIST>), grid, dim3(kLinThreads), lds_bytes, st, p);
     return hipSuccess;
 }
-template <int WM>
+template <int WM, bool CLEAN, bool PERSIST>
 static hipError_t launch_shape(bool trans_w, bool fast, dim3 grid, hipStream_t st, const LinArgs& p) {
-    if (trans_w) return fast ? launch_absgemm<true, true, WM>(grid, st, p) : launch_absgemm<true, false, WM>(grid, st, p);
-    return fast ? launch_absgemm<false, true, WM>(grid, st, p) : launch_absgemm<false, false, WM>(grid, st, p);
+    if (trans_w) return fast ? launch_absgemm<true, true, WM, CLEAN, PERSIST>(grid, st, p) : launch_absgemm<true, false, WM, CLEAN, PERSIST>(grid, st, p);
+    return fast ? launch_absgemm<false, true, WM, CLEAN, PERSIST>(grid, st, p) : launch_absgemm<false, false, WM, CLEAN, PERSIST>(grid, st, p);
 }
 
 // ---- matrix-core self test ----------------------------------------------------------------
@@ -399,7 +454,6 @@ int tao_bound_linear(const float* A, const float* W, const float* bias, float* t
     if (lda < K || ldt < N || ldw < (trans_w ? N : K)) return TAO_ERR_SHAPE;
     if (strideA < 0 || strideW < 0 || strideT < 0) return TAO_ERR_SHAPE;
     if (batch > 1 && strideT < M * ldt - (ldt - N)) return TAO_ERR_SHAPE;   // outputs would overlap
-    if (batch > 65535) return TAO_ERR_SHAPE;
     const long Kp = K + (bias ? 1 : 0);
     const double c = gamma_up(Kp, md);
     if (!(c == c)) return TAO_ERR_K_RANGE;
@@ -435,11 +489,24 @@ int tao_bound_linear(const float* A, const float* W, const float* bias, float* t
     const long tiles128 = tiles_n * ((M + 127) / 128) * batch;
     const bool small = tiles128 <= 192 && M > 64;
     const long bm = small ? 64 : 128;
-    dim3 grid((unsigned)tiles_n, (unsigned)((M + bm - 1) / bm), (unsigned)batch);
-    if (grid.y > 65535u) return TAO_ERR_SHAPE;
+    const long tiles_m = (M + bm - 1) / bm;
+    const long ntiles = tiles_n * tiles_m * batch;
+    if (ntiles >= (1L << 31)) return TAO_ERR_SHAPE;
+    p.tiles_n = (unsigned)tiles_n; p.tiles_m = (unsigned)tiles_m; p.ntiles = (unsigned)ntiles;
+    p.all_clean = p.fast_ok && (M % bm == 0) && (N % BN == 0) && (K % BK == 0);
+    // One workgroup per CU walks several tiles when every tile is regular and the K loop is short
+    // (its pipeline then runs across tile boundaries); otherwise one workgroup per tile.
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (cus < 1) cus = 256;
+    const bool persist = p.all_clean && ntiles > cus && K <= 32 * BK;
+    dim3 grid((unsigned)(persist ? cus : ntiles));
     hipStream_t st = (hipStream_t)stream;
-    const hipError_t e = small ? launch_shape<2>(trans_w != 0, fast, grid, st, p)
-                               : launch_shape<4>(trans_w != 0, fast, grid, st, p);
+    const bool tw = trans_w != 0;
+    hipError_t e;
+    if (persist)          e = small ? launch_shape<2, true, true>(tw, fast, grid, st, p) : launch_shape<4, true, true>(tw, fast, grid, st, p);
+    else if (p.all_clean) e = small ? launch_shape<2, true, false>(tw, fast, grid, st, p) : launch_shape<4, true, false>(tw, fast, grid, st, p);
+    else                  e = small ? launch_shape<2, false, false>(tw, fast, grid, st, p) : launch_shape<4, false, false>(tw, fast, grid, st, p);
     if (e != hipSuccess) { g_last_hip_error = (int)e; return TAO_ERR_LAUNCH; }
     return launch_status();
 }
