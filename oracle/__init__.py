@@ -93,6 +93,8 @@ def lib():
                                           ctypes.POINTER(ErrorProfile)]
         L.taoo_error_profile_size.restype = ctypes.c_size_t
         assert L.taoo_error_profile_size() == ctypes.sizeof(ErrorProfile)
+        L.taoo_calibrate_thresholds.argtypes = [ctypes.POINTER(ErrorProfile), ctypes.c_long, ctypes.c_double,
+                                                fp, fp, fp, fp]
         L.taoo_num_threads.restype = ctypes.c_int
         L.taoo_profile_size.restype = ctypes.c_size_t
         assert L.taoo_profile_size() == ctypes.sizeof(Profile)
@@ -203,6 +205,22 @@ def profile_errors(claimed, ref, eps_rel=1e-12, thr_abs=None, thr_rel=None):
     _chk(lib().taoo_profile_errors(_p(claimed), _p(ref), claimed.size, float(eps_rel), _p(ta), _p(tr),
                                    ctypes.byref(out)))
     return out.as_dict()
+
+
+def calibrate_thresholds(profiles, alpha=3.0):
+    """Max-envelope of the 22-point profiles of several runs and the alpha-scaled thresholds
+    (Sec. 3.2).  profiles: list of (abs_p, rel_p) pairs of 22 float32 values each.
+    Returns (env_abs, env_rel, thr_abs, thr_rel)."""
+    arr = (ErrorProfile * len(profiles))()
+    for i, (a, r) in enumerate(profiles):
+        a = _f32(a); r = _f32(r)
+        assert a.size == NGRID and r.size == NGRID
+        for g in range(NGRID):
+            arr[i].abs_p[g] = float(a[g]) if a[g] == a[g] else float("nan")
+            arr[i].rel_p[g] = float(r[g]) if r[g] == r[g] else float("nan")
+    out = [np.empty(NGRID, np.float32) for _ in range(4)]
+    _chk(lib().taoo_calibrate_thresholds(arr, len(profiles), float(alpha), *[_p(o) for o in out]))
+    return tuple(out)
 
 
 def num_threads():

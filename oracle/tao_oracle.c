@@ -583,6 +583,38 @@ int taoo_profile_errors(const float *claimed, const float *ref, long n, double e
 }
 size_t taoo_error_profile_size(void) { return sizeof(taoo_error_profile); }
 
+/* ------------------------------------------------- calibration: envelope and thresholds */
+/* Sec. 3.2: the device- and input-agnostic profile of an operator is the max-envelope, per grid
+ * point p, of the percentile profiles of all (device pair, input) runs,
+ *   P_abs(p) = max_r P_abs^(r)(p),   P_rel(p) = max_r P_rel^(r)(p),
+ * and the committed thresholds are alpha times it (alpha = 3 in the paper):
+ *   thr_abs(p) = alpha P_abs(p),     thr_rel(p) = alpha P_rel(p).
+ * Here: NaN profile entries are skipped by the maximum (NaN only if every run is NaN there);
+ * the product is one IEEE binary64 multiplication, rounded UP to binary32, so a threshold is
+ * never below alpha times the envelope.  count >= 1, alpha >= 0. */
+int taoo_calibrate_thresholds(const taoo_error_profile *profiles, long count, double alpha,
+                              float *env_abs, float *env_rel, float *thr_abs, float *thr_rel) {
+    if (count < 1 || !(alpha >= 0.0)) return -1;
+    int saved = fegetround(); fesetround(FE_TONEAREST);
+    for (int g = 0; g < TAOO_NGRID; ++g) {
+        float ma = NAN, mr = NAN;
+        for (long r = 0; r < count; ++r) {
+            float a = profiles[r].abs_p[g], e = profiles[r].rel_p[g];
+            if (a == a && !(ma >= a)) ma = a;
+            if (e == e && !(mr >= e)) mr = e;
+        }
+        if (env_abs) env_abs[g] = ma;
+        if (env_rel) env_rel[g] = mr;
+        volatile double ta = alpha * (double)ma, tr = alpha * (double)mr;
+        fesetround(FE_UPWARD);
+        volatile float fa = (float)ta, fr = (float)tr;      /* smallest binary32 >= product */
+        fesetround(FE_TONEAREST);
+        thr_abs[g] = fa; thr_rel[g] = fr;
+    }
+    fesetround(saved);
+    return 0;
+}
+
 int taoo_num_threads(void) {
 #ifdef _OPENMP
     return omp_get_max_threads();

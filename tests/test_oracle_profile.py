@@ -99,3 +99,61 @@ def test_nan_and_empty(oracle_mod):
     assert np.isnan(p["rel_p"][-1])           # the largest rank lands in the NaN bin
     e = oracle_mod.profile_errors(np.zeros(0, f32), np.zeros(0, f32))
     assert e["n"] == 0 and e["hist_abs"].sum() == 0
+
+
+# ---------------------------------------------------------------- calibration (Sec. 3.2)
+
+def test_envelope_is_the_pointwise_maximum(oracle_mod):
+    rng = np.random.Generator(np.random.Philox(46))
+    runs = [(rng.random(22).astype(f32), rng.random(22).astype(f32)) for _ in range(7)]
+    ea, er, ta, tr = oracle_mod.calibrate_thresholds(runs, alpha=3.0)
+    assert np.array_equal(ea, np.max([a for a, _ in runs], axis=0))
+    assert np.array_equal(er, np.max([r for _, r in runs], axis=0))
+    # thresholds: never below 3 x envelope, and within one binary32 step of it
+    for env, thr in ((ea, ta), (er, tr)):
+        exact = 3.0 * env.astype(np.float64)
+        assert np.all(thr.astype(np.float64) >= exact)
+        assert np.all(thr.astype(np.float64) <= exact * (1 + 2.0 ** -23))
+    # order of the runs does not matter; one more run never lowers a threshold
+    ea2, er2, ta2, tr2 = oracle_mod.calibrate_thresholds(runs[::-1], alpha=3.0)
+    assert np.array_equal(ta, ta2) and np.array_equal(tr, tr2)
+    more = runs + [(rng.random(22).astype(f32) * 2, rng.random(22).astype(f32) * 2)]
+    _, _, ta3, tr3 = oracle_mod.calibrate_thresholds(more, alpha=3.0)
+    assert np.all(ta3 >= ta) and np.all(tr3 >= tr) and np.any(ta3 > ta)
+
+
+def test_threshold_values_by_hand(oracle_mod):
+    a = np.full(22, 0.25, f32); r = np.full(22, 2.0 ** -20, f32)
+    b = np.full(22, 0.125, f32); q = np.full(22, 2.0 ** -19, f32)
+    ea, er, ta, tr = oracle_mod.calibrate_thresholds([(a, r), (b, q)], alpha=3.0)
+    assert np.all(ea == 0.25) and np.all(er == f32(2.0 ** -19))
+    assert np.all(ta == 0.75) and np.all(tr == f32(3 * 2.0 ** -19))        # exact products
+    # a product that is not a binary32 number is rounded up: 3 x (1 + 2^-23) = 3 + 3 x 2^-23
+    x = np.full(22, 1 + 2.0 ** -23, f32)
+    _, _, t, _ = oracle_mod.calibrate_thresholds([(x, x)], alpha=3.0)
+    assert np.all(t == f32(3 + 4 * 2.0 ** -23)) and np.all(t.astype(np.float64) > 3 * (1 + 2.0 ** -23))
+    # NaN entries are skipped unless every run is NaN there; infinities propagate
+    n1 = a.copy(); n1[3] = np.nan; n2 = b.copy(); n2[3] = np.nan; n2[5] = np.inf
+    ea, _, ta, _ = oracle_mod.calibrate_thresholds([(n1, r), (n2, q)], alpha=2.0)
+    assert np.isnan(ea[3]) and np.isnan(ta[3]) and ea[5] == np.inf and ta[5] == np.inf and ea[4] == 0.25
+    n2[3] = 0.5
+    ea, _, ta, _ = oracle_mod.calibrate_thresholds([(n1, r), (n2, q)], alpha=2.0)
+    assert ea[3] == 0.5 and ta[3] == 1.0
+    with pytest.raises(ValueError):
+        oracle_mod.calibrate_thresholds([], alpha=3.0)
+
+
+def test_calibrated_runs_are_never_offending(oracle_mod):
+    """Thresholds built from a set of runs accept every one of those runs with p_max <= 1/alpha
+    (the property the paper relies on: honest executions on calibrated hardware never trip the
+    selection rule), and a run with 10x larger errors is offending."""
+    rng = np.random.Generator(np.random.Philox(47))
+    ref = rng.standard_normal(20000).astype(f32)
+    runs = [(ref * (1 + s * rng.standard_normal(20000))).astype(f32) for s in (1e-6, 2e-6, 5e-7, 3e-6)]
+    profs = [oracle_mod.profile_errors(c, ref) for c in runs]
+    _, _, ta, tr = oracle_mod.calibrate_thresholds([(p["abs_p"], p["rel_p"]) for p in profs], alpha=3.0)
+    for c in runs:
+        p = oracle_mod.profile_errors(c, ref, thr_abs=ta, thr_rel=tr)
+        assert p["offending"] == 0 and p["p_max"] <= 1 / 3 + 1e-7
+    bad = (ref * (1 + 3e-5 * rng.standard_normal(20000))).astype(f32)
+    assert oracle_mod.profile_errors(bad, ref, thr_abs=ta, thr_rel=tr)["offending"] == 1
