@@ -207,6 +207,18 @@ int tao_profile_errors(const float *claimed, const float *ref, long n, double ep
                        void *ws, size_t ws_bytes, void *stream);
 size_t tao_profile_workspace_bytes(long n);
 
+/* Offline calibration of an operator's thresholds (Sec. 3.2): `profiles` is a DEVICE array of
+ * `count` >= 1 results of tao_profile_errors (one per device pair and input).  Per grid point
+ *     env_abs(p) = max over the runs of abs_p(p),   env_rel(p) likewise (NaN entries are skipped;
+ *                  NaN only if every run is NaN there),
+ *     thr_abs(p) = alpha * env_abs(p),  thr_rel(p) = alpha * env_rel(p)   (alpha = 3 in the paper),
+ * the product being one binary64 multiplication rounded UP to binary32, so that a threshold is never
+ * below alpha times the envelope.  env_abs / env_rel (DEVICE, 22 values, may be NULL) receive the
+ * envelope, thr_abs / thr_rel (DEVICE, 22 values) the thresholds, in the form tao_profile_errors
+ * takes them.  alpha must be finite and >= 0. */
+int tao_calibrate_thresholds(const tao_error_profile *profiles, long count, double alpha,
+                             float *env_abs, float *env_rel, float *thr_abs, float *thr_rel, void *stream);
+
 /* Runs crafted inputs through the FP32 matrix-core instruction and reports, as
  * a bit mask in *report (HOST pointer), which modelling assumptions of the
  * linear bound's inflation hold on this device: bit 0 accumulation rounds to

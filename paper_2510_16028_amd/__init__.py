@@ -89,6 +89,7 @@ class TaoError(RuntimeError):
 EXPORTS = ["tao_default_model", "tao_gamma", "tao_bound_linear", "tao_bound_softmax",
            "tao_bound_norm", "tao_bound_act", "tao_check_and_profile",
            "tao_check_workspace_bytes", "tao_profile_errors", "tao_profile_workspace_bytes",
+           "tao_calibrate_thresholds",
            "tao_selftest_matrix_core", "tao_last_hip_error", "tao_status_string"]
 
 _lib = None
@@ -118,6 +119,7 @@ def lib():
     L.tao_check_workspace_bytes.argtypes = [lg]
     L.tao_check_workspace_bytes.restype = ctypes.c_size_t
     L.tao_profile_errors.argtypes = [vp, vp, lg, dbl, vp, vp, vp, vp, ctypes.c_size_t, vp]
+    L.tao_calibrate_thresholds.argtypes = [vp, lg, dbl, vp, vp, vp, vp, vp]
     L.tao_profile_workspace_bytes.argtypes = [lg]
     L.tao_profile_workspace_bytes.restype = ctypes.c_size_t
     L.tao_selftest_matrix_core.argtypes = [ctypes.POINTER(ctypes.c_uint), vp]
@@ -370,6 +372,22 @@ def tao_profile_errors(claimed, ref, eps_rel=1e-12, thr_abs=None, thr_rel=None, 
     if not readback:
         return out
     return ErrorProfile.from_buffer_copy(out.cpu().numpy().tobytes()).as_dict()
+
+
+def tao_calibrate_thresholds(profiles, alpha=3.0):
+    """profiles: uint8 CUDA tensor holding `count` consecutive tao_error_profile structs (the
+    `out` buffers of tao_profile_errors, e.g. rows of one [count, sizeof] tensor).
+    Returns (env_abs, env_rel, thr_abs, thr_rel) as float32 CUDA tensors of 22 values."""
+    torch = _torch()
+    size = ctypes.sizeof(ErrorProfile)
+    if not (isinstance(profiles, torch.Tensor) and profiles.is_cuda and profiles.dtype == torch.uint8
+            and profiles.is_contiguous() and profiles.numel() % size == 0):
+        raise TypeError("profiles must be a contiguous uint8 CUDA tensor of whole tao_error_profile structs")
+    count = profiles.numel() // size
+    outs = [torch.empty(NGRID, dtype=torch.float32, device=profiles.device) for _ in range(4)]
+    rc = lib().tao_calibrate_thresholds(_ptr(profiles), count, float(alpha), *[_ptr(o) for o in outs], _stream())
+    _check(rc, "tao_calibrate_thresholds")
+    return tuple(outs)
 
 
 def tao_profile_workspace_bytes(n):

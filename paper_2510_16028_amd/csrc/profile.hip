@@ -152,9 +152,42 @@ __global__ __launch_bounds__(256) void errors_finalize(const ErrStats* __restric
     out->offending = (pmax > 1.0) ? 1u : 0u;
 }
 
+// Calibration (Sec. 3.2): per grid point the maximum over the runs' percentile values (NaN entries
+// skipped) and alpha times it, the product one binary64 multiplication rounded up to binary32.
+// One thread per (kind, grid point); the runs are read with independent strided loads.
+__global__ __launch_bounds__(64) void calibrate_kernel(const tao_error_profile* __restrict__ profiles, long count,
+                                                       double alpha, float* __restrict__ env_abs,
+                                                       float* __restrict__ env_rel, float* __restrict__ thr_abs,
+                                                       float* __restrict__ thr_rel) {
+    const int t = threadIdx.x;
+    if (t >= 2 * kGrid) return;
+    const bool rel = t >= kGrid;
+    const int g = rel ? t - kGrid : t;
+    float m = NAN;
+    for (long r = 0; r < count; ++r) {
+        const float v = rel ? profiles[r].rel_p[g] : profiles[r].abs_p[g];
+        if (v == v && !(m >= v)) m = v;
+    }
+    float* env = rel ? env_rel : env_abs;
+    if (env) env[g] = m;
+    (rel ? thr_rel : thr_abs)[g] = up32(alpha * (double)m);
+}
+
 }  // namespace tao
 
 extern "C" {
+
+int tao_calibrate_thresholds(const tao_error_profile* profiles, long count, double alpha,
+                             float* env_abs, float* env_rel, float* thr_abs, float* thr_rel, void* stream) {
+    using namespace tao;
+    if (count < 1 || !(alpha >= 0.0) || !std::isfinite(alpha)) return TAO_ERR_SHAPE;
+    if (!profiles || !thr_abs || !thr_rel) return TAO_ERR_NULL;
+    if (!aligned(profiles, 8) || !aligned(env_abs, 4) || !aligned(env_rel, 4) || !aligned(thr_abs, 4) || !aligned(thr_rel, 4))
+        return TAO_ERR_ALIGN;
+    hipLaunchKernelGGL(calibrate_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, profiles, count, alpha,
+                       env_abs, env_rel, thr_abs, thr_rel);
+    return launch_status();
+}
 
 size_t tao_profile_workspace_bytes(long n) {
     (void)n;

@@ -114,6 +114,12 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_profile_errors(p, nul, 10, 0.0, nul, nul, p, ws, need, None) == tao.ERR_NULL
     assert L.tao_profile_errors(p, p, -1, 0.0, nul, nul, p, ws, need, None) == tao.ERR_SHAPE
     assert L.tao_profile_errors(odd, p, 10, 0.0, nul, nul, p, ws, need, None) == tao.ERR_ALIGN
+    # calibration
+    assert L.tao_calibrate_thresholds(p, 0, 3.0, nul, nul, p, p, None) == tao.ERR_SHAPE
+    assert L.tao_calibrate_thresholds(p, 2, -1.0, nul, nul, p, p, None) == tao.ERR_SHAPE
+    assert L.tao_calibrate_thresholds(nul, 2, 3.0, nul, nul, p, p, None) == tao.ERR_NULL
+    assert L.tao_calibrate_thresholds(p, 2, 3.0, nul, nul, nul, p, None) == tao.ERR_NULL
+    assert L.tao_calibrate_thresholds(odd, 2, 3.0, nul, nul, p, p, None) == tao.ERR_ALIGN
     for code in range(0, -9, -1):
         assert L.tao_status_string(code)
     assert L.tao_selftest_matrix_core(None, None) == tao.ERR_NULL

@@ -308,3 +308,37 @@ def test_profile_errors_special_values(tao, oracle_mod):
         pg = tao.tao_profile_errors(claimed.cuda(), ref.cuda(), eps_rel=0.0)
         po = oracle_mod.profile_errors(_np(claimed), _np(ref), eps_rel=0.0)
         _assert_error_profile_equal(pg, po, "single bin")
+
+
+def test_calibration_envelope_and_thresholds(tao, oracle_mod):
+    """Calibration loop of Sec. 3.2 on the device: profiles of several runs -> envelope -> thresholds,
+    bit-exact against the oracle; the thresholds then accept every calibration run."""
+    import ctypes
+    rng = np.random.Generator(np.random.Philox(48))
+    ref = torch.from_numpy(rng.standard_normal(70001).astype(np.float32))
+    runs = [(ref * (1 + s * torch.from_numpy(rng.standard_normal(70001).astype(np.float32)))) for s in (1e-6, 2e-6, 5e-7, 3e-6, 1e-6)]
+    size = ctypes.sizeof(tao.ErrorProfile)
+    bufs = torch.empty((len(runs), size), dtype=torch.uint8, device="cuda")
+    for i, c in enumerate(runs):
+        tao.tao_profile_errors(c.cuda(), ref.cuda(), out=bufs[i], readback=False)
+    for alpha in (3.0, 1.0, 2.5):
+        ea, er, ta, tr = [_np(t) for t in tao.tao_calibrate_thresholds(bufs, alpha=alpha)]
+        profs = [oracle_mod.profile_errors(_np(c), _np(ref)) for c in runs]
+        oa, orr, ota, otr = oracle_mod.calibrate_thresholds([(p["abs_p"], p["rel_p"]) for p in profs], alpha=alpha)
+        for g, o in ((ea, oa), (er, orr), (ta, ota), (tr, otr)):
+            assert np.array_equal(g.view(np.uint32), o.view(np.uint32))
+    ea, er, ta, tr = tao.tao_calibrate_thresholds(bufs, alpha=3.0)
+    for c in runs:
+        p = tao.tao_profile_errors(c.cuda(), ref.cuda(), thr_abs=ta, thr_rel=tr)
+        assert p["offending"] == 0 and p["p_max"] <= 1 / 3 + 1e-7
+    bad = ref * (1 + 3e-5 * torch.from_numpy(rng.standard_normal(70001).astype(np.float32)))
+    assert tao.tao_profile_errors(bad.cuda(), ref.cuda(), thr_abs=ta, thr_rel=tr)["offending"] == 1
+    # a single run and NaN handling: a run whose profile is NaN at the top (NaN errors) is skipped there
+    c = runs[0].clone(); c[5] = float("nan")
+    tao.tao_profile_errors(c.cuda(), ref.cuda(), out=bufs[0], readback=False)
+    ea, er, ta, tr = [_np(t) for t in tao.tao_calibrate_thresholds(bufs[:2], alpha=3.0)]
+    profs = [oracle_mod.profile_errors(_np(c), _np(ref)), oracle_mod.profile_errors(_np(runs[1]), _np(ref))]
+    oa, orr, ota, otr = oracle_mod.calibrate_thresholds([(p["abs_p"], p["rel_p"]) for p in profs], alpha=3.0)
+    assert np.isnan(profs[0]["rel_p"][-1]) and not np.isnan(orr[-1])
+    for g, o in ((ea, oa), (er, orr), (ta, ota), (tr, otr)):
+        assert np.array_equal(g.view(np.uint32), o.view(np.uint32))
