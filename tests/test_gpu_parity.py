@@ -104,6 +104,32 @@ def test_linear_shapes(tao, oracle_mod, M, N, K, bias, trans_w, batch):
     assert_bound_parity(_np(t_gpu), t_or, "linear %s" % ((M, N, K, bias, trans_w, batch),))
 
 
+@pytest.mark.parametrize("M,N,K,bias,trans_w,batch", [
+    (2048, 2560, 64, True, False, 1),      # 320 tiles of 128 rows: persistent walk, several groups per tile
+    (2048, 2560, 96, False, True, 1),      # same with W stored K x N
+    (2048, 1280, 160, True, True, 1),      # 64-row tiles (few 128-row tiles), persistent
+    (512, 640, 32, False, False, 5),       # batched, one k-slab per tile: the shortest pipeline
+    (384, 384, 224, True, False, 3),       # batched 64-row tiles, odd number of groups
+    (1024, 1536, 64, False, True, 2),      # batched, 64-row tiles, persistent across batch entries
+    (1024, 1024, 1056, False, False, 1),   # just past the persistent limit: one tile per workgroup
+])
+def test_linear_aligned_tile_walks(tao, oracle_mod, M, N, K, bias, trans_w, batch):
+    """Aligned shapes take the buffer-load pipeline; with more tiles than compute units and a
+    short K loop each workgroup walks several tiles. Every element against the oracle."""
+    g = torch.Generator().manual_seed(M + 7 * N + 13 * K + batch)
+    A = torch.randn((batch, M, K), generator=g)
+    W = torch.randn((batch, K, N) if trans_w else (batch, N, K), generator=g)
+    b = torch.randn((N,), generator=g) if bias else None
+    if batch == 1:
+        A, W = A[0], W[0]
+    t_or = oracle_mod.bound_linear(_np(A), _np(W), None if b is None else _np(b), trans_w=trans_w)
+    t_gpu = tao.tao_bound_linear(A.cuda(), W.cuda(), None if b is None else b.cuda(), trans_w=trans_w)
+    assert_bound_parity(_np(t_gpu), t_or, "linear %s" % ((M, N, K, bias, trans_w, batch),))
+    fast = tao.tao_bound_linear(A.cuda(), W.cuda(), None if b is None else b.cuda(), trans_w=trans_w,
+                                model=tao.FpModel(flags=tao.FLAG_FAST_ACCUM))
+    assert_bound_parity(_np(fast), t_or, "fast", rel_tol=2.5 * max(K, 1) * 2.0 ** -24)
+
+
 def test_linear_unaligned_views_and_modes(tao, oracle_mod):
     g = torch.Generator().manual_seed(77)
     Abig = torch.randn((150, 203), generator=g).cuda()
