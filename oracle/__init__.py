@@ -83,6 +83,7 @@ def lib():
         L.taoo_bound_linear.argtypes = [fp, fp, fp, fp] + [ctypes.c_long] * 6 + [ctypes.c_int] + \
             [ctypes.c_long] * 4 + [mp]
         L.taoo_bound_softmax.argtypes = [fp, fp, fp, ctypes.c_long, ctypes.c_long, ctypes.c_long, mp]
+        L.taoo_bound_conv2d.argtypes = [fp, fp, fp, fp] + [ctypes.c_long] * 13 + [mp]
         L.taoo_bound_norm.argtypes = [ctypes.c_int, fp, fp, fp, fp, ctypes.c_double, fp,
                                       ctypes.c_long, ctypes.c_long, ctypes.c_long, mp]
         L.taoo_bound_act.argtypes = [ctypes.c_int, fp, fp, fp, fp, ctypes.c_long, mp]
@@ -139,6 +140,31 @@ def bound_linear(A, W, bias=None, trans_w=False, model=None):
     _chk(lib().taoo_bound_linear(_p(A3), _p(W3), _p(bias), _p(tau), M, N, K, K, W3.shape[2], N,
                                  int(bool(trans_w)), B, M * K, sW, M * N, ctypes.byref(model)))
     return tau if batched else tau[0]
+
+
+def conv_out_size(size, k, stride, pad, dil):
+    return (size + 2 * pad - dil * (k - 1) - 1) // stride + 1
+
+
+def bound_conv2d(x, w, bias=None, stride=(1, 1), padding=(0, 0), dilation=(1, 1), model=None):
+    """tau[Nb, OH, OW, Cout] for x[Nb, H, W, C] (channels last) and w[Cout, R, S, C]."""
+    model = model or Model()
+    x = _f32(x); w = _f32(w)
+    Nb, H, W, C = x.shape
+    Cout, R, S, C2 = w.shape
+    assert C == C2
+    bias = None if bias is None else _f32(bias)
+    if min(stride) < 1 or min(dilation) < 1 or min(padding) < 0:
+        raise ValueError("bad convolution geometry")
+    if min(H + 2 * padding[0] - dilation[0] * (R - 1), W + 2 * padding[1] - dilation[1] * (S - 1)) < 1:
+        raise ValueError("filter larger than the padded input")
+    OH = conv_out_size(H, R, stride[0], padding[0], dilation[0])
+    OW = conv_out_size(W, S, stride[1], padding[1], dilation[1])
+    tau = np.empty((Nb, OH, OW, Cout), dtype=np.float32)
+    _chk(lib().taoo_bound_conv2d(_p(x), _p(w), _p(bias), _p(tau), Nb, H, W, C, Cout, R, S,
+                                 stride[0], stride[1], padding[0], padding[1], dilation[0], dilation[1],
+                                 ctypes.byref(model)))
+    return tau
 
 
 def bound_softmax(x, y, model=None):

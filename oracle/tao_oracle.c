@@ -156,6 +156,52 @@ int taoo_bound_linear(const float *A, const float *W, const float *bias, float *
     return 0;
 }
 
+/* 2-D convolution as a reduction (Sec. 3.1: conv takes gamma_k with the k of the
+ * output element; operator list of the appendix: Conv2D).  Input x[Nb][H][W][C],
+ * filter w[Cout][R][S][C], output tau[Nb][OH][OW][Cout], all contiguous:
+ *   tau[n,oh,ow,co] = Gamma(K') ( sum_{r,s,c} |x[n, oh*sh-ph+r*dh, ow*sw-pw+s*dw, c]| |w[co,r,s,c]| + |b_co| )
+ * with K = R*S*C for every output element and K' = K (+1 with bias).  Taps that
+ * fall into the zero padding are exact zeros: they add nothing to the sum and
+ * keep their place in the count (a larger k stays sound).  Terms are added in
+ * the order (r, s, c). */
+int taoo_bound_conv2d(const float *x, const float *w, const float *bias, float *tau,
+                      long Nb, long H, long W, long C, long Cout, long R, long S,
+                      long sh, long sw, long ph, long pw, long dh, long dw,
+                      const taoo_model *md) {
+    if (sh < 1 || sw < 1 || dh < 1 || dw < 1 || ph < 0 || pw < 0) return -2;
+    long OH = (H + 2 * ph - dh * (R - 1) - 1) / sh + 1;
+    long OW = (W + 2 * pw - dw * (S - 1) - 1) / sw + 1;
+    if (H + 2 * ph - dh * (R - 1) - 1 < 0 || W + 2 * pw - dw * (S - 1) - 1 < 0) return -2;
+    long K = R * S * C, Kp = K + (bias ? 1 : 0);
+    double G = taoo_gamma(Kp, md);
+    if (!(G == G)) return -4;
+#pragma omp parallel for schedule(static)
+    for (long pix = 0; pix < Nb * OH * OW; ++pix) {
+        int saved = fegetround(); fesetround(FE_UPWARD);
+        long n = pix / (OH * OW), oh = (pix / OW) % OH, ow = pix % OW;
+        for (long co = 0; co < Cout; ++co) {
+            volatile double Sum = 0.0;
+            for (long r = 0; r < R; ++r) {
+                long ih = oh * sh - ph + r * dh;
+                for (long s = 0; s < S; ++s) {
+                    long iw = ow * sw - pw + s * dw;
+                    if (ih < 0 || ih >= H || iw < 0 || iw >= W) continue;   /* padding: exact zeros */
+                    const float *xp = x + ((n * H + ih) * W + iw) * C;
+                    const float *wp = w + ((co * R + r) * S + s) * C;
+                    for (long c = 0; c < C; ++c)
+                        Sum = Sum + fabs((double)xp[c]) * fabs((double)wp[c]);
+                }
+            }
+            if (bias) Sum = Sum + fabs((double)bias[co]);
+            volatile double t = G * Sum;
+            if (md->flags & 1u) t = t + (double)Kp * 0x1p-149;
+            tau[pix * Cout + co] = (float)t;    /* rounds up */
+        }
+        fesetround(saved);
+    }
+    return 0;
+}
+
 /* --------------------------------------------------- T3: softmax            */
 /* Sec. 3.1 "Minimal example: softmax", made rigorous by closing each
  * first-order step (exp(a)-1 <= a+a^2, 1/(1-c*u), S* >= S^(1-sigma)),
