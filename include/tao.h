@@ -118,6 +118,29 @@ int tao_bound_linear(const float *A, const float *W, const float *bias, float *t
                      long batch, long strideA, long strideW, long strideT,
                      const tao_fp_model *model, void *stream);
 
+/* 2-D convolution bound without a stored patch matrix (Sec. 3.1: conv is a
+ * reduction with gamma_k of the output element; Conv2D of the operator list,
+ * App. A.3):
+ *     tau[n][oh][ow][co] = Gamma(K') * ( sum_{r,s,c} |x[n][oh*stride_h - pad_h + r*dil_h]
+ *                                        [ow*stride_w - pad_w + s*dil_w][c]| |w[co][r][s][c]| + |bias[co]| ),
+ *     K = R*S*C for every output element, K' = K or K + 1 with a bias.
+ * Taps that fall into the zero padding add nothing and keep their place in K.
+ * x: [batch][H][W][C] channels last, contiguous (device).  w: [Cout][R][S][C]
+ * contiguous.  bias: [Cout] or NULL.  tau: [batch][OH][OW][Cout] contiguous,
+ * OH = (H + 2 pad_h - dil_h (R-1) - 1)/stride_h + 1, OW likewise; groups = 1.
+ * Same accumulation scheme and guarantee as tao_bound_linear, applied to the
+ * implicit patch matrix [batch*OH*OW][R*S*C]: its 32-wide k slabs are gathered
+ * from x while loading (16-byte gathers when C is a multiple of 32, x is
+ * 16-byte aligned and at most 2^31 bytes; element by element otherwise).
+ * Errors: TAO_ERR_SHAPE for a non-positive filter size, stride or dilation, a
+ * negative padding, a filter larger than the padded input, any extent >= 2^28,
+ * batch*OH*OW or R*S*C >= 2^31; TAO_ERR_K_RANGE as for tao_bound_linear.
+ * batch*OH*OW == 0 or Cout == 0 is a no-op. */
+int tao_bound_conv2d(const float *x, const float *w, const float *bias, float *tau,
+                     long batch, long H, long W, long C, long Cout, long R, long S,
+                     long stride_h, long stride_w, long pad_h, long pad_w, long dil_h, long dil_w,
+                     const tao_fp_model *model, void *stream);
+
 /* Softmax over the last dimension (Sec. 3.1 "Minimal example: softmax", closed
  * to second order).  x, y_ref, tau: [rows][cols] with row stride ld; y_ref is
  * the verifier's own binary32 softmax output.  Per row, with n = cols:

@@ -86,7 +86,7 @@ class TaoError(RuntimeError):
         super().__init__("%s: %s%s" % (where, msg, extra))
 
 
-EXPORTS = ["tao_default_model", "tao_gamma", "tao_bound_linear", "tao_bound_softmax",
+EXPORTS = ["tao_default_model", "tao_gamma", "tao_bound_linear", "tao_bound_conv2d", "tao_bound_softmax",
            "tao_bound_norm", "tao_bound_act", "tao_check_and_profile",
            "tao_check_workspace_bytes", "tao_profile_errors", "tao_profile_workspace_bytes",
            "tao_calibrate_thresholds",
@@ -112,6 +112,7 @@ def lib():
     L.tao_gamma.restype = dbl
     L.tao_bound_linear.argtypes = [vp, vp, vp, vp, lg, lg, lg, lg, lg, lg, ctypes.c_int,
                                    lg, lg, lg, lg, mp, vp]
+    L.tao_bound_conv2d.argtypes = [vp, vp, vp, vp] + [lg] * 13 + [mp, vp]
     L.tao_bound_softmax.argtypes = [vp, vp, vp, lg, lg, lg, mp, vp]
     L.tao_bound_norm.argtypes = [ctypes.c_int, vp, vp, vp, vp, dbl, vp, lg, lg, lg, mp, vp]
     L.tao_bound_act.argtypes = [ctypes.c_int, vp, vp, vp, vp, lg, mp, vp]
@@ -223,6 +224,45 @@ def tao_bound_linear(A, W, bias=None, trans_w=False, model=None, out=None):
     rc = lib().tao_bound_linear(_ptr(A), _ptr(W), _ptr(bias), _ptr(out), M, N, K, lda, ldw, N,
                                 int(bool(trans_w)), batch, sA, sW, M * N, _mref(model), _stream())
     _check(rc, "tao_bound_linear")
+    return out
+
+
+def _pair(v, name):
+    if isinstance(v, int):
+        return v, v
+    if len(v) != 2:
+        raise ValueError("%s must be an int or a pair" % name)
+    return int(v[0]), int(v[1])
+
+
+def tao_bound_conv2d(x, w, bias=None, stride=1, padding=0, dilation=1, model=None, out=None):
+    """tau[B, OH, OW, Cout] for a channels-last input x[B, H, W, C] and filters w[Cout, R, S, C],
+    both contiguous (a torch NCHW tensor in channels_last memory format, permuted to
+    (0, 2, 3, 1), is such a tensor without a copy)."""
+    torch = _torch()
+    x = _dev(x, "x"); w = _dev(w, "w"); bias = _dev(bias, "bias")
+    if x.dim() != 4 or w.dim() != 4 or not x.is_contiguous() or not w.is_contiguous():
+        raise ValueError("x [B, H, W, C] and w [Cout, R, S, C] must be contiguous 4-D tensors")
+    B, H, W, C = x.shape
+    Cout, R, S, C2 = w.shape
+    if C != C2:
+        raise ValueError("channel counts of x and w differ")
+    if bias is not None and (bias.dim() != 1 or bias.shape[0] != Cout or not bias.is_contiguous()):
+        raise ValueError("bias must be a contiguous [Cout] tensor")
+    sh, sw = _pair(stride, "stride"); ph, pw = _pair(padding, "padding"); dh, dw = _pair(dilation, "dilation")
+    if min(sh, sw, dh, dw) < 1 or min(ph, pw) < 0 or min(R, S) < 1:
+        raise ValueError("bad convolution geometry")
+    eh, ew = H + 2 * ph - dh * (R - 1) - 1, W + 2 * pw - dw * (S - 1) - 1
+    if eh < 0 or ew < 0:
+        raise ValueError("filter larger than the padded input")
+    shape = (B, eh // sh + 1, ew // sw + 1, Cout)
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float32, device=x.device)
+    elif tuple(out.shape) != shape or not out.is_contiguous() or out.dtype != torch.float32:
+        raise ValueError("out must be a contiguous float32 tensor of shape %s" % (shape,))
+    rc = lib().tao_bound_conv2d(_ptr(x), _ptr(w), _ptr(bias), _ptr(out), B, H, W, C, Cout, R, S,
+                                sh, sw, ph, pw, dh, dw, _mref(model), _stream())
+    _check(rc, "tao_bound_conv2d")
     return out
 
 

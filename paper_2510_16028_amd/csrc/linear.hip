@@ -70,6 +70,23 @@ struct LinArgs {
     double uflow;              // optional absolute underflow term
 };
 
+// Convolution as an implicit matrix product: row m = (image, oh, ow) of the patch matrix, column
+// k = (r, s, c); the patch matrix is never stored, its slabs are gathered from the channels-last
+// input while they are loaded.
+struct ConvGeom {
+    int H, W, C, OW, S;              // input height, width, channels; output width; filter taps along W
+    int sh, sw, ph, pw, dh, dw;      // stride, padding, dilation
+    unsigned ohow;                   // output pixels per image
+    unsigned xbytes;                 // bytes of the input (range of the buffer descriptor)
+    int c_fast;                      // a 32-wide k slab lies inside one tap and 16-byte gathers are allowed
+};
+struct NoConv {};
+template <bool CONV> struct ConvSel { using type = NoConv; };
+template <> struct ConvSel<true> { using type = ConvGeom; };
+// byte offset no input reaches on the gather path (inputs there are at most 2^31 bytes): a
+// buffer load at it is out of range and returns zeros, which is what a padding tap contributes
+constexpr unsigned kConvOutside = 0xC0000000u;
+
 __device__ __forceinline__ float4 abs4(float4 v) {
     return make_float4(fabsf(v.x), fabsf(v.y), fabsf(v.z), fabsf(v.w));
 }
@@ -100,8 +117,10 @@ constexpr int kStages = 4;            // a power of two (stage index = group & 3
 // PERSIST: a workgroup walks several tiles (short K loops, where the start-up and the epilogue of
 // a tile would otherwise stay exposed); without it one workgroup computes one tile and the steady
 // loop carries no tile bookkeeping (measured 2 - 3 % faster for long K loops).
-template <bool TRANS_W, bool FAST, int WM, bool CLEAN, bool PERSIST>
-__global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
+// CONV: the A operand is the implicit patch matrix of a convolution (geometry in `cv`).
+template <bool TRANS_W, bool FAST, int WM, bool CLEAN, bool PERSIST, bool CONV = false>
+__global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p, typename ConvSel<CONV>::type cv) {
+    static_assert(!CONV || (!TRANS_W && !PERSIST), "convolution: k-contiguous filters, one tile per workgroup");
     extern __shared__ __attribute__((aligned(16))) float lds[];
     constexpr int BM = Shape<WM>::kBM, WN = Shape<WM>::kWN, TN = Shape<WM>::kTN;
     constexpr int kVecA = Shape<WM>::kVecA, kVecW = Shape<WM>::kVecW;
@@ -152,6 +171,13 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
     const float* l_A = p.A; const float* l_W = p.W;     // batch entry (edge path)
     const char* l_pa0 = nullptr; const char* l_pw0 = nullptr; // first byte of the tile's first slab
     bool l_interior = false;
+    // convolution: the tap (l_r, l_s) and first channel l_c0 of the next slab (gather path), and
+    // per patch row of this thread the input coordinates of tap (0, 0), the byte offset of its
+    // first element (gather path) and its pixel index (edge path; -1 marks a row beyond M)
+    int l_r = 0, l_s = 0, l_c0 = 0;
+    int cv_ih0[kVecA], cv_iw0[kVecA];
+    unsigned cv_base[kVecA];
+    long cv_pix[kVecA];
     auto set_load_tile = [&](unsigned t) __attribute__((always_inline)) {
         const Origin o = origin(t);
         l_m0 = o.m0; l_n0 = o.n0;
@@ -160,6 +186,22 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
         l_pw0 = reinterpret_cast<const char*>(TRANS_W ? l_W + o.n0 : l_W + o.n0 * p.ldw);
         // Interior tiles of aligned operands take unguarded 16-byte loads
         l_interior = (o.m0 + BM <= p.M) && (o.n0 + BN <= p.N) && p.fast_ok;
+        if constexpr (CONV) {
+#pragma unroll
+            for (int i = 0; i < kVecA; ++i) {
+                const long m = o.m0 + ld_row + 64 * i;
+                const bool row_ok = m < p.M;
+                const unsigned mm = row_ok ? (unsigned)m : 0u;
+                const unsigned img = mm / cv.ohow, rem = mm - img * cv.ohow;
+                const unsigned oh = rem / (unsigned)cv.OW, ow = rem - oh * (unsigned)cv.OW;
+                cv_ih0[i] = (int)oh * cv.sh - cv.ph;
+                cv_iw0[i] = (int)ow * cv.sw - cv.pw;
+                const long pix = ((long)img * cv.H + cv_ih0[i]) * cv.W + cv_iw0[i];
+                cv_pix[i] = pix;
+                cv_base[i] = (unsigned)((pix * cv.C + ld_k) * 4);      // modulo 2^32; exact whenever the tap is inside
+                if (!row_ok) cv_ih0[i] = -(1 << 30);                   // no tap of such a row is inside
+            }
+        }
     };
     if (my_tiles > 0) set_load_tile(l_tile);
 
@@ -167,6 +209,52 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p) {
     float4 ra0[kVecA], rw0[kVecW], ra1[kVecA], rw1[kVecW];
     auto load_slab = [&](float4* ra, float4* rw) __attribute__((always_inline)) {
         const long k0 = l_g * BK;
+        if constexpr (CONV) {
+            if (CLEAN || (l_interior && k0 + BK <= p.K)) {
+                // Gather path: the slab is 32 consecutive channels of one tap, 128 contiguous bytes
+                // per patch row; rows whose tap falls into the padding read out of range (zeros).
+                const int dr = l_r * cv.dh, ds = l_s * cv.dw;
+                const unsigned tap = (unsigned)(((dr * cv.W + ds) * cv.C + l_c0) * 4);
+                const __amdgpu_buffer_rsrc_t dx = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(p.A), 0, (int)cv.xbytes, 0x00020000);
+                const char* pw = l_pw0 + l_g * slabW;
+                const __amdgpu_buffer_rsrc_t dw = __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(pw), 0, (int)spanW, 0x00020000);
+#pragma unroll
+                for (int i = 0; i < kVecA; ++i) {
+                    const bool inside = (unsigned)(cv_ih0[i] + dr) < (unsigned)cv.H && (unsigned)(cv_iw0[i] + ds) < (unsigned)cv.W;
+                    const unsigned off = inside ? cv_base[i] + tap : kConvOutside;
+                    ra[i] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(dx, (int)off, 0, 0));
+                }
+#pragma unroll
+                for (int i = 0; i < kVecW; ++i)
+                    rw[i] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(dw, (int)offW, (int)(strideWi * i), 0));
+                l_c0 += BK;
+                if (l_c0 >= cv.C) { l_c0 = 0; if (++l_s == cv.S) { l_s = 0; ++l_r; } }
+            } else {
+                // Edge path: element by element, k -> (tap, channel) -> (r, s)
+#pragma unroll
+                for (int i = 0; i < kVecA; ++i) {
+                    float v[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const long k = k0 + ld_k + j;
+                        v[j] = 0.f;
+                        if (k < p.K) {
+                            const unsigned tp = (unsigned)k / (unsigned)cv.C, ch = (unsigned)k - tp * (unsigned)cv.C;
+                            const unsigned r = tp / (unsigned)cv.S, sx = tp - r * (unsigned)cv.S;
+                            const int dr = (int)r * cv.dh, ds = (int)sx * cv.dw;
+                            if ((unsigned)(cv_ih0[i] + dr) < (unsigned)cv.H && (unsigned)(cv_iw0[i] + ds) < (unsigned)cv.W)
+                                v[j] = p.A[(cv_pix[i] + (long)dr * cv.W + ds) * cv.C + ch];
+                        }
+                    }
+                    ra[i] = make_float4(v[0], v[1], v[2], v[3]);
+                }
+#pragma unroll
+                for (int i = 0; i < kVecW; ++i)
+                    rw[i] = gload(l_W, l_n0 + ld_row + 64 * i, p.N, p.ldw, k0 + ld_k, p.K, p.vecW);
+            }
+            ++l_g;
+            return;
+        }
         if (CLEAN || (l_interior && k0 + BK <= p.K)) {
             // Buffer loads: descriptor (uniform base of this group's slab) in SGPRs, one 32-bit
             // per-thread offset, the vector index as a scalar offset.  Next to FP32 MFMA this
@@ -420,13 +508,43 @@ static hipError_t launch_absgemm(dim3 grid, hipStream_t st, const LinArgs& p) {
         if (e != hipSuccess) return e;
         configured = true;
     }
-    hipLaunchKernelGGL((absgemm_bound<TRANS_W, FAST, WM, CLEAN, PERSIST>), grid, dim3(kLinThreads), lds_bytes, st, p);
+    hipLaunchKernelGGL((absgemm_bound<TRANS_W, FAST, WM, CLEAN, PERSIST>), grid, dim3(kLinThreads), lds_bytes, st, p, NoConv());
     return hipSuccess;
+}
+template <bool FAST, int WM, bool CLEAN>
+static hipError_t launch_conv(dim3 grid, hipStream_t st, const LinArgs& p, const ConvGeom& cv) {
+    constexpr size_t lds_bytes = (size_t)kStages * Shape<WM>::kStageFloats * sizeof(float);
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_bound<false, FAST, WM, CLEAN, false, true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL((absgemm_bound<false, FAST, WM, CLEAN, false, true>), grid, dim3(kLinThreads), lds_bytes, st, p, cv);
+    return hipSuccess;
+}
+template <int WM>
+static hipError_t launch_conv_shape(bool fast, bool clean, dim3 grid, hipStream_t st, const LinArgs& p, const ConvGeom& cv) {
+    if (clean) return fast ? launch_conv<true, WM, true>(grid, st, p, cv) : launch_conv<false, WM, true>(grid, st, p, cv);
+    return fast ? launch_conv<true, WM, false>(grid, st, p, cv) : launch_conv<false, WM, false>(grid, st, p, cv);
 }
 template <int WM, bool CLEAN, bool PERSIST>
 static hipError_t launch_shape(bool trans_w, bool fast, dim3 grid, hipStream_t st, const LinArgs& p) {
     if (trans_w) return fast ? launch_absgemm<true, true, WM, CLEAN, PERSIST>(grid, st, p) : launch_absgemm<true, false, WM, CLEAN, PERSIST>(grid, st, p);
     return fast ? launch_absgemm<false, true, WM, CLEAN, PERSIST>(grid, st, p) : launch_absgemm<false, false, WM, CLEAN, PERSIST>(grid, st, p);
+}
+
+// Tile height.  One workgroup occupies a CU, so a launch takes ceil(tiles / CUs) rounds of one
+// tile time each; a 64-row tile takes half the time of a 128-row tile plus about 9 % (one MFMA
+// tile per wavefront reuses each A operand once instead of twice: measured 86 - 88 against 94 - 96
+// TFLOP/s on full rounds).  Take the cheaper shape; up to 64 rows the tall tile is kept.
+static bool prefer_64_row_tiles(long M, long tiles_per_row_block, int cus) {
+    if (M <= 64) return false;
+    const long t128 = tiles_per_row_block * ((M + 127) / 128), t64 = tiles_per_row_block * ((M + 63) / 64);
+    const double c128 = (double)((t128 + cus - 1) / cus) * 128.0;
+    const double c64 = (double)((t64 + cus - 1) / cus) * 64.0 * 1.09;
+    return c64 < c128;
 }
 
 // ---- matrix-core self test ----------------------------------------------------------------
@@ -486,11 +604,11 @@ int tao_bound_linear(const float* A, const float* W, const float* bias, float* t
     p.infl = widen(1.0 / (lower * (1.0 - 0x1p-52)));
     p.uflow = (md.flags & TAO_FLAG_UNDERFLOW_TERMS) ? (double)Kp * 0x1p-149 : 0.0;
 
-    // 128-row tiles unless they would leave a quarter or more of the 256 CUs without a
-    // workgroup while 64-row tiles would not
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (cus < 1) cus = 256;
     const long tiles_n = (N + BN - 1) / BN;
-    const long tiles128 = tiles_n * ((M + 127) / 128) * batch;
-    const bool small = tiles128 <= 192 && M > 64;
+    const bool small = prefer_64_row_tiles(M, tiles_n * batch, cus);
     const long bm = small ? 64 : 128;
     const long tiles_m = (M + bm - 1) / bm;
     const long ntiles = tiles_n * tiles_m * batch;
@@ -499,9 +617,6 @@ int tao_bound_linear(const float* A, const float* W, const float* bias, float* t
     p.all_clean = p.fast_ok && (M % bm == 0) && (N % BN == 0) && (K % BK == 0);
     // One workgroup per CU walks several tiles when every tile is regular and the K loop is short
     // (its pipeline then runs across tile boundaries); otherwise one workgroup per tile.
-    int dev = 0, cus = 256;
-    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    if (cus < 1) cus = 256;
     const bool persist = p.all_clean && ntiles > cus && K <= 32 * BK;
     dim3 grid((unsigned)(persist ? cus : ntiles));
     hipStream_t st = (hipStream_t)stream;
@@ -510,6 +625,82 @@ int tao_bound_linear(const float* A, const float* W, const float* bias, float* t
     if (persist)          e = small ? launch_shape<2, true, true>(tw, fast, grid, st, p) : launch_shape<4, true, true>(tw, fast, grid, st, p);
     else if (p.all_clean) e = small ? launch_shape<2, true, false>(tw, fast, grid, st, p) : launch_shape<4, true, false>(tw, fast, grid, st, p);
     else                  e = small ? launch_shape<2, false, false>(tw, fast, grid, st, p) : launch_shape<4, false, false>(tw, fast, grid, st, p);
+    if (e != hipSuccess) { g_last_hip_error = (int)e; return TAO_ERR_LAUNCH; }
+    return launch_status();
+}
+
+int tao_bound_conv2d(const float* x, const float* w, const float* bias, float* tau,
+                     long batch, long H, long W, long C, long Cout, long R, long S,
+                     long stride_h, long stride_w, long pad_h, long pad_w, long dil_h, long dil_w,
+                     const tao_fp_model* model, void* stream) {
+    using namespace tao;
+    tao_fp_model md;
+    int rc = resolve_model(model, &md);
+    if (rc != TAO_OK) return rc;
+    if (batch < 0 || H < 0 || W < 0 || C < 0 || Cout < 0 || R < 1 || S < 1) return TAO_ERR_SHAPE;
+    if (stride_h < 1 || stride_w < 1 || dil_h < 1 || dil_w < 1 || pad_h < 0 || pad_w < 0) return TAO_ERR_SHAPE;
+    const long lim = 1L << 28;       // each extent, so that coordinate arithmetic stays in 32 bits
+    if (H >= lim || W >= lim || C >= lim || R >= lim || S >= lim || Cout >= lim || batch >= lim ||
+        stride_h >= lim || stride_w >= lim || dil_h >= lim || dil_w >= lim || pad_h >= lim || pad_w >= lim) return TAO_ERR_SHAPE;
+    const long eh = H + 2 * pad_h - dil_h * (R - 1) - 1, ew = W + 2 * pad_w - dil_w * (S - 1) - 1;
+    if (eh < 0 || ew < 0) return TAO_ERR_SHAPE;          // filter larger than the padded input
+    const long OH = eh / stride_h + 1, OW = ew / stride_w + 1;
+    if (dil_h * (R - 1) >= lim || dil_w * (S - 1) >= lim) return TAO_ERR_SHAPE;
+    // patch-matrix shape; every index the kernel forms must fit its integer types
+    const __int128 M128 = (__int128)batch * OH * OW, K128 = (__int128)R * S * C;
+    if (M128 >= (1L << 31) || K128 >= (1L << 31) || OH * OW >= (1L << 31)) return TAO_ERR_SHAPE;
+    const long M = (long)M128, K = (long)K128, N = Cout;
+    if ((__int128)batch * H * W * C >= ((__int128)1 << 61) || (__int128)M * N >= ((__int128)1 << 61)) return TAO_ERR_SHAPE;
+    const long Kp = K + (bias ? 1 : 0);
+    const double c = gamma_up(Kp, md);
+    if (!(c == c)) return TAO_ERR_K_RANGE;
+    if (M == 0 || N == 0) return TAO_OK;
+    const long xbytes = batch * H * W * C * 4;
+    if (!tau || (K > 0 && !w) || (K > 0 && xbytes > 0 && !x)) return TAO_ERR_NULL;
+    if (!aligned(x, 4) || !aligned(w, 4) || !aligned(bias, 4) || !aligned(tau, 4)) return TAO_ERR_ALIGN;
+
+    LinArgs p;
+    p.A = x; p.W = w; p.bias = bias; p.tau = tau;
+    p.M = M; p.N = N; p.K = K; p.lda = K; p.ldw = K; p.ldt = N;
+    p.strideA = 0; p.strideW = 0; p.strideT = 0;
+    ConvGeom cv;
+    cv.H = (int)H; cv.W = (int)W; cv.C = (int)C; cv.OW = (int)OW; cv.S = (int)S;
+    cv.sh = (int)stride_h; cv.sw = (int)stride_w; cv.ph = (int)pad_h; cv.pw = (int)pad_w;
+    cv.dh = (int)dil_h; cv.dw = (int)dil_w;
+    cv.ohow = (unsigned)(OH * OW);
+    // gather path: whole 32-channel slabs inside one tap, 16-byte aligned, input within 2^31 bytes,
+    // and the tap offset (dil_h (R-1) W + dil_w (S-1)) C * 4 within 32 bits
+    cv.c_fast = (C % BK == 0) && aligned(x, 16) && xbytes <= (1L << 31) &&
+                (__int128)(dil_h * (R - 1) * W + dil_w * (S - 1) + 1) * C * 4 < ((__int128)1 << 31);
+    cv.xbytes = cv.c_fast ? (unsigned)xbytes : 0u;
+    p.vecA = cv.c_fast;
+    p.vecW = aligned(w, 16) && (K % 4 == 0);
+    p.fast_ok = cv.c_fast && p.vecW && ((long)(BN - 1) * K + BK) * 4 < (1L << 31);
+    p.c = c;
+    const bool fast = (md.flags & TAO_FLAG_FAST_ACCUM) != 0;
+    const double u = md.u;
+    const double r32 = fast ? (double)(K > 0 ? K : 1) : 7.0;
+    const double f64 = (double)(K / 32 + 2);
+    if (!(r32 * u < 0.5)) return TAO_ERR_K_RANGE;
+    const double lower = (1.0 - r32 * u) * (1.0 - f64 * 0x1p-53);
+    p.infl = widen(1.0 / (lower * (1.0 - 0x1p-52)));
+    p.uflow = (md.flags & TAO_FLAG_UNDERFLOW_TERMS) ? (double)Kp * 0x1p-149 : 0.0;
+
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (cus < 1) cus = 256;
+    const long tiles_n = (N + BN - 1) / BN;
+    const bool small = prefer_64_row_tiles(M, tiles_n, cus);
+    const long bm = small ? 64 : 128;
+    const long tiles_m = (M + bm - 1) / bm;
+    const long ntiles = tiles_n * tiles_m;
+    if (ntiles >= (1L << 31)) return TAO_ERR_SHAPE;
+    p.tiles_n = (unsigned)tiles_n; p.tiles_m = (unsigned)tiles_m; p.ntiles = (unsigned)ntiles;
+    p.all_clean = p.fast_ok && (M % bm == 0) && (N % BN == 0) && (K % BK == 0);
+    dim3 grid((unsigned)ntiles);
+    hipStream_t st = (hipStream_t)stream;
+    const hipError_t e = small ? launch_conv_shape<2>(fast, p.all_clean != 0, grid, st, p, cv)
+                               : launch_conv_shape<4>(fast, p.all_clean != 0, grid, st, p, cv);
     if (e != hipSuccess) { g_last_hip_error = (int)e; return TAO_ERR_LAUNCH; }
     return launch_status();
 }

@@ -33,7 +33,7 @@ class Op:
     args: Dict[str, Optional[torch.Tensor]]
     y_ref: torch.Tensor
     claimed: torch.Tensor
-    attrs: Dict[str, float] = field(default_factory=dict)
+    attrs: Dict[str, object] = field(default_factory=dict)
 
 
 def _gen(seed, device):
@@ -294,6 +294,10 @@ def config4(device="cpu", seed=SEED0 + 4, scale=1):
     W = randn(g, (CO, C * 9), math.sqrt(2.0 / (C * 9)))
     y = A @ W.t()
     ops = [Op("conv_im2col", "linear", {"A": A, "W": W, "bias": None}, y, matmul_permuted_k(g, A, W))]
+    # the same convolution in the layout of the native entry point: channels-last input and
+    # filters [Cout][R][S][C] (the patch matrix above orders its columns (c, r, s) instead)
+    ops[0].attrs["conv"] = {"x": x.permute(0, 2, 3, 1).contiguous(),
+                            "w": W.reshape(CO, C, 3, 3).permute(0, 2, 3, 1).contiguous(), "padding": 1}
     s = 1.0 + randn(g, (CO,), 0.1)
     t = randn(g, (CO,), 0.1)
     z = y * s + t

@@ -93,6 +93,23 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_bound_linear(nul, p, nul, p, *args(4, 4, 8, 8, 8, 4), None, None) == tao.ERR_NULL
     assert L.tao_bound_linear(p, odd, nul, p, *args(4, 4, 8, 8, 8, 4), None, None) == tao.ERR_ALIGN
     assert L.tao_bound_linear(nul, nul, nul, nul, *args(0, 4, 8, 8, 8, 4), None, None) == tao.OK
+    # conv2d: (batch, H, W, C, Cout, R, S, stride h/w, pad h/w, dilation h/w)
+    cargs = lambda B=1, H=8, W=8, C=4, Co=4, R=3, S=3, sh=1, sw=1, ph=1, pw=1, dh=1, dw=1: \
+        (B, H, W, C, Co, R, S, sh, sw, ph, pw, dh, dw)
+    assert L.tao_bound_conv2d(p, p, nul, p, *cargs(sh=0), None, None) == tao.ERR_SHAPE
+    assert L.tao_bound_conv2d(p, p, nul, p, *cargs(dw=0), None, None) == tao.ERR_SHAPE
+    assert L.tao_bound_conv2d(p, p, nul, p, *cargs(ph=-1), None, None) == tao.ERR_SHAPE
+    assert L.tao_bound_conv2d(p, p, nul, p, *cargs(R=0), None, None) == tao.ERR_SHAPE
+    assert L.tao_bound_conv2d(p, p, nul, p, *cargs(H=2, R=5, ph=0), None, None) == tao.ERR_SHAPE   # filter > input
+    assert L.tao_bound_conv2d(p, p, nul, p, *cargs(H=2 ** 28), None, None) == tao.ERR_SHAPE
+    assert L.tao_bound_conv2d(p, p, nul, p, *cargs(B=2 ** 20, H=2 ** 10, W=2 ** 10), None, None) == tao.ERR_SHAPE  # rows >= 2^31
+    assert L.tao_bound_conv2d(p, p, nul, p, *cargs(C=2 ** 22, R=2, S=2, ph=0, pw=0), None, None) == tao.ERR_K_RANGE
+    assert L.tao_bound_conv2d(nul, p, nul, p, *cargs(), None, None) == tao.ERR_NULL
+    assert L.tao_bound_conv2d(p, nul, nul, p, *cargs(), None, None) == tao.ERR_NULL
+    assert L.tao_bound_conv2d(p, p, nul, odd, *cargs(), None, None) == tao.ERR_ALIGN
+    assert L.tao_bound_conv2d(nul, nul, nul, nul, *cargs(B=0), None, None) == tao.OK
+    assert L.tao_bound_conv2d(nul, nul, nul, nul, *cargs(Co=0), None, None) == tao.OK
+    assert L.tao_bound_conv2d(p, p, nul, p, *cargs(), ctypes.byref(bad), None) == tao.ERR_MODEL
     # check
     need = L.tao_check_workspace_bytes(1000)
     assert need > 0

@@ -98,6 +98,29 @@ def test_config4_conv_stage_full_size(tao, oracle_mod):
     _check_ops_sampled(tao, oracle_mod, ops, nsample=13, seed=400)
 
 
+def test_config4_native_convolution_full_size(tao, oracle_mod):
+    """The same conv stage through tao_bound_conv2d (no stored patch matrix): the honest
+    claim is accepted on all 25.7 M outputs, one whole image and the border rows of another
+    against the oracle's direct loop, and the bound agrees with the patch-matrix path to the
+    parity tolerance (the two sum their terms in different orders)."""
+    op = tao_inputs.config4("cuda", scale=1)[0]
+    cv = op.attrs["conv"]
+    x, w = cv["x"], cv["w"]
+    tau = tao.tao_bound_conv2d(x, w, None, 1, cv["padding"], 1)
+    B, H, W, Cout = tau.shape
+    flat = tau.reshape(-1, Cout)
+    p = tao.tao_check_and_profile(op.claimed.contiguous(), op.y_ref.contiguous(), flat)
+    assert p["violations"] == 0 and p["n"] == op.y_ref.numel()
+    for b in (0, B - 1):
+        t_or = oracle_mod.bound_conv2d(_np(x[b:b + 1]), _np(w), None, (1, 1), (1, 1), (1, 1))
+        worst = assert_bound_parity(_np(tau[b:b + 1]), t_or, "native conv image %d" % b)
+        print("image %d: max tau_gpu/tau_oracle - 1 = %.3e" % (b, worst), flush=True)
+    via_patches = gpu_tau(tao, op)
+    ratio = (flat / via_patches - 1).abs().max().item()
+    print("native vs patch-matrix bound: max relative difference %.3e" % ratio, flush=True)
+    assert ratio <= 1e-6
+
+
 def test_config5_stress_full_size(tao, oracle_mod):
     g, A, W = tao_inputs.config5_operands("cuda", size=8192)
     ref = A @ W.t()

@@ -107,10 +107,10 @@ def test_linear_shapes(tao, oracle_mod, M, N, K, bias, trans_w, batch):
 @pytest.mark.parametrize("M,N,K,bias,trans_w,batch", [
     (2048, 2560, 64, True, False, 1),      # 320 tiles of 128 rows: persistent walk, several groups per tile
     (2048, 2560, 96, False, True, 1),      # same with W stored K x N
-    (2048, 1280, 160, True, True, 1),      # 64-row tiles (few 128-row tiles), persistent
+    (3840, 1280, 160, True, True, 1),      # 300 / 600 tiles: 64-row tiles make fewer, cheaper rounds; persistent
     (512, 640, 32, False, False, 5),       # batched, one k-slab per tile: the shortest pipeline
     (384, 384, 224, True, False, 3),       # batched 64-row tiles, odd number of groups
-    (1024, 1536, 64, False, True, 2),      # batched, 64-row tiles, persistent across batch entries
+    (1920, 1280, 64, False, True, 2),      # batched, 64-row tiles, persistent across batch entries
     (1024, 1024, 1056, False, False, 1),   # just past the persistent limit: one tile per workgroup
 ])
 def test_linear_aligned_tile_walks(tao, oracle_mod, M, N, K, bias, trans_w, batch):
@@ -128,6 +128,53 @@ def test_linear_aligned_tile_walks(tao, oracle_mod, M, N, K, bias, trans_w, batc
     fast = tao.tao_bound_linear(A.cuda(), W.cuda(), None if b is None else b.cuda(), trans_w=trans_w,
                                 model=tao.FpModel(flags=tao.FLAG_FAST_ACCUM))
     assert_bound_parity(_np(fast), t_or, "fast", rel_tol=2.5 * max(K, 1) * 2.0 ** -24)
+
+
+@pytest.mark.parametrize("B,H,W,C,Cout,R,S,stride,pad,dil,bias", [
+    (2, 16, 16, 32, 128, 3, 3, (1, 1), (1, 1), (1, 1), True),     # gather path, 512 patch rows, padding on all sides
+    (1, 32, 24, 64, 256, 3, 3, (1, 1), (1, 1), (1, 1), False),    # gather path, two column tiles, two slabs per tap
+    (2, 17, 19, 32, 128, 3, 2, (2, 1), (0, 1), (1, 2), True),     # stride, dilation, ragged row tile (gather + edge tiles)
+    (1, 31, 33, 96, 128, 1, 1, (2, 2), (0, 0), (1, 1), False),    # 1 x 1 strided (a projection shortcut)
+    (3, 9, 11, 3, 5, 7, 7, (2, 2), (3, 3), (1, 1), True),         # stem-like: 3 channels, element path
+    (1, 8, 8, 40, 130, 3, 3, (1, 1), (2, 2), (2, 2), False),      # channels not a multiple of 32, ragged columns
+    (2, 6, 5, 32, 64, 5, 5, (1, 1), (2, 2), (1, 1), True),        # filter as large as the input
+    (1, 4, 4, 32, 128, 3, 3, (1, 1), (3, 3), (1, 1), False),      # outputs whose taps all fall into the padding
+    (1, 1, 1, 1, 1, 1, 1, (1, 1), (0, 0), (1, 1), True),
+    (8, 56, 56, 64, 128, 3, 3, (1, 1), (1, 1), (1, 1), True),     # 196 tiles of 128 rows: the large-tile gather kernel
+])
+def test_conv2d_shapes(tao, oracle_mod, B, H, W, C, Cout, R, S, stride, pad, dil, bias):
+    """The implicit-patch-matrix convolution bound against the oracle's direct triple loop,
+    every output element; both accumulation modes."""
+    g = torch.Generator().manual_seed(B + 3 * H + 5 * W + 7 * C + 11 * Cout + 13 * R)
+    x = torch.randn((B, H, W, C), generator=g)
+    w = torch.randn((Cout, R, S, C), generator=g) * 0.1
+    b = torch.randn((Cout,), generator=g) if bias else None
+    t_or = oracle_mod.bound_conv2d(_np(x), _np(w), None if b is None else _np(b), stride, pad, dil)
+    t_gpu = tao.tao_bound_conv2d(x.cuda(), w.cuda(), None if b is None else b.cuda(), stride, pad, dil)
+    assert tuple(t_gpu.shape) == t_or.shape
+    assert_bound_parity(_np(t_gpu), t_or, "conv %s" % ((B, H, W, C, Cout, R, S, stride, pad, dil),))
+    fast = tao.tao_bound_conv2d(x.cuda(), w.cuda(), None if b is None else b.cuda(), stride, pad, dil,
+                                model=tao.FpModel(flags=tao.FLAG_FAST_ACCUM))
+    assert_bound_parity(_np(fast), t_or, "conv fast", rel_tol=2.5 * R * S * C * 2.0 ** -24)
+
+
+def test_conv2d_accepts_a_real_convolution(tao, oracle_mod):
+    """A binary32 convolution computed by another algorithm (torch on the CPU, NCHW) against the
+    binary64 reference: every error within the GPU's bound, and the bound identical whether the
+    operand is a channels-last view of an NCHW tensor or a plain NHWC tensor."""
+    g = torch.Generator().manual_seed(9)
+    x = torch.randn((2, 64, 14, 14), generator=g)
+    w = torch.randn((128, 64, 3, 3), generator=g) * 0.05
+    y32 = torch.nn.functional.conv2d(x, w, padding=1)
+    y64 = torch.nn.functional.conv2d(x.double(), w.double(), padding=1)
+    xl = x.cuda().contiguous(memory_format=torch.channels_last).permute(0, 2, 3, 1)
+    wl = w.cuda().contiguous(memory_format=torch.channels_last).permute(0, 2, 3, 1)
+    assert xl.is_contiguous() and wl.is_contiguous()
+    tau = tao.tao_bound_conv2d(xl, wl, None, 1, 1, 1)
+    err = (y32.double() - y64).abs().permute(0, 2, 3, 1)
+    assert bool((err <= tau.cpu().double()).all())
+    t_or = oracle_mod.bound_conv2d(_np(xl), _np(wl), None, (1, 1), (1, 1), (1, 1))
+    assert_bound_parity(_np(tau), t_or, "conv nchw view")
 
 
 def test_linear_unaligned_views_and_modes(tao, oracle_mod):
