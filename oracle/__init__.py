@@ -16,6 +16,7 @@ NBINS = 2048
 
 LAYERNORM, RMSNORM, BN_AFFINE, SUM, MEAN = 0, 1, 2, 3, 4
 GELU_ERF, SILU, MUL, ADD, RELU = 0, 1, 2, 3, 4
+SUB, DIV, EXACT, SQRT, RSQRT, EXP, LOG, SIN, COS, TANH, POW, SIGMOID, GELU_TANH = range(5, 18)
 UNDERFLOW_TERMS = 1
 
 
@@ -24,11 +25,14 @@ class Model(ctypes.Structure):
     _fields_ = [("u", ctypes.c_double), ("mode", ctypes.c_int), ("lam", ctypes.c_double),
                 ("c_exp", ctypes.c_double), ("c_erf", ctypes.c_double),
                 ("c_rsqrt", ctypes.c_double), ("c_div", ctypes.c_double),
-                ("flags", ctypes.c_uint)]
+                ("flags", ctypes.c_uint),
+                ("c_log", ctypes.c_double), ("c_sin", ctypes.c_double), ("c_cos", ctypes.c_double),
+                ("c_tanh", ctypes.c_double), ("c_pow", ctypes.c_double)]
 
     def __init__(self, u=2.0 ** -24, mode=0, lam=4.0, c_exp=2.0, c_erf=2.0, c_rsqrt=2.0,
-                 c_div=2.0, flags=0):
-        super().__init__(u, mode, lam, c_exp, c_erf, c_rsqrt, c_div, flags)
+                 c_div=2.0, flags=0, c_log=2.0, c_sin=4.0, c_cos=4.0, c_tanh=4.0, c_pow=8.0):
+        super().__init__(u, mode, lam, c_exp, c_erf, c_rsqrt, c_div, flags,
+                         c_log, c_sin, c_cos, c_tanh, c_pow)
 
 
 class Profile(ctypes.Structure):
@@ -87,6 +91,7 @@ def lib():
         L.taoo_bound_norm.argtypes = [ctypes.c_int, fp, fp, fp, fp, ctypes.c_double, fp,
                                       ctypes.c_long, ctypes.c_long, ctypes.c_long, mp]
         L.taoo_bound_act.argtypes = [ctypes.c_int, fp, fp, fp, fp, ctypes.c_long, mp]
+        L.taoo_bound_rope.argtypes = [fp, fp, fp, fp] + [ctypes.c_long] * 4 + [ctypes.c_int, mp]
         L.taoo_check_and_profile.argtypes = [fp, fp, fp, ctypes.c_long, ctypes.c_double,
                                              ctypes.c_double, ctypes.POINTER(Profile)]
         L.taoo_rel_errors.argtypes = [fp, fp, ctypes.c_long, ctypes.c_double, fp]
@@ -199,6 +204,20 @@ def bound_act(kind, x, y, x2=None, model=None):
     x2 = None if x2 is None else _f32(x2)
     tau = np.empty_like(y)
     _chk(lib().taoo_bound_act(kind, _p(x), _p(x2), _p(y), _p(tau), y.size, ctypes.byref(model)))
+    return tau
+
+
+def bound_rope(x, cos, sin, inner=1, interleaved=False, model=None):
+    """tau like x[..., d] for the rotation by the tables cos, sin [npos, d/2]; row r of the
+    flattened x uses table row (r // inner) % npos."""
+    model = model or Model()
+    x = _f32(x); cos = _f32(cos); sin = _f32(sin)
+    d = x.shape[-1]; rows = x.size // max(d, 1)
+    if not (cos.shape == sin.shape and cos.ndim == 2 and cos.shape[1] * 2 == d):
+        raise ValueError("cos and sin must be [npos, d/2] with d even")
+    tau = np.empty_like(x)
+    _chk(lib().taoo_bound_rope(_p(x), _p(cos), _p(sin), _p(tau), rows, d, int(inner), cos.shape[0],
+                               int(bool(interleaved)), ctypes.byref(model)))
     return tau
 
 

@@ -51,6 +51,7 @@ typedef struct {
     double lambda;   /* 4 in the paper */
     double c_exp, c_erf, c_rsqrt, c_div;
     unsigned flags;  /* bit 0: add underflow terms (off: App. A.1 excludes underflow) */
+    double c_log, c_sin, c_cos, c_tanh, c_pow;   /* further library functions, units of u */
 } taoo_model;
 
 typedef struct {
@@ -66,7 +67,10 @@ typedef struct {
 } taoo_profile;
 
 enum { TAOO_LAYERNORM = 0, TAOO_RMSNORM = 1, TAOO_BN_AFFINE = 2, TAOO_SUM = 3, TAOO_MEAN = 4 };
-enum { TAOO_GELU_ERF = 0, TAOO_SILU = 1, TAOO_MUL = 2, TAOO_ADD = 3, TAOO_RELU = 4 };
+enum { TAOO_GELU_ERF = 0, TAOO_SILU = 1, TAOO_MUL = 2, TAOO_ADD = 3, TAOO_RELU = 4,
+       TAOO_SUB = 5, TAOO_DIV = 6, TAOO_EXACT = 7, TAOO_SQRT = 8, TAOO_RSQRT = 9, TAOO_EXP = 10,
+       TAOO_LOG = 11, TAOO_SIN = 12, TAOO_COS = 13, TAOO_TANH = 14, TAOO_POW = 15, TAOO_SIGMOID = 16,
+       TAOO_GELU_TANH = 17 };
 
 /* ------------------------------------------------------------------ helpers */
 
@@ -74,6 +78,8 @@ enum { TAOO_GELU_ERF = 0, TAOO_SILU = 1, TAOO_MUL = 2, TAOO_ADD = 3, TAOO_RELU =
 static double one_minus_lo(double x) { volatile double t = x - 1.0; return -t; }
 /* lower bound of (a - b) while the mode is upward. */
 static double sub_lo(double a, double b) { volatile double t = b - a; return -t; }
+/* lower bound of (a + b) while the mode is upward. */
+static double add_lo(double a, double b) { volatile double t = (-a) - b; return -t; }
 
 /* libm calls are made in round-to-nearest (their error bound is stated for
  * that mode) and then widened by a few ulps. */
@@ -440,14 +446,29 @@ int taoo_bound_norm(int kind, const float *x, const float *y, const float *g, co
  *   t* = x/sqrt2, E_t = (2u+u^2)|t*|, t_lo = max(0,|t*|-E_t),
  *   G' = (2/sqrt pi) exp(-t_lo^2), A = min(1, (2/sqrt pi)|t*|(1+4u)),
  *   E_g = G' E_t + c_erf u A,  tau = (|x|/2) E_g + u|y| (1 + 1/(1-u)).
+ * GELU (tanh form): y = fl(0.5 x) * fl(1 + tanh(p^)), p^ the binary32 evaluation of
+ *   p* = b (x + a x^3), b = sqrt(2/pi), a = 0.044715, in either association
+ *   (b*(x + a*x*x*x) or b*x*(1 + a*x*x)); both terms have the sign of x and pass
+ *   through at most 7 roundings, the two constants' included:
+ *   E_p = Gamma(7)|p*|, p_lo = max(0,|p*|-E_p), G' = sech^2(p_lo) = 4q/(1+q)^2 with
+ *   q = exp(-2 p_lo), A = min(1, |p*|(1+Gamma(7))), E_T = G' E_p + c_tanh u A,
+ *   tau = (|x|/2) E_T + u|y| (1 + 1/(1-u)).
  * SiLU: y = fl(x / fl(1 + exp(-x))): c' = c_exp u/(1-c_exp u), w = (c'+u)/(1-u),
  *   tau = |y| (w/(1-u) + u).
- * MUL / ADD: one rounding, tau = u|y|.  RELU: exact, tau = 0.
+ * MUL / ADD / SUB / SQRT: one correctly rounded operation, tau = u|y|.
+ * RELU / EXACT (Neg, Abs, Max, Min, max-pooling, masked fill, data movement): tau = 0.
+ * DIV, RSQRT, EXP, LOG, SIN, COS, TANH, POW: a library function whose result is
+ *   within c u of the exact one relatively, y = y*(1+d), |d| <= c u, so
+ *   |y - y*| <= c u |y*| <= |y| c u/(1 - c u); c = c_div, c_rsqrt, c_exp, c_log,
+ *   c_sin, c_cos, c_tanh, c_pow.  (Inputs are exact: operator-local scope.)
+ * SIGMOID: y = fl(1 / fl(1 + exp(-x))): the SiLU factor (the numerator is exact
+ *   in both).
  * (Sec. 3.1 primitive rule; App. A.3 lists these operators, no template printed.) */
 int taoo_bound_act(int kind, const float *x, const float *x2, const float *y, float *tau, long n,
                    const taoo_model *md) {
     (void)x2;
     const double u = md->u;
+    if (kind < 0 || kind > TAOO_GELU_TANH) return -3;
 #pragma omp parallel
     {
         int saved = fegetround(); fesetround(FE_UPWARD);
@@ -458,6 +479,18 @@ int taoo_bound_act(int kind, const float *x, const float *x2, const float *y, fl
         volatile double om = (c1 + u) / one_minus_lo(u);
         volatile double silu_f = om / one_minus_lo(u) + u;
         volatile double fresh2 = u * (1.0 + 1.0 / one_minus_lo(u));
+        double cf = -1.0;                                   /* library-function kinds */
+        switch (kind) {
+            case TAOO_DIV: cf = md->c_div; break;   case TAOO_RSQRT: cf = md->c_rsqrt; break;
+            case TAOO_EXP: cf = md->c_exp; break;   case TAOO_LOG: cf = md->c_log; break;
+            case TAOO_SIN: cf = md->c_sin; break;   case TAOO_COS: cf = md->c_cos; break;
+            case TAOO_TANH: cf = md->c_tanh; break; case TAOO_POW: cf = md->c_pow; break;
+            default: break;
+        }
+        volatile double lib_f = (cf >= 0.0) ? (cf * u) / one_minus_lo(cf * u) : 0.0;
+        const double beta_up = 0x1.9884533d43651p-1, beta_lo = 0x1.9884533d43650p-1;   /* sqrt(2/pi) */
+        const double a_up = 0x1.6e4e26d4801f8p-5, a_lo = 0x1.6e4e26d4801f7p-5;         /* 0.044715  */
+        volatile double g7 = (7.0 * u) / one_minus_lo(7.0 * u);
 #pragma omp for schedule(static)
         for (long i = 0; i < n; ++i) {
             volatile double t;
@@ -474,14 +507,69 @@ int taoo_bound_act(int kind, const float *x, const float *x2, const float *y, fl
                 if (A > 1.0) A = 1.0;
                 volatile double E_g = Gp * E_t + md->c_erf * u * A;
                 t = 0.5 * ax * E_g + ay * fresh2;
-            } else if (kind == TAOO_SILU) {
+            } else if (kind == TAOO_GELU_TANH) {
+                double ax = fabs((double)x[i]);
+                double x2 = ax * ax;                                     /* exact */
+                volatile double poly_up = 1.0 + a_up * x2;
+                volatile double ps = beta_up * ax * poly_up;             /* >= |p*| */
+                double poly_lo = add_lo(1.0, mul_lo(a_lo, x2));          /* <= 1 + a x^2 */
+                double p_dn = mul_lo(mul_lo(beta_lo, ax), poly_lo);      /* <= |p*| */
+                volatile double E_p = g7 * ps;
+                double p_lo = sub_lo(p_dn, E_p);
+                if (p_lo < 0.0) p_lo = 0.0;
+                volatile double q = exp_up(-2.0 * p_lo);                 /* -2 p_lo exact; q >= exp(-2 p_lo) */
+                if (q > 1.0) q = 1.0;
+                double den_lo = mul_lo(add_lo(1.0, q), add_lo(1.0, q));  /* <= (1+q)^2 */
+                volatile double Gp = (4.0 * q) / den_lo;
+                if (Gp > 1.0) Gp = 1.0;                                  /* sech^2 <= 1 */
+                volatile double A = ps * (1.0 + g7);
+                if (A > 1.0) A = 1.0;
+                volatile double E_T = Gp * E_p + md->c_tanh * u * A;
+                t = 0.5 * ax * E_T + ay * fresh2;
+            } else if (kind == TAOO_SILU || kind == TAOO_SIGMOID) {
                 t = ay * silu_f;
-            } else if (kind == TAOO_MUL || kind == TAOO_ADD) {
+            } else if (kind == TAOO_MUL || kind == TAOO_ADD || kind == TAOO_SUB || kind == TAOO_SQRT) {
                 t = u * ay;
+            } else if (cf >= 0.0) {
+                t = ay * lib_f;
             } else {
                 t = 0.0;
             }
             tau[i] = (float)t;
+        }
+        fesetround(saved);
+    }
+    return 0;
+}
+
+/* Rotary position embedding (operator list of App. A.3: Sin/Cos tables times the
+ * activations; Sec. 3.1: a reduction of k terms takes gamma_k).  Each output is a
+ * two-term dot product of exact inputs,
+ *   y_a = x_a cos - x_b sin,   y_b = x_b cos + x_a sin,
+ * so tau_a = Gamma(2) (|x_a cos| + |x_b sin|), tau_b = Gamma(2) (|x_b cos| + |x_a sin|)
+ * for any order and with or without fused multiply-add.  x, tau: [rows][d];
+ * cos, sin: [npos][d/2]; row r uses table row (r / inner) % npos.  Pairs (a, b):
+ * (j, j + d/2) when interleaved == 0, (2j, 2j + 1) otherwise. */
+int taoo_bound_rope(const float *x, const float *cs, const float *sn, float *tau,
+                    long rows, long d, long inner, long npos, int interleaved, const taoo_model *md) {
+    if (d < 0 || (d & 1) || inner < 1 || npos < 1 || rows < 0) return -2;
+    double G = taoo_gamma(2, md);
+    if (!(G == G)) return -4;
+    long h = d / 2;
+#pragma omp parallel for schedule(static)
+    for (long r = 0; r < rows; ++r) {
+        int saved = fegetround(); fesetround(FE_UPWARD);
+        const float *xr = x + r * d, *cr = cs + ((r / inner) % npos) * h, *sr = sn + ((r / inner) % npos) * h;
+        float *tr = tau + r * d;
+        for (long j = 0; j < h; ++j) {
+            long a = interleaved ? 2 * j : j, b = interleaved ? 2 * j + 1 : j + h;
+            double xa = fabs((double)xr[a]), xb = fabs((double)xr[b]);
+            double c = fabs((double)cr[j]), sv = fabs((double)sr[j]);
+            volatile double sa = xa * c + xb * sv;      /* products exact, sum rounded up */
+            volatile double sb = xb * c + xa * sv;
+            volatile double ta = G * sa, tb = G * sb;
+            if (md->flags & 1u) { ta = ta + 2.0 * 0x1p-149; tb = tb + 2.0 * 0x1p-149; }
+            tr[a] = (float)ta; tr[b] = (float)tb;
         }
         fesetround(saved);
     }

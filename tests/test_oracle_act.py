@@ -114,3 +114,75 @@ def test_mul_add_relu(oracle_mod):
             assert frac(tau[i]) <= want * (1 + Fraction(1, 2 ** 22)) or tau[i] <= np.float32(1e-44)
     y = np.maximum(a, 0)
     assert np.all(oracle_mod.bound_act(oracle_mod.RELU, a, y) == 0)
+
+
+# ---- GELU, tanh form -----------------------------------------------------------------------------
+
+def _gelu_tanh_run(x, theta, horner):
+    """The binary32 algorithm with the tanh result pushed by the relative error theta."""
+    beta = f32(np.sqrt(2.0 / np.pi)); a = f32(0.044715)
+    if horner:
+        inner = ((beta * x).astype(f32) * (f32(1) + (a * (x * x).astype(f32)).astype(f32)).astype(f32)).astype(f32)
+    else:
+        cube = ((x * x).astype(f32) * x).astype(f32)
+        inner = (beta * (x + (a * cube).astype(f32)).astype(f32)).astype(f32)
+    t = (np.tanh(inner.astype(np.float64)) * (1 + theta)).astype(f32)
+    t = np.clip(t, f32(-1), f32(1))
+    h = (f32(1) + t).astype(f32)
+    return ((f32(0.5) * x).astype(f32) * h).astype(f32)
+
+
+def _gelu_tanh_exact(xv):
+    xs = mp.mpf(float(xv))
+    return xs / 2 * (1 + mp.tanh(mp.sqrt(2 / mp.pi) * (xs + mp.mpf("0.044715") * xs ** 3)))
+
+
+def test_constants_used_by_gelu_tanh():
+    b = mp.sqrt(2 / mp.pi)
+    assert mp.mpf(float.fromhex("0x1.9884533d43650p-1")) < b < mp.mpf(float.fromhex("0x1.9884533d43651p-1"))
+    a = mp.mpf("0.044715")
+    assert mp.mpf(float.fromhex("0x1.6e4e26d4801f7p-5")) < a < mp.mpf(float.fromhex("0x1.6e4e26d4801f8p-5"))
+
+
+@pytest.mark.parametrize("theta,horner", [(0.0, False), (1.99 * U, False), (-1.99 * U, True), (0.0, True)])
+def test_gelu_tanh_bound_is_sound_on_a_dense_sweep(oracle_mod, theta, horner):
+    x = _sweep(1e-30, 30.0, 4001)
+    y = _gelu_tanh_run(x, theta, horner)
+    tau = oracle_mod.bound_act(oracle_mod.GELU_TANH, x, y)
+    worst = mp.mpf(0)
+    for xi, yi, ti in zip(x[::7], y[::7], tau[::7]):
+        err = abs(mp.mpf(float(yi)) - _gelu_tanh_exact(xi))
+        assert err <= mp.mpf(float(ti)), (xi, yi, ti)
+        if ti > 0:
+            worst = max(worst, err / mp.mpf(float(ti)))
+    assert worst > 0.15
+    # tightness: a handful of u times the magnitudes involved (7 roundings of p at sech^2 p <= 1,
+    # p <= 1.2 |x| where it matters, the tanh accuracy, two fresh roundings)
+    xd = np.abs(x.astype(np.float64))
+    assert np.all(tau <= 12 * U * np.maximum(xd, np.abs(y)) + 1e-300)
+
+
+def test_gelu_tanh_closed_form_special_values_and_limits(oracle_mod):
+    o = oracle_mod
+    z = np.zeros(3, f32)
+    assert np.all(o.bound_act(o.GELU_TANH, z, z) == 0)
+    xa = np.array([0.3, 1.0, 2.5], f32); ya = np.array([0.1, 0.2, 0.3], f32)
+    assert np.array_equal(o.bound_act(o.GELU_TANH, xa, ya), o.bound_act(o.GELU_TANH, -xa, -ya))
+    # the formula at a few points with 60 digits
+    u = mp.mpf(2) ** -24
+    g7 = 7 * u / (1 - 7 * u)
+    for xv in (0.01, 0.75, 1.25, 3.0, 9.0):
+        x1 = f32(xv); y1 = _gelu_tanh_run(np.array([x1]), 0.0, False)[0]
+        xs = mp.mpf(float(x1))
+        ps = mp.sqrt(2 / mp.pi) * (xs + mp.mpf("0.044715") * xs ** 3)
+        E_p = g7 * ps
+        Gp = 1 / mp.cosh(max(mp.mpf(0), ps - E_p)) ** 2
+        A = min(mp.mpf(1), ps * (1 + g7))
+        want = xs / 2 * (Gp * E_p + 4 * u * A) + u * mp.mpf(float(y1)) * (1 + 1 / (1 - u))
+        got = mp.mpf(float(o.bound_act(o.GELU_TANH, np.array([x1]), np.array([y1]))[0]))
+        assert want <= got <= want * (1 + mp.mpf(2) ** -22), xv
+    # far out the sensitivity term is gone: (|x|/2) c_tanh u + 2u|y|, and a looser tanh moves it
+    x = np.array([20.0], f32); y = x.copy()
+    t = float(o.bound_act(o.GELU_TANH, x, y)[0])
+    assert abs(t / (20.0 / 2 * 4 * U + 2 * U * 20.0) - 1) < 1e-6
+    assert o.bound_act(o.GELU_TANH, x, y, model=o.Model(c_tanh=8.0))[0] > t
