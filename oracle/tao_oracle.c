@@ -469,6 +469,7 @@ int taoo_bound_act(int kind, const float *x, const float *x2, const float *y, fl
     (void)x2;
     const double u = md->u;
     if (kind < 0 || kind > TAOO_GELU_TANH) return -3;
+    if ((kind == TAOO_GELU_ERF || kind == TAOO_GELU_TANH) && !x && n > 0) return -1;
 #pragma omp parallel
     {
         int saved = fegetround(); fesetround(FE_UPWARD);

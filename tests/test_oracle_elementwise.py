@@ -48,7 +48,9 @@ def test_factor_of_every_kind_as_an_exact_rational(oracle_mod):
     assert np.all(o.bound_act(o.LOG, None, y[:4], model=loose) > o.bound_act(o.LOG, None, y[:4]))
     assert np.array_equal(o.bound_act(o.SIN, None, y, model=loose), o.bound_act(o.SIN, None, y))
     with pytest.raises(ValueError):
-        o.bound_act(17, None, y)
+        o.bound_act(18, None, y)
+    with pytest.raises(ValueError):
+        o.bound_act(o.GELU_TANH, None, y)          # needs x
 
 
 FUNCS = {
