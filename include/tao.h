@@ -62,6 +62,11 @@ typedef struct tao_fp_model {
     double c_rsqrt;  /* rsqrt, or sqrt followed by a division (default 2) */
     double c_div;    /* division by n, or multiplication by a rounded 1/n (default 2) */
     unsigned flags;  /* TAO_FLAG_* */
+    double c_log;    /* log   (default 2) */
+    double c_sin;    /* sin   (default 4) */
+    double c_cos;    /* cos   (default 4) */
+    double c_tanh;   /* tanh  (default 4) */
+    double c_pow;    /* pow   (default 8) */
 } tao_fp_model;
 
 enum { TAO_MODE_DETERMINISTIC = 0, TAO_MODE_PROBABILISTIC = 1 };
@@ -87,10 +92,13 @@ typedef struct tao_profile {
 /* Operator kinds of tao_bound_norm and tao_bound_act (operator list of App. A.3). */
 enum { TAO_NORM_LAYERNORM = 0, TAO_NORM_RMSNORM = 1, TAO_NORM_BN_AFFINE = 2,
        TAO_NORM_SUM = 3, TAO_NORM_MEAN = 4 };
-enum { TAO_ACT_GELU_ERF = 0, TAO_ACT_SILU = 1, TAO_ACT_MUL = 2, TAO_ACT_ADD = 3, TAO_ACT_RELU = 4 };
+enum { TAO_ACT_GELU_ERF = 0, TAO_ACT_SILU = 1, TAO_ACT_MUL = 2, TAO_ACT_ADD = 3, TAO_ACT_RELU = 4,
+       TAO_ACT_SUB = 5, TAO_ACT_DIV = 6, TAO_ACT_EXACT = 7, TAO_ACT_SQRT = 8, TAO_ACT_RSQRT = 9,
+       TAO_ACT_EXP = 10, TAO_ACT_LOG = 11, TAO_ACT_SIN = 12, TAO_ACT_COS = 13, TAO_ACT_TANH = 14,
+       TAO_ACT_POW = 15, TAO_ACT_SIGMOID = 16, TAO_ACT_GELU_TANH = 17 };
 
 /* Fills *m with u = 2^-24, deterministic mode, lambda = 4, c_exp = c_erf =
- * c_rsqrt = c_div = 2, flags = 0. */
+ * c_rsqrt = c_div = c_log = 2, c_sin = c_cos = c_tanh = 4, c_pow = 8, flags = 0. */
 void tao_default_model(tao_fp_model *m);
 
 /* Gamma(k) on the host, rounded up in binary64: gamma_k = k u/(1 - k u)
@@ -174,10 +182,32 @@ int tao_bound_norm(int kind, const float *x, const float *y_ref,
  *            tau = |x|/2 ((2/sqrt pi) e^{-t_lo^2} E_t + c_erf u min(1, (2/sqrt pi)|t|(1+4u)))
  *                  + u |y| (1 + 1/(1-u)),  t = x/sqrt 2, E_t = (2u+u^2)|t|, t_lo = max(0,|t|-E_t).
  *  SILU      y = x/(1 + exp(-x)): tau = |y| (w/(1-u) + u), w = (c_exp u/(1-c_exp u) + u)/(1-u).
- *  MUL, ADD  one rounding: tau = u |y|.     RELU  exact: tau = 0.
- * x and x2 (the operands) are ignored except by GELU_ERF and may be NULL there. */
+ *  GELU_TANH y = 0.5 x (1 + tanh(p)), p = sqrt(2/pi)(x + 0.044715 x^3); needs x.
+ *            tau = |x|/2 (sech^2(p_lo) E_p + c_tanh u min(1, |p|(1+Gamma(7)))) + u |y| (1 + 1/(1-u)),
+ *            E_p = Gamma(7)|p| (seven roundings at most in either association of p,
+ *            constants included), p_lo = max(0, |p| - E_p).
+ *  SILU, SIGMOID  y = x/(1 + exp(-x)), 1/(1 + exp(-x)):
+ *            tau = |y| (w/(1-u) + u), w = (c_exp u/(1-c_exp u) + u)/(1-u).
+ *  MUL, ADD, SUB, SQRT  one correctly rounded operation: tau = u |y|.
+ *  RELU, EXACT  (Neg, Abs, Max, Min, max-pooling, masked fill, data movement): tau = 0.
+ *  DIV, RSQRT, EXP, LOG, SIN, COS, TANH, POW  a library function accurate to c u
+ *            relatively (c = c_div, c_rsqrt, c_exp, c_log, c_sin, c_cos, c_tanh, c_pow):
+ *            tau = |y| c u/(1 - c u).
+ * x and x2 (the operands) are ignored except by the two GELU kinds and may be NULL otherwise. */
 int tao_bound_act(int kind, const float *x, const float *x2, const float *y_ref, float *tau, long n,
                   const tao_fp_model *model, void *stream);
+
+/* Rotary position embedding (App. A.3: Sin/Cos tables applied to activations;
+ * each output is a two-term dot product of exact inputs, Sec. 3.1 reductions):
+ *     y_a = x_a cos - x_b sin,  y_b = x_b cos + x_a sin,
+ *     tau_a = Gamma(2)(|x_a cos| + |x_b sin|),  tau_b = Gamma(2)(|x_b cos| + |x_a sin|).
+ * x, tau: [rows][d] contiguous, d even; cos, sin: [npos][d/2] contiguous; row r
+ * uses table row (r / inner) % npos (inner = heads for a [token][head][d]
+ * layout, 1 for [head][token][d]).  Pairs (a, b) = (j, j + d/2), or (2j, 2j+1)
+ * when interleaved != 0.  TAO_ERR_SHAPE for odd d, inner < 1 or npos < 1. */
+int tao_bound_rope(const float *x, const float *cos_table, const float *sin_table, float *tau,
+                   long rows, long d, long inner, long npos, int interleaved,
+                   const tao_fp_model *model, void *stream);
 
 /* Leaf check (Sec. 5.4) and relative-error profile (Sec. 5.3; Sec. 3.2 Eq. 2)
  * of n elements, in IEEE binary64 per element:

@@ -22,6 +22,8 @@ MODE_DETERMINISTIC, MODE_PROBABILISTIC = 0, 1
 FLAG_UNDERFLOW_TERMS, FLAG_FAST_ACCUM = 1, 2
 NORM_LAYERNORM, NORM_RMSNORM, NORM_BN_AFFINE, NORM_SUM, NORM_MEAN = 0, 1, 2, 3, 4
 ACT_GELU_ERF, ACT_SILU, ACT_MUL, ACT_ADD, ACT_RELU = 0, 1, 2, 3, 4
+(ACT_SUB, ACT_DIV, ACT_EXACT, ACT_SQRT, ACT_RSQRT, ACT_EXP, ACT_LOG, ACT_SIN, ACT_COS, ACT_TANH,
+ ACT_POW, ACT_SIGMOID, ACT_GELU_TANH) = range(5, 18)
 
 
 class FpModel(ctypes.Structure):
@@ -29,11 +31,14 @@ class FpModel(ctypes.Structure):
     _fields_ = [("u", ctypes.c_double), ("mode", ctypes.c_int), ("lam", ctypes.c_double),
                 ("c_exp", ctypes.c_double), ("c_erf", ctypes.c_double),
                 ("c_rsqrt", ctypes.c_double), ("c_div", ctypes.c_double),
-                ("flags", ctypes.c_uint)]
+                ("flags", ctypes.c_uint),
+                ("c_log", ctypes.c_double), ("c_sin", ctypes.c_double), ("c_cos", ctypes.c_double),
+                ("c_tanh", ctypes.c_double), ("c_pow", ctypes.c_double)]
 
     def __init__(self, u=2.0 ** -24, mode=0, lam=4.0, c_exp=2.0, c_erf=2.0, c_rsqrt=2.0,
-                 c_div=2.0, flags=0):
-        super().__init__(u, mode, lam, c_exp, c_erf, c_rsqrt, c_div, flags)
+                 c_div=2.0, flags=0, c_log=2.0, c_sin=4.0, c_cos=4.0, c_tanh=4.0, c_pow=8.0):
+        super().__init__(u, mode, lam, c_exp, c_erf, c_rsqrt, c_div, flags,
+                         c_log, c_sin, c_cos, c_tanh, c_pow)
 
 
 class Profile(ctypes.Structure):
@@ -87,7 +92,7 @@ class TaoError(RuntimeError):
 
 
 EXPORTS = ["tao_default_model", "tao_gamma", "tao_bound_linear", "tao_bound_conv2d", "tao_bound_softmax",
-           "tao_bound_norm", "tao_bound_act", "tao_check_and_profile",
+           "tao_bound_norm", "tao_bound_act", "tao_bound_rope", "tao_check_and_profile",
            "tao_check_workspace_bytes", "tao_profile_errors", "tao_profile_workspace_bytes",
            "tao_calibrate_thresholds",
            "tao_selftest_matrix_core", "tao_last_hip_error", "tao_status_string"]
@@ -116,6 +121,7 @@ def lib():
     L.tao_bound_softmax.argtypes = [vp, vp, vp, lg, lg, lg, mp, vp]
     L.tao_bound_norm.argtypes = [ctypes.c_int, vp, vp, vp, vp, dbl, vp, lg, lg, lg, mp, vp]
     L.tao_bound_act.argtypes = [ctypes.c_int, vp, vp, vp, vp, lg, mp, vp]
+    L.tao_bound_rope.argtypes = [vp, vp, vp, vp, lg, lg, lg, lg, ctypes.c_int, mp, vp]
     L.tao_check_and_profile.argtypes = [vp, vp, vp, lg, dbl, dbl, vp, vp, ctypes.c_size_t, vp]
     L.tao_check_workspace_bytes.argtypes = [lg]
     L.tao_check_workspace_bytes.restype = ctypes.c_size_t
@@ -327,6 +333,28 @@ def tao_bound_act(kind, x, y_ref, x2=None, model=None, out=None):
     rc = lib().tao_bound_act(int(kind), _ptr(x), _ptr(x2), _ptr(y_ref), _ptr(out), y_ref.numel(),
                              _mref(model), _stream())
     _check(rc, "tao_bound_act")
+    return out
+
+
+def tao_bound_rope(x, cos, sin, inner=1, interleaved=False, model=None, out=None):
+    """tau like x[..., d] for the rotation of x by the tables cos, sin [npos, d/2]; row r of the
+    flattened x uses table row (r // inner) % npos; pairs (j, j + d/2), or (2j, 2j+1) when
+    interleaved."""
+    torch = _torch()
+    x = _dev(x, "x"); cos = _dev(cos, "cos"); sin = _dev(sin, "sin")
+    if x.dim() < 1 or not x.is_contiguous() or not cos.is_contiguous() or not sin.is_contiguous():
+        raise ValueError("x, cos and sin must be contiguous")
+    d = x.shape[-1]
+    if cos.dim() != 2 or cos.shape != sin.shape or cos.shape[1] * 2 != d:
+        raise ValueError("cos and sin must be [npos, d/2] with d even")
+    rows = x.numel() // d if d else 0
+    if out is None:
+        out = torch.empty_like(x)
+    elif out.shape != x.shape or not out.is_contiguous():
+        raise ValueError("out must be contiguous and shaped like x")
+    rc = lib().tao_bound_rope(_ptr(x), _ptr(cos), _ptr(sin), _ptr(out), rows, d, int(inner), cos.shape[0],
+                              int(bool(interleaved)), _mref(model), _stream())
+    _check(rc, "tao_bound_rope")
     return out
 
 

@@ -15,6 +15,7 @@ int resolve_model(const tao_fp_model* m, tao_fp_model* out) {
     if (out->mode == TAO_MODE_PROBABILISTIC && !(std::isfinite(out->lambda) && out->lambda > 0.0))
         return TAO_ERR_MODEL;
     if (!ok(out->c_exp) || !ok(out->c_erf) || !ok(out->c_rsqrt) || !ok(out->c_div)) return TAO_ERR_MODEL;
+    if (!ok(out->c_log) || !ok(out->c_sin) || !ok(out->c_cos) || !ok(out->c_tanh) || !ok(out->c_pow)) return TAO_ERR_MODEL;
     if (out->flags & ~(TAO_FLAG_UNDERFLOW_TERMS | TAO_FLAG_FAST_ACCUM)) return TAO_ERR_MODEL;
     return TAO_OK;
 }
@@ -46,6 +47,7 @@ void tao_default_model(tao_fp_model* m) {
     m->lambda = 4.0;
     m->c_exp = 2.0; m->c_erf = 2.0; m->c_rsqrt = 2.0; m->c_div = 2.0;
     m->flags = 0;
+    m->c_log = 2.0; m->c_sin = 4.0; m->c_cos = 4.0; m->c_tanh = 4.0; m->c_pow = 8.0;
 }
 
 double tao_gamma(long k, const tao_fp_model* model) {

@@ -20,9 +20,11 @@ __device__ __forceinline__ float up32(double v) {
 // and at most v(1 + 2^-23 + 2^-31) (three halves of that near the bottom of the normal range).
 // v(1 + 2^-24 + 2^-32) lies above the midpoint of the two binary32 neighbours of v, so round-to-
 // nearest moves it to the upper one; the 2^-150 keeps that true among subnormal results, where
-// rounding is absolute (0 stays 0: the tie goes to even).  NaN and +inf pass through.
+// rounding is absolute (0 stays 0: the tie goes to even; any v > 0 gets the next binary64 above
+// 2^-150 instead, so that a v too small to move the sum still ends on the smallest subnormal).
+// NaN and +inf pass through.
 __device__ __forceinline__ float up32g(double v) {
-    return (float)fma(v, 1.0 + 0x1p-24 + 0x1p-32, 0x1p-150);
+    return (float)fma(v, 1.0 + 0x1p-24 + 0x1p-32, v > 0.0 ? 0x1.0000000000001p-150 : 0x1p-150);
 }
 
 __device__ __forceinline__ double wave_sum(double v) {

@@ -38,7 +38,7 @@ def test_library_exports_every_declared_function(tao):
 def test_struct_layouts_match_the_header(tao):
     assert ctypes.sizeof(tao.Profile) == 8 * 3 + 4 * 10 + 8 * 2048
     assert tao.Profile.hist.offset == 64
-    assert ctypes.sizeof(tao.FpModel) == 64
+    assert ctypes.sizeof(tao.FpModel) == 104 and tao.FpModel.c_log.offset == 64
     assert ctypes.sizeof(tao.ErrorProfile) == 8 * 2 + 4 * 2 + 4 * 22 * 4 + 8 + 4 * 2 + 8 * 2048 * 2
     assert tao.ErrorProfile.p_max.offset % 8 == 0 and tao.ErrorProfile.hist_abs.offset % 8 == 0
     assert tao.GRID_PERCENT == [1, 5, 10, 15, 20, 25, 30, 35, 40, 45, 50, 55, 60, 65, 70, 75, 80, 85, 90,
@@ -46,6 +46,7 @@ def test_struct_layouts_match_the_header(tao):
     m = tao.tao_default_model()
     assert (m.u, m.mode, m.lam, m.c_exp, m.c_erf, m.c_rsqrt, m.c_div, m.flags) == \
         (2.0 ** -24, 0, 4.0, 2.0, 2.0, 2.0, 2.0, 0)
+    assert (m.c_log, m.c_sin, m.c_cos, m.c_tanh, m.c_pow) == (2.0, 4.0, 4.0, 4.0, 8.0)
 
 
 def test_host_gamma(tao):
@@ -78,7 +79,17 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_bound_norm(2, p, p, nul, p, 0.0, p, 4, 4, 4, None, None) == tao.ERR_NULL    # scale required
     assert L.tao_bound_norm(0, p, p, p, p, -1.0, p, 4, 4, 4, None, None) == tao.ERR_SHAPE
     # act
-    assert L.tao_bound_act(7, p, p, p, p, 4, None, None) == tao.ERR_KIND
+    assert L.tao_bound_act(18, p, p, p, p, 4, None, None) == tao.ERR_KIND
+    assert L.tao_bound_act(-1, p, p, p, p, 4, None, None) == tao.ERR_KIND
+    assert L.tao_bound_act(17, nul, nul, p, p, 4, None, None) == tao.ERR_NULL                # tanh-form GELU needs x
+    assert L.tao_bound_act(11, p, p, p, p, 4, ctypes.byref(tao.FpModel(c_log=-1.0)), None) == tao.ERR_MODEL
+    # rope: (rows, d, inner, npos, interleaved)
+    assert L.tao_bound_rope(p, p, p, p, 4, 7, 1, 1, 0, None, None) == tao.ERR_SHAPE          # odd d
+    assert L.tao_bound_rope(p, p, p, p, 4, 8, 0, 1, 0, None, None) == tao.ERR_SHAPE
+    assert L.tao_bound_rope(p, p, p, p, 4, 8, 1, 0, 0, None, None) == tao.ERR_SHAPE
+    assert L.tao_bound_rope(p, nul, p, p, 4, 8, 1, 1, 0, None, None) == tao.ERR_NULL
+    assert L.tao_bound_rope(p, p, odd, p, 4, 8, 1, 1, 0, None, None) == tao.ERR_ALIGN
+    assert L.tao_bound_rope(nul, nul, nul, nul, 0, 8, 1, 1, 0, None, None) == tao.OK
     assert L.tao_bound_act(0, nul, nul, p, p, 4, None, None) == tao.ERR_NULL                 # GELU needs x
     assert L.tao_bound_act(1, nul, nul, p, p, -4, None, None) == tao.ERR_SHAPE
     assert L.tao_bound_act(1, nul, nul, nul, nul, 0, None, None) == tao.OK

@@ -283,6 +283,83 @@ def test_act_shapes(tao, oracle_mod, kind, n, offset):
     assert_bound_parity(_np(t_gpu), t_or, "%s n=%d" % (kind, n))
 
 
+@pytest.mark.parametrize("kind", ["SUB", "DIV", "EXACT", "SQRT", "RSQRT", "EXP", "LOG", "SIN", "COS", "TANH",
+                                  "POW", "SIGMOID"])
+def test_one_step_kinds(tao, oracle_mod, kind):
+    """tau depends on the verifier's output alone: any y exercises the formula; sizes with a
+    ragged tail and a misaligned base, default and non-default accuracy constants."""
+    code = getattr(oracle_mod, kind)
+    assert code == getattr(tao, "ACT_" + kind)
+    g = torch.Generator().manual_seed(code)
+    for n, offset in ((1, 0), (4099, 1), ((1 << 18) + 3, 0)):
+        y = (torch.randn((n + offset,), generator=g) * 10.0 ** torch.randint(-30, 30, (n + offset,), generator=g))[offset:]
+        yg = torch.cat([torch.zeros(offset), y]).cuda()[offset:] if offset else y.cuda()
+        for mo, mg in ((None, None),
+                       (oracle_mod.Model(c_div=1.0, c_rsqrt=3.0, c_exp=1.0, c_log=5.0, c_sin=2.0, c_cos=6.0, c_tanh=2.0, c_pow=32.0),
+                        tao.FpModel(c_div=1.0, c_rsqrt=3.0, c_exp=1.0, c_log=5.0, c_sin=2.0, c_cos=6.0, c_tanh=2.0, c_pow=32.0))):
+            t_or = oracle_mod.bound_act(code, None, _np(y), model=mo)
+            t_gpu = tao.tao_bound_act(code, None, yg, model=mg)
+            assert_bound_parity(_np(t_gpu), t_or, "%s n=%d" % (kind, n))
+
+
+def test_gelu_tanh_shapes_and_range(tao, oracle_mod):
+    code = oracle_mod.GELU_TANH
+    for n, offset in ((1, 0), (1023, 0), (4096, 1), ((1 << 20) + 3, 0)):
+        g = torch.Generator().manual_seed(n + offset)
+        x = (torch.randn((n + offset,), generator=g) * 4)[offset:]
+        y = torch.nn.functional.gelu(x, approximate="tanh")
+        xg = torch.cat([torch.zeros(offset), x]).cuda()[offset:] if offset else x.cuda()
+        yg = torch.cat([torch.zeros(offset), y]).cuda()[offset:] if offset else y.cuda()
+        assert_bound_parity(_np(tao.tao_bound_act(code, xg, yg)), oracle_mod.bound_act(code, _np(x), _np(y)), "gelu tanh n=%d" % n)
+    x = torch.cat([torch.linspace(-40, 40, 200001),
+                   torch.tensor([0.0, -0.0, 1e-30, -1e-30, 1e-45, 38.5, -38.5, 1e20, -3e38, float("inf"), float("nan")])])
+    y = torch.nn.functional.gelu(x, approximate="tanh")
+    t_or = oracle_mod.bound_act(code, _np(x), _np(y))
+    assert_bound_parity(_np(tao.tao_bound_act(code, x.cuda(), y.cuda())), t_or, "gelu tanh range")
+    # the honest binary32 result is inside the bound, against binary64
+    y64 = torch.nn.functional.gelu(x[:200001].double(), approximate="tanh")
+    assert bool(((y[:200001].double() - y64).abs() <= torch.from_numpy(t_or[:200001]).double()).all())
+    m_o, m_g = oracle_mod.Model(c_tanh=9.0, flags=0), tao.FpModel(c_tanh=9.0)
+    assert_bound_parity(_np(tao.tao_bound_act(code, x.cuda(), y.cuda(), model=m_g)),
+                        oracle_mod.bound_act(code, _np(x), _np(y), model=m_o), "gelu tanh c_tanh=9")
+
+
+@pytest.mark.parametrize("rows,d,inner,npos,interleaved", [
+    (64, 128, 4, 16, False), (64, 128, 1, 64, True), (37, 6, 3, 5, False), (37, 6, 1, 7, True),
+    (5, 2, 1, 1, False), (1000, 64, 8, 125, False), (33, 20, 2, 3, True), (16384, 128, 32, 512, False)])
+def test_rope_shapes(tao, oracle_mod, rows, d, inner, npos, interleaved):
+    g = torch.Generator().manual_seed(rows + d)
+    x = torch.randn((rows, d), generator=g) * 3
+    pos = torch.arange(npos, dtype=torch.float64)[:, None]
+    freq = 1e6 ** (-torch.arange(d // 2, dtype=torch.float64) / max(d // 2, 1))[None, :]
+    cs, sn = torch.cos(pos * freq).float(), torch.sin(pos * freq).float()
+    t_or = oracle_mod.bound_rope(_np(x), _np(cs), _np(sn), inner=inner, interleaved=interleaved)
+    t_gpu = tao.tao_bound_rope(x.cuda(), cs.cuda(), sn.cuda(), inner=inner, interleaved=interleaved)
+    assert_bound_parity(_np(t_gpu), t_or, "rope %s" % ((rows, d, inner, npos, interleaved),))
+    # misaligned base: the scalar path
+    xo = torch.cat([torch.zeros(1), x.reshape(-1)]).cuda()[1:].reshape(rows, d)
+    assert_bound_parity(_np(tao.tao_bound_rope(xo, cs.cuda(), sn.cuda(), inner=inner, interleaved=interleaved)), t_or, "rope misaligned")
+    mo, mg = oracle_mod.Model(flags=1, mode=1), tao.FpModel(flags=tao.FLAG_UNDERFLOW_TERMS, mode=1)
+    assert_bound_parity(_np(tao.tao_bound_rope(x.cuda(), cs.cuda(), sn.cuda(), inner=inner, interleaved=interleaved, model=mg)),
+                        oracle_mod.bound_rope(_np(x), _np(cs), _np(sn), inner=inner, interleaved=interleaved, model=mo), "rope flags")
+
+
+def test_rope_accepts_a_real_rotation(tao, oracle_mod):
+    """Binary32 rotate-half RoPE against binary64: every error inside the GPU's bound."""
+    g = torch.Generator().manual_seed(4)
+    T, Hd, d = 256, 8, 128
+    x = torch.randn((T, Hd, d), generator=g)
+    pos = torch.arange(T, dtype=torch.float64)[:, None]
+    freq = 1e6 ** (-torch.arange(d // 2, dtype=torch.float64) / (d // 2))[None, :]
+    cs, sn = torch.cos(pos * freq).float(), torch.sin(pos * freq).float()
+    def rot(x, c, s):
+        a, b = x[..., :d // 2], x[..., d // 2:]
+        return torch.cat([a * c[:, None, :] - b * s[:, None, :], b * c[:, None, :] + a * s[:, None, :]], dim=-1)
+    y32, y64 = rot(x, cs, sn), rot(x.double(), cs.double(), sn.double())
+    tau = tao.tao_bound_rope(x.cuda(), cs.cuda(), sn.cuda(), inner=Hd)
+    assert bool(((y32.double() - y64).abs() <= tau.cpu().double()).all())
+
+
 def test_gelu_wide_range(tao, oracle_mod):
     x = torch.cat([torch.linspace(-40, 40, 200001), torch.tensor([0.0, -0.0, 1e-30, -1e-30, 38.5, -38.5])])
     y = tao_inputs.gelu_f32(x)
