@@ -48,7 +48,7 @@ _ACT = {"gelu": 0, "silu": 1, "mul": 2, "add": 3, "relu": 4}
 # algorithmic HBM bytes per output element of the streaming bound kernels (inputs read once,
 # tau written once)
 _STREAM_BYTES = {"softmax": 12, "layernorm": 12, "rmsnorm": 12, "bn_affine": 12, "gelu": 12,
-                 "silu": 8, "mul": 8, "add": 8}
+                 "silu": 8, "mul": 8, "add": 8, "rope": 8}
 
 
 class PlannedOp:
@@ -83,6 +83,8 @@ class PlannedOp:
                                eps=op.attrs["eps"], out=self.tau)
         elif self.kind == "bn_affine":
             tao.tao_bound_norm(2, a["x"], self.y_ref, a["scale"], a["shift"], out=self.tau)
+        elif self.kind == "rope":
+            tao.tao_bound_rope(a["x"], a["cos"], a["sin"], inner=op.attrs["inner"], out=self.tau)
         else:
             tao.tao_bound_act(_ACT[self.kind], a.get("x"), self.y_ref, x2=a.get("x2"), out=self.tau)
 
@@ -137,6 +139,7 @@ def cpu_baseline(ops, rows_per_op):
                     return t
                 return t.reshape(-1, t.shape[-1])[:rows_per_op] if t.dim() > 1 else t
             args = {k: (cut(v) if k in ("x", "x2") else v) for k, v in op.args.items()}
+            # (the first rows of a rotary operator are the first tokens: same table rows)
             sub = tao_inputs.Op(op.name, op.kind, args, cut(y), cut(op.claimed), op.attrs)
         # move to host before timing: the baseline is CPU work only
         sub.args = {k: (None if v is None else v.detach().cpu().contiguous()) for k, v in sub.args.items()}

@@ -29,7 +29,7 @@ class Op:
     """One traced operator: what kind of bound it needs, its operands, the
     verifier's own output and the claimed output."""
     name: str
-    kind: str                      # linear | softmax | layernorm | rmsnorm | bn_affine | gelu | silu | mul | add | sum | mean
+    kind: str                      # linear | softmax | layernorm | rmsnorm | bn_affine | gelu | silu | mul | add | sum | mean | rope
     args: Dict[str, Optional[torch.Tensor]]
     y_ref: torch.Tensor
     claimed: torch.Tensor
@@ -145,14 +145,20 @@ def affine_fused(x, s, t):
     return (x.double() * s.double() + t.double()).float()
 
 
-def rope(x, theta):
-    """Rotary embedding over the last dimension of [..., seq, head_dim] (harness-side input prep)."""
-    seq, hd = x.shape[-2], x.shape[-1]
-    inv = theta ** (-torch.arange(0, hd, 2, device=x.device, dtype=torch.float32) / hd)
-    ang = torch.arange(seq, device=x.device, dtype=torch.float32)[:, None] * inv[None, :]
-    cos, sin = torch.cos(ang), torch.sin(ang)
-    x1, x2 = x[..., : hd // 2], x[..., hd // 2:]
-    return torch.cat([x1 * cos - x2 * sin, x2 * cos + x1 * sin], dim=-1)
+def rope_tables(seq, hd, theta, device):
+    """cos / sin tables [seq, hd/2] of the rotary embedding, binary32."""
+    inv = theta ** (-torch.arange(0, hd, 2, device=device, dtype=torch.float32) / hd)
+    ang = torch.arange(seq, device=device, dtype=torch.float32)[:, None] * inv[None, :]
+    return torch.cos(ang), torch.sin(ang)
+
+
+def rope_rows(x, cos, sin, heads):
+    """Rotate-half embedding of x [seq*heads, hd] (token-major rows), binary32."""
+    hd = x.shape[-1]
+    xs = x.reshape(-1, heads, hd)
+    c, s = cos[:, None, :], sin[:, None, :]
+    a, b = xs[..., : hd // 2], xs[..., hd // 2:]
+    return torch.cat([a * c - b * s, b * c + a * s], dim=-1).reshape(x.shape)
 
 
 # ------------------------------------------------------------------ configurations
@@ -248,11 +254,22 @@ def config3(device="cpu", seed=SEED0 + 3, scale=1):
         return y
 
     h = rmsnorm("input_norm", x)
-    q = linear("q_proj", h, NQ * HD, 0).reshape(S, NQ, HD).permute(1, 0, 2)
-    k = linear("k_proj", h, NKV * HD, 1).reshape(S, NKV, HD).permute(1, 0, 2)
+    q = linear("q_proj", h, NQ * HD, 0)
+    k = linear("k_proj", h, NKV * HD, 1)
     v = linear("v_proj", h, NKV * HD, 2).reshape(S, NKV, HD).permute(1, 0, 2).contiguous()
-    q = rope(q, 1e6) * (1.0 / math.sqrt(HD))
-    k = rope(k, 1e6).contiguous()
+    cos, sin = rope_tables(S, HD, 1e6, device)
+
+    def rotary(name, a, heads):
+        rows = a.reshape(S * heads, HD)
+        y = rope_rows(rows, cos, sin, heads)
+        # two products and one addition leave no order to vary: the honest claim is bit-identical
+        # (a fused variant or the correctly rounded rotation can differ from y by up to 1.5 tau,
+        # which only a scale factor alpha = 2 admits)
+        ops.append(Op(name, "rope", {"x": rows, "cos": cos, "sin": sin}, y, y.clone(), {"inner": heads}))
+        return y.reshape(S, heads, HD).permute(1, 0, 2)
+
+    q = rotary("q_rope", q, NQ) * (1.0 / math.sqrt(HD))
+    k = rotary("k_rope", k, NKV).contiguous()
     # grouped-query attention: the G query heads of one kv head are stacked along M
     qg = q.reshape(NKV, G, S, HD).reshape(NKV, G * S, HD).contiguous()
     scores = qg @ k.transpose(-1, -2)                                   # [NKV, G*S, S]

@@ -23,6 +23,8 @@ def oracle_tau(oracle, op, model=None):
         return oracle.bound_norm(2, _np(a["x"]), y=_np(op.y_ref), g=_np(a["scale"]), b=_np(a["shift"]), model=model)
     if op.kind in ("sum", "mean"):
         return oracle.bound_norm(_NORM[op.kind], _np(a["x"]), y=_np(op.y_ref), model=model)
+    if op.kind == "rope":
+        return oracle.bound_rope(_np(a["x"]), _np(a["cos"]), _np(a["sin"]), inner=op.attrs["inner"], model=model)
     return oracle.bound_act(_ACT[op.kind], _np(a.get("x")), _np(op.y_ref), x2=_np(a.get("x2")), model=model)
 
 
@@ -42,6 +44,8 @@ def gpu_tau(tao, op, model=None, device="cuda"):
         return tao.tao_bound_norm(2, d(a["x"]), d(op.y_ref), d(a["scale"]), d(a["shift"]), model=model)
     if op.kind in ("sum", "mean"):
         return tao.tao_bound_norm(_NORM[op.kind], d(a["x"]), d(op.y_ref), model=model)
+    if op.kind == "rope":
+        return tao.tao_bound_rope(d(a["x"]), d(a["cos"]), d(a["sin"]), inner=op.attrs["inner"], model=model)
     return tao.tao_bound_act(_ACT[op.kind], d(a.get("x")), d(op.y_ref), x2=d(a.get("x2")), model=model)
 
 

@@ -50,6 +50,13 @@ def _sub_op(op, rows, batch=None):
             return t.reshape(-1, cols).index_select(0, dev_rows)
         args = {k: (cut(v) if k in ("x", "x2") and v is not None else v) for k, v in a.items()}
         y, c = cut(op.y_ref), cut(op.claimed)
+        attrs = op.attrs
+        if op.kind == "rope":       # each sampled row brings its own table row along
+            pos = (dev_rows // op.attrs["inner"]) % a["cos"].shape[0]
+            args["cos"], args["sin"] = a["cos"].index_select(0, pos), a["sin"].index_select(0, pos)
+            attrs = {"inner": 1}
+        cpu = lambda t: None if t is None else t.detach().cpu().contiguous()
+        return tao_inputs.Op(op.name, op.kind, {k: cpu(v) for k, v in args.items()}, cpu(y), cpu(c), attrs)
     cpu = lambda t: None if t is None else t.detach().cpu().contiguous()
     return tao_inputs.Op(op.name, op.kind, {k: cpu(v) for k, v in args.items()}, cpu(y), cpu(c), op.attrs)
 
