@@ -197,6 +197,26 @@ def bound_norm(kind, x, y=None, g=None, b=None, eps=0.0, model=None):
     return tau
 
 
+def bound_groupnorm(x, y, groups, g=None, b=None, eps=0.0, model=None):
+    """GroupNorm of x[N, C, *spatial] (channel-major, contiguous) with `groups` groups: each
+    (sample, group) is a LayerNorm over its C/groups channels times all spatial positions, with
+    the affine parameters of a channel repeated over that channel's positions.  Written as that
+    definition: one LayerNorm bound per group on the rows gathered over the batch."""
+    x = _f32(x); y = _f32(y)
+    N, C = x.shape[0], x.shape[1]
+    hw = int(np.prod(x.shape[2:], dtype=np.int64))
+    if groups < 1 or C % groups:
+        raise ValueError("channels must be a multiple of groups")
+    cpg = C // groups
+    xr = x.reshape(N, groups, cpg * hw); yr = y.reshape(N, groups, cpg * hw)
+    tau = np.empty_like(xr)
+    for j in range(groups):
+        gj = None if g is None else np.repeat(_f32(g)[j * cpg:(j + 1) * cpg], hw)
+        bj = None if b is None else np.repeat(_f32(b)[j * cpg:(j + 1) * cpg], hw)
+        tau[:, j, :] = bound_norm(LAYERNORM, xr[:, j, :], y=yr[:, j, :], g=gj, b=bj, eps=eps, model=model)
+    return tau.reshape(x.shape)
+
+
 def bound_act(kind, x, y, x2=None, model=None):
     model = model or Model()
     y = _f32(y)

@@ -231,3 +231,75 @@ def test_bn_affine_sound_fused_and_unfused(oracle_mod):
                 want = Fraction(1, 2 ** 24) * abs(frac(x[i, c]) * frac(s[c])) * (1 + Fraction(1, 2 ** 24)) \
                     + Fraction(1, 2 ** 24) * abs(frac(y[i, c]))
                 assert want <= frac(tau[i, c]) <= want * (1 + Fraction(1, 2 ** 22))
+
+
+# ---- GroupNorm (App. A.3 operator list): LayerNorm over each (sample, group) -------------------
+
+def _groupnorm_two_pass(x, groups, g, b, eps, dtype):
+    """The canonical two-pass algorithm on x[N, C, H, W] in the given precision."""
+    N, C = x.shape[:2]
+    xr = x.reshape(N, groups, -1).astype(dtype)
+    n = xr.shape[-1]
+    mu = (xr.sum(axis=-1, keepdims=True, dtype=dtype) / dtype(n)).astype(dtype)
+    d = (xr - mu).astype(dtype)
+    var = ((d * d).astype(dtype).sum(axis=-1, keepdims=True, dtype=dtype) / dtype(n)).astype(dtype)
+    r = (dtype(1) / np.sqrt((var + dtype(np.float32(eps))).astype(dtype))).astype(dtype)
+    h = (d * r).astype(dtype).reshape(x.shape)
+    shape = (1, C) + (1,) * (x.ndim - 2)
+    return ((h * g.reshape(shape).astype(dtype)).astype(dtype) + b.reshape(shape).astype(dtype)).astype(dtype)
+
+
+def test_groupnorm_is_layernorm_per_group_with_repeated_affine(oracle_mod):
+    o = oracle_mod
+    rng = np.random.Generator(np.random.Philox(71))
+    N, C, H, W, G = 3, 12, 4, 5, 4
+    x = rng.standard_normal((N, C, H, W)).astype(f32)
+    g = (1 + 0.3 * rng.standard_normal(C)).astype(f32); b = rng.standard_normal(C).astype(f32)
+    y = _groupnorm_two_pass(x, G, g, b, 1e-5, f32)
+    tau = o.bound_groupnorm(x, y, G, g, b, eps=1e-5)
+    assert tau.shape == x.shape
+    # one group, one position: plain LayerNorm over the channels
+    x1 = x[:, :, 0, 0].copy(); y1 = _groupnorm_two_pass(x1[:, :, None, None], 1, g, b, 1e-5, f32)[:, :, 0, 0]
+    assert np.array_equal(o.bound_groupnorm(x1[:, :, None, None], y1[:, :, None, None], 1, g, b, eps=1e-5)[:, :, 0, 0],
+                          o.bound_norm(o.LAYERNORM, x1, y=y1, g=g, b=b, eps=1e-5))
+    # a (sample, group) block on its own, element by element against the LayerNorm bound
+    cpg = C // G
+    for n_, j in ((0, 0), (2, 3), (1, 2)):
+        row = x[n_, j * cpg:(j + 1) * cpg].reshape(1, -1)
+        yrow = y[n_, j * cpg:(j + 1) * cpg].reshape(1, -1)
+        want = o.bound_norm(o.LAYERNORM, row, y=yrow, g=np.repeat(g[j * cpg:(j + 1) * cpg], H * W),
+                            b=np.repeat(b[j * cpg:(j + 1) * cpg], H * W), eps=1e-5)
+        assert np.array_equal(tau[n_, j * cpg:(j + 1) * cpg].reshape(1, -1), want)
+    # groups == channels is instance normalisation: every channel its own row, scalar affine
+    ti = o.bound_groupnorm(x, _groupnorm_two_pass(x, C, g, b, 1e-5, f32), C, g, b, eps=1e-5)
+    c = 7
+    yi = _groupnorm_two_pass(x, C, g, b, 1e-5, f32)
+    want = o.bound_norm(o.LAYERNORM, x[1, c].reshape(1, -1), y=yi[1, c].reshape(1, -1),
+                        g=np.full(H * W, g[c], f32), b=np.full(H * W, b[c], f32), eps=1e-5)
+    assert np.array_equal(ti[1, c].reshape(1, -1), want)
+    with pytest.raises(ValueError):
+        o.bound_groupnorm(x, y, 5, g, b)
+
+
+def test_groupnorm_bound_is_sound_and_follows_channel_permutations(oracle_mod):
+    o = oracle_mod
+    rng = np.random.Generator(np.random.Philox(72))
+    N, C, H, W, G = 2, 8, 6, 6, 2
+    worst = 0.0
+    for trial in range(5):
+        x = (rng.standard_normal((N, C, H, W)) * 2.0 ** rng.integers(-4, 5) + rng.standard_normal()).astype(f32)
+        g = (1 + 0.5 * rng.standard_normal(C)).astype(f32); b = rng.standard_normal(C).astype(f32)
+        y = _groupnorm_two_pass(x, G, g, b, 1e-5, f32)
+        ystar = _groupnorm_two_pass(x.astype(np.float64), G, g, b, 1e-5, np.float64)
+        tau = o.bound_groupnorm(x, y, G, g, b, eps=1e-5)
+        err = np.abs(y.astype(np.float64) - ystar)
+        assert np.all(err <= tau.astype(np.float64) + 1e-13 * np.abs(ystar))
+        worst = max(worst, float((err / tau).max()))
+    assert 0.02 < worst <= 1.0
+    # permuting the channels inside each group (with their affine parameters) permutes tau
+    cpg = C // G
+    perm = np.concatenate([j * cpg + rng.permutation(cpg) for j in range(G)])
+    xp, yp = x[:, perm], y[:, perm]
+    tp = o.bound_groupnorm(xp, yp, G, g[perm], b[perm], eps=1e-5)
+    # the sums run over the same multiset in another order: equal up to the last bits of binary64
+    assert np.all(np.abs(tp / tau[:, perm] - 1) < 1e-6)
