@@ -176,6 +176,24 @@ int tao_bound_norm(int kind, const float *x, const float *y_ref,
                    float *tau, long rows, long cols, long ld,
                    const tao_fp_model *model, void *stream);
 
+/* GroupNorm (operator list of App. A.3) of a channel-major tensor x[batch][channels][positions]
+ * (contiguous; positions = product of the spatial extents): every (sample, group) is a
+ * LayerNorm over its channels/groups channels times all positions, with gamma[c], beta[c]
+ * of a channel applied at all its positions; the bound is tao_bound_norm's LAYERNORM
+ * formula on those rows (n = channels/groups * positions).  gamma, beta: [channels] or
+ * NULL.  y_ref, tau: like x.  groups == channels gives instance normalisation.
+ * Rows of more than 8192 elements, when there are fewer than 512 of them, are cut
+ * into chunks that exchange partial sums through ws: device memory, 8-byte
+ * aligned, at least tao_groupnorm_workspace_bytes(...) bytes (0 otherwise; ws
+ * may then be NULL), contents irrelevant before and after; calls that share ws must be
+ * ordered on one stream.
+ * TAO_ERR_SHAPE when channels is not a multiple of groups or a row reaches 2^31
+ * elements; TAO_ERR_K_RANGE when n u >= 1; TAO_ERR_WORKSPACE when ws is too small. */
+int tao_bound_groupnorm(const float *x, const float *y_ref, const float *gamma, const float *beta,
+                        double eps, float *tau, long batch, long channels, long positions, long groups,
+                        const tao_fp_model *model, void *ws, size_t ws_bytes, void *stream);
+size_t tao_groupnorm_workspace_bytes(long batch, long channels, long positions, long groups);
+
 /* Element-wise operators (App. A.3), flat length n.  y_ref is the verifier's
  * binary32 output and is always required.
  *  GELU_ERF  y = 0.5 x (1 + erf(x/sqrt 2)); needs x.

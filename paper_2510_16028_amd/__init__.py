@@ -92,7 +92,7 @@ class TaoError(RuntimeError):
 
 
 EXPORTS = ["tao_default_model", "tao_gamma", "tao_bound_linear", "tao_bound_conv2d", "tao_bound_softmax",
-           "tao_bound_norm", "tao_bound_act", "tao_bound_rope", "tao_check_and_profile",
+           "tao_bound_norm", "tao_bound_groupnorm", "tao_groupnorm_workspace_bytes", "tao_bound_act", "tao_bound_rope", "tao_check_and_profile",
            "tao_check_workspace_bytes", "tao_profile_errors", "tao_profile_workspace_bytes",
            "tao_calibrate_thresholds",
            "tao_selftest_matrix_core", "tao_last_hip_error", "tao_status_string"]
@@ -120,6 +120,9 @@ def lib():
     L.tao_bound_conv2d.argtypes = [vp, vp, vp, vp] + [lg] * 13 + [mp, vp]
     L.tao_bound_softmax.argtypes = [vp, vp, vp, lg, lg, lg, mp, vp]
     L.tao_bound_norm.argtypes = [ctypes.c_int, vp, vp, vp, vp, dbl, vp, lg, lg, lg, mp, vp]
+    L.tao_bound_groupnorm.argtypes = [vp, vp, vp, vp, dbl, vp, lg, lg, lg, lg, mp, vp, ctypes.c_size_t, vp]
+    L.tao_groupnorm_workspace_bytes.argtypes = [lg, lg, lg, lg]
+    L.tao_groupnorm_workspace_bytes.restype = ctypes.c_size_t
     L.tao_bound_act.argtypes = [ctypes.c_int, vp, vp, vp, vp, lg, mp, vp]
     L.tao_bound_rope.argtypes = [vp, vp, vp, vp, lg, lg, lg, lg, ctypes.c_int, mp, vp]
     L.tao_check_and_profile.argtypes = [vp, vp, vp, lg, dbl, dbl, vp, vp, ctypes.c_size_t, vp]
@@ -318,6 +321,33 @@ def tao_bound_norm(kind, x, y_ref=None, gamma_or_scale=None, beta_or_shift=None,
     return out
 
 
+def tao_groupnorm_workspace_bytes(batch, channels, positions, groups):
+    return int(lib().tao_groupnorm_workspace_bytes(int(batch), int(channels), int(positions), int(groups)))
+
+
+def tao_bound_groupnorm(x, y_ref, groups, gamma=None, beta=None, eps=1e-5, model=None, out=None, ws=None):
+    """tau like x[N, C, *spatial] (contiguous, channel-major) for GroupNorm with `groups` groups."""
+    torch = _torch()
+    x = _dev(x, "x"); y_ref = _dev(y_ref, "y_ref"); gamma = _dev(gamma, "gamma"); beta = _dev(beta, "beta")
+    if x.dim() < 2 or not x.is_contiguous() or y_ref.shape != x.shape or not y_ref.is_contiguous():
+        raise ValueError("x and y_ref must be contiguous [N, C, ...] tensors of one shape")
+    N, C = x.shape[0], x.shape[1]
+    positions = x.numel() // (N * C) if N * C else 0
+    for t, nm in ((gamma, "gamma"), (beta, "beta")):
+        if t is not None and (t.dim() != 1 or t.shape[0] != C or not t.is_contiguous()):
+            raise ValueError("%s must be a contiguous [C] tensor" % nm)
+    if out is None:
+        out = torch.empty_like(x)
+    elif out.shape != x.shape or not out.is_contiguous():
+        raise ValueError("out must be contiguous and shaped like x")
+    if ws is None:
+        ws = _scratch(x.device, tao_groupnorm_workspace_bytes(N, C, positions, groups))
+    rc = lib().tao_bound_groupnorm(_ptr(x), _ptr(y_ref), _ptr(gamma), _ptr(beta), float(eps), _ptr(out),
+                                   N, C, positions, int(groups), _mref(model), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "tao_bound_groupnorm")
+    return out
+
+
 def tao_bound_act(kind, x, y_ref, x2=None, model=None, out=None):
     torch = _torch()
     x = _dev(x, "x"); x2 = _dev(x2, "x2"); y_ref = _dev(y_ref, "y_ref")
@@ -361,17 +391,20 @@ def tao_bound_rope(x, cos, sin, inner=1, interleaved=False, model=None, out=None
 _ws_cache = {}
 
 
-def _workspace(device, n):
+def _scratch(device, need):
     """One scratch tensor per (device, stream); calls on one stream are ordered, so sharing is safe."""
     torch = _torch()
-    need = lib().tao_check_workspace_bytes(int(n))
     key = (device.index if device.index is not None else torch.cuda.current_device(),
            torch.cuda.current_stream().cuda_stream)
     ws = _ws_cache.get(key)
     if ws is None or ws.numel() < need:
-        ws = torch.empty(need, dtype=torch.uint8, device=device)
+        ws = torch.empty(max(int(need), 256), dtype=torch.uint8, device=device)
         _ws_cache[key] = ws
     return ws
+
+
+def _workspace(device, n):
+    return _scratch(device, lib().tao_check_workspace_bytes(int(n)))
 
 
 def new_profile_buffer(device):

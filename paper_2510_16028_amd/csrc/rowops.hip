@@ -180,11 +180,48 @@ __device__ __forceinline__ bool rsqrt_tail(double vstar, double E_v, const RowCo
 //   E_p/|g| = (1+u) E_h + u r|d|,  E_h = D (E_r + u R) + r E_d
 // collapses to K1 |d| + K0.  Same real-number formula as the step-by-step chain; the different
 // binary64 rounding (a few 2^-53) is covered by the rounding margin of up32g.
-template <int TPR, int V>
-__global__ __launch_bounds__(kRowThreads) void layernorm_bound(
+// From E_mu, sum|d|, sum d^2 to the per-element coefficients: E_p/|g| = K1 |d| + K0.
+__device__ __forceinline__ void layernorm_tail(double E_mu, double s_ad, double s_d2, double n, const RowConsts& k,
+                                               double& K1, double& K0) {
+    const double up = k.u * k.inv1mu, Ep = E_mu * k.inv1mu;       // u', E'
+    const double c1 = 1.0 + up;
+    const double sD2 = c1 * c1 * s_d2 + 2.0 * c1 * Ep * s_ad + n * Ep * Ep;           // sum D^2
+    const double sEdD = up * (1.0 + c1) * s_d2 + Ep * (up + 1.0 + c1) * s_ad + n * Ep * Ep;  // sum E_d(|d|+D)
+    const double E_t = k.G * (1.0 + k.u) * sD2 + sEdD + k.u * sD2;
+    const double vstar = s_d2 * k.inv_n;
+    const double E_v = (E_t * k.inv_n + k.cd_u * vstar) * k.inv1mcd;
+    double rs, E_r, R;
+    const bool ok = rsqrt_tail(vstar, E_v, k, rs, E_r, R);
+    const double hc = E_r + k.u * R;                              // E_h = D hc + r E_d
+    K1 = (1.0 + k.u) * (c1 * hc + rs * up) + k.u * rs;
+    K0 = ok ? (1.0 + k.u) * Ep * (hc + rs) : NAN;                 // NaN row when the bound is not finite
+}
+
+// GROUPED (GroupNorm): a row is one (sample, group) of a channel-major tensor, cols = channels per
+// group x positions; column c takes the affine scale of channel (row % groups) * cpg + c / hw.
+struct GroupGeom { unsigned hw, cpg, groups; };
+template <int TPR, int V, bool GROUPED>
+__device__ __forceinline__ void layernorm_body(
     const float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ g,
-    float* __restrict__ tau, long rows, long cols, long ld, int vec_ok, int vec_g, RowConsts k) {
+    float* __restrict__ tau, long rows, long cols, long ld, int vec_ok, int vec_g, const RowConsts& k,
+    GroupGeom gg) {
     TAO_ROW_PROLOGUE
+    // the four scales of the vector that starts at column idx
+    const float* gb = (GROUPED && g && active) ? g + (unsigned long)(row % (long)gg.groups) * gg.cpg : g;
+    auto scales = [&](long idx) {
+        if (!g) return make_float4(1.f, 1.f, 1.f, 1.f);
+        if (!GROUPED) return load4(g, idx, limit, vec_g, 1.f);
+        float ge[4] = {1.f, 1.f, 1.f, 1.f};
+        if (idx < limit) {
+            unsigned ch = (unsigned)idx / gg.hw, rem = (unsigned)idx - ch * gg.hw;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (idx + c < limit) ge[c] = gb[ch];
+                if (++rem == gg.hw) { rem = 0; ++ch; }
+            }
+        }
+        return make_float4(ge[0], ge[1], ge[2], ge[3]);
+    };
     // a cached row also requests y and g up front: their latency then overlaps the reductions
     float4 xv[CACHED ? V : 1], yv[CACHED ? V : 1], gv[CACHED ? V : 1];
     double a1[2] = {0.0, 0.0};                                   // sum x, sum |x|
@@ -193,7 +230,7 @@ __global__ __launch_bounds__(kRowThreads) void layernorm_bound(
         if (CACHED) {
             xv[v] = X;
             yv[v] = load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
-            gv[v] = g ? load4(g, TAO_VEC_INDEX(v), limit, vec_g, 1.f) : make_float4(1.f, 1.f, 1.f, 1.f);
+            gv[v] = scales(TAO_VEC_INDEX(v));
         }
         const float e[4] = {X.x, X.y, X.z, X.w};
 #pragma unroll
@@ -216,23 +253,12 @@ __global__ __launch_bounds__(kRowThreads) void layernorm_bound(
         }
     }
     group_sum<TPR>(a2, 2, smem + 16);
-    const double up = k.u * k.inv1mu, Ep = E_mu * k.inv1mu;       // u', E'
-    const double c1 = 1.0 + up;
-    const double sD2 = c1 * c1 * a2[1] + 2.0 * c1 * Ep * a2[0] + n * Ep * Ep;           // sum D^2
-    const double sEdD = up * (1.0 + c1) * a2[1] + Ep * (up + 1.0 + c1) * a2[0] + n * Ep * Ep;  // sum E_d(|d|+D)
-    const double E_t = k.G * (1.0 + k.u) * sD2 + sEdD + k.u * sD2;
-    const double vstar = a2[1] * k.inv_n;
-    const double E_v = (E_t * k.inv_n + k.cd_u * vstar) * k.inv1mcd;
-    double rs, E_r, R;
-    const bool ok = rsqrt_tail(vstar, E_v, k, rs, E_r, R);
-    // E_p/|g| = K1 |d| + K0
-    const double hc = E_r + k.u * R;                              // E_h = D hc + r E_d
-    const double K1 = (1.0 + k.u) * (c1 * hc + rs * up) + k.u * rs;
-    const double K0 = ok ? (1.0 + k.u) * Ep * (hc + rs) : NAN;    // NaN row when the bound is not finite
+    double K1, K0;
+    layernorm_tail(E_mu, a2[0], a2[1], n, k, K1, K0);
     for (int v = 0; v < nv; ++v) {
         const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
         const float4 Y = CACHED ? yv[v] : load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
-        const float4 Gv = CACHED ? gv[v] : (g ? load4(g, TAO_VEC_INDEX(v), limit, vec_g, 1.f) : make_float4(1.f, 1.f, 1.f, 1.f));
+        const float4 Gv = CACHED ? gv[v] : scales(TAO_VEC_INDEX(v));
         const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w};
         const float ge[4] = {Gv.x, Gv.y, Gv.z, Gv.w};
         float te[4];
@@ -243,6 +269,127 @@ __global__ __launch_bounds__(kRowThreads) void layernorm_bound(
             te[c] = up32g(fma(k.u, (double)fabsf(ye[c]), ep));
         }
         store4(tau + roff, TAO_VEC_INDEX(v), limit, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
+    }
+}
+template <int TPR, int V>
+__global__ __launch_bounds__(kRowThreads) void layernorm_bound(
+    const float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ g,
+    float* __restrict__ tau, long rows, long cols, long ld, int vec_ok, int vec_g, RowConsts k) {
+    layernorm_body<TPR, V, false>(x, y, g, tau, rows, cols, ld, vec_ok, vec_g, k, GroupGeom());
+}
+template <int TPR, int V>
+__global__ __launch_bounds__(kRowThreads) void groupnorm_bound(
+    const float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ g,
+    float* __restrict__ tau, long rows, long cols, long ld, int vec_ok, RowConsts k, GroupGeom gg) {
+    layernorm_body<TPR, V, true>(x, y, g, tau, rows, cols, ld, vec_ok, 0, k, gg);
+}
+
+// ---- GroupNorm rows longer than the cached variants hold: the row is cut into chunks of
+// kChunk columns, one workgroup each, so that a few very long rows still fill the chip.  Three
+// passes, each reading its chunk once: (a) sum x, sum |x|; (b) the mean from the partials of
+// (a), then sum |d|, sum d^2; (c) all four sums, the row's coefficients, the bound.  Partials
+// live in a caller-supplied workspace, four binary64 values per (row, chunk); every workgroup
+// adds them up in the same order, so all chunks of a row see identical row constants.
+constexpr long kSplitMaxRows = 512;                            // from here on one workgroup per row
+constexpr int kChunkVecs = 8;                                  // float4 per thread
+constexpr long kChunk = (long)kRowThreads * kChunkVecs * 4;    // 8192 columns
+
+struct ChunkPos { long row, c0, limit; int s; };
+__device__ __forceinline__ ChunkPos chunk_pos(long cols, unsigned nchunk) {
+    ChunkPos p;
+    p.row = blockIdx.x / nchunk; p.s = (int)(blockIdx.x % nchunk);
+    p.c0 = (long)p.s * kChunk;
+    p.limit = cols - p.c0 < kChunk ? cols - p.c0 : kChunk;      // columns of this chunk
+    return p;
+}
+// sum over the chunks of a row of partial `which` .. `which + 1` (same order in every workgroup)
+__device__ __forceinline__ void chunk_totals(const double* __restrict__ part, unsigned nchunk, int which,
+                                             double* out2, double* smem) {
+    double a[2] = {0.0, 0.0};
+    for (unsigned s = threadIdx.x; s < nchunk; s += kRowThreads) { a[0] += part[s * 4 + which]; a[1] += part[s * 4 + which + 1]; }
+    group_sum<kRowThreads>(a, 2, smem);
+    out2[0] = a[0]; out2[1] = a[1];
+}
+__global__ __launch_bounds__(kRowThreads) void groupnorm_sums_a(const float* __restrict__ x, double* __restrict__ ws,
+                                                                long cols, unsigned nchunk, int vec_ok) {
+    __shared__ double smem[16];
+    const ChunkPos p = chunk_pos(cols, nchunk);
+    const float* xr = x + p.row * cols + p.c0;
+    double a[2] = {0.0, 0.0};
+#pragma unroll
+    for (int v = 0; v < kChunkVecs; ++v) {
+        const float4 X = load4<true>(xr, ((long)v * kRowThreads + threadIdx.x) * 4, p.limit, vec_ok, 0.f);
+        const float e[4] = {X.x, X.y, X.z, X.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { a[0] += (double)e[c]; a[1] += (double)fabsf(e[c]); }
+    }
+    group_sum<kRowThreads>(a, 2, smem);
+    if (threadIdx.x == 0) { double* o = ws + ((long)blockIdx.x) * 4; o[0] = a[0]; o[1] = a[1]; }
+}
+__global__ __launch_bounds__(kRowThreads) void groupnorm_sums_b(const float* __restrict__ x, double* __restrict__ ws,
+                                                                long cols, unsigned nchunk, int vec_ok, RowConsts k) {
+    __shared__ double smem[32];
+    const ChunkPos p = chunk_pos(cols, nchunk);
+    double t[2];
+    chunk_totals(ws + p.row * nchunk * 4, nchunk, 0, t, smem);
+    const double mu = t[0] * k.inv_n;
+    const float* xr = x + p.row * cols + p.c0;
+    double a[2] = {0.0, 0.0};
+#pragma unroll
+    for (int v = 0; v < kChunkVecs; ++v) {
+        const long idx = ((long)v * kRowThreads + threadIdx.x) * 4;
+        const float4 X = load4<true>(xr, idx, p.limit, vec_ok, 0.f);
+        const float e[4] = {X.x, X.y, X.z, X.w};
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const double d = (idx + c < p.limit) ? (double)e[c] - mu : 0.0;
+            a[0] += fabs(d);
+            a[1] = fma(d, d, a[1]);
+        }
+    }
+    group_sum<kRowThreads>(a, 2, smem + 16);
+    if (threadIdx.x == 0) { double* o = ws + ((long)blockIdx.x) * 4; o[2] = a[0]; o[3] = a[1]; }
+}
+__global__ __launch_bounds__(kRowThreads) void groupnorm_apply(
+    const float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ g, float* __restrict__ tau,
+    const double* __restrict__ ws, long cols, unsigned nchunk, int vec_ok, RowConsts k, GroupGeom gg) {
+    __shared__ double smem[32];
+    const ChunkPos p = chunk_pos(cols, nchunk);
+    double t1[2], t2[2];
+    chunk_totals(ws + p.row * nchunk * 4, nchunk, 0, t1, smem);
+    chunk_totals(ws + p.row * nchunk * 4, nchunk, 2, t2, smem + 16);
+    const double n = (double)cols;
+    const double mu = t1[0] * k.inv_n;
+    const double E_mu = ((k.G * t1[1]) * k.inv_n + k.cd_u * fabs(mu)) * k.inv1mcd;
+    double K1, K0;
+    layernorm_tail(E_mu, t2[0], t2[1], n, k, K1, K0);
+    const long roff = p.row * cols + p.c0;
+    const float* gb = g ? g + (unsigned long)(p.row % (long)gg.groups) * gg.cpg : nullptr;
+#pragma unroll 2
+    for (int v = 0; v < kChunkVecs; ++v) {
+        const long idx = ((long)v * kRowThreads + threadIdx.x) * 4;
+        if (idx >= p.limit) break;
+        const float4 X = load4<true>(x + roff, idx, p.limit, vec_ok, 0.f);
+        const float4 Y = load4<true>(y + roff, idx, p.limit, vec_ok, 0.f);
+        float ge[4] = {1.f, 1.f, 1.f, 1.f};
+        if (gb) {
+            const unsigned col = (unsigned)(p.c0 + idx);
+            unsigned ch = col / gg.hw, rem = col - ch * gg.hw;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (idx + c < p.limit) ge[c] = gb[ch];
+                if (++rem == gg.hw) { rem = 0; ++ch; }
+            }
+        }
+        const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w};
+        float te[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const double ad = fabs((double)xe[c] - mu);
+            const double ep = (double)fabsf(ge[c]) * fma(K1, ad, K0);
+            te[c] = up32g(fma(k.u, (double)fabsf(ye[c]), ep));
+        }
+        store4(tau + roff, idx, p.limit, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
     }
 }
 
@@ -446,6 +593,58 @@ int tao_bound_norm(int kind, const float* x, const float* y_ref, const float* ga
             break;
         }
     }
+    return launch_status();
+}
+
+size_t tao_groupnorm_workspace_bytes(long batch, long channels, long positions, long groups) {
+    using namespace tao;
+    if (batch <= 0 || channels <= 0 || positions <= 0 || groups < 1 || channels % groups) return 0;
+    const __int128 cols = (__int128)(channels / groups) * positions;
+    if (cols <= 8192 || cols >= (1L << 31) || batch * groups >= kSplitMaxRows) return 0;   // the row kernels need none
+    const long nchunk = (long)((cols + kChunk - 1) / kChunk);
+    return (size_t)batch * (size_t)groups * (size_t)nchunk * 4 * sizeof(double);
+}
+
+int tao_bound_groupnorm(const float* x, const float* y_ref, const float* gamma, const float* beta, double eps,
+                        float* tau, long batch, long channels, long positions, long groups,
+                        const tao_fp_model* model, void* ws, size_t ws_bytes, void* stream) {
+    using namespace tao;
+    (void)beta;
+    tao_fp_model md;
+    int rc = resolve_model(model, &md);
+    if (rc != TAO_OK) return rc;
+    if (batch < 0 || channels < 0 || positions < 0 || groups < 1 || channels % groups) return TAO_ERR_SHAPE;
+    const long cpg = channels / groups;
+    if (positions >= (1L << 31) || cpg >= (1L << 31) || groups >= (1L << 31)) return TAO_ERR_SHAPE;
+    if ((__int128)cpg * positions >= (1L << 31) || (__int128)batch * groups >= (1L << 40)) return TAO_ERR_SHAPE;
+    const long rows = batch * groups, cols = cpg * positions;
+    if (rows == 0 || cols == 0) return TAO_OK;
+    if (!x || !tau || !y_ref) return TAO_ERR_NULL;
+    if (!aligned(x, 4) || !aligned(y_ref, 4) || !aligned(tau, 4) || !aligned(gamma, 4)) return TAO_ERR_ALIGN;
+    if (!(eps >= 0.0) || !std::isfinite(eps)) return TAO_ERR_SHAPE;
+    RowConsts k;
+    rc = make_consts(md, cols, eps, &k);
+    if (rc != TAO_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const int vec_ok = aligned(x, 16) && aligned(y_ref, 16) && aligned(tau, 16) && (cols % 4 == 0);
+    GroupGeom gg;
+    gg.hw = (unsigned)positions; gg.cpg = (unsigned)cpg; gg.groups = (unsigned)groups;
+    // rows the cached variants hold, or enough rows to fill the chip with one workgroup each
+    // (measured: 1024 rows of 25088 run at 42 % of the HBM roofline that way, 32 % in chunks;
+    // 256 rows of 40960 at 20 % against 32 %)
+    if (cols <= 8192 || rows >= kSplitMaxRows) {
+        TAO_DISPATCH_ROWS(groupnorm_bound, 1024, rows, cols, st, x, y_ref, gamma, tau, rows, cols, cols, vec_ok, k, gg);
+        return launch_status();
+    }
+    const long nchunk = (cols + kChunk - 1) / kChunk;
+    if ((__int128)rows * nchunk >= (1L << 31)) return TAO_ERR_SHAPE;
+    const size_t need = (size_t)rows * (size_t)nchunk * 4 * sizeof(double);
+    if (!ws || ws_bytes < need || !aligned(ws, 8)) return TAO_ERR_WORKSPACE;
+    double* part = static_cast<double*>(ws);
+    const dim3 grid((unsigned)(rows * nchunk)), blk(kRowThreads);
+    hipLaunchKernelGGL(groupnorm_sums_a, grid, blk, 0, st, x, part, cols, (unsigned)nchunk, vec_ok);
+    hipLaunchKernelGGL(groupnorm_sums_b, grid, blk, 0, st, x, part, cols, (unsigned)nchunk, vec_ok, k);
+    hipLaunchKernelGGL(groupnorm_apply, grid, blk, 0, st, x, y_ref, gamma, tau, part, cols, (unsigned)nchunk, vec_ok, k, gg);
     return launch_status();
 }
 

@@ -78,6 +78,19 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_bound_norm(0, p, nul, p, p, 1e-5, p, 4, 4, 4, None, None) == tao.ERR_NULL   # y_ref required
     assert L.tao_bound_norm(2, p, p, nul, p, 0.0, p, 4, 4, 4, None, None) == tao.ERR_NULL    # scale required
     assert L.tao_bound_norm(0, p, p, p, p, -1.0, p, 4, 4, 4, None, None) == tao.ERR_SHAPE
+    # groupnorm: (eps, tau, batch, channels, positions, groups)
+    gn = lambda *a: L.tao_bound_groupnorm(*a, None, nul, 0, None)
+    assert gn(p, p, p, p, 1e-5, p, 2, 10, 16, 4) == tao.ERR_SHAPE    # 10 % 4
+    assert gn(p, p, p, p, 1e-5, p, 2, 8, 16, 0) == tao.ERR_SHAPE
+    assert gn(p, p, p, p, -1.0, p, 2, 8, 16, 4) == tao.ERR_SHAPE
+    assert gn(p, p, p, p, 1e-5, p, 2, 8, 2 ** 31, 4) == tao.ERR_SHAPE
+    assert gn(p, p, p, p, 1e-5, p, 2, 8, 2 ** 24, 4) == tao.ERR_K_RANGE
+    assert gn(p, nul, p, p, 1e-5, p, 2, 8, 16, 4) == tao.ERR_NULL
+    assert gn(odd, p, p, p, 1e-5, p, 2, 8, 16, 4) == tao.ERR_ALIGN
+    assert gn(nul, nul, nul, nul, 1e-5, nul, 0, 8, 16, 4) == tao.OK
+    assert gn(p, p, p, p, 1e-5, p, 2, 8, 8192, 4) == tao.ERR_WORKSPACE       # rows of 16384 need scratch
+    assert L.tao_groupnorm_workspace_bytes(2, 8, 8192, 4) == 2 * 4 * 2 * 4 * 8
+    assert L.tao_groupnorm_workspace_bytes(2, 8, 4096, 4) == 0 and L.tao_groupnorm_workspace_bytes(2, 9, 8192, 4) == 0
     # act
     assert L.tao_bound_act(18, p, p, p, p, 4, None, None) == tao.ERR_KIND
     assert L.tao_bound_act(-1, p, p, p, p, 4, None, None) == tao.ERR_KIND

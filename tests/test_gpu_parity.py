@@ -267,6 +267,36 @@ def test_norm_failure_rows_and_no_gamma(tao, oracle_mod):
     assert_bound_parity(_np(tao.tao_bound_norm(1, x[1:2].cuda(), y[1:2].cuda(), eps=1e-6)), t_or, "rmsnorm g=1")
 
 
+@pytest.mark.parametrize("N,C,spatial,G,affine", [
+    (2, 32, (16, 16), 8, True),       # rows of 1024: cached, one wavefront per row
+    (3, 12, (5, 7), 4, True),         # 105 columns: ragged, channel boundaries inside a vector
+    (2, 6, (3,), 6, True),            # instance norm, three positions
+    (1, 64, (32, 32), 32, False),     # 2048 columns, no affine
+    (2, 128, (24, 24), 32, True),     # 2304 columns
+    (1, 32, (64, 64), 2, True),       # 65536 columns: eight chunks per row
+    (3, 10, (41, 43), 2, True),       # 8815 columns: a full chunk and a ragged one, unaligned rows
+    (2, 4, (8193,), 4, False),        # one column beyond a chunk
+    (16, 64, (48, 48), 32, True),     # 512 rows of 4608 ... and
+    (64, 16, (70, 70), 8, True),      # 512 rows of 9800: long rows, one workgroup each (re-reading path)
+    (4, 16, (1,), 1, True),           # one position, one group: LayerNorm over the channels
+])
+def test_groupnorm_shapes(tao, oracle_mod, N, C, spatial, G, affine):
+    g = torch.Generator().manual_seed(N + 3 * C + G)
+    x = torch.randn((N, C) + spatial, generator=g) * 2 + 0.5
+    gam = (1 + 0.2 * torch.randn((C,), generator=g)) if affine else None
+    bet = torch.randn((C,), generator=g) if affine else None
+    y = torch.nn.functional.group_norm(x, G, gam, bet, eps=1e-5)
+    t_or = oracle_mod.bound_groupnorm(_np(x), _np(y), G, None if gam is None else _np(gam),
+                                      None if bet is None else _np(bet), eps=1e-5)
+    t_gpu = tao.tao_bound_groupnorm(x.cuda(), y.cuda(), G, None if gam is None else gam.cuda(),
+                                    None if bet is None else bet.cuda(), eps=1e-5)
+    assert_bound_parity(_np(t_gpu), t_or, "groupnorm %s" % ((N, C, spatial, G),))
+    # and the binary32 operator is inside the bound, against binary64
+    y64 = torch.nn.functional.group_norm(x.double(), G, None if gam is None else gam.double(),
+                                         None if bet is None else bet.double(), eps=float(np.float32(1e-5)))
+    assert bool(((y.double() - y64).abs() <= t_gpu.cpu().double()).all())
+
+
 @pytest.mark.parametrize("kind", ["gelu", "silu", "mul", "add", "relu"])
 @pytest.mark.parametrize("n,offset", [(1, 0), (1023, 0), (4096, 1), ((1 << 20) + 3, 0)])
 def test_act_shapes(tao, oracle_mod, kind, n, offset):
