@@ -177,6 +177,56 @@ def test_conv2d_accepts_a_real_convolution(tao, oracle_mod):
     assert_bound_parity(_np(tau), t_or, "conv nchw view")
 
 
+def test_linear_random_shapes_and_strides(tao, oracle_mod):
+    """Forty seeded shapes around the tile and slab sizes, with padded row strides, batches,
+    either W layout and optional bias: every element against the oracle."""
+    rng = np.random.Generator(np.random.Philox(2024))
+    edges = [1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 191, 255, 256, 257]
+    for case in range(40):
+        M = int(rng.choice(edges)) if rng.random() < 0.6 else int(rng.integers(1, 300))
+        N = int(rng.choice(edges)) if rng.random() < 0.6 else int(rng.integers(1, 300))
+        K = int(rng.choice(edges + [0, 4, 96, 160])) if rng.random() < 0.6 else int(rng.integers(1, 300))
+        batch = int(rng.integers(1, 4))
+        trans_w = bool(rng.integers(0, 2)); bias = bool(rng.integers(0, 2))
+        pad_a, pad_w = int(rng.choice([0, 0, 1, 4, 7])), int(rng.choice([0, 0, 3, 4, 12]))
+        g = torch.Generator().manual_seed(1000 + case)
+        Afull = torch.randn((batch, M, K + pad_a), generator=g)
+        wshape = (batch, K, N + pad_w) if trans_w else (batch, N, K + pad_w)
+        Wfull = torch.randn(wshape, generator=g)
+        b = torch.randn((N,), generator=g) if bias else None
+        A = Afull[:, :, :K]; W = Wfull[:, :, :N] if trans_w else Wfull[:, :, :K]
+        what = "case %d: M=%d N=%d K=%d batch=%d trans_w=%s bias=%s pads=(%d,%d)" % (case, M, N, K, batch, trans_w, bias, pad_a, pad_w)
+        print(what, flush=True)
+        t_or = oracle_mod.bound_linear(_np(A.contiguous()), _np(W.contiguous()), None if b is None else _np(b), trans_w=trans_w)
+        t_gpu = tao.tao_bound_linear(Afull.cuda()[:, :, :K], Wfull.cuda()[:, :, :N] if trans_w else Wfull.cuda()[:, :, :K],
+                                     None if b is None else b.cuda(), trans_w=trans_w)
+        assert_bound_parity(_np(t_gpu), t_or, what)
+
+
+def test_conv2d_random_geometries(tao, oracle_mod):
+    """Thirty seeded convolution geometries (strides, paddings, dilations, channel counts on both
+    sides of the 32-channel gather path) against the oracle's direct loop."""
+    rng = np.random.Generator(np.random.Philox(2025))
+    for case in range(30):
+        C = int(rng.choice([1, 3, 8, 32, 32, 64, 96, 40]))
+        Cout = int(rng.choice([1, 5, 64, 128, 128, 130, 256]))
+        R, S = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        sh, sw = int(rng.integers(1, 3)), int(rng.integers(1, 3))
+        dh, dw = int(rng.integers(1, 3)), int(rng.integers(1, 3))
+        ph, pw = int(rng.integers(0, 3)), int(rng.integers(0, 3))
+        H = int(rng.integers(max(1, dh * (R - 1) + 1 - 2 * ph), 20)); W = int(rng.integers(max(1, dw * (S - 1) + 1 - 2 * pw), 20))
+        B = int(rng.integers(1, 4))
+        what = "case %d: B=%d H=%d W=%d C=%d Cout=%d R=%d S=%d stride=(%d,%d) pad=(%d,%d) dil=(%d,%d)" % (
+            case, B, H, W, C, Cout, R, S, sh, sw, ph, pw, dh, dw)
+        print(what, flush=True)
+        g = torch.Generator().manual_seed(3000 + case)
+        x = torch.randn((B, H, W, C), generator=g); w = torch.randn((Cout, R, S, C), generator=g)
+        b = torch.randn((Cout,), generator=g) if case % 2 else None
+        t_or = oracle_mod.bound_conv2d(_np(x), _np(w), None if b is None else _np(b), (sh, sw), (ph, pw), (dh, dw))
+        t_gpu = tao.tao_bound_conv2d(x.cuda(), w.cuda(), None if b is None else b.cuda(), (sh, sw), (ph, pw), (dh, dw))
+        assert_bound_parity(_np(t_gpu), t_or, what)
+
+
 def test_linear_unaligned_views_and_modes(tao, oracle_mod):
     g = torch.Generator().manual_seed(77)
     Abig = torch.randn((150, 203), generator=g).cuda()
