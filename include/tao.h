@@ -245,6 +245,19 @@ int tao_check_and_profile(const float *claimed, const float *ref, const float *t
  * Calls that share a workspace must be ordered on one stream. */
 size_t tao_check_workspace_bytes(long n);
 
+/* Softmax bound and leaf check in one pass (Sec. 3.1 softmax template, Sec. 5.4
+ * check, Sec. 5.3 profile): the result is, field by field, that of
+ *     tao_bound_softmax(x, y_ref, tau, ...); tao_check_and_profile(claimed, y_ref, tau, ...)
+ * but tau lives only in registers (rounded to binary32 as it would have been
+ * stored): the pass reads x, y_ref and claimed once and writes nothing but the
+ * profile.  x, y_ref, claimed: [rows][cols], row stride ld (n = rows * cols).
+ * alpha, eps_rel, out, ws, ws_bytes: as for tao_check_and_profile (workspace of
+ * tao_check_workspace_bytes(n)).  Errors as for the two calls. */
+int tao_bound_check_softmax(const float *x, const float *y_ref, const float *claimed,
+                            long rows, long cols, long ld, double alpha, double eps_rel,
+                            const tao_fp_model *model, tao_profile *out,
+                            void *ws, size_t ws_bytes, void *stream);
+
 /* Error profile of tao_profile_errors (lives in DEVICE memory, 8-byte aligned). */
 #define TAO_NGRID 22   /* percentile grid P = {1, 5, 10, ..., 95, 99, 100} of Sec. 3.2 / Sec. 5.3 */
 typedef struct tao_error_profile {

@@ -93,7 +93,7 @@ class TaoError(RuntimeError):
 
 EXPORTS = ["tao_default_model", "tao_gamma", "tao_bound_linear", "tao_bound_conv2d", "tao_bound_softmax",
            "tao_bound_norm", "tao_bound_groupnorm", "tao_groupnorm_workspace_bytes", "tao_bound_act", "tao_bound_rope", "tao_check_and_profile",
-           "tao_check_workspace_bytes", "tao_profile_errors", "tao_profile_workspace_bytes",
+           "tao_check_workspace_bytes", "tao_bound_check_softmax", "tao_profile_errors", "tao_profile_workspace_bytes",
            "tao_calibrate_thresholds",
            "tao_selftest_matrix_core", "tao_last_hip_error", "tao_status_string"]
 
@@ -127,6 +127,7 @@ def lib():
     L.tao_bound_rope.argtypes = [vp, vp, vp, vp, lg, lg, lg, lg, ctypes.c_int, mp, vp]
     L.tao_check_and_profile.argtypes = [vp, vp, vp, lg, dbl, dbl, vp, vp, ctypes.c_size_t, vp]
     L.tao_check_workspace_bytes.argtypes = [lg]
+    L.tao_bound_check_softmax.argtypes = [vp, vp, vp, lg, lg, lg, dbl, dbl, mp, vp, vp, ctypes.c_size_t, vp]
     L.tao_check_workspace_bytes.restype = ctypes.c_size_t
     L.tao_profile_errors.argtypes = [vp, vp, lg, dbl, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.tao_calibrate_thresholds.argtypes = [vp, lg, dbl, vp, vp, vp, vp, vp]
@@ -436,6 +437,24 @@ def tao_check_and_profile(claimed, ref, tau, alpha=1.0, eps_rel=1e-12, out=None,
     rc = lib().tao_check_and_profile(_ptr(claimed), _ptr(ref), _ptr(tau), n, float(alpha),
                                      float(eps_rel), _ptr(out), _ptr(ws), ws.numel(), _stream())
     _check(rc, "tao_check_and_profile")
+    return read_profile(out) if readback else out
+
+
+def tao_bound_check_softmax(x, y_ref, claimed, alpha=1.0, eps_rel=1e-12, model=None, out=None, ws=None,
+                            readback=True):
+    """The softmax bound checked against `claimed` in one pass; same result as tao_bound_softmax
+    followed by tao_check_and_profile(claimed, y_ref, tau), without a stored tau."""
+    x = _dev(x, "x"); y_ref = _dev(y_ref, "y_ref"); claimed = _dev(claimed, "claimed")
+    if x.shape != y_ref.shape or x.stride() != y_ref.stride() or claimed.shape != x.shape or claimed.stride() != x.stride():
+        raise ValueError("x, y_ref and claimed must have the same shape and strides")
+    rows, cols, ld = _rows_view(x, "x")
+    if out is None:
+        out = new_profile_buffer(x.device)
+    if ws is None:
+        ws = _workspace(x.device, rows * cols)
+    rc = lib().tao_bound_check_softmax(_ptr(x), _ptr(y_ref), _ptr(claimed), rows, cols, ld, float(alpha),
+                                       float(eps_rel), _mref(model), _ptr(out), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "tao_bound_check_softmax")
     return read_profile(out) if readback else out
 
 

@@ -13,42 +13,9 @@
 // number of elements below its own bins; it can then decide by itself whether a
 // nearest-rank percentile falls into one of its bins -- no cross-workgroup
 // ordering, fences or atomics.  Workgroup 0 also writes the scalar fields.
-#include "tao_hist.hpp"
-#include "tao_host.hpp"
+#include "tao_check.hpp"
 
 namespace tao {
-
-constexpr int kCheckThreads = 1024;          // one workgroup per CU: one partial histogram per CU
-constexpr int kMaxCheckBlocks = kMaxPartials;
-constexpr int kReduceBlocks = kGroups;
-
-struct BlockStats {          // one per pass-1 workgroup, in the workspace after the histograms
-    unsigned long long violations;
-    unsigned long long nans;
-    unsigned int max_bits;   // bit pattern of the largest non-NaN error (errors are >= 0)
-    unsigned int pad;
-};
-
-struct ThreadAcc {
-    unsigned int violations = 0, nans = 0, max_bits = 0;
-};
-
-__device__ __forceinline__ void check_one(float c, float r, float t, double alpha, double eps_rel,
-                                          unsigned int* hist, int rep, ThreadAcc& acc) {
-    const double cd = (double)c, rd = (double)r;
-    const double d = fabs(cd - rd);
-    const double T = alpha * (double)t;
-    acc.violations += !(d <= T);
-    const double den = fabs(rd) + eps_rel;
-    const double e = d / den;
-    const float e32 = (float)e;
-    bool isn;
-    const unsigned int bin = error_bin(e32, isn);
-    const unsigned int bits = __float_as_uint(e32);
-    acc.nans += isn;
-    if (!isn) acc.max_bits = max(acc.max_bits, bits);
-    atomicAdd(&hist[bin * kReplicas + rep], 1u);
-}
 
 __global__ __launch_bounds__(kCheckThreads) void check_pass(
     const float* __restrict__ claimed, const float* __restrict__ ref, const float* __restrict__ tau,
@@ -78,25 +45,7 @@ __global__ __launch_bounds__(kCheckThreads) void check_pass(
     for (long i = (nvec << 2) + (long)blockIdx.x * kCheckThreads + tid; i < n; i += stride)
         check_one(claimed[i], ref[i], tau[i], alpha, eps_rel, hist, rep, acc);
 
-    // workgroup totals of the three counters
-    unsigned int v = acc.violations, q = acc.nans, m = acc.max_bits;
-#pragma unroll
-    for (int o = kWave / 2; o > 0; o >>= 1) {
-        v += __shfl_xor(v, o, kWave);
-        q += __shfl_xor(q, o, kWave);
-        m = max(m, (unsigned int)__shfl_xor(m, o, kWave));
-    }
-    const int wave = tid / kWave;
-    if ((tid & (kWave - 1)) == 0) { red[wave * 3] = v; red[wave * 3 + 1] = q; red[wave * 3 + 2] = m; }
-    __syncthreads();
-    if (tid == 0) {
-        BlockStats s{0, 0, 0, 0};
-        for (int w = 0; w < kCheckThreads / kWave; ++w) {
-            s.violations += red[w * 3]; s.nans += red[w * 3 + 1];
-            s.max_bits = max(s.max_bits, red[w * 3 + 2]);
-        }
-        ws_stats[blockIdx.x] = s;
-    }
+    flush_block_stats(acc, red, ws_stats);
     flush_histogram(hist, ws_hist + (size_t)blockIdx.x * kBins, ws_coarse + blockIdx.x * kGroups);
 }
 
@@ -141,14 +90,18 @@ __global__ __launch_bounds__(kReduceThreads) void profile_reduce(
     }
 }
 
+void launch_profile_reduce(const CheckWorkspace& w, int nblocks, unsigned long long n, tao_profile* out, hipStream_t st) {
+    hipLaunchKernelGGL(profile_reduce, dim3(kReduceBlocks), dim3(kReduceThreads), 0, st, w.hist, w.coarse,
+                       w.stats, nblocks, n, out);
+}
+
 }  // namespace tao
 
 extern "C" {
 
 size_t tao_check_workspace_bytes(long n) {
     (void)n;
-    return (size_t)tao::kMaxCheckBlocks *
-           ((tao::kBins + tao::kGroups) * sizeof(unsigned int) + sizeof(tao::BlockStats));
+    return tao::check_workspace_bytes();
 }
 
 int tao_check_and_profile(const float* claimed, const float* ref, const float* tau, long n,
@@ -166,13 +119,10 @@ int tao_check_and_profile(const float* claimed, const float* ref, const float* t
     // 16 elements (four 16-byte vectors) per thread before another workgroup is worth it
     long want = (n + (long)kCheckThreads * 16 - 1) / ((long)kCheckThreads * 16);
     int nblocks = (int)(want < 1 ? 1 : (want > kMaxCheckBlocks ? kMaxCheckBlocks : want));
-    unsigned int* ws_hist = (unsigned int*)ws;
-    unsigned int* ws_coarse = ws_hist + (size_t)kMaxCheckBlocks * kBins;
-    BlockStats* ws_stats = (BlockStats*)(ws_coarse + (size_t)kMaxCheckBlocks * kGroups);
+    const CheckWorkspace w = carve_check_workspace(ws);
     hipLaunchKernelGGL(check_pass, dim3(nblocks), dim3(kCheckThreads), 0, st, claimed, ref, tau, n,
-                       vec_ok, alpha, eps_rel, ws_hist, ws_coarse, ws_stats);
-    hipLaunchKernelGGL(profile_reduce, dim3(kReduceBlocks), dim3(kReduceThreads), 0, st, ws_hist, ws_coarse,
-                       ws_stats, nblocks, (unsigned long long)n, out);
+                       vec_ok, alpha, eps_rel, w.hist, w.coarse, w.stats);
+    launch_profile_reduce(w, nblocks, (unsigned long long)n, out, st);
     return launch_status();
 }
 

@@ -12,6 +12,7 @@
 // Formulas: Sec. 3.1 softmax template closed to second order; LayerNorm,
 // RMSNorm, BatchNorm-affine, sum and mean (operators of App. A.3) from the
 // primitive rule of Sec. 3.1 with Gamma(n-1) for the reductions (App. A.2).
+#include "tao_check.hpp"
 #include "tao_device.hpp"
 #include "tao_host.hpp"
 
@@ -152,6 +153,127 @@ __global__ __launch_bounds__(kRowThreads) void softmax_bound(
         }
         store4(tau + roff, TAO_VEC_INDEX(v), limit, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
     }
+}
+
+// ---- softmax bound checked in registers (the bound is never stored) --------------------------
+// Same arithmetic as softmax_bound element by element, followed by the leaf check of
+// tao_check_and_profile on (claimed, y, tau) with tau first rounded to binary32 as it would have
+// been stored.  Workgroups of 1024 threads walk the rows (1024 / TPR at a time), keep the
+// histogram of relative errors in LDS and leave one partial per workgroup, like the streaming
+// check pass; the same finalising kernel turns the partials into the profile.  HBM traffic:
+// x, y and claimed read once (12 B per element), nothing written.
+template <int TPR>
+__device__ __forceinline__ void wide_group_sum(double* v, int count, double* smem) {
+    for (int i = 0; i < count; ++i) v[i] = wave_sum(v[i]);
+    if (TPR > kWave) {
+        const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+        const int first = (threadIdx.x / TPR) * (TPR / kWave);       // first wavefront of this row group
+        if (lane == 0) for (int i = 0; i < count; ++i) smem[wave * 4 + i] = v[i];
+        __syncthreads();
+        for (int i = 0; i < count; ++i) {
+            double s = 0;
+            for (int w = 0; w < TPR / kWave; ++w) s += smem[(first + w) * 4 + i];
+            v[i] = s;
+        }
+    }
+}
+template <int TPR>
+__device__ __forceinline__ void wide_group_max_or(float& m, int& flag, double* smem) {
+    m = wave_max(m);
+    flag = wave_or(flag);
+    if (TPR > kWave) {
+        const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+        const int first = (threadIdx.x / TPR) * (TPR / kWave);
+        if (lane == 0) { smem[wave * 4] = (double)m; smem[wave * 4 + 1] = (double)flag; }
+        __syncthreads();
+        float mm = -INFINITY; int ff = 0;
+        for (int w = 0; w < TPR / kWave; ++w) { mm = fmaxf(mm, (float)smem[(first + w) * 4]); ff |= (int)smem[(first + w) * 4 + 1]; }
+        m = mm; flag = ff;
+    }
+}
+
+template <int TPR, int V>
+__global__ __launch_bounds__(kCheckThreads) void softmax_check(
+    const float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ claimed,
+    long rows, long cols, long ld, int vec_ok, RowConsts k, double alpha, double eps_rel,
+    unsigned int* __restrict__ ws_hist, unsigned int* __restrict__ ws_coarse, BlockStats* __restrict__ ws_stats) {
+    constexpr int RPB = kCheckThreads / TPR;
+    constexpr bool CACHED = (V > 0);
+    __shared__ unsigned int hist[kBins * kReplicas];
+    __shared__ unsigned int red[3 * (kCheckThreads / kWave)];
+    __shared__ double smem[2 * 4 * (kCheckThreads / kWave)];       // one slot per reduction of a row
+    const int tid = threadIdx.x;
+    for (int i = tid; i < kBins * kReplicas; i += kCheckThreads) hist[i] = 0;
+    __syncthreads();
+    ThreadAcc acc_chk;
+    const int rep = tid & (kReplicas - 1);
+    const int lt = tid % TPR;
+    const int nv = CACHED ? V : (int)((cols + TPR * 4 - 1) / (TPR * 4));
+    const long nblocks = (rows + RPB - 1) / RPB;
+    // every thread of the workgroup takes the same number of trips (the reductions hold barriers)
+    for (long rb = blockIdx.x; rb < nblocks; rb += gridDim.x) {
+        const long row = rb * RPB + tid / TPR;
+        const bool active = row < rows;
+        const long limit = active ? cols : 0;
+        const long roff = active ? row * ld : 0;
+        float4 xv[CACHED ? V : 1], yv[CACHED ? V : 1];
+        float m = -INFINITY; int bad = 0;
+        for (int v = 0; v < nv; ++v) {
+            const float4 X = load4<CACHED>(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, -INFINITY);
+            if (CACHED) { xv[v] = X; yv[v] = load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f); }
+            const float e[4] = {X.x, X.y, X.z, X.w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) { bad |= (e[c] != e[c]) | (e[c] == INFINITY); m = fmaxf(m, e[c]); }
+        }
+        wide_group_max_or<TPR>(m, bad, smem);
+        if (m == -INFINITY) bad = 1;
+        const double uam = k.u * fabs((double)m);
+        const double ce_inv = k.ce_u * k.inv1mce;
+        double acc[2] = {0.0, 0.0};
+        auto q_rho = [&](float xe, float ye, double& q, double& rho) __attribute__((always_inline)) {
+            const bool masked = xe == -INFINITY;
+            const double ax = (double)(masked ? 0.f : fabsf(xe));
+            const double a = fma(k.u, ax, uam);
+            rho = fma(fma(a, a, a), k.inv1mce, ce_inv);
+            q = (double)(masked ? 0.f : fabsf(ye)) * k.inv1mu;
+        };
+        for (int v = 0; v < nv; ++v) {
+            const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, -INFINITY);
+            const float4 Y = CACHED ? yv[v] : load4(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+            const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                double q, rho;
+                q_rho(xe[c], ye[c], q, rho);
+                acc[0] += q; acc[1] = fma(rho, q, acc[1]);
+            }
+        }
+        wide_group_sum<TPR>(acc, 2, smem + 4 * (kCheckThreads / kWave));
+        const double sigma = k.G * acc[0] + (1.0 + k.G) * acc[1];
+        if (!(sigma < 1.0)) bad = 1;
+        const double sfac = sigma / (1.0 - sigma);
+        const double w1 = bad ? NAN : 1.0 + sfac;
+        const double w0 = bad ? NAN : sfac + k.u;
+        for (int v = 0; v < nv; ++v) {
+            const long idx = TAO_VEC_INDEX(v);
+            if (idx >= limit) continue;
+            const float4 X = CACHED ? xv[v] : load4(x + roff, idx, limit, vec_ok, -INFINITY);
+            const float4 Y = CACHED ? yv[v] : load4(y + roff, idx, limit, vec_ok, 0.f);
+            const float4 C = load4<true>(claimed + roff, idx, limit, vec_ok, 0.f);
+            const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w}, ce[4] = {C.x, C.y, C.z, C.w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (idx + c >= limit) break;
+                double q, rho;
+                q_rho(xe[c], ye[c], q, rho);
+                const float t = up32g(q * fma(rho, w1, w0));
+                check_one(ce[c], ye[c], t, alpha, eps_rel, hist, rep, acc_chk);
+            }
+        }
+    }
+    __syncthreads();
+    flush_block_stats(acc_chk, red, ws_stats);
+    flush_histogram(hist, ws_hist + (size_t)blockIdx.x * kBins, ws_coarse + blockIdx.x * kGroups);
 }
 
 // tail shared by LayerNorm and RMSNorm: from v*, E_v to (r*, E_r, R); ok = finite bound
@@ -645,6 +767,53 @@ int tao_bound_groupnorm(const float* x, const float* y_ref, const float* gamma, 
     hipLaunchKernelGGL(groupnorm_sums_a, grid, blk, 0, st, x, part, cols, (unsigned)nchunk, vec_ok);
     hipLaunchKernelGGL(groupnorm_sums_b, grid, blk, 0, st, x, part, cols, (unsigned)nchunk, vec_ok, k);
     hipLaunchKernelGGL(groupnorm_apply, grid, blk, 0, st, x, y_ref, gamma, tau, part, cols, (unsigned)nchunk, vec_ok, k, gg);
+    return launch_status();
+}
+
+int tao_bound_check_softmax(const float* x, const float* y_ref, const float* claimed, long rows, long cols, long ld,
+                            double alpha, double eps_rel, const tao_fp_model* model, tao_profile* out,
+                            void* ws, size_t ws_bytes, void* stream) {
+    using namespace tao;
+    tao_fp_model md;
+    int rc = resolve_model(model, &md);
+    if (rc != TAO_OK) return rc;
+    if (!out || !ws) return out ? TAO_ERR_WORKSPACE : TAO_ERR_NULL;
+    if (rows < 0 || cols < 0 || ld < cols) return TAO_ERR_SHAPE;
+    const long n = rows * cols;
+    if (rows > 0 && cols > 0 && n / cols != rows) return TAO_ERR_SHAPE;
+    if (n >= (1L << 36)) return TAO_ERR_SHAPE;                      // 32-bit per-workgroup counters
+    if (n > 0 && (!x || !y_ref || !claimed)) return TAO_ERR_NULL;
+    if (!aligned(x, 4) || !aligned(y_ref, 4) || !aligned(claimed, 4) || !aligned(out, 8)) return TAO_ERR_ALIGN;
+    if (!aligned(ws, 256) || ws_bytes < check_workspace_bytes()) return TAO_ERR_WORKSPACE;
+    RowConsts k;
+    rc = make_consts(md, cols > 0 ? cols : 1, 0.0, &k);
+    if (rc != TAO_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const CheckWorkspace w = carve_check_workspace(ws);
+    const int vec_ok = aligned(x, 16) && aligned(y_ref, 16) && aligned(claimed, 16) && (ld % 4 == 0);
+    int nblocks = 1;
+    if (n > 0) {
+        auto launch = [&](auto kernel, int tpr) {
+            const long rb = (rows + (kCheckThreads / tpr) - 1) / (kCheckThreads / tpr);
+            nblocks = (int)(rb < kMaxCheckBlocks ? rb : kMaxCheckBlocks);
+            hipLaunchKernelGGL(kernel, dim3(nblocks), dim3(kCheckThreads), 0, st, x, y_ref, claimed, rows, cols, ld,
+                               vec_ok, k, alpha, eps_rel, w.hist, w.coarse, w.stats);
+        };
+        // at most two vectors per thread (the check's binary64 division leaves no room for more
+        // under the 128-register limit of a 1024-thread workgroup): longer rows take wider groups
+        if (cols <= 256)       launch(softmax_check<64, 1>, 64);
+        else if (cols <= 512)  launch(softmax_check<64, 2>, 64);
+        else if (cols <= 1024) launch(softmax_check<256, 1>, 256);
+        else if (cols <= 2048) launch(softmax_check<256, 2>, 256);
+        else if (cols <= 4096) launch(softmax_check<512, 2>, 512);
+        else if (cols <= 8192) launch(softmax_check<1024, 2>, 1024);
+        else                   launch(softmax_check<1024, 0>, 1024);
+    } else {
+        // nothing to examine: an empty partial, so that the profile reports n = 0
+        hipLaunchKernelGGL((softmax_check<64, 1>), dim3(1), dim3(kCheckThreads), 0, st, x, y_ref, claimed, 0L, 1L, 1L,
+                           0, k, alpha, eps_rel, w.hist, w.coarse, w.stats);
+    }
+    launch_profile_reduce(w, nblocks, (unsigned long long)n, out, st);
     return launch_status();
 }
 

@@ -1,0 +1,84 @@
+// Pieces of the leaf check (Sec. 5.4) and relative-error profile (Sec. 5.3; Sec. 3.2 Eq. 2) shared by
+// the streaming check pass and by bound kernels that check their bound in registers instead of
+// storing it: the per-element step, the per-workgroup counters, the workspace layout and the
+// launch of the finalising kernel.
+#pragma once
+#include "tao_hist.hpp"
+#include "tao_host.hpp"
+
+namespace tao {
+
+constexpr int kCheckThreads = 1024;          // one workgroup per CU: one partial histogram per CU
+constexpr int kMaxCheckBlocks = kMaxPartials;
+constexpr int kReduceBlocks = kGroups;
+
+struct BlockStats {          // one per pass-1 workgroup, in the workspace after the histograms
+    unsigned long long violations;
+    unsigned long long nans;
+    unsigned int max_bits;   // bit pattern of the largest non-NaN error (errors are >= 0)
+    unsigned int pad;
+};
+
+struct ThreadAcc {
+    unsigned int violations = 0, nans = 0, max_bits = 0;
+};
+
+__device__ __forceinline__ void check_one(float c, float r, float t, double alpha, double eps_rel,
+                                          unsigned int* hist, int rep, ThreadAcc& acc) {
+    const double cd = (double)c, rd = (double)r;
+    const double d = fabs(cd - rd);
+    const double T = alpha * (double)t;
+    acc.violations += !(d <= T);
+    const double den = fabs(rd) + eps_rel;
+    const double e = d / den;
+    const float e32 = (float)e;
+    bool isn;
+    const unsigned int bin = error_bin(e32, isn);
+    const unsigned int bits = __float_as_uint(e32);
+    acc.nans += isn;
+    if (!isn) acc.max_bits = max(acc.max_bits, bits);
+    atomicAdd(&hist[bin * kReplicas + rep], 1u);
+}
+
+// Workgroup totals of the per-thread counters (kCheckThreads threads) into ws_stats[blockIdx.x];
+// red: 3 * (kCheckThreads / kWave) words of LDS.  Contains one barrier.
+__device__ __forceinline__ void flush_block_stats(const ThreadAcc& acc, unsigned int* red, BlockStats* __restrict__ ws_stats) {
+    const int tid = threadIdx.x;
+    unsigned int v = acc.violations, q = acc.nans, m = acc.max_bits;
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) {
+        v += __shfl_xor(v, o, kWave);
+        q += __shfl_xor(q, o, kWave);
+        m = max(m, (unsigned int)__shfl_xor(m, o, kWave));
+    }
+    const int wave = tid / kWave;
+    if ((tid & (kWave - 1)) == 0) { red[wave * 3] = v; red[wave * 3 + 1] = q; red[wave * 3 + 2] = m; }
+    __syncthreads();
+    if (tid == 0) {
+        BlockStats s{0, 0, 0, 0};
+        for (int w = 0; w < kCheckThreads / kWave; ++w) {
+            s.violations += red[w * 3]; s.nans += red[w * 3 + 1];
+            s.max_bits = max(s.max_bits, red[w * 3 + 2]);
+        }
+        ws_stats[blockIdx.x] = s;
+    }
+}
+
+// The caller's workspace: kMaxCheckBlocks partial histograms, their coarse group counts, the counters.
+struct CheckWorkspace {
+    unsigned int* hist; unsigned int* coarse; BlockStats* stats;
+};
+inline size_t check_workspace_bytes() {
+    return (size_t)kMaxCheckBlocks * ((kBins + kGroups) * sizeof(unsigned int) + sizeof(BlockStats));
+}
+inline CheckWorkspace carve_check_workspace(void* ws) {
+    CheckWorkspace w;
+    w.hist = (unsigned int*)ws;
+    w.coarse = w.hist + (size_t)kMaxCheckBlocks * kBins;
+    w.stats = (BlockStats*)(w.coarse + (size_t)kMaxCheckBlocks * kGroups);
+    return w;
+}
+// Enqueue the finalising kernel over the partials of `nblocks` pass-1 workgroups (defined with the check pass).
+void launch_profile_reduce(const CheckWorkspace& w, int nblocks, unsigned long long n, tao_profile* out, hipStream_t st);
+
+}  // namespace tao

@@ -138,6 +138,13 @@ def test_argument_validation_without_a_gpu(tao):
     need = L.tao_check_workspace_bytes(1000)
     assert need > 0
     ws = ctypes.c_void_p(0x10000)
+    # softmax bound checked in one pass: (rows, cols, ld, alpha, eps_rel, model, out, ws, ws_bytes)
+    assert L.tao_bound_check_softmax(p, p, p, 4, 8, 4, 1.0, 0.0, None, p, ws, need, None) == tao.ERR_SHAPE      # ld < cols
+    assert L.tao_bound_check_softmax(p, p, nul, 4, 8, 8, 1.0, 0.0, None, p, ws, need, None) == tao.ERR_NULL
+    assert L.tao_bound_check_softmax(p, p, p, 4, 8, 8, 1.0, 0.0, None, nul, ws, need, None) == tao.ERR_NULL
+    assert L.tao_bound_check_softmax(p, p, p, 4, 8, 8, 1.0, 0.0, None, p, ws, need - 1, None) == tao.ERR_WORKSPACE
+    assert L.tao_bound_check_softmax(p, odd, p, 4, 8, 8, 1.0, 0.0, None, p, ws, need, None) == tao.ERR_ALIGN
+    assert L.tao_bound_check_softmax(p, p, p, 4, 2 ** 24 + 2, 2 ** 24 + 2, 1.0, 0.0, None, p, ws, need, None) == tao.ERR_K_RANGE
     assert L.tao_check_and_profile(p, p, p, 10, 1.0, 0.0, nul, ws, need, None) == tao.ERR_NULL
     assert L.tao_check_and_profile(p, p, p, 10, 1.0, 0.0, p, nul, need, None) == tao.ERR_WORKSPACE
     assert L.tao_check_and_profile(p, p, p, 10, 1.0, 0.0, p, ws, need - 1, None) == tao.ERR_WORKSPACE

@@ -317,6 +317,33 @@ def test_norm_failure_rows_and_no_gamma(tao, oracle_mod):
     assert_bound_parity(_np(tao.tao_bound_norm(1, x[1:2].cuda(), y[1:2].cuda(), eps=1e-6)), t_or, "rmsnorm g=1")
 
 
+@pytest.mark.parametrize("rows,cols", [(1, 1), (3, 7), (64, 128), (100, 200), (513, 512), (257, 1000), (96, 2048),
+                                       (40, 3000), (33, 4096), (9, 5000), (4, 20000), (5000, 64), (0, 16)])
+def test_softmax_bound_checked_in_one_pass(tao, oracle_mod, rows, cols):
+    """Field for field the profile of the two separate calls on the GPU, and of the oracle's check
+    run on the GPU's stored bound; masked entries, a failing row and planted violations included."""
+    g = torch.Generator().manual_seed(rows * 31 + cols)
+    x = torch.randn((rows, cols), generator=g) * 3
+    if rows > 2 and cols > 4:
+        x[1, cols // 2:] = float("-inf")           # masked tail
+        x[2, 0] = float("nan")                     # a row without a bound
+    y = tao_inputs.softmax_f32(x) if rows else x.clone()
+    claimed = tao_inputs.softmax_f32_reordered(g, x) if rows else x.clone()
+    if rows > 4:
+        claimed[3] = claimed[3] * 1.001            # planted violations
+    xg, yg, cg = x.cuda(), y.cuda(), claimed.cuda()
+    for alpha, eps in ((1.0, 1e-12), (2.5, 1e-6)):
+        fused = tao.tao_bound_check_softmax(xg, yg, cg, alpha=alpha, eps_rel=eps)
+        tau = tao.tao_bound_softmax(xg, yg)
+        two = tao.tao_check_and_profile(cg, yg, tau, alpha=alpha, eps_rel=eps)
+        assert_profile_equal(fused, two, "one pass vs two passes %dx%d" % (rows, cols))
+        po = oracle_mod.check_and_profile(_np(claimed), _np(y), _np(tau), alpha=alpha, eps_rel=eps)
+        assert_profile_equal(fused, po, "one pass vs oracle check %dx%d" % (rows, cols))
+        assert fused["n"] == rows * cols
+    if rows > 4 and cols > 4:
+        assert fused["violations"] > 0
+
+
 @pytest.mark.parametrize("N,C,spatial,G,affine", [
     (2, 32, (16, 16), 8, True),       # rows of 1024: cached, one wavefront per row
     (3, 12, (5, 7), 4, True),         # 105 columns: ragged, channel boundaries inside a vector
