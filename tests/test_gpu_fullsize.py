@@ -181,3 +181,35 @@ def test_profile_errors_67m_elements_bit_exact(tao, oracle_mod):
         assert np.array_equal(pg[k].view(np.uint32), po[k].view(np.uint32)), k
     assert pg["max_abs"] == po["max_abs"] and pg["max_rel"] == po["max_rel"] and pg["p_max"] == po["p_max"]
     assert pg["n"] == n and abs(pg["p_max"] - 1 / 3) < 1e-6
+
+
+def test_more_than_2_31_elements(tao, oracle_mod):
+    """Index arithmetic beyond 32 bits: the check over 2^31 + 12345 elements bit-exact against the
+    oracle, an element-wise bound of the same length on sampled stretches, and a matmul bound
+    with more than 2^31 outputs on sampled rows."""
+    n = (1 << 31) + 12345
+    c, r, t = tao_inputs.check_triplet("cuda", seed=99, n=n)
+    pg = tao.tao_check_and_profile(c, r, t)
+    assert pg["n"] == n
+    po = oracle_mod.check_and_profile(_np(c), _np(r), _np(t))
+    assert_profile_equal(pg, po, "2^31 check")
+    assert 0 < po["violations"] < n
+    del c, t
+    # SiLU bound over the same length: first, last and two inner stretches
+    y = torch.nn.functional.silu(r)
+    tau = tao.tao_bound_act(tao.ACT_SILU, r, y)
+    for lo in (0, (1 << 31) - 4096, n - 5000, 1234567891):
+        hi = min(lo + 8192, n)
+        assert_bound_parity(_np(tau[lo:hi]), oracle_mod.bound_act(oracle_mod.SILU, _np(r[lo:hi]), _np(y[lo:hi])),
+                            "silu stretch at %d" % lo)
+    del r, y, tau
+    torch.cuda.empty_cache()
+    # 70000 x 32768 outputs (2.29e9), K = 16
+    M, N, K = 70000, 32768, 16
+    g = torch.Generator(device="cuda").manual_seed(98)
+    A = torch.randn((M, K), device="cuda", generator=g); W = torch.randn((N, K), device="cuda", generator=g)
+    tau = tao.tao_bound_linear(A, W)
+    rows = torch.tensor([0, 1, 65535, 65536, 65537, M - 1, 31337], device="cuda")
+    t_or = oracle_mod.bound_linear(_np(A.index_select(0, rows)), _np(W))
+    assert_bound_parity(_np(tau.index_select(0, rows)), t_or, "2.29e9-output matmul rows")
+    assert bool((tau > 0).all())
