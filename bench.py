@@ -54,7 +54,7 @@ _STREAM_BYTES = {"softmax": 12, "layernorm": 12, "rmsnorm": 12, "bn_affine": 12,
 class PlannedOp:
     """One operator with every buffer preallocated; run() only enqueues kernels."""
 
-    def __init__(self, tao, torch, op):
+    def __init__(self, tao, torch, op, use_split=True):
         self.tao, self.op, self.kind, self.name = tao, op, op.kind, op.name
         self.claimed = op.claimed.contiguous()
         self.y_ref = op.y_ref.contiguous()
@@ -62,11 +62,20 @@ class PlannedOp:
         self.prof = tao.new_profile_buffer(self.y_ref.device)
         self.n = self.y_ref.numel()
         a = op.args
+        self.split = False
         if self.kind == "linear":
             A, W = a["A"], a["W"]
             K = A.shape[-1]
             self.flops = 2.0 * self.n * K
             self.min_bytes = 4.0 * (A.numel() + W.numel() + self.n)
+            batch = A.shape[0] if A.dim() == 3 else 1
+            M, N = self.y_ref.shape[-2], self.y_ref.shape[-1]
+            # the library's own rule picks the BF16-split or the FP32 matrix-core path per shape
+            self.split = use_split and tao.tao_linear_split_preferred(M, N, K, batch)
+            if self.split:
+                shared = W.dim() == 2 or batch == 1
+                self.ws = torch.empty(tao.tao_linear_split_workspace_bytes(M, N, K, batch, shared),
+                                      dtype=torch.uint8, device=A.device)
         else:
             self.flops = 0.0
             self.min_bytes = 0.0
@@ -74,7 +83,10 @@ class PlannedOp:
 
     def bound(self):
         tao, a, op = self.tao, self.op.args, self.op
-        if self.kind == "linear":
+        if self.kind == "linear" and self.split:
+            tao.tao_bound_linear_split(a["A"], a["W"], a.get("bias"), trans_w=bool(op.attrs.get("trans_w", 0)),
+                                       out=self.tau, ws=self.ws)
+        elif self.kind == "linear":
             tao.tao_bound_linear(a["A"], a["W"], a.get("bias"), trans_w=bool(op.attrs.get("trans_w", 0)), out=self.tau)
         elif self.kind == "softmax":
             tao.tao_bound_softmax(a["x"], self.y_ref, out=self.tau)
@@ -168,6 +180,7 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=2048, help="output rows per operator for the CPU oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stress", action="store_true", help="skip the 8192^3 / 67M-element side measurements")
+    ap.add_argument("--fp32-only", action="store_true", help="matmul bounds on the FP32 matrix cores only (no BF16-split path)")
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run three 1 GiB element-wise copy kernels (reference kernel for scaling FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -185,7 +198,7 @@ def main():
     torch.cuda.set_device(0)
 
     ops = tao_inputs.config3(dev, scale=args.scale)
-    plan = [PlannedOp(tao, torch, op) for op in ops]
+    plan = [PlannedOp(tao, torch, op, use_split=not args.fp32_only) for op in ops]
     torch.cuda.synchronize()
 
     for _ in range(args.warmup):
@@ -210,9 +223,21 @@ def main():
     lin_launches = sum(len(p.bound_events) for p in lin)
     lin_flops = sum(p.flops * len(p.bound_events) for p in lin)
     achieved = lin_flops / (lin_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "absgemm_bound", "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
-                "traffic": measured_traffic("absgemm_bound") if args.scale == 1 else None,
+    # the matmul bound, both paths together: algorithmic flop (2MNK) per second against the FP32 MFMA
+    # peak the metric names; a BF16-split launch issues 8 BF16 products per operand pair and includes
+    # its pre-pass
+    sp = [p for p in lin if p.split]
+    paths = {}
+    for nm, sel, mult, peak in (("bf16_split", sp, 8.0, 2500.0), ("fp32", [p for p in lin if not p.split], 1.0, PEAK_FP32_MFMA_TFLOPS)):
+        if sel:
+            ms = sum(sum(_ms(p.bound_events)) for p in sel)
+            fl = sum(p.flops * len(p.bound_events) for p in sel)
+            paths[nm] = {"ops": [p.name for p in sel], "TFLOP/s": fl / (ms * 1e-3) / 1e12,
+                         "issued_TFLOP/s": mult * fl / (ms * 1e-3) / 1e12, "issued_frac_of_own_peak": mult * fl / (ms * 1e-3) / 1e12 / peak}
+    roofline = {"bound": "mfma", "kernel": "absgemm_split + absgemm_bound" if sp else "absgemm_bound",
+                "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "paths": paths,
+                "traffic": measured_traffic("absgemm" if sp else "absgemm_bound") if args.scale == 1 else None,
                 "compulsory_bytes_per_launch": sum(p.min_bytes for p in lin) / len(lin),
                 "launches": lin_launches, "avg_launch_ms": lin_ms / lin_launches,
                 "flop_per_launch": lin_flops / lin_launches,
@@ -233,6 +258,7 @@ def main():
     for p in lin:
         ms = sum(_ms(p.bound_events)) / len(p.bound_events)
         kernels["linear_" + p.name] = {"shape": list(p.op.args["A"].shape) + [p.op.y_ref.shape[-1]],
+                                       "path": "bf16_split" if p.split else "fp32",
                                        "TFLOP/s": p.flops / (ms * 1e-3) / 1e12, "ms": ms}
 
     if not args.no_stress:
@@ -244,6 +270,13 @@ def main():
             ms = _event_time(torch, lambda: tao.tao_bound_linear(A, W, model=md, out=out), 5, 1)
             tf = 2.0 * 8192 ** 3 / (ms * 1e-3) / 1e12
             kernels[nm] = {"ms": ms, "TFLOP/s": tf, "frac_mfma": tf / PEAK_FP32_MFMA_TFLOPS}
+        ws5 = torch.empty(tao.tao_linear_split_workspace_bytes(8192, 8192, 8192, 1, True), dtype=torch.uint8, device=dev)
+        ms = _event_time(torch, lambda: tao.tao_bound_linear_split(A, W, out=out, ws=ws5), 5, 1)
+        tf = 2.0 * 8192 ** 3 / (ms * 1e-3) / 1e12
+        kernels["linear_8192^3_bf16_split"] = {"ms": ms, "TFLOP/s": tf, "frac_mfma": tf / PEAK_FP32_MFMA_TFLOPS,
+                                               "issued_frac_of_bf16_peak": 8.0 * tf / 2500.0}
+        del ws5
+        tao.tao_bound_linear(A, W, out=out)      # the stored bound of the check below: the FP32 path's
         ref = A @ W.t()
         claimed, cls = tao_inputs.config5_claimed(g, ref, out)
         buf = tao.new_profile_buffer(ref.device)
@@ -267,7 +300,8 @@ def main():
         "metric": "traced-operator GB/s verified (bound+check) & % FP32 MFMA/HBM peak, 1 GPU",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32 (MFMA) + f64 (accumulation, scalars, check)", "data": "synthetic",
+        "dtype": ("bf16 x 3 exact split / f32 (MFMA) + f64 (accumulation, scalars, check)" if sp
+                  else "f32 (MFMA) + f64 (accumulation, scalars, check)"), "data": "synthetic",
         "config": {"workload": "config 3: Qwen3-8B-shaped decoder layer ops, FP32, seq %d: %d traced operators, "
                                "%d output elements verified per step" % (ops[0].y_ref.shape[0], len(plan), elems),
                    "scale": args.scale},

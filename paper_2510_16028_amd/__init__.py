@@ -91,7 +91,8 @@ class TaoError(RuntimeError):
         super().__init__("%s: %s%s" % (where, msg, extra))
 
 
-EXPORTS = ["tao_default_model", "tao_gamma", "tao_bound_linear", "tao_bound_conv2d", "tao_bound_softmax",
+EXPORTS = ["tao_default_model", "tao_gamma", "tao_bound_linear", "tao_bound_linear_split",
+           "tao_linear_split_workspace_bytes", "tao_linear_split_preferred", "tao_selftest_matrix_core_bf16", "tao_bound_conv2d", "tao_bound_softmax",
            "tao_bound_norm", "tao_bound_groupnorm", "tao_groupnorm_workspace_bytes", "tao_bound_act", "tao_bound_rope", "tao_check_and_profile",
            "tao_check_workspace_bytes", "tao_bound_check_softmax", "tao_profile_errors", "tao_profile_workspace_bytes",
            "tao_calibrate_thresholds",
@@ -117,6 +118,12 @@ def lib():
     L.tao_gamma.restype = dbl
     L.tao_bound_linear.argtypes = [vp, vp, vp, vp, lg, lg, lg, lg, lg, lg, ctypes.c_int,
                                    lg, lg, lg, lg, mp, vp]
+    L.tao_bound_linear_split.argtypes = [vp, vp, vp, vp, lg, lg, lg, lg, lg, lg, ctypes.c_int,
+                                         lg, lg, lg, lg, mp, vp, ctypes.c_size_t, vp]
+    L.tao_linear_split_workspace_bytes.argtypes = [lg, lg, lg, lg, ctypes.c_int]
+    L.tao_linear_split_workspace_bytes.restype = ctypes.c_size_t
+    L.tao_linear_split_preferred.argtypes = [lg, lg, lg, lg]
+    L.tao_selftest_matrix_core_bf16.argtypes = [ctypes.POINTER(ctypes.c_uint), vp]
     L.tao_bound_conv2d.argtypes = [vp, vp, vp, vp] + [lg] * 13 + [mp, vp]
     L.tao_bound_softmax.argtypes = [vp, vp, vp, lg, lg, lg, mp, vp]
     L.tao_bound_norm.argtypes = [ctypes.c_int, vp, vp, vp, vp, dbl, vp, lg, lg, lg, mp, vp]
@@ -204,8 +211,7 @@ def tao_gamma(k, model=None):
     return lib().tao_gamma(int(k), _mref(model))
 
 
-def tao_bound_linear(A, W, bias=None, trans_w=False, model=None, out=None):
-    """tau[..., M, N] for A[..., M, K] and W[N, K] / [B, N, K] (trans_w: [K, N] / [B, K, N])."""
+def _linear_args(A, W, bias, trans_w, out):
     torch = _torch()
     A = _dev(A, "A"); W = _dev(W, "W"); bias = _dev(bias, "bias")
     if A.dim() not in (2, 3) or W.dim() not in (2, 3):
@@ -231,9 +237,43 @@ def tao_bound_linear(A, W, bias=None, trans_w=False, model=None, out=None):
     ldw = W.stride(-2) if W.shape[-2] > 1 else max(W.shape[-1], 1)
     sA = A.stride(0) if A.dim() == 3 and batch > 1 else M * lda
     sW = (W.stride(0) if W.shape[0] > 1 else 0) if W.dim() == 3 else 0
-    rc = lib().tao_bound_linear(_ptr(A), _ptr(W), _ptr(bias), _ptr(out), M, N, K, lda, ldw, N,
-                                int(bool(trans_w)), batch, sA, sW, M * N, _mref(model), _stream())
+    return A, W, bias, out, (M, N, K, lda, ldw, N, int(bool(trans_w)), batch, sA, sW, M * N)
+
+
+def tao_bound_linear(A, W, bias=None, trans_w=False, model=None, out=None):
+    """tau[..., M, N] for A[..., M, K] and W[N, K] / [B, N, K] (trans_w: [K, N] / [B, K, N])."""
+    A, W, bias, out, dims = _linear_args(A, W, bias, trans_w, out)
+    rc = lib().tao_bound_linear(_ptr(A), _ptr(W), _ptr(bias), _ptr(out), *dims, _mref(model), _stream())
     _check(rc, "tao_bound_linear")
+    return out
+
+
+def tao_linear_split_workspace_bytes(M, N, K, batch=1, shared_w=True):
+    return int(lib().tao_linear_split_workspace_bytes(int(M), int(N), int(K), int(batch), int(bool(shared_w))))
+
+
+def tao_linear_split_preferred(M, N, K, batch=1):
+    _torch()
+    return bool(lib().tao_linear_split_preferred(int(M), int(N), int(K), int(batch)))
+
+
+def tao_selftest_matrix_core_bf16():
+    _torch()
+    rep = ctypes.c_uint(0)
+    _check(lib().tao_selftest_matrix_core_bf16(ctypes.byref(rep), _stream()), "tao_selftest_matrix_core_bf16")
+    return int(rep.value)
+
+
+def tao_bound_linear_split(A, W, bias=None, trans_w=False, model=None, out=None, ws=None):
+    """tao_bound_linear on the BF16 matrix cores (three exact BF16 pieces per operand); same
+    arguments, plus an optional scratch tensor."""
+    A, W, bias, out, dims = _linear_args(A, W, bias, trans_w, out)
+    M, N, K, batch, sW = dims[0], dims[1], dims[2], dims[7], dims[9]
+    if ws is None:
+        ws = _scratch(A.device, tao_linear_split_workspace_bytes(M, N, K, batch, sW == 0 or batch == 1))
+    rc = lib().tao_bound_linear_split(_ptr(A), _ptr(W), _ptr(bias), _ptr(out), *dims, _mref(model),
+                                      _ptr(ws), ws.numel(), _stream())
+    _check(rc, "tao_bound_linear_split")
     return out
 
 

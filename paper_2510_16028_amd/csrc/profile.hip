@@ -16,7 +16,7 @@
 namespace tao {
 
 constexpr int kErrThreads = 1024;            // one workgroup per CU
-constexpr int kErrReplicas = 2;              // two histograms of 2 x 2048 counters: 32 KB of LDS
+constexpr int kErrReplicas = 4;              // two histograms of 4 x 2048 counters: 64 KB of LDS
 constexpr int kGrid = TAO_NGRID;
 
 struct ErrStats {            // one per pass-1 workgroup

@@ -15,7 +15,7 @@ __device__ __forceinline__ float up32(double v) {
     return f;
 }
 
-// Cheaper upper rounding for the streaming kernels (two operations instead of five), which also
+// Cheaper upper rounding for the streaming kernels (four operations instead of five, no branch), which also
 // takes the place of the guard factor: for v >= 0 the result is a binary32 value >= v(1 + 2^-33)
 // and at most v(1 + 2^-23 + 2^-31) (three halves of that near the bottom of the normal range).
 // v(1 + 2^-24 + 2^-32) lies above the midpoint of the two binary32 neighbours of v, so round-to-

@@ -117,6 +117,18 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_bound_linear(nul, p, nul, p, *args(4, 4, 8, 8, 8, 4), None, None) == tao.ERR_NULL
     assert L.tao_bound_linear(p, odd, nul, p, *args(4, 4, 8, 8, 8, 4), None, None) == tao.ERR_ALIGN
     assert L.tao_bound_linear(nul, nul, nul, nul, *args(0, 4, 8, 8, 8, 4), None, None) == tao.OK
+    # the same through the BF16 path: needs a workspace
+    wsb = L.tao_linear_split_workspace_bytes(4, 4, 8, 1, 1)
+    assert wsb == 2 * 24576 + 512 and L.tao_linear_split_workspace_bytes(0, 4, 8, 1, 1) == 0
+    assert L.tao_linear_split_workspace_bytes(300, 129, 33, 2, 0) == 2 * (3 + 2) * 2 * 24576 + 512
+    big = ctypes.c_void_p(0x100000)
+    assert L.tao_bound_linear_split(p, p, nul, p, *args(4, 4, 8, 4, 8, 4), None, big, wsb, None) == tao.ERR_SHAPE
+    assert L.tao_bound_linear_split(p, p, nul, p, *args(4, 4, 8, 8, 8, 4), None, nul, wsb, None) == tao.ERR_WORKSPACE
+    assert L.tao_bound_linear_split(p, p, nul, p, *args(4, 4, 8, 8, 8, 4), None, big, wsb - 1, None) == tao.ERR_WORKSPACE
+    assert L.tao_bound_linear_split(p, p, nul, p, *args(4, 4, 8, 8, 8, 4), None, ctypes.c_void_p(0x100010), wsb, None) == tao.ERR_WORKSPACE
+    assert L.tao_bound_linear_split(nul, p, nul, p, *args(4, 4, 8, 8, 8, 4), None, big, wsb, None) == tao.ERR_NULL
+    assert L.tao_bound_linear_split(p, p, nul, p, *args(4, 4, K, K, K, 4), None, big, wsb, None) == tao.ERR_K_RANGE
+    assert L.tao_bound_linear_split(nul, nul, nul, nul, *args(0, 4, 8, 8, 8, 4), None, nul, 0, None) == tao.OK
     # conv2d: (batch, H, W, C, Cout, R, S, stride h/w, pad h/w, dilation h/w)
     cargs = lambda B=1, H=8, W=8, C=4, Co=4, R=3, S=3, sh=1, sw=1, ph=1, pw=1, dh=1, dw=1: \
         (B, H, W, C, Co, R, S, sh, sw, ph, pw, dh, dw)

@@ -95,6 +95,35 @@ def test_config3_qwen_layer_full_size(tao, oracle_mod):
     _check_ops_sampled(tao, oracle_mod, ops, nsample=5, seed=300)
 
 
+def test_config3_matmuls_through_the_bf16_split_path(tao, oracle_mod):
+    """The shapes bench.py sends through tao_bound_linear_split (the library's own rule), at full
+    size: the honest split-K claim is accepted on every element, sampled rows against the oracle,
+    and the bound stays within 1e-6 of the FP32 path's (both are within 1e-6 above the oracle)."""
+    ops = [op for op in tao_inputs.config3("cuda", scale=1) if op.kind == "linear"]
+    taken = 0
+    for idx, op in enumerate(ops):
+        A, W = op.args["A"], op.args["W"]
+        batch = A.shape[0] if A.dim() == 3 else 1
+        M, N, K = op.y_ref.shape[-2], op.y_ref.shape[-1], A.shape[-1]
+        if not tao.tao_linear_split_preferred(M, N, K, batch):
+            continue
+        taken += 1
+        print("op", op.name, (batch, M, N, K), flush=True)
+        tau = tao.tao_bound_linear_split(A, W, op.args.get("bias"), trans_w=bool(op.attrs.get("trans_w", 0)))
+        p = tao.tao_check_and_profile(op.claimed.contiguous(), op.y_ref.contiguous(), tau)
+        assert p["violations"] == 0 and p["n"] == op.y_ref.numel(), op.name
+        rows = _sample_rows(M, 5, 700 + idx)
+        b = (idx % batch) if A.dim() == 3 else None
+        sub = _sub_op(op, rows, b)
+        t_or = oracle_tau(oracle_mod, sub)
+        worst = assert_bound_parity(_np(_tau_rows(tau, op, rows, b)), t_or, op.name + " (bf16 split)")
+        print("   sampled %d rows: max tau_gpu/tau_oracle - 1 = %.3e" % (len(rows), worst), flush=True)
+        ref = gpu_tau(tao, op)
+        assert float((tau / ref - 1).abs().max()) <= 1e-6
+        del tau, ref
+    assert taken >= 5
+
+
 def test_config2_bert_block_full_size(tao, oracle_mod):
     ops = tao_inputs.config2("cuda", scale=1)
     _check_ops_sampled(tao, oracle_mod, ops, nsample=13, seed=200)
@@ -150,6 +179,12 @@ def test_config5_stress_full_size(tao, oracle_mod):
     assert po["violations"] == int((cls_o == 2).sum())
     pg = tao.tao_check_and_profile(claimed_o.cuda(), ref_rows.cuda(), torch.from_numpy(t_or).cuda())
     assert_profile_equal(pg, po, "c5 check rows")
+    # the BF16-split path on the same rows
+    split = tao.tao_bound_linear_split(A, W)
+    worst = assert_bound_parity(_np(split.index_select(0, rows.cuda())), t_or, "c5 bf16 split rows")
+    print("c5 bf16 split: max tau_gpu/tau_oracle - 1 = %.3e" % worst, flush=True)
+    assert tao.tao_check_and_profile(claimed, ref, split)["violations"] == p["violations"]
+    del split
     # the fast-accumulation variant stays an upper bound on the same rows
     fast = tao.tao_bound_linear(A, W, model=tao.FpModel(flags=tao.FLAG_FAST_ACCUM))
     assert_bound_parity(_np(fast.index_select(0, rows.cuda())), t_or, "c5 fast", rel_tol=2.5 * 8192 * 2.0 ** -24)

@@ -51,6 +51,15 @@ def test_matrix_core_selftest(tao):
     assert rep & 4, "6-step chain exceeds gamma_6"
 
 
+def test_bf16_matrix_core_selftest(tao):
+    rep = tao.tao_selftest_matrix_core_bf16()
+    print("bf16 matrix-core self test report:", rep, flush=True)
+    assert rep & 1, "v_mfma_f32_32x32x16_bf16 does not follow the model the split bound's inflation rests on"
+    assert rep & 2, "a zero-accumulator instruction left [S(1-10u), S(1+2u)]"
+    assert tao.tao_linear_split_preferred(2048, 4096, 4096) and not tao.tao_linear_split_preferred(2048, 128, 2048, 8)
+    assert not tao.tao_linear_split_preferred(512, 768, 768)
+
+
 def test_config1_linear_and_softmax(tao, oracle_mod):
     ops = tao_inputs.config1("cpu")
     _run_ops(tao, oracle_mod, ops)
@@ -175,6 +184,51 @@ def test_conv2d_accepts_a_real_convolution(tao, oracle_mod):
     assert bool((err <= tau.cpu().double()).all())
     t_or = oracle_mod.bound_conv2d(_np(xl), _np(wl), None, (1, 1), (1, 1), (1, 1))
     assert_bound_parity(_np(tau), t_or, "conv nchw view")
+
+
+@pytest.mark.parametrize("M,N,K,bias,trans_w,batch", [
+    (1, 1, 1, False, False, 1), (1, 5, 7, True, False, 1), (129, 257, 49, True, False, 1),
+    (130, 64, 601, False, True, 1), (33, 200, 48, True, True, 3), (256, 128, 96, False, False, 2),
+    (5, 3, 0, True, False, 1), (70, 130, 13, False, False, 1), (512, 384, 2048, True, False, 1),
+    (2048, 256, 64, False, True, 2), (384, 384, 1088, True, False, 3)])
+def test_linear_split_shapes(tao, oracle_mod, M, N, K, bias, trans_w, batch):
+    """The BF16-split path against the oracle, every element (same tolerance as the FP32 path)."""
+    g = torch.Generator().manual_seed(M * 1000 + N * 10 + K + 5)
+    A = torch.randn((batch, M, K), generator=g)
+    W = torch.randn((batch, K, N) if trans_w else (batch, N, K), generator=g)
+    b = torch.randn((N,), generator=g) if bias else None
+    if batch == 1:
+        A, W = A[0], W[0]
+    t_or = oracle_mod.bound_linear(_np(A), _np(W), None if b is None else _np(b), trans_w=trans_w)
+    t_gpu = tao.tao_bound_linear_split(A.cuda(), W.cuda(), None if b is None else b.cuda(), trans_w=trans_w)
+    worst = assert_bound_parity(_np(t_gpu), t_or, "split linear %s" % ((M, N, K, bias, trans_w, batch),))
+    print("max tau_gpu/tau_oracle - 1 = %.3e" % worst, flush=True)
+
+
+def test_linear_split_value_ranges_and_shared_w(tao, oracle_mod):
+    """Wide dynamic range inside the reduction (the truncation steps of the instruction bite
+    there), heavy tails, exact powers of two, a W shared across the batch, infinities."""
+    g = torch.Generator().manual_seed(808)
+    M, N, K = 96, 160, 320
+    expo = torch.randint(-20, 21, (M, K), generator=g).float()
+    A = torch.randn((M, K), generator=g) * 2.0 ** expo
+    W = torch.randn((N, K), generator=g) * 2.0 ** torch.randint(-12, 13, (N, K), generator=g).float()
+    for a, w, what in ((A, W, "wide exponents"), (2.0 ** expo, torch.ones(N, K), "powers of two"),
+                       (A * 1e-25, W * 1e-8, "small magnitudes"), (A * 1e15, W * 1e10, "large magnitudes")):
+        t_or = oracle_mod.bound_linear(_np(a), _np(w))
+        assert_bound_parity(_np(tao.tao_bound_linear_split(a.cuda(), w.cuda())), t_or, what)
+    A3 = torch.randn((3, M, K), generator=g)
+    t_or = oracle_mod.bound_linear(_np(A3), _np(W[None]))
+    t_gpu = tao.tao_bound_linear_split(A3.cuda(), W.cuda()[None].expand(3, N, K))
+    assert_bound_parity(_np(t_gpu), t_or, "shared W")
+    # an infinite operand: the oracle's row is +inf; a piece of the other operand that is exactly
+    # zero turns inf into NaN on the matrix cores, so the row is +inf or NaN (never finite)
+    Ai = A.clone(); Ai[2, 5] = float("inf")
+    t_or = oracle_mod.bound_linear(_np(Ai), _np(W))
+    t_gpu = _np(tao.tao_bound_linear_split(Ai.cuda(), W.cuda()))
+    assert np.all(np.isinf(t_or[2])) and not np.any(np.isfinite(t_gpu[2]))
+    keep = np.arange(M) != 2
+    assert_bound_parity(t_gpu[keep], t_or[keep], "rows beside an infinite operand")
 
 
 def test_linear_random_shapes_and_strides(tao, oracle_mod):
