@@ -109,6 +109,9 @@ def lib():
     if not os.path.exists(LIB_PATH):
         raise RuntimeError("libtao.so not built: run `python -m paper_2510_16028_amd.build` "
                            "(there is no CPU fallback)")
+    # torch brings its own copy of the HIP runtime; load it first so that libtao.so binds to the
+    # same one (two runtimes in one process do not share a device context)
+    import torch  # noqa: F401
     L = ctypes.CDLL(LIB_PATH)
     vp, lg, dbl = ctypes.c_void_p, ctypes.c_long, ctypes.c_double
     mp = ctypes.POINTER(FpModel)

@@ -252,9 +252,10 @@ def test_linear_random_shapes_and_strides(tao, oracle_mod):
         what = "case %d: M=%d N=%d K=%d batch=%d trans_w=%s bias=%s pads=(%d,%d)" % (case, M, N, K, batch, trans_w, bias, pad_a, pad_w)
         print(what, flush=True)
         t_or = oracle_mod.bound_linear(_np(A.contiguous()), _np(W.contiguous()), None if b is None else _np(b), trans_w=trans_w)
-        t_gpu = tao.tao_bound_linear(Afull.cuda()[:, :, :K], Wfull.cuda()[:, :, :N] if trans_w else Wfull.cuda()[:, :, :K],
-                                     None if b is None else b.cuda(), trans_w=trans_w)
-        assert_bound_parity(_np(t_gpu), t_or, what)
+        Ag = Afull.cuda()[:, :, :K]; Wg = Wfull.cuda()[:, :, :N] if trans_w else Wfull.cuda()[:, :, :K]
+        bg = None if b is None else b.cuda()
+        assert_bound_parity(_np(tao.tao_bound_linear(Ag, Wg, bg, trans_w=trans_w)), t_or, what)
+        assert_bound_parity(_np(tao.tao_bound_linear_split(Ag, Wg, bg, trans_w=trans_w)), t_or, what + " (bf16 split)")
 
 
 def test_conv2d_random_geometries(tao, oracle_mod):
