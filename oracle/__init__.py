@@ -11,6 +11,7 @@ import os
 import numpy as np
 
 from . import build as _build
+from .project import cap_curve, project_clip, project_empirical  # noqa: F401  (Sec. 4.4)
 
 NBINS = 2048
 
