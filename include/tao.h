@@ -328,6 +328,34 @@ size_t tao_profile_workspace_bytes(long n);
 int tao_calibrate_thresholds(const tao_error_profile *profiles, long count, double alpha,
                              float *env_abs, float *env_rel, float *thr_abs, float *thr_rel, void *stream);
 
+/* Projection of a tentative perturbation onto the admissible set of the theoretical bound
+ * (Sec. 4.4 (i)): out = clip(delta, -alpha tau, alpha tau) element by element.  The cap alpha*tau is
+ * one binary64 product; an element beyond it takes the largest binary32 value not above the cap
+ * (the result never leaves the set through rounding), its sign kept; NaN elements stay NaN.
+ * delta, tau, out: DEVICE, n values each; out may be delta.  alpha finite and >= 0
+ * (TAO_ERR_SHAPE otherwise, as for n < 0). */
+int tao_project_clip(const float *delta, const float *tau, double alpha, float *out, long n, void *stream);
+
+/* Projection onto the admissible set of the empirical thresholds (Sec. 4.4 (ii), cap curve of
+ * Sec. 4.2): with a = |delta| sorted increasingly (equal values in index order) and ranks
+ * k = 1..n,
+ *     r_k = ((k - 0.5) / n) * 100,
+ *     C(r) = c_{j-1} + (c_j - c_{j-1}) * ((r - p_{j-1}) / (p_j - p_{j-1})),   j the first grid
+ *            point with r <= p_j,  c_j = alpha * thr_abs[j],  (p_0, c_0) = (0, 0)     (binary64),
+ *     cap_k = max over k' <= k of C(r_k'),
+ *     out[sigma(k)] = sign(delta[sigma(k)]) * min(a_sigma(k), cap_k),
+ * a capped element taking the largest binary32 value not above its cap.  NaN elements rank last
+ * and stay NaN.  The result is bit-identical to a stable sort followed by those steps.
+ * delta, out: DEVICE, n values (out may be delta itself, no other overlap); thr_abs: DEVICE, the operator's 22 absolute
+ * thresholds on the grid of Sec. 3.2 (as tao_calibrate_thresholds writes them), which must be
+ * finite and >= 0 (not checked: device data; other values cannot fault, the result is then
+ * unspecified).  ws / ws_bytes: DEVICE scratch of at least tao_project_workspace_bytes(n)
+ * (about 16 n bytes), 256-byte aligned, contents on entry irrelevant.
+ * TAO_ERR_SHAPE for n < 0, n >= 2^31 or alpha not finite and >= 0; TAO_ERR_WORKSPACE. */
+int tao_project_empirical(const float *delta, const float *thr_abs, double alpha, float *out, long n,
+                          void *ws, size_t ws_bytes, void *stream);
+size_t tao_project_workspace_bytes(long n);   /* 0 for n <= 0 or n >= 2^31 */
+
 /* Runs crafted inputs through the FP32 matrix-core instruction and reports, as
  * a bit mask in *report (HOST pointer), which modelling assumptions of the
  * linear bound's inflation hold on this device: bit 0 accumulation rounds to

@@ -21,7 +21,8 @@ GRID_PERCENT = np.array([1] + [5 * g for g in range(1, 20)] + [99, 100], dtype=n
 
 def _f32_not_above(c):
     """Largest binary32 value <= c, for binary64 c >= 0."""
-    f = c.astype(np.float32)
+    with np.errstate(over="ignore"):
+        f = c.astype(np.float32)                             # beyond the binary32 range: inf, stepped down below
     over = f.astype(np.float64) > c
     return np.where(over, np.nextafter(f, np.float32(-np.inf), dtype=np.float32), f).astype(np.float32)
 

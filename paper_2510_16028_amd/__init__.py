@@ -95,7 +95,7 @@ EXPORTS = ["tao_default_model", "tao_gamma", "tao_bound_linear", "tao_bound_line
            "tao_linear_split_workspace_bytes", "tao_linear_split_preferred", "tao_selftest_matrix_core_bf16", "tao_bound_conv2d", "tao_bound_softmax",
            "tao_bound_norm", "tao_bound_groupnorm", "tao_groupnorm_workspace_bytes", "tao_bound_act", "tao_bound_rope", "tao_check_and_profile",
            "tao_check_workspace_bytes", "tao_bound_check_softmax", "tao_profile_errors", "tao_profile_workspace_bytes",
-           "tao_calibrate_thresholds",
+           "tao_calibrate_thresholds", "tao_project_clip", "tao_project_empirical", "tao_project_workspace_bytes",
            "tao_selftest_matrix_core", "tao_last_hip_error", "tao_status_string"]
 
 _lib = None
@@ -141,6 +141,10 @@ def lib():
     L.tao_check_workspace_bytes.restype = ctypes.c_size_t
     L.tao_profile_errors.argtypes = [vp, vp, lg, dbl, vp, vp, vp, vp, ctypes.c_size_t, vp]
     L.tao_calibrate_thresholds.argtypes = [vp, lg, dbl, vp, vp, vp, vp, vp]
+    L.tao_project_clip.argtypes = [vp, vp, dbl, vp, lg, vp]
+    L.tao_project_empirical.argtypes = [vp, vp, dbl, vp, lg, vp, ctypes.c_size_t, vp]
+    L.tao_project_workspace_bytes.argtypes = [lg]
+    L.tao_project_workspace_bytes.restype = ctypes.c_size_t
     L.tao_profile_workspace_bytes.argtypes = [lg]
     L.tao_profile_workspace_bytes.restype = ctypes.c_size_t
     L.tao_selftest_matrix_core.argtypes = [ctypes.POINTER(ctypes.c_uint), vp]
@@ -551,6 +555,45 @@ def tao_calibrate_thresholds(profiles, alpha=3.0):
     rc = lib().tao_calibrate_thresholds(_ptr(profiles), count, float(alpha), *[_ptr(o) for o in outs], _stream())
     _check(rc, "tao_calibrate_thresholds")
     return tuple(outs)
+
+
+def tao_project_clip(delta, tau, alpha=1.0, out=None):
+    """clip(delta, -alpha tau, alpha tau) (Sec. 4.4 (i)); float32 CUDA tensors of one shape."""
+    torch = _torch()
+    delta = _dev(delta, "delta"); tau = _dev(tau, "tau")
+    if delta.shape != tau.shape or not (delta.is_contiguous() and tau.is_contiguous()):
+        raise ValueError("delta and tau must be contiguous tensors of one shape")
+    if out is None:
+        out = torch.empty_like(delta)
+    elif _dev(out, "out").shape != delta.shape or not out.is_contiguous():
+        raise ValueError("out must be contiguous and shaped like delta")
+    _check(lib().tao_project_clip(_ptr(delta), _ptr(tau), float(alpha), _ptr(out), delta.numel(), _stream()),
+           "tao_project_clip")
+    return out
+
+
+def tao_project_workspace_bytes(n):
+    return lib().tao_project_workspace_bytes(int(n))
+
+
+def tao_project_empirical(delta, thr_abs, alpha=1.0, out=None, ws=None):
+    """Order-statistic projection onto the empirical admissible set (Sec. 4.4 (ii)).
+    delta: contiguous float32 CUDA tensor; thr_abs: 22 float32 thresholds on the same device."""
+    torch = _torch()
+    delta = _dev(delta, "delta"); thr_abs = _dev(thr_abs, "thr_abs")
+    if not delta.is_contiguous() or thr_abs.numel() != NGRID or not thr_abs.is_contiguous():
+        raise ValueError("delta must be contiguous and thr_abs hold %d contiguous values" % NGRID)
+    if out is None:
+        out = torch.empty_like(delta)
+    elif _dev(out, "out").shape != delta.shape or not out.is_contiguous():
+        raise ValueError("out must be contiguous and shaped like delta")
+    n = delta.numel()
+    need = lib().tao_project_workspace_bytes(n)
+    if ws is None:
+        ws = _scratch(delta.device, need)
+    _check(lib().tao_project_empirical(_ptr(delta), _ptr(thr_abs), float(alpha), _ptr(out), n,
+                                       _ptr(ws), ws.numel(), _stream()), "tao_project_empirical")
+    return out
 
 
 def tao_profile_workspace_bytes(n):

@@ -17,7 +17,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtao.so")
 OBJDIR = os.path.join(HERE, "_build")
 
-SOURCES = ["tao_api.hip", "check.hip", "profile.hip", "rowops.hip", "act.hip", "linear.hip", "linear_split.hip"]
+SOURCES = ["tao_api.hip", "check.hip", "profile.hip", "rowops.hip", "act.hip", "linear.hip", "linear_split.hip", "project.hip"]
 
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-fno-gpu-flush-denormals-to-zero", "-fno-fast-math",

@@ -180,6 +180,26 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_calibrate_thresholds(nul, 2, 3.0, nul, nul, p, p, None) == tao.ERR_NULL
     assert L.tao_calibrate_thresholds(p, 2, 3.0, nul, nul, nul, p, None) == tao.ERR_NULL
     assert L.tao_calibrate_thresholds(odd, 2, 3.0, nul, nul, p, p, None) == tao.ERR_ALIGN
+    # projections
+    assert L.tao_project_clip(p, p, 1.0, p, -1, None) == tao.ERR_SHAPE
+    assert L.tao_project_clip(p, p, -1.0, p, 10, None) == tao.ERR_SHAPE
+    assert L.tao_project_clip(p, p, float("nan"), p, 10, None) == tao.ERR_SHAPE
+    assert L.tao_project_clip(p, nul, 1.0, p, 10, None) == tao.ERR_NULL
+    assert L.tao_project_clip(odd, p, 1.0, p, 10, None) == tao.ERR_ALIGN
+    assert L.tao_project_clip(nul, nul, 1.0, nul, 0, None) == tao.OK
+    need = L.tao_project_workspace_bytes(100000)
+    assert 16 * 100000 <= need <= 16 * 100000 + (1 << 16)
+    assert L.tao_project_workspace_bytes(0) == 0 and L.tao_project_workspace_bytes(1 << 31) == 0
+    assert L.tao_project_workspace_bytes((1 << 31) - 1) > 16 * ((1 << 31) - 1)
+    assert L.tao_project_empirical(p, p, 1.0, p, -1, ws, need, None) == tao.ERR_SHAPE
+    assert L.tao_project_empirical(p, p, 1.0, p, 1 << 31, ws, 1 << 40, None) == tao.ERR_SHAPE
+    assert L.tao_project_empirical(p, p, float("inf"), p, 100000, ws, need, None) == tao.ERR_SHAPE
+    assert L.tao_project_empirical(p, nul, 1.0, p, 100000, ws, need, None) == tao.ERR_NULL
+    assert L.tao_project_empirical(odd, p, 1.0, p, 100000, ws, need, None) == tao.ERR_ALIGN
+    assert L.tao_project_empirical(p, p, 1.0, p, 100000, nul, need, None) == tao.ERR_WORKSPACE
+    assert L.tao_project_empirical(p, p, 1.0, p, 100000, ws, need - 1, None) == tao.ERR_WORKSPACE
+    assert L.tao_project_empirical(p, p, 1.0, p, 100000, ctypes.c_void_p(0x10010), need, None) == tao.ERR_WORKSPACE
+    assert L.tao_project_empirical(nul, nul, 1.0, nul, 0, nul, 0, None) == tao.OK
     for code in range(0, -9, -1):
         assert L.tao_status_string(code)
     assert L.tao_selftest_matrix_core(None, None) == tao.ERR_NULL

@@ -1,0 +1,152 @@
+"""GPU parity of the two projections of Sec. 4.4 against the CPU oracle: bit for bit (the caps
+are binary64 formulas evaluated identically on both sides and equal magnitudes keep their index
+order on both sides, so every output element is unique)."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+f32 = np.float32
+TILE = 4096
+
+
+@pytest.fixture(scope="module")
+def tao():
+    import paper_2510_16028_amd as t
+    t.lib()
+    assert torch.cuda.is_available()
+    return t
+
+
+def _rng(seed):
+    return np.random.Generator(np.random.Philox(seed))
+
+
+def _bits(a):
+    return np.ascontiguousarray(a, dtype=f32).view(np.uint32)
+
+
+def _thr(rng, scale, monotone=True):
+    t = np.abs(rng.standard_normal(22)) * scale
+    return (np.sort(t) if monotone else t).astype(f32)
+
+
+def _same(got, want, what):
+    g, w = _bits(got.cpu().numpy()), _bits(want)
+    nan = np.isnan(want)
+    bad = np.nonzero((g != w) & ~nan)[0]
+    assert bad.size == 0, "%s: %d elements differ, first at %d: gpu %r oracle %r" % (
+        what, bad.size, bad[0], got.flatten()[int(bad[0])].item(), want.flatten()[bad[0]])
+    assert np.array_equal(np.isnan(got.cpu().numpy()), nan), what
+
+
+def _delta(rng, n, kind):
+    if kind == "errors":          # what an honest re-execution differs by: ~1e-6 of outputs of mixed size
+        y = rng.standard_normal(n) * 10.0 ** rng.uniform(-2, 2, n)
+        return (y * rng.standard_normal(n) * 6e-8).astype(f32)
+    if kind == "wide":            # every byte of the key varies
+        return (rng.standard_normal(n) * 10.0 ** rng.uniform(-30, 10, n)).astype(f32)
+    if kind == "ties":            # few distinct magnitudes, many exact zeros
+        v = rng.integers(-6, 7, n).astype(f32) * f32(2.5e-7)
+        v[rng.random(n) < 0.3] = 0.0
+        v[rng.random(n) < 0.1] = -0.0
+        return v
+    if kind == "equal":
+        v = np.full(n, 3e-6, f32); v[::3] *= -1
+        return v
+    if kind == "special":
+        v = (rng.standard_normal(n) * 1e-6).astype(f32)
+        idx = rng.integers(0, n, max(1, n // 50))
+        v[idx] = rng.choice(np.array([np.nan, np.inf, -np.inf, 0.0, -0.0, 1e-45, -1e-45, 3e38], f32), idx.size)
+        return v
+    raise ValueError(kind)
+
+
+def test_clip_matches_the_oracle(tao, oracle_mod):
+    rng = _rng(1)
+    for n, alpha, off in ((1, 1.0, 0), (5, 1.0, 0), (1023, 0.5, 0), (100003, 1.0, 0), (100003, 0.37, 1), (262144, 3.0, 0)):
+        print("clip n", n, "alpha", alpha, "offset", off, flush=True)
+        d = _delta(rng, n + off, "special")
+        t = np.abs(rng.standard_normal(n + off) * 1e-6).astype(f32)
+        t[rng.integers(0, n + off, 3)] = 0.0
+        dg, tg = torch.from_numpy(d).cuda()[off:], torch.from_numpy(t).cuda()[off:]
+        out = tao.tao_project_clip(dg, tg, alpha)
+        torch.cuda.synchronize()
+        _same(out, oracle_mod.project_clip(d[off:], t[off:], alpha), "clip n=%d" % n)
+    # in place
+    dg2 = dg.clone()
+    tao.tao_project_clip(dg2, tg, alpha, out=dg2)
+    _same(dg2, oracle_mod.project_clip(d[off:], t[off:], alpha), "clip in place")
+    assert tao.tao_project_clip(torch.empty(0, device="cuda"), torch.empty(0, device="cuda")).numel() == 0
+
+
+SIZES = [1, 2, 63, 64, 65, 1000, TILE - 1, TILE, TILE + 1, 8 * TILE + 37, 16 * TILE, 300001]
+
+
+@pytest.mark.parametrize("kind", ["errors", "wide", "ties", "equal", "special"])
+def test_empirical_projection_matches_the_oracle(tao, oracle_mod, kind):
+    rng = _rng(hash(kind) % 1000 + 7)
+    for n in SIZES:
+        d = _delta(rng, n, kind)
+        thr = _thr(rng, 2e-6 if kind != "wide" else 1e-3)
+        alpha = float(rng.choice([1.0, 2.0, 3.0]))
+        print("empirical", kind, "n", n, "alpha", alpha, flush=True)
+        out = tao.tao_project_empirical(torch.from_numpy(d).cuda(), torch.from_numpy(thr).cuda(), alpha)
+        torch.cuda.synchronize()
+        want = oracle_mod.project_empirical(d, thr, alpha)
+        _same(out, want, "%s n=%d" % (kind, n))
+        clipped = int(np.sum(_bits(want) != _bits(d)))
+        print("   clipped", clipped, "of", n, flush=True)
+
+
+def test_empirical_projection_threshold_tables(tao, oracle_mod):
+    rng = _rng(21)
+    n = 5 * TILE + 11
+    d = _delta(rng, n, "errors")
+    dg = torch.from_numpy(d).cuda()
+    tables = {"not monotone": _thr(rng, 2e-7, monotone=False), "zeros": np.zeros(22, f32),
+              "huge": np.full(22, 3e38, f32), "steps": np.repeat(np.array([1e-8, 1e-7], f32), 11),
+              "tiny": np.full(22, 1e-45, f32)}
+    for name, thr in tables.items():
+        for alpha in (1.0, 3.0, 0.0):
+            print("table", name, "alpha", alpha, flush=True)
+            out = tao.tao_project_empirical(dg, torch.from_numpy(thr).cuda(), alpha)
+            torch.cuda.synchronize()
+            _same(out, oracle_mod.project_empirical(d, thr, alpha), "%s alpha=%g" % (name, alpha))
+    # in place, a caller's workspace, a multi-dimensional tensor, the empty tensor
+    thr = tables["not monotone"]
+    m = dg[: 4 * 32 * 160].reshape(4, 32, 160).clone()
+    ws = torch.empty(tao.tao_project_workspace_bytes(m.numel()), dtype=torch.uint8, device="cuda")
+    tao.tao_project_empirical(m, torch.from_numpy(thr).cuda(), 2.0, out=m, ws=ws)
+    torch.cuda.synchronize()
+    _same(m, oracle_mod.project_empirical(d[: m.numel()].reshape(4, 32, 160), thr, 2.0), "in place")
+    assert tao.tao_project_empirical(torch.empty(0, device="cuda"), torch.from_numpy(thr).cuda()).numel() == 0
+    with pytest.raises(tao.TaoError):
+        tao.tao_project_empirical(dg, torch.from_numpy(thr).cuda(), 1.0, ws=ws[:4096])
+
+
+def test_projection_with_calibrated_thresholds_end_to_end(tao, oracle_mod):
+    """Thresholds as tao_calibrate_thresholds leaves them on the device; a perturbation ten times the
+    honest error is projected back until the selection statistic of Sec. 5.3 no longer flags it."""
+    rng = _rng(22)
+    n = 70001
+    ref = torch.from_numpy((rng.standard_normal(n) * 3).astype(f32))
+    runs = [ref * (1 + 1e-6 * torch.from_numpy(rng.standard_normal(n).astype(f32))) for _ in range(3)]
+    import ctypes
+    bufs = torch.empty((3, ctypes.sizeof(tao.ErrorProfile)), dtype=torch.uint8, device="cuda")
+    for i, c in enumerate(runs):
+        tao.tao_profile_errors(c.cuda(), ref.cuda(), out=bufs[i], readback=False)
+    ea, er, ta, tr = tao.tao_calibrate_thresholds(bufs, alpha=1.0)
+    delta = (ref * 1e-5 * torch.from_numpy(rng.standard_normal(n).astype(f32)))
+    for alpha in (1.0, 3.0):
+        out = tao.tao_project_empirical(delta.cuda(), ta, alpha)
+        torch.cuda.synchronize()
+        _same(out, oracle_mod.project_empirical(delta.numpy(), ta.cpu().numpy(), alpha), "calibrated alpha=%g" % alpha)
+        # order statistics whose rank lies at or below a grid point sit under alpha x its threshold
+        srt = np.sort(np.abs(out.cpu().numpy()))
+        caps = np.maximum.accumulate(ta.cpu().numpy().astype(np.float64)) * alpha
+        for g, p in enumerate(oracle_mod.GRID_PERCENT):
+            k = int(np.floor(n * p / 100.0 + 0.5))              # largest k with (k - 1/2)/n <= p/100
+            assert k >= 1 and float(srt[k - 1]) <= caps[g], (g, p)
+        assert np.any(out.cpu().numpy() != delta.numpy())
