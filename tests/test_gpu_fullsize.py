@@ -248,3 +248,47 @@ def test_more_than_2_31_elements(tao, oracle_mod):
     t_or = oracle_mod.bound_linear(_np(A.index_select(0, rows)), _np(W))
     assert_bound_parity(_np(tau.index_select(0, rows)), t_or, "2.29e9-output matmul rows")
     assert bool((tau > 0).all())
+
+
+def test_projections_full_size(tao, oracle_mod):
+    """Sec. 4.4 at the sizes of configuration 3's largest tensors: 2048 x 12288 (an MLP activation)
+    bit for bit against the oracle; 32 x 2048 x 2048 (the attention scores) through what holds at
+    any size -- admissible at sampled ranks, untouched elements identical, idempotent -- and
+    against the oracle on the elements of sampled ranks."""
+    n = 2048 * 12288
+    c, r, t = tao_inputs.check_triplet("cpu", seed=71, n=n)
+    delta = (c - r).contiguous()
+    thr = oracle_mod.profile_errors(_np(r + delta / 4), _np(r))["abs_p"].astype(np.float32)
+    thr_g = torch.from_numpy(thr).cuda()
+    out = tao.tao_project_empirical(delta.cuda(), thr_g, 1.0)
+    want = oracle_mod.project_empirical(_np(delta), thr, 1.0)
+    assert np.array_equal(_np(out).view(np.uint32), want.view(np.uint32))
+    changed = int((want != _np(delta)).sum())
+    print("25M: %d elements capped" % changed, flush=True)
+    assert 0 < changed < n
+    clip = tao.tao_project_clip(delta.cuda(), t.cuda(), 0.5)
+    assert np.array_equal(_np(clip).view(np.uint32), oracle_mod.project_clip(_np(delta), _np(t), 0.5).view(np.uint32))
+    del c, r, t, out, clip
+
+    n = 32 * 2048 * 2048
+    g = torch.Generator(device="cuda").manual_seed(72)
+    d = torch.randn(n, device="cuda", generator=g) * torch.pow(10.0, torch.rand(n, device="cuda", generator=g) * 3 - 8)
+    thr = np.sort(thr)                                           # nondecreasing: the running maximum is the curve itself
+    thr_g = torch.from_numpy(thr).cuda()
+    out = tao.tao_project_empirical(d, thr_g, 2.0)
+    a, idx = torch.sort(d.abs(), stable=True)
+    ranks = np.unique(np.concatenate([np.arange(1, 2000), np.linspace(1, n, 20000).astype(np.int64),
+                                      np.arange(n - 2000, n + 1)]))
+    caps = oracle_mod.cap_curve(ranks, n, thr, 2.0)
+    at = torch.from_numpy(ranks - 1).cuda()
+    a_s = _np(a[at]); o_s = _np(out[idx[at]]); d_s = _np(d[idx[at]])
+    over = a_s.astype(np.float64) > caps
+    from oracle.project import _f32_not_above
+    expect = np.copysign(np.where(over, _f32_not_above(caps), a_s), d_s).astype(np.float32)
+    assert np.array_equal(o_s.view(np.uint32), expect.view(np.uint32))
+    assert over.any() and not over.all()
+    same = out == d
+    assert bool((out.abs() <= d.abs()).all()) and bool((torch.signbit(out) == torch.signbit(d)).all())
+    print("134M: %.1f%% of the elements capped" % (100.0 * (1 - same.float().mean().item())), flush=True)
+    again = tao.tao_project_empirical(out, thr_g, 2.0)
+    assert bool((again.view(torch.int32) == out.view(torch.int32)).all())
