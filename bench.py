@@ -286,17 +286,19 @@ def main():
                                 "frac_hbm": 12.0 * ref.numel() / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
                                 "violations": prof["violations"], "expected_violations": int((cls == 2).sum()),
                                 "p50": prof["p50"], "p99": prof["p99"], "p999": prof["p999"], "max_rel": prof["max_rel"]}
-        # the two projections of Sec. 4.4 on the 67M deviations claimed - ref (thresholds: a third of
-        # the deviations' own percentile profile, so that a good part is capped)
+        # the two projections of Sec. 4.4 on the 67M deviations claimed - ref; thresholds: the
+        # deviations' own percentile profile (bin upper edges: part of the elements is capped) and a
+        # third of it (every element is capped: the worst case of the last pass's random writes)
         delta = claimed - ref
         eprof = tao.tao_profile_errors(claimed, ref)
-        thr = torch.from_numpy((eprof["abs_p"] / 3).astype("float32")).to(dev)
         pws = torch.empty(tao.tao_project_workspace_bytes(delta.numel()), dtype=torch.uint8, device=dev)
         pout = torch.empty_like(delta)
-        ms = _event_time(torch, lambda: tao.tao_project_empirical(delta, thr, 1.0, out=pout, ws=pws), 5, 1)
-        kernels["project_empirical_67M"] = {"ms": ms, "Gelem/s": delta.numel() / (ms * 1e-3) / 1e9,
-                                            "capped_frac": float((pout != delta).float().mean().item()),
-                                            "GB/s_at_72B_per_element": 72.0 * delta.numel() / (ms * 1e-3) / 1e9}
+        for nm, f in (("project_empirical_67M", 1.0), ("project_empirical_67M_all_capped", 1.0 / 3)):
+            thr = torch.from_numpy((eprof["abs_p"] * f).astype("float32")).to(dev)
+            ms = _event_time(torch, lambda: tao.tao_project_empirical(delta, thr, 1.0, out=pout, ws=pws), 5, 1)
+            kernels[nm] = {"ms": ms, "Gelem/s": delta.numel() / (ms * 1e-3) / 1e9,
+                           "capped_frac": float((pout != delta).float().mean().item()),
+                           "GB/s_at_72B_per_element": 72.0 * delta.numel() / (ms * 1e-3) / 1e9}
         ms = _event_time(torch, lambda: tao.tao_project_clip(delta, out, 1.0, out=pout), 20, 2)
         kernels["project_clip_67M"] = {"ms": ms, "GB/s": 12.0 * delta.numel() / (ms * 1e-3) / 1e9,
                                        "frac_hbm": 12.0 * delta.numel() / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}

@@ -150,3 +150,68 @@ def test_projection_with_calibrated_thresholds_end_to_end(tao, oracle_mod):
             k = int(np.floor(n * p / 100.0 + 0.5))              # largest k with (k - 1/2)/n <= p/100
             assert k >= 1 and float(srt[k - 1]) <= caps[g], (g, p)
         assert np.any(out.cpu().numpy() != delta.numpy())
+
+
+def test_library_calls_replay_from_a_hip_graph(tao, oracle_mod):
+    """The entry points only enqueue kernels on the caller's stream (no allocation, no memset, no
+    synchronisation), so a sequence of them can be captured once and replayed.  Three replays on
+    fresh inputs, with eager work and synchronisations in between, each compared bit for bit with
+    the eager result of the same calls."""
+    rng = _rng(31)
+    M, N, K = 384, 256, 320
+    A = torch.empty((M, K), device="cuda"); W = torch.empty((N, K), device="cuda")
+    x = torch.empty((M, N), device="cuda")
+    thr = torch.from_numpy(_thr(rng, 2e-6)).cuda()
+    tau_f = torch.empty((M, N), device="cuda"); tau_s = torch.empty((M, N), device="cuda")
+    tau_sm = torch.empty((M, N), device="cuda"); y_sm = torch.empty((M, N), device="cuda")
+    proj = torch.empty((M, N), device="cuda"); claimed = torch.empty((M, N), device="cuda"); ref = torch.empty((M, N), device="cuda")
+    prof = tao.new_profile_buffer(A.device)
+    ws_split = torch.empty(tao.tao_linear_split_workspace_bytes(M, N, K, 1, True), dtype=torch.uint8, device="cuda")
+    ws_proj = torch.empty(tao.tao_project_workspace_bytes(M * N), dtype=torch.uint8, device="cuda")
+    ws_chk = torch.empty(tao.tao_check_workspace_bytes(M * N), dtype=torch.uint8, device="cuda")
+
+    def fill(seed):
+        g = torch.Generator(device="cuda").manual_seed(seed)
+        A.normal_(generator=g); W.normal_(generator=g); x.normal_(generator=g)
+        ref.copy_(A @ W.t())
+        claimed.copy_(ref * (1 + 3e-7 * torch.randn((M, N), device="cuda", generator=g)))
+        y_sm.copy_(torch.softmax(x, -1))
+
+    def calls():
+        tao.tao_bound_linear(A, W, out=tau_f)
+        tao.tao_bound_linear_split(A, W, out=tau_s, ws=ws_split)
+        tao.tao_bound_softmax(x, y_sm, out=tau_sm)
+        tao.tao_check_and_profile(claimed, ref, tau_f, out=prof, readback=False, ws=ws_chk)
+        tao.tao_project_empirical(x, thr, 2.0, out=proj, ws=ws_proj)
+
+    outs = (tau_f, tau_s, tau_sm, proj)
+    fill(100)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        calls()
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        calls()
+    torch.cuda.synchronize()
+    for seed in (101, 102, 103):
+        print("graph replay, seed", seed, flush=True)
+        fill(seed)
+        for o in outs:
+            o.fill_(-1.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [o.clone() for o in outs]
+        got_prof = tao.read_profile(prof)
+        for o in outs:
+            o.fill_(-2.0)
+        calls()
+        torch.cuda.synchronize()
+        for g_, o in zip(got, outs):
+            assert bool((g_.view(torch.int32) == o.view(torch.int32)).all())
+        eager_prof = tao.read_profile(prof)
+        assert got_prof["violations"] == eager_prof["violations"] and np.array_equal(got_prof["hist"], eager_prof["hist"])
+        want = oracle_mod.project_empirical(x.cpu().numpy(), thr.cpu().numpy(), 2.0)
+        assert np.array_equal(got[3].cpu().numpy().view(np.uint32), want.view(np.uint32))
