@@ -292,3 +292,50 @@ def test_projections_full_size(tao, oracle_mod):
     print("134M: %.1f%% of the elements capped" % (100.0 * (1 - same.float().mean().item())), flush=True)
     again = tao.tao_project_empirical(out, thr_g, 2.0)
     assert bool((again.view(torch.int32) == out.view(torch.int32)).all())
+
+
+def test_projection_at_the_maximum_size(tao, oracle_mod):
+    """n = 2^31 - 1, the largest tensor tao_project_empirical takes (the payload keeps the index in
+    31 bits).  The magnitudes are bit patterns 2^23 + (pi(i) >> 1) for the bijection
+    pi(i) = i g mod n (n is prime), so every value occurs twice and the rank of element i follows
+    in closed form: 2 (pi >> 1) + 1, plus one if its twin has the smaller index (equal magnitudes
+    keep their index order).  Sampled elements are compared with the oracle's cap at that rank."""
+    from oracle.project import _f32_not_above
+    n = (1 << 31) - 1
+    g = 1234567891
+    g_inv = pow(g, -1, n)
+    idx = torch.arange(n, device="cuda", dtype=torch.int64)
+    pi = (idx * g) % n
+    bits = (pi >> 1) + (1 << 23) + ((idx & 1) << 31)           # odd indices negative
+    del pi
+    d = (bits & 0xffffffff).to(torch.int64)
+    d = torch.where(d >= (1 << 31), d - (1 << 32), d).to(torch.int32).view(torch.float32)
+    del bits, idx
+    torch.cuda.empty_cache()
+    # thresholds: the magnitude curve itself at 0.9 of each grid percentage (monotone), so that low
+    # ranks pass and high ranks are capped
+    grid = np.asarray(oracle_mod.GRID_PERCENT, dtype=np.float64)
+    tb = ((grid / 100.0 * 0.9 * (1 << 30)).astype(np.int64) + (1 << 23)).astype(np.uint32)
+    thr = tb.view(np.float32).copy()
+    out = tao.tao_project_empirical(d, torch.from_numpy(thr).cuda(), 1.0)
+    torch.cuda.synchronize()
+    rng = np.random.Generator(np.random.Philox(77))
+    sample = np.unique(np.concatenate([np.arange(0, 4096), np.arange(n - 4096, n),
+                                       rng.integers(0, n, 200000), [g_inv, (g_inv * (n - 1)) % n]])).astype(np.int64)
+    p = (sample.astype(object) * g) % n                          # exact integers
+    m = np.array([int(v) >> 1 for v in p], dtype=np.int64)
+    twin = np.array([int(v) ^ 1 for v in p], dtype=object)
+    twin_idx = np.array([(int(t) * g_inv) % n if t < n else n for t in twin], dtype=np.int64)
+    rank = 2 * m + 1 + (twin_idx < sample)
+    caps = oracle_mod.cap_curve(rank, n, thr, 1.0)
+    at = torch.from_numpy(sample).cuda()
+    d_s = d[at].cpu().numpy(); o_s = out[at].cpu().numpy()
+    a_s = np.abs(d_s)
+    over = a_s.astype(np.float64) > caps
+    expect = np.copysign(np.where(over, _f32_not_above(caps), a_s), d_s).astype(np.float32)
+    bad = np.nonzero(o_s.view(np.uint32) != expect.view(np.uint32))[0]
+    assert bad.size == 0, (bad.size, sample[bad[:5]], o_s[bad[:5]], expect[bad[:5]])
+    assert over.any() and not over.all()
+    capped = float((out != d).float().mean().item())
+    print("2^31 - 1 elements: %.1f%% capped" % (100 * capped), flush=True)
+    assert abs(capped - float(over.mean())) < 0.01
