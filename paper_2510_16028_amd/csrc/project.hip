@@ -38,10 +38,12 @@ constexpr int kXcds = 8;
 struct CapSeg {
     double c0, dc, p0, dp;     // C(r) = c0 + dc * ((r - p0) / dp)
     double head;               // max of the caps of all earlier ranks' segments and of this one's first rank
+    double inv_dp;             // ~ 1 / dp, for estimates only
 };
 struct CapTable {
     CapSeg seg[TAO_NGRID];
     double n;                  // (double)n
+    double percent_per_rank;   // ~ 100 / n, for estimates only
 };
 
 __device__ __forceinline__ double grid_percent(int j) {      // P = {1, 5, 10, ..., 95, 99, 100}
@@ -104,9 +106,10 @@ __global__ void __launch_bounds__(kWave) cap_table_kernel(const float* __restric
         double head = cfirst;
         for (int e = 0; e < j; ++e) head = fmax(head, seg_max[e]);
         s.head = head;
+        s.inv_dp = 1.0 / s.dp;
         tab->seg[j] = s;
     }
-    if (j == 0) tab->n = dn;
+    if (j == 0) { tab->n = dn; tab->percent_per_rank = 100.0 / dn; }
 }
 
 // ---- (i) -------------------------------------------------------------------------------------
@@ -155,10 +158,12 @@ __device__ __forceinline__ void load_item(const float* delta, const unsigned* __
     }
 }
 
-// Digit histogram of every tile: hist[digit * tiles + tile].
+// Digit histogram of every tile: hist[digit * tiles + tile].  Counting does not depend on the
+// order inside the tile, so a thread takes four runs of four consecutive keys (16-byte loads, all
+// issued before the first is used).
 template <bool FIRST>
 __global__ void __launch_bounds__(kSortThreads) radix_count(const float* __restrict__ delta, const unsigned* __restrict__ keys,
-                                                            long n, long tiles, long tiles_per_xcd, int shift,
+                                                            long n, long tiles, long tiles_per_xcd, int shift, int vec_ok,
                                                             unsigned* __restrict__ hist) {
     __shared__ unsigned cnt[kSortWaves][kRadix];
     const long tile = tile_of_block(tiles_per_xcd);
@@ -166,18 +171,32 @@ __global__ void __launch_bounds__(kSortThreads) radix_count(const float* __restr
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
     for (int d = lane; d < kRadix; d += kWave) cnt[wave][d] = 0;
     __builtin_amdgcn_wave_barrier();
-    const long base = tile * kSortTile + (long)wave * (kSortItems * kWave) + lane;
-#pragma unroll 4
+    const unsigned* src = FIRST ? reinterpret_cast<const unsigned*>(delta) : keys;
+    const long tile_base = tile * kSortTile;
+    unsigned key[kSortItems];
+    const bool full = tile_base + kSortTile <= n;
+    if (full && vec_ok) {
+#pragma unroll
+        for (int q = 0; q < kSortItems / 4; ++q) {
+            const uint4 v = *reinterpret_cast<const uint4*>(src + tile_base + ((long)q * kSortThreads + threadIdx.x) * 4);
+            key[4 * q] = v.x; key[4 * q + 1] = v.y; key[4 * q + 2] = v.z; key[4 * q + 3] = v.w;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < kSortItems; ++i) {
+            const long e = tile_base + (long)i * kSortThreads + threadIdx.x;
+            key[i] = e < n ? src[e] : 0u;
+        }
+    }
+#pragma unroll
     for (int i = 0; i < kSortItems; ++i) {
-        const long e = base + (long)i * kWave;
-        const bool valid = e < n;
-        unsigned key = 0;
-        if (valid) key = FIRST ? (__float_as_uint(delta[e]) & 0x7fffffffu) : keys[e];
-        const unsigned d = (key >> shift) & (kRadix - 1);
+        // element index of key[i] in the scalar layout (the vector layout is only used on full tiles)
+        const bool valid = full || tile_base + (long)i * kSortThreads + threadIdx.x < n;
+        const unsigned d = ((FIRST ? key[i] & 0x7fffffffu : key[i]) >> shift) & (kRadix - 1);
         // a wave whose valid lanes all hold one digit (the rule in the exponent bytes) adds once
         const unsigned long long vmask = __ballot(valid);
         if (vmask == 0) continue;
-        const unsigned d0 = __builtin_amdgcn_readfirstlane(d);
+        const unsigned d0 = __shfl(d, (int)__builtin_ctzll(vmask), kWave);
         if (__ballot(valid && d == d0) == vmask) {
             if (lane == (int)__builtin_ctzll(vmask)) cnt[wave][d0] += (unsigned)__popcll(vmask);
         } else if (valid) {
@@ -243,18 +262,36 @@ __global__ void __launch_bounds__(1024) scan_spine(unsigned* __restrict__ sums, 
 __global__ void __launch_bounds__(kSortThreads) scan_apply(unsigned* __restrict__ c, long count,
                                                            const unsigned* __restrict__ sums) {
     __shared__ unsigned wave_tot[kSortWaves];
-    // thread t owns 16 consecutive counters: local sequential scan between two block scans
+    // thread t owns 16 consecutive counters (the array is 256-byte aligned and chunks start at
+    // multiples of 4096 counters): local sequential scan between two block scans
     const long base = (long)blockIdx.x * kScanChunk + (long)threadIdx.x * 16;
     unsigned v[16];
     unsigned s = 0;
+    const bool whole = base + 16 <= count;
+    if (whole) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { v[i] = base + i < count ? c[base + i] : 0u; s += v[i]; }
+        for (int q = 0; q < 4; ++q) {
+            const uint4 t = *reinterpret_cast<const uint4*>(c + base + 4 * q);
+            v[4 * q] = t.x; v[4 * q + 1] = t.y; v[4 * q + 2] = t.z; v[4 * q + 3] = t.w;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = base + i < count ? c[base + i] : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += v[i];
     unsigned total;
     unsigned run = block_exclusive_scan(s, wave_tot, total) + sums[blockIdx.x];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        if (base + i < count) c[base + i] = run;
-        run += v[i];
+    for (int i = 0; i < 16; ++i) { const unsigned t = v[i]; v[i] = run; run += t; }
+    if (whole) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            *reinterpret_cast<uint4*>(c + base + 4 * q) = make_uint4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if (base + i < count) c[base + i] = v[i];
     }
 }
 
@@ -346,11 +383,20 @@ __global__ void __launch_bounds__(kSortThreads) radix_scatter(const float* delta
             keys_out[dest] = k;
             vals_out[dest] = v;
         } else {
-            // dest is the 0-based rank: cap of rank dest + 1, running maximum included
+            // dest is the 0-based rank: cap of rank dest + 1, running maximum included.  Most of the
+            // work is two binary64 divisions; an estimate with reciprocals (absolute error far below
+            // the margin used) first sorts out the elements that are clearly under their cap.
+            const float a = __uint_as_float(k);
+            const double kk = (double)dest + 0.5;
+            const double re = kk * tab->percent_per_rank;
+            const int je = segment_of(re);
+            const CapSeg se = tab->seg[je];
+            const double ce = fmax(se.head, se.c0 + se.dc * ((re - se.p0) * se.inv_dp));
+            const bool near_knot = fabs(re - se.p0) < 1e-6 || fabs(re - (se.p0 + se.dp)) < 1e-6;
+            if (!near_knot && (double)a < ce - (fabs(se.dc) + ce) * 1e-9) continue;
             const double r = rank_percent((double)dest + 1.0, tab->n);
             const CapSeg s = tab->seg[segment_of(r)];
             const double cap = fmax(s.head, cap_in_segment(s, r));
-            const float a = __uint_as_float(k);
             const unsigned idx = v & 0x7fffffffu;
             if ((double)a > cap && (long)idx < n)                   // NaN compares false; out holds delta already
                 out[idx] = __uint_as_float(__float_as_uint(down32(cap)) | (v & 0x80000000u));
@@ -428,8 +474,9 @@ int tao_project_empirical(const float* delta, const float* thr_abs, double alpha
     unsigned* kout = w.keys_a; unsigned* vout = w.vals_a;
     for (int pass = 0; pass < 4; ++pass) {
         const int shift = 8 * pass;
-        if (pass == 0) hipLaunchKernelGGL((radix_count<true>), grid, blk, 0, st, delta, kin, n, w.tiles, per_xcd, shift, w.hist);
-        else           hipLaunchKernelGGL((radix_count<false>), grid, blk, 0, st, delta, kin, n, w.tiles, per_xcd, shift, w.hist);
+        if (pass == 0) hipLaunchKernelGGL((radix_count<true>), grid, blk, 0, st, delta, kin, n, w.tiles, per_xcd, shift,
+                                          (int)aligned(delta, 16), w.hist);
+        else           hipLaunchKernelGGL((radix_count<false>), grid, blk, 0, st, delta, kin, n, w.tiles, per_xcd, shift, 1, w.hist);
         hipLaunchKernelGGL(scan_chunk_sums, sgrid, blk, 0, st, w.hist, w.counters, w.sums);
         hipLaunchKernelGGL(scan_spine, dim3(1), dim3(1024), 0, st, w.sums, w.chunks);
         hipLaunchKernelGGL(scan_apply, sgrid, blk, 0, st, w.hist, w.counters, w.sums);
