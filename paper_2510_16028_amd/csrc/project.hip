@@ -10,7 +10,7 @@
 // with its sign bit on top.  Per pass: count (digit histogram per tile), scan (of the digit-major
 // counter array), scatter (stable rank inside the tile by wave-wide digit matching, elements
 // reordered in LDS so that runs of one digit leave as contiguous writes).  The first pass reads
-// delta itself (and copies it to out when the two differ); the last pass writes no sorted array at
+// delta itself (its count kernel copies it to out when the two differ); the last pass writes no sorted array at
 // all: the destination of an element IS its rank, so the cap is evaluated there and only the
 // elements that exceed their cap are written, straight to out[index] -- the one access of the
 // whole path that is random, 4 bytes per 64-byte line, and therefore kept to the elements that
@@ -144,12 +144,9 @@ __device__ __forceinline__ long tile_of_block(long tiles_per_xcd) {
 
 template <bool FIRST>
 __device__ __forceinline__ void load_item(const float* delta, const unsigned* __restrict__ keys,
-                                          const unsigned* __restrict__ vals, long e, unsigned& key, unsigned& val,
-                                          float* copy_to) {
+                                          const unsigned* __restrict__ vals, long e, unsigned& key, unsigned& val) {
     if (FIRST) {
-        const float x = delta[e];
-        if (copy_to) copy_to[e] = x;
-        const unsigned b = __float_as_uint(x);
+        const unsigned b = __float_as_uint(delta[e]);
         key = b & 0x7fffffffu;
         val = (unsigned)e | (b & 0x80000000u);
     } else {
@@ -160,11 +157,11 @@ __device__ __forceinline__ void load_item(const float* delta, const unsigned* __
 
 // Digit histogram of every tile: hist[digit * tiles + tile].  Counting does not depend on the
 // order inside the tile, so a thread takes four runs of four consecutive keys (16-byte loads, all
-// issued before the first is used).
+// issued before the first is used).  The first pass also copies delta to out on the way.
 template <bool FIRST>
-__global__ void __launch_bounds__(kSortThreads) radix_count(const float* __restrict__ delta, const unsigned* __restrict__ keys,
+__global__ void __launch_bounds__(kSortThreads) radix_count(const float* delta, const unsigned* __restrict__ keys,
                                                             long n, long tiles, long tiles_per_xcd, int shift, int vec_ok,
-                                                            unsigned* __restrict__ hist) {
+                                                            unsigned* __restrict__ hist, unsigned* copy_to) {
     __shared__ unsigned cnt[kSortWaves][kRadix];
     const long tile = tile_of_block(tiles_per_xcd);
     if (tile >= tiles) return;                                 // whole workgroup
@@ -178,7 +175,9 @@ __global__ void __launch_bounds__(kSortThreads) radix_count(const float* __restr
     if (full && vec_ok) {
 #pragma unroll
         for (int q = 0; q < kSortItems / 4; ++q) {
-            const uint4 v = *reinterpret_cast<const uint4*>(src + tile_base + ((long)q * kSortThreads + threadIdx.x) * 4);
+            const long e = tile_base + ((long)q * kSortThreads + threadIdx.x) * 4;
+            const uint4 v = *reinterpret_cast<const uint4*>(src + e);
+            if (FIRST && copy_to) *reinterpret_cast<uint4*>(copy_to + e) = v;
             key[4 * q] = v.x; key[4 * q + 1] = v.y; key[4 * q + 2] = v.z; key[4 * q + 3] = v.w;
         }
     } else {
@@ -186,6 +185,7 @@ __global__ void __launch_bounds__(kSortThreads) radix_count(const float* __restr
         for (int i = 0; i < kSortItems; ++i) {
             const long e = tile_base + (long)i * kSortThreads + threadIdx.x;
             key[i] = e < n ? src[e] : 0u;
+            if (FIRST && copy_to && e < n) copy_to[e] = key[i];
         }
     }
 #pragma unroll
@@ -303,7 +303,7 @@ __global__ void __launch_bounds__(kSortThreads) radix_scatter(const float* delta
                                                               unsigned* __restrict__ keys_out, unsigned* __restrict__ vals_out,
                                                               long n, long tiles, long tiles_per_xcd, int shift,
                                                               const unsigned* __restrict__ hist,
-                                                              const CapTable* __restrict__ tab, float* out, int copy_delta) {
+                                                              const CapTable* __restrict__ tab, float* out) {
     __shared__ unsigned skey[kSortTile];
     __shared__ unsigned sval[kSortTile];
     __shared__ unsigned cnt[kSortWaves][kRadix];               // per wave: running count, then the wave's offset
@@ -328,7 +328,7 @@ __global__ void __launch_bounds__(kSortThreads) radix_scatter(const float* delta
     for (int i = 0; i < kSortItems; ++i) {
         const long e = base + (long)i * kWave;
         key[i] = 0xffffffffu; val[i] = 0;
-        if (e < n) load_item<FIRST>(delta, keys_in, vals_in, e, key[i], val[i], copy_delta ? out : nullptr);
+        if (e < n) load_item<FIRST>(delta, keys_in, vals_in, e, key[i], val[i]);
     }
     // Stable rank of every element among those of its wave with the same digit: the elements of a
     // wave are ordered by (i, lane), which is their order in memory.
@@ -475,20 +475,21 @@ int tao_project_empirical(const float* delta, const float* thr_abs, double alpha
     for (int pass = 0; pass < 4; ++pass) {
         const int shift = 8 * pass;
         if (pass == 0) hipLaunchKernelGGL((radix_count<true>), grid, blk, 0, st, delta, kin, n, w.tiles, per_xcd, shift,
-                                          (int)aligned(delta, 16), w.hist);
-        else           hipLaunchKernelGGL((radix_count<false>), grid, blk, 0, st, delta, kin, n, w.tiles, per_xcd, shift, 1, w.hist);
+                                          (int)(aligned(delta, 16) && aligned(out, 16)), w.hist,
+                                          out != delta ? reinterpret_cast<unsigned*>(out) : nullptr);
+        else           hipLaunchKernelGGL((radix_count<false>), grid, blk, 0, st, delta, kin, n, w.tiles, per_xcd, shift, 1, w.hist, nullptr);
         hipLaunchKernelGGL(scan_chunk_sums, sgrid, blk, 0, st, w.hist, w.counters, w.sums);
         hipLaunchKernelGGL(scan_spine, dim3(1), dim3(1024), 0, st, w.sums, w.chunks);
         hipLaunchKernelGGL(scan_apply, sgrid, blk, 0, st, w.hist, w.counters, w.sums);
         if (pass == 0)
             hipLaunchKernelGGL((radix_scatter<true, false>), grid, blk, 0, st, delta, kin, vin, kout, vout, n, w.tiles, per_xcd,
-                               shift, w.hist, w.tab, out, (int)(out != delta));
+                               shift, w.hist, w.tab, out);
         else if (pass < 3)
             hipLaunchKernelGGL((radix_scatter<false, false>), grid, blk, 0, st, delta, kin, vin, kout, vout, n, w.tiles, per_xcd,
-                               shift, w.hist, w.tab, out, 0);
+                               shift, w.hist, w.tab, out);
         else
             hipLaunchKernelGGL((radix_scatter<false, true>), grid, blk, 0, st, delta, kin, vin, kout, vout, n, w.tiles, per_xcd,
-                               shift, w.hist, w.tab, out, 0);
+                               shift, w.hist, w.tab, out);
         kin = kout; vin = vout;
         kout = kin == w.keys_a ? w.keys_b : w.keys_a;
         vout = vin == w.vals_a ? w.vals_b : w.vals_a;
