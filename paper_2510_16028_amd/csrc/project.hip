@@ -70,8 +70,8 @@ __device__ __forceinline__ float down32(double c) {
     return f;
 }
 
-__global__ void __launch_bounds__(kWave) cap_table_kernel(const float* __restrict__ thr, double alpha, long n,
-                                                          CapTable* __restrict__ tab) {
+// Fills *tab (global or LDS); called by all threads of a workgroup of at least 64, ends with a barrier.
+__device__ __forceinline__ void build_cap_table(const float* __restrict__ thr, double alpha, long n, CapTable* tab) {
     __shared__ double seg_max[TAO_NGRID];
     __shared__ long first_rank[TAO_NGRID + 1];
     const int j = threadIdx.x;
@@ -110,6 +110,12 @@ __global__ void __launch_bounds__(kWave) cap_table_kernel(const float* __restric
         tab->seg[j] = s;
     }
     if (j == 0) { tab->n = dn; tab->percent_per_rank = 100.0 / dn; }
+    __syncthreads();
+}
+
+__global__ void __launch_bounds__(kWave) cap_table_kernel(const float* __restrict__ thr, double alpha, long n,
+                                                          CapTable* __restrict__ tab) {
+    build_cap_table(thr, alpha, n, tab);
 }
 
 // ---- (i) -------------------------------------------------------------------------------------
@@ -295,6 +301,98 @@ __global__ void __launch_bounds__(kSortThreads) scan_apply(unsigned* __restrict_
     }
 }
 
+// LDS of one tile's pass.
+struct TileSort {
+    unsigned skey[kSortTile];
+    unsigned sval[kSortTile];
+    unsigned cnt[kSortWaves][kRadix];        // per wave: running count, then the wave's offset in the digit's run
+    unsigned tile_excl[kRadix];              // first tile-local position of a digit
+    unsigned dest_off[kRadix];               // global destination minus tile-local position
+    unsigned wave_tot[kSortWaves];
+};
+
+// One stable counting-sort step of a tile on the digit at `shift`: element i of lane l of wave w is
+// the tile's element w * 1024 + i * 64 + l (`valid_count` of them exist); on return sh.skey / sh.sval
+// hold the tile ordered by digit, equal digits in their old order, and sh.tile_excl the start of
+// every digit's run.  All threads of the workgroup call it; it ends with a barrier.
+__device__ __forceinline__ void tile_sort_step(TileSort& sh, const unsigned (&key)[kSortItems],
+                                               const unsigned (&val)[kSortItems], int valid_count, int shift) {
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    for (int d = lane; d < kRadix; d += kWave) sh.cnt[wave][d] = 0;
+    __builtin_amdgcn_wave_barrier();
+    const int first = wave * (kSortItems * kWave) + lane;
+    unsigned short rank[kSortItems];
+    // Stable rank of every element among those of its wave with the same digit: the elements of a
+    // wave are ordered by (i, lane), which is their order in memory.  Eight ballots find the lanes
+    // that share a digit; the lowest of them advances the wave's counter.
+    const unsigned long long lanes_below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int i = 0; i < kSortItems; ++i) {
+        const bool valid = first + i * kWave < valid_count;
+        const unsigned d = (key[i] >> shift) & (kRadix - 1);
+        unsigned long long same = __ballot(valid);
+#pragma unroll
+        for (int b = 0; b < 8; ++b) {
+            const bool bit = (d >> b) & 1u;
+            const unsigned long long bal = __ballot(bit);
+            same &= bit ? bal : ~bal;
+        }
+        const unsigned prev = valid ? sh.cnt[wave][d] : 0u;
+        const unsigned r = prev + (unsigned)__popcll(same & lanes_below);
+        __builtin_amdgcn_wave_barrier();                       // all reads of this round before its writes
+        if (valid && (same & lanes_below) == 0) sh.cnt[wave][d] = prev + (unsigned)__popcll(same);
+        rank[i] = (unsigned short)r;
+        __builtin_amdgcn_wave_barrier();
+    }
+    __syncthreads();
+    {   // per digit: offsets of the waves inside the digit's run, the run's place in the tile
+        const int d = threadIdx.x;                             // kSortThreads == kRadix
+        unsigned run = 0;
+#pragma unroll
+        for (int w = 0; w < kSortWaves; ++w) { const unsigned t = sh.cnt[w][d]; sh.cnt[w][d] = run; run += t; }
+        unsigned total;
+        sh.tile_excl[d] = block_exclusive_scan(run, sh.wave_tot, total);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kSortItems; ++i) {
+        if (first + i * kWave < valid_count) {
+            const unsigned d = (key[i] >> shift) & (kRadix - 1);
+            const unsigned pos = sh.tile_excl[d] + sh.cnt[wave][d] + rank[i];
+            if (pos < (unsigned)kSortTile) { sh.skey[pos] = key[i]; sh.sval[pos] = val[i]; }
+        }
+    }
+    __syncthreads();
+}
+
+// The element of 0-based rank `rank0` with magnitude bits k and payload v: write its capped value
+// if it exceeds its cap (out already holds delta, unless WRITE_ALL).  Most of the work is two
+// binary64 divisions; an estimate with reciprocals (error far below the margin used) first sorts
+// out the elements that are clearly under their cap.
+template <bool WRITE_ALL>
+__device__ __forceinline__ void cap_and_store(const CapTable& tab, unsigned rank0, unsigned k, unsigned v, long n,
+                                              float* out) {
+    const float a = __uint_as_float(k);
+    const unsigned idx = v & 0x7fffffffu;
+    if ((long)idx >= n) return;                                // cannot happen
+    const double kk = (double)rank0 + 0.5;
+    const double re = kk * tab.percent_per_rank;
+    const CapSeg se = tab.seg[segment_of(re)];
+    const double ce = fmax(se.head, se.c0 + se.dc * ((re - se.p0) * se.inv_dp));
+    const bool near_knot = fabs(re - se.p0) < 1e-6 || fabs(re - (se.p0 + se.dp)) < 1e-6;
+    float star = a;
+    if (near_knot || !((double)a < ce - (fabs(se.dc) + ce) * 1e-9)) {
+        const double r = rank_percent((double)rank0 + 1.0, tab.n);
+        const CapSeg s = tab.seg[segment_of(r)];
+        const double cap = fmax(s.head, cap_in_segment(s, r));
+        if ((double)a > cap) star = down32(cap);               // NaN compares false and stays
+        else if (!WRITE_ALL) return;
+    } else if (!WRITE_ALL) {
+        return;
+    }
+    out[idx] = __uint_as_float(__float_as_uint(star) | (v & 0x80000000u));
+}
+
 // Scatter pass.  `hist` holds the scanned counters: hist[d * tiles + tile] is the destination of
 // the tile's first element with digit d.
 template <bool FIRST, bool LAST>
@@ -304,104 +402,68 @@ __global__ void __launch_bounds__(kSortThreads) radix_scatter(const float* delta
                                                               long n, long tiles, long tiles_per_xcd, int shift,
                                                               const unsigned* __restrict__ hist,
                                                               const CapTable* __restrict__ tab, float* out) {
-    __shared__ unsigned skey[kSortTile];
-    __shared__ unsigned sval[kSortTile];
-    __shared__ unsigned cnt[kSortWaves][kRadix];               // per wave: running count, then the wave's offset
-    __shared__ unsigned tile_excl[kRadix];                     // first tile-local position of a digit
-    __shared__ unsigned dest_off[kRadix];                      // global destination minus tile-local position
-    __shared__ unsigned wave_tot[kSortWaves];
-
+    __shared__ TileSort sh;
     const long tile = tile_of_block(tiles_per_xcd);
     if (tile >= tiles) return;                                 // whole workgroup
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-    for (int d = lane; d < kRadix; d += kWave) cnt[wave][d] = 0;
-    __builtin_amdgcn_wave_barrier();
-
     const long tile_base = tile * kSortTile;
     const long base = tile_base + (long)wave * (kSortItems * kWave) + lane;
     const long left = n - tile_base;
     const int tile_count = left < kSortTile ? (int)left : kSortTile;
 
     unsigned key[kSortItems], val[kSortItems];
-    unsigned short rank[kSortItems];
 #pragma unroll
     for (int i = 0; i < kSortItems; ++i) {
         const long e = base + (long)i * kWave;
         key[i] = 0xffffffffu; val[i] = 0;
         if (e < n) load_item<FIRST>(delta, keys_in, vals_in, e, key[i], val[i]);
     }
-    // Stable rank of every element among those of its wave with the same digit: the elements of a
-    // wave are ordered by (i, lane), which is their order in memory.
-    const unsigned long long lanes_below = (1ull << lane) - 1ull;
-#pragma unroll
-    for (int i = 0; i < kSortItems; ++i) {
-        const bool valid = base + (long)i * kWave < n;
-        const unsigned d = (key[i] >> shift) & (kRadix - 1);
-        unsigned long long same = __ballot(valid);
-#pragma unroll
-        for (int b = 0; b < 8; ++b) {
-            const bool bit = (d >> b) & 1u;
-            const unsigned long long bal = __ballot(bit);
-            same &= bit ? bal : ~bal;
-        }
-        const unsigned prev = valid ? cnt[wave][d] : 0u;
-        const unsigned r = prev + (unsigned)__popcll(same & lanes_below);
-        __builtin_amdgcn_wave_barrier();                       // all reads of this round before its writes
-        if (valid && (same & lanes_below) == 0) cnt[wave][d] = prev + (unsigned)__popcll(same);
-        rank[i] = (unsigned short)r;
-        __builtin_amdgcn_wave_barrier();
-    }
-    __syncthreads();
-
-    // per digit: offsets of the waves inside the digit's run, the run's place in the tile and in memory
-    {
-        const int d = threadIdx.x;                             // kSortThreads == kRadix
-        unsigned run = 0;
-#pragma unroll
-        for (int w = 0; w < kSortWaves; ++w) { const unsigned t = cnt[w][d]; cnt[w][d] = run; run += t; }
-        unsigned total;
-        const unsigned ex = block_exclusive_scan(run, wave_tot, total);
-        tile_excl[d] = ex;
-        dest_off[d] = hist[(long)d * tiles + tile] - ex;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < kSortItems; ++i) {
-        if (base + (long)i * kWave < n) {
-            const unsigned d = (key[i] >> shift) & (kRadix - 1);
-            const unsigned pos = tile_excl[d] + cnt[wave][d] + rank[i];
-            if (pos < (unsigned)kSortTile) { skey[pos] = key[i]; sval[pos] = val[i]; }
-        }
-    }
+    tile_sort_step(sh, key, val, tile_count, shift);
+    sh.dest_off[threadIdx.x] = hist[(long)threadIdx.x * tiles + tile] - sh.tile_excl[threadIdx.x];   // kSortThreads == kRadix
     __syncthreads();
     for (int j = threadIdx.x; j < tile_count; j += kSortThreads) {
-        const unsigned k = skey[j], v = sval[j];
+        const unsigned k = sh.skey[j], v = sh.sval[j];
         const unsigned d = (k >> shift) & (kRadix - 1);
-        const unsigned dest = dest_off[d] + (unsigned)j;
+        const unsigned dest = sh.dest_off[d] + (unsigned)j;
         if ((long)dest >= n) continue;                         // cannot happen with consistent counters
         if (!LAST) {
             keys_out[dest] = k;
             vals_out[dest] = v;
         } else {
-            // dest is the 0-based rank: cap of rank dest + 1, running maximum included.  Most of the
-            // work is two binary64 divisions; an estimate with reciprocals (absolute error far below
-            // the margin used) first sorts out the elements that are clearly under their cap.
-            const float a = __uint_as_float(k);
-            const double kk = (double)dest + 0.5;
-            const double re = kk * tab->percent_per_rank;
-            const int je = segment_of(re);
-            const CapSeg se = tab->seg[je];
-            const double ce = fmax(se.head, se.c0 + se.dc * ((re - se.p0) * se.inv_dp));
-            const bool near_knot = fabs(re - se.p0) < 1e-6 || fabs(re - (se.p0 + se.dp)) < 1e-6;
-            if (!near_knot && (double)a < ce - (fabs(se.dc) + ce) * 1e-9) continue;
-            const double r = rank_percent((double)dest + 1.0, tab->n);
-            const CapSeg s = tab->seg[segment_of(r)];
-            const double cap = fmax(s.head, cap_in_segment(s, r));
-            const unsigned idx = v & 0x7fffffffu;
-            if ((double)a > cap && (long)idx < n)                   // NaN compares false; out holds delta already
-                out[idx] = __uint_as_float(__float_as_uint(down32(cap)) | (v & 0x80000000u));
+            cap_and_store<false>(*tab, dest, k, v, n, out);     // dest is the 0-based rank
         }
     }
+}
+
+// Tensors of at most one tile: the four passes in LDS by one workgroup, cap table included.
+__global__ void __launch_bounds__(kSortThreads) project_one_tile(const float* delta, const float* __restrict__ thr, double alpha,
+                                                                 int n, float* out) {
+    __shared__ TileSort sh;
+    __shared__ CapTable tab;
+    build_cap_table(thr, alpha, n, &tab);                      // ends with a barrier
+    const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+    const int first = wave * (kSortItems * kWave) + lane;
+    unsigned key[kSortItems], val[kSortItems];
+#pragma unroll
+    for (int i = 0; i < kSortItems; ++i) {
+        const int e = first + i * kWave;
+        key[i] = 0xffffffffu; val[i] = 0;
+        if (e < n) load_item<true>(delta, nullptr, nullptr, e, key[i], val[i]);
+    }
+#pragma unroll 1
+    for (int pass = 0; pass < 4; ++pass) {
+        tile_sort_step(sh, key, val, n, 8 * pass);
+        if (pass < 3) {
+#pragma unroll
+            for (int i = 0; i < kSortItems; ++i) {
+                const int e = first + i * kWave;
+                if (e < n) { key[i] = sh.skey[e]; val[i] = sh.sval[e]; }
+            }
+            __syncthreads();                                   // before the next step overwrites the tile
+        }
+    }
+    for (int j = threadIdx.x; j < n; j += kSortThreads)
+        cap_and_store<true>(tab, (unsigned)j, sh.skey[j], sh.sval[j], n, out);
 }
 
 struct ProjectWorkspace {
@@ -462,6 +524,11 @@ int tao_project_empirical(const float* delta, const float* thr_abs, double alpha
     if (!delta || !thr_abs || !out) return TAO_ERR_NULL;
     if (!aligned(delta, 4) || !aligned(thr_abs, 4) || !aligned(out, 4)) return TAO_ERR_ALIGN;
     if (!ws || !aligned(ws, 256) || ws_bytes < tao_project_workspace_bytes(n)) return TAO_ERR_WORKSPACE;
+    if (n <= kSortTile) {
+        hipLaunchKernelGGL(project_one_tile, dim3(1), dim3(kSortThreads), 0, (hipStream_t)stream, delta, thr_abs, alpha,
+                           (int)n, out);
+        return launch_status();
+    }
     ProjectWorkspace w;
     carve_project(n, (char*)ws, &w);
     hipStream_t st = (hipStream_t)stream;
