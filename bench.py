@@ -127,6 +127,26 @@ def _event_time(torch, fn, reps, warm=2):
     return sum(_ms(ev)) / reps
 
 
+def projection_only(torch, tao, tao_inputs, dev, n, steps, warmup):
+    """The two projections on n deviations claimed - ref of the check generator; thresholds: the
+    deviations' own percentile profile (part of the elements is capped)."""
+    claimed, ref, tau = tao_inputs.check_triplet(dev, n=n)
+    delta = claimed - ref
+    eprof = tao.tao_profile_errors(claimed, ref)
+    del claimed, ref
+    thr = torch.from_numpy(eprof["abs_p"].astype("float32")).to(dev)
+    ws = torch.empty(tao.tao_project_workspace_bytes(n), dtype=torch.uint8, device=dev)
+    out = torch.empty_like(delta)
+    ms = _event_time(torch, lambda: tao.tao_project_empirical(delta, thr, 1.0, out=out, ws=ws), steps, warmup)
+    capped = float((out != delta).float().mean().item())
+    ms_clip = _event_time(torch, lambda: tao.tao_project_clip(delta, tau, 1.0, out=out), steps, warmup)
+    return {"workload": "projections of Sec. 4.4, %d elements" % n,
+            "project_empirical": {"ms": ms, "Gelem/s": n / (ms * 1e-3) / 1e9, "capped_frac": capped,
+                                  "GB/s_at_72B_per_element": 72.0 * n / (ms * 1e-3) / 1e9},
+            "project_clip": {"ms": ms_clip, "GB/s": 12.0 * n / (ms_clip * 1e-3) / 1e9,
+                             "frac_hbm": 12.0 * n / (ms_clip * 1e-3) / 1e9 / PEAK_HBM_GBS}}
+
+
 def cpu_baseline(ops, rows_per_op):
     """The oracle, as it stands, on the first `rows_per_op` output rows of every operator."""
     import numpy as np
@@ -181,6 +201,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stress", action="store_true", help="skip the 8192^3 / 67M-element side measurements")
     ap.add_argument("--fp32-only", action="store_true", help="matmul bounds on the FP32 matrix cores only (no BF16-split path)")
+    ap.add_argument("--projection-elems", type=int, default=0,
+                    help="only time the two projections of Sec. 4.4 on this many synthetic elements and exit "
+                         "(side measurement; used for the committed kernel trace)")
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run three 1 GiB element-wise copy kernels (reference kernel for scaling FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -196,6 +219,10 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU (no CPU fallback)"
     dev = "cuda"
     torch.cuda.set_device(0)
+
+    if args.projection_elems > 0:
+        print(json.dumps(projection_only(torch, tao, tao_inputs, dev, args.projection_elems, args.steps, args.warmup)))
+        return
 
     ops = tao_inputs.config3(dev, scale=args.scale)
     plan = [PlannedOp(tao, torch, op, use_split=not args.fp32_only) for op in ops]

@@ -33,6 +33,8 @@ constexpr int kSortTile = kSortThreads * kSortItems;          // 4096 elements p
 constexpr int kRadix = 256;
 constexpr int kScanChunk = kSortThreads * 16;                 // counters per scan workgroup
 constexpr int kXcds = 8;
+constexpr int kCountCopies = 4;                               // histogram copies per wave in radix_count
+constexpr int kCountStride = kRadix + 4;                      // copy c of digit d in LDS bank (d + 4c) % 32
 
 // One segment of the cap curve: ranks whose r lies in (p0, p0 + dp].
 struct CapSeg {
@@ -168,11 +170,11 @@ template <bool FIRST>
 __global__ void __launch_bounds__(kSortThreads) radix_count(const float* delta, const unsigned* __restrict__ keys,
                                                             long n, long tiles, long tiles_per_xcd, int shift, int vec_ok,
                                                             unsigned* __restrict__ hist, unsigned* copy_to) {
-    __shared__ unsigned cnt[kSortWaves][kRadix];
+    __shared__ unsigned cnt[kSortWaves][kCountCopies][kCountStride];
     const long tile = tile_of_block(tiles_per_xcd);
     if (tile >= tiles) return;                                 // whole workgroup
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-    for (int d = lane; d < kRadix; d += kWave) cnt[wave][d] = 0;
+    for (int d = lane; d < kCountCopies * kCountStride; d += kWave) (&cnt[wave][0][0])[d] = 0;
     __builtin_amdgcn_wave_barrier();
     const unsigned* src = FIRST ? reinterpret_cast<const unsigned*>(delta) : keys;
     const long tile_base = tile * kSortTile;
@@ -199,14 +201,18 @@ __global__ void __launch_bounds__(kSortThreads) radix_count(const float* delta, 
         // element index of key[i] in the scalar layout (the vector layout is only used on full tiles)
         const bool valid = full || tile_base + (long)i * kSortThreads + threadIdx.x < n;
         const unsigned d = ((FIRST ? key[i] & 0x7fffffffu : key[i]) >> shift) & (kRadix - 1);
-        // a wave whose valid lanes all hold one digit (the rule in the exponent bytes) adds once
+        // A wave whose valid lanes all hold one digit (the rule in the top byte of narrow data) adds
+        // once.  Otherwise LDS atomics, spread over eight copies of the histogram chosen by the lane
+        // (a few distinct digits per wave -- exponent bytes, trailing zero bytes of deviations that are
+        // differences of nearby values -- would serialise 64 atomics on a handful of addresses); the
+        // copies are 260 counters apart, so equal digits of different copies fall into different banks.
         const unsigned long long vmask = __ballot(valid);
         if (vmask == 0) continue;
         const unsigned d0 = __shfl(d, (int)__builtin_ctzll(vmask), kWave);
         if (__ballot(valid && d == d0) == vmask) {
-            if (lane == (int)__builtin_ctzll(vmask)) cnt[wave][d0] += (unsigned)__popcll(vmask);
+            if (lane == (int)__builtin_ctzll(vmask)) cnt[wave][0][d0] += (unsigned)__popcll(vmask);
         } else if (valid) {
-            atomicAdd(&cnt[wave][d], 1u);
+            atomicAdd(&cnt[wave][lane & (kCountCopies - 1)][d], 1u);
         }
         __builtin_amdgcn_wave_barrier();
     }
@@ -214,7 +220,9 @@ __global__ void __launch_bounds__(kSortThreads) radix_count(const float* delta, 
     const int d = threadIdx.x;                                 // kSortThreads == kRadix
     unsigned total = 0;
 #pragma unroll
-    for (int w = 0; w < kSortWaves; ++w) total += cnt[w][d];
+    for (int w = 0; w < kSortWaves; ++w)
+#pragma unroll
+        for (int c = 0; c < kCountCopies; ++c) total += cnt[w][c][d];
     hist[(long)d * tiles + tile] = total;
 }
 
