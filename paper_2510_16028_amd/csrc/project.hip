@@ -411,8 +411,16 @@ __global__ void __launch_bounds__(kSortThreads) radix_scatter(const float* delta
                                                               const unsigned* __restrict__ hist,
                                                               const CapTable* __restrict__ tab, float* out) {
     __shared__ TileSort sh;
+    __shared__ CapTable stab;                                  // LAST: the cap table, read per element
+    __shared__ double run_cap[LAST ? kRadix : 1];
     const long tile = tile_of_block(tiles_per_xcd);
     if (tile >= tiles) return;                                 // whole workgroup
+    if (LAST) {
+        static_assert(sizeof(CapTable) % sizeof(double) == 0 && sizeof(CapTable) / sizeof(double) <= kSortThreads, "one double per thread");
+        if (threadIdx.x < sizeof(CapTable) / sizeof(double))
+            reinterpret_cast<double*>(&stab)[threadIdx.x] = reinterpret_cast<const double*>(tab)[threadIdx.x];
+        // visible after the barriers of the sort step
+    }
     const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
     const long tile_base = tile * kSortTile;
     const long base = tile_base + (long)wave * (kSortItems * kWave) + lane;
@@ -427,7 +435,18 @@ __global__ void __launch_bounds__(kSortThreads) radix_scatter(const float* delta
         if (e < n) load_item<FIRST>(delta, keys_in, vals_in, e, key[i], val[i]);
     }
     tile_sort_step(sh, key, val, tile_count, shift);
-    sh.dest_off[threadIdx.x] = hist[(long)threadIdx.x * tiles + tile] - sh.tile_excl[threadIdx.x];   // kSortThreads == kRadix
+    {
+        const unsigned first_dest = hist[(long)threadIdx.x * tiles + tile];                  // kSortThreads == kRadix
+        sh.dest_off[threadIdx.x] = first_dest - sh.tile_excl[threadIdx.x];
+        if (LAST) {
+            // Caps do not decrease with the rank: the exact cap of the first rank this tile reaches
+            // with digit d is a lower bound for all its elements of that digit, and most elements are
+            // settled by one comparison with it.
+            const double r = rank_percent((double)first_dest + 1.0, stab.n);
+            const CapSeg s = stab.seg[segment_of(r)];
+            run_cap[threadIdx.x] = (long)first_dest < n ? fmax(s.head, cap_in_segment(s, r)) : 0.0;
+        }
+    }
     __syncthreads();
     for (int j = threadIdx.x; j < tile_count; j += kSortThreads) {
         const unsigned k = sh.skey[j], v = sh.sval[j];
@@ -438,7 +457,8 @@ __global__ void __launch_bounds__(kSortThreads) radix_scatter(const float* delta
             keys_out[dest] = k;
             vals_out[dest] = v;
         } else {
-            cap_and_store<false>(*tab, dest, k, v, n, out);     // dest is the 0-based rank
+            if ((double)__uint_as_float(k) <= run_cap[d]) continue;
+            cap_and_store<false>(stab, dest, k, v, n, out);     // dest is the 0-based rank
         }
     }
 }
