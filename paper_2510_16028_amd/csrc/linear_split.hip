@@ -160,12 +160,12 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
     };
 
     double S[2][16];
-    floatx16 X[2], zero;
+    floatx16 X[2], D[2], zero;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         zero[v] = 0.f;
 #pragma unroll
-        for (int tj = 0; tj < 2; ++tj) { S[tj][v] = 0.0; X[tj][v] = 0.f; }
+        for (int tj = 0; tj < 2; ++tj) { S[tj][v] = 0.0; X[tj][v] = 0.f; D[tj][v] = 0.f; }
     }
     // operand fragments: lane (r32, h) holds k = 16 kg + 8 h .. + 7 of its row: unit 2 kg + h, swizzled
     const int swz = (r32 >> 2) & 3;
@@ -175,8 +175,21 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
     auto frag = [&](const char* stage, int off) __attribute__((always_inline)) {
         return *reinterpret_cast<const bf16x8*>(stage + off);
     };
-    // One group (32 k-steps) of both tiles of the wavefront.  The chains of the two tiles
-    // alternate, so that no instruction waits for the one issued just before it.
+    // One group (32 k-steps) of both tiles of the wavefront, in four parts (k half, tile): a part
+    // issues the eight matrix-core instructions of its tile (hi x hi from zero into D, the seven
+    // cross products into the chain X) and, in their shadow, folds into the binary64 sums what the
+    // OTHER tile finished one part earlier: its D always, its chain X where the chain has just ended
+    // (tile 0's ends in the third part, tile 1's in the fourth and is folded in the first part of the
+    // next group).  A matrix-core instruction occupies its pipe for 32 cycles, in which the SIMD
+    // issues up to eight vector instructions; folding a result right after the instruction that
+    // produced it instead stalls the wavefront until that instruction has drained (measured: the loop
+    // runs at the matrix cores' own pace with this order and 19 % slower without).  The scheduling
+    // directives ask for exactly that interleaving: one matrix-core instruction, then 4 or 8 vector
+    // instructions.
+    auto fold = [&](double (&acc)[16], const floatx16& part) __attribute__((always_inline)) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] += (double)part[v];
+    };
     auto compute = [&](const char* stage) __attribute__((always_inline)) {
 #pragma unroll
         for (int kg = 0; kg < 2; ++kg) {
@@ -188,30 +201,28 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
                 b[0][s] = frag(stage, s * kSlab + fragW + unit);
                 b[1][s] = frag(stage, s * kSlab + fragW + 32 * SROW + unit);
             }
-            const floatx16 D0 = TAO_MFMA_BF16(a[0], b[0][0], zero);
-            const floatx16 D1 = TAO_MFMA_BF16(a[0], b[1][0], zero);
-            // the cross products: hi x mid, mid x hi, then the five of the order of 2^-14 and below
-            X[0] = TAO_MFMA_BF16(a[0], b[0][1], kg == 0 ? zero : X[0]);
-            X[1] = TAO_MFMA_BF16(a[0], b[1][1], kg == 0 ? zero : X[1]);
-            X[0] = TAO_MFMA_BF16(a[1], b[0][0], X[0]);
-            X[1] = TAO_MFMA_BF16(a[1], b[1][0], X[1]);
-            X[0] = TAO_MFMA_BF16(a[0], b[0][2], X[0]);
-            X[1] = TAO_MFMA_BF16(a[0], b[1][2], X[1]);
-            X[0] = TAO_MFMA_BF16(a[2], b[0][0], X[0]);
-            X[1] = TAO_MFMA_BF16(a[2], b[1][0], X[1]);
-            X[0] = TAO_MFMA_BF16(a[1], b[0][1], X[0]);
-            X[1] = TAO_MFMA_BF16(a[1], b[1][1], X[1]);
-            X[0] = TAO_MFMA_BF16(a[1], b[0][2], X[0]);
-            X[1] = TAO_MFMA_BF16(a[1], b[1][2], X[1]);
-            X[0] = TAO_MFMA_BF16(a[2], b[0][1], X[0]);
-            X[1] = TAO_MFMA_BF16(a[2], b[1][1], X[1]);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) { S[0][v] += (double)D0[v]; S[1][v] += (double)D1[v]; }
-        }
+            for (int t = 0; t < 2; ++t) {
+                const int o = t ^ 1;
+                const bool chain_ended = (kg == 0) == (t == 0);  // parts (0, 0) and (1, 1)
+                fold(S[o], D[o]);
+                if (chain_ended) fold(S[o], X[o]);
+                D[t] = TAO_MFMA_BF16(a[0], b[t][0], zero);
+                // the cross products: hi x mid, mid x hi, then the five of the order of 2^-14 and below
+                X[t] = TAO_MFMA_BF16(a[0], b[t][1], kg == 0 ? zero : X[t]);
+                X[t] = TAO_MFMA_BF16(a[1], b[t][0], X[t]);
+                X[t] = TAO_MFMA_BF16(a[0], b[t][2], X[t]);
+                X[t] = TAO_MFMA_BF16(a[2], b[t][0], X[t]);
+                X[t] = TAO_MFMA_BF16(a[1], b[t][1], X[t]);
+                X[t] = TAO_MFMA_BF16(a[1], b[t][2], X[t]);
+                X[t] = TAO_MFMA_BF16(a[2], b[t][1], X[t]);
 #pragma unroll
-        for (int tj = 0; tj < 2; ++tj) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) S[tj][v] += (double)X[tj][v];
+                for (int q = 0; q < 8; ++q) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                     // one MFMA
+                    if (chain_ended) __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);    // vector ALU
+                    else             __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                }
+            }
         }
     };
 
@@ -236,6 +247,8 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
         __syncthreads();
         compute(lds + cur * kSplitStage);
     }
+    fold(S[1], D[1]);                                        // what the last part left unfolded
+    fold(S[1], X[1]);
 
     // epilogue: D[i][j] of a 32x32 tile sits in lane (j + 32*((i/4)%2)), register 4*(i/8) + i%4
     float* __restrict__ T = p.tau + z * p.strideT;
