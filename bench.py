@@ -54,7 +54,7 @@ _STREAM_BYTES = {"softmax": 12, "layernorm": 12, "rmsnorm": 12, "bn_affine": 12,
 class PlannedOp:
     """One operator with every buffer preallocated; run() only enqueues kernels."""
 
-    def __init__(self, tao, torch, op, use_split=True):
+    def __init__(self, tao, torch, op, use_split=True, use_fused=True):
         self.tao, self.op, self.kind, self.name = tao, op, op.kind, op.name
         self.claimed = op.claimed.contiguous()
         self.y_ref = op.y_ref.contiguous()
@@ -63,6 +63,7 @@ class PlannedOp:
         self.n = self.y_ref.numel()
         a = op.args
         self.split = False
+        self.fused = False
         if self.kind == "linear":
             A, W = a["A"], a["W"]
             K = A.shape[-1]
@@ -72,10 +73,13 @@ class PlannedOp:
             M, N = self.y_ref.shape[-2], self.y_ref.shape[-1]
             # the library's own rule picks the BF16-split or the FP32 matrix-core path per shape
             self.split = use_split and tao.tao_linear_split_preferred(M, N, K, batch)
+            # ... and there the check runs in the matrix kernel's epilogue (tau is never stored)
+            self.fused = self.split and use_fused
             if self.split:
                 shared = W.dim() == 2 or batch == 1
-                self.ws = torch.empty(tao.tao_linear_split_workspace_bytes(M, N, K, batch, shared),
-                                      dtype=torch.uint8, device=A.device)
+                need = (tao.tao_bound_check_linear_workspace_bytes if self.fused
+                        else tao.tao_linear_split_workspace_bytes)(M, N, K, batch, shared)
+                self.ws = torch.empty(need, dtype=torch.uint8, device=A.device)
         else:
             self.flops = 0.0
             self.min_bytes = 0.0
@@ -103,7 +107,21 @@ class PlannedOp:
     def check(self):
         self.tao.tao_check_and_profile(self.claimed, self.y_ref, self.tau, out=self.prof, readback=False)
 
+    def bound_and_check(self):
+        a, op = self.op.args, self.op
+        self.tao.tao_bound_check_linear(a["A"], a["W"], a.get("bias"), self.y_ref, self.claimed,
+                                        trans_w=bool(op.attrs.get("trans_w", 0)), out=self.prof, ws=self.ws,
+                                        readback=False)
+
     def run(self, torch, record):
+        if self.fused:
+            if record:
+                e = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                e[0].record(); self.bound_and_check(); e[1].record()
+                self.bound_events.append((e[0], e[1]))
+            else:
+                self.bound_and_check()
+            return
         if record:
             e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
             e[0].record(); self.bound(); e[1].record(); self.check(); e[2].record()
@@ -201,6 +219,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stress", action="store_true", help="skip the 8192^3 / 67M-element side measurements")
     ap.add_argument("--fp32-only", action="store_true", help="matmul bounds on the FP32 matrix cores only (no BF16-split path)")
+    ap.add_argument("--no-fused-check", action="store_true",
+                    help="store tau and run the streaming check after the BF16-split matmul bound as well "
+                         "(default: its epilogue checks the bound in registers)")
     ap.add_argument("--projection-elems", type=int, default=0,
                     help="only time the two projections of Sec. 4.4 on this many synthetic elements and exit "
                          "(side measurement; used for the committed kernel trace)")
@@ -225,7 +246,7 @@ def main():
         return
 
     ops = tao_inputs.config3(dev, scale=args.scale)
-    plan = [PlannedOp(tao, torch, op, use_split=not args.fp32_only) for op in ops]
+    plan = [PlannedOp(tao, torch, op, use_split=not args.fp32_only, use_fused=not args.no_fused_check) for op in ops]
     torch.cuda.synchronize()
 
     for _ in range(args.warmup):
@@ -262,6 +283,7 @@ def main():
             paths[nm] = {"ops": [p.name for p in sel], "TFLOP/s": fl / (ms * 1e-3) / 1e12,
                          "issued_TFLOP/s": mult * fl / (ms * 1e-3) / 1e12, "issued_frac_of_own_peak": mult * fl / (ms * 1e-3) / 1e12 / peak}
     roofline = {"bound": "mfma", "kernel": "absgemm_split + absgemm_bound" if sp else "absgemm_bound",
+                "check_in_epilogue": [p.name for p in lin if p.fused],
                 "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "paths": paths,
                 "traffic": measured_traffic("absgemm" if sp else "absgemm_bound") if args.scale == 1 else None,
@@ -285,7 +307,7 @@ def main():
     for p in lin:
         ms = sum(_ms(p.bound_events)) / len(p.bound_events)
         kernels["linear_" + p.name] = {"shape": list(p.op.args["A"].shape) + [p.op.y_ref.shape[-1]],
-                                       "path": "bf16_split" if p.split else "fp32",
+                                       "path": ("bf16_split+check" if p.fused else "bf16_split") if p.split else "fp32",
                                        "TFLOP/s": p.flops / (ms * 1e-3) / 1e12, "ms": ms}
 
     if not args.no_stress:

@@ -145,6 +145,23 @@ size_t tao_linear_split_workspace_bytes(long M, long N, long K, long batch, int 
 /* 1 when the BF16 path is expected to be the faster one for this shape on the current device
  * (enough 128 x 128 tiles to fill it, both output extents at least 256), else 0.  Host only. */
 int tao_linear_split_preferred(long M, long N, long K, long batch);
+/* The bound of tao_bound_linear_split checked on the spot (Sec. 5.4 leaf check, Sec. 5.3 profile):
+ * *out receives exactly what tao_check_and_profile(claimed, y_ref, tau, ...) would return for the
+ * tau that tao_bound_linear_split computes from the same operands, but tau is compared in registers
+ * in the matrix kernel's epilogue and only stored when `tau` is not NULL (layout ldy / strideY, like
+ * y_ref and claimed: M x N per batch entry, ldy >= N).
+ * y_ref: the verifier's re-executed output, claimed: the proposer's.  out: DEVICE, fully overwritten,
+ * valid once the stream has drained.  ws / ws_bytes: DEVICE scratch of at least
+ * tao_bound_check_linear_workspace_bytes(...), 256-byte aligned.  Runs the BF16-split kernel for every
+ * shape (tao_linear_split_preferred tells where that is the faster one).  Errors as for
+ * tao_bound_linear_split and tao_check_and_profile; TAO_ERR_SHAPE also for M N batch >= 2^36. */
+int tao_bound_check_linear(const float *A, const float *W, const float *bias, const float *y_ref,
+                           const float *claimed, float *tau,
+                           long M, long N, long K, long lda, long ldw, long ldy, int trans_w,
+                           long batch, long strideA, long strideW, long strideY,
+                           double alpha, double eps_rel, const tao_fp_model *model, tao_profile *out,
+                           void *ws, size_t ws_bytes, void *stream);
+size_t tao_bound_check_linear_workspace_bytes(long M, long N, long K, long batch, int shared_w);
 /* Probes v_mfma_f32_32x32x16_bf16 with 3072 seeded non-negative cases and compares every result
  * with the exact integer model the inflation of tao_bound_linear_split rests on.  *report (HOST):
  * bit 0 every case reproduced bit for bit; bit 1 every result from a zero accumulator within

@@ -92,7 +92,8 @@ class TaoError(RuntimeError):
 
 
 EXPORTS = ["tao_default_model", "tao_gamma", "tao_bound_linear", "tao_bound_linear_split",
-           "tao_linear_split_workspace_bytes", "tao_linear_split_preferred", "tao_selftest_matrix_core_bf16", "tao_bound_conv2d", "tao_bound_softmax",
+           "tao_linear_split_workspace_bytes", "tao_linear_split_preferred",
+           "tao_bound_check_linear", "tao_bound_check_linear_workspace_bytes", "tao_selftest_matrix_core_bf16", "tao_bound_conv2d", "tao_bound_softmax",
            "tao_bound_norm", "tao_bound_groupnorm", "tao_groupnorm_workspace_bytes", "tao_bound_act", "tao_bound_rope", "tao_check_and_profile",
            "tao_check_workspace_bytes", "tao_bound_check_softmax", "tao_profile_errors", "tao_profile_workspace_bytes",
            "tao_calibrate_thresholds", "tao_project_clip", "tao_project_empirical", "tao_project_workspace_bytes",
@@ -123,6 +124,10 @@ def lib():
                                    lg, lg, lg, lg, mp, vp]
     L.tao_bound_linear_split.argtypes = [vp, vp, vp, vp, lg, lg, lg, lg, lg, lg, ctypes.c_int,
                                          lg, lg, lg, lg, mp, vp, ctypes.c_size_t, vp]
+    L.tao_bound_check_linear.argtypes = [vp, vp, vp, vp, vp, vp, lg, lg, lg, lg, lg, lg, ctypes.c_int,
+                                         lg, lg, lg, lg, dbl, dbl, mp, vp, vp, ctypes.c_size_t, vp]
+    L.tao_bound_check_linear_workspace_bytes.argtypes = [lg, lg, lg, lg, ctypes.c_int]
+    L.tao_bound_check_linear_workspace_bytes.restype = ctypes.c_size_t
     L.tao_linear_split_workspace_bytes.argtypes = [lg, lg, lg, lg, ctypes.c_int]
     L.tao_linear_split_workspace_bytes.restype = ctypes.c_size_t
     L.tao_linear_split_preferred.argtypes = [lg, lg, lg, lg]
@@ -282,6 +287,38 @@ def tao_bound_linear_split(A, W, bias=None, trans_w=False, model=None, out=None,
                                       _ptr(ws), ws.numel(), _stream())
     _check(rc, "tao_bound_linear_split")
     return out
+
+
+def tao_bound_check_linear_workspace_bytes(M, N, K, batch=1, shared_w=True):
+    return int(lib().tao_bound_check_linear_workspace_bytes(int(M), int(N), int(K), int(batch), int(bool(shared_w))))
+
+
+def tao_bound_check_linear(A, W, bias, y_ref, claimed, trans_w=False, alpha=1.0, eps_rel=1e-12, model=None,
+                           tau_out=None, out=None, ws=None, readback=True):
+    """The matmul bound of tao_bound_linear_split checked in the kernel's epilogue against
+    `claimed` and `y_ref` (contiguous, shaped like the product); tau is stored only into `tau_out`
+    if given.  Returns the profile dict (readback=True) or the device buffer."""
+    torch = _torch()
+    y_ref = _dev(y_ref, "y_ref"); claimed = _dev(claimed, "claimed")
+    if tau_out is None:
+        # shape checks of A, W, bias against the product's shape, without allocating tau
+        A, W, bias, _, dims = _linear_args(A, W, bias, trans_w, y_ref)
+    else:
+        A, W, bias, tau_out, dims = _linear_args(A, W, bias, trans_w, tau_out)
+    M, N, K, batch, sW = dims[0], dims[1], dims[2], dims[7], dims[9]
+    shape = (batch, M, N) if A.dim() == 3 else (M, N)
+    for t, nm in ((y_ref, "y_ref"), (claimed, "claimed")):
+        if tuple(t.shape) != shape or not t.is_contiguous():
+            raise ValueError("%s must be a contiguous tensor of shape %s" % (nm, shape))
+    if out is None:
+        out = new_profile_buffer(A.device)
+    if ws is None:
+        ws = _scratch(A.device, tao_bound_check_linear_workspace_bytes(M, N, K, batch, sW == 0 or batch == 1))
+    rc = lib().tao_bound_check_linear(_ptr(A), _ptr(W), _ptr(bias), _ptr(y_ref), _ptr(claimed), _ptr(tau_out),
+                                      *dims, float(alpha), float(eps_rel), _mref(model), _ptr(out),
+                                      _ptr(ws), ws.numel(), _stream())
+    _check(rc, "tao_bound_check_linear")
+    return read_profile(out) if readback else out
 
 
 def _pair(v, name):

@@ -31,6 +31,7 @@
 #include <type_traits>
 #include "tao_device.hpp"
 #include "tao_host.hpp"
+#include "tao_check.hpp"
 
 namespace tao {
 
@@ -121,10 +122,50 @@ struct SplitArgs {
     long batchA3, batchW3;            // elements between batch entries (0 for a shared W)
     unsigned tiles_n, tiles_m;
     double c, infl, uflow;
+    // CHECK instantiation: the claimed and the re-executed output (layout ldy / strideY), the check's
+    // parameters and the partial results of the leaf check in the caller's workspace
+    const float* claimed; const float* ref;
+    long ldy, strideY;
+    double alpha, eps_rel;
+    unsigned int* ws_hist; unsigned int* ws_coarse; BlockStats* ws_stats;
 };
 
+// check_one with the histogram layout of the CHECK instantiation below (16-bit counters, bin b in
+// half b & 1 of word (b >> 1) * 4 + copy).
+__device__ __forceinline__ void check_one_packed(float c, float r, float t, double alpha, double eps_rel,
+                                                 unsigned int* hist, int copy, ThreadAcc& acc) {
+    const double cd = (double)c, rd = (double)r;
+    const double d = fabs(cd - rd);
+    const double T = alpha * (double)t;
+    acc.violations += !(d <= T);
+    const double den = fabs(rd) + eps_rel;
+    const double e = d / den;
+    const float e32 = (float)e;
+    bool isn;
+    const unsigned int bin = error_bin(e32, isn);
+    acc.nans += isn;
+    if (!isn) acc.max_bits = max(acc.max_bits, __float_as_uint(e32));
+    atomicAdd(&hist[(bin >> 1) * 4 + copy], (bin & 1) ? 0x10000u : 1u);
+}
+
+// CHECK: the epilogue also runs the leaf check of Sec. 5.4 and the relative-error profile of Sec. 5.3
+// on every bound it has just formed (the binary32 value the plain instantiation would store), against
+// `claimed` and `ref`, with a 2048-bin histogram in the 16 KB of LDS the three stages leave free; tau
+// itself is stored only if p.tau is not NULL.  Workgroups add their counts to one of kMaxCheckBlocks
+// partial results (integer atomics: the sums do not depend on the order), which profile_reduce
+// finishes as it does for the streaming check.
+template <bool CHECK>
 __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
+    // CHECK: four copies of the 2048-bin histogram with 16-bit counters (a tile has 16384 elements, so
+    // none overflows), two bins to a word and the four copies of a word in consecutive banks: 16 KB,
+    // all the LDS the stages leave.  The copy is chosen by the lane; errors crowd into a few bins, and
+    // a single copy serialised the workgroup's atomics.
+    __shared__ unsigned int chk_hist[CHECK ? kBins * 2 : 1];
+    if (CHECK) {
+        for (int i = threadIdx.x; i < kBins * 2; i += kSplitThreads) chk_hist[i] = 0;
+        __syncthreads();
+    }
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;                 // 4 x 2 wavefronts, two 32x32 tiles each (along N)
     const int r32 = lane & 31, h = lane >> 5;
@@ -242,16 +283,39 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
         compute(lds + cur * kSplitStage);
         cur = cur == 2 ? 0 : cur + 1;
     }
+    // CHECK: the tile's claimed and re-executed values, requested before the last group so that their
+    // latency passes under its arithmetic.  Element (tj, v) of a lane: row m0 + wm*32 + 8*(v/4) + 4*h + v%4,
+    // column n0 + wn*64 + tj*32 + r32 (the accumulator layout of a 32x32 tile).
+    const float* __restrict__ Cl = CHECK ? p.claimed + z * p.strideY : nullptr;
+    const float* __restrict__ Rf = CHECK ? p.ref + z * p.strideY : nullptr;
+    float pc[CHECK ? 2 : 1][CHECK ? 16 : 1], pr[CHECK ? 2 : 1][CHECK ? 16 : 1];
+    auto prefetch_claims = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int tj = 0; tj < 2; ++tj) {
+            const long col = n0 + wn * 64 + tj * 32 + r32;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const long row = m0 + wm * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+                const bool in = row < p.M && col < p.N;
+                pc[tj][v] = in ? Cl[row * p.ldy + col] : 0.f;
+                pr[tj][v] = in ? Rf[row * p.ldy + col] : 0.f;
+            }
+        }
+    };
     if (ngroup > 0) {
         __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0)
         __syncthreads();
+        if (CHECK) prefetch_claims();
         compute(lds + cur * kSplitStage);
+    } else if (CHECK) {
+        prefetch_claims();
     }
     fold(S[1], D[1]);                                        // what the last part left unfolded
     fold(S[1], X[1]);
 
     // epilogue: D[i][j] of a 32x32 tile sits in lane (j + 32*((i/4)%2)), register 4*(i/8) + i%4
-    float* __restrict__ T = p.tau + z * p.strideT;
+    float* __restrict__ T = p.tau ? p.tau + z * p.strideT : nullptr;
+    ThreadAcc acc;
 #pragma unroll
     for (int tj = 0; tj < 2; ++tj) {
         const long col = n0 + wn * 64 + tj * 32 + r32;
@@ -262,10 +326,48 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
             if (row < p.M && col < p.N) {
                 const double sv = S[tj][v];
                 const double tt = p.c * (sv * p.infl + ab) * kGuard + p.uflow;
-                T[row * p.ldt + col] = up32(tt);
+                const float t32 = up32(tt);
+                if (!CHECK) {
+                    T[row * p.ldt + col] = t32;
+                } else {
+                    if (T) T[row * p.ldt + col] = t32;
+                    check_one_packed(pc[tj][v], pr[tj][v], t32, p.alpha, p.eps_rel, chk_hist, lane & 3, acc);
+                }
             }
         }
     }
+    if (CHECK) {
+        __syncthreads();
+        const unsigned slot = blockIdx.x % (unsigned)kMaxCheckBlocks;
+        // non-empty bins to the slot's partial histogram; a wavefront covers one group of 64 bins
+        for (int b = tid; b < kBins; b += kSplitThreads) {
+            unsigned int cnt = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) cnt += (chk_hist[(b >> 1) * 4 + c] >> (16 * (b & 1))) & 0xffffu;
+            if (cnt) atomicAdd(&p.ws_hist[(size_t)slot * kBins + b], cnt);
+            unsigned int gsum = cnt;
+#pragma unroll
+            for (int o = kWave / 2; o > 0; o >>= 1) gsum += __shfl_xor(gsum, o, kWave);
+            if (lane == 0 && gsum) atomicAdd(&p.ws_coarse[slot * kGroups + b / kBinsPerReduceBlock], gsum);
+        }
+        unsigned int vio = acc.violations, nn = acc.nans, mx = acc.max_bits;
+#pragma unroll
+        for (int o = kWave / 2; o > 0; o >>= 1) {
+            vio += __shfl_xor(vio, o, kWave);
+            nn += __shfl_xor(nn, o, kWave);
+            mx = max(mx, (unsigned int)__shfl_xor(mx, o, kWave));
+        }
+        if (lane == 0) {
+            BlockStats* st = p.ws_stats + slot;
+            if (vio) atomicAdd(&st->violations, (unsigned long long)vio);
+            if (nn) atomicAdd(&st->nans, (unsigned long long)nn);
+            if (mx) atomicMax(&st->max_bits, mx);
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void zero_words(unsigned int* __restrict__ p, long n) {
+    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (long)gridDim.x * blockDim.x) p[i] = 0;
 }
 
 // ---- instruction self test ------------------------------------------------------------------
@@ -407,24 +509,57 @@ int tao_linear_split_preferred(long M, long N, long K, long batch) {
     return tiles >= cus && M >= 2 * tao::STILE && N >= 2 * tao::STILE && K >= 64;
 }
 
-int tao_bound_linear_split(const float* A, const float* W, const float* bias, float* tau,
-                           long M, long N, long K, long lda, long ldw, long ldt, int trans_w,
-                           long batch, long strideA, long strideW, long strideT,
-                           const tao_fp_model* model, void* ws, size_t ws_bytes, void* stream) {
-    using namespace tao;
+}  // extern "C"
+
+namespace tao {
+inline size_t round_up_256(size_t b) { return (b + 255) / 256 * 256; }
+// The fused check: NULL for the plain bound.
+struct SplitCheckHost {
+    const float* claimed; const float* ref; long ldy, strideY; double alpha, eps_rel; tao_profile* out;
+};
+
+static int split_run(const float* A, const float* W, const float* bias, float* tau,
+                     long M, long N, long K, long lda, long ldw, long ldt, int trans_w,
+                     long batch, long strideA, long strideW, long strideT,
+                     const tao_fp_model* model, void* ws, size_t ws_bytes, void* stream, const SplitCheckHost* chk) {
     tao_fp_model md;
     int rc = resolve_model(model, &md);
     if (rc != TAO_OK) return rc;
     if (M < 0 || N < 0 || K < 0 || batch < 0) return TAO_ERR_SHAPE;
-    if (lda < K || ldt < N || ldw < (trans_w ? N : K)) return TAO_ERR_SHAPE;
-    if (strideA < 0 || strideW < 0 || strideT < 0) return TAO_ERR_SHAPE;
-    if (batch > 1 && strideT < M * ldt - (ldt - N)) return TAO_ERR_SHAPE;   // outputs would overlap
+    if (lda < K || ldw < (trans_w ? N : K)) return TAO_ERR_SHAPE;
+    if (strideA < 0 || strideW < 0) return TAO_ERR_SHAPE;
+    if (tau || !chk) {
+        if (ldt < N || strideT < 0) return TAO_ERR_SHAPE;
+        if (batch > 1 && strideT < M * ldt - (ldt - N)) return TAO_ERR_SHAPE;   // outputs would overlap
+    }
     const long Kp_ = K + (bias ? 1 : 0);
     const double c = gamma_up(Kp_, md);
     if (!(c == c)) return TAO_ERR_K_RANGE;
-    if (M == 0 || N == 0 || batch == 0) return TAO_OK;
-    if (!tau || (K > 0 && (!A || !W))) return TAO_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    const size_t need_split = K > 0 ? round_up_256(tao_linear_split_workspace_bytes(M, N, K, batch,
+                                                   ((strideW == 0) || batch == 1) ? 1 : 0)) : 0;
+    CheckWorkspace cw = {};
+    if (chk) {
+        if (!chk->out) return TAO_ERR_NULL;
+        if (!aligned(chk->out, 8)) return TAO_ERR_ALIGN;
+        if (chk->ldy < N || chk->strideY < 0 || !(chk->alpha >= 0.0) || !std::isfinite(chk->alpha) ||
+            !(chk->eps_rel >= 0.0) || !std::isfinite(chk->eps_rel)) return TAO_ERR_SHAPE;
+        if ((__int128)M * N * batch >= ((__int128)1 << 36)) return TAO_ERR_SHAPE;   // 32-bit partial counters
+        if (!ws || !aligned(ws, 256) || ws_bytes < need_split + check_workspace_bytes()) return TAO_ERR_WORKSPACE;
+        cw = carve_check_workspace(static_cast<char*>(ws) + need_split);
+    }
+    if (M == 0 || N == 0 || batch == 0) {
+        if (chk) {                                           // the profile of an empty tensor
+            hipLaunchKernelGGL(zero_words, dim3(8), dim3(256), 0, st, cw.hist, (long)(check_workspace_bytes() / 4));
+            launch_profile_reduce(cw, 1, 0ull, chk->out, st);
+            return launch_status();
+        }
+        return TAO_OK;
+    }
+    if ((!chk && !tau) || (K > 0 && (!A || !W))) return TAO_ERR_NULL;
+    if (chk && (!chk->claimed || !chk->ref)) return TAO_ERR_NULL;
     if (!aligned(A, 4) || !aligned(W, 4) || !aligned(bias, 4) || !aligned(tau, 4)) return TAO_ERR_ALIGN;
+    if (chk && (!aligned(chk->claimed, 4) || !aligned(chk->ref, 4))) return TAO_ERR_ALIGN;
     const long Kp = (K + SBK - 1) / SBK * SBK;
     const bool shared_w = (strideW == 0) || batch == 1;
     // descriptor ranges (128 rows of a plane) and the per-thread offsets must fit 32 bits
@@ -434,7 +569,6 @@ int tao_bound_linear_split(const float* A, const float* W, const float* bias, fl
     const long tiles_n = (N + STILE - 1) / STILE, tiles_m = (M + STILE - 1) / STILE;
     const long ntiles = tiles_n * tiles_m * batch;
     if (ntiles >= (1L << 31)) return TAO_ERR_SHAPE;
-    hipStream_t st = (hipStream_t)stream;
 
     unsigned short* A3 = static_cast<unsigned short*>(ws);
     const long blocksA = (M + STILE - 1) / STILE, blocksW = (N + STILE - 1) / STILE;
@@ -476,13 +610,56 @@ int tao_bound_linear_split(const float* A, const float* W, const float* bias, fl
     static bool configured = false;
     constexpr int lds_bytes = kSplitStages * kSplitStage;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split<false>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split<true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) { g_last_hip_error = (int)e; return TAO_ERR_LAUNCH; }
         configured = true;
     }
-    hipLaunchKernelGGL(absgemm_split, dim3((unsigned)ntiles), dim3(kSplitThreads), lds_bytes, st, p);
+    p.claimed = nullptr; p.ref = nullptr; p.ldy = 0; p.strideY = 0; p.alpha = 0.0; p.eps_rel = 0.0;
+    p.ws_hist = nullptr; p.ws_coarse = nullptr; p.ws_stats = nullptr;
+    if (!chk) {
+        hipLaunchKernelGGL(absgemm_split<false>, dim3((unsigned)ntiles), dim3(kSplitThreads), lds_bytes, st, p);
+        return launch_status();
+    }
+    p.claimed = chk->claimed; p.ref = chk->ref; p.ldy = chk->ldy; p.strideY = chk->strideY;
+    p.alpha = chk->alpha; p.eps_rel = chk->eps_rel;
+    p.ws_hist = cw.hist; p.ws_coarse = cw.coarse; p.ws_stats = cw.stats;
+    const int slots = (int)(ntiles < kMaxCheckBlocks ? ntiles : kMaxCheckBlocks);
+    hipLaunchKernelGGL(zero_words, dim3(64), dim3(256), 0, st, cw.hist, (long)(check_workspace_bytes() / 4));
+    hipLaunchKernelGGL(absgemm_split<true>, dim3((unsigned)ntiles), dim3(kSplitThreads), lds_bytes, st, p);
+    launch_profile_reduce(cw, slots, (unsigned long long)((__int128)M * N * batch), chk->out, st);
     return launch_status();
+}
+}  // namespace tao
+
+extern "C" {
+
+int tao_bound_linear_split(const float* A, const float* W, const float* bias, float* tau,
+                           long M, long N, long K, long lda, long ldw, long ldt, int trans_w,
+                           long batch, long strideA, long strideW, long strideT,
+                           const tao_fp_model* model, void* ws, size_t ws_bytes, void* stream) {
+    return tao::split_run(A, W, bias, tau, M, N, K, lda, ldw, ldt, trans_w, batch, strideA, strideW, strideT,
+                          model, ws, ws_bytes, stream, nullptr);
+}
+
+size_t tao_bound_check_linear_workspace_bytes(long M, long N, long K, long batch, int shared_w) {
+    const size_t split = K > 0 ? tao_linear_split_workspace_bytes(M, N, K, batch, shared_w) : 0;
+    if (K > 0 && split == 0) return 0;
+    return tao::round_up_256(split) + tao::check_workspace_bytes();
+}
+
+int tao_bound_check_linear(const float* A, const float* W, const float* bias, const float* y_ref,
+                           const float* claimed, float* tau,
+                           long M, long N, long K, long lda, long ldw, long ldy, int trans_w,
+                           long batch, long strideA, long strideW, long strideY,
+                           double alpha, double eps_rel, const tao_fp_model* model, tao_profile* out,
+                           void* ws, size_t ws_bytes, void* stream) {
+    tao::SplitCheckHost chk = {claimed, y_ref, ldy, strideY, alpha, eps_rel, out};
+    return tao::split_run(A, W, bias, tau, M, N, K, lda, ldw, ldy, trans_w, batch, strideA, strideW, strideY,
+                          model, ws, ws_bytes, stream, &chk);
 }
 
 }  // extern "C"

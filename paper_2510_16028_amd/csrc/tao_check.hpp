@@ -23,6 +23,8 @@ struct ThreadAcc {
     unsigned int violations = 0, nans = 0, max_bits = 0;
 };
 
+// R: copies of every bin in the LDS histogram `hist` (copy `rep` is used).
+template <int R = kReplicas>
 __device__ __forceinline__ void check_one(float c, float r, float t, double alpha, double eps_rel,
                                           unsigned int* hist, int rep, ThreadAcc& acc) {
     const double cd = (double)c, rd = (double)r;
@@ -37,7 +39,7 @@ __device__ __forceinline__ void check_one(float c, float r, float t, double alph
     const unsigned int bits = __float_as_uint(e32);
     acc.nans += isn;
     if (!isn) acc.max_bits = max(acc.max_bits, bits);
-    atomicAdd(&hist[bin * kReplicas + rep], 1u);
+    atomicAdd(&hist[bin * R + rep], 1u);
 }
 
 // Workgroup totals of the per-thread counters (kCheckThreads threads) into ws_stats[blockIdx.x];

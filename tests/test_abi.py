@@ -129,6 +129,23 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_bound_linear_split(nul, p, nul, p, *args(4, 4, 8, 8, 8, 4), None, big, wsb, None) == tao.ERR_NULL
     assert L.tao_bound_linear_split(p, p, nul, p, *args(4, 4, K, K, K, 4), None, big, wsb, None) == tao.ERR_K_RANGE
     assert L.tao_bound_linear_split(nul, nul, nul, nul, *args(0, 4, 8, 8, 8, 4), None, nul, 0, None) == tao.OK
+    # ... and with the check fused into the epilogue
+    cwb = L.tao_bound_check_linear_workspace_bytes(4, 4, 8, 1, 1)
+    assert cwb == (wsb + 255) // 256 * 256 + L.tao_check_workspace_bytes(16)
+    fc = lambda a, w, y, c, t, dims, alpha, out, wsp, wsn: L.tao_bound_check_linear(a, w, nul, y, c, t, *dims, alpha, 0.0, None, out, wsp, wsn, None)
+    ok = args(4, 4, 8, 8, 8, 4)
+    assert fc(p, p, p, p, nul, args(4, 4, 8, 4, 8, 4), 1.0, p, big, cwb) == tao.ERR_SHAPE        # lda < K
+    assert fc(p, p, p, p, nul, args(4, 4, 8, 8, 8, 2), 1.0, p, big, cwb) == tao.ERR_SHAPE        # ldy < N
+    assert fc(p, p, p, p, nul, ok, -1.0, p, big, cwb) == tao.ERR_SHAPE
+    assert fc(p, p, p, p, nul, ok, 1.0, nul, big, cwb) == tao.ERR_NULL                           # no result buffer
+    assert fc(p, p, nul, p, nul, ok, 1.0, p, big, cwb) == tao.ERR_NULL
+    assert fc(p, p, p, nul, nul, ok, 1.0, p, big, cwb) == tao.ERR_NULL
+    assert fc(nul, p, p, p, nul, ok, 1.0, p, big, cwb) == tao.ERR_NULL
+    assert fc(p, p, odd, p, nul, ok, 1.0, p, big, cwb) == tao.ERR_ALIGN
+    assert fc(p, p, p, p, nul, ok, 1.0, p, nul, cwb) == tao.ERR_WORKSPACE
+    assert fc(p, p, p, p, nul, ok, 1.0, p, big, cwb - 1) == tao.ERR_WORKSPACE
+    assert fc(p, p, p, p, nul, args(4, 4, K, K, K, 4), 1.0, p, big, 1 << 40) == tao.ERR_K_RANGE
+    assert fc(p, p, p, p, nul, args(1 << 18, 1 << 18, 8, 8, 8, 1 << 18), 1.0, p, big, 1 << 50) == tao.ERR_SHAPE   # 2^36 outputs
     # conv2d: (batch, H, W, C, Cout, R, S, stride h/w, pad h/w, dilation h/w)
     cargs = lambda B=1, H=8, W=8, C=4, Co=4, R=3, S=3, sh=1, sw=1, ph=1, pw=1, dh=1, dw=1: \
         (B, H, W, C, Co, R, S, sh, sw, ph, pw, dh, dw)

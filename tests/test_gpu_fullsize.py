@@ -112,6 +112,10 @@ def test_config3_matmuls_through_the_bf16_split_path(tao, oracle_mod):
         tau = tao.tao_bound_linear_split(A, W, op.args.get("bias"), trans_w=bool(op.attrs.get("trans_w", 0)))
         p = tao.tao_check_and_profile(op.claimed.contiguous(), op.y_ref.contiguous(), tau)
         assert p["violations"] == 0 and p["n"] == op.y_ref.numel(), op.name
+        # the same with the check in the matrix kernel's epilogue, as bench.py runs it
+        fused = tao.tao_bound_check_linear(A, W, op.args.get("bias"), op.y_ref.contiguous(), op.claimed.contiguous(),
+                                           trans_w=bool(op.attrs.get("trans_w", 0)))
+        assert_profile_equal(fused, p, op.name + " (check in the epilogue)")
         rows = _sample_rows(M, 5, 700 + idx)
         b = (idx % batch) if A.dim() == 3 else None
         sub = _sub_op(op, rows, b)

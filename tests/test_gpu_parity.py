@@ -399,6 +399,57 @@ def test_softmax_bound_checked_in_one_pass(tao, oracle_mod, rows, cols):
         assert fused["violations"] > 0
 
 
+@pytest.mark.parametrize("M,N,K,bias,trans_w,batch", [
+    (1, 1, 1, False, False, 1), (5, 7, 3, True, False, 1), (128, 128, 32, False, False, 1),
+    (129, 257, 100, True, True, 1), (300, 200, 64, False, False, 3), (64, 640, 0, True, False, 1),
+    (700, 390, 513, True, False, 2), (1024, 1152, 256, False, True, 1),     # 72 tiles: several per slot of the partials
+    (4200, 1100, 96, True, False, 1),                                         # 297 tiles: more tiles than partial results
+    (0, 16, 8, False, False, 1),
+])
+def test_matmul_bound_checked_in_the_epilogue(tao, oracle_mod, M, N, K, bias, trans_w, batch):
+    """tao_bound_check_linear: field for field the profile of tao_bound_linear_split followed by
+    tao_check_and_profile, and of the oracle's check run on the stored bound; the optional tau
+    output is bit-identical to the split path's; planted violations, NaN and infinite claims."""
+    g = torch.Generator().manual_seed(M * 7 + N * 3 + K + batch)
+    A = torch.randn((batch, M, K), generator=g)
+    W = torch.randn((batch, K, N) if trans_w else (batch, N, K), generator=g)
+    b = torch.randn((N,), generator=g) if bias else None
+    if batch == 1:
+        A, W = A[0], W[0]
+    Wnk = W.transpose(-1, -2) if trans_w else W                      # [.., N, K]
+    if K > 0:
+        ref = A @ Wnk.transpose(-1, -2)
+        claimed = tao_inputs.matmul_permuted_k(g, A, Wnk)            # another summation order
+    else:
+        ref = torch.zeros(A.shape[:-1] + (N,))
+        claimed = ref.clone()
+    if b is not None:
+        ref = ref + b; claimed = claimed + b
+    claimed = claimed.contiguous().clone()
+    if M * N > 40:
+        flat = claimed.reshape(-1)
+        flat[3] = flat[3] * 1.01 + 1.0              # planted violation
+        flat[7] = float("nan")
+        flat[11] = float("inf")
+    Ag, Wg, bg = A.cuda(), W.cuda(), None if b is None else b.cuda()
+    rg, cg = ref.cuda().contiguous(), claimed.cuda().contiguous()
+    tau = tao.tao_bound_linear_split(Ag, Wg, bg, trans_w=trans_w)
+    for alpha, eps in ((1.0, 1e-12), (0.5, 1e-6)):
+        fused = tao.tao_bound_check_linear(Ag, Wg, bg, rg, cg, trans_w=trans_w, alpha=alpha, eps_rel=eps)
+        two = tao.tao_check_and_profile(cg, rg, tau, alpha=alpha, eps_rel=eps)
+        assert_profile_equal(fused, two, "epilogue vs two passes %s" % ((M, N, K, batch),))
+        po = oracle_mod.check_and_profile(_np(claimed), _np(ref), _np(tau), alpha=alpha, eps_rel=eps)
+        assert_profile_equal(fused, po, "epilogue vs oracle check %s" % ((M, N, K, batch),))
+        assert fused["n"] == batch * M * N
+    # tau on request: the split path's bits
+    tau2 = torch.full_like(tau, -1.0)
+    again = tao.tao_bound_check_linear(Ag, Wg, bg, rg, cg, trans_w=trans_w, tau_out=tau2)
+    assert bool((tau2.view(torch.int32) == tau.view(torch.int32)).all())
+    assert_profile_equal(again, tao.tao_check_and_profile(cg, rg, tau), "with tau stored")
+    if M * N > 40:
+        assert again["violations"] >= 3 and again["nan_count"] >= 1
+
+
 @pytest.mark.parametrize("N,C,spatial,G,affine", [
     (2, 32, (16, 16), 8, True),       # rows of 1024: cached, one wavefront per row
     (3, 12, (5, 7), 4, True),         # 105 columns: ragged, channel boundaries inside a vector
