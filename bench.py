@@ -51,6 +51,10 @@ _STREAM_BYTES = {"softmax": 12, "layernorm": 12, "rmsnorm": 12, "bn_affine": 12,
                  "silu": 8, "mul": 8, "add": 8, "rope": 8}
 
 
+# the same with the check in the same pass: inputs and the claimed output read once, nothing written
+_FUSED_BYTES = {"softmax": 12, "gelu": 12, "silu": 8, "mul": 8, "add": 8, "relu": 8}
+
+
 class PlannedOp:
     """One operator with every buffer preallocated; run() only enqueues kernels."""
 
@@ -83,6 +87,10 @@ class PlannedOp:
         else:
             self.flops = 0.0
             self.min_bytes = 0.0
+            # element-wise operators and softmax: bound and check in one streaming pass
+            self.fused = use_fused and self.kind in _FUSED_BYTES
+            if self.fused:
+                self.ws = torch.empty(tao.tao_check_workspace_bytes(self.n), dtype=torch.uint8, device=self.y_ref.device)
         self.bound_events, self.check_events = [], []
 
     def bound(self):
@@ -109,6 +117,13 @@ class PlannedOp:
 
     def bound_and_check(self):
         a, op = self.op.args, self.op
+        if self.kind == "softmax":
+            self.tao.tao_bound_check_softmax(a["x"], self.y_ref, self.claimed, out=self.prof, ws=self.ws, readback=False)
+            return
+        if self.kind != "linear":
+            self.tao.tao_bound_check_act(_ACT[self.kind], a.get("x"), self.y_ref, self.claimed, x2=a.get("x2"),
+                                         out=self.prof, ws=self.ws, readback=False)
+            return
         self.tao.tao_bound_check_linear(a["A"], a["W"], a.get("bias"), self.y_ref, self.claimed,
                                         trans_w=bool(op.attrs.get("trans_w", 0)), out=self.prof, ws=self.ws,
                                         readback=False)
@@ -220,8 +235,8 @@ def main():
     ap.add_argument("--no-stress", action="store_true", help="skip the 8192^3 / 67M-element side measurements")
     ap.add_argument("--fp32-only", action="store_true", help="matmul bounds on the FP32 matrix cores only (no BF16-split path)")
     ap.add_argument("--no-fused-check", action="store_true",
-                    help="store tau and run the streaming check after the BF16-split matmul bound as well "
-                         "(default: its epilogue checks the bound in registers)")
+                    help="store every tau and run the streaming check after every bound (default: the BF16-split "
+                         "matmul kernel, the element-wise kernels and softmax check their bound in registers)")
     ap.add_argument("--projection-elems", type=int, default=0,
                     help="only time the two projections of Sec. 4.4 on this many synthetic elements and exit "
                          "(side measurement; used for the committed kernel trace)")
@@ -299,11 +314,15 @@ def main():
                                     "frac_hbm": chk_bytes / (chk_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
                                     "avg_launch_ms": chk_ms / sum(len(p.check_events) for p in plan)}
     for kind in sorted({p.kind for p in plan if p.kind != "linear"}):
-        sel = [p for p in plan if p.kind == kind]
-        ms = sum(sum(_ms(p.bound_events)) for p in sel)
-        by = sum(_STREAM_BYTES[kind] * p.n * len(p.bound_events) for p in sel)
-        kernels["bound_" + kind] = {"GB/s": by / (ms * 1e-3) / 1e9, "frac_hbm": by / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                                    "avg_launch_ms": ms / sum(len(p.bound_events) for p in sel)}
+        for fused in (False, True):
+            sel = [p for p in plan if p.kind == kind and p.fused == fused]
+            if not sel:
+                continue
+            ms = sum(sum(_ms(p.bound_events)) for p in sel)
+            by = sum((_FUSED_BYTES if fused else _STREAM_BYTES)[kind] * p.n * len(p.bound_events) for p in sel)
+            kernels[("bound_check_" if fused else "bound_") + kind] = {
+                "GB/s": by / (ms * 1e-3) / 1e9, "frac_hbm": by / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                "avg_launch_ms": ms / sum(len(p.bound_events) for p in sel)}
     for p in lin:
         ms = sum(_ms(p.bound_events)) / len(p.bound_events)
         kernels["linear_" + p.name] = {"shape": list(p.op.args["A"].shape) + [p.op.y_ref.shape[-1]],

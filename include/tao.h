@@ -287,6 +287,15 @@ int tao_check_and_profile(const float *claimed, const float *ref, const float *t
  * Calls that share a workspace must be ordered on one stream. */
 size_t tao_check_workspace_bytes(long n);
 
+/* tao_bound_act checked on the spot: *out receives exactly what tao_check_and_profile(claimed,
+ * y_ref, tau, ...) returns for the tau of tao_bound_act(kind, x, x2, y_ref, ...), formed in
+ * registers and never stored (Sec. 5.4 leaf check, Sec. 5.3 profile; 8 - 12 bytes per element
+ * instead of 20 - 24).  Arguments as for the two calls; ws / ws_bytes: DEVICE scratch of at least
+ * tao_check_workspace_bytes(n), 256-byte aligned. */
+int tao_bound_check_act(int kind, const float *x, const float *x2, const float *y_ref, const float *claimed,
+                        long n, double alpha, double eps_rel, const tao_fp_model *model, tao_profile *out,
+                        void *ws, size_t ws_bytes, void *stream);
+
 /* Softmax bound and leaf check in one pass (Sec. 3.1 softmax template, Sec. 5.4
  * check, Sec. 5.3 profile): the result is, field by field, that of
  *     tao_bound_softmax(x, y_ref, tau, ...); tao_check_and_profile(claimed, y_ref, tau, ...)

@@ -94,7 +94,7 @@ class TaoError(RuntimeError):
 EXPORTS = ["tao_default_model", "tao_gamma", "tao_bound_linear", "tao_bound_linear_split",
            "tao_linear_split_workspace_bytes", "tao_linear_split_preferred",
            "tao_bound_check_linear", "tao_bound_check_linear_workspace_bytes", "tao_selftest_matrix_core_bf16", "tao_bound_conv2d", "tao_bound_softmax",
-           "tao_bound_norm", "tao_bound_groupnorm", "tao_groupnorm_workspace_bytes", "tao_bound_act", "tao_bound_rope", "tao_check_and_profile",
+           "tao_bound_norm", "tao_bound_groupnorm", "tao_groupnorm_workspace_bytes", "tao_bound_act", "tao_bound_check_act", "tao_bound_rope", "tao_check_and_profile",
            "tao_check_workspace_bytes", "tao_bound_check_softmax", "tao_profile_errors", "tao_profile_workspace_bytes",
            "tao_calibrate_thresholds", "tao_project_clip", "tao_project_empirical", "tao_project_workspace_bytes",
            "tao_selftest_matrix_core", "tao_last_hip_error", "tao_status_string"]
@@ -139,6 +139,7 @@ def lib():
     L.tao_groupnorm_workspace_bytes.argtypes = [lg, lg, lg, lg]
     L.tao_groupnorm_workspace_bytes.restype = ctypes.c_size_t
     L.tao_bound_act.argtypes = [ctypes.c_int, vp, vp, vp, vp, lg, mp, vp]
+    L.tao_bound_check_act.argtypes = [ctypes.c_int, vp, vp, vp, vp, lg, dbl, dbl, mp, vp, vp, ctypes.c_size_t, vp]
     L.tao_bound_rope.argtypes = [vp, vp, vp, vp, lg, lg, lg, lg, ctypes.c_int, mp, vp]
     L.tao_check_and_profile.argtypes = [vp, vp, vp, lg, dbl, dbl, vp, vp, ctypes.c_size_t, vp]
     L.tao_check_workspace_bytes.argtypes = [lg]
@@ -521,6 +522,24 @@ def tao_check_and_profile(claimed, ref, tau, alpha=1.0, eps_rel=1e-12, out=None,
     rc = lib().tao_check_and_profile(_ptr(claimed), _ptr(ref), _ptr(tau), n, float(alpha),
                                      float(eps_rel), _ptr(out), _ptr(ws), ws.numel(), _stream())
     _check(rc, "tao_check_and_profile")
+    return read_profile(out) if readback else out
+
+
+def tao_bound_check_act(kind, x, y_ref, claimed, x2=None, alpha=1.0, eps_rel=1e-12, model=None, out=None,
+                        ws=None, readback=True):
+    """tao_bound_act checked against `claimed` in one pass, tau never stored."""
+    x = _dev(x, "x"); x2 = _dev(x2, "x2"); y_ref = _dev(y_ref, "y_ref"); claimed = _dev(claimed, "claimed")
+    for t, nm in ((x, "x"), (x2, "x2"), (y_ref, "y_ref"), (claimed, "claimed")):
+        if t is not None and (not t.is_contiguous() or t.numel() != y_ref.numel()):
+            raise ValueError("%s must be contiguous and sized like y_ref" % nm)
+    n = y_ref.numel()
+    if out is None:
+        out = new_profile_buffer(y_ref.device)
+    if ws is None:
+        ws = _workspace(y_ref.device, n)
+    rc = lib().tao_bound_check_act(int(kind), _ptr(x), _ptr(x2), _ptr(y_ref), _ptr(claimed), n, float(alpha),
+                                   float(eps_rel), _mref(model), _ptr(out), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "tao_bound_check_act")
     return read_profile(out) if readback else out
 
 

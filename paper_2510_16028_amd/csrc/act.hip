@@ -5,6 +5,7 @@
 // step).  One grid-stride streaming pass with 16-byte loads each; HBM-bound.
 #include "tao_device.hpp"
 #include "tao_host.hpp"
+#include "tao_check.hpp"
 
 namespace tao {
 
@@ -112,6 +113,40 @@ __global__ __launch_bounds__(256) void act_bound(const float* __restrict__ x, co
         tau[i] = act_one<KIND>(NEEDS_X ? x[i] : 0.f, y[i], k);
 }
 
+// The same bound checked on the spot (Sec. 5.4 / 5.3): the structure of the streaming check pass
+// (1024-thread workgroups, one partial histogram each), with tau formed in registers from y (and
+// x) instead of loaded -- 8 or 12 bytes per element where the two passes move 20 or 24.
+template <int KIND>
+__global__ __launch_bounds__(kCheckThreads) void act_check(
+    const float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ claimed, long n, int vec_ok,
+    ActConsts k, double alpha, double eps_rel,
+    unsigned int* __restrict__ ws_hist, unsigned int* __restrict__ ws_coarse, BlockStats* __restrict__ ws_stats) {
+    constexpr bool NEEDS_X = (KIND == TAO_ACT_GELU_ERF || KIND == TAO_ACT_GELU_TANH);
+    __shared__ unsigned int hist[kBins * kReplicas];
+    __shared__ unsigned int red[3 * (kCheckThreads / kWave)];
+    const int tid = threadIdx.x;
+    for (int i = tid; i < kBins * kReplicas; i += kCheckThreads) hist[i] = 0;
+    __syncthreads();
+    ThreadAcc acc;
+    const int rep = tid & (kReplicas - 1);
+    const long nvec = vec_ok ? (n >> 2) : 0;
+    const long stride = (long)gridDim.x * kCheckThreads;
+    for (long i = (long)blockIdx.x * kCheckThreads + tid; i < nvec; i += stride) {
+        float4 X = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (NEEDS_X) X = ntload4(reinterpret_cast<const float4*>(x) + i);
+        const float4 Y = ntload4(reinterpret_cast<const float4*>(y) + i);
+        const float4 C = ntload4(reinterpret_cast<const float4*>(claimed) + i);
+        check_one(C.x, Y.x, act_one<KIND>(X.x, Y.x, k), alpha, eps_rel, hist, rep, acc);
+        check_one(C.y, Y.y, act_one<KIND>(X.y, Y.y, k), alpha, eps_rel, hist, rep, acc);
+        check_one(C.z, Y.z, act_one<KIND>(X.z, Y.z, k), alpha, eps_rel, hist, rep, acc);
+        check_one(C.w, Y.w, act_one<KIND>(X.w, Y.w, k), alpha, eps_rel, hist, rep, acc);
+    }
+    for (long i = (nvec << 2) + (long)blockIdx.x * kCheckThreads + tid; i < n; i += stride)
+        check_one(claimed[i], y[i], act_one<KIND>(NEEDS_X ? x[i] : 0.f, y[i], k), alpha, eps_rel, hist, rep, acc);
+    flush_block_stats(acc, red, ws_stats);
+    flush_histogram(hist, ws_hist + (size_t)blockIdx.x * kBins, ws_coarse + blockIdx.x * kGroups);
+}
+
 // Rotary embedding: one thread per output pair and float4 of a half (pairs (j, j + d/2)) or per
 // float4 of interleaved pairs.  Tables are read through the cache (every head of a position
 // shares a row), activations and bounds stream.
@@ -164,19 +199,13 @@ __global__ __launch_bounds__(256) void rope_bound(const float* __restrict__ x, c
 
 extern "C" {
 
-int tao_bound_act(int kind, const float* x, const float* x2, const float* y_ref, float* tau, long n,
-                  const tao_fp_model* model, void* stream) {
+// Validates kind and model and fills the constants of the element-wise kernels.
+static int act_setup(int kind, const tao_fp_model* model, tao::ActConsts* out) {
     using namespace tao;
-    (void)x2;
     tao_fp_model md;
     int rc = resolve_model(model, &md);
     if (rc != TAO_OK) return rc;
     if (kind < TAO_ACT_GELU_ERF || kind > TAO_ACT_GELU_TANH) return TAO_ERR_KIND;
-    if (n < 0) return TAO_ERR_SHAPE;
-    if (n == 0) return TAO_OK;
-    const bool needs_x = kind == TAO_ACT_GELU_ERF || kind == TAO_ACT_GELU_TANH;
-    if (!y_ref || !tau || (needs_x && !x)) return TAO_ERR_NULL;
-    if (!aligned(x, 4) || !aligned(y_ref, 4) || !aligned(tau, 4)) return TAO_ERR_ALIGN;
     const double u = md.u;
     if (!(md.c_exp * u < 0.5)) return TAO_ERR_MODEL;
     ActConsts k;
@@ -202,6 +231,22 @@ int tao_bound_act(int kind, const float* x, const float* x2, const float* y_ref,
     }
     if (cf >= 0.0 && !(cf * u < 0.5)) return TAO_ERR_MODEL;
     k.scale_f = cf >= 0.0 ? widen(cf * u / (1.0 - cf * u)) : u;
+    *out = k;
+    return TAO_OK;
+}
+
+int tao_bound_act(int kind, const float* x, const float* x2, const float* y_ref, float* tau, long n,
+                  const tao_fp_model* model, void* stream) {
+    using namespace tao;
+    (void)x2;
+    ActConsts k;
+    int rc = act_setup(kind, model, &k);
+    if (rc != TAO_OK) return rc;
+    if (n < 0) return TAO_ERR_SHAPE;
+    if (n == 0) return TAO_OK;
+    const bool needs_x = kind == TAO_ACT_GELU_ERF || kind == TAO_ACT_GELU_TANH;
+    if (!y_ref || !tau || (needs_x && !x)) return TAO_ERR_NULL;
+    if (!aligned(x, 4) || !aligned(y_ref, 4) || !aligned(tau, 4)) return TAO_ERR_ALIGN;
     const int vec_ok = aligned(y_ref, 16) && aligned(tau, 16) && (!needs_x || aligned(x, 16));
     // up to 64 workgroups of 256 threads per CU, grid-stride beyond that (sweeping 2 .. 128 per
     // CU at 8 M .. 100 M elements: the kernels with more arithmetic keep gaining up to 32 - 64)
@@ -220,6 +265,41 @@ int tao_bound_act(int kind, const float* x, const float* x2, const float* y_ref,
         default:        // MUL, ADD, SUB, SQRT and the library functions
             hipLaunchKernelGGL(act_bound<kKindScale>, grid, blk, 0, st, x, y_ref, tau, n, vec_ok, k); break;
     }
+    return launch_status();
+}
+
+int tao_bound_check_act(int kind, const float* x, const float* x2, const float* y_ref, const float* claimed,
+                        long n, double alpha, double eps_rel, const tao_fp_model* model, tao_profile* out,
+                        void* ws, size_t ws_bytes, void* stream) {
+    using namespace tao;
+    (void)x2;
+    ActConsts k;
+    int rc = act_setup(kind, model, &k);
+    if (rc != TAO_OK) return rc;
+    if (!out || !ws) return out ? TAO_ERR_WORKSPACE : TAO_ERR_NULL;
+    if (n < 0 || n >= (1L << 36) || !(alpha >= 0.0) || !std::isfinite(alpha) || !(eps_rel >= 0.0) || !std::isfinite(eps_rel))
+        return TAO_ERR_SHAPE;
+    const bool needs_x = kind == TAO_ACT_GELU_ERF || kind == TAO_ACT_GELU_TANH;
+    if (n > 0 && (!y_ref || !claimed || (needs_x && !x))) return TAO_ERR_NULL;
+    if (!aligned(x, 4) || !aligned(y_ref, 4) || !aligned(claimed, 4) || !aligned(out, 8)) return TAO_ERR_ALIGN;
+    if (!aligned(ws, 256) || ws_bytes < check_workspace_bytes()) return TAO_ERR_WORKSPACE;
+    const int vec_ok = aligned(y_ref, 16) && aligned(claimed, 16) && (!needs_x || aligned(x, 16));
+    long want = (n + (long)kCheckThreads * 16 - 1) / ((long)kCheckThreads * 16);
+    const int nblocks = (int)(want < 1 ? 1 : (want > kMaxCheckBlocks ? kMaxCheckBlocks : want));
+    const CheckWorkspace w = carve_check_workspace(ws);
+    hipStream_t st = (hipStream_t)stream;
+    dim3 grid((unsigned)nblocks), blk(kCheckThreads);
+#define TAO_ACT_CHECK(K) hipLaunchKernelGGL(act_check<K>, grid, blk, 0, st, x, y_ref, claimed, n, vec_ok, k, alpha, eps_rel, \
+                                            w.hist, w.coarse, w.stats)
+    switch (kind) {
+        case TAO_ACT_GELU_ERF: TAO_ACT_CHECK(TAO_ACT_GELU_ERF); break;
+        case TAO_ACT_GELU_TANH: TAO_ACT_CHECK(TAO_ACT_GELU_TANH); break;
+        case TAO_ACT_SILU: case TAO_ACT_SIGMOID: TAO_ACT_CHECK(TAO_ACT_SILU); break;
+        case TAO_ACT_RELU: case TAO_ACT_EXACT: TAO_ACT_CHECK(TAO_ACT_RELU); break;
+        default: TAO_ACT_CHECK(kKindScale); break;
+    }
+#undef TAO_ACT_CHECK
+    launch_profile_reduce(w, nblocks, (unsigned long long)n, out, st);
     return launch_status();
 }
 

@@ -106,6 +106,17 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_bound_act(0, nul, nul, p, p, 4, None, None) == tao.ERR_NULL                 # GELU needs x
     assert L.tao_bound_act(1, nul, nul, p, p, -4, None, None) == tao.ERR_SHAPE
     assert L.tao_bound_act(1, nul, nul, nul, nul, 0, None, None) == tao.OK
+    cneed = L.tao_check_workspace_bytes(100)
+    wsp = ctypes.c_void_p(0x100000)
+    assert L.tao_bound_check_act(1, nul, nul, p, p, 10, 1.0, 0.0, None, nul, wsp, cneed, None) == tao.ERR_NULL
+    assert L.tao_bound_check_act(1, nul, nul, p, p, 10, 1.0, 0.0, None, p, nul, cneed, None) == tao.ERR_WORKSPACE
+    assert L.tao_bound_check_act(1, nul, nul, p, p, 10, 1.0, 0.0, None, p, wsp, cneed - 1, None) == tao.ERR_WORKSPACE
+    assert L.tao_bound_check_act(1, nul, nul, p, nul, 10, 1.0, 0.0, None, p, wsp, cneed, None) == tao.ERR_NULL
+    assert L.tao_bound_check_act(0, nul, nul, p, p, 10, 1.0, 0.0, None, p, wsp, cneed, None) == tao.ERR_NULL   # GELU needs x
+    assert L.tao_bound_check_act(18, nul, nul, p, p, 10, 1.0, 0.0, None, p, wsp, cneed, None) == tao.ERR_KIND
+    assert L.tao_bound_check_act(1, nul, nul, p, p, -1, 1.0, 0.0, None, p, wsp, cneed, None) == tao.ERR_SHAPE
+    assert L.tao_bound_check_act(1, nul, nul, p, p, 10, -1.0, 0.0, None, p, wsp, cneed, None) == tao.ERR_SHAPE
+    assert L.tao_bound_check_act(1, nul, nul, p, odd, 10, 1.0, 0.0, None, p, wsp, cneed, None) == tao.ERR_ALIGN
     # linear
     args = lambda M, N, K, lda, ldw, ldt, tw=0, batch=1: (M, N, K, lda, ldw, ldt, tw, batch, 0, 0, 0)
     assert L.tao_bound_linear(p, p, nul, p, *args(4, 4, 8, 4, 8, 4), None, None) == tao.ERR_SHAPE   # lda < K

@@ -75,6 +75,15 @@ def _check_ops_sampled(tao, oracle_mod, ops, nsample, seed):
         # property on the whole tensor: the honest claim is accepted by the GPU's own bound
         p = tao.tao_check_and_profile(op.claimed.contiguous(), op.y_ref.contiguous(), tau.contiguous())
         assert p["violations"] == 0 and p["n"] == op.y_ref.numel(), op.name
+        # the one-pass variants bench.py runs: the same profile without a stored tau
+        acts = {"gelu": 0, "silu": 1, "mul": 2, "add": 3, "relu": 4}
+        if op.kind in acts:
+            fused = tao.tao_bound_check_act(acts[op.kind], op.args.get("x"), op.y_ref.contiguous(), op.claimed.contiguous(),
+                                            x2=op.args.get("x2"))
+            assert_profile_equal(fused, p, op.name + " (one pass)")
+        elif op.kind == "softmax":
+            fused = tao.tao_bound_check_softmax(op.args["x"], op.y_ref, op.claimed)
+            assert_profile_equal(fused, p, op.name + " (one pass)")
         nrows = op.y_ref.shape[-2] if op.kind == "linear" else op.y_ref.numel() // op.y_ref.shape[-1]
         rows = _sample_rows(nrows, nsample, seed + idx)
         batch = (idx % op.args["A"].shape[0]) if (op.kind == "linear" and op.args["A"].dim() == 3) else None

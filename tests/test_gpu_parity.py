@@ -515,6 +515,39 @@ def test_one_step_kinds(tao, oracle_mod, kind):
             assert_bound_parity(_np(t_gpu), t_or, "%s n=%d" % (kind, n))
 
 
+@pytest.mark.parametrize("kind", ["GELU_ERF", "GELU_TANH", "SILU", "MUL", "ADD", "RELU", "DIV", "EXP", "EXACT", "SIGMOID"])
+def test_elementwise_bound_checked_in_one_pass(tao, oracle_mod, kind):
+    """tao_bound_check_act: field for field the profile of tao_bound_act followed by
+    tao_check_and_profile on the GPU, and of the oracle's check on the GPU's stored bound; ragged
+    sizes, a misaligned base, planted violations, NaN and infinite claims."""
+    code = getattr(oracle_mod, kind)
+    g = torch.Generator().manual_seed(code + 77)
+    for n, offset in ((0, 0), (1, 0), (4099, 1), ((1 << 20) + 3, 0), (5 * (1 << 20), 0)):
+        x = (torch.randn((n + offset,), generator=g) * 3)[offset:]
+        x2 = torch.randn((n + offset,), generator=g)[offset:]
+        ref = {"GELU_ERF": tao_inputs.gelu_f32, "GELU_TANH": lambda v: torch.nn.functional.gelu(v, approximate="tanh"),
+               "SILU": tao_inputs.silu_f32, "RELU": torch.relu, "EXP": torch.exp, "SIGMOID": torch.sigmoid,
+               "EXACT": lambda v: v.clone(), "MUL": lambda v: v * x2, "ADD": lambda v: v + x2, "DIV": lambda v: v / x2}[kind](x)
+        claimed = tao_inputs.ulp_noise(g, ref, max_ulps=2) if n else ref.clone()
+        if n > 100:
+            claimed[5] = claimed[5] * 1.001 + 1e-3
+            claimed[17] = float("nan")
+            claimed[40] = float("inf")
+        dev = lambda t: (torch.cat([torch.zeros(offset), t]).cuda()[offset:] if offset else t.cuda())
+        xg, yg, cg = dev(x), dev(ref), dev(claimed)
+        needs_x = kind.startswith("GELU")
+        for alpha, eps in ((1.0, 1e-12), (3.0, 1e-6)):
+            fused = tao.tao_bound_check_act(code, xg if needs_x else None, yg, cg, alpha=alpha, eps_rel=eps)
+            tau = tao.tao_bound_act(code, xg if needs_x else None, yg) if n else torch.empty(0, device="cuda")
+            two = tao.tao_check_and_profile(cg, yg, tau, alpha=alpha, eps_rel=eps)
+            assert_profile_equal(fused, two, "%s n=%d one pass vs two" % (kind, n))
+            po = oracle_mod.check_and_profile(_np(claimed), _np(ref), _np(tau), alpha=alpha, eps_rel=eps)
+            assert_profile_equal(fused, po, "%s n=%d one pass vs oracle check" % (kind, n))
+            assert fused["n"] == n
+        if n > 100:
+            assert fused["violations"] >= 2 and fused["nan_count"] >= 1
+
+
 def test_gelu_tanh_shapes_and_range(tao, oracle_mod):
     code = oracle_mod.GELU_TANH
     for n, offset in ((1, 0), (1023, 0), (4096, 1), ((1 << 20) + 3, 0)):
