@@ -275,6 +275,8 @@ int tao_bound_rope(const float *x, const float *cos_table, const float *sin_tabl
  *     e = d / (|ref| + eps_rel), cast to binary32;  bin = NaN ? 2047 : bits(e) >> 20.
  * Percentiles p50, p99, p99.9 by nearest rank, rank = max(1, ceil(n p)), on the
  * histogram; alpha is the bound scale factor of Sec. 4.5 (1 = the paper's check).
+ * eps_rel must be >= 0 (TAO_ERR_SHAPE for a negative or NaN value, here and in every entry point
+ * that takes it).
  * out: DEVICE pointer, fully overwritten; valid once the stream has drained.
  * ws / ws_bytes: DEVICE scratch of at least tao_check_workspace_bytes(n). */
 int tao_check_and_profile(const float *claimed, const float *ref, const float *tau, long n,

@@ -109,7 +109,7 @@ int tao_check_and_profile(const float* claimed, const float* ref, const float* t
                           void* ws, size_t ws_bytes, void* stream) {
     using namespace tao;
     if (!out || !ws) return out ? TAO_ERR_WORKSPACE : TAO_ERR_NULL;
-    if (n < 0) return TAO_ERR_SHAPE;
+    if (n < 0 || !(eps_rel >= 0.0)) return TAO_ERR_SHAPE;       // a negative or NaN eps_rel has no meaning
     if (n > 0 && (!claimed || !ref || !tau)) return TAO_ERR_NULL;
     if (!aligned(claimed, 4) || !aligned(ref, 4) || !aligned(tau, 4) || !aligned(out, 8)) return TAO_ERR_ALIGN;
     if (!aligned(ws, 256) || ws_bytes < tao_check_workspace_bytes(n)) return TAO_ERR_WORKSPACE;

@@ -134,18 +134,11 @@ struct SplitArgs {
 // half b & 1 of word (b >> 1) * 4 + copy).
 __device__ __forceinline__ void check_one_packed(float c, float r, float t, double alpha, double eps_rel,
                                                  unsigned int* hist, int copy, ThreadAcc& acc) {
-    const double cd = (double)c, rd = (double)r;
-    const double d = fabs(cd - rd);
-    const double T = alpha * (double)t;
-    acc.violations += !(d <= T);
-    const double den = fabs(rd) + eps_rel;
-    const double e = d / den;
-    const float e32 = (float)e;
-    bool isn;
-    const unsigned int bin = error_bin(e32, isn);
-    acc.nans += isn;
-    if (!isn) acc.max_bits = max(acc.max_bits, __float_as_uint(e32));
-    atomicAdd(&hist[(bin >> 1) * 4 + copy], (bin & 1) ? 0x10000u : 1u);
+    const CheckedElement o = check_arith(c, r, t, alpha, eps_rel);
+    acc.violations += o.violation;
+    acc.nans += o.is_nan;
+    if (!o.is_nan) acc.max_bits = max(acc.max_bits, o.bits);
+    atomicAdd(&hist[(o.bin >> 1) * 4 + copy], (o.bin & 1) ? 0x10000u : 1u);
 }
 
 // CHECK: the epilogue also runs the leaf check of Sec. 5.4 and the relative-error profile of Sec. 5.3

@@ -200,7 +200,7 @@ int tao_profile_errors(const float* claimed, const float* ref, long n, double ep
                        void* ws, size_t ws_bytes, void* stream) {
     using namespace tao;
     if (!out || !ws) return out ? TAO_ERR_WORKSPACE : TAO_ERR_NULL;
-    if (n < 0) return TAO_ERR_SHAPE;
+    if (n < 0 || !(eps_rel >= 0.0)) return TAO_ERR_SHAPE;       // a negative or NaN eps_rel has no meaning
     if (n > 0 && (!claimed || !ref)) return TAO_ERR_NULL;
     if ((thr_abs == nullptr) != (thr_rel == nullptr)) return TAO_ERR_NULL;
     if (!aligned(claimed, 4) || !aligned(ref, 4) || !aligned(thr_abs, 4) || !aligned(thr_rel, 4) || !aligned(out, 8))

@@ -778,7 +778,7 @@ int tao_bound_check_softmax(const float* x, const float* y_ref, const float* cla
     int rc = resolve_model(model, &md);
     if (rc != TAO_OK) return rc;
     if (!out || !ws) return out ? TAO_ERR_WORKSPACE : TAO_ERR_NULL;
-    if (rows < 0 || cols < 0 || ld < cols) return TAO_ERR_SHAPE;
+    if (rows < 0 || cols < 0 || ld < cols || !(eps_rel >= 0.0)) return TAO_ERR_SHAPE;
     const long n = rows * cols;
     if (rows > 0 && cols > 0 && n / cols != rows) return TAO_ERR_SHAPE;
     if (n >= (1L << 36)) return TAO_ERR_SHAPE;                      // 32-bit per-workgroup counters

@@ -23,23 +23,41 @@ struct ThreadAcc {
     unsigned int violations = 0, nans = 0, max_bits = 0;
 };
 
+// The arithmetic of one element: violation flag, bin of the relative error, its bits.  A claimed
+// value that equals the re-executed one bit for bit (and is finite) has d = 0 exactly, so the error is
+// 0 (NaN for 0/0) without the binary64 division; whole wavefronts of such elements -- the masked
+// half of a causal softmax, exact operators -- skip the division's instructions altogether.
+struct CheckedElement { bool violation, is_nan; unsigned int bin, bits; };
+__device__ __forceinline__ CheckedElement check_arith(float c, float r, float t, double alpha, double eps_rel) {
+    CheckedElement o;
+    const double rd = (double)r;
+    const double T = alpha * (double)t;
+    const double den = fabs(rd) + eps_rel;
+    if (c == r && fabsf(c) != INFINITY) {
+        o.violation = !(0.0 <= T);
+        o.is_nan = !(den > 0.0);                             // 0/0
+        o.bits = 0u;
+        o.bin = o.is_nan ? (unsigned)(kBins - 1) : 0u;
+        return o;
+    }
+    const double d = fabs((double)c - rd);
+    o.violation = !(d <= T);
+    const double e = d / den;
+    const float e32 = (float)e;
+    o.bin = error_bin(e32, o.is_nan);
+    o.bits = __float_as_uint(e32);
+    return o;
+}
+
 // R: copies of every bin in the LDS histogram `hist` (copy `rep` is used).
 template <int R = kReplicas>
 __device__ __forceinline__ void check_one(float c, float r, float t, double alpha, double eps_rel,
                                           unsigned int* hist, int rep, ThreadAcc& acc) {
-    const double cd = (double)c, rd = (double)r;
-    const double d = fabs(cd - rd);
-    const double T = alpha * (double)t;
-    acc.violations += !(d <= T);
-    const double den = fabs(rd) + eps_rel;
-    const double e = d / den;
-    const float e32 = (float)e;
-    bool isn;
-    const unsigned int bin = error_bin(e32, isn);
-    const unsigned int bits = __float_as_uint(e32);
-    acc.nans += isn;
-    if (!isn) acc.max_bits = max(acc.max_bits, bits);
-    atomicAdd(&hist[bin * R + rep], 1u);
+    const CheckedElement o = check_arith(c, r, t, alpha, eps_rel);
+    acc.violations += o.violation;
+    acc.nans += o.is_nan;
+    if (!o.is_nan) acc.max_bits = max(acc.max_bits, o.bits);
+    atomicAdd(&hist[o.bin * R + rep], 1u);
 }
 
 // Workgroup totals of the per-thread counters (kCheckThreads threads) into ws_stats[blockIdx.x];

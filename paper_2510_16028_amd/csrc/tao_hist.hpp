@@ -21,7 +21,9 @@ constexpr int kReduceWaves = kReduceThreads / kWave;
 // bin of an error value: bits >> 20 (8 exponent bits, 3 mantissa bits); NaN -> last bin
 __device__ __forceinline__ unsigned int error_bin(float e32, bool& is_nan) {
     is_nan = e32 != e32;
-    return is_nan ? (unsigned)(kBins - 1) : (__float_as_uint(e32) >> 20);
+    // (errors are non-negative: the entry points reject a negative eps_rel; the minimum keeps a
+    // stray sign bit from indexing past the histogram all the same)
+    return is_nan ? (unsigned)(kBins - 1) : min(__float_as_uint(e32) >> 20, (unsigned)(kBins - 1));
 }
 
 __device__ __forceinline__ float bin_upper_edge(unsigned int b) {

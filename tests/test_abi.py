@@ -190,6 +190,8 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_check_and_profile(p, p, p, 10, 1.0, 0.0, p, ws, need - 1, None) == tao.ERR_WORKSPACE
     assert L.tao_check_and_profile(p, p, p, 10, 1.0, 0.0, p, ctypes.c_void_p(0x10010), need, None) == tao.ERR_WORKSPACE
     assert L.tao_check_and_profile(p, p, p, -1, 1.0, 0.0, p, ws, need, None) == tao.ERR_SHAPE
+    assert L.tao_check_and_profile(p, p, p, 10, 1.0, -1e-9, p, ws, need, None) == tao.ERR_SHAPE      # negative eps_rel
+    assert L.tao_check_and_profile(p, p, p, 10, 1.0, float("nan"), p, ws, need, None) == tao.ERR_SHAPE
     assert L.tao_check_and_profile(nul, p, p, 10, 1.0, 0.0, p, ws, need, None) == tao.ERR_NULL
     assert L.tao_check_and_profile(odd, p, p, 10, 1.0, 0.0, p, ws, need, None) == tao.ERR_ALIGN
     # error profiles
@@ -201,6 +203,7 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_profile_errors(p, p, 10, 0.0, p, nul, p, ws, need, None) == tao.ERR_NULL      # one table only
     assert L.tao_profile_errors(p, nul, 10, 0.0, nul, nul, p, ws, need, None) == tao.ERR_NULL
     assert L.tao_profile_errors(p, p, -1, 0.0, nul, nul, p, ws, need, None) == tao.ERR_SHAPE
+    assert L.tao_profile_errors(p, p, 10, -1.0, nul, nul, p, ws, need, None) == tao.ERR_SHAPE
     assert L.tao_profile_errors(odd, p, 10, 0.0, nul, nul, p, ws, need, None) == tao.ERR_ALIGN
     # calibration
     assert L.tao_calibrate_thresholds(p, 0, 3.0, nul, nul, p, p, None) == tao.ERR_SHAPE
