@@ -69,21 +69,34 @@ __device__ __forceinline__ void split_one(float v, unsigned& h, unsigned& m, uns
 }
 
 // One thread per 8 consecutive k of one row.  TRANS: the source is [K][ld] with the row index
-// running along its columns (W stored K x N).
+// running along its columns (W stored K x N); adjacent threads then take adjacent rows.  Otherwise a
+// workgroup takes patches of 64 rows x 256 k: per 32-k slab its 256 threads read 128 contiguous bytes
+// of each row (1 KB per row over the patch) and write 4 KB contiguous per piece (64 rows of one
+// slab are adjacent in the block layout) -- with threads running along k instead, every 64 bytes
+// written landed in another block.
 template <bool TRANS>
 __global__ __launch_bounds__(256) void split3_bf16(const float* __restrict__ src, long rows, long K, long ld,
                                                     long src_batch_stride, unsigned short* __restrict__ dst, long Kp,
                                                     int vec_ok) {
     const long chunks = Kp >> 3;
-    const long total = rows * chunks;
     const long z = blockIdx.y;
     const long rblocks = (rows + STILE - 1) / STILE;
     const float* s = src + z * src_batch_stride;
     unsigned short* d = dst + z * ((Kp / SBK) * rblocks * (kBlock / 2));
+    // work items: TRANS (chunk, row) pairs, row fastest; else (row group, k span, slab, row, chunk of the slab)
+    const long kspans = (Kp + 255) >> 8, rgroups = (rows + 63) >> 6;
+    const long total = TRANS ? rows * chunks : rgroups * kspans * 8 * 256;
     for (long w = (long)blockIdx.x * blockDim.x + threadIdx.x; w < total; w += (long)gridDim.x * blockDim.x) {
         long row, ch;
-        if (TRANS) { ch = w / rows; row = w - ch * rows; }      // adjacent threads: adjacent rows (source columns)
-        else       { row = w / chunks; ch = w - row * chunks; } // adjacent threads: adjacent chunks of one row
+        if (TRANS) {
+            ch = w / rows; row = w - ch * rows;
+        } else {
+            const long patch = w >> 11, in = w & 2047;          // 8 slabs x 64 rows x 4 chunks
+            const long rg = patch / kspans, ks = patch - rg * kspans;
+            row = (rg << 6) + ((in & 255) >> 2);
+            ch = (ks << 5) + ((in >> 8) << 2) + (in & 3);
+            if (row >= rows || ch >= chunks) continue;
+        }
         const long k0 = ch << 3;
         float v[8];
         if (!TRANS && vec_ok && k0 + 8 <= K) {
@@ -568,20 +581,21 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
     const size_t bytesA = (size_t)(Kp / SBK) * blocksA * kBlock * batch;          // a multiple of 256
     unsigned short* W3 = reinterpret_cast<unsigned short*>(static_cast<char*>(ws) + bytesA);
     if (K > 0) {
-        auto blocks_for = [](long rows, long kp) {
-            long b = (rows * (kp >> 3) + 255) / 256;
+        auto blocks_for = [](long rows, long kp, bool trans) {
+            // work items of split3_bf16: (row, chunk) pairs, or whole 64-row x 256-k patches of 2048
+            long b = trans ? (rows * (kp >> 3) + 255) / 256 : ((rows + 63) / 64) * ((kp + 255) / 256) * 8;
             return (unsigned)(b < 1 ? 1 : (b > 256L * 64 ? 256L * 64 : b));
         };
         const int vecA = aligned(A, 16) && (lda % 4 == 0) && (strideA % 4 == 0);
-        hipLaunchKernelGGL((split3_bf16<false>), dim3(blocks_for(M, Kp), (unsigned)batch), dim3(256), 0, st,
+        hipLaunchKernelGGL((split3_bf16<false>), dim3(blocks_for(M, Kp, false), (unsigned)batch), dim3(256), 0, st,
                            A, M, K, lda, strideA, A3, Kp, vecA);
         const unsigned wb = shared_w ? 1u : (unsigned)batch;
         if (trans_w) {
-            hipLaunchKernelGGL((split3_bf16<true>), dim3(blocks_for(N, Kp), wb), dim3(256), 0, st,
+            hipLaunchKernelGGL((split3_bf16<true>), dim3(blocks_for(N, Kp, true), wb), dim3(256), 0, st,
                                W, N, K, ldw, strideW, W3, Kp, 0);
         } else {
             const int vecW = aligned(W, 16) && (ldw % 4 == 0) && (strideW % 4 == 0);
-            hipLaunchKernelGGL((split3_bf16<false>), dim3(blocks_for(N, Kp), wb), dim3(256), 0, st,
+            hipLaunchKernelGGL((split3_bf16<false>), dim3(blocks_for(N, Kp, false), wb), dim3(256), 0, st,
                                W, N, K, ldw, strideW, W3, Kp, vecW);
         }
     }
