@@ -52,7 +52,8 @@ _STREAM_BYTES = {"softmax": 12, "layernorm": 12, "rmsnorm": 12, "bn_affine": 12,
 
 
 # the same with the check in the same pass: inputs and the claimed output read once, nothing written
-_FUSED_BYTES = {"softmax": 12, "gelu": 12, "silu": 8, "mul": 8, "add": 8, "relu": 8}
+_FUSED_BYTES = {"softmax": 12, "gelu": 12, "silu": 8, "mul": 8, "add": 8, "relu": 8, "layernorm": 12, "rmsnorm": 12,
+                "rope": 12}
 
 
 class PlannedOp:
@@ -119,6 +120,14 @@ class PlannedOp:
         a, op = self.op.args, self.op
         if self.kind == "softmax":
             self.tao.tao_bound_check_softmax(a["x"], self.y_ref, self.claimed, out=self.prof, ws=self.ws, readback=False)
+            return
+        if self.kind in ("layernorm", "rmsnorm"):
+            self.tao.tao_bound_check_norm(_NORM[self.kind], a["x"], self.y_ref, self.claimed, a.get("gamma"), a.get("beta"),
+                                          eps=op.attrs["eps"], out=self.prof, ws=self.ws, readback=False)
+            return
+        if self.kind == "rope":
+            self.tao.tao_bound_check_rope(a["x"], a["cos"], a["sin"], self.y_ref, self.claimed, inner=op.attrs["inner"],
+                                          out=self.prof, ws=self.ws, readback=False)
             return
         if self.kind != "linear":
             self.tao.tao_bound_check_act(_ACT[self.kind], a.get("x"), self.y_ref, self.claimed, x2=a.get("x2"),
@@ -236,7 +245,7 @@ def main():
     ap.add_argument("--fp32-only", action="store_true", help="matmul bounds on the FP32 matrix cores only (no BF16-split path)")
     ap.add_argument("--no-fused-check", action="store_true",
                     help="store every tau and run the streaming check after every bound (default: the BF16-split "
-                         "matmul kernel, the element-wise kernels and softmax check their bound in registers)")
+                         "matmul kernel and all streaming bound kernels check their bound in registers)")
     ap.add_argument("--projection-elems", type=int, default=0,
                     help="only time the two projections of Sec. 4.4 on this many synthetic elements and exit "
                          "(side measurement; used for the committed kernel trace)")

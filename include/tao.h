@@ -269,6 +269,25 @@ int tao_bound_rope(const float *x, const float *cos_table, const float *sin_tabl
                    long rows, long d, long inner, long npos, int interleaved,
                    const tao_fp_model *model, void *stream);
 
+/* tao_bound_norm checked on the spot, for kind TAO_NORM_LAYERNORM and TAO_NORM_RMSNORM (TAO_ERR_KIND
+ * otherwise): *out receives exactly what tao_check_and_profile(claimed, y_ref, tau, ...) returns for the
+ * tau of tao_bound_norm(kind, x, y_ref, gamma, beta, eps, ...), never stored.  claimed: DEVICE, laid out
+ * like x and y_ref (rows x cols, leading dimension ld).  ws / ws_bytes: DEVICE scratch of at least
+ * tao_check_workspace_bytes(rows * cols), 256-byte aligned. */
+int tao_bound_check_norm(int kind, const float *x, const float *y_ref, const float *gamma, const float *beta,
+                         double eps, const float *claimed, long rows, long cols, long ld,
+                         double alpha, double eps_rel, const tao_fp_model *model, tao_profile *out,
+                         void *ws, size_t ws_bytes, void *stream);
+
+/* tao_bound_rope checked on the spot: *out receives exactly what tao_check_and_profile(claimed,
+ * y_ref, tau, ...) returns for the tau of tao_bound_rope(x, cos_table, sin_table, ...), never stored.
+ * y_ref, claimed: DEVICE, rows x d contiguous like x.  ws / ws_bytes: DEVICE scratch of at least
+ * tao_check_workspace_bytes(rows * d), 256-byte aligned. */
+int tao_bound_check_rope(const float *x, const float *cos_table, const float *sin_table, const float *y_ref,
+                         const float *claimed, long rows, long d, long inner, long npos, int interleaved,
+                         double alpha, double eps_rel, const tao_fp_model *model, tao_profile *out,
+                         void *ws, size_t ws_bytes, void *stream);
+
 /* Leaf check (Sec. 5.4) and relative-error profile (Sec. 5.3; Sec. 3.2 Eq. 2)
  * of n elements, in IEEE binary64 per element:
  *     d = |claimed - ref|;  violation iff !(d <= alpha * tau);

@@ -94,7 +94,7 @@ class TaoError(RuntimeError):
 EXPORTS = ["tao_default_model", "tao_gamma", "tao_bound_linear", "tao_bound_linear_split",
            "tao_linear_split_workspace_bytes", "tao_linear_split_preferred",
            "tao_bound_check_linear", "tao_bound_check_linear_workspace_bytes", "tao_selftest_matrix_core_bf16", "tao_bound_conv2d", "tao_bound_softmax",
-           "tao_bound_norm", "tao_bound_groupnorm", "tao_groupnorm_workspace_bytes", "tao_bound_act", "tao_bound_check_act", "tao_bound_rope", "tao_check_and_profile",
+           "tao_bound_norm", "tao_bound_groupnorm", "tao_groupnorm_workspace_bytes", "tao_bound_act", "tao_bound_check_act", "tao_bound_rope", "tao_bound_check_rope", "tao_bound_check_norm", "tao_check_and_profile",
            "tao_check_workspace_bytes", "tao_bound_check_softmax", "tao_profile_errors", "tao_profile_workspace_bytes",
            "tao_calibrate_thresholds", "tao_project_clip", "tao_project_empirical", "tao_project_workspace_bytes",
            "tao_selftest_matrix_core", "tao_last_hip_error", "tao_status_string"]
@@ -140,6 +140,10 @@ def lib():
     L.tao_groupnorm_workspace_bytes.restype = ctypes.c_size_t
     L.tao_bound_act.argtypes = [ctypes.c_int, vp, vp, vp, vp, lg, mp, vp]
     L.tao_bound_check_act.argtypes = [ctypes.c_int, vp, vp, vp, vp, lg, dbl, dbl, mp, vp, vp, ctypes.c_size_t, vp]
+    L.tao_bound_check_norm.argtypes = [ctypes.c_int, vp, vp, vp, vp, dbl, vp, lg, lg, lg, dbl, dbl, mp, vp, vp,
+                                       ctypes.c_size_t, vp]
+    L.tao_bound_check_rope.argtypes = [vp, vp, vp, vp, vp, lg, lg, lg, lg, ctypes.c_int, dbl, dbl, mp, vp, vp,
+                                       ctypes.c_size_t, vp]
     L.tao_bound_rope.argtypes = [vp, vp, vp, vp, lg, lg, lg, lg, ctypes.c_int, mp, vp]
     L.tao_check_and_profile.argtypes = [vp, vp, vp, lg, dbl, dbl, vp, vp, ctypes.c_size_t, vp]
     L.tao_check_workspace_bytes.argtypes = [lg]
@@ -540,6 +544,53 @@ def tao_bound_check_act(kind, x, y_ref, claimed, x2=None, alpha=1.0, eps_rel=1e-
     rc = lib().tao_bound_check_act(int(kind), _ptr(x), _ptr(x2), _ptr(y_ref), _ptr(claimed), n, float(alpha),
                                    float(eps_rel), _mref(model), _ptr(out), _ptr(ws), ws.numel(), _stream())
     _check(rc, "tao_bound_check_act")
+    return read_profile(out) if readback else out
+
+
+def tao_bound_check_norm(kind, x, y_ref, claimed, g=None, b=None, eps=0.0, alpha=1.0, eps_rel=1e-12, model=None,
+                         out=None, ws=None, readback=True):
+    """tao_bound_norm (LayerNorm or RMSNorm) checked against `claimed` in one pass, tau never stored."""
+    x = _dev(x, "x"); y_ref = _dev(y_ref, "y_ref"); claimed = _dev(claimed, "claimed"); g = _dev(g, "g"); b = _dev(b, "b")
+    for t, nm in ((y_ref, "y_ref"), (claimed, "claimed")):
+        if t.shape != x.shape or t.stride() != x.stride():
+            raise ValueError("%s must have the shape and strides of x" % nm)
+    rows, cols, ld = _rows_view(x, "x")
+    for t, nm in ((g, "g"), (b, "b")):
+        if t is not None and (t.dim() != 1 or t.shape[0] != cols or not t.is_contiguous()):
+            raise ValueError("%s must be a contiguous [cols] tensor" % nm)
+    if out is None:
+        out = new_profile_buffer(x.device)
+    if ws is None:
+        ws = _workspace(x.device, rows * cols)
+    rc = lib().tao_bound_check_norm(int(kind), _ptr(x), _ptr(y_ref), _ptr(g), _ptr(b), float(eps), _ptr(claimed),
+                                    rows, cols, ld, float(alpha), float(eps_rel), _mref(model), _ptr(out),
+                                    _ptr(ws), ws.numel(), _stream())
+    _check(rc, "tao_bound_check_norm")
+    return read_profile(out) if readback else out
+
+
+def tao_bound_check_rope(x, cos, sin, y_ref, claimed, inner=1, interleaved=False, alpha=1.0, eps_rel=1e-12,
+                         model=None, out=None, ws=None, readback=True):
+    """tao_bound_rope checked against `claimed` in one pass, tau never stored."""
+    x = _dev(x, "x"); cos = _dev(cos, "cos"); sin = _dev(sin, "sin")
+    y_ref = _dev(y_ref, "y_ref"); claimed = _dev(claimed, "claimed")
+    if x.dim() < 1 or not x.is_contiguous() or not cos.is_contiguous() or not sin.is_contiguous():
+        raise ValueError("x, cos and sin must be contiguous")
+    d = x.shape[-1]
+    if cos.dim() != 2 or cos.shape != sin.shape or cos.shape[1] * 2 != d:
+        raise ValueError("cos and sin must be [npos, d/2] tables")
+    for t, nm in ((y_ref, "y_ref"), (claimed, "claimed")):
+        if t.shape != x.shape or not t.is_contiguous():
+            raise ValueError("%s must be contiguous and shaped like x" % nm)
+    rows = x.numel() // max(d, 1)
+    if out is None:
+        out = new_profile_buffer(x.device)
+    if ws is None:
+        ws = _workspace(x.device, x.numel())
+    rc = lib().tao_bound_check_rope(_ptr(x), _ptr(cos), _ptr(sin), _ptr(y_ref), _ptr(claimed), rows, d, int(inner),
+                                    cos.shape[0], int(bool(interleaved)), float(alpha), float(eps_rel), _mref(model),
+                                    _ptr(out), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "tao_bound_check_rope")
     return read_profile(out) if readback else out
 
 

@@ -149,11 +149,27 @@ __global__ __launch_bounds__(kCheckThreads) void act_check(
 
 // Rotary embedding: one thread per output pair and float4 of a half (pairs (j, j + d/2)) or per
 // float4 of interleaved pairs.  Tables are read through the cache (every head of a position
-// shares a row), activations and bounds stream.
-template <bool INTERLEAVED, bool VEC>
-__global__ __launch_bounds__(256) void rope_bound(const float* __restrict__ x, const float* __restrict__ cs,
-                                                   const float* __restrict__ sn, float* __restrict__ tau,
-                                                   long rows, int d, long inner, long npos, double g2, double uflow) {
+// shares a row), activations and bounds stream.  The bounds go to a sink: stored (rope_bound) or
+// checked on the spot against the claimed and the re-executed output (rope_check).
+struct StoreSink {
+    float* tau;
+    __device__ __forceinline__ void put4(long idx, float4 t) { ntstore4(reinterpret_cast<float4*>(tau + idx), t); }
+    __device__ __forceinline__ void put1(long idx, float t) { tau[idx] = t; }
+};
+struct CheckSink {
+    const float* y; const float* claimed; double alpha, eps_rel; unsigned int* hist; int rep; ThreadAcc acc;
+    __device__ __forceinline__ void put1(long idx, float t) { check_one(claimed[idx], y[idx], t, alpha, eps_rel, hist, rep, acc); }
+    __device__ __forceinline__ void put4(long idx, float4 t) {
+        const float4 Y = ntload4(reinterpret_cast<const float4*>(y + idx));
+        const float4 C = ntload4(reinterpret_cast<const float4*>(claimed + idx));
+        check_one(C.x, Y.x, t.x, alpha, eps_rel, hist, rep, acc); check_one(C.y, Y.y, t.y, alpha, eps_rel, hist, rep, acc);
+        check_one(C.z, Y.z, t.z, alpha, eps_rel, hist, rep, acc); check_one(C.w, Y.w, t.w, alpha, eps_rel, hist, rep, acc);
+    }
+};
+
+template <bool INTERLEAVED, bool VEC, class Sink>
+__device__ __forceinline__ void rope_body(const float* __restrict__ x, const float* __restrict__ cs, const float* __restrict__ sn,
+                                          long rows, int d, long inner, long npos, double g2, double uflow, Sink& sink) {
     const int h = d >> 1;
     // work items per row: h/4 vectors of a half, or d/4 vectors of interleaved pairs (2 pairs each);
     // the scalar variants take one pair per item
@@ -169,7 +185,8 @@ __global__ __launch_bounds__(256) void rope_bound(const float* __restrict__ x, c
         const long r = w / per_row;
         const int j = (int)(w - r * per_row);
         const long t = (r / inner) % npos;
-        const float* xr = x + r * d; float* tr = tau + r * d;
+        const float* xr = x + r * d;
+        const long base = r * d;
         const float* cr = cs + t * h; const float* sr = sn + t * h;
         if (VEC && !INTERLEAVED) {
             const float4 A = ntload4(reinterpret_cast<const float4*>(xr) + j);
@@ -179,20 +196,47 @@ __global__ __launch_bounds__(256) void rope_bound(const float* __restrict__ x, c
             float4 TA, TB;
             one(A.x, B.x, C.x, S.x, TA.x, TB.x); one(A.y, B.y, C.y, S.y, TA.y, TB.y);
             one(A.z, B.z, C.z, S.z, TA.z, TB.z); one(A.w, B.w, C.w, S.w, TA.w, TB.w);
-            ntstore4(reinterpret_cast<float4*>(tr) + j, TA);
-            ntstore4(reinterpret_cast<float4*>(tr + h) + j, TB);
+            sink.put4(base + 4L * j, TA);
+            sink.put4(base + h + 4L * j, TB);
         } else if (VEC) {
             const float4 X = ntload4(reinterpret_cast<const float4*>(xr) + j);      // pairs 2j, 2j+1
             const float2 C = reinterpret_cast<const float2*>(cr)[j];
             const float2 S = reinterpret_cast<const float2*>(sr)[j];
             float4 T;
             one(X.x, X.y, C.x, S.x, T.x, T.y); one(X.z, X.w, C.y, S.y, T.z, T.w);
-            ntstore4(reinterpret_cast<float4*>(tr) + j, T);
+            sink.put4(base + 4L * j, T);
         } else {
             const int a = INTERLEAVED ? 2 * j : j, b = INTERLEAVED ? 2 * j + 1 : j + h;
-            one(xr[a], xr[b], cr[j], sr[j], tr[a], tr[b]);
+            float ta, tb;
+            one(xr[a], xr[b], cr[j], sr[j], ta, tb);
+            sink.put1(base + a, ta);
+            sink.put1(base + b, tb);
         }
     }
+}
+
+template <bool INTERLEAVED, bool VEC>
+__global__ __launch_bounds__(256) void rope_bound(const float* __restrict__ x, const float* __restrict__ cs,
+                                                   const float* __restrict__ sn, float* __restrict__ tau,
+                                                   long rows, int d, long inner, long npos, double g2, double uflow) {
+    StoreSink sink{tau};
+    rope_body<INTERLEAVED, VEC>(x, cs, sn, rows, d, inner, npos, g2, uflow, sink);
+}
+
+template <bool INTERLEAVED, bool VEC>
+__global__ __launch_bounds__(kCheckThreads) void rope_check(
+    const float* __restrict__ x, const float* __restrict__ cs, const float* __restrict__ sn,
+    const float* __restrict__ y, const float* __restrict__ claimed,
+    long rows, int d, long inner, long npos, double g2, double uflow, double alpha, double eps_rel,
+    unsigned int* __restrict__ ws_hist, unsigned int* __restrict__ ws_coarse, BlockStats* __restrict__ ws_stats) {
+    __shared__ unsigned int hist[kBins * kReplicas];
+    __shared__ unsigned int red[3 * (kCheckThreads / kWave)];
+    for (int i = threadIdx.x; i < kBins * kReplicas; i += kCheckThreads) hist[i] = 0;
+    __syncthreads();
+    CheckSink sink{y, claimed, alpha, eps_rel, hist, (int)(threadIdx.x & (kReplicas - 1)), ThreadAcc()};
+    rope_body<INTERLEAVED, VEC>(x, cs, sn, rows, d, inner, npos, g2, uflow, sink);
+    flush_block_stats(sink.acc, red, ws_stats);
+    flush_histogram(hist, ws_hist + (size_t)blockIdx.x * kBins, ws_coarse + blockIdx.x * kGroups);
 }
 
 }  // namespace tao
@@ -333,6 +377,43 @@ int tao_bound_rope(const float* x, const float* cos_table, const float* sin_tabl
         if (vec) hipLaunchKernelGGL((rope_bound<false, true>), grid, blk, 0, st, x, cos_table, sin_table, tau, rows, (int)d, inner, npos, g2, uflow);
         else     hipLaunchKernelGGL((rope_bound<false, false>), grid, blk, 0, st, x, cos_table, sin_table, tau, rows, (int)d, inner, npos, g2, uflow);
     }
+    return launch_status();
+}
+
+int tao_bound_check_rope(const float* x, const float* cos_table, const float* sin_table, const float* y_ref,
+                         const float* claimed, long rows, long d, long inner, long npos, int interleaved,
+                         double alpha, double eps_rel, const tao_fp_model* model, tao_profile* out,
+                         void* ws, size_t ws_bytes, void* stream) {
+    using namespace tao;
+    tao_fp_model md;
+    int rc = resolve_model(model, &md);
+    if (rc != TAO_OK) return rc;
+    if (!out || !ws) return out ? TAO_ERR_WORKSPACE : TAO_ERR_NULL;
+    if (rows < 0 || d < 0 || (d & 1) || inner < 1 || npos < 1 || d >= (1L << 30)) return TAO_ERR_SHAPE;
+    if (!(alpha >= 0.0) || !std::isfinite(alpha) || !(eps_rel >= 0.0) || !std::isfinite(eps_rel)) return TAO_ERR_SHAPE;
+    if (rows > 0 && d > 0 && rows > ((1L << 36) - 1) / d) return TAO_ERR_SHAPE;   // 32-bit per-workgroup counters
+    const double g2 = gamma_up(2, md);
+    if (!(g2 == g2)) return TAO_ERR_K_RANGE;
+    const long n = rows * d;
+    if (n > 0 && (!x || !cos_table || !sin_table || !y_ref || !claimed)) return TAO_ERR_NULL;
+    if (!aligned(x, 4) || !aligned(cos_table, 4) || !aligned(sin_table, 4) || !aligned(y_ref, 4) || !aligned(claimed, 4) ||
+        !aligned(out, 8)) return TAO_ERR_ALIGN;
+    if (!aligned(ws, 256) || ws_bytes < check_workspace_bytes()) return TAO_ERR_WORKSPACE;
+    const double uflow = (md.flags & TAO_FLAG_UNDERFLOW_TERMS) ? 2.0 * 0x1p-149 : 0.0;
+    const bool vec = aligned(x, 16) && aligned(y_ref, 16) && aligned(claimed, 16) && aligned(cos_table, 16) &&
+                     aligned(sin_table, 16) && (interleaved ? d % 4 == 0 : d % 8 == 0);
+    const long per_row = vec ? (interleaved ? d / 4 : d / 8) : d / 2;
+    long want = (rows * per_row + (long)kCheckThreads * 4 - 1) / ((long)kCheckThreads * 4);
+    const int nblocks = (int)(want < 1 ? 1 : (want > kMaxCheckBlocks ? kMaxCheckBlocks : want));
+    const CheckWorkspace w = carve_check_workspace(ws);
+    hipStream_t st = (hipStream_t)stream;
+    dim3 grid((unsigned)nblocks), blk(kCheckThreads);
+#define TAO_ROPE_CHECK(I, V) hipLaunchKernelGGL((rope_check<I, V>), grid, blk, 0, st, x, cos_table, sin_table, y_ref, claimed, \
+                                                rows, (int)d, inner, npos, g2, uflow, alpha, eps_rel, w.hist, w.coarse, w.stats)
+    if (interleaved) { if (vec) TAO_ROPE_CHECK(true, true); else TAO_ROPE_CHECK(true, false); }
+    else             { if (vec) TAO_ROPE_CHECK(false, true); else TAO_ROPE_CHECK(false, false); }
+#undef TAO_ROPE_CHECK
+    launch_profile_reduce(w, nblocks, (unsigned long long)n, out, st);
     return launch_status();
 }
 

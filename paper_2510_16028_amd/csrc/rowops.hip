@@ -558,6 +558,112 @@ __global__ __launch_bounds__(kRowThreads) void rmsnorm_bound(
     }
 }
 
+// LayerNorm / RMSNorm bounds checked on the spot: the structure of softmax_check (1024-thread
+// workgroups that walk the rows, kCheckThreads / TPR rows at a time, one partial histogram each)
+// with the arithmetic of layernorm_body / rmsnorm_bound, operation for operation, so that the bound
+// compared in registers is the binary32 value the bound kernels store.
+template <bool RMS, int TPR, int V>
+__global__ __launch_bounds__(kCheckThreads) void norm_check(
+    const float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ g, const float* __restrict__ claimed,
+    long rows, long cols, long ld, int vec_ok, int vec_g, RowConsts k, double alpha, double eps_rel,
+    unsigned int* __restrict__ ws_hist, unsigned int* __restrict__ ws_coarse, BlockStats* __restrict__ ws_stats) {
+    constexpr int RPB = kCheckThreads / TPR;
+    constexpr bool CACHED = (V > 0);
+    __shared__ unsigned int hist[kBins * kReplicas];
+    __shared__ unsigned int red[3 * (kCheckThreads / kWave)];
+    __shared__ double smem[2 * 4 * (kCheckThreads / kWave)];       // one slot per reduction of a row
+    const int tid = threadIdx.x;
+    for (int i = tid; i < kBins * kReplicas; i += kCheckThreads) hist[i] = 0;
+    __syncthreads();
+    ThreadAcc acc_chk;
+    const int rep = tid & (kReplicas - 1);
+    const int lt = tid % TPR;
+    const int nv = CACHED ? V : (int)((cols + TPR * 4 - 1) / (TPR * 4));
+    const long nblocks = (rows + RPB - 1) / RPB;
+    const double n = (double)cols;
+    auto scales = [&](long idx, long limit) {
+        return g ? load4(g, idx, limit, vec_g, 1.f) : make_float4(1.f, 1.f, 1.f, 1.f);
+    };
+    // every thread of the workgroup takes the same number of trips (the reductions hold barriers)
+    for (long rb = blockIdx.x; rb < nblocks; rb += gridDim.x) {
+        const long row = rb * RPB + tid / TPR;
+        const bool active = row < rows;
+        const long limit = active ? cols : 0;
+        const long roff = active ? row * ld : 0;
+        float4 xv[CACHED ? V : 1], yv[CACHED ? V : 1], gv[CACHED ? V : 1];
+        double a1[2] = {0.0, 0.0};                 // RMS: sum x^2;  LayerNorm: sum x, sum |x|
+        for (int v = 0; v < nv; ++v) {
+            const float4 X = load4<CACHED>(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+            if (CACHED) {
+                xv[v] = X;
+                yv[v] = load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+                gv[v] = scales(TAO_VEC_INDEX(v), limit);
+            }
+            const float e[4] = {X.x, X.y, X.z, X.w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (RMS) a1[0] += (double)e[c] * (double)e[c];
+                else { a1[0] += (double)e[c]; a1[1] += (double)fabsf(e[c]); }
+            }
+        }
+        wide_group_sum<TPR>(a1, RMS ? 1 : 2, smem);
+        double mu = 0.0, K1 = 0.0, K0 = 0.0, f = 0.0;
+        bool ok = true;
+        if (RMS) {
+            const double E_t = (k.G * (1.0 + k.u) + k.u) * a1[0];
+            const double vstar = a1[0] * k.inv_n;
+            const double E_v = (E_t * k.inv_n + k.cd_u * vstar) * k.inv1mcd;
+            double rs, E_r, R;
+            ok = rsqrt_tail(vstar, E_v, k, rs, E_r, R);
+            f = E_r + k.u * R;
+        } else {
+            mu = a1[0] * k.inv_n;
+            const double E_mu = ((k.G * a1[1]) * k.inv_n + k.cd_u * fabs(mu)) * k.inv1mcd;
+            double a2[2] = {0.0, 0.0};                                   // sum |d|, sum d^2
+            for (int v = 0; v < nv; ++v) {
+                const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+                const float e[4] = {X.x, X.y, X.z, X.w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const double d = (TAO_VEC_INDEX(v) + c < limit) ? (double)e[c] - mu : 0.0;
+                    a2[0] += fabs(d);
+                    a2[1] = fma(d, d, a2[1]);
+                }
+            }
+            wide_group_sum<TPR>(a2, 2, smem + 4 * (kCheckThreads / kWave));
+            layernorm_tail(E_mu, a2[0], a2[1], n, k, K1, K0);
+        }
+        for (int v = 0; v < nv; ++v) {
+            const long idx = TAO_VEC_INDEX(v);
+            if (idx >= limit) continue;
+            const float4 X = CACHED ? xv[v] : load4(x + roff, idx, limit, vec_ok, 0.f);
+            const float4 Y = CACHED ? yv[v] : load4<true>(y + roff, idx, limit, vec_ok, 0.f);
+            const float4 Gv = CACHED ? gv[v] : scales(idx, limit);
+            const float4 C = load4<true>(claimed + roff, idx, limit, vec_ok, 0.f);
+            const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w};
+            const float ge[4] = {Gv.x, Gv.y, Gv.z, Gv.w}, ce[4] = {C.x, C.y, C.z, C.w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (idx + c >= limit) break;
+                float t;
+                if (RMS) {
+                    const double xg = fabs((double)xe[c] * (double)ge[c]);
+                    const double tt = xg * f + k.u * fabs((double)ye[c]);
+                    t = ok ? up32g(tt) : NAN;
+                } else {
+                    const double ad = fabs((double)xe[c] - mu);
+                    const double ep = (double)fabsf(ge[c]) * fma(K1, ad, K0);
+                    t = up32g(fma(k.u, (double)fabsf(ye[c]), ep));
+                }
+                check_one(ce[c], ye[c], t, alpha, eps_rel, hist, rep, acc_chk);
+            }
+        }
+    }
+    __syncthreads();
+    flush_block_stats(acc_chk, red, ws_stats);
+    flush_histogram(hist, ws_hist + (size_t)blockIdx.x * kBins, ws_coarse + blockIdx.x * kGroups);
+}
+
 // ------------------------------------------------------------------ sum / mean
 template <int TPR, int V>
 __global__ __launch_bounds__(kRowThreads) void summean_bound(
@@ -767,6 +873,65 @@ int tao_bound_groupnorm(const float* x, const float* y_ref, const float* gamma, 
     hipLaunchKernelGGL(groupnorm_sums_a, grid, blk, 0, st, x, part, cols, (unsigned)nchunk, vec_ok);
     hipLaunchKernelGGL(groupnorm_sums_b, grid, blk, 0, st, x, part, cols, (unsigned)nchunk, vec_ok, k);
     hipLaunchKernelGGL(groupnorm_apply, grid, blk, 0, st, x, y_ref, gamma, tau, part, cols, (unsigned)nchunk, vec_ok, k, gg);
+    return launch_status();
+}
+
+int tao_bound_check_norm(int kind, const float* x, const float* y_ref, const float* gamma, const float* beta,
+                         double eps, const float* claimed, long rows, long cols, long ld,
+                         double alpha, double eps_rel, const tao_fp_model* model, tao_profile* out,
+                         void* ws, size_t ws_bytes, void* stream) {
+    using namespace tao;
+    (void)beta;
+    tao_fp_model md;
+    int rc = resolve_model(model, &md);
+    if (rc != TAO_OK) return rc;
+    if (kind != TAO_NORM_LAYERNORM && kind != TAO_NORM_RMSNORM) return TAO_ERR_KIND;
+    if (!out || !ws) return out ? TAO_ERR_WORKSPACE : TAO_ERR_NULL;
+    if (rows < 0 || cols < 0 || ld < cols || !(eps >= 0.0) || !std::isfinite(eps)) return TAO_ERR_SHAPE;
+    if (!(alpha >= 0.0) || !std::isfinite(alpha) || !(eps_rel >= 0.0) || !std::isfinite(eps_rel)) return TAO_ERR_SHAPE;
+    const long n = rows * cols;
+    if (rows > 0 && cols > 0 && n / cols != rows) return TAO_ERR_SHAPE;
+    if (n >= (1L << 36)) return TAO_ERR_SHAPE;                      // 32-bit per-workgroup counters
+    if (n > 0 && (!x || !y_ref || !claimed)) return TAO_ERR_NULL;
+    if (!aligned(x, 4) || !aligned(y_ref, 4) || !aligned(claimed, 4) || !aligned(gamma, 4) || !aligned(out, 8))
+        return TAO_ERR_ALIGN;
+    if (!aligned(ws, 256) || ws_bytes < check_workspace_bytes()) return TAO_ERR_WORKSPACE;
+    RowConsts k;
+    rc = make_consts(md, cols > 0 ? cols : 1, eps, &k);
+    if (rc != TAO_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const int vec_ok = aligned(x, 16) && (ld % 4 == 0) && aligned(y_ref, 16) && aligned(claimed, 16);
+    const int vec_g = aligned(gamma, 16);
+    const CheckWorkspace w = carve_check_workspace(ws);
+    int nblocks = 1;
+    const bool rms = kind == TAO_NORM_RMSNORM;
+    auto launch = [&](auto kernel, int tpr, long r, long c, long l) {
+        const long rb = (r + (kCheckThreads / tpr) - 1) / (kCheckThreads / tpr);
+        nblocks = (int)(rb < 1 ? 1 : (rb < kMaxCheckBlocks ? rb : kMaxCheckBlocks));
+        hipLaunchKernelGGL(kernel, dim3(nblocks), dim3(kCheckThreads), 0, st, x, y_ref, gamma, claimed, r, c, l,
+                           vec_ok, vec_g, k, alpha, eps_rel, w.hist, w.coarse, w.stats);
+    };
+    // at most two vectors per thread for RMSNorm and one, up to 1024 columns, for LayerNorm (its
+    // second reduction and the check's binary64 division leave no more room under the 128-register
+    // limit of a 1024-thread workgroup): longer rows take wider groups, or re-read the row
+#define TAO_NORM_CHECK(RMS, TPR, V) launch(norm_check<RMS, TPR, V>, TPR, rows, cols, ld)
+    if (n == 0) {
+        if (rms) launch(norm_check<true, 64, 1>, 64, 0L, 1L, 1L); else launch(norm_check<false, 64, 1>, 64, 0L, 1L, 1L);
+    } else if (rms) {
+        if (cols <= 256)       TAO_NORM_CHECK(true, 64, 1);
+        else if (cols <= 512)  TAO_NORM_CHECK(true, 64, 2);
+        else if (cols <= 1024) TAO_NORM_CHECK(true, 256, 1);
+        else if (cols <= 2048) TAO_NORM_CHECK(true, 256, 2);
+        else if (cols <= 4096) TAO_NORM_CHECK(true, 512, 2);
+        else if (cols <= 8192) TAO_NORM_CHECK(true, 1024, 2);
+        else                   TAO_NORM_CHECK(true, 1024, 0);
+    } else {
+        if (cols <= 256)       TAO_NORM_CHECK(false, 64, 1);
+        else if (cols <= 1024) TAO_NORM_CHECK(false, 256, 1);
+        else                   TAO_NORM_CHECK(false, 1024, 0);     // wider cached rows spill: re-read instead
+    }
+#undef TAO_NORM_CHECK
+    launch_profile_reduce(w, nblocks, (unsigned long long)n, out, st);
     return launch_status();
 }
 

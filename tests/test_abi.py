@@ -117,6 +117,23 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_bound_check_act(1, nul, nul, p, p, -1, 1.0, 0.0, None, p, wsp, cneed, None) == tao.ERR_SHAPE
     assert L.tao_bound_check_act(1, nul, nul, p, p, 10, -1.0, 0.0, None, p, wsp, cneed, None) == tao.ERR_SHAPE
     assert L.tao_bound_check_act(1, nul, nul, p, odd, 10, 1.0, 0.0, None, p, wsp, cneed, None) == tao.ERR_ALIGN
+    fr = lambda x_, y_, c_, rows, d, inner, npos, a, e, o, w_, wn: L.tao_bound_check_rope(x_, p, p, y_, c_, rows, d, inner, npos, 0, a, e, None, o, w_, wn, None)
+    assert fr(p, p, p, 4, 7, 1, 1, 1.0, 0.0, p, wsp, cneed) == tao.ERR_SHAPE          # odd d
+    assert fr(p, p, p, 4, 8, 0, 1, 1.0, 0.0, p, wsp, cneed) == tao.ERR_SHAPE
+    assert fr(p, p, p, 4, 8, 1, 1, 1.0, -1.0, p, wsp, cneed) == tao.ERR_SHAPE
+    assert fr(p, nul, p, 4, 8, 1, 1, 1.0, 0.0, p, wsp, cneed) == tao.ERR_NULL
+    assert fr(p, p, p, 4, 8, 1, 1, 1.0, 0.0, nul, wsp, cneed) == tao.ERR_NULL
+    assert fr(p, p, odd, 4, 8, 1, 1, 1.0, 0.0, p, wsp, cneed) == tao.ERR_ALIGN
+    assert fr(p, p, p, 4, 8, 1, 1, 1.0, 0.0, p, wsp, cneed - 1) == tao.ERR_WORKSPACE
+    fn = lambda kind, x_, y_, c_, rows, cols, ld, a, e, o, w_, wn: L.tao_bound_check_norm(kind, x_, y_, p, p, 1e-5, c_, rows, cols, ld, a, e, None, o, w_, wn, None)
+    assert fn(2, p, p, p, 4, 8, 8, 1.0, 0.0, p, wsp, cneed) == tao.ERR_KIND              # only LayerNorm and RMSNorm
+    assert fn(0, p, p, p, 4, 8, 4, 1.0, 0.0, p, wsp, cneed) == tao.ERR_SHAPE             # ld < cols
+    assert fn(1, p, p, p, 4, 8, 8, 1.0, float("nan"), p, wsp, cneed) == tao.ERR_SHAPE
+    assert fn(1, p, nul, p, 4, 8, 8, 1.0, 0.0, p, wsp, cneed) == tao.ERR_NULL
+    assert fn(1, p, p, p, 4, 8, 8, 1.0, 0.0, nul, wsp, cneed) == tao.ERR_NULL
+    assert fn(0, p, p, odd, 4, 8, 8, 1.0, 0.0, p, wsp, cneed) == tao.ERR_ALIGN
+    assert fn(0, p, p, p, 4, 8, 8, 1.0, 0.0, p, nul, cneed) == tao.ERR_WORKSPACE
+    assert fn(0, p, p, p, 4, 2 ** 24 + 2, 2 ** 24 + 2, 1.0, 0.0, p, wsp, cneed) == tao.ERR_K_RANGE
     # linear
     args = lambda M, N, K, lda, ldw, ldt, tw=0, batch=1: (M, N, K, lda, ldw, ldt, tw, batch, 0, 0, 0)
     assert L.tao_bound_linear(p, p, nul, p, *args(4, 4, 8, 4, 8, 4), None, None) == tao.ERR_SHAPE   # lda < K

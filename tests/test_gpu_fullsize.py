@@ -84,6 +84,14 @@ def _check_ops_sampled(tao, oracle_mod, ops, nsample, seed):
         elif op.kind == "softmax":
             fused = tao.tao_bound_check_softmax(op.args["x"], op.y_ref, op.claimed)
             assert_profile_equal(fused, p, op.name + " (one pass)")
+        elif op.kind in ("layernorm", "rmsnorm"):
+            fused = tao.tao_bound_check_norm({"layernorm": 0, "rmsnorm": 1}[op.kind], op.args["x"], op.y_ref, op.claimed,
+                                             op.args.get("gamma"), op.args.get("beta"), eps=op.attrs["eps"])
+            assert_profile_equal(fused, p, op.name + " (one pass)")
+        elif op.kind == "rope":
+            fused = tao.tao_bound_check_rope(op.args["x"], op.args["cos"], op.args["sin"], op.y_ref.contiguous(),
+                                             op.claimed.contiguous(), inner=op.attrs["inner"])
+            assert_profile_equal(fused, p, op.name + " (one pass)")
         nrows = op.y_ref.shape[-2] if op.kind == "linear" else op.y_ref.numel() // op.y_ref.shape[-1]
         rows = _sample_rows(nrows, nsample, seed + idx)
         batch = (idx % op.args["A"].shape[0]) if (op.kind == "linear" and op.args["A"].dim() == 3) else None

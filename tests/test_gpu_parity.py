@@ -361,6 +361,48 @@ def test_norm_shapes(tao, oracle_mod, kind, rows, cols):
     assert_bound_parity(_np(t_gpu), t_or, "%s %dx%d" % (kind, rows, cols))
 
 
+@pytest.mark.parametrize("kind", ["layernorm", "rmsnorm"])
+@pytest.mark.parametrize("rows,cols", [(1, 1), (5, 3), (300, 256), (17, 500), (130, 768), (257, 1024), (33, 1030),
+                                       (40, 2048), (19, 4096), (6, 5000), (3, 8200), (4, 20000), (5000, 64), (0, 16)])
+def test_norm_bound_checked_in_one_pass(tao, oracle_mod, kind, rows, cols):
+    """tao_bound_check_norm: field for field the profile of tao_bound_norm followed by
+    tao_check_and_profile, and of the oracle's check on the GPU's stored bound; a row without a bound
+    (NaN), planted violations, with and without the affine scale, padded rows."""
+    g = torch.Generator().manual_seed(rows * 131 + cols)
+    ld = cols + (4 if cols % 8 == 0 and cols > 8 else 0)
+    big = torch.randn((rows, ld), generator=g) * 2 + 0.5
+    x = big[:, :cols]
+    gam = 1 + 0.1 * torch.randn((cols,), generator=g)
+    bet = 0.1 * torch.randn((cols,), generator=g)
+    code = {"layernorm": 0, "rmsnorm": 1}[kind]
+    eps = 1e-5
+    xc = x.contiguous()
+    y = (tao_inputs.layernorm_f32(xc, gam, bet, eps) if kind == "layernorm" else tao_inputs.rmsnorm_f32(xc, gam, eps)) if rows else xc.clone()
+    claimed = tao_inputs.ulp_noise(g, y, max_ulps=2) if rows else y.clone()
+    if rows > 2 and cols > 4:
+        claimed[1, 2] = claimed[1, 2] * 1.01 + 0.1          # planted violation
+        claimed[2, 0] = float("nan")
+    if rows > 4 and cols > 4:
+        big[3, 1] = float("nan")                            # a row without a bound
+    pad = lambda t: torch.cat([t, torch.zeros((rows, ld - cols))], dim=1).cuda()[:, :cols] if ld != cols else t.cuda()
+    xg, yg, cg = big.cuda()[:, :cols], pad(y), pad(claimed)
+    for use_g in (True, False):
+        gg, bb = (gam.cuda(), bet.cuda()) if use_g else (None, None)
+        for alpha, eps_rel in ((1.0, 1e-12), (4.0, 1e-6)):
+            fused = tao.tao_bound_check_norm(code, xg, yg, cg, gg, bb, eps=eps, alpha=alpha, eps_rel=eps_rel)
+            if rows:
+                tau = tao.tao_bound_norm(code, xg, yg, gg, bb, eps=eps)
+            else:
+                tau = torch.empty((0, cols), device="cuda")
+            two = tao.tao_check_and_profile(cg.contiguous(), yg.contiguous(), tau.contiguous(), alpha=alpha, eps_rel=eps_rel)
+            assert_profile_equal(fused, two, "%s %dx%d one pass vs two" % (kind, rows, cols))
+            po = oracle_mod.check_and_profile(_np(claimed), _np(y), _np(tau), alpha=alpha, eps_rel=eps_rel)
+            assert_profile_equal(fused, po, "%s %dx%d one pass vs oracle check" % (kind, rows, cols))
+            assert fused["n"] == rows * cols
+    if rows > 4 and cols > 4:
+        assert fused["violations"] >= cols          # the whole NaN-bound row counts as violated
+
+
 def test_norm_failure_rows_and_no_gamma(tao, oracle_mod):
     x = torch.full((3, 64), 3.0); x[1] = torch.arange(64.0); x[2, 5] = float("nan")
     y = torch.zeros((3, 64))
@@ -585,6 +627,24 @@ def test_rope_shapes(tao, oracle_mod, rows, d, inner, npos, interleaved):
     # misaligned base: the scalar path
     xo = torch.cat([torch.zeros(1), x.reshape(-1)]).cuda()[1:].reshape(rows, d)
     assert_bound_parity(_np(tao.tao_bound_rope(xo, cs.cuda(), sn.cuda(), inner=inner, interleaved=interleaved)), t_or, "rope misaligned")
+    # checked in the same pass: the profile of the two separate calls, and of the oracle's check on the stored bound
+    rot = torch.empty_like(x)
+    tpos = (torch.arange(rows) // inner) % npos
+    c_, s_ = cs[tpos], sn[tpos]
+    if interleaved:
+        xa, xb = x[:, 0::2], x[:, 1::2]
+        rot[:, 0::2], rot[:, 1::2] = xa * c_ - xb * s_, xb * c_ + xa * s_
+    else:
+        xa, xb = x[:, : d // 2], x[:, d // 2:]
+        rot[:, : d // 2], rot[:, d // 2:] = xa * c_ - xb * s_, xb * c_ + xa * s_
+    claimed = tao_inputs.ulp_noise(g, rot, max_ulps=1)
+    claimed[0, 0] = claimed[0, 0] + 1.0
+    fused = tao.tao_bound_check_rope(x.cuda(), cs.cuda(), sn.cuda(), rot.cuda(), claimed.cuda(), inner=inner,
+                                     interleaved=interleaved, alpha=2.0)
+    two = tao.tao_check_and_profile(claimed.cuda(), rot.cuda(), t_gpu, alpha=2.0)
+    assert_profile_equal(fused, two, "rope one pass vs two")
+    assert_profile_equal(fused, oracle_mod.check_and_profile(_np(claimed), _np(rot), _np(t_gpu), alpha=2.0), "rope one pass vs oracle check")
+    assert fused["violations"] >= 1 and fused["n"] == rows * d
     mo, mg = oracle_mod.Model(flags=1, mode=1), tao.FpModel(flags=tao.FLAG_UNDERFLOW_TERMS, mode=1)
     assert_bound_parity(_np(tao.tao_bound_rope(x.cuda(), cs.cuda(), sn.cuda(), inner=inner, interleaved=interleaved, model=mg)),
                         oracle_mod.bound_rope(_np(x), _np(cs), _np(sn), inner=inner, interleaved=interleaved, model=mo), "rope flags")
