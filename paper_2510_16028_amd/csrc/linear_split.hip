@@ -141,6 +141,10 @@ struct SplitArgs {
     long ldy, strideY;
     double alpha, eps_rel;
     unsigned int* ws_hist; unsigned int* ws_coarse; BlockStats* ws_stats;
+    // PARTIAL instantiation (the reduction cut into `ksplit` parts of `gpp` groups, one workgroup per
+    // tile and part): binary64 partial sums [part][batch][M][N]
+    unsigned ntiles; int ksplit; long gpp;
+    double* partial;
 };
 
 // check_one with the histogram layout of the CHECK instantiation below (16-bit counters, bin b in
@@ -160,8 +164,12 @@ __device__ __forceinline__ void check_one_packed(float c, float r, float t, doub
 // itself is stored only if p.tau is not NULL.  Workgroups add their counts to one of kMaxCheckBlocks
 // partial results (integer atomics: the sums do not depend on the order), which profile_reduce
 // finishes as it does for the streaming check.
-template <bool CHECK>
+// PARTIAL: launches with fewer tiles than compute units cut the reduction into parts; a workgroup
+// then leaves the binary64 sums of its part in the workspace and split_combine adds the parts and
+// forms (and, if asked, checks) the bound.
+template <bool CHECK, bool PARTIAL = false>
 __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
+    static_assert(!(CHECK && PARTIAL), "the parts are checked by split_combine");
     extern __shared__ __attribute__((aligned(16))) char lds[];
     // CHECK: four copies of the 2048-bin histogram with 16-bit counters (a tile has 16384 elements, so
     // none overflows), two bins to a word and the four copies of a word in consecutive banks: 16 KB,
@@ -176,10 +184,14 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
     const int wm = wave >> 1, wn = wave & 1;                 // 4 x 2 wavefronts, two 32x32 tiles each (along N)
     const int r32 = lane & 31, h = lane >> 5;
 
-    const unsigned t = blockIdx.x;
+    const unsigned t = PARTIAL ? blockIdx.x % p.ntiles : blockIdx.x;
+    const long part = PARTIAL ? blockIdx.x / p.ntiles : 0;
     const unsigned tx = t % p.tiles_n, yz = t / p.tiles_n;
     const long n0 = (long)tx * STILE, m0 = (long)(yz % p.tiles_m) * STILE, z = yz / p.tiles_m;
-    const long ngroup = p.Kp / SBK;
+    // groups [g0, g0 + ngroup) of the reduction
+    const long all_groups = p.Kp / SBK;
+    const long g0 = PARTIAL ? part * p.gpp : 0;
+    const long ngroup = PARTIAL ? (all_groups - g0 < p.gpp ? all_groups - g0 : p.gpp) : all_groups;
 
     // global -> LDS without a stop in registers: the workspace holds, per group and 128-row block,
     // the LDS image of the three pieces (24576 contiguous bytes); every wavefront copies three 1 KB
@@ -190,8 +202,8 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
     const char* srcW = reinterpret_cast<const char*>(p.W3 + z * p.batchW3) + (n0 / STILE) * kBlock + tid * 16;
     const long stepA = blocksA * kBlock, stepW = blocksW * kBlock;            // bytes between groups
     auto request = [&](char* stage, long g) __attribute__((always_inline)) {
-        const char* a = srcA + g * stepA;
-        const char* w = srcW + g * stepW;
+        const char* a = srcA + (g0 + g) * stepA;
+        const char* w = srcW + (g0 + g) * stepW;
         // (written as assembly: the compiler would otherwise wait for all outstanding copies before
         // every barrier, which is exactly the overlap this pipeline exists for; the waits are the
         // explicit s_waitcnt instructions below)
@@ -321,6 +333,7 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
 
     // epilogue: D[i][j] of a 32x32 tile sits in lane (j + 32*((i/4)%2)), register 4*(i/8) + i%4
     float* __restrict__ T = p.tau ? p.tau + z * p.strideT : nullptr;
+    const long nbatch = PARTIAL ? (long)(p.ntiles / (p.tiles_n * p.tiles_m)) : 1;
     ThreadAcc acc;
 #pragma unroll
     for (int tj = 0; tj < 2; ++tj) {
@@ -329,6 +342,10 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const long row = m0 + wm * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
+            if (PARTIAL) {
+                if (row < p.M && col < p.N) p.partial[((part * nbatch + z) * p.M + row) * p.N + col] = S[tj][v];
+                continue;
+            }
             if (row < p.M && col < p.N) {
                 const double sv = S[tj][v];
                 const double tt = p.c * (sv * p.infl + ab) * kGuard + p.uflow;
@@ -369,6 +386,38 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
             if (nn) atomicAdd(&st->nans, (unsigned long long)nn);
             if (mx) atomicMax(&st->max_bits, mx);
         }
+    }
+}
+
+// Adds the parts of a PARTIAL launch in a fixed order and forms the bound exactly as the epilogue
+// above does; CHECK: checks it on the spot, in the structure of the streaming check pass.
+template <bool CHECK>
+__global__ __launch_bounds__(kCheckThreads) void split_combine(SplitArgs p, long batch) {
+    __shared__ unsigned int hist[CHECK ? kBins * kReplicas : 1];
+    __shared__ unsigned int red[CHECK ? 3 * (kCheckThreads / kWave) : 1];
+    if (CHECK) {
+        for (int i = threadIdx.x; i < kBins * kReplicas; i += kCheckThreads) hist[i] = 0;
+        __syncthreads();
+    }
+    ThreadAcc acc;
+    const int rep = threadIdx.x & (kReplicas - 1);
+    const long per = p.M * p.N, total = per * batch;
+    for (long i = (long)blockIdx.x * kCheckThreads + threadIdx.x; i < total; i += (long)gridDim.x * kCheckThreads) {
+        const long z = i / per, rc = i - z * per, row = rc / p.N, col = rc - row * p.N;
+        double sv = 0.0;
+        for (int k = 0; k < p.ksplit; ++k) sv += p.partial[(long)k * total + i];
+        const double ab = p.bias ? fabs((double)p.bias[col]) : 0.0;
+        const double tt = p.c * (sv * p.infl + ab) * kGuard + p.uflow;
+        const float t32 = up32(tt);
+        if (p.tau) p.tau[z * p.strideT + row * p.ldt + col] = t32;
+        if (CHECK) {
+            const long y = z * p.strideY + row * p.ldy + col;
+            check_one(p.claimed[y], p.ref[y], t32, p.alpha, p.eps_rel, hist, rep, acc);
+        }
+    }
+    if (CHECK) {
+        flush_block_stats(acc, red, p.ws_stats);
+        flush_histogram(hist, p.ws_hist + (size_t)blockIdx.x * kBins, p.ws_coarse + blockIdx.x * kGroups);
     }
 }
 
@@ -495,30 +544,59 @@ int tao_selftest_matrix_core_bf16(unsigned* report, void* stream) {
     return TAO_OK;
 }
 
+}  // extern "C"
+
+namespace tao {
+inline size_t round_up_256(size_t b) { return (b + 255) / 256 * 256; }
+static int device_cus() {
+    int dev = 0, cus = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    return cus;
+}
+// Parts the reduction is cut into: launches with fewer 128 x 128 tiles than compute units take as
+// many parts as fill the chip, each at least 16 groups (512 k-steps) long.
+static int split_k_parts(long M, long N, long K, long batch) {
+    if (M <= 0 || N <= 0 || K <= 0 || batch <= 0) return 1;
+    const long tiles = ((M + STILE - 1) / STILE) * ((N + STILE - 1) / STILE) * batch;
+    const long groups = (K + SBK - 1) / SBK;
+    const long cus = device_cus();
+    if (tiles >= cus) return 1;
+    long parts = cus / tiles;
+    if (parts > groups / 16) parts = groups / 16;
+    if (parts > 16) parts = 16;
+    return parts < 2 ? 1 : (int)parts;
+}
+}  // namespace tao
+
+extern "C" {
+
 size_t tao_linear_split_workspace_bytes(long M, long N, long K, long batch, int shared_w) {
     if (M <= 0 || N <= 0 || K < 0 || batch <= 0) return 0;
     const long Kp = (K + tao::SBK - 1) / tao::SBK * tao::SBK;
     const __int128 blocks = (__int128)(Kp / tao::SBK) *
                             ((__int128)((M + tao::STILE - 1) / tao::STILE) * batch + (__int128)((N + tao::STILE - 1) / tao::STILE) * (shared_w ? 1 : batch));
     if (blocks * tao::kBlock + 512 >= ((__int128)1 << 62)) return 0;
-    return (size_t)(blocks * tao::kBlock) + 512;
+    const size_t operands = (size_t)(blocks * tao::kBlock) + 512;
+    // binary64 partial sums of a reduction cut into parts (launches that would not fill the chip)
+    const int parts = tao::split_k_parts(M, N, K, batch);
+    if (parts < 2) return operands;
+    return tao::round_up_256(operands) + (size_t)parts * (size_t)batch * (size_t)M * (size_t)N * sizeof(double);
 }
 
 int tao_linear_split_preferred(long M, long N, long K, long batch) {
     // The BF16 path has one tile shape (128 x 128) and pays a pre-pass of 10 bytes per operand
     // element: it wins when the tiles fill the chip and each operand slab is shared by at least
     // two of them (measured: 1.2 - 1.4 x on such shapes, slower on 128-column or half-empty launches).
+    // Launches with fewer tiles than compute units cut the reduction into parts; they count when the
+    // parts fill the chip.
     if (M <= 0 || N <= 0 || K <= 0 || batch <= 0) return 0;
-    int dev = 0, cus = 256;
-    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     const long tiles = ((M + tao::STILE - 1) / tao::STILE) * ((N + tao::STILE - 1) / tao::STILE) * batch;
-    return tiles >= cus && M >= 2 * tao::STILE && N >= 2 * tao::STILE && K >= 64;
+    return tiles * tao::split_k_parts(M, N, K, batch) >= tao::device_cus() && M >= 2 * tao::STILE && N >= 2 * tao::STILE && K >= 64;
 }
 
 }  // extern "C"
 
 namespace tao {
-inline size_t round_up_256(size_t b) { return (b + 255) / 256 * 256; }
 // The fused check: NULL for the plain bound.
 struct SplitCheckHost {
     const float* claimed; const float* ref; long ldy, strideY; double alpha, eps_rel; tao_profile* out;
@@ -580,6 +658,7 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
     const long blocksA = (M + STILE - 1) / STILE, blocksW = (N + STILE - 1) / STILE;
     const size_t bytesA = (size_t)(Kp / SBK) * blocksA * kBlock * batch;          // a multiple of 256
     unsigned short* W3 = reinterpret_cast<unsigned short*>(static_cast<char*>(ws) + bytesA);
+    const size_t bytesW3 = (size_t)(Kp / SBK) * blocksW * kBlock * (shared_w ? 1 : batch);
     if (K > 0) {
         auto blocks_for = [](long rows, long kp, bool trans) {
             // work items of split3_bf16: (row, chunk) pairs, or whole 64-row x 256-k patches of 2048
@@ -609,7 +688,7 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
     const double u = md.u;
     // lower factor of the accumulation: (1 - 11.5u) for the matrix-core steps (10u main, 1.44u
     // cross, rounded up), 2^-53 per binary64 addition (three per 32 k-steps and output element)
-    const double f64 = (double)(3 * (Kp / SBK) + 4);
+    const double f64 = (double)(3 * (Kp / SBK) + 4 + 16);             // + the additions of up to 16 parts
     const double lower = (1.0 - 11.5 * u) * (1.0 - f64 * 0x1p-53);
     p.infl = widen(1.0 / (lower * (1.0 - 0x1p-52)));
     p.uflow = (md.flags & TAO_FLAG_UNDERFLOW_TERMS) ? (double)Kp_ * 0x1p-149 : 0.0;
@@ -622,21 +701,46 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
         if (e == hipSuccess)
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split<true>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split<false, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e != hipSuccess) { g_last_hip_error = (int)e; return TAO_ERR_LAUNCH; }
         configured = true;
     }
     p.claimed = nullptr; p.ref = nullptr; p.ldy = 0; p.strideY = 0; p.alpha = 0.0; p.eps_rel = 0.0;
     p.ws_hist = nullptr; p.ws_coarse = nullptr; p.ws_stats = nullptr;
-    if (!chk) {
-        hipLaunchKernelGGL(absgemm_split<false>, dim3((unsigned)ntiles), dim3(kSplitThreads), lds_bytes, st, p);
+    p.ntiles = (unsigned)ntiles; p.ksplit = 1; p.gpp = Kp / SBK; p.partial = nullptr;
+    if (chk) {
+        p.claimed = chk->claimed; p.ref = chk->ref; p.ldy = chk->ldy; p.strideY = chk->strideY;
+        p.alpha = chk->alpha; p.eps_rel = chk->eps_rel;
+        p.ws_hist = cw.hist; p.ws_coarse = cw.coarse; p.ws_stats = cw.stats;
+    }
+    const int parts = split_k_parts(M, N, K, batch);
+    if (parts >= 2) {
+        // the reduction in parts, then one pass that adds them and forms (and checks) the bound
+        const long groups = Kp / SBK;
+        p.ksplit = parts; p.gpp = (groups + parts - 1) / parts;
+        p.ksplit = (int)((groups + p.gpp - 1) / p.gpp);             // no empty part
+        p.partial = reinterpret_cast<double*>(static_cast<char*>(ws) + round_up_256((size_t)bytesA + bytesW3 + 512));
+        hipLaunchKernelGGL((absgemm_split<false, true>), dim3((unsigned)(ntiles * p.ksplit)), dim3(kSplitThreads), lds_bytes, st, p);
+        const long total = M * N * batch;
+        long want = (total + (long)kCheckThreads * 8 - 1) / ((long)kCheckThreads * 8);
+        const int nblocks = (int)(want < 1 ? 1 : (want > kMaxCheckBlocks ? kMaxCheckBlocks : want));
+        if (chk) {
+            hipLaunchKernelGGL(split_combine<true>, dim3(nblocks), dim3(kCheckThreads), 0, st, p, batch);
+            launch_profile_reduce(cw, nblocks, (unsigned long long)total, chk->out, st);
+        } else {
+            hipLaunchKernelGGL(split_combine<false>, dim3(nblocks), dim3(kCheckThreads), 0, st, p, batch);
+        }
         return launch_status();
     }
-    p.claimed = chk->claimed; p.ref = chk->ref; p.ldy = chk->ldy; p.strideY = chk->strideY;
-    p.alpha = chk->alpha; p.eps_rel = chk->eps_rel;
-    p.ws_hist = cw.hist; p.ws_coarse = cw.coarse; p.ws_stats = cw.stats;
+    if (!chk) {
+        hipLaunchKernelGGL((absgemm_split<false>), dim3((unsigned)ntiles), dim3(kSplitThreads), lds_bytes, st, p);
+        return launch_status();
+    }
     const int slots = (int)(ntiles < kMaxCheckBlocks ? ntiles : kMaxCheckBlocks);
     hipLaunchKernelGGL(zero_words, dim3(64), dim3(256), 0, st, cw.hist, (long)(check_workspace_bytes() / 4));
-    hipLaunchKernelGGL(absgemm_split<true>, dim3((unsigned)ntiles), dim3(kSplitThreads), lds_bytes, st, p);
+    hipLaunchKernelGGL((absgemm_split<true>), dim3((unsigned)ntiles), dim3(kSplitThreads), lds_bytes, st, p);
     launch_profile_reduce(cw, slots, (unsigned long long)((__int128)M * N * batch), chk->out, st);
     return launch_status();
 }

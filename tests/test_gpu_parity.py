@@ -190,7 +190,10 @@ def test_conv2d_accepts_a_real_convolution(tao, oracle_mod):
     (1, 1, 1, False, False, 1), (1, 5, 7, True, False, 1), (129, 257, 49, True, False, 1),
     (130, 64, 601, False, True, 1), (33, 200, 48, True, True, 3), (256, 128, 96, False, False, 2),
     (5, 3, 0, True, False, 1), (70, 130, 13, False, False, 1), (512, 384, 2048, True, False, 1),
-    (2048, 256, 64, False, True, 2), (384, 384, 1088, True, False, 3)])
+    (2048, 256, 64, False, True, 2), (384, 384, 1088, True, False, 3),
+    # fewer tiles than compute units and a long reduction: cut into parts (the first, K = 2048, and the
+    # one before are too), parts of unequal length, the shape of configuration 3's k/v projections
+    (200, 300, 1500, True, False, 1), (2048, 1024, 4096, False, False, 1)])
 def test_linear_split_shapes(tao, oracle_mod, M, N, K, bias, trans_w, batch):
     """The BF16-split path against the oracle, every element (same tolerance as the FP32 path)."""
     g = torch.Generator().manual_seed(M * 1000 + N * 10 + K + 5)
@@ -446,6 +449,7 @@ def test_softmax_bound_checked_in_one_pass(tao, oracle_mod, rows, cols):
     (129, 257, 100, True, True, 1), (300, 200, 64, False, False, 3), (64, 640, 0, True, False, 1),
     (700, 390, 513, True, False, 2), (1024, 1152, 256, False, True, 1),     # 72 tiles: several per slot of the partials
     (4200, 1100, 96, True, False, 1),                                         # 297 tiles: more tiles than partial results
+    (512, 384, 2048, True, False, 1), (300, 260, 1100, False, True, 2),       # reduction cut into parts: checked by the combining pass
     (0, 16, 8, False, False, 1),
 ])
 def test_matmul_bound_checked_in_the_epilogue(tao, oracle_mod, M, N, K, bias, trans_w, batch):
