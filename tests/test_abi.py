@@ -149,6 +149,15 @@ def test_argument_validation_without_a_gpu(tao):
     wsb = L.tao_linear_split_workspace_bytes(4, 4, 8, 1, 1)
     assert wsb == 2 * 24576 + 512 and L.tao_linear_split_workspace_bytes(0, 4, 8, 1, 1) == 0
     assert L.tao_linear_split_workspace_bytes(300, 129, 33, 2, 0) == 2 * (3 + 2) * 2 * 24576 + 512
+    # fewer tiles than compute units (256 assumed without a device) and a long reduction: the reduction is
+    # cut into parts whose binary64 partial sums follow the operands in the workspace
+    operands = (4096 // 32) * (16 + 8) * 24576 + 512
+    assert L.tao_linear_split_workspace_bytes(2048, 1024, 4096, 1, 1) == (operands + 255) // 256 * 256 + 2 * 2048 * 1024 * 8
+    assert L.tao_linear_split_workspace_bytes(2048, 4096, 4096, 1, 1) == (4096 // 32) * (16 + 32) * 24576 + 512   # 512 tiles: one part
+    assert L.tao_linear_split_workspace_bytes(2048, 1024, 256, 1, 1) == (256 // 32) * (16 + 8) * 24576 + 512     # too short to cut
+    L.tao_linear_split_preferred.restype = ctypes.c_int
+    assert L.tao_linear_split_preferred(2048, 1024, 4096, 1) == 1 and L.tao_linear_split_preferred(2048, 4096, 4096, 1) == 1
+    assert L.tao_linear_split_preferred(8192, 128, 2048, 8) == 0 and L.tao_linear_split_preferred(512, 1024, 1024, 1) == 0
     big = ctypes.c_void_p(0x100000)
     assert L.tao_bound_linear_split(p, p, nul, p, *args(4, 4, 8, 4, 8, 4), None, big, wsb, None) == tao.ERR_SHAPE
     assert L.tao_bound_linear_split(p, p, nul, p, *args(4, 4, 8, 8, 8, 4), None, nul, wsb, None) == tao.ERR_WORKSPACE
