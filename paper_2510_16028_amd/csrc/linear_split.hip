@@ -151,7 +151,7 @@ struct SplitArgs {
 // half b & 1 of word (b >> 1) * 4 + copy).
 __device__ __forceinline__ void check_one_packed(float c, float r, float t, double alpha, double eps_rel,
                                                  unsigned int* hist, int copy, ThreadAcc& acc) {
-    const CheckedElement o = check_arith(c, r, t, alpha, eps_rel);
+    const CheckedElement o = check_arith<false>(c, r, t, alpha, eps_rel);
     acc.violations += o.violation;
     acc.nans += o.is_nan;
     if (!o.is_nan) acc.max_bits = max(acc.max_bits, o.bits);

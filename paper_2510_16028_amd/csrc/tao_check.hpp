@@ -27,13 +27,16 @@ struct ThreadAcc {
 // value that equals the re-executed one bit for bit (and is finite) has d = 0 exactly, so the error is
 // 0 (NaN for 0/0) without the binary64 division; whole wavefronts of such elements -- the masked
 // half of a causal softmax, exact operators -- skip the division's instructions altogether.
+// SHORTCUT = false leaves the test out: straight-line code, which a caller that unrolls many elements
+// (the matrix kernel's epilogue) wants more than the shortcut.
 struct CheckedElement { bool violation, is_nan; unsigned int bin, bits; };
+template <bool SHORTCUT = true>
 __device__ __forceinline__ CheckedElement check_arith(float c, float r, float t, double alpha, double eps_rel) {
     CheckedElement o;
     const double rd = (double)r;
     const double T = alpha * (double)t;
     const double den = fabs(rd) + eps_rel;
-    if (c == r && fabsf(c) != INFINITY) {
+    if (SHORTCUT && c == r && fabsf(c) != INFINITY) {
         o.violation = !(0.0 <= T);
         o.is_nan = !(den > 0.0);                             // 0/0
         o.bits = 0u;
