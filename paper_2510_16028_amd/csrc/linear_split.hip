@@ -49,7 +49,6 @@ constexpr int kSlab = STILE * SROW;     // one operand, one piece
 constexpr int kBlock = 3 * kSlab;       // one operand, three pieces: 24576 bytes, contiguous in the workspace
 constexpr int kSplitStage = 2 * kBlock; // |A| hi, mid, lo, |W| hi, mid, lo: 49152 bytes
 constexpr int kSplitStages = 3;         // 144 KB of LDS
-constexpr int kBandCols = 16;           // column tiles per band of the tile order
 
 #define TAO_MFMA_BF16(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
 
@@ -146,6 +145,8 @@ struct SplitArgs {
     // tile and part): binary64 partial sums [part][batch][M][N]
     unsigned ntiles; int ksplit; long gpp;
     double* partial;
+    // workgroup -> tile: slots per super-tile (8 patches of ph x pw tiles), per batch entry, patches side by side
+    unsigned slots, slots_per_z, super_rows, pw, ph, npx;
 };
 
 // check_one with the histogram layout of the CHECK instantiation below (16-bit counters, bin b in
@@ -177,29 +178,31 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
     // all the LDS the stages leave.  The copy is chosen by the lane; errors crowd into a few bins, and
     // a single copy serialised the workgroup's atomics.
     __shared__ unsigned int chk_hist[CHECK ? kBins * 2 : 1];
-    if (CHECK) {
-        for (int i = threadIdx.x; i < kBins * 2; i += kSplitThreads) chk_hist[i] = 0;
-        __syncthreads();
-    }
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;                 // 4 x 2 wavefronts, two 32x32 tiles each (along N)
     const int r32 = lane & 31, h = lane >> 5;
 
-    const unsigned t = PARTIAL ? blockIdx.x % p.ntiles : blockIdx.x;
+    const unsigned t = PARTIAL ? blockIdx.x % p.ntiles : blockIdx.x;     // ntiles: slots of all batch entries
     const long part = PARTIAL ? blockIdx.x / p.ntiles : 0;
-    // Tiles are taken in bands of kBandCols columns, rows running down a band: the 256 tiles in flight
-    // then cover about 16 x 16 blocks of the output and read 16 + 16 operand blocks per group, instead
-    // of a few rows times every column, which re-read all of W for every wave of tiles (8192^3: 8.47
-    // -> 8.04 ms).  Dealing the tiles of such a square to the eight XCDs in 4 x 8 patches cut the L2
-    // fills by another third (FETCH_SIZE 14.5 -> 9.7 GB) but not the time, and starves XCDs on
-    // outputs narrower than a band: not kept.
-    const unsigned per_z = p.tiles_n * p.tiles_m;
-    const unsigned tz = t / per_z, tr = t - tz * per_z;
-    const unsigned band = tr / (kBandCols * p.tiles_m), in_band = tr - band * (kBandCols * p.tiles_m);
-    const unsigned first_col = band * kBandCols;
-    const unsigned gw = p.tiles_n - first_col < (unsigned)kBandCols ? p.tiles_n - first_col : (unsigned)kBandCols;
-    const unsigned ty = in_band / gw, tx = first_col + (in_band - ty * gw);
-    const long n0 = (long)tx * STILE, m0 = (long)ty * STILE, z = tz;
+    // Workgroup -> tile.  The output is walked in super-tiles of up to 16 x 16 tiles (column bands of
+    // 16, rows running down a band): the workgroups in flight then read about 16 + 16 operand blocks
+    // per group instead of a few rows times every column, which re-read all of W for every wave of
+    // tiles.  Workgroups are dealt round-robin to the eight XCDs, each with its own L2: a super-tile is
+    // cut into eight patches (ph rows x pw columns, npx of them side by side) and XCD x takes patch x,
+    // so its tiles share ph + pw blocks (4 + 8 for a full super-tile).  Slots that fall beyond the
+    // output's edge belong to no tile: those workgroups leave at once.
+    const unsigned zp = t / p.slots_per_z, bb = t - zp * p.slots_per_z;
+    const unsigned sup = bb / p.slots, w8 = bb - sup * p.slots;
+    const unsigned xcd = w8 & 7u, j = w8 >> 3;
+    const unsigned ly = (xcd / p.npx) * p.ph + j / p.pw, lx = (xcd % p.npx) * p.pw + j % p.pw;
+    const unsigned sband = sup / p.super_rows, srow = sup - sband * p.super_rows;
+    const unsigned ty = srow * 16u + ly, tx = sband * 16u + lx;
+    if (ly >= 16u || lx >= 16u || ty >= p.tiles_m || tx >= p.tiles_n) return;      // whole workgroup
+    const long n0 = (long)tx * STILE, m0 = (long)ty * STILE, z = zp;
+    if (CHECK) {
+        for (int i = threadIdx.x; i < kBins * 2; i += kSplitThreads) chk_hist[i] = 0;
+        __syncthreads();
+    }
     // groups [g0, g0 + ngroup) of the reduction
     const long all_groups = p.Kp / SBK;
     const long g0 = PARTIAL ? part * p.gpp : 0;
@@ -345,7 +348,7 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
 
     // epilogue: D[i][j] of a 32x32 tile sits in lane (j + 32*((i/4)%2)), register 4*(i/8) + i%4
     float* __restrict__ T = p.tau ? p.tau + z * p.strideT : nullptr;
-    const long nbatch = PARTIAL ? (long)(p.ntiles / (p.tiles_n * p.tiles_m)) : 1;
+    const long nbatch = PARTIAL ? (long)(p.ntiles / p.slots_per_z) : 1;
     ThreadAcc acc;
 #pragma unroll
     for (int tj = 0; tj < 2; ++tj) {
@@ -721,7 +724,20 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
     }
     p.claimed = nullptr; p.ref = nullptr; p.ldy = 0; p.strideY = 0; p.alpha = 0.0; p.eps_rel = 0.0;
     p.ws_hist = nullptr; p.ws_coarse = nullptr; p.ws_stats = nullptr;
-    p.ntiles = (unsigned)ntiles; p.ksplit = 1; p.gpp = Kp / SBK; p.partial = nullptr;
+    p.ksplit = 1; p.gpp = Kp / SBK; p.partial = nullptr;
+    {
+        const unsigned gw = (unsigned)(tiles_n < 16 ? tiles_n : 16), gh = (unsigned)(tiles_m < 16 ? tiles_m : 16);
+        p.pw = gw < 8 ? gw : 8;
+        p.npx = (gw + p.pw - 1) / p.pw;                              // 1 or 2
+        const unsigned npy = 8 / p.npx;
+        p.ph = (gh + npy - 1) / npy;
+        p.slots = 8 * p.ph * p.pw;
+        p.super_rows = (unsigned)((tiles_m + 15) / 16);
+        const long per_z = (long)p.super_rows * ((tiles_n + 15) / 16) * p.slots;
+        if (per_z * batch * 16 >= (1L << 31)) return TAO_ERR_SHAPE;
+        p.slots_per_z = (unsigned)per_z;
+        p.ntiles = (unsigned)(per_z * batch);                        // workgroups of one part
+    }
     if (chk) {
         p.claimed = chk->claimed; p.ref = chk->ref; p.ldy = chk->ldy; p.strideY = chk->strideY;
         p.alpha = chk->alpha; p.eps_rel = chk->eps_rel;
@@ -734,7 +750,7 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
         p.ksplit = parts; p.gpp = (groups + parts - 1) / parts;
         p.ksplit = (int)((groups + p.gpp - 1) / p.gpp);             // no empty part
         p.partial = reinterpret_cast<double*>(static_cast<char*>(ws) + round_up_256((size_t)bytesA + bytesW3 + 512));
-        hipLaunchKernelGGL((absgemm_split<false, true>), dim3((unsigned)(ntiles * p.ksplit)), dim3(kSplitThreads), lds_bytes, st, p);
+        hipLaunchKernelGGL((absgemm_split<false, true>), dim3(p.ntiles * (unsigned)p.ksplit), dim3(kSplitThreads), lds_bytes, st, p);
         const long total = M * N * batch;
         long want = (total + (long)kCheckThreads * 8 - 1) / ((long)kCheckThreads * 8);
         const int nblocks = (int)(want < 1 ? 1 : (want > kMaxCheckBlocks ? kMaxCheckBlocks : want));
@@ -747,12 +763,12 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
         return launch_status();
     }
     if (!chk) {
-        hipLaunchKernelGGL((absgemm_split<false>), dim3((unsigned)ntiles), dim3(kSplitThreads), lds_bytes, st, p);
+        hipLaunchKernelGGL((absgemm_split<false>), dim3(p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
         return launch_status();
     }
-    const int slots = (int)(ntiles < kMaxCheckBlocks ? ntiles : kMaxCheckBlocks);
+    const int slots = kMaxCheckBlocks;                       // workgroup b adds to partial result b % 256
     hipLaunchKernelGGL(zero_words, dim3(64), dim3(256), 0, st, cw.hist, (long)(check_workspace_bytes() / 4));
-    hipLaunchKernelGGL((absgemm_split<true>), dim3((unsigned)ntiles), dim3(kSplitThreads), lds_bytes, st, p);
+    hipLaunchKernelGGL((absgemm_split<true>), dim3(p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
     launch_profile_reduce(cw, slots, (unsigned long long)((__int128)M * N * batch), chk->out, st);
     return launch_status();
 }
