@@ -49,6 +49,8 @@ constexpr int kSlab = STILE * SROW;     // one operand, one piece
 constexpr int kBlock = 3 * kSlab;       // one operand, three pieces: 24576 bytes, contiguous in the workspace
 constexpr int kSplitStage = 2 * kBlock; // |A| hi, mid, lo, |W| hi, mid, lo: 49152 bytes
 constexpr int kSplitStages = 3;         // 144 KB of LDS
+constexpr long kWalkMaxGroups = 32;     // reductions up to 1024 k-steps walk their tiles ...
+constexpr int kWalkMinTilesPerCu = 4;   // ... when a compute unit has at least this many
 
 #define TAO_MFMA_BF16(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
 
@@ -169,9 +171,13 @@ __device__ __forceinline__ void check_one_packed(float c, float r, float t, doub
 // PARTIAL: launches with fewer tiles than compute units cut the reduction into parts; a workgroup
 // then leaves the binary64 sums of its part in the workspace and split_combine adds the parts and
 // forms (and, if asked, checks) the bound.
-template <bool CHECK, bool PARTIAL = false>
+// WALK: the plain bound as the host launches it.  A workgroup takes the slots blockIdx.x,
+// + gridDim.x, ... and its pipeline of slabs runs on across the tile boundaries: with a workgroup
+// per slot that is one tile, with a workgroup per compute unit (short reductions) a walk over many.
+template <bool CHECK, bool PARTIAL = false, bool WALK = false>
 __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
     static_assert(!(CHECK && PARTIAL), "the parts are checked by split_combine");
+    static_assert(!(WALK && (CHECK || PARTIAL)), "only the plain bound walks tiles");
     extern __shared__ __attribute__((aligned(16))) char lds[];
     // CHECK: four copies of the 2048-bin histogram with 16-bit counters (a tile has 16384 elements, so
     // none overflows), two bins to a word and the four copies of a word in consecutive banks: 16 KB,
@@ -182,23 +188,34 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
     const int wm = wave >> 1, wn = wave & 1;                 // 4 x 2 wavefronts, two 32x32 tiles each (along N)
     const int r32 = lane & 31, h = lane >> 5;
 
-    const unsigned t = PARTIAL ? blockIdx.x % p.ntiles : blockIdx.x;     // ntiles: slots of all batch entries
-    const long part = PARTIAL ? blockIdx.x / p.ntiles : 0;
-    // Workgroup -> tile.  The output is walked in super-tiles of up to 16 x 16 tiles (column bands of
+    // Workgroup -> tiles.  The output is walked in super-tiles of up to 16 x 16 tiles (column bands of
     // 16, rows running down a band): the workgroups in flight then read about 16 + 16 operand blocks
     // per group instead of a few rows times every column, which re-read all of W for every wave of
     // tiles.  Workgroups are dealt round-robin to the eight XCDs, each with its own L2: a super-tile is
     // cut into eight patches (ph rows x pw columns, npx of them side by side) and XCD x takes patch x,
     // so its tiles share ph + pw blocks (4 + 8 for a full super-tile).  Slots that fall beyond the
-    // output's edge belong to no tile: those workgroups leave at once.
-    const unsigned zp = t / p.slots_per_z, bb = t - zp * p.slots_per_z;
-    const unsigned sup = bb / p.slots, w8 = bb - sup * p.slots;
-    const unsigned xcd = w8 & 7u, j = w8 >> 3;
-    const unsigned ly = (xcd / p.npx) * p.ph + j / p.pw, lx = (xcd % p.npx) * p.pw + j % p.pw;
-    const unsigned sband = sup / p.super_rows, srow = sup - sband * p.super_rows;
-    const unsigned ty = srow * 16u + ly, tx = sband * 16u + lx;
-    if (ly >= 16u || lx >= 16u || ty >= p.tiles_m || tx >= p.tiles_n) return;      // whole workgroup
-    const long n0 = (long)tx * STILE, m0 = (long)ty * STILE, z = zp;
+    // output's edge belong to no tile.  (A walk's stride is a multiple of 8, so a workgroup stays
+    // with its XCD's patches.)  CHECK and PARTIAL launches have one workgroup per slot (and part).
+    const long part = PARTIAL ? blockIdx.x / p.ntiles : 0;
+    unsigned m0 = 0, n0 = 0, z = 0;                          // first row and column of the tile, batch entry
+    auto locate = [&](unsigned t, unsigned& tm0, unsigned& tn0, unsigned& tz) __attribute__((always_inline)) -> bool {
+        const unsigned zp = t / p.slots_per_z, bb = t - zp * p.slots_per_z;
+        const unsigned sup = bb / p.slots, w8 = bb - sup * p.slots;
+        const unsigned xcd = w8 & 7u, j = w8 >> 3;
+        const unsigned ly = (xcd / p.npx) * p.ph + j / p.pw, lx = (xcd % p.npx) * p.pw + j % p.pw;
+        const unsigned sband = sup / p.super_rows, srow = sup - sband * p.super_rows;
+        const unsigned ty = srow * 16u + ly, tx = sband * 16u + lx;
+        tn0 = tx * STILE; tm0 = ty * STILE; tz = zp;
+        return ly < 16u && lx < 16u && ty < p.tiles_m && tx < p.tiles_n;
+    };
+    // first slot at or after t (stepping by the grid) that holds a tile; p.ntiles if there is none
+    auto next_tile = [&](unsigned t, unsigned& tm0, unsigned& tn0, unsigned& tz) __attribute__((always_inline)) -> unsigned {
+        if (!WALK) return (t < p.ntiles && locate(t, tm0, tn0, tz)) ? t : p.ntiles;
+        while (t < p.ntiles && !locate(t, tm0, tn0, tz)) t += gridDim.x;
+        return t < p.ntiles ? t : p.ntiles;
+    };
+    unsigned t = next_tile(PARTIAL ? blockIdx.x % p.ntiles : blockIdx.x, m0, n0, z);
+    if (t >= p.ntiles) return;                               // whole workgroup
     if (CHECK) {
         for (int i = threadIdx.x; i < kBins * 2; i += kSplitThreads) chk_hist[i] = 0;
         __syncthreads();
@@ -213,12 +230,10 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
     // pieces of it per operand with 16-byte loads that write lane i's data at the wavefront's LDS
     // base + 16 i.
     const long blocksA = (p.M + STILE - 1) / STILE, blocksW = (p.N + STILE - 1) / STILE;
-    const char* srcA = reinterpret_cast<const char*>(p.A3 + z * p.batchA3) + (m0 / STILE) * kBlock + tid * 16;
-    const char* srcW = reinterpret_cast<const char*>(p.W3 + z * p.batchW3) + (n0 / STILE) * kBlock + tid * 16;
     const long stepA = blocksA * kBlock, stepW = blocksW * kBlock;            // bytes between groups
-    auto request = [&](char* stage, long g) __attribute__((always_inline)) {
-        const char* a = srcA + (g0 + g) * stepA;
-        const char* w = srcW + (g0 + g) * stepW;
+    auto request = [&](char* stage, unsigned tm0, unsigned tn0, unsigned tz, long g) __attribute__((always_inline)) {
+        const char* a = reinterpret_cast<const char*>(p.A3 + (long)tz * p.batchA3) + (long)(tm0 / STILE) * kBlock + tid * 16 + (g0 + g) * stepA;
+        const char* w = reinterpret_cast<const char*>(p.W3 + (long)tz * p.batchW3) + (long)(tn0 / STILE) * kBlock + tid * 16 + (g0 + g) * stepW;
         // (written as assembly: the compiler would otherwise wait for all outstanding copies before
         // every barrier, which is exactly the overlap this pipeline exists for; the waits are the
         // explicit s_waitcnt instructions below)
@@ -300,94 +315,147 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
         }
     };
 
-    // Three LDS stages.  Slab j is requested at the top of group j - 2 into stage j % 3 and used in
-    // group j.  At the top of a group a wavefront waits until only its six youngest requests (slab
-    // j + 1) are outstanding, so its part of slab j has landed; the barrier then publishes the
-    // slab and separates the last reads of stage (j + 2) % 3 (group j - 1) from its next fill.
-    if (ngroup > 0) request(lds, 0);
-    if (ngroup > 1) request(lds + kSplitStage, 1);
+    // Three LDS stages.  The slabs of a workgroup's tiles form one sequence: slab j of it is requested
+    // at the top of group j - 2 into stage j % 3 and used in group j, so the first two slabs of the
+    // next tile are on their way while this tile's last groups and its epilogue run.  At the top of
+    // a group a wavefront waits until only its six youngest requests (slab j + 1) are outstanding,
+    // so its part of slab j has landed; the barrier then publishes the slab and separates the last
+    // reads of stage (j + 2) % 3 (group j - 1) from its next fill.  The first group of a later tile
+    // waits for everything instead: the epilogue before it has issued loads, stores and atomics of
+    // its own, which count in the same counter.
+    if (ngroup > 0) request(lds, m0, n0, z, 0);
+    if (ngroup > 1) request(lds + kSplitStage, m0, n0, z, 1);
     int cur = 0;
+    bool first = true;
+    ThreadAcc acc;
+    const long nbatch = PARTIAL ? (long)(p.ntiles / p.slots_per_z) : 1;
 #pragma unroll 1
-    for (long g = 0; g + 1 < ngroup; ++g) {
-        __builtin_amdgcn_s_waitcnt(0x0F76);                  // vmcnt(6)
-        __syncthreads();
-        const int nxt2 = cur == 0 ? 2 : cur - 1;              // (cur + 2) % 3
-        if (g + 2 < ngroup) request(lds + nxt2 * kSplitStage, g + 2);
-        compute(lds + cur * kSplitStage);
-        cur = cur == 2 ? 0 : cur + 1;
-    }
-    // CHECK: the tile's claimed and re-executed values, requested before the last group so that their
-    // latency passes under its arithmetic.  Element (tj, v) of a lane: row m0 + wm*32 + 8*(v/4) + 4*h + v%4,
-    // column n0 + wn*64 + tj*32 + r32 (the accumulator layout of a 32x32 tile).
-    const float* __restrict__ Cl = CHECK ? p.claimed + z * p.strideY : nullptr;
-    const float* __restrict__ Rf = CHECK ? p.ref + z * p.strideY : nullptr;
-    float pc[CHECK ? 2 : 1][CHECK ? 16 : 1], pr[CHECK ? 2 : 1][CHECK ? 16 : 1];
-    auto prefetch_claims = [&]() __attribute__((always_inline)) {
-#pragma unroll
-        for (int tj = 0; tj < 2; ++tj) {
-            const long col = n0 + wn * 64 + tj * 32 + r32;
+    for (;;) {
+        float pc[CHECK ? 2 : 1][CHECK ? 16 : 1], pr[CHECK ? 2 : 1][CHECK ? 16 : 1];
+        unsigned m1 = 0, n1 = 0, z1 = 0;
+        const unsigned tnext = WALK ? next_tile(t + gridDim.x, m1, n1, z1) : p.ntiles;
+        const bool more = WALK && tnext < p.ntiles;          // (the host walks tiles only if ngroup >= 2)
+        // CHECK: the tile's claimed and re-executed values, requested before the last group so that their
+        // latency passes under its arithmetic (the first 32-column half; the second half is requested
+        // after that group, keeping 32 registers free during it).  Element (tj, v) of a lane: row m0 + wm*32 + 8*(v/4) + 4*h + v%4,
+        // column n0 + wn*64 + tj*32 + r32 (the accumulator layout of a 32x32 tile).
+        const float* __restrict__ Cl = CHECK ? p.claimed + (long)z * p.strideY : nullptr;
+        const float* __restrict__ Rf = CHECK ? p.ref + (long)z * p.strideY : nullptr;
+        // (Rows and columns beyond the edge read the edge's element instead: the epilogue does not
+        // use them.  The empty asm statements keep the address arithmetic at the point of use: hoisted
+        // out of the loops it would occupy a hundred registers through the whole reduction.)
+        auto prefetch_claims = [&](int tj) __attribute__((always_inline)) {
+            unsigned mo = m0, no = n0;
+            int lrow = wm * 32 + 4 * h, lcol = wn * 64 + r32;
+            asm volatile("" : "+s"(mo), "+s"(no), "+v"(lrow), "+v"(lcol));
+            const long col = (long)no + lcol + tj * 32;
+            const long colc = col < p.N ? col : p.N - 1;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
-                const long row = m0 + wm * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-                const bool in = row < p.M && col < p.N;
-                pc[tj][v] = in ? Cl[row * p.ldy + col] : 0.f;
-                pr[tj][v] = in ? Rf[row * p.ldy + col] : 0.f;
+                const long row = (long)mo + lrow + 8 * (v >> 2) + (v & 3);
+                const long rowc = row < p.M ? row : p.M - 1;
+                pc[tj][v] = Cl[rowc * p.ldy + colc];
+                pr[tj][v] = Rf[rowc * p.ldy + colc];
+            }
+        };
+        // (the last group stands apart from the loop: the registers of the prefetched values are then
+        // occupied in that copy of the arithmetic only)
+#pragma unroll 1
+        for (long g = 0; g + 1 < ngroup; ++g) {
+            if (g == 0 && !first) __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
+            else                  __builtin_amdgcn_s_waitcnt(0x0F76);      // vmcnt(6)
+            __syncthreads();
+            const int nxt2 = cur == 0 ? 2 : cur - 1;          // (cur + 2) % 3
+            if (g + 2 < ngroup)  request(lds + nxt2 * kSplitStage, m0, n0, z, g + 2);
+            else if (more)       request(lds + nxt2 * kSplitStage, m1, n1, z1, 0);
+            compute(lds + cur * kSplitStage);
+            cur = cur == 2 ? 0 : cur + 1;
+        }
+        float bias_c[2] = {0.f, 0.f};
+        if (!PARTIAL && p.bias) {
+#pragma unroll
+            for (int tj = 0; tj < 2; ++tj) {
+                const long col = (long)n0 + wn * 64 + tj * 32 + r32;
+                bias_c[tj] = p.bias[col < p.N ? col : p.N - 1];
             }
         }
-    };
-    if (ngroup > 0) {
-        __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0)
-        __syncthreads();
-        if (CHECK) prefetch_claims();
-        compute(lds + cur * kSplitStage);
-    } else if (CHECK) {
-        prefetch_claims();
-    }
-    fold(S[1], D[1]);                                        // what the last part left unfolded
-    fold(S[1], X[1]);
+        if (ngroup > 0) {
+            if ((ngroup == 1 && !first) || !more) __builtin_amdgcn_s_waitcnt(0x0F70);
+            else                                  __builtin_amdgcn_s_waitcnt(0x0F76);
+            __syncthreads();
+            const int nxt2 = cur == 0 ? 2 : cur - 1;
+            if (more) request(lds + nxt2 * kSplitStage, m1, n1, z1, 1);
+            if (CHECK) prefetch_claims(0);
+            compute(lds + cur * kSplitStage);
+            cur = cur == 2 ? 0 : cur + 1;
+        } else if (CHECK) {
+            prefetch_claims(0);
+        }
+        if (CHECK) prefetch_claims(1);                       // the second half passes under the first half's check
+        fold(S[1], D[1]);                                    // what the last part left unfolded
+        fold(S[1], X[1]);
 
-    // epilogue: D[i][j] of a 32x32 tile sits in lane (j + 32*((i/4)%2)), register 4*(i/8) + i%4
-    float* __restrict__ T = p.tau ? p.tau + z * p.strideT : nullptr;
-    const long nbatch = PARTIAL ? (long)(p.ntiles / p.slots_per_z) : 1;
-    ThreadAcc acc;
+        // epilogue: D[i][j] of a 32x32 tile sits in lane (j + 32*((i/4)%2)), register 4*(i/8) + i%4
+        float* __restrict__ T = p.tau ? p.tau + (long)z * p.strideT : nullptr;
+        unsigned me = m0, ne = n0;
+        int erow = wm * 32 + 4 * h, ecol = wn * 64 + r32;
+        asm volatile("" : "+s"(me), "+s"(ne), "+v"(erow), "+v"(ecol));     // (as above)
 #pragma unroll
-    for (int tj = 0; tj < 2; ++tj) {
-        const long col = n0 + wn * 64 + tj * 32 + r32;
-        const double ab = (p.bias && col < p.N) ? fabs((double)p.bias[col]) : 0.0;
+        for (int tj = 0; tj < 2; ++tj) {
+            const long col = (long)ne + ecol + tj * 32;
+            const double ab = fabs((double)bias_c[tj]);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const long row = m0 + wm * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
-            if (PARTIAL) {
-                if (row < p.M && col < p.N) p.partial[((part * nbatch + z) * p.M + row) * p.N + col] = S[tj][v];
-                continue;
-            }
-            if (row < p.M && col < p.N) {
-                const double sv = S[tj][v];
-                const double tt = p.c * (sv * p.infl + ab) * kGuard + p.uflow;
-                const float t32 = up32(tt);
-                if (!CHECK) {
-                    T[row * p.ldt + col] = t32;
-                } else {
-                    if (T) T[row * p.ldt + col] = t32;
-                    check_one_packed(pc[tj][v], pr[tj][v], t32, p.alpha, p.eps_rel, chk_hist, lane & 3, acc);
+            for (int v = 0; v < 16; ++v) {
+                const long row = (long)me + erow + 8 * (v >> 2) + (v & 3);
+                if (PARTIAL) {
+                    if (row < p.M && col < p.N) p.partial[((part * nbatch + z) * p.M + row) * p.N + col] = S[tj][v];
+                    continue;
+                }
+                if (row < p.M && col < p.N) {
+                    const double sv = S[tj][v];
+                    const double tt = p.c * (sv * p.infl + ab) * kGuard + p.uflow;
+                    const float t32 = up32(tt);
+                    if (!CHECK) {
+                        T[row * p.ldt + col] = t32;
+                    } else {
+                        if (T) T[row * p.ldt + col] = t32;
+                        check_one_packed(pc[tj][v], pr[tj][v], t32, p.alpha, p.eps_rel, chk_hist, lane & 3, acc);
+                    }
                 }
             }
         }
+        if (CHECK) {
+            __syncthreads();
+            const unsigned slot = blockIdx.x % (unsigned)kMaxCheckBlocks;
+            // non-empty bins to the slot's partial histogram; a wavefront covers one group of 64 bins and
+            // clears the words it has read (lanes b and b ^ 1 share four words: two each), so the next
+            // tile starts from zero: its groups' barriers lie between this and its own epilogue
+            for (int b = tid; b < kBins; b += kSplitThreads) {
+                unsigned int cnt = 0;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) cnt += (chk_hist[(b >> 1) * 4 + c] >> (16 * (b & 1))) & 0xffffu;
+                if (more) { chk_hist[(b >> 1) * 4 + 2 * (b & 1)] = 0; chk_hist[(b >> 1) * 4 + 2 * (b & 1) + 1] = 0; }
+                if (cnt) atomicAdd(&p.ws_hist[(size_t)slot * kBins + b], cnt);
+                unsigned int gsum = cnt;
+#pragma unroll
+                for (int o = kWave / 2; o > 0; o >>= 1) gsum += __shfl_xor(gsum, o, kWave);
+                if (lane == 0 && gsum) atomicAdd(&p.ws_coarse[slot * kGroups + b / kBinsPerReduceBlock], gsum);
+            }
+        }
+        if (!more) break;
+        // Everything this tile has in flight ends here (the next tile's first two slabs were requested
+        // long ago): prefetched values of elements beyond the edge are never read, and the compiler
+        // would otherwise guard the registers they were meant for inside the next tile's groups.
+        __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0)
+        t = tnext; m0 = m1; n0 = n1; z = z1; first = false;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+#pragma unroll
+            for (int tj = 0; tj < 2; ++tj) { S[tj][v] = 0.0; X[tj][v] = 0.f; D[tj][v] = 0.f; }
+        }
     }
     if (CHECK) {
-        __syncthreads();
         const unsigned slot = blockIdx.x % (unsigned)kMaxCheckBlocks;
-        // non-empty bins to the slot's partial histogram; a wavefront covers one group of 64 bins
-        for (int b = tid; b < kBins; b += kSplitThreads) {
-            unsigned int cnt = 0;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) cnt += (chk_hist[(b >> 1) * 4 + c] >> (16 * (b & 1))) & 0xffffu;
-            if (cnt) atomicAdd(&p.ws_hist[(size_t)slot * kBins + b], cnt);
-            unsigned int gsum = cnt;
-#pragma unroll
-            for (int o = kWave / 2; o > 0; o >>= 1) gsum += __shfl_xor(gsum, o, kWave);
-            if (lane == 0 && gsum) atomicAdd(&p.ws_coarse[slot * kGroups + b / kBinsPerReduceBlock], gsum);
-        }
         unsigned int vio = acc.violations, nn = acc.nans, mx = acc.max_bits;
 #pragma unroll
         for (int o = kWave / 2; o > 0; o >>= 1) {
@@ -711,7 +779,7 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
     static bool configured = false;
     constexpr int lds_bytes = kSplitStages * kSplitStage;
     if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split<false>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split<false, false, true>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
         if (e == hipSuccess)
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split<true>),
@@ -763,7 +831,17 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
         return launch_status();
     }
     if (!chk) {
-        hipLaunchKernelGGL((absgemm_split<false>), dim3(p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
+        // One workgroup per slot; short reductions with many tiles per compute unit instead walk their
+        // tiles with one workgroup per compute unit (a multiple of 8, so a workgroup stays with its
+        // XCD's patches), which takes the launch of a workgroup and the latency of its first slabs off
+        // the critical path of every tile.  (Long reductions lose more to the fixed assignment of
+        // tiles than they gain; the checking instantiation's epilogue is arithmetic that a walk
+        // cannot hide.)  The walk needs two groups per tile.
+        const long groups = Kp / SBK;
+        const unsigned cus = (unsigned)device_cus() & ~7u;
+        const bool walk = groups >= 2 && groups <= kWalkMaxGroups && cus >= 8 && (long)p.ntiles >= (long)kWalkMinTilesPerCu * cus;
+        // (one instantiation for both: with a workgroup per slot its walk ends after the first tile)
+        hipLaunchKernelGGL((absgemm_split<false, false, true>), dim3(walk ? cus : p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
         return launch_status();
     }
     const int slots = kMaxCheckBlocks;                       // workgroup b adds to partial result b % 256

@@ -193,7 +193,10 @@ def test_conv2d_accepts_a_real_convolution(tao, oracle_mod):
     (2048, 256, 64, False, True, 2), (384, 384, 1088, True, False, 3),
     # fewer tiles than compute units and a long reduction: cut into parts (the first, K = 2048, and the
     # one before are too), parts of unequal length, the shape of configuration 3's k/v projections
-    (200, 300, 1500, True, False, 1), (2048, 1024, 4096, False, False, 1)])
+    (200, 300, 1500, True, False, 1), (2048, 1024, 4096, False, False, 1),
+    # short reductions with many tiles per compute unit: a workgroup walks several tiles (ragged edges,
+    # so many of its slots hold no tile; the second has the shortest reduction that walks)
+    (2100, 1500, 100, True, False, 6), (1100, 2300, 40, False, True, 4)])
 def test_linear_split_shapes(tao, oracle_mod, M, N, K, bias, trans_w, batch):
     """The BF16-split path against the oracle, every element (same tolerance as the FP32 path)."""
     g = torch.Generator().manual_seed(M * 1000 + N * 10 + K + 5)
@@ -451,6 +454,7 @@ def test_softmax_bound_checked_in_one_pass(tao, oracle_mod, rows, cols):
     (4200, 1100, 96, True, False, 1),                                         # 297 tiles: more tiles than partial results
     (512, 384, 2048, True, False, 1), (300, 260, 1100, False, True, 2),       # reduction cut into parts: checked by the combining pass
     (0, 16, 8, False, False, 1),
+    (2100, 1500, 100, True, False, 6), (1100, 2300, 40, False, True, 4),      # workgroups that walk several tiles
 ])
 def test_matmul_bound_checked_in_the_epilogue(tao, oracle_mod, M, N, K, bias, trans_w, batch):
     """tao_bound_check_linear: field for field the profile of tao_bound_linear_split followed by
