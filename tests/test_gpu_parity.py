@@ -447,6 +447,34 @@ def test_softmax_bound_checked_in_one_pass(tao, oracle_mod, rows, cols):
         assert fused["violations"] > 0
 
 
+def test_split_tile_walk_against_one_workgroup_per_tile(tao):
+    """Seeded shapes with short reductions and many tiles: the plain split bound walks its tiles
+    (one workgroup per compute unit, slots beyond the ragged edges skipped), the checking launch
+    takes one workgroup per slot; the bounds both store must be the same bits."""
+    rng = np.random.default_rng(4711)
+    for case in range(10):
+        batch = int(rng.integers(4, 9))
+        K = int(rng.integers(33, 1025))
+        # at least 4 * 256 slots, so that the walk is taken on a 256-CU device: 280 to 450 tiles per
+        # batch entry, ragged in both directions
+        tm = int(rng.integers(10, 29)); tn = int(rng.integers(280, 450)) // tm + 1
+        M = tm * 128 - int(rng.integers(0, 128)); N = tn * 128 - int(rng.integers(0, 128))
+        assert batch * tm * tn >= 1100
+        trans_w = bool(rng.integers(0, 2)); bias = bool(rng.integers(0, 2))
+        g = torch.Generator().manual_seed(9000 + case)
+        A = (torch.randn((batch, M, K), generator=g) * torch.exp(torch.randn((batch, M, 1), generator=g))).cuda()
+        W = torch.randn((batch, K, N) if trans_w else (batch, N, K), generator=g).cuda()
+        b = torch.randn((N,), generator=g).cuda() if bias else None
+        walked = tao.tao_bound_linear_split(A, W, b, trans_w=trans_w)
+        y = torch.zeros((batch, M, N), device="cuda")
+        per_slot = torch.empty_like(y)
+        tao.tao_bound_check_linear(A, W, b, y, y, trans_w=trans_w, tau_out=per_slot)
+        torch.cuda.synchronize()
+        same = torch.equal(walked.view(torch.int32), per_slot.view(torch.int32))
+        assert same, "case %d: M=%d N=%d K=%d batch=%d trans_w=%s bias=%s" % (case, M, N, K, batch, trans_w, bias)
+        print("case %d: M=%d N=%d K=%d batch=%d identical" % (case, M, N, K, batch), flush=True)
+
+
 @pytest.mark.parametrize("M,N,K,bias,trans_w,batch", [
     (1, 1, 1, False, False, 1), (5, 7, 3, True, False, 1), (128, 128, 32, False, False, 1),
     (129, 257, 100, True, True, 1), (300, 200, 64, False, False, 3), (64, 640, 0, True, False, 1),
