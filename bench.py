@@ -307,7 +307,9 @@ def main():
             paths[nm] = {"ops": [p.name for p in sel], "TFLOP/s": fl / (ms * 1e-3) / 1e12,
                          "issued_TFLOP/s": mult * fl / (ms * 1e-3) / 1e12, "issued_frac_of_own_peak": mult * fl / (ms * 1e-3) / 1e12 / peak}
     roofline = {"bound": "mfma", "kernel": "absgemm_split + absgemm_bound" if sp else "absgemm_bound",
-                "check_in_epilogue": [p.name for p in lin if p.fused],
+                # operators that go through tao_bound_check_linear: their launches (and this figure) contain the
+                # check -- in the matrix kernel's epilogue, or as the streaming pass where the reduction is short
+                "check_inside": [p.name for p in lin if p.fused],
                 "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "paths": paths,
                 "traffic": measured_traffic("absgemm" if sp else "absgemm_bound") if args.scale == 1 else None,

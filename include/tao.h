@@ -149,7 +149,9 @@ int tao_linear_split_preferred(long M, long N, long K, long batch);
  * *out receives exactly what tao_check_and_profile(claimed, y_ref, tau, ...) would return for the
  * tau that tao_bound_linear_split computes from the same operands, but tau is compared in registers
  * in the matrix kernel's epilogue and only stored when `tau` is not NULL (layout ldy / strideY, like
- * y_ref and claimed: M x N per batch entry, ldy >= N).
+ * y_ref and claimed: M x N per batch entry, ldy >= N).  Where the epilogue would cost more than it
+ * saves -- reductions shorter than 256 with contiguous outputs -- the bound is stored instead (into
+ * `tau`, else into the workspace) and the streaming check reads it: the same result, sooner.
  * y_ref: the verifier's re-executed output, claimed: the proposer's.  out: DEVICE, fully overwritten,
  * valid once the stream has drained.  ws / ws_bytes: DEVICE scratch of at least
  * tao_bound_check_linear_workspace_bytes(...), 256-byte aligned.  Runs the BF16-split kernel for every

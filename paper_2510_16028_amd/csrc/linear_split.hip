@@ -49,6 +49,7 @@ constexpr int kSlab = STILE * SROW;     // one operand, one piece
 constexpr int kBlock = 3 * kSlab;       // one operand, three pieces: 24576 bytes, contiguous in the workspace
 constexpr int kSplitStage = 2 * kBlock; // |A| hi, mid, lo, |W| hi, mid, lo: 49152 bytes
 constexpr int kSplitStages = 3;         // 144 KB of LDS
+constexpr long kEpilogueCheckMinK = 256; // shorter reductions: the bound is stored and the streaming check reads it (see split_run)
 constexpr long kWalkMaxGroups = 32;     // reductions up to 1024 k-steps walk their tiles ...
 constexpr int kWalkMinTilesPerCu = 4;   // ... when a compute unit has at least this many
 
@@ -706,6 +707,7 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
     const size_t need_split = K > 0 ? round_up_256(tao_linear_split_workspace_bytes(M, N, K, batch,
                                                    ((strideW == 0) || batch == 1) ? 1 : 0)) : 0;
     CheckWorkspace cw = {};
+    bool two_pass = false;
     if (chk) {
         if (!chk->out) return TAO_ERR_NULL;
         if (!aligned(chk->out, 8)) return TAO_ERR_ALIGN;
@@ -714,6 +716,19 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
         if ((__int128)M * N * batch >= ((__int128)1 << 36)) return TAO_ERR_SHAPE;   // 32-bit partial counters
         if (!ws || !aligned(ws, 256) || ws_bytes < need_split + check_workspace_bytes()) return TAO_ERR_WORKSPACE;
         cw = carve_check_workspace(static_cast<char*>(ws) + need_split);
+        // Short reductions: in the epilogue the check is arithmetic that nothing overlaps (about 70
+        // instructions per element on a compute unit whose matrix cores idle meanwhile), as long as
+        // the reduction itself up to K = 128; the streaming check spends the same arithmetic under
+        // its loads.  There the bound is stored (in the workspace unless the caller wants it) and
+        // checked by that pass: the same results, field for field, sooner.
+        two_pass = K < kEpilogueCheckMinK && chk->ldy == N && (batch == 1 || chk->strideY == M * N);
+        if (two_pass && !tau && M > 0 && N > 0 && batch > 0) {
+            const size_t off = need_split + round_up_256(check_workspace_bytes());
+            const size_t stored = round_up_256((size_t)M * N * batch * 4);      // (M N batch < 2^36, checked above)
+            if (stored > ws_bytes || ws_bytes - stored < off) return TAO_ERR_WORKSPACE;
+            tau = reinterpret_cast<float*>(static_cast<char*>(ws) + off);
+            ldt = N; strideT = M * N;
+        }
     }
     if (M == 0 || N == 0 || batch == 0) {
         if (chk) {                                           // the profile of an empty tensor
@@ -806,11 +821,19 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
         p.slots_per_z = (unsigned)per_z;
         p.ntiles = (unsigned)(per_z * batch);                        // workgroups of one part
     }
-    if (chk) {
+    const SplitCheckHost* epi = two_pass ? nullptr : chk;      // the check inside these launches, if any
+    if (epi) {
         p.claimed = chk->claimed; p.ref = chk->ref; p.ldy = chk->ldy; p.strideY = chk->strideY;
         p.alpha = chk->alpha; p.eps_rel = chk->eps_rel;
         p.ws_hist = cw.hist; p.ws_coarse = cw.coarse; p.ws_stats = cw.stats;
     }
+    // the streaming check of a stored bound, after the launches that store it
+    auto then_check = [&]() -> int {
+        const int lrc = launch_status();
+        if (lrc != TAO_OK || !two_pass) return lrc;
+        return tao_check_and_profile(chk->claimed, chk->ref, tau, M * N * batch, chk->alpha, chk->eps_rel, chk->out,
+                                     static_cast<char*>(ws) + need_split, check_workspace_bytes(), stream);
+    };
     const int parts = split_k_parts(M, N, K, batch);
     if (parts >= 2) {
         // the reduction in parts, then one pass that adds them and forms (and checks) the bound
@@ -822,15 +845,15 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
         const long total = M * N * batch;
         long want = (total + (long)kCheckThreads * 8 - 1) / ((long)kCheckThreads * 8);
         const int nblocks = (int)(want < 1 ? 1 : (want > kMaxCheckBlocks ? kMaxCheckBlocks : want));
-        if (chk) {
+        if (epi) {
             hipLaunchKernelGGL(split_combine<true>, dim3(nblocks), dim3(kCheckThreads), 0, st, p, batch);
             launch_profile_reduce(cw, nblocks, (unsigned long long)total, chk->out, st);
         } else {
             hipLaunchKernelGGL(split_combine<false>, dim3(nblocks), dim3(kCheckThreads), 0, st, p, batch);
         }
-        return launch_status();
+        return then_check();
     }
-    if (!chk) {
+    if (!epi) {
         // One workgroup per slot; short reductions with many tiles per compute unit instead walk their
         // tiles with one workgroup per compute unit (a multiple of 8, so a workgroup stays with its
         // XCD's patches), which takes the launch of a workgroup and the latency of its first slabs off
@@ -842,7 +865,7 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
         const bool walk = groups >= 2 && groups <= kWalkMaxGroups && cus >= 8 && (long)p.ntiles >= (long)kWalkMinTilesPerCu * cus;
         // (one instantiation for both: with a workgroup per slot its walk ends after the first tile)
         hipLaunchKernelGGL((absgemm_split<false, false, true>), dim3(walk ? cus : p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
-        return launch_status();
+        return then_check();
     }
     const int slots = kMaxCheckBlocks;                       // workgroup b adds to partial result b % 256
     hipLaunchKernelGGL(zero_words, dim3(64), dim3(256), 0, st, cw.hist, (long)(check_workspace_bytes() / 4));
@@ -865,7 +888,9 @@ int tao_bound_linear_split(const float* A, const float* W, const float* bias, fl
 size_t tao_bound_check_linear_workspace_bytes(long M, long N, long K, long batch, int shared_w) {
     const size_t split = K > 0 ? tao_linear_split_workspace_bytes(M, N, K, batch, shared_w) : 0;
     if (K > 0 && split == 0) return 0;
-    return tao::round_up_256(split) + tao::check_workspace_bytes();
+    // (reductions shorter than kEpilogueCheckMinK: room for the stored bound behind the check's workspace)
+    const size_t stored = (K < tao::kEpilogueCheckMinK && M > 0 && N > 0 && batch > 0) ? tao::round_up_256((size_t)M * N * batch * 4) : 0;
+    return tao::round_up_256(split) + tao::round_up_256(tao::check_workspace_bytes()) + stored;
 }
 
 int tao_bound_check_linear(const float* A, const float* W, const float* bias, const float* y_ref,

@@ -168,7 +168,10 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_bound_linear_split(nul, nul, nul, nul, *args(0, 4, 8, 8, 8, 4), None, nul, 0, None) == tao.OK
     # ... and with the check fused into the epilogue
     cwb = L.tao_bound_check_linear_workspace_bytes(4, 4, 8, 1, 1)
-    assert cwb == (wsb + 255) // 256 * 256 + L.tao_check_workspace_bytes(16)
+    # (a reduction shorter than 256: room for the stored bound, 4 x 4 x 4 bytes rounded to 256)
+    assert cwb == (wsb + 255) // 256 * 256 + L.tao_check_workspace_bytes(16) + 256
+    wsb_long = L.tao_linear_split_workspace_bytes(4, 4, 512, 1, 1)
+    assert L.tao_bound_check_linear_workspace_bytes(4, 4, 512, 1, 1) == (wsb_long + 255) // 256 * 256 + L.tao_check_workspace_bytes(16)
     fc = lambda a, w, y, c, t, dims, alpha, out, wsp, wsn: L.tao_bound_check_linear(a, w, nul, y, c, t, *dims, alpha, 0.0, None, out, wsp, wsn, None)
     ok = args(4, 4, 8, 8, 8, 4)
     assert fc(p, p, p, p, nul, args(4, 4, 8, 4, 8, 4), 1.0, p, big, cwb) == tao.ERR_SHAPE        # lda < K
