@@ -447,6 +447,41 @@ def test_softmax_bound_checked_in_one_pass(tao, oracle_mod, rows, cols):
         assert fused["violations"] > 0
 
 
+@pytest.mark.parametrize("M,N,K,batch", [(300, 200, 64, 2), (260, 390, 320, 2), (129, 70, 1100, 1)])
+def test_matmul_check_with_padded_outputs(tao, M, N, K, batch):
+    """y_ref, claimed and tau with a leading dimension beyond N and a batch stride beyond M ldy, through
+    the C ABI: the same profile and the same bound as for contiguous tensors (short reductions take the
+    epilogue route here, since the streaming check needs contiguous outputs)."""
+    import paper_2510_16028_amd as binding
+    g = torch.Generator().manual_seed(31 * M + N + K)
+    A = torch.randn((batch, M, K), generator=g).cuda()
+    W = torch.randn((batch, N, K), generator=g).cuda()
+    y = torch.bmm(A, W.transpose(1, 2)).contiguous()
+    claimed = (y * (1.0 + 3e-4 * torch.randn(y.shape, generator=g).cuda())).contiguous()
+    tau_c = torch.empty_like(y)
+    want = tao.tao_bound_check_linear(A, W, None, y, claimed, tau_out=tau_c)
+    ldy, pad_rows = N + 8, 3
+    sY = (M + pad_rows) * ldy
+    def padded(t):
+        buf = torch.full((batch, M + pad_rows, ldy), float("nan"), device="cuda")
+        buf[:, :M, :N] = t
+        return buf
+    yp, cp = padded(y), padded(claimed)
+    tp = torch.full((batch, M + pad_rows, ldy), -1.0, device="cuda")
+    out = tao.new_profile_buffer(A.device)
+    nbytes = tao.tao_bound_check_linear_workspace_bytes(M, N, K, batch, False)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    rc = binding.lib().tao_bound_check_linear(
+        A.data_ptr(), W.data_ptr(), None, yp.data_ptr(), cp.data_ptr(), tp.data_ptr(),
+        M, N, K, K, K, ldy, 0, batch, M * K, N * K, sY, 1.0, 1e-12, None, out.data_ptr(), ws.data_ptr(), nbytes, None)
+    assert rc == 0
+    torch.cuda.synchronize()
+    got = tao.read_profile(out)
+    assert_profile_equal(got, want, "padded outputs %s" % ((M, N, K, batch),))
+    assert torch.equal(tp[:, :M, :N].contiguous().view(torch.int32), tau_c.view(torch.int32))
+    assert bool((tp[:, :, N:] == -1.0).all()) and bool((tp[:, M:, :] == -1.0).all())      # nothing written outside
+
+
 def test_split_tile_walk_against_one_workgroup_per_tile(tao):
     """Seeded shapes with short reductions and many tiles: the plain split bound walks its tiles
     (one workgroup per compute unit, slots beyond the ragged edges skipped), the checking launch
