@@ -428,14 +428,12 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
         if (CHECK) {
             __syncthreads();
             const unsigned slot = blockIdx.x % (unsigned)kMaxCheckBlocks;
-            // non-empty bins to the slot's partial histogram; a wavefront covers one group of 64 bins and
-            // clears the words it has read (lanes b and b ^ 1 share four words: two each), so the next
-            // tile starts from zero: its groups' barriers lie between this and its own epilogue
+            // non-empty bins to the slot's partial histogram; a wavefront covers one group of 64 bins
+            // (a checking workgroup has one tile, so the histogram is not cleared again)
             for (int b = tid; b < kBins; b += kSplitThreads) {
                 unsigned int cnt = 0;
 #pragma unroll
                 for (int c = 0; c < 4; ++c) cnt += (chk_hist[(b >> 1) * 4 + c] >> (16 * (b & 1))) & 0xffffu;
-                if (more) { chk_hist[(b >> 1) * 4 + 2 * (b & 1)] = 0; chk_hist[(b >> 1) * 4 + 2 * (b & 1) + 1] = 0; }
                 if (cnt) atomicAdd(&p.ws_hist[(size_t)slot * kBins + b], cnt);
                 unsigned int gsum = cnt;
 #pragma unroll
@@ -445,8 +443,7 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
         }
         if (!more) break;
         // Everything this tile has in flight ends here (the next tile's first two slabs were requested
-        // long ago): prefetched values of elements beyond the edge are never read, and the compiler
-        // would otherwise guard the registers they were meant for inside the next tile's groups.
+        // long ago), so that no load or store of this tile counts in the next tile's waits.
         __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0)
         t = tnext; m0 = m1; n0 = n1; z = z1; first = false;
 #pragma unroll
