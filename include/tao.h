@@ -164,6 +164,10 @@ int tao_bound_check_linear(const float *A, const float *W, const float *bias, co
                            double alpha, double eps_rel, const tao_fp_model *model, tao_profile *out,
                            void *ws, size_t ws_bytes, void *stream);
 size_t tao_bound_check_linear_workspace_bytes(long M, long N, long K, long batch, int shared_w);
+/* 1 if tao_bound_check_linear checks a product of this shape (contiguous outputs) in the matrix
+ * kernel's epilogue, 0 if it stores the bound and runs the streaming check.  Host only: for callers
+ * that time or schedule the two kernels separately. */
+int tao_bound_check_linear_in_epilogue(long M, long N, long K, long batch);
 /* Probes v_mfma_f32_32x32x16_bf16 with 3072 seeded non-negative cases and compares every result
  * with the exact integer model the inflation of tao_bound_linear_split rests on.  *report (HOST):
  * bit 0 every case reproduced bit for bit; bit 1 every result from a zero accumulator within

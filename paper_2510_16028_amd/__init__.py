@@ -92,7 +92,7 @@ class TaoError(RuntimeError):
 
 
 EXPORTS = ["tao_default_model", "tao_gamma", "tao_bound_linear", "tao_bound_linear_split",
-           "tao_linear_split_workspace_bytes", "tao_linear_split_preferred",
+           "tao_linear_split_workspace_bytes", "tao_linear_split_preferred", "tao_bound_check_linear_in_epilogue",
            "tao_bound_check_linear", "tao_bound_check_linear_workspace_bytes", "tao_selftest_matrix_core_bf16", "tao_bound_conv2d", "tao_bound_softmax",
            "tao_bound_norm", "tao_bound_groupnorm", "tao_groupnorm_workspace_bytes", "tao_bound_act", "tao_bound_check_act", "tao_bound_rope", "tao_bound_check_rope", "tao_bound_check_norm", "tao_check_and_profile",
            "tao_check_workspace_bytes", "tao_bound_check_softmax", "tao_profile_errors", "tao_profile_workspace_bytes",
@@ -131,6 +131,7 @@ def lib():
     L.tao_linear_split_workspace_bytes.argtypes = [lg, lg, lg, lg, ctypes.c_int]
     L.tao_linear_split_workspace_bytes.restype = ctypes.c_size_t
     L.tao_linear_split_preferred.argtypes = [lg, lg, lg, lg]
+    L.tao_bound_check_linear_in_epilogue.argtypes = [lg, lg, lg, lg]
     L.tao_selftest_matrix_core_bf16.argtypes = [ctypes.POINTER(ctypes.c_uint), vp]
     L.tao_bound_conv2d.argtypes = [vp, vp, vp, vp] + [lg] * 13 + [mp, vp]
     L.tao_bound_softmax.argtypes = [vp, vp, vp, lg, lg, lg, mp, vp]
@@ -292,6 +293,11 @@ def tao_bound_linear_split(A, W, bias=None, trans_w=False, model=None, out=None,
                                       _ptr(ws), ws.numel(), _stream())
     _check(rc, "tao_bound_linear_split")
     return out
+
+
+def tao_bound_check_linear_in_epilogue(M, N, K, batch=1):
+    _torch()
+    return bool(lib().tao_bound_check_linear_in_epilogue(int(M), int(N), int(K), int(batch)))
 
 
 def tao_bound_check_linear_workspace_bytes(M, N, K, batch=1, shared_w=True):

@@ -890,6 +890,11 @@ size_t tao_bound_check_linear_workspace_bytes(long M, long N, long K, long batch
     return tao::round_up_256(split) + tao::round_up_256(tao::check_workspace_bytes()) + stored;
 }
 
+int tao_bound_check_linear_in_epilogue(long M, long N, long K, long batch) {
+    (void)M; (void)N; (void)batch;
+    return K >= tao::kEpilogueCheckMinK ? 1 : 0;
+}
+
 int tao_bound_check_linear(const float* A, const float* W, const float* bias, const float* y_ref,
                            const float* claimed, float* tau,
                            long M, long N, long K, long lda, long ldw, long ldy, int trans_w,

@@ -158,6 +158,7 @@ def test_argument_validation_without_a_gpu(tao):
     L.tao_linear_split_preferred.restype = ctypes.c_int
     assert L.tao_linear_split_preferred(2048, 1024, 4096, 1) == 1 and L.tao_linear_split_preferred(2048, 4096, 4096, 1) == 1
     assert L.tao_linear_split_preferred(8192, 128, 2048, 8) == 0 and L.tao_linear_split_preferred(512, 1024, 1024, 1) == 0
+    assert L.tao_bound_check_linear_in_epilogue(2048, 4096, 4096, 1) == 1 and L.tao_bound_check_linear_in_epilogue(8192, 2048, 128, 8) == 0
     big = ctypes.c_void_p(0x100000)
     assert L.tao_bound_linear_split(p, p, nul, p, *args(4, 4, 8, 4, 8, 4), None, big, wsb, None) == tao.ERR_SHAPE
     assert L.tao_bound_linear_split(p, p, nul, p, *args(4, 4, 8, 8, 8, 4), None, nul, wsb, None) == tao.ERR_WORKSPACE
