@@ -501,26 +501,24 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p, typename
 template <bool TRANS_W, bool FAST, int WM, bool CLEAN, bool PERSIST>
 static hipError_t launch_absgemm(dim3 grid, hipStream_t st, const LinArgs& p) {
     constexpr size_t lds_bytes = (size_t)kStages * Shape<WM>::kStageFloats * sizeof(float);
-    static bool configured = false;      // raise the dynamic LDS limit once per instantiation
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_bound<TRANS_W, FAST, WM, CLEAN, PERSIST>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static OncePerDevice configured;      // raise the dynamic LDS limit once per instantiation and device
+    const hipError_t e = configured.run([] {
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_bound<TRANS_W, FAST, WM, CLEAN, PERSIST>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    });
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL((absgemm_bound<TRANS_W, FAST, WM, CLEAN, PERSIST>), grid, dim3(kLinThreads), lds_bytes, st, p, NoConv());
     return hipSuccess;
 }
 template <bool FAST, int WM, bool CLEAN>
 static hipError_t launch_conv(dim3 grid, hipStream_t st, const LinArgs& p, const ConvGeom& cv) {
     constexpr size_t lds_bytes = (size_t)kStages * Shape<WM>::kStageFloats * sizeof(float);
-    static bool configured = false;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_bound<false, FAST, WM, CLEAN, false, true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return e;
-        configured = true;
-    }
+    static OncePerDevice configured;
+    const hipError_t e = configured.run([] {
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_bound<false, FAST, WM, CLEAN, false, true>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+    });
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL((absgemm_bound<false, FAST, WM, CLEAN, false, true>), grid, dim3(kLinThreads), lds_bytes, st, p, cv);
     return hipSuccess;
 }

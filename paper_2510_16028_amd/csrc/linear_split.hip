@@ -788,19 +788,21 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
     p.infl = widen(1.0 / (lower * (1.0 - 0x1p-52)));
     p.uflow = (md.flags & TAO_FLAG_UNDERFLOW_TERMS) ? (double)Kp_ * 0x1p-149 : 0.0;
 
-    static bool configured = false;
     constexpr int lds_bytes = kSplitStages * kSplitStage;
-    if (!configured) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split<false, false, true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split<true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split<false, true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    static OncePerDevice configured;      // the dynamic LDS limit of the three instantiations, once per device
+    {
+        const hipError_t e = configured.run([] {
+            hipError_t r = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split<false, false, true>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            if (r == hipSuccess)
+                r = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split<true>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            if (r == hipSuccess)
+                r = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split<false, true>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            return r;
+        });
         if (e != hipSuccess) { g_last_hip_error = (int)e; return TAO_ERR_LAUNCH; }
-        configured = true;
     }
     p.claimed = nullptr; p.ref = nullptr; p.ldy = 0; p.strideY = 0; p.alpha = 0.0; p.eps_rel = 0.0;
     p.ws_hist = nullptr; p.ws_coarse = nullptr; p.ws_stats = nullptr;

@@ -3,12 +3,30 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <cmath>
+#include <atomic>
 #include <cstdint>
 #include "tao.h"
 
 namespace tao {
 
 extern thread_local int g_last_hip_error;
+
+// Per-device "done once" mark for settings that a device keeps (the dynamic LDS limit of a kernel):
+// bit d of `done` is set once device d has them.  Two threads that race both apply the setting,
+// which is idempotent.
+struct OncePerDevice {
+    std::atomic<unsigned long long> done{0};
+    template <class F> hipError_t run(F&& apply) {
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        const unsigned long long bit = 1ull << (dev & 63);
+        if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+        e = apply();
+        if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+        return e;
+    }
+};
 
 inline int launch_status() {
     hipError_t e = hipGetLastError();
