@@ -169,6 +169,14 @@ def test_library_calls_replay_from_a_hip_graph(tao, oracle_mod):
     ws_split = torch.empty(tao.tao_linear_split_workspace_bytes(M, N, K, 1, True), dtype=torch.uint8, device="cuda")
     ws_proj = torch.empty(tao.tao_project_workspace_bytes(M * N), dtype=torch.uint8, device="cuda")
     ws_chk = torch.empty(tao.tao_check_workspace_bytes(M * N), dtype=torch.uint8, device="cuda")
+    # the matmul bound checked in one call: in the epilogue (K = 320) and, for a short reduction (the
+    # first 96 columns of the same operands), through the stored bound and the streaming check
+    KS = 96
+    prof_e = tao.new_profile_buffer(A.device); prof_s = tao.new_profile_buffer(A.device)
+    ws_e = torch.empty(tao.tao_bound_check_linear_workspace_bytes(M, N, K, 1, True), dtype=torch.uint8, device="cuda")
+    ws_s = torch.empty(tao.tao_bound_check_linear_workspace_bytes(M, N, KS, 1, True), dtype=torch.uint8, device="cuda")
+    ref_s = torch.empty((M, N), device="cuda"); claimed_s = torch.empty((M, N), device="cuda")
+    assert tao.tao_bound_check_linear_in_epilogue(M, N, K) and not tao.tao_bound_check_linear_in_epilogue(M, N, KS)
 
     def fill(seed):
         g = torch.Generator(device="cuda").manual_seed(seed)
@@ -176,6 +184,8 @@ def test_library_calls_replay_from_a_hip_graph(tao, oracle_mod):
         ref.copy_(A @ W.t())
         claimed.copy_(ref * (1 + 3e-7 * torch.randn((M, N), device="cuda", generator=g)))
         y_sm.copy_(torch.softmax(x, -1))
+        ref_s.copy_(A[:, :KS] @ W[:, :KS].t())
+        claimed_s.copy_(ref_s * (1 + 3e-7 * torch.randn((M, N), device="cuda", generator=g)))
 
     def calls():
         tao.tao_bound_linear(A, W, out=tau_f)
@@ -183,6 +193,8 @@ def test_library_calls_replay_from_a_hip_graph(tao, oracle_mod):
         tao.tao_bound_softmax(x, y_sm, out=tau_sm)
         tao.tao_check_and_profile(claimed, ref, tau_f, out=prof, readback=False, ws=ws_chk)
         tao.tao_project_empirical(x, thr, 2.0, out=proj, ws=ws_proj)
+        tao.tao_bound_check_linear(A, W, None, ref, claimed, out=prof_e, ws=ws_e, readback=False)
+        tao.tao_bound_check_linear(A[:, :KS], W[:, :KS], None, ref_s, claimed_s, out=prof_s, ws=ws_s, readback=False)
 
     outs = (tau_f, tau_s, tau_sm, proj)
     fill(100)
@@ -205,6 +217,9 @@ def test_library_calls_replay_from_a_hip_graph(tao, oracle_mod):
         torch.cuda.synchronize()
         got = [o.clone() for o in outs]
         got_prof = tao.read_profile(prof)
+        got_more = [tao.read_profile(b) for b in (prof_e, prof_s)]
+        for b in (prof_e, prof_s):
+            b.zero_()
         for o in outs:
             o.fill_(-2.0)
         calls()
@@ -213,5 +228,9 @@ def test_library_calls_replay_from_a_hip_graph(tao, oracle_mod):
             assert bool((g_.view(torch.int32) == o.view(torch.int32)).all())
         eager_prof = tao.read_profile(prof)
         assert got_prof["violations"] == eager_prof["violations"] and np.array_equal(got_prof["hist"], eager_prof["hist"])
+        for g_, b in zip(got_more, (prof_e, prof_s)):
+            e_ = tao.read_profile(b)
+            assert g_["n"] == e_["n"] == M * N and g_["violations"] == e_["violations"] and g_["max_rel"] == e_["max_rel"]
+            assert np.array_equal(g_["hist"], e_["hist"])
         want = oracle_mod.project_empirical(x.cpu().numpy(), thr.cpu().numpy(), 2.0)
         assert np.array_equal(got[3].cpu().numpy().view(np.uint32), want.view(np.uint32))
