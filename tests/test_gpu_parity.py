@@ -196,7 +196,9 @@ def test_conv2d_accepts_a_real_convolution(tao, oracle_mod):
     (200, 300, 1500, True, False, 1), (2048, 1024, 4096, False, False, 1),
     # short reductions with many tiles per compute unit: a workgroup walks several tiles (ragged edges,
     # so many of its slots hold no tile; the second has the shortest reduction that walks)
-    (2100, 1500, 100, True, False, 6), (1100, 2300, 40, False, True, 4)])
+    (2100, 1500, 100, True, False, 6), (1100, 2300, 40, False, True, 4),
+    # as many tiles, but a single group per tile: too short to walk, one workgroup per tile
+    (2100, 1500, 20, True, False, 6)])
 def test_linear_split_shapes(tao, oracle_mod, M, N, K, bias, trans_w, batch):
     """The BF16-split path against the oracle, every element (same tolerance as the FP32 path)."""
     g = torch.Generator().manual_seed(M * 1000 + N * 10 + K + 5)
