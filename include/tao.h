@@ -72,8 +72,11 @@ typedef struct tao_fp_model {
 enum { TAO_MODE_DETERMINISTIC = 0, TAO_MODE_PROBABILISTIC = 1 };
 enum {
     TAO_FLAG_UNDERFLOW_TERMS = 1u,  /* linear: add K'*2^-149 for gradual underflow (App. A.1 excludes it) */
-    TAO_FLAG_FAST_ACCUM = 2u        /* linear: one FP32 accumulation chain over K; still an upper
+    TAO_FLAG_FAST_ACCUM = 2u,       /* linear: one FP32 accumulation chain over K; still an upper
                                        bound, but looser than the default by about 2*K*u relative */
+    TAO_FLAG_CHECK_IN_EPILOGUE = 4u /* tao_bound_check_linear: check in the matrix kernel's epilogue for
+                                       every reduction length (no stored bound, its workspace unused);
+                                       same result, slower for short reductions */
 };
 
 /* Result of tao_check_and_profile (lives in DEVICE memory, 8-byte aligned). */
@@ -150,7 +153,7 @@ int tao_linear_split_preferred(long M, long N, long K, long batch);
  * tau that tao_bound_linear_split computes from the same operands, but tau is compared in registers
  * in the matrix kernel's epilogue and only stored when `tau` is not NULL (layout ldy / strideY, like
  * y_ref and claimed: M x N per batch entry, ldy >= N).  Where the epilogue would cost more than it
- * saves -- reductions shorter than 256 with contiguous outputs -- the bound is stored instead (into
+ * saves -- reductions up to 1024 long with contiguous outputs -- the bound is stored instead (into
  * `tau`, else into the workspace) and the streaming check reads it: the same result, sooner.
  * y_ref: the verifier's re-executed output, claimed: the proposer's.  out: DEVICE, fully overwritten,
  * valid once the stream has drained.  ws / ws_bytes: DEVICE scratch of at least

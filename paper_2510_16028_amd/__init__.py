@@ -19,7 +19,7 @@ OK = 0
 ERR_NULL, ERR_SHAPE, ERR_ALIGN, ERR_K_RANGE, ERR_MODEL, ERR_KIND, ERR_LAUNCH, ERR_WORKSPACE = \
     -1, -2, -3, -4, -5, -6, -7, -8
 MODE_DETERMINISTIC, MODE_PROBABILISTIC = 0, 1
-FLAG_UNDERFLOW_TERMS, FLAG_FAST_ACCUM = 1, 2
+FLAG_UNDERFLOW_TERMS, FLAG_FAST_ACCUM, FLAG_CHECK_IN_EPILOGUE = 1, 2, 4
 NORM_LAYERNORM, NORM_RMSNORM, NORM_BN_AFFINE, NORM_SUM, NORM_MEAN = 0, 1, 2, 3, 4
 ACT_GELU_ERF, ACT_SILU, ACT_MUL, ACT_ADD, ACT_RELU = 0, 1, 2, 3, 4
 (ACT_SUB, ACT_DIV, ACT_EXACT, ACT_SQRT, ACT_RSQRT, ACT_EXP, ACT_LOG, ACT_SIN, ACT_COS, ACT_TANH,

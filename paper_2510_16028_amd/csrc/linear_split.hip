@@ -49,7 +49,7 @@ constexpr int kSlab = STILE * SROW;     // one operand, one piece
 constexpr int kBlock = 3 * kSlab;       // one operand, three pieces: 24576 bytes, contiguous in the workspace
 constexpr int kSplitStage = 2 * kBlock; // |A| hi, mid, lo, |W| hi, mid, lo: 49152 bytes
 constexpr int kSplitStages = 3;         // 144 KB of LDS
-constexpr long kEpilogueCheckMinK = 256; // shorter reductions: the bound is stored and the streaming check reads it (see split_run)
+constexpr long kEpilogueCheckMinK = 1025; // shorter reductions (up to 1024, as far as the plain bound walks its tiles): the bound is stored and the streaming check reads it (see split_run)
 constexpr long kWalkMaxGroups = 32;     // reductions up to 1024 k-steps walk their tiles ...
 constexpr int kWalkMinTilesPerCu = 4;   // ... when a compute unit has at least this many
 
@@ -714,11 +714,14 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
         if (!ws || !aligned(ws, 256) || ws_bytes < need_split + check_workspace_bytes()) return TAO_ERR_WORKSPACE;
         cw = carve_check_workspace(static_cast<char*>(ws) + need_split);
         // Short reductions: in the epilogue the check is arithmetic that nothing overlaps (about 70
-        // instructions per element on a compute unit whose matrix cores idle meanwhile), as long as
-        // the reduction itself up to K = 128; the streaming check spends the same arithmetic under
-        // its loads.  There the bound is stored (in the workspace unless the caller wants it) and
-        // checked by that pass: the same results, field for field, sooner.
-        two_pass = K < kEpilogueCheckMinK && chk->ldy == N && (batch == 1 || chk->strideY == M * N);
+        // instructions per element on a compute unit whose matrix cores idle meanwhile), while the
+        // streaming check spends the same arithmetic under its loads and the plain bound walks its
+        // tiles.  Up to K = 1024 the bound is therefore stored (in the workspace unless the caller
+        // wants it) and checked by that pass: the same results, field for field, 1 - 8 % sooner
+        // (measured at K = 128 ... 1024); beyond, the two routes take the same time and the epilogue
+        // saves the traffic of the stored bound.
+        two_pass = K < kEpilogueCheckMinK && !(md.flags & TAO_FLAG_CHECK_IN_EPILOGUE) &&
+                   chk->ldy == N && (batch == 1 || chk->strideY == M * N);
         if (two_pass && !tau && M > 0 && N > 0 && batch > 0) {
             const size_t off = need_split + round_up_256(check_workspace_bytes());
             const size_t stored = round_up_256((size_t)M * N * batch * 4);      // (M N batch < 2^36, checked above)

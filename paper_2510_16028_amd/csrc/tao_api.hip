@@ -16,7 +16,7 @@ int resolve_model(const tao_fp_model* m, tao_fp_model* out) {
         return TAO_ERR_MODEL;
     if (!ok(out->c_exp) || !ok(out->c_erf) || !ok(out->c_rsqrt) || !ok(out->c_div)) return TAO_ERR_MODEL;
     if (!ok(out->c_log) || !ok(out->c_sin) || !ok(out->c_cos) || !ok(out->c_tanh) || !ok(out->c_pow)) return TAO_ERR_MODEL;
-    if (out->flags & ~(TAO_FLAG_UNDERFLOW_TERMS | TAO_FLAG_FAST_ACCUM)) return TAO_ERR_MODEL;
+    if (out->flags & ~(TAO_FLAG_UNDERFLOW_TERMS | TAO_FLAG_FAST_ACCUM | TAO_FLAG_CHECK_IN_EPILOGUE)) return TAO_ERR_MODEL;
     return TAO_OK;
 }
 

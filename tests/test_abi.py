@@ -73,6 +73,7 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_bound_softmax(nul, nul, nul, 0, 4, 4, None, None) == tao.OK             # empty: no-op
     bad = tao.FpModel(u=0.5)
     assert L.tao_bound_softmax(p, p, p, 4, 4, 4, ctypes.byref(bad), None) == tao.ERR_MODEL
+    assert L.tao_bound_softmax(p, p, p, 4, 4, 4, ctypes.byref(tao.FpModel(flags=8)), None) == tao.ERR_MODEL     # unknown flag bit
     # norm
     assert L.tao_bound_norm(9, p, p, p, p, 1e-5, p, 4, 4, 4, None, None) == tao.ERR_KIND
     assert L.tao_bound_norm(0, p, nul, p, p, 1e-5, p, 4, 4, 4, None, None) == tao.ERR_NULL   # y_ref required
@@ -159,6 +160,7 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_linear_split_preferred(2048, 1024, 4096, 1) == 1 and L.tao_linear_split_preferred(2048, 4096, 4096, 1) == 1
     assert L.tao_linear_split_preferred(8192, 128, 2048, 8) == 0 and L.tao_linear_split_preferred(512, 1024, 1024, 1) == 0
     assert L.tao_bound_check_linear_in_epilogue(2048, 4096, 4096, 1) == 1 and L.tao_bound_check_linear_in_epilogue(8192, 2048, 128, 8) == 0
+    assert L.tao_bound_check_linear_in_epilogue(64, 64, 1024, 1) == 0 and L.tao_bound_check_linear_in_epilogue(64, 64, 1025, 1) == 1
     big = ctypes.c_void_p(0x100000)
     assert L.tao_bound_linear_split(p, p, nul, p, *args(4, 4, 8, 4, 8, 4), None, big, wsb, None) == tao.ERR_SHAPE
     assert L.tao_bound_linear_split(p, p, nul, p, *args(4, 4, 8, 8, 8, 4), None, nul, wsb, None) == tao.ERR_WORKSPACE
@@ -169,10 +171,10 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_bound_linear_split(nul, nul, nul, nul, *args(0, 4, 8, 8, 8, 4), None, nul, 0, None) == tao.OK
     # ... and with the check fused into the epilogue
     cwb = L.tao_bound_check_linear_workspace_bytes(4, 4, 8, 1, 1)
-    # (a reduction shorter than 256: room for the stored bound, 4 x 4 x 4 bytes rounded to 256)
+    # (a reduction up to 1024 long: room for the stored bound, 4 x 4 x 4 bytes rounded to 256)
     assert cwb == (wsb + 255) // 256 * 256 + L.tao_check_workspace_bytes(16) + 256
-    wsb_long = L.tao_linear_split_workspace_bytes(4, 4, 512, 1, 1)
-    assert L.tao_bound_check_linear_workspace_bytes(4, 4, 512, 1, 1) == (wsb_long + 255) // 256 * 256 + L.tao_check_workspace_bytes(16)
+    wsb_long = L.tao_linear_split_workspace_bytes(4, 4, 2048, 1, 1)
+    assert L.tao_bound_check_linear_workspace_bytes(4, 4, 2048, 1, 1) == (wsb_long + 255) // 256 * 256 + L.tao_check_workspace_bytes(16)
     fc = lambda a, w, y, c, t, dims, alpha, out, wsp, wsn: L.tao_bound_check_linear(a, w, nul, y, c, t, *dims, alpha, 0.0, None, out, wsp, wsn, None)
     ok = args(4, 4, 8, 8, 8, 4)
     assert fc(p, p, p, p, nul, args(4, 4, 8, 4, 8, 4), 1.0, p, big, cwb) == tao.ERR_SHAPE        # lda < K

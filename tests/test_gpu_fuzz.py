@@ -54,7 +54,8 @@ def test_one_pass_entry_points_on_random_cases(tao, oracle_mod, seed):
             ref = ref.contiguous(); c = noisy(ref, 3e-7)
             Ag, Wg, bg = A.cuda(), W.cuda(), None if b is None else b.cuda()
             tau = tao.tao_bound_linear_split(Ag, Wg, bg, trans_w=tw)
-            fused = tao.tao_bound_check_linear(Ag, Wg, bg, ref.cuda(), c.cuda(), trans_w=tw, alpha=alpha, eps_rel=eps)
+            route = tao.FpModel(flags=tao.FLAG_CHECK_IN_EPILOGUE) if rng.integers(2) else None      # both routes of the entry point
+            fused = tao.tao_bound_check_linear(Ag, Wg, bg, ref.cuda(), c.cuda(), trans_w=tw, alpha=alpha, eps_rel=eps, model=route)
             two = tao.tao_check_and_profile(c.cuda(), ref.cuda(), tau, alpha=alpha, eps_rel=eps)
             assert_profile_equal(fused, two, "linear %s" % ((M, N, K, batch, tw, hb),))
             po = oracle.check_and_profile(c.numpy(), ref.numpy(), tau.cpu().numpy(), alpha=alpha, eps_rel=eps)

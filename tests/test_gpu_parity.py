@@ -549,18 +549,23 @@ def test_matmul_bound_checked_in_the_epilogue(tao, oracle_mod, M, N, K, bias, tr
     Ag, Wg, bg = A.cuda(), W.cuda(), None if b is None else b.cuda()
     rg, cg = ref.cuda().contiguous(), claimed.cuda().contiguous()
     tau = tao.tao_bound_linear_split(Ag, Wg, bg, trans_w=trans_w)
+    # both routes of the entry point: its own choice (stored bound + streaming check up to K = 1024) and
+    # the check in the matrix kernel's epilogue asked for by flag
+    routes = (None, tao.FpModel(flags=tao.FLAG_CHECK_IN_EPILOGUE))
     for alpha, eps in ((1.0, 1e-12), (0.5, 1e-6)):
-        fused = tao.tao_bound_check_linear(Ag, Wg, bg, rg, cg, trans_w=trans_w, alpha=alpha, eps_rel=eps)
         two = tao.tao_check_and_profile(cg, rg, tau, alpha=alpha, eps_rel=eps)
-        assert_profile_equal(fused, two, "epilogue vs two passes %s" % ((M, N, K, batch),))
         po = oracle_mod.check_and_profile(_np(claimed), _np(ref), _np(tau), alpha=alpha, eps_rel=eps)
-        assert_profile_equal(fused, po, "epilogue vs oracle check %s" % ((M, N, K, batch),))
-        assert fused["n"] == batch * M * N
+        for model in routes:
+            fused = tao.tao_bound_check_linear(Ag, Wg, bg, rg, cg, trans_w=trans_w, alpha=alpha, eps_rel=eps, model=model)
+            assert_profile_equal(fused, two, "one call vs two passes %s" % ((M, N, K, batch, model is None),))
+            assert_profile_equal(fused, po, "one call vs oracle check %s" % ((M, N, K, batch, model is None),))
+            assert fused["n"] == batch * M * N
     # tau on request: the split path's bits
-    tau2 = torch.full_like(tau, -1.0)
-    again = tao.tao_bound_check_linear(Ag, Wg, bg, rg, cg, trans_w=trans_w, tau_out=tau2)
-    assert bool((tau2.view(torch.int32) == tau.view(torch.int32)).all())
-    assert_profile_equal(again, tao.tao_check_and_profile(cg, rg, tau), "with tau stored")
+    for model in routes:
+        tau2 = torch.full_like(tau, -1.0)
+        again = tao.tao_bound_check_linear(Ag, Wg, bg, rg, cg, trans_w=trans_w, tau_out=tau2, model=model)
+        assert bool((tau2.view(torch.int32) == tau.view(torch.int32)).all())
+        assert_profile_equal(again, tao.tao_check_and_profile(cg, rg, tau), "with tau stored")
     if M * N > 40:
         assert again["violations"] >= 3 and again["nan_count"] >= 1
 

@@ -169,14 +169,16 @@ def test_library_calls_replay_from_a_hip_graph(tao, oracle_mod):
     ws_split = torch.empty(tao.tao_linear_split_workspace_bytes(M, N, K, 1, True), dtype=torch.uint8, device="cuda")
     ws_proj = torch.empty(tao.tao_project_workspace_bytes(M * N), dtype=torch.uint8, device="cuda")
     ws_chk = torch.empty(tao.tao_check_workspace_bytes(M * N), dtype=torch.uint8, device="cuda")
-    # the matmul bound checked in one call: in the epilogue (K = 320) and, for a short reduction (the
-    # first 96 columns of the same operands), through the stored bound and the streaming check
+    # the matmul bound checked in one call, both routes: in the epilogue (asked for by flag: K = 320 would
+    # take the other route) and, on the first 96 columns of the same operands, through the stored bound
+    # and the streaming check
     KS = 96
     prof_e = tao.new_profile_buffer(A.device); prof_s = tao.new_profile_buffer(A.device)
     ws_e = torch.empty(tao.tao_bound_check_linear_workspace_bytes(M, N, K, 1, True), dtype=torch.uint8, device="cuda")
     ws_s = torch.empty(tao.tao_bound_check_linear_workspace_bytes(M, N, KS, 1, True), dtype=torch.uint8, device="cuda")
     ref_s = torch.empty((M, N), device="cuda"); claimed_s = torch.empty((M, N), device="cuda")
-    assert tao.tao_bound_check_linear_in_epilogue(M, N, K) and not tao.tao_bound_check_linear_in_epilogue(M, N, KS)
+    assert not tao.tao_bound_check_linear_in_epilogue(M, N, KS)
+    epi = tao.FpModel(flags=tao.FLAG_CHECK_IN_EPILOGUE)
 
     def fill(seed):
         g = torch.Generator(device="cuda").manual_seed(seed)
@@ -193,7 +195,7 @@ def test_library_calls_replay_from_a_hip_graph(tao, oracle_mod):
         tao.tao_bound_softmax(x, y_sm, out=tau_sm)
         tao.tao_check_and_profile(claimed, ref, tau_f, out=prof, readback=False, ws=ws_chk)
         tao.tao_project_empirical(x, thr, 2.0, out=proj, ws=ws_proj)
-        tao.tao_bound_check_linear(A, W, None, ref, claimed, out=prof_e, ws=ws_e, readback=False)
+        tao.tao_bound_check_linear(A, W, None, ref, claimed, model=epi, out=prof_e, ws=ws_e, readback=False)
         tao.tao_bound_check_linear(A[:, :KS], W[:, :KS], None, ref_s, claimed_s, out=prof_s, ws=ws_s, readback=False)
 
     outs = (tau_f, tau_s, tau_sm, proj)
