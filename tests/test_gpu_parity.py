@@ -520,6 +520,7 @@ def test_split_tile_walk_against_one_workgroup_per_tile(tao):
     (512, 384, 2048, True, False, 1), (300, 260, 1100, False, True, 2),       # reduction cut into parts: checked by the combining pass
     (0, 16, 8, False, False, 1),
     (2100, 1500, 100, True, False, 6), (1100, 2300, 40, False, True, 4),      # workgroups that walk several tiles
+    (300, 260, 1000, True, False, 1),                                         # stored-bound route with the reduction cut into parts
 ])
 def test_matmul_bound_checked_in_the_epilogue(tao, oracle_mod, M, N, K, bias, trans_w, batch):
     """tao_bound_check_linear: field for field the profile of tao_bound_linear_split followed by
