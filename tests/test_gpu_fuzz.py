@@ -43,7 +43,7 @@ def test_one_pass_entry_points_on_random_cases(tao, oracle_mod, seed):
         which = int(rng.integers(6))
         alpha = float(rng.choice([0.5, 1.0, 3.0])); eps = float(rng.choice([0.0, 1e-12, 1e-6]))
         if which == 0:      # linear
-            M, N, K = int(rng.integers(1, 700)), int(rng.integers(1, 700)), int(rng.integers(0, 600))
+            M, N, K = int(rng.integers(1, 700)), int(rng.integers(1, 700)), int(rng.choice([0, 1, 31, 32, 33, 64, 200, 600, 1024, 1025, 1400, int(rng.integers(0, 1500))]))
             batch = int(rng.choice([1, 1, 2, 3])); tw = bool(rng.integers(2)); hb = bool(rng.integers(2)) and batch == 1
             A = torch.randn((batch, M, K), generator=g); W = torch.randn((batch, K, N) if tw else (batch, N, K), generator=g)
             if batch == 1: A, W = A[0], W[0]
