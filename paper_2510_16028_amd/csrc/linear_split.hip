@@ -80,7 +80,11 @@ __device__ __forceinline__ void split_one(float v, unsigned& h, unsigned& m, uns
 template <bool TRANS>
 __global__ __launch_bounds__(256) void split3_bf16(const float* __restrict__ src, long rows, long K, long ld,
                                                     long src_batch_stride, unsigned short* __restrict__ dst, long Kp,
-                                                    int vec_ok) {
+                                                    int vec_ok, unsigned int* __restrict__ zero_ptr, long zero_n) {
+    // (side job for the launch that follows: clears zero_n words at zero_ptr, the partial results of
+    // a check in the matrix kernel's epilogue, so that no launch of its own is needed for that)
+    if (zero_ptr && blockIdx.y == 0)
+        for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < zero_n; i += (long)gridDim.x * blockDim.x) zero_ptr[i] = 0;
     const long chunks = Kp >> 3;
     const long z = blockIdx.y;
     const long rblocks = (rows + STILE - 1) / STILE;
@@ -757,6 +761,7 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
     const size_t bytesA = (size_t)(Kp / SBK) * blocksA * kBlock * batch;          // a multiple of 256
     unsigned short* W3 = reinterpret_cast<unsigned short*>(static_cast<char*>(ws) + bytesA);
     const size_t bytesW3 = (size_t)(Kp / SBK) * blocksW * kBlock * (shared_w ? 1 : batch);
+    bool cleared = false;                                    // the check's partial results are zero already
     if (K > 0) {
         auto blocks_for = [](long rows, long kp, bool trans) {
             // work items of split3_bf16: (row, chunk) pairs, or whole 64-row x 256-k patches of 2048
@@ -764,16 +769,19 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
             return (unsigned)(b < 1 ? 1 : (b > 256L * 64 ? 256L * 64 : b));
         };
         const int vecA = aligned(A, 16) && (lda % 4 == 0) && (strideA % 4 == 0);
+        // the operand pre-pass also clears the partial results of an epilogue check (no parts: those
+        // are checked by the combining pass, which needs none)
+        cleared = chk && !two_pass && split_k_parts(M, N, K, batch) < 2;
         hipLaunchKernelGGL((split3_bf16<false>), dim3(blocks_for(M, Kp, false), (unsigned)batch), dim3(256), 0, st,
-                           A, M, K, lda, strideA, A3, Kp, vecA);
+                           A, M, K, lda, strideA, A3, Kp, vecA, cleared ? cw.hist : nullptr, (long)(check_workspace_bytes() / 4));
         const unsigned wb = shared_w ? 1u : (unsigned)batch;
         if (trans_w) {
             hipLaunchKernelGGL((split3_bf16<true>), dim3(blocks_for(N, Kp, true), wb), dim3(256), 0, st,
-                               W, N, K, ldw, strideW, W3, Kp, 0);
+                               W, N, K, ldw, strideW, W3, Kp, 0, nullptr, 0L);
         } else {
             const int vecW = aligned(W, 16) && (ldw % 4 == 0) && (strideW % 4 == 0);
             hipLaunchKernelGGL((split3_bf16<false>), dim3(blocks_for(N, Kp, false), wb), dim3(256), 0, st,
-                               W, N, K, ldw, strideW, W3, Kp, vecW);
+                               W, N, K, ldw, strideW, W3, Kp, vecW, nullptr, 0L);
         }
     }
 
@@ -870,7 +878,7 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
         return then_check();
     }
     const int slots = kMaxCheckBlocks;                       // workgroup b adds to partial result b % 256
-    hipLaunchKernelGGL(zero_words, dim3(64), dim3(256), 0, st, cw.hist, (long)(check_workspace_bytes() / 4));
+    if (!cleared) hipLaunchKernelGGL(zero_words, dim3(64), dim3(256), 0, st, cw.hist, (long)(check_workspace_bytes() / 4));
     hipLaunchKernelGGL((absgemm_split<true>), dim3(p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
     launch_profile_reduce(cw, slots, (unsigned long long)((__int128)M * N * batch), chk->out, st);
     return launch_status();
