@@ -71,7 +71,10 @@ typedef struct tao_fp_model {
 
 enum { TAO_MODE_DETERMINISTIC = 0, TAO_MODE_PROBABILISTIC = 1 };
 enum {
-    TAO_FLAG_UNDERFLOW_TERMS = 1u,  /* linear: add K'*2^-149 for gradual underflow (App. A.1 excludes it) */
+    TAO_FLAG_UNDERFLOW_TERMS = 1u,  /* linear, conv, rope: add K'*2^-149 for gradual underflow in the operator
+                                       (App. A.1 excludes it); a product sum that comes out as exactly zero is
+                                       then no longer taken for an exact zero (see tao_bound_linear); the
+                                       result is the reference value or the next binary32 value above it */
     TAO_FLAG_FAST_ACCUM = 2u,       /* linear: one FP32 accumulation chain over K; still an upper
                                        bound, but looser than the default by about 2*K*u relative */
     TAO_FLAG_CHECK_IN_EPILOGUE = 4u /* tao_bound_check_linear: check in the matrix kernel's epilogue for
@@ -123,7 +126,16 @@ double tao_gamma(long k, const tao_fp_model *model);
  * root is folded into a binary64 accumulator (at most 7 binary32 roundings per
  * term); the result is inflated by the proven rounding error of that scheme, so
  * exact <= tau <= exact * (1 + 1e-6).  M, N or batch equal to 0 is a no-op;
- * K == 0 gives tau = Gamma(K') |bias| (0 without bias). */
+ * K == 0 gives tau = Gamma(K') |bias| (0 without bias).
+ * Gradual underflow inside the bound's own evaluation: partial sums that fall
+ * below 2^-126 are rounded absolutely (2^-150 per rounding), so a positive sum
+ * also receives (1.25 K + 40) 2^-150 before the inflation ((K + 63) 2^-149 on the
+ * BF16 path); the upper tolerance then reads exact (1 + 1e-6) + Gamma(K') times
+ * that term, which only matters for bounds that are themselves about 2^-126 or
+ * smaller.  A sum that comes out as exactly 0 is reported as the exact zero of
+ * zero operands or padding; operands whose every product lies below 2^-150
+ * (which binary32 arithmetic cannot represent either: App. A.1 excludes
+ * underflow) need TAO_FLAG_UNDERFLOW_TERMS to stay covered. */
 int tao_bound_linear(const float *A, const float *W, const float *bias, float *tau,
                      long M, long N, long K, long lda, long ldw, long ldt, int trans_w,
                      long batch, long strideA, long strideW, long strideT,
@@ -221,7 +233,11 @@ int tao_bound_softmax(const float *x, const float *y_ref, float *tau, long rows,
  *  BN_AFFINE  y = x s_c + t_c per column c; s = gamma_or_scale (required), t = beta_or_shift.
  *  SUM, MEAN  tau: [rows];  Gamma(cols-1) sum|x|  (/cols + |y| c_div u/(1 - c_div u) for MEAN).
  * eps is rounded to binary32 first, as the operator does.  A row whose bound is
- * not finite (lower end of var + eps not positive) gets NaN. */
+ * not finite (lower end of var + eps not positive) gets NaN.
+ * TAO_ERR_K_RANGE when Gamma(cols - 1) is undefined (cols u >= 1) and, for LAYERNORM and
+ * RMSNORM (also in tao_bound_groupnorm and tao_bound_check_norm), when it exceeds 1/2
+ * (cols above about 5.59 million with the default model): the template subtracts the
+ * variance's own error bound from the variance, and nothing useful is left of it there. */
 int tao_bound_norm(int kind, const float *x, const float *y_ref,
                    const float *gamma_or_scale, const float *beta_or_shift, double eps,
                    float *tau, long rows, long cols, long ld,

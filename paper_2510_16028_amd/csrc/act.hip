@@ -84,9 +84,11 @@ __device__ __forceinline__ float act_one(float x, float y, const ActConsts& k) {
         const double E_T = Gp * E_p + k.c_tanh_u * A;
         t = 0.5 * ax * E_T + ay * k.fresh2;
     } else if (KIND == TAO_ACT_SILU) {
-        t = ay * k.silu_f;
+        // one product with a factor that already carries its margin (widened on the host; u itself for
+        // the correctly rounded kinds, where the product is exact): nothing is added to a subnormal result
+        return up32g(ay * k.silu_f, kUpMul, 1.0);
     } else if (KIND == kKindScale) {
-        t = ay * k.scale_f;
+        return up32g(ay * k.scale_f, kUpMul, 1.0);
     } else {
         return 0.f;
     }
@@ -178,8 +180,8 @@ __device__ __forceinline__ void rope_body(const float* __restrict__ x, const flo
     const long stride = (long)gridDim.x * blockDim.x;
     auto one = [&](float xa, float xb, float c, float s, float& ta, float& tb) {
         const double ca = fabs((double)c), sa = fabs((double)s), a = fabs((double)xa), b = fabs((double)xb);
-        ta = up32g(g2 * (a * ca + b * sa) + uflow);
-        tb = up32g(g2 * (b * ca + a * sa) + uflow);
+        ta = up32g(g2 * (a * ca + b * sa) + uflow, kUpMul, 1.0 + 0x1p-48);   // (three round-to-nearest operations)
+        tb = up32g(g2 * (b * ca + a * sa) + uflow, kUpMul, 1.0 + 0x1p-48);
     };
     for (long w = (long)blockIdx.x * blockDim.x + threadIdx.x; w < total; w += stride) {
         const long r = w / per_row;

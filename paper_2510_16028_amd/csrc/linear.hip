@@ -67,6 +67,8 @@ struct LinArgs {
     int all_clean;             // every tile interior and K a multiple of the group size
     double c;                  // Gamma(K'), upper
     double infl;               // reciprocal of the lower rounding factor of the accumulation
+    double sabs, sabs0;        // absolute part of the accumulation's rounding error (roundings to subnormal
+                               // results), added to a positive sum / to a sum that came out as exactly zero
     double uflow;              // optional absolute underflow term
 };
 
@@ -332,7 +334,7 @@ __global__ __launch_bounds__(kLinThreads) void absgemm_bound(LinArgs p, typename
                 const long row = o.m0 + wm * 32 + 8 * (v >> 2) + 4 * h + (v & 3);
                 if (row < p.M && col < p.N) {
                     const double sv = FAST ? (double)c0[tj][v] : S[tj][v];
-                    const double tt = p.c * (sv * p.infl + ab) * kGuard + p.uflow;
+                    const double tt = p.c * ((sv + (sv > 0.0 ? p.sabs : p.sabs0)) * p.infl + ab) * kGuard + p.uflow;
                     T[row * p.ldt + col] = up32(tt);
                 }
             }
@@ -545,6 +547,17 @@ static bool prefer_64_row_tiles(long M, long tiles_per_row_block, int cus) {
     return c64 < c128;
 }
 
+// A binary32 rounding whose result is subnormal loses up to 2^-150 absolutely instead of u
+// relatively (gradual underflow; the matrix cores keep subnormal values).  An output element sees at
+// most 39 roundings per 32 k-steps (32 chain steps and the 7 additions of the tree; K in the
+// single-chain mode), each amplified by at most (1 + u)^7 afterwards, so the computed sum is at least
+// S lower - sabs with sabs = (1.25 K + 40) 2^-150: the epilogue adds it to every positive sum before
+// the inflation.  For sums in the normal range it is far below the 1e-6 budget (K^2 2^-48 of a
+// bound of 2^-126).  A sum that comes out as exactly zero is taken as an exact zero (every product
+// zero: padding taps, zero operands) -- unless the caller asked for underflow terms, in which case
+// it may also be a sum whose every product rounded to zero, and sabs is added there as well.
+static double accumulation_abs_term(long K) { return K > 0 ? (1.25 * (double)K + 40.0) * 0x1p-150 : 0.0; }
+
 // ---- matrix-core self test ----------------------------------------------------------------
 // out[v*64 + lane] = register v of the accumulator after `steps` chained MFMAs from zero.
 __global__ void mfma_probe(const float* __restrict__ a, const float* __restrict__ b, int steps,
@@ -600,6 +613,8 @@ int tao_bound_linear(const float* A, const float* W, const float* bias, float* t
     if (!(r32 * u < 0.5)) return TAO_ERR_K_RANGE;
     const double lower = (1.0 - r32 * u) * (1.0 - f64 * 0x1p-53);   // <= (1-u)^r (1-2^-53)^f
     p.infl = widen(1.0 / (lower * (1.0 - 0x1p-52)));
+    p.sabs = accumulation_abs_term(K);
+    p.sabs0 = (md.flags & TAO_FLAG_UNDERFLOW_TERMS) ? p.sabs : 0.0;
     p.uflow = (md.flags & TAO_FLAG_UNDERFLOW_TERMS) ? (double)Kp * 0x1p-149 : 0.0;
 
     int dev = 0, cus = 256;
@@ -682,6 +697,8 @@ int tao_bound_conv2d(const float* x, const float* w, const float* bias, float* t
     if (!(r32 * u < 0.5)) return TAO_ERR_K_RANGE;
     const double lower = (1.0 - r32 * u) * (1.0 - f64 * 0x1p-53);
     p.infl = widen(1.0 / (lower * (1.0 - 0x1p-52)));
+    p.sabs = accumulation_abs_term(K);
+    p.sabs0 = (md.flags & TAO_FLAG_UNDERFLOW_TERMS) ? p.sabs : 0.0;
     p.uflow = (md.flags & TAO_FLAG_UNDERFLOW_TERMS) ? (double)Kp * 0x1p-149 : 0.0;
 
     int dev = 0, cus = 256;

@@ -26,7 +26,9 @@
 // and rounds up:  exact <= tau <= exact (1 + 11.5u + 2.44u + 2u + ...) < exact (1 + 16u) < exact (1 + 1e-6).
 // tao_selftest_matrix_core_bf16 re-checks the instruction model on the device in use.  Operands below
 // 2^-110 in magnitude lose low bits of their lo piece in BF16's subnormal range; the pre-pass rounds
-// that piece up, so the bound stays an upper bound but can exceed 1e-6 there.
+// that piece up, so the bound stays an upper bound but can exceed 1e-6 there.  Sums that reach
+// down into the binary32 subnormal range carry an absolute error instead of a relative one; the
+// epilogue adds a bound on it (see split_run), which is far below 1e-6 of any bound above 2^-120.
 #include <cstring>
 #include <type_traits>
 #include "tao_device.hpp"
@@ -142,6 +144,7 @@ struct SplitArgs {
     long batchA3, batchW3;            // elements between batch entries (0 for a shared W)
     unsigned tiles_n, tiles_m;
     double c, infl, uflow;
+    double sabs, sabs0;               // absolute part of the accumulation's error, for a positive / an exactly zero sum
     // CHECK instantiation: the claimed and the re-executed output (layout ldy / strideY), the check's
     // parameters and the partial results of the leaf check in the caller's workspace
     const float* claimed; const float* ref;
@@ -418,7 +421,7 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
                 }
                 if (row < p.M && col < p.N) {
                     const double sv = S[tj][v];
-                    const double tt = p.c * (sv * p.infl + ab) * kGuard + p.uflow;
+                    const double tt = p.c * ((sv + (sv > 0.0 ? p.sabs : p.sabs0)) * p.infl + ab) * kGuard + p.uflow;
                     const float t32 = up32(tt);
                     if (!CHECK) {
                         T[row * p.ldt + col] = t32;
@@ -492,7 +495,7 @@ __global__ __launch_bounds__(kCheckThreads) void split_combine(SplitArgs p, long
         double sv = 0.0;
         for (int k = 0; k < p.ksplit; ++k) sv += p.partial[(long)k * total + i];
         const double ab = p.bias ? fabs((double)p.bias[col]) : 0.0;
-        const double tt = p.c * (sv * p.infl + ab) * kGuard + p.uflow;
+        const double tt = p.c * ((sv + (sv > 0.0 ? p.sabs : p.sabs0)) * p.infl + ab) * kGuard + p.uflow;
         const float t32 = up32(tt);
         if (p.tau) p.tau[z * p.strideT + row * p.ldt + col] = t32;
         if (CHECK) {
@@ -798,6 +801,14 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
     const double lower = (1.0 - 11.5 * u) * (1.0 - f64 * 0x1p-53);
     p.infl = widen(1.0 / (lower * (1.0 - 0x1p-52)));
     p.uflow = (md.flags & TAO_FLAG_UNDERFLOW_TERMS) ? (double)Kp_ * 0x1p-149 : 0.0;
+    // Results in the binary32 subnormal range: the instruction keeps subnormal operands, products
+    // and sums (gradual underflow) and then errs absolutely, by less than one step of 2^-149 per
+    // instruction (probed like the model above: 160 000 cases with products between 2^-160 and
+    // 2^-120); two steps are budgeted for each of the 16 instructions an output element sees per
+    // 32 k-steps.  Added to every positive sum; to an exactly zero sum only when the caller asked for
+    // underflow terms (otherwise such a sum is taken as the exact zero of zero operands).
+    p.sabs = K > 0 ? ((double)Kp + 32.0) * 0x1p-149 : 0.0;
+    p.sabs0 = (md.flags & TAO_FLAG_UNDERFLOW_TERMS) ? p.sabs : 0.0;
 
     constexpr int lds_bytes = kSplitStages * kSplitStage;
     static OncePerDevice configured;      // the dynamic LDS limit of the three instantiations, once per device

@@ -32,6 +32,13 @@ struct RowConsts {
     double eps;        // (double)(float)eps
     double inv_n;      // 1/cols (nearest; covered by the guard factor)
     double mean_f;     // c_div u / (1 - c_div u), upper
+    double m;          // rounding margin of a bound of this row length (see make_consts)
+};
+
+// Factors of the final upper rounding (up32g) for a rounding margin m.
+struct UpFactors {
+    double mul, sub;
+    __device__ __forceinline__ explicit UpFactors(double m) : mul(1.0 + 0x1p-24 + fmax(0x1p-32, 2.0 * m)), sub(1.0 + m) {}
 };
 
 // ---- reductions over the TPR threads of a row group (result in every thread) ----
@@ -134,6 +141,8 @@ __global__ __launch_bounds__(kRowThreads) void softmax_bound(
     const double sfac = sigma / (1.0 - sigma);
     const double w1 = bad ? NAN : 1.0 + sfac;
     const double w0 = bad ? NAN : sfac + k.u;
+    // (an error of the sums enters sfac amplified by 1/(1 - sigma): the margin follows)
+    const UpFactors up(k.m * (1.0 + 2.0 / (1.0 - sigma)));
     for (int v = 0; v < nv; ++v) {
         float4 X = make_float4(0.f, 0.f, 0.f, 0.f), Y = X;
         if (!CACHED) {
@@ -149,7 +158,7 @@ __global__ __launch_bounds__(kRowThreads) void softmax_bound(
             double q, rho;
             if (KEEP) { q = qv[v * 4 + c]; rho = rv[v * 4 + c]; }
             else q_rho(xe[c], ye[c], q, rho);
-            te[c] = up32g(q * fma(rho, w1, w0));
+            te[c] = up32g(q * fma(rho, w1, w0), up.mul, up.sub);
         }
         store4(tau + roff, TAO_VEC_INDEX(v), limit, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
     }
@@ -254,6 +263,7 @@ __global__ __launch_bounds__(kCheckThreads) void softmax_check(
         const double sfac = sigma / (1.0 - sigma);
         const double w1 = bad ? NAN : 1.0 + sfac;
         const double w0 = bad ? NAN : sfac + k.u;
+        const UpFactors up(k.m * (1.0 + 2.0 / (1.0 - sigma)));
         for (int v = 0; v < nv; ++v) {
             const long idx = TAO_VEC_INDEX(v);
             if (idx >= limit) continue;
@@ -266,7 +276,7 @@ __global__ __launch_bounds__(kCheckThreads) void softmax_check(
                 if (idx + c >= limit) break;
                 double q, rho;
                 q_rho(xe[c], ye[c], q, rho);
-                const float t = up32g(q * fma(rho, w1, w0));
+                const float t = up32g(q * fma(rho, w1, w0), up.mul, up.sub);
                 check_one(ce[c], ye[c], t, alpha, eps_rel, hist, rep, acc_chk);
             }
         }
@@ -277,12 +287,15 @@ __global__ __launch_bounds__(kCheckThreads) void softmax_check(
 }
 
 // tail shared by LayerNorm and RMSNorm: from v*, E_v to (r*, E_r, R); ok = finite bound
+// amp: how much a relative error of the row sums is amplified on its way into E_r (the sums enter
+// through the difference w_lo = w - E_w, and E_r falls with w_lo at most like its power -3/2)
 __device__ __forceinline__ bool rsqrt_tail(double vstar, double E_v, const RowConsts& k,
-                                           double& rs, double& E_r, double& R) {
+                                           double& rs, double& E_r, double& R, double& amp) {
     const double w = vstar + k.eps;
     const double E_w = (E_v + k.u * w) * k.inv1mu;
     const double w_lo = w - E_w;
     const bool ok = w_lo > 0.0;
+    amp = (w + E_w) / w_lo;
     const double inv_s = 1.0 / sqrt(w_lo);
     const double inv_s3 = inv_s / w_lo;
     E_r = 0.5 * E_w * inv_s3 + k.cr_u * inv_s;
@@ -304,7 +317,7 @@ __device__ __forceinline__ bool rsqrt_tail(double vstar, double E_v, const RowCo
 // binary64 rounding (a few 2^-53) is covered by the rounding margin of up32g.
 // From E_mu, sum|d|, sum d^2 to the per-element coefficients: E_p/|g| = K1 |d| + K0.
 __device__ __forceinline__ void layernorm_tail(double E_mu, double s_ad, double s_d2, double n, const RowConsts& k,
-                                               double& K1, double& K0) {
+                                               double& K1, double& K0, double& amp) {
     const double up = k.u * k.inv1mu, Ep = E_mu * k.inv1mu;       // u', E'
     const double c1 = 1.0 + up;
     const double sD2 = c1 * c1 * s_d2 + 2.0 * c1 * Ep * s_ad + n * Ep * Ep;           // sum D^2
@@ -313,7 +326,7 @@ __device__ __forceinline__ void layernorm_tail(double E_mu, double s_ad, double 
     const double vstar = s_d2 * k.inv_n;
     const double E_v = (E_t * k.inv_n + k.cd_u * vstar) * k.inv1mcd;
     double rs, E_r, R;
-    const bool ok = rsqrt_tail(vstar, E_v, k, rs, E_r, R);
+    const bool ok = rsqrt_tail(vstar, E_v, k, rs, E_r, R, amp);
     const double hc = E_r + k.u * R;                              // E_h = D hc + r E_d
     K1 = (1.0 + k.u) * (c1 * hc + rs * up) + k.u * rs;
     K0 = ok ? (1.0 + k.u) * Ep * (hc + rs) : NAN;                 // NaN row when the bound is not finite
@@ -375,8 +388,9 @@ __device__ __forceinline__ void layernorm_body(
         }
     }
     group_sum<TPR>(a2, 2, smem + 16);
-    double K1, K0;
-    layernorm_tail(E_mu, a2[0], a2[1], n, k, K1, K0);
+    double K1, K0, amp;
+    layernorm_tail(E_mu, a2[0], a2[1], n, k, K1, K0, amp);
+    const UpFactors up(k.m * (1.0 + 2.0 * amp));
     for (int v = 0; v < nv; ++v) {
         const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
         const float4 Y = CACHED ? yv[v] : load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
@@ -388,7 +402,7 @@ __device__ __forceinline__ void layernorm_body(
         for (int c = 0; c < 4; ++c) {
             const double ad = fabs((double)xe[c] - mu);
             const double ep = (double)fabsf(ge[c]) * fma(K1, ad, K0);
-            te[c] = up32g(fma(k.u, (double)fabsf(ye[c]), ep));
+            te[c] = up32g(fma(k.u, (double)fabsf(ye[c]), ep), up.mul, up.sub);
         }
         store4(tau + roff, TAO_VEC_INDEX(v), limit, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
     }
@@ -483,8 +497,9 @@ __global__ __launch_bounds__(kRowThreads) void groupnorm_apply(
     const double n = (double)cols;
     const double mu = t1[0] * k.inv_n;
     const double E_mu = ((k.G * t1[1]) * k.inv_n + k.cd_u * fabs(mu)) * k.inv1mcd;
-    double K1, K0;
-    layernorm_tail(E_mu, t2[0], t2[1], n, k, K1, K0);
+    double K1, K0, amp;
+    layernorm_tail(E_mu, t2[0], t2[1], n, k, K1, K0, amp);
+    const UpFactors up(k.m * (1.0 + 2.0 * amp));
     const long roff = p.row * cols + p.c0;
     const float* gb = g ? g + (unsigned long)(p.row % (long)gg.groups) * gg.cpg : nullptr;
 #pragma unroll 2
@@ -509,7 +524,7 @@ __global__ __launch_bounds__(kRowThreads) void groupnorm_apply(
         for (int c = 0; c < 4; ++c) {
             const double ad = fabs((double)xe[c] - mu);
             const double ep = (double)fabsf(ge[c]) * fma(K1, ad, K0);
-            te[c] = up32g(fma(k.u, (double)fabsf(ye[c]), ep));
+            te[c] = up32g(fma(k.u, (double)fabsf(ye[c]), ep), up.mul, up.sub);
         }
         store4(tau + roff, idx, p.limit, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
     }
@@ -538,9 +553,10 @@ __global__ __launch_bounds__(kRowThreads) void rmsnorm_bound(
     const double E_t = (k.G * (1.0 + k.u) + k.u) * a1[0];
     const double vstar = a1[0] * k.inv_n;
     const double E_v = (E_t * k.inv_n + k.cd_u * vstar) * k.inv1mcd;
-    double rs, E_r, R;
-    const bool ok = rsqrt_tail(vstar, E_v, k, rs, E_r, R);
+    double rs, E_r, R, amp;
+    const bool ok = rsqrt_tail(vstar, E_v, k, rs, E_r, R, amp);
     const double f = E_r + k.u * R;
+    const UpFactors up(k.m * (1.0 + 2.0 * amp));
     for (int v = 0; v < nv; ++v) {
         const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
         const float4 Y = CACHED ? yv[v] : load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
@@ -552,7 +568,7 @@ __global__ __launch_bounds__(kRowThreads) void rmsnorm_bound(
         for (int c = 0; c < 4; ++c) {
             const double xg = fabs((double)xe[c] * (double)ge[c]);
             const double t = xg * f + k.u * fabs((double)ye[c]);
-            te[c] = ok ? up32g(t) : NAN;
+            te[c] = ok ? up32g(t, up.mul, up.sub) : NAN;
         }
         store4(tau + roff, TAO_VEC_INDEX(v), limit, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
     }
@@ -607,14 +623,14 @@ __global__ __launch_bounds__(kCheckThreads) void norm_check(
             }
         }
         wide_group_sum<TPR>(a1, RMS ? 1 : 2, smem);
-        double mu = 0.0, K1 = 0.0, K0 = 0.0, f = 0.0;
+        double mu = 0.0, K1 = 0.0, K0 = 0.0, f = 0.0, amp = 1.0;
         bool ok = true;
         if (RMS) {
             const double E_t = (k.G * (1.0 + k.u) + k.u) * a1[0];
             const double vstar = a1[0] * k.inv_n;
             const double E_v = (E_t * k.inv_n + k.cd_u * vstar) * k.inv1mcd;
             double rs, E_r, R;
-            ok = rsqrt_tail(vstar, E_v, k, rs, E_r, R);
+            ok = rsqrt_tail(vstar, E_v, k, rs, E_r, R, amp);
             f = E_r + k.u * R;
         } else {
             mu = a1[0] * k.inv_n;
@@ -631,8 +647,9 @@ __global__ __launch_bounds__(kCheckThreads) void norm_check(
                 }
             }
             wide_group_sum<TPR>(a2, 2, smem + 4 * (kCheckThreads / kWave));
-            layernorm_tail(E_mu, a2[0], a2[1], n, k, K1, K0);
+            layernorm_tail(E_mu, a2[0], a2[1], n, k, K1, K0, amp);
         }
+        const UpFactors up(k.m * (1.0 + 2.0 * amp));
         for (int v = 0; v < nv; ++v) {
             const long idx = TAO_VEC_INDEX(v);
             if (idx >= limit) continue;
@@ -649,11 +666,11 @@ __global__ __launch_bounds__(kCheckThreads) void norm_check(
                 if (RMS) {
                     const double xg = fabs((double)xe[c] * (double)ge[c]);
                     const double tt = xg * f + k.u * fabs((double)ye[c]);
-                    t = ok ? up32g(tt) : NAN;
+                    t = ok ? up32g(tt, up.mul, up.sub) : NAN;
                 } else {
                     const double ad = fabs((double)xe[c] - mu);
                     const double ep = (double)fabsf(ge[c]) * fma(K1, ad, K0);
-                    t = up32g(fma(k.u, (double)fabsf(ye[c]), ep));
+                    t = up32g(fma(k.u, (double)fabsf(ye[c]), ep), up.mul, up.sub);
                 }
                 check_one(ce[c], ye[c], t, alpha, eps_rel, hist, rep, acc_chk);
             }
@@ -679,7 +696,8 @@ __global__ __launch_bounds__(kRowThreads) void summean_bound(
     if (active && lt == 0) {
         double t = k.G * a1[0];
         if (is_mean) t = t * k.inv_n + fabs((double)y[row]) * k.mean_f;
-        tau[row] = up32g(t);
+        const UpFactors up(k.m);
+        tau[row] = up32g(t, up.mul, up.sub);
     }
 }
 
@@ -708,7 +726,7 @@ __global__ __launch_bounds__(kRowThreads) void bn_affine_bound(
         for (int c = 0; c < 4; ++c) {
             const double xs = fabs((double)xe[c] * (double)se[c]);
             const double t = u * xs * (1.0 + u) + u * fabs((double)ye[c]);
-            te[c] = up32g(t);
+            te[c] = up32g(t, kUpMul, 1.0 + 0x1p-48);
         }
         store4(tau + row * ld, j, cols, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
     }
@@ -733,9 +751,13 @@ __global__ __launch_bounds__(kRowThreads) void bn_affine_bound(
         else                 hipLaunchKernelGGL((KERNEL<256, 0>), grid_(256), dim3(kRowThreads), 0, stream, __VA_ARGS__); \
     } while (0)
 
-static int make_consts(const tao_fp_model& md, long cols, double eps, RowConsts* k) {
+// variance: the operator divides by a computed variance (LayerNorm, RMSNorm, GroupNorm).  Its
+// template subtracts the variance's own error bound, about Gamma(n-1) times the variance, from the
+// variance: beyond Gamma(n-1) = 1/2 the difference has lost its relative accuracy (and soon its
+// sign), so such rows are refused rather than bounded by noise.
+static int make_consts(const tao_fp_model& md, long cols, double eps, RowConsts* k, bool variance = false) {
     const double G = gamma_up(cols - 1, md);
-    if (!(G == G)) return TAO_ERR_K_RANGE;
+    if (!(G == G) || (variance && G > 0.5)) return TAO_ERR_K_RANGE;
     const double u = md.u;
     k->u = u; k->G = G;
     k->inv1mu = widen(1.0 / (1.0 - u));
@@ -747,6 +769,13 @@ static int make_consts(const tao_fp_model& md, long cols, double eps, RowConsts*
     k->eps = (double)(float)eps;
     k->inv_n = 1.0 / (double)cols;
     k->mean_f = widen(k->cd_u * k->inv1mcd);
+    // Rounding margin of the emitted bound.  The row sums are formed here in round-to-nearest
+    // binary64 (each thread a sequential part, then a tree: at most cols 2^-53 below the real sum),
+    // and a reference that adds the row sequentially with upward rounding sits up to cols 2^-52
+    // above it; the scalar chain after the sums adds a few dozen roundings.  m covers both for a
+    // bound that depends on the sums with unit sensitivity; the kernels scale it where a sum enters
+    // through a difference (1 - sigma of the softmax, the lower end w_lo of the variance).
+    k->m = ((double)cols + 130.0) * 0x1p-51;
     if (!(md.c_exp * u < 0.5) || !(md.c_div * u < 0.5)) return TAO_ERR_MODEL;
     return TAO_OK;
 }
@@ -793,7 +822,7 @@ int tao_bound_norm(int kind, const float* x, const float* y_ref, const float* ga
     if (!aligned(x, 4) || !aligned(y_ref, 4) || !aligned(tau, 4) || !aligned(gamma_or_scale, 4)) return TAO_ERR_ALIGN;
     if (!(eps >= 0.0) || !std::isfinite(eps)) return TAO_ERR_SHAPE;
     RowConsts k;
-    rc = make_consts(md, cols, eps, &k);
+    rc = make_consts(md, cols, eps, &k, kind == TAO_NORM_LAYERNORM || kind == TAO_NORM_RMSNORM);
     if (rc != TAO_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     const int vec_x = aligned(x, 16) && (ld % 4 == 0);
@@ -851,7 +880,7 @@ int tao_bound_groupnorm(const float* x, const float* y_ref, const float* gamma, 
     if (!aligned(x, 4) || !aligned(y_ref, 4) || !aligned(tau, 4) || !aligned(gamma, 4)) return TAO_ERR_ALIGN;
     if (!(eps >= 0.0) || !std::isfinite(eps)) return TAO_ERR_SHAPE;
     RowConsts k;
-    rc = make_consts(md, cols, eps, &k);
+    rc = make_consts(md, cols, eps, &k, true);
     if (rc != TAO_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     const int vec_ok = aligned(x, 16) && aligned(y_ref, 16) && aligned(tau, 16) && (cols % 4 == 0);
@@ -897,7 +926,7 @@ int tao_bound_check_norm(int kind, const float* x, const float* y_ref, const flo
         return TAO_ERR_ALIGN;
     if (!aligned(ws, 256) || ws_bytes < check_workspace_bytes()) return TAO_ERR_WORKSPACE;
     RowConsts k;
-    rc = make_consts(md, cols > 0 ? cols : 1, eps, &k);
+    rc = make_consts(md, cols > 0 ? cols : 1, eps, &k, true);
     if (rc != TAO_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     const int vec_ok = aligned(x, 16) && (ld % 4 == 0) && aligned(y_ref, 16) && aligned(claimed, 16);

@@ -15,16 +15,28 @@ __device__ __forceinline__ float up32(double v) {
     return f;
 }
 
-// Cheaper upper rounding for the streaming kernels (four operations instead of five, no branch), which also
-// takes the place of the guard factor: for v >= 0 the result is a binary32 value >= v(1 + 2^-33)
-// and at most v(1 + 2^-23 + 2^-31) (three halves of that near the bottom of the normal range).
-// v(1 + 2^-24 + 2^-32) lies above the midpoint of the two binary32 neighbours of v, so round-to-
-// nearest moves it to the upper one; the 2^-150 keeps that true among subnormal results, where
-// rounding is absolute (0 stays 0: the tie goes to even; any v > 0 gets the next binary64 above
-// 2^-150 instead, so that a v too small to move the sum still ends on the smallest subnormal).
+// Cheaper upper rounding for the streaming kernels, which also takes the place of the guard
+// factor: for v >= 0 the result is a binary32 value >= v (1 + m) and at most one binary32 step
+// above the smallest such value, where m is the rounding margin the caller asks for.
+//  - Normal results: with mul = 1 + 2^-24 + 2m the product v mul lies above the midpoint of the
+//    binary32 neighbours of v (1 + m) (their distance is at most 2^-23 of the lower one), so the
+//    conversion's round-to-nearest lands on the upper neighbour or beyond: no compare, no step.
+//  - Results below 2^-126 (subnormal, or zero): the spacing is absolute there and one step is a
+//    large relative amount, so v (1 + m) is rounded up exactly (sub = 1 + m): the result is the
+//    smallest representable value >= v sub, and 0 stays 0.
+// The defaults serve the element-wise kernels (a handful of binary64 roundings and, for GELU, an
+// exponential accurate to 2^-40); the row kernels pass constants that grow with the row length.
 // NaN and +inf pass through.
-__device__ __forceinline__ float up32g(double v) {
-    return (float)fma(v, 1.0 + 0x1p-24 + 0x1p-32, v > 0.0 ? 0x1.0000000000001p-150 : 0x1p-150);
+constexpr double kUpMul = 1.0 + 0x1p-24 + 0x1p-32;
+constexpr double kUpSub = 1.0 + 0x1p-36;
+__device__ __forceinline__ float up32g(double v, double mul = kUpMul, double sub = kUpSub) {
+    float f = (float)(v * mul);
+    if (f < 0x1p-126f) {
+        const double w = v * sub;
+        f = (float)w;
+        if ((double)f < w) f = __uint_as_float(__float_as_uint(f) + 1u);
+    }
+    return f;
 }
 
 __device__ __forceinline__ double wave_sum(double v) {

@@ -44,10 +44,10 @@ double gamma_up(long k, const tao_fp_model& m);            // NaN when undefined
 inline double widen(double v) { return v * (1.0 + 0x1p-49); }   // for v >= 0
 
 // Every kernel evaluates its formula in round-to-nearest binary64; a margin that dominates the
-// accumulated binary64 rounding (at most ~2^-52 per operation, rows up to 2^24 elements) keeps the
-// emitted bound at or above the real-number value.  The matrix kernel multiplies by this factor
-// and rounds up exactly (up32); the streaming kernels fold the margin into their upper rounding
-// (up32g, at least 1 + 2^-33).
+// accumulated binary64 rounding keeps the emitted bound at or above the real-number value.  The
+// matrix kernel multiplies by this factor and rounds up exactly (up32); the streaming kernels fold
+// a margin into their upper rounding (up32g): a fixed one for element-wise work, one that grows
+// with the row length ((cols + 130) 2^-51, at least 2^-33) for the row kernels.
 constexpr double kGuard = 1.0 + 0x1p-32;
 
 }  // namespace tao

@@ -64,8 +64,7 @@ def assert_bound_parity(tau_gpu, tau_or, what="", rel_tol=REL_TOL):
     below = g < o
     assert not below.any(), "%s: %d elements below the oracle, worst ratio %.3e" % (
         what, below.sum(), (g[below] / o[below]).min())
-    # one binary32 subnormal step is allowed at the very bottom of the range
-    above = g > o * (1.0 + rel_tol) + 2.0 ** -149
+    above = g > o * (1.0 + rel_tol)
     assert not above.any(), "%s: %d elements above tolerance, worst excess %.3e" % (
         what, above.sum(), (g[above] / np.maximum(o[above], 1e-300) - 1).max())
     pos = o > 0

@@ -48,6 +48,7 @@ def test_matrix_core_selftest(tao):
     rep = tao.tao_selftest_matrix_core()
     print("matrix-core self test report:", rep, flush=True)
     assert rep & 1, "accumulation is not round-to-nearest-even"
+    assert rep & 2, "subnormal products or operands are flushed"
     assert rep & 4, "6-step chain exceeds gamma_6"
 
 
@@ -305,8 +306,10 @@ def test_linear_unaligned_views_and_modes(tao, oracle_mod):
     # underflow term
     mo, mg = oracle_mod.Model(flags=1), tao.FpModel(flags=tao.FLAG_UNDERFLOW_TERMS)
     tiny = (A * 1e-30, W * 1e-12)
-    assert_bound_parity(_np(tao.tao_bound_linear(tiny[0], tiny[1], model=mg)),
-                        oracle_mod.bound_linear(_np(tiny[0]), _np(tiny[1]), model=mo), "underflow term")
+    # (with the flag the bound carries absolute terms of the order of the subnormal step itself, on both
+    # sides: the flag's contract is the reference's value or the next binary32 value above it)
+    t_uf, t_uf_or = _np(tao.tao_bound_linear(tiny[0], tiny[1], model=mg)), oracle_mod.bound_linear(_np(tiny[0]), _np(tiny[1]), model=mo)
+    assert np.all(t_uf >= t_uf_or) and np.all(t_uf <= np.nextafter(t_uf_or * np.float32(1 + 1e-6), np.float32(np.inf)))
     # single-chain accumulation: still never below the oracle, looser by at most ~2 K u
     fast = _np(tao.tao_bound_linear(A, W, model=tao.FpModel(flags=tao.FLAG_FAST_ACCUM)))
     K = A.shape[1]
@@ -346,8 +349,6 @@ def test_softmax_padded_rows_and_probabilistic(tao, oracle_mod):
 @pytest.mark.parametrize("kind", ["layernorm", "rmsnorm", "bn_affine", "sum", "mean"])
 @pytest.mark.parametrize("rows,cols", [(1, 1), (5, 3), (16, 256), (7, 768), (3, 1030), (4, 4096), (2, 8200)])
 def test_norm_shapes(tao, oracle_mod, kind, rows, cols):
-    if kind in ("layernorm",) and cols == 1:
-        pytest.skip("variance of a single element is zero: NaN row by construction, covered below")
     g = torch.Generator().manual_seed(rows * 7919 + cols)
     x = torch.randn((rows, cols), generator=g) * 2 + 0.5
     gam = 1 + 0.1 * torch.randn((cols,), generator=g)
@@ -367,6 +368,107 @@ def test_norm_shapes(tao, oracle_mod, kind, rows, cols):
     t_or = oracle_mod.bound_norm(code, _np(x), y=None if y is None else _np(y), g=_np(gam), b=_np(bet), eps=eps)
     t_gpu = tao.tao_bound_norm(code, x.cuda(), None if y is None else y.cuda(), gam.cuda(), bet.cuda(), eps=eps)
     assert_bound_parity(_np(t_gpu), t_or, "%s %dx%d" % (kind, rows, cols))
+
+
+@pytest.mark.parametrize("cols", [1 << 20, (1 << 22) + 3, 1 << 23])
+def test_very_long_rows(tao, oracle_mod, cols):
+    """One row of millions of columns: the reference adds the row sequentially with upward rounding
+    (up to cols 2^-52 above the real sum) and the kernels add it as a tree in round-to-nearest, so the
+    margin of the kernels' final upper rounding has to grow with the row length for the bound to
+    stay at or above the reference's -- and the whole still has to fit the 1e-6 tolerance."""
+    g = torch.Generator().manual_seed(cols)
+    x = torch.randn((1, cols), generator=g) + 0.25
+    gam = 1 + 0.1 * torch.randn((cols,), generator=g)
+    bet = 0.1 * torch.randn((cols,), generator=g)
+    xs = x * 3
+    ys = tao_inputs.softmax_f32(xs)
+    assert_bound_parity(_np(tao.tao_bound_softmax(xs.cuda(), ys.cuda())), oracle_mod.bound_softmax(_np(xs), _np(ys)),
+                        "softmax 1x%d" % cols)
+    for kind, code in (("sum", 3), ("mean", 4), ("rmsnorm", 1), ("layernorm", 0)):
+        if kind == "sum":
+            y = None
+        elif kind == "mean":
+            y = x.sum(-1) / cols
+        elif kind == "rmsnorm":
+            y = tao_inputs.rmsnorm_f32(x, gam, 1e-6)
+        else:
+            y = tao_inputs.layernorm_f32(x, gam, bet, 1e-6)
+        if code in (0, 1) and cols > 5_590_000:
+            # Gamma(n - 1) > 1/2: the variance's error bound has eaten the variance; refused
+            with pytest.raises(tao.TaoError) as ei:
+                tao.tao_bound_norm(code, x.cuda(), y.cuda(), gam.cuda(), bet.cuda(), eps=1e-6)
+            assert ei.value.status == tao.ERR_K_RANGE
+            continue
+        t_or = oracle_mod.bound_norm(code, _np(x), y=None if y is None else _np(y), g=_np(gam), b=_np(bet), eps=1e-6)
+        t_gpu = tao.tao_bound_norm(code, x.cuda(), None if y is None else y.cuda(), gam.cuda(), bet.cuda(), eps=1e-6)
+        worst = assert_bound_parity(_np(t_gpu), t_or, "%s 1x%d" % (kind, cols))
+        print("   %s 1x%d: max tau_gpu/tau_oracle - 1 = %.3e" % (kind, cols, worst), flush=True)
+
+
+def test_bounds_in_the_subnormal_range(tao, oracle_mod):
+    """Bounds that land among the binary32 subnormals (one step there is a large relative amount):
+    the kernels round such values up exactly, so they agree with the reference to the stated
+    tolerance without any absolute allowance."""
+    g = torch.Generator().manual_seed(4242)
+    # softmax rows with a wide spread: most outputs, and their bounds, are tiny or zero
+    x = torch.randn((64, 300), generator=g) * 25
+    y = tao_inputs.softmax_f32(x)
+    t_or = oracle_mod.bound_softmax(_np(x), _np(y))
+    assert ((t_or > 0) & (t_or < 2.0 ** -126)).sum() > 100
+    assert_bound_parity(_np(tao.tao_bound_softmax(x.cuda(), y.cuda())), t_or, "softmax, subnormal bounds")
+    # element-wise kinds and the row kernels on outputs scaled into the subnormal range
+    ysm = (torch.randn((8, 1000), generator=g) * 1e-33).contiguous()
+    xsm = torch.randn((8, 1000), generator=g)
+    for kind in (0, 1, 2, 6, 17):
+        t_or = oracle_mod.bound_act(kind, _np(xsm * 1e-32), _np(ysm))
+        assert_bound_parity(_np(tao.tao_bound_act(kind, (xsm * 1e-32).cuda(), ysm.cuda())), t_or, "act %d, subnormal bounds" % kind)
+    gam = (torch.randn((1000,), generator=g) * 1e-34).contiguous()
+    for code in (0, 1, 2):
+        t_or = oracle_mod.bound_norm(code, _np(xsm), y=_np(ysm), g=_np(gam), b=None, eps=1e-5)
+        assert ((t_or > 0) & (t_or < 2.0 ** -126)).sum() > 100
+        assert_bound_parity(_np(tao.tao_bound_norm(code, xsm.cuda(), ysm.cuda(), gam.cuda(), None, eps=1e-5)), t_or,
+                            "norm %d, subnormal bounds" % code)
+    cs = torch.cos(torch.arange(32 * 64, dtype=torch.float32).reshape(32, 64) * 0.01)
+    sn = torch.sin(torch.arange(32 * 64, dtype=torch.float32).reshape(32, 64) * 0.01)
+    xr = (torch.randn((32, 128), generator=g) * 1e-33).contiguous()
+    assert_bound_parity(_np(tao.tao_bound_rope(xr.cuda(), cs.cuda(), sn.cuda(), inner=1)),
+                        oracle_mod.bound_rope(_np(xr), _np(cs), _np(sn), inner=1), "rope, subnormal bounds")
+
+
+def test_linear_tiny_operands_stay_above_the_reference(tao, oracle_mod):
+    """Operands so small that products and partial sums fall into the binary32 subnormal range (or
+    below it), with default flags: the matrix cores round such values absolutely, not relatively,
+    so the bound carries an absolute term for its own evaluation and may exceed 1e-6 there -- but
+    it never falls below the reference, which forms the products exactly in binary64."""
+    g = torch.Generator().manual_seed(99)
+    for sa, sw in ((1e-30, 1e-12), (1e-20, 1e-20), (1e-25, 1e-12), (1e-38, 1.0), (1e-19, 1e-19)):
+        for M, N, K in ((70, 130, 200), (128, 128, 64), (33, 17, 1031)):
+            A = torch.randn((M, K), generator=g) * sa
+            W = torch.randn((N, K), generator=g) * sw
+            t_or = oracle_mod.bound_linear(_np(A), _np(W))
+            t_gpu = _np(tao.tao_bound_linear(A.cuda(), W.cuda()))
+            assert np.all(t_gpu >= t_or), "FP32 path below the reference at scales %g x %g: %d elements" % (
+                sa, sw, int((t_gpu < t_or).sum()))
+            # the excess is the absolute term: Gamma(K) (1.25 K + 40) 2^-150, i.e. a few subnormal steps
+            K_ = float(K)
+            slack = (K_ * 2.0 ** -24 / (1 - K_ * 2.0 ** -24)) * (1.25 * K_ + 40) * 2.0 ** -150 * 1.01
+            assert np.all(t_gpu <= t_or.astype(np.float64) * (1 + 1e-6) + slack + 2.0 ** -149)
+            # the same operands through the BF16-split path (its absolute term: Gamma(K) (Kp + 32) 2^-149)
+            t_split = _np(tao.tao_bound_linear_split(A.cuda(), W.cuda()))
+            assert np.all(t_split >= t_or), "BF16 path below the reference at scales %g x %g: %d elements" % (
+                sa, sw, int((t_split < t_or).sum()))
+            Kp = float((K + 31) // 32 * 32)
+            slack = (K_ * 2.0 ** -24 / (1 - K_ * 2.0 ** -24)) * (Kp + 32) * 2.0 ** -149 * 1.01
+            if min(sa, sw) >= 1e-25:           # operands below 2^-110 round their third piece up: sound, looser
+                assert np.all(t_split <= t_or.astype(np.float64) * (1 + 1e-6) + slack + 2.0 ** -149)
+    # products that vanish altogether (every one below 2^-150): with the underflow terms the bound still
+    # covers the reference, which adds K' 2^-149 to the exact sum
+    mo, mg = oracle_mod.Model(flags=1), tao.FpModel(flags=tao.FLAG_UNDERFLOW_TERMS)
+    A = torch.randn((70, 200), generator=g) * 1e-30
+    W = torch.randn((130, 200), generator=g) * 1e-20
+    t_or = oracle_mod.bound_linear(_np(A), _np(W), model=mo)
+    for t_gpu in (_np(tao.tao_bound_linear(A.cuda(), W.cuda(), model=mg)), _np(tao.tao_bound_linear_split(A.cuda(), W.cuda(), model=mg))):
+        assert np.all(t_gpu >= t_or) and np.all(t_gpu <= t_or + np.float32(2.0 ** -149))
 
 
 @pytest.mark.parametrize("kind", ["layernorm", "rmsnorm"])
