@@ -327,6 +327,20 @@ int tao_check_and_profile(const float *claimed, const float *ref, const float *t
                           double alpha, double eps_rel, tao_profile *out,
                           void *ws, size_t ws_bytes, void *stream);
 
+/* tao_check_and_profile for callers that cannot allocate device memory or hand over a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * kernels and, field for field, the same result, with the partial histograms and counters in a
+ * fixed array inside the library (about 2.1 MB of device memory per GPU the call has run on, held
+ * until the process ends) instead of `ws`.  Allocates nothing and calls no allocating routine; the
+ * first call on a device looks up the array's address there.  n may be at most
+ * TAO_STATIC_CHECK_MAX_N (TAO_ERR_SHAPE beyond it: the per-workgroup counters are 32 bits wide);
+ * other errors as for tao_check_and_profile.  All calls on one GPU share the one array: calls that
+ * may overlap there (different streams, different threads) race and must be ordered by the caller;
+ * calls on one stream are ordered by the stream.  Nothing has to be cleared between calls. */
+#define TAO_STATIC_CHECK_MAX_N ((1L << 36) - 1)
+int tao_check_and_profile_static(const float *claimed, const float *ref, const float *tau, long n,
+                                 double alpha, double eps_rel, tao_profile *out, void *stream);
+
 /* Bytes of DEVICE workspace tao_check_and_profile needs for n elements (per-
  * workgroup partial histograms and counters).  The workspace must be 256-byte
  * aligned; its contents on entry do not matter and are garbage afterwards.

@@ -95,6 +95,7 @@ EXPORTS = ["tao_default_model", "tao_gamma", "tao_bound_linear", "tao_bound_line
            "tao_linear_split_workspace_bytes", "tao_linear_split_preferred", "tao_bound_check_linear_in_epilogue",
            "tao_bound_check_linear", "tao_bound_check_linear_workspace_bytes", "tao_selftest_matrix_core_bf16", "tao_bound_conv2d", "tao_bound_softmax",
            "tao_bound_norm", "tao_bound_groupnorm", "tao_groupnorm_workspace_bytes", "tao_bound_act", "tao_bound_check_act", "tao_bound_rope", "tao_bound_check_rope", "tao_bound_check_norm", "tao_check_and_profile",
+           "tao_check_and_profile_static",
            "tao_check_workspace_bytes", "tao_bound_check_softmax", "tao_profile_errors", "tao_profile_workspace_bytes",
            "tao_calibrate_thresholds", "tao_project_clip", "tao_project_empirical", "tao_project_workspace_bytes",
            "tao_selftest_matrix_core", "tao_last_hip_error", "tao_status_string"]
@@ -147,6 +148,7 @@ def lib():
                                        ctypes.c_size_t, vp]
     L.tao_bound_rope.argtypes = [vp, vp, vp, vp, lg, lg, lg, lg, ctypes.c_int, mp, vp]
     L.tao_check_and_profile.argtypes = [vp, vp, vp, lg, dbl, dbl, vp, vp, ctypes.c_size_t, vp]
+    L.tao_check_and_profile_static.argtypes = [vp, vp, vp, lg, dbl, dbl, vp, vp]
     L.tao_check_workspace_bytes.argtypes = [lg]
     L.tao_bound_check_softmax.argtypes = [vp, vp, vp, lg, lg, lg, dbl, dbl, mp, vp, vp, ctypes.c_size_t, vp]
     L.tao_check_workspace_bytes.restype = ctypes.c_size_t
@@ -532,6 +534,28 @@ def tao_check_and_profile(claimed, ref, tau, alpha=1.0, eps_rel=1e-12, out=None,
     rc = lib().tao_check_and_profile(_ptr(claimed), _ptr(ref), _ptr(tau), n, float(alpha),
                                      float(eps_rel), _ptr(out), _ptr(ws), ws.numel(), _stream())
     _check(rc, "tao_check_and_profile")
+    return read_profile(out) if readback else out
+
+
+STATIC_CHECK_MAX_N = (1 << 36) - 1
+
+
+def tao_check_and_profile_static(claimed, ref, tau, alpha=1.0, eps_rel=1e-12, out=None, readback=True):
+    """tao_check_and_profile through the entry point that allocates nothing (its scratch memory is a
+    fixed array inside the library).  `out` must be a buffer from new_profile_buffer when the caller
+    may not allocate either."""
+    claimed = _dev(claimed, "claimed"); ref = _dev(ref, "ref"); tau = _dev(tau, "tau")
+    for t, nm in ((claimed, "claimed"), (ref, "ref"), (tau, "tau")):
+        if not t.is_contiguous():
+            raise ValueError("%s must be contiguous" % nm)
+    n = claimed.numel()
+    if ref.numel() != n or tau.numel() != n:
+        raise ValueError("claimed, ref and tau must have the same number of elements")
+    if out is None:
+        out = new_profile_buffer(claimed.device)
+    rc = lib().tao_check_and_profile_static(_ptr(claimed), _ptr(ref), _ptr(tau), n, float(alpha),
+                                            float(eps_rel), _ptr(out), _stream())
+    _check(rc, "tao_check_and_profile_static")
     return read_profile(out) if readback else out
 
 

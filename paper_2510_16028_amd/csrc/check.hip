@@ -13,6 +13,7 @@
 // number of elements below its own bins; it can then decide by itself whether a
 // nearest-rank percentile falls into one of its bins -- no cross-workgroup
 // ordering, fences or atomics.  Workgroup 0 also writes the scalar fields.
+#include <atomic>
 #include "tao_check.hpp"
 
 namespace tao {
@@ -95,9 +96,47 @@ void launch_profile_reduce(const CheckWorkspace& w, int nblocks, unsigned long l
                        w.stats, nblocks, n, out);
 }
 
+// ---- the entry point that allocates nothing -------------------------------------------------
+// Its partial histograms and counters live in this array instead of a caller's workspace: one copy
+// per device, held until the process ends.  Host code never uses the array's name as an address
+// (on the host it is only a handle): the device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[check_workspace_bytes()];
+
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device (looked up on the first call there).
+static int static_scratch(void** ptr) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { g_last_hip_error = (int)e; return TAO_ERR_LAUNCH; }
+    if (dev < 0 || dev >= kMaxDevices) return TAO_ERR_WORKSPACE;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) { g_last_hip_error = (int)e; return TAO_ERR_LAUNCH; }
+        g_scratch_ptr[dev].store(p, std::memory_order_release);   // (two racing threads store the same address)
+    }
+    *ptr = p;
+    return TAO_OK;
+}
+
 }  // namespace tao
 
 extern "C" {
+
+int tao_check_and_profile_static(const float* claimed, const float* ref, const float* tau, long n,
+                                 double alpha, double eps_rel, tao_profile* out, void* stream) {
+    using namespace tao;
+    if (!out) return TAO_ERR_NULL;
+    if (n < 0 || n > TAO_STATIC_CHECK_MAX_N || !(eps_rel >= 0.0)) return TAO_ERR_SHAPE;
+    void* ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != TAO_OK) return rc;
+    // every workgroup of the pass overwrites its own partial result and the finalising kernel reads
+    // only those, so nothing of the previous call's contents has to be cleared
+    return tao_check_and_profile(claimed, ref, tau, n, alpha, eps_rel, out, ws, check_workspace_bytes(), stream);
+}
 
 size_t tao_check_workspace_bytes(long n) {
     (void)n;

@@ -91,7 +91,7 @@ __device__ __forceinline__ void flush_block_stats(const ThreadAcc& acc, unsigned
 struct CheckWorkspace {
     unsigned int* hist; unsigned int* coarse; BlockStats* stats;
 };
-inline size_t check_workspace_bytes() {
+constexpr size_t check_workspace_bytes() {
     return (size_t)kMaxCheckBlocks * ((kBins + kGroups) * sizeof(unsigned int) + sizeof(BlockStats));
 }
 inline CheckWorkspace carve_check_workspace(void* ws) {
