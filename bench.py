@@ -4,16 +4,20 @@
 A step is one pass of the whole hot path over one batch of synthetic input: for
 every traced operator of a Qwen3-8B-shaped decoder layer (hidden 4096,
 intermediate 12288, 32 q / 8 kv heads, head_dim 128, seq 2048) compute the
-bound tensor tau (linear, softmax, RMSNorm, SiLU, Mul, Add kinds) and run the
-check + relative-error profile of the claimed output against the re-executed
-one.  All inputs are resident in HBM before the timed region.
+bound tensor tau (linear, softmax, RMSNorm, SiLU, Mul, Add, rotary kinds) and run
+the check + relative-error profile of the claimed output against the re-executed
+one.  All inputs are resident in HBM before the timed region.  The weights of the
+layer are committed constants: their BF16 images are prepared once, before the
+timed region; every activation is split again in every step, inside it.
 
 Prints ONE JSON line.  `value` = bytes of claimed operator output verified per
-second (4 bytes per element that went through bound + check).  `roofline` is for
-the dominant kernel (the MFMA |A||W| bound), from HIP events recorded around its
-launches inside the timed region.  `cpu_baseline` times the CPU oracle on a row
-sample of the same workload.  Extra key `kernels` lists the other kernels and
-the 8192^3 / 67M-element stress shapes.
+second (4 bytes per element that went through bound + check) on configuration 3.
+`roofline` is for the dominant kernel (the MFMA |A||W| bound), from HIP events
+recorded around its launches inside the timed region.  `configs` holds the same
+measurement for the other configurations (1, 2, 4 and the 8192^3 stress case),
+`kernels` the individual kernels, also the bound kernels that store tau at
+100 M elements and more.  `cpu_baseline` times the CPU oracle on a row sample of
+configuration 3.
 """
 import argparse
 import json
@@ -26,6 +30,7 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_BF16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel, measured offline with two rocprofv3 counter passes
 # over this same command (FETCH_SIZE, WRITE_SIZE, scaled by a copy kernel); the summary is kept
@@ -43,23 +48,26 @@ def measured_traffic(kernel):
     m = re.search(r"^%s traffic bytes per launch: (\d+)$" % re.escape(kernel), text, re.M)
     return int(m.group(1)) if m else None
 
+
 _NORM = {"layernorm": 0, "rmsnorm": 1, "bn_affine": 2, "sum": 3, "mean": 4}
 _ACT = {"gelu": 0, "silu": 1, "mul": 2, "add": 3, "relu": 4}
 # algorithmic HBM bytes per output element of the streaming bound kernels (inputs read once,
 # tau written once)
 _STREAM_BYTES = {"softmax": 12, "layernorm": 12, "rmsnorm": 12, "bn_affine": 12, "gelu": 12,
                  "silu": 8, "mul": 8, "add": 8, "rope": 8}
-
-
 # the same with the check in the same pass: inputs and the claimed output read once, nothing written
 _FUSED_BYTES = {"softmax": 12, "gelu": 12, "silu": 8, "mul": 8, "add": 8, "relu": 8, "layernorm": 12, "rmsnorm": 12,
                 "rope": 12}
 
 
 class PlannedOp:
-    """One operator with every buffer preallocated; run() only enqueues kernels."""
+    """One operator with every buffer preallocated; run() only enqueues kernels.
 
-    def __init__(self, tao, torch, op, use_split=True, use_fused=True):
+    images: the plan's table of activation images (key: the activation's address); the first operator
+    that multiplies an activation splits it, in every step, and later operators of the step reuse the
+    image (the q / k / v and the gate / up projections share theirs)."""
+
+    def __init__(self, tao, torch, op, images, use_split=True, use_fused=True, prepared=True):
         self.tao, self.op, self.kind, self.name = tao, op, op.kind, op.name
         self.claimed = op.claimed.contiguous()
         self.y_ref = op.y_ref.contiguous()
@@ -67,8 +75,8 @@ class PlannedOp:
         self.prof = tao.new_profile_buffer(self.y_ref.device)
         self.n = self.y_ref.numel()
         a = op.args
-        self.split = False
-        self.fused = False
+        self.split = self.fused = self.prepared = self.conv = False
+        self.owns_image = False
         if self.kind == "linear":
             A, W = a["A"], a["W"]
             K = A.shape[-1]
@@ -76,13 +84,26 @@ class PlannedOp:
             self.min_bytes = 4.0 * (A.numel() + W.numel() + self.n)
             batch = A.shape[0] if A.dim() == 3 else 1
             M, N = self.y_ref.shape[-2], self.y_ref.shape[-1]
+            self.dims = (M, N, K, batch)
+            self.conv = "conv" in op.attrs
             # the library's own rule picks the BF16-split or the FP32 matrix-core path per shape
-            self.split = use_split and tao.tao_linear_split_preferred(M, N, K, batch)
+            self.split = (not self.conv) and use_split and tao.tao_linear_split_preferred(M, N, K, batch)
             # ... and there the check runs in the matrix kernel's epilogue (tau is never stored)
             # (short reductions: the library itself would store the bound and run the streaming check; the
             # benchmark makes the two calls itself so that the matmul figure times the matmul kernels alone)
             self.fused = self.split and use_fused and tao.tao_bound_check_linear_in_epilogue(M, N, K, batch)
-            if self.split:
+            self.prepared = self.split and prepared and bool(op.attrs.get("weight")) and not op.attrs.get("trans_w", 0)
+            if self.prepared:
+                self.w_image = tao.tao_split_operand(W)            # once: the weights do not change
+                key = (A.data_ptr(), tuple(A.shape))
+                if key not in images:
+                    images[key] = torch.empty(tao.tao_split_image_bytes(M, K, batch), dtype=torch.uint8, device=A.device)
+                    self.owns_image = True
+                self.a_image = images[key]
+                need = (tao.lib().tao_check_linear_images_workspace_bytes if self.fused
+                        else tao.lib().tao_linear_images_workspace_bytes)(M, N, K, batch)
+                self.ws = torch.empty(max(int(need), 256), dtype=torch.uint8, device=A.device)
+            elif self.split:
                 shared = W.dim() == 2 or batch == 1
                 need = (tao.tao_bound_check_linear_workspace_bytes if self.fused
                         else tao.tao_linear_split_workspace_bytes)(M, N, K, batch, shared)
@@ -96,9 +117,25 @@ class PlannedOp:
                 self.ws = torch.empty(tao.tao_check_workspace_bytes(self.n), dtype=torch.uint8, device=self.y_ref.device)
         self.bound_events, self.check_events = [], []
 
+    @property
+    def path(self):
+        if self.conv:
+            return "fp32 (implicit patch matrix)"
+        if not self.split:
+            return "fp32"
+        return "bf16_split" + ("+prepared_w" if self.prepared else "") + ("+check" if self.fused else "")
+
     def bound(self):
         tao, a, op = self.tao, self.op.args, self.op
-        if self.kind == "linear" and self.split:
+        if self.kind == "linear" and self.conv:
+            cv = op.attrs["conv"]
+            tao.tao_bound_conv2d(cv["x"], cv["w"], None, 1, cv["padding"], 1, out=self.tau.view(self.conv_shape()))
+        elif self.kind == "linear" and self.prepared:
+            M, N, K, batch = self.dims
+            if self.owns_image:
+                tao.tao_split_operand(a["A"], out=self.a_image)
+            tao.tao_bound_linear_images(self.a_image, self.w_image, M, N, K, bias=a.get("bias"), batch=batch, out=self.tau, ws=self.ws)
+        elif self.kind == "linear" and self.split:
             tao.tao_bound_linear_split(a["A"], a["W"], a.get("bias"), trans_w=bool(op.attrs.get("trans_w", 0)),
                                        out=self.tau, ws=self.ws)
         elif self.kind == "linear":
@@ -114,6 +151,10 @@ class PlannedOp:
             tao.tao_bound_rope(a["x"], a["cos"], a["sin"], inner=op.attrs["inner"], out=self.tau)
         else:
             tao.tao_bound_act(_ACT[self.kind], a.get("x"), self.y_ref, x2=a.get("x2"), out=self.tau)
+
+    def conv_shape(self):
+        x = self.op.attrs["conv"]["x"]                      # [B, H, W, C], 3x3 / stride 1 / pad 1: same extent
+        return (x.shape[0], x.shape[1], x.shape[2], self.tau.shape[-1])
 
     def check(self):
         self.tao.tao_check_and_profile(self.claimed, self.y_ref, self.tau, out=self.prof, readback=False)
@@ -134,6 +175,13 @@ class PlannedOp:
         if self.kind != "linear":
             self.tao.tao_bound_check_act(_ACT[self.kind], a.get("x"), self.y_ref, self.claimed, x2=a.get("x2"),
                                          out=self.prof, ws=self.ws, readback=False)
+            return
+        if self.prepared:
+            M, N, K, batch = self.dims
+            if self.owns_image:
+                self.tao.tao_split_operand(a["A"], out=self.a_image)
+            self.tao.tao_bound_check_linear_images(self.a_image, self.w_image, M, N, K, self.y_ref, self.claimed, bias=a.get("bias"),
+                                                   batch=batch, out=self.prof, ws=self.ws, readback=False)
             return
         self.tao.tao_bound_check_linear(a["A"], a["W"], a.get("bias"), self.y_ref, self.claimed,
                                         trans_w=bool(op.attrs.get("trans_w", 0)), out=self.prof, ws=self.ws,
@@ -169,6 +217,100 @@ def _event_time(torch, fn, reps, warm=2):
         a.record(); fn(); b.record()
     torch.cuda.synchronize()
     return sum(_ms(ev)) / reps
+
+
+def make_plan(torch, tao, ops, args):
+    images = {}
+    return [PlannedOp(tao, torch, op, images, use_split=not args.fp32_only, use_fused=not args.no_fused_check,
+                      prepared=not args.no_prepared_weights) for op in ops]
+
+
+def timed_passes(torch, plan, steps, warmup):
+    """`warmup` untimed passes of the plan, then `steps` timed ones (per-operator HIP events inside)."""
+    for _ in range(warmup):
+        for p in plan:
+            p.run(torch, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        for p in plan:
+            p.run(torch, True)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def plan_summary(tao, plan, ms_per_pass, what):
+    """Whole-pass figures of one configuration: throughput, the matmul bound against the FP32 MFMA peak
+    (algorithmic flop) and the streaming operators against the HBM peak (algorithmic bytes)."""
+    elems = sum(p.n for p in plan)
+    lin = [p for p in plan if p.kind == "linear"]
+    out = {"workload": what, "operators": len(plan), "elements": elems, "ms_per_pass": ms_per_pass,
+           "GB/s_verified": elems * 4 / (ms_per_pass * 1e-3) / 1e9,
+           "violations": sum(tao.read_profile(p.prof)["violations"] for p in plan)}
+    if lin:
+        ms = sum(sum(_ms(p.bound_events)) for p in lin)
+        fl = sum(p.flops * len(p.bound_events) for p in lin)
+        out["matmul"] = {"TFLOP/s": fl / (ms * 1e-3) / 1e12, "frac_fp32_mfma_peak": fl / (ms * 1e-3) / 1e12 / PEAK_FP32_MFMA_TFLOPS,
+                         "ms_per_pass": ms / len(lin[0].bound_events),
+                         "per_op": {p.name: {"shape": list(p.op.args["A"].shape) + [p.op.y_ref.shape[-1]], "path": p.path,
+                                             "TFLOP/s": p.flops / (sum(_ms(p.bound_events)) / len(p.bound_events) * 1e-3) / 1e12,
+                                             "ms": sum(_ms(p.bound_events)) / len(p.bound_events)} for p in lin}}
+    st = [p for p in plan if p.kind != "linear"]
+    if st:
+        # streaming operators: bound (+ check in the same pass where fused); separate checks counted apart
+        ms = sum(sum(_ms(p.bound_events)) for p in st)
+        by = sum((_FUSED_BYTES if p.fused else _STREAM_BYTES)[p.kind] * p.n * len(p.bound_events) for p in st)
+        out["streaming"] = {"GB/s": by / (ms * 1e-3) / 1e9, "frac_hbm": by / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                            "ms_per_pass": ms / len(st[0].bound_events)}
+    chk = [p for p in plan if p.check_events]
+    if chk:
+        ms = sum(sum(_ms(p.check_events)) for p in chk)
+        by = sum(12.0 * p.n * len(p.check_events) for p in chk)
+        out["separate_checks"] = {"GB/s": by / (ms * 1e-3) / 1e9, "frac_hbm": by / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                  "ms_per_pass": ms / len(chk[0].check_events)}
+    return out
+
+
+def stream_bound_kernels(torch, tao, tao_inputs, dev):
+    """The bound kernels that store tau (no check in the same pass) at 100 M elements and more:
+    algorithmic bytes per second against the HBM peak."""
+    out = {}
+    g = torch.Generator(device=dev); g.manual_seed(777)
+
+    def put(name, nbytes, fn, reps=5):
+        ms = _event_time(torch, fn, reps, 1)
+        out[name] = {"ms": ms, "GB/s": nbytes / (ms * 1e-3) / 1e9, "frac_hbm": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+
+    rows, cols = 65536, 2048                                          # 134 M elements, dense rows
+    x = torch.randn((rows, cols), generator=g, device=dev) * 3
+    y = torch.softmax(x, dim=-1); tau = torch.empty_like(x)
+    put("bound_softmax_134M", 12.0 * x.numel(), lambda: tao.tao_bound_softmax(x, y, out=tau))
+    rowpos = torch.arange(rows, device=dev) % cols
+    x.masked_fill_(torch.arange(cols, device=dev)[None, :] > rowpos[:, None], float("-inf"))
+    y = torch.softmax(x, dim=-1)
+    put("bound_softmax_134M_causal", 12.0 * x.numel(), lambda: tao.tao_bound_softmax(x, y, out=tau))
+    del x, y, tau
+    rows, cols = 24576, 4096                                          # 100.7 M
+    x = torch.randn((rows, cols), generator=g, device=dev)
+    gam = 1 + 0.02 * torch.randn((cols,), generator=g, device=dev)
+    y = tao_inputs.rmsnorm_f32(x, gam, 1e-6); tau = torch.empty_like(x)
+    put("bound_rmsnorm_100M", 12.0 * x.numel(), lambda: tao.tao_bound_norm(1, x, y, gam, None, eps=1e-6, out=tau))
+    t1 = torch.empty((rows,), device=dev)
+    put("bound_sum_100M", 4.0 * x.numel(), lambda: tao.tao_bound_norm(3, x, None, out=t1))
+    ym = x.sum(-1) / cols
+    put("bound_mean_100M", 4.0 * x.numel(), lambda: tao.tao_bound_norm(4, x, ym, out=t1))
+    flat_x, flat_y, flat_t = x.view(-1), y.view(-1), tau.view(-1)
+    for nm, kind, nb in (("gelu", 0, 12.0), ("silu", 1, 8.0), ("mul", 2, 8.0)):
+        put("bound_%s_100M" % nm, nb * flat_x.numel(), lambda kind=kind: tao.tao_bound_act(kind, flat_x, flat_y, out=flat_t))
+    del x, y, tau, gam, flat_x, flat_y, flat_t
+    rows, cols = 131072, 768                                          # 100.7 M
+    x = torch.randn((rows, cols), generator=g, device=dev)
+    gam = 1 + 0.02 * torch.randn((cols,), generator=g, device=dev); bet = 0.02 * torch.randn((cols,), generator=g, device=dev)
+    y = tao_inputs.layernorm_f32(x, gam, bet, 1e-12); tau = torch.empty_like(x)
+    put("bound_layernorm_100M", 12.0 * x.numel(), lambda: tao.tao_bound_norm(0, x, y, gam, bet, eps=1e-12, out=tau))
+    put("bound_bn_affine_100M", 12.0 * x.numel(), lambda: tao.tao_bound_norm(2, x, y, gam, bet, out=tau))
+    del x, y, tau
+    return out
 
 
 def projection_only(torch, tao, tao_inputs, dev, n, steps, warmup):
@@ -244,13 +386,18 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=2048, help="output rows per operator for the CPU oracle baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-stress", action="store_true", help="skip the 8192^3 / 67M-element side measurements")
+    ap.add_argument("--no-configs", action="store_true", help="skip configurations 1, 2 and 4 and the 100 M-element bound kernels")
     ap.add_argument("--fp32-only", action="store_true", help="matmul bounds on the FP32 matrix cores only (no BF16-split path)")
     ap.add_argument("--no-fused-check", action="store_true",
                     help="store every tau and run the streaming check after every bound (default: the BF16-split "
                          "matmul kernel and all streaming bound kernels check their bound in registers)")
+    ap.add_argument("--no-prepared-weights", action="store_true",
+                    help="split the weights again in every step (default: their images are prepared once)")
     ap.add_argument("--projection-elems", type=int, default=0,
                     help="only time the two projections of Sec. 4.4 on this many synthetic elements and exit "
                          "(side measurement; used for the committed kernel trace)")
+    ap.add_argument("--only-config", type=int, default=0,
+                    help="only time this configuration (1, 2 or 4) and exit (side measurement; used for the committed kernel traces)")
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run three 1 GiB element-wise copy kernels (reference kernel for scaling FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -271,21 +418,29 @@ def main():
         print(json.dumps(projection_only(torch, tao, tao_inputs, dev, args.projection_elems, args.steps, args.warmup)))
         return
 
-    ops = tao_inputs.config3(dev, scale=args.scale)
-    plan = [PlannedOp(tao, torch, op, use_split=not args.fp32_only, use_fused=not args.no_fused_check) for op in ops]
-    torch.cuda.synchronize()
+    other = {1: ("config 1: one 64x256 @ 256x128 linear and a 64x128 softmax", lambda: tao_inputs.config1(dev)),
+             2: ("config 2: BERT-base-shaped encoder block, seq 512, hidden 768, 12 heads, FFN 3072", lambda: tao_inputs.config2(dev)),
+             4: ("config 4: ResNet-50-like conv stage, batch 32, 56x56x256, 3x3 conv (K = 2304) + BatchNorm-affine",
+                 lambda: tao_inputs.config4(dev))}
 
-    for _ in range(args.warmup):
-        for p in plan:
-            p.run(torch, False)
+    def measure_config(c):
+        what, gen = other[c]
+        cops = gen()
+        cplan = make_plan(torch, tao, cops, args)
+        ms = timed_passes(torch, cplan, args.steps, args.warmup)
+        res = plan_summary(tao, cplan, ms, what)
+        del cplan, cops
+        torch.cuda.empty_cache()
+        return res
+
+    if args.only_config:
+        print(json.dumps(measure_config(args.only_config)))
+        return
+
+    ops = tao_inputs.config3(dev, scale=args.scale)
+    plan = make_plan(torch, tao, ops, args)
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        for p in plan:
-            p.run(torch, True)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = timed_passes(torch, plan, args.steps, args.warmup)
 
     elems = sum(p.n for p in plan)
     violations = sum(tao.read_profile(p.prof)["violations"] for p in plan)
@@ -299,10 +454,10 @@ def main():
     achieved = lin_flops / (lin_ms * 1e-3) / 1e12
     # the matmul bound, both paths together: algorithmic flop (2MNK) per second against the FP32 MFMA
     # peak the metric names; a BF16-split launch issues 8 BF16 products per operand pair and includes
-    # its pre-pass
+    # the pre-pass of its activation (and of its weight, unless that was prepared)
     sp = [p for p in lin if p.split]
     paths = {}
-    for nm, sel, mult, peak in (("bf16_split", sp, 8.0, 2500.0), ("fp32", [p for p in lin if not p.split], 1.0, PEAK_FP32_MFMA_TFLOPS)):
+    for nm, sel, mult, peak in (("bf16_split", sp, 8.0, PEAK_BF16_MFMA_TFLOPS), ("fp32", [p for p in lin if not p.split], 1.0, PEAK_FP32_MFMA_TFLOPS)):
         if sel:
             ms = sum(sum(_ms(p.bound_events)) for p in sel)
             fl = sum(p.flops * len(p.bound_events) for p in sel)
@@ -312,9 +467,18 @@ def main():
                 # operators checked in the matrix kernel's epilogue (tao_bound_check_linear): their launches, and
                 # so this figure, contain the check
                 "check_in_epilogue": [p.name for p in lin if p.fused],
+                "prepared_weight_images": [p.name for p in lin if p.prepared],
                 "achieved": achieved, "peak": PEAK_FP32_MFMA_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS, "paths": paths,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_MFMA_TFLOPS,
+                # the two paths against the peak of the matrix cores each of them runs on: the FP32 path's
+                # algorithmic flop against the FP32 MFMA peak, the BF16-split path's issued flop (8 BF16
+                # products per operand pair) against the BF16 MFMA peak
+                "frac_fp32_path_of_fp32_peak": paths["fp32"]["issued_frac_of_own_peak"] if "fp32" in paths else None,
+                "frac_bf16_path_of_bf16_peak": paths["bf16_split"]["issued_frac_of_own_peak"] if "bf16_split" in paths else None,
+                "paths": paths,
+                # not measured by this run: the figure of the committed rocprofv3 --pmc summary of this command
                 "traffic": measured_traffic("absgemm" if sp else "absgemm_bound") if args.scale == 1 else None,
+                "traffic_source": "offline: profiles/bench_c3_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command)",
                 "compulsory_bytes_per_launch": sum(p.min_bytes for p in lin) / len(lin),
                 "launches": lin_launches, "avg_launch_ms": lin_ms / lin_launches,
                 "flop_per_launch": lin_flops / lin_launches,
@@ -323,9 +487,10 @@ def main():
     kernels = {}
     chk_ms = sum(sum(_ms(p.check_events)) for p in plan)
     chk_bytes = sum(12.0 * p.n * len(p.check_events) for p in plan)
-    kernels["check_and_profile"] = {"GB/s": chk_bytes / (chk_ms * 1e-3) / 1e9,
-                                    "frac_hbm": chk_bytes / (chk_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-                                    "avg_launch_ms": chk_ms / sum(len(p.check_events) for p in plan)}
+    if chk_ms > 0:
+        kernels["check_and_profile"] = {"GB/s": chk_bytes / (chk_ms * 1e-3) / 1e9,
+                                        "frac_hbm": chk_bytes / (chk_ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                        "avg_launch_ms": chk_ms / sum(len(p.check_events) for p in plan)}
     for kind in sorted({p.kind for p in plan if p.kind != "linear"}):
         for fused in (False, True):
             sel = [p for p in plan if p.kind == kind and p.fused == fused]
@@ -338,10 +503,10 @@ def main():
                 "avg_launch_ms": ms / sum(len(p.bound_events) for p in sel)}
     for p in lin:
         ms = sum(_ms(p.bound_events)) / len(p.bound_events)
-        kernels["linear_" + p.name] = {"shape": list(p.op.args["A"].shape) + [p.op.y_ref.shape[-1]],
-                                       "path": ("bf16_split+check" if p.fused else "bf16_split") if p.split else "fp32",
+        kernels["linear_" + p.name] = {"shape": list(p.op.args["A"].shape) + [p.op.y_ref.shape[-1]], "path": p.path,
                                        "TFLOP/s": p.flops / (ms * 1e-3) / 1e12, "ms": ms}
 
+    configs = {}
     if not args.no_stress:
         # side measurements on the stress shapes (not part of `value`)
         g, A, W = tao_inputs.config5_operands(dev, size=8192)
@@ -355,8 +520,13 @@ def main():
         ms = _event_time(torch, lambda: tao.tao_bound_linear_split(A, W, out=out, ws=ws5), 5, 1)
         tf = 2.0 * 8192 ** 3 / (ms * 1e-3) / 1e12
         kernels["linear_8192^3_bf16_split"] = {"ms": ms, "TFLOP/s": tf, "frac_mfma": tf / PEAK_FP32_MFMA_TFLOPS,
-                                               "issued_frac_of_bf16_peak": 8.0 * tf / 2500.0}
-        del ws5
+                                               "issued_frac_of_bf16_peak": 8.0 * tf / PEAK_BF16_MFMA_TFLOPS}
+        a_img, w_img = tao.tao_split_operand(A), tao.tao_split_operand(W)
+        ms = _event_time(torch, lambda: tao.tao_bound_linear_images(a_img, w_img, 8192, 8192, 8192, out=out), 5, 1)
+        tf = 2.0 * 8192 ** 3 / (ms * 1e-3) / 1e12
+        kernels["linear_8192^3_bf16_split_prepared_operands"] = {"ms": ms, "TFLOP/s": tf, "frac_mfma": tf / PEAK_FP32_MFMA_TFLOPS,
+                                                                 "issued_frac_of_bf16_peak": 8.0 * tf / PEAK_BF16_MFMA_TFLOPS}
+        del ws5, a_img, w_img
         tao.tao_bound_linear(A, W, out=out)      # the stored bound of the check below: the FP32 path's
         ref = A @ W.t()
         claimed, cls = tao_inputs.config5_claimed(g, ref, out)
@@ -367,6 +537,18 @@ def main():
                                 "frac_hbm": 12.0 * ref.numel() / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
                                 "violations": prof["violations"], "expected_violations": int((cls == 2).sum()),
                                 "p50": prof["p50"], "p99": prof["p99"], "p999": prof["p999"], "max_rel": prof["max_rel"]}
+        # configuration 5 as one pass: the bound of the 8192^3 product checked on the spot against the
+        # perturbed claims (the library's route: BF16-split kernel, check in its epilogue)
+        ws5 = torch.empty(tao.tao_bound_check_linear_workspace_bytes(8192, 8192, 8192, 1, True), dtype=torch.uint8, device=dev)
+        ms = _event_time(torch, lambda: tao.tao_bound_check_linear(A, W, None, ref, claimed, out=buf, ws=ws5, readback=False), 5, 1)
+        prof = tao.read_profile(buf)
+        tf = 2.0 * 8192 ** 3 / (ms * 1e-3) / 1e12
+        configs["5"] = {"workload": "config 5: 8192^3 GEMM, U(-1,1) with 1 % x100, claims at 0.5 / 0.99 / 1.01 of the bound: bound + check of 67 M elements in one call",
+                        "operators": 1, "elements": ref.numel(), "ms_per_pass": ms, "GB/s_verified": 4.0 * ref.numel() / (ms * 1e-3) / 1e9,
+                        "violations": prof["violations"], "expected_violations": int((cls == 2).sum()),
+                        "matmul": {"TFLOP/s": tf, "frac_fp32_mfma_peak": tf / PEAK_FP32_MFMA_TFLOPS,
+                                   "issued_frac_of_bf16_peak": 8.0 * tf / PEAK_BF16_MFMA_TFLOPS, "path": "bf16_split+check"}}
+        del ws5
         # the two projections of Sec. 4.4 on the 67M deviations claimed - ref; thresholds: the
         # deviations' own percentile profile (bin upper edges: part of the elements is capped) and a
         # third of it (every element is capped: the worst case of the last pass's random writes)
@@ -383,7 +565,18 @@ def main():
         ms = _event_time(torch, lambda: tao.tao_project_clip(delta, out, 1.0, out=pout), 20, 2)
         kernels["project_clip_67M"] = {"ms": ms, "GB/s": 12.0 * delta.numel() / (ms * 1e-3) / 1e9,
                                        "frac_hbm": 12.0 * delta.numel() / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
-        del A, W, out, ref, claimed, cls, delta, pws, pout
+        ews = torch.empty(tao.tao_profile_workspace_bytes(delta.numel()), dtype=torch.uint8, device=dev)
+        ebuf = torch.empty(ctypes_sizeof_error_profile(tao), dtype=torch.uint8, device=dev)
+        ms = _event_time(torch, lambda: tao.tao_profile_errors(claimed, ref, out=ebuf, ws=ews, readback=False), 10, 2)
+        kernels["profile_errors_67M"] = {"ms": ms, "GB/s": 8.0 * delta.numel() / (ms * 1e-3) / 1e9,
+                                         "frac_hbm": 8.0 * delta.numel() / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS}
+        del A, W, out, ref, claimed, cls, delta, pws, pout, ews, ebuf
+        torch.cuda.empty_cache()
+
+    if not args.no_configs and args.scale == 1:
+        for c in (1, 2, 4):
+            configs[str(c)] = measure_config(c)
+        kernels.update(stream_bound_kernels(torch, tao, tao_inputs, dev))
 
     if args.copy_calib:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -393,6 +586,8 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    configs["3"] = plan_summary(tao, plan, ms_per_step, "config 3 (the workload of `value`)")
+    configs["3"].pop("matmul", None); configs["3"].pop("streaming", None)      # detailed in `roofline` and `kernels`
     result = {
         "metric": "traced-operator GB/s verified (bound+check) & % FP32 MFMA/HBM peak, 1 GPU",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -405,10 +600,16 @@ def main():
         "violations": violations,
         "roofline": roofline,
         "kernels": kernels,
+        "configs": configs,
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(ops, args.cpu_rows)
     print(json.dumps(result))
+
+
+def ctypes_sizeof_error_profile(tao):
+    import ctypes
+    return ctypes.sizeof(tao.ErrorProfile)
 
 
 if __name__ == "__main__":

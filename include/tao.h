@@ -179,6 +179,37 @@ int tao_bound_check_linear(const float *A, const float *W, const float *bias, co
                            double alpha, double eps_rel, const tao_fp_model *model, tao_profile *out,
                            void *ws, size_t ws_bytes, void *stream);
 size_t tao_bound_check_linear_workspace_bytes(long M, long N, long K, long batch, int shared_w);
+/* Prepared operands.  The pre-pass of the BF16 path turns an operand into its three-piece image; an
+ * operand that takes part in many products -- the committed weights of a layer, which never change
+ * (Sec. 5.2), or an activation that feeds several projections -- can be split once and reused:
+ *   tao_split_operand          writes the image of src: [batch][rows][K] with row stride ld and batch
+ *                              stride `stride` (trans == 0), or [batch][K][rows] (trans != 0: a weight
+ *                              stored K x N); rows = M for the A side, N for the W side.  image: DEVICE,
+ *                              256-byte aligned, at least tao_split_image_bytes(rows, K, batch) bytes
+ *                              (about 6 bytes per element, rows and K padded to 128 and 32).  An image
+ *                              depends on (rows, K, batch) only and may be used on either side.
+ *   tao_bound_linear_images    tao_bound_linear_split on two images: the same tau, bit for bit.
+ *                              shared_w != 0: one W image for every batch entry.  ws: DEVICE scratch of
+ *                              tao_linear_images_workspace_bytes(M, N, K, batch) bytes (0 unless the
+ *                              launch has fewer tiles than compute units and cuts the reduction into
+ *                              parts; ws may then be NULL), 256-byte aligned.
+ *   tao_bound_check_linear_images  tao_bound_check_linear on two images (same result, field for field);
+ *                              ws of tao_check_linear_images_workspace_bytes(M, N, K, batch) bytes.
+ * Images are read only by the products; products that share an image may run concurrently.  Errors
+ * as for the calls they mirror; TAO_ERR_ALIGN for an image that is not 256-byte aligned. */
+size_t tao_split_image_bytes(long rows, long K, long batch);
+int tao_split_operand(const float *src, long rows, long K, long ld, int trans, long batch, long stride,
+                      void *image, size_t image_bytes, void *stream);
+int tao_bound_linear_images(const void *A_image, const void *W_image, const float *bias, float *tau,
+                            long M, long N, long K, long ldt, long batch, long strideT, int shared_w,
+                            const tao_fp_model *model, void *ws, size_t ws_bytes, void *stream);
+size_t tao_linear_images_workspace_bytes(long M, long N, long K, long batch);
+int tao_bound_check_linear_images(const void *A_image, const void *W_image, const float *bias, const float *y_ref,
+                                  const float *claimed, float *tau, long M, long N, long K, long ldy, long batch,
+                                  long strideY, int shared_w, double alpha, double eps_rel, const tao_fp_model *model,
+                                  tao_profile *out, void *ws, size_t ws_bytes, void *stream);
+size_t tao_check_linear_images_workspace_bytes(long M, long N, long K, long batch);
+
 /* 1 if tao_bound_check_linear checks a product of this shape (contiguous outputs) in the matrix
  * kernel's epilogue, 0 if it stores the bound and runs the streaming check.  Host only: for callers
  * that time or schedule the two kernels separately. */

@@ -92,7 +92,9 @@ class TaoError(RuntimeError):
 
 
 EXPORTS = ["tao_default_model", "tao_gamma", "tao_bound_linear", "tao_bound_linear_split",
-           "tao_linear_split_workspace_bytes", "tao_linear_split_preferred", "tao_bound_check_linear_in_epilogue",
+           "tao_linear_split_workspace_bytes", "tao_linear_split_preferred",
+           "tao_split_image_bytes", "tao_split_operand", "tao_bound_linear_images", "tao_linear_images_workspace_bytes",
+           "tao_bound_check_linear_images", "tao_check_linear_images_workspace_bytes", "tao_bound_check_linear_in_epilogue",
            "tao_bound_check_linear", "tao_bound_check_linear_workspace_bytes", "tao_selftest_matrix_core_bf16", "tao_bound_conv2d", "tao_bound_softmax",
            "tao_bound_norm", "tao_bound_groupnorm", "tao_groupnorm_workspace_bytes", "tao_bound_act", "tao_bound_check_act", "tao_bound_rope", "tao_bound_check_rope", "tao_bound_check_norm", "tao_check_and_profile",
            "tao_check_and_profile_static",
@@ -132,6 +134,16 @@ def lib():
     L.tao_linear_split_workspace_bytes.argtypes = [lg, lg, lg, lg, ctypes.c_int]
     L.tao_linear_split_workspace_bytes.restype = ctypes.c_size_t
     L.tao_linear_split_preferred.argtypes = [lg, lg, lg, lg]
+    L.tao_split_image_bytes.argtypes = [lg, lg, lg]
+    L.tao_split_image_bytes.restype = ctypes.c_size_t
+    L.tao_split_operand.argtypes = [vp, lg, lg, lg, ctypes.c_int, lg, lg, vp, ctypes.c_size_t, vp]
+    L.tao_bound_linear_images.argtypes = [vp, vp, vp, vp, lg, lg, lg, lg, lg, lg, ctypes.c_int, mp, vp, ctypes.c_size_t, vp]
+    L.tao_linear_images_workspace_bytes.argtypes = [lg, lg, lg, lg]
+    L.tao_linear_images_workspace_bytes.restype = ctypes.c_size_t
+    L.tao_bound_check_linear_images.argtypes = [vp, vp, vp, vp, vp, vp, lg, lg, lg, lg, lg, lg, ctypes.c_int, dbl, dbl, mp, vp,
+                                                vp, ctypes.c_size_t, vp]
+    L.tao_check_linear_images_workspace_bytes.argtypes = [lg, lg, lg, lg]
+    L.tao_check_linear_images_workspace_bytes.restype = ctypes.c_size_t
     L.tao_bound_check_linear_in_epilogue.argtypes = [lg, lg, lg, lg]
     L.tao_selftest_matrix_core_bf16.argtypes = [ctypes.POINTER(ctypes.c_uint), vp]
     L.tao_bound_conv2d.argtypes = [vp, vp, vp, vp] + [lg] * 13 + [mp, vp]
@@ -331,6 +343,64 @@ def tao_bound_check_linear(A, W, bias, y_ref, claimed, trans_w=False, alpha=1.0,
                                       *dims, float(alpha), float(eps_rel), _mref(model), _ptr(out),
                                       _ptr(ws), ws.numel(), _stream())
     _check(rc, "tao_bound_check_linear")
+    return read_profile(out) if readback else out
+
+
+def tao_split_image_bytes(rows, K, batch=1):
+    return int(lib().tao_split_image_bytes(int(rows), int(K), int(batch)))
+
+
+def tao_split_operand(X, trans=False, out=None):
+    """The three-piece BF16 image of an operand X [rows, K] or [batch, rows, K] (trans: [.., K, rows]),
+    as a uint8 tensor; reusable by every product X takes part in."""
+    torch = _torch()
+    X = _dev(X, "X")
+    if X.dim() not in (2, 3) or (X.shape[-1] > 1 and X.stride(-1) != 1):
+        raise ValueError("X must be 2-D or 3-D with a contiguous last dimension")
+    batch = X.shape[0] if X.dim() == 3 else 1
+    rows, K = (X.shape[-1], X.shape[-2]) if trans else (X.shape[-2], X.shape[-1])
+    ld = X.stride(-2) if X.shape[-2] > 1 else max(X.shape[-1], 1)
+    stride = X.stride(0) if X.dim() == 3 and batch > 1 else X.shape[-2] * ld
+    need = tao_split_image_bytes(rows, K, batch)
+    if out is None:
+        out = torch.empty(max(need, 256), dtype=torch.uint8, device=X.device)
+    rc = lib().tao_split_operand(_ptr(X), rows, K, ld, int(bool(trans)), batch, stride, _ptr(out), out.numel(), _stream())
+    _check(rc, "tao_split_operand")
+    return out
+
+
+def tao_bound_linear_images(A_image, W_image, M, N, K, bias=None, batch=1, shared_w=True, model=None, out=None, ws=None):
+    """tao_bound_linear_split on prepared images (tao_split_operand); returns tau [M, N] or [batch, M, N]."""
+    torch = _torch()
+    bias = _dev(bias, "bias")
+    shape = (batch, M, N) if batch > 1 else (M, N)
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float32, device=A_image.device)
+    elif out.numel() != batch * M * N or not out.is_contiguous():
+        raise ValueError("out must be contiguous with %d elements" % (batch * M * N))
+    if ws is None:
+        ws = _scratch(A_image.device, lib().tao_linear_images_workspace_bytes(M, N, K, batch))
+    rc = lib().tao_bound_linear_images(_ptr(A_image), _ptr(W_image), _ptr(bias), _ptr(out), M, N, K, N, batch, M * N,
+                                       int(bool(shared_w)), _mref(model), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "tao_bound_linear_images")
+    return out
+
+
+def tao_bound_check_linear_images(A_image, W_image, M, N, K, y_ref, claimed, bias=None, batch=1, shared_w=True,
+                                  alpha=1.0, eps_rel=1e-12, model=None, tau_out=None, out=None, ws=None, readback=True):
+    """tao_bound_check_linear on prepared images."""
+    y_ref = _dev(y_ref, "y_ref"); claimed = _dev(claimed, "claimed"); bias = _dev(bias, "bias")
+    for t, nm in ((y_ref, "y_ref"), (claimed, "claimed"), (tau_out, "tau_out")):
+        if t is not None and (t.numel() != batch * M * N or not t.is_contiguous()):
+            raise ValueError("%s must be contiguous with %d elements" % (nm, batch * M * N))
+    if out is None:
+        out = new_profile_buffer(y_ref.device)
+    if ws is None:
+        ws = _scratch(y_ref.device, lib().tao_check_linear_images_workspace_bytes(M, N, K, batch))
+    rc = lib().tao_bound_check_linear_images(_ptr(A_image), _ptr(W_image), _ptr(bias), _ptr(y_ref), _ptr(claimed), _ptr(tau_out),
+                                             M, N, K, N, batch, M * N, int(bool(shared_w)), float(alpha), float(eps_rel),
+                                             _mref(model), _ptr(out), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "tao_bound_check_linear_images")
     return read_profile(out) if readback else out
 
 

@@ -656,19 +656,48 @@ static int split_k_parts(long M, long N, long K, long batch) {
 }
 }  // namespace tao
 
+namespace tao {
+// ---- workspace layout -------------------------------------------------------------------------
+// An operand image: per 32 k-steps and 128-row block the LDS image of the three pieces (kBlock bytes),
+// batch entries one after the other; 512 bytes of slack at the end.
+static size_t image_bytes(long rows, long K, long batch) {
+    if (rows <= 0 || K <= 0 || batch <= 0) return 0;
+    const long Kp = (K + SBK - 1) / SBK * SBK;
+    const __int128 blocks = (__int128)(Kp / SBK) * ((rows + STILE - 1) / STILE) * batch;
+    if (blocks * kBlock + 512 >= ((__int128)1 << 62)) return 0;
+    return round_up_256((size_t)(blocks * kBlock) + 512);
+}
+// What the product itself needs beyond the images: the binary64 partial sums of a reduction cut into
+// parts and, with a check, the check's partial results and (short reductions) the stored bound.
+static size_t core_workspace_bytes(long M, long N, long K, long batch, bool check) {
+    if (M <= 0 || N <= 0 || batch <= 0) return check ? round_up_256(check_workspace_bytes()) : 0;
+    const int parts = split_k_parts(M, N, K, batch);
+    size_t b = parts >= 2 ? round_up_256((size_t)parts * (size_t)batch * (size_t)M * (size_t)N * sizeof(double)) : 0;
+    if (check) {
+        b += round_up_256(check_workspace_bytes());
+        if (K < kEpilogueCheckMinK) b += round_up_256((size_t)M * N * batch * 4);
+    }
+    return b;
+}
+}  // namespace tao
+
 extern "C" {
+
+size_t tao_split_image_bytes(long rows, long K, long batch) { return tao::image_bytes(rows, K, batch); }
 
 size_t tao_linear_split_workspace_bytes(long M, long N, long K, long batch, int shared_w) {
     if (M <= 0 || N <= 0 || K < 0 || batch <= 0) return 0;
-    const long Kp = (K + tao::SBK - 1) / tao::SBK * tao::SBK;
-    const __int128 blocks = (__int128)(Kp / tao::SBK) *
-                            ((__int128)((M + tao::STILE - 1) / tao::STILE) * batch + (__int128)((N + tao::STILE - 1) / tao::STILE) * (shared_w ? 1 : batch));
-    if (blocks * tao::kBlock + 512 >= ((__int128)1 << 62)) return 0;
-    const size_t operands = (size_t)(blocks * tao::kBlock) + 512;
-    // binary64 partial sums of a reduction cut into parts (launches that would not fill the chip)
-    const int parts = tao::split_k_parts(M, N, K, batch);
-    if (parts < 2) return operands;
-    return tao::round_up_256(operands) + (size_t)parts * (size_t)batch * (size_t)M * (size_t)N * sizeof(double);
+    if (K == 0) return 0;
+    const size_t a = tao::image_bytes(M, K, batch), w = tao::image_bytes(N, K, shared_w ? 1 : batch);
+    if (a == 0 || w == 0) return 0;
+    return a + w + tao::core_workspace_bytes(M, N, K, batch, false);
+}
+
+size_t tao_linear_images_workspace_bytes(long M, long N, long K, long batch) {
+    return tao::core_workspace_bytes(M, N, K, batch, false);
+}
+size_t tao_check_linear_images_workspace_bytes(long M, long N, long K, long batch) {
+    return tao::core_workspace_bytes(M, N, K, batch, true);
 }
 
 int tao_linear_split_preferred(long M, long N, long K, long batch) {
@@ -690,36 +719,44 @@ struct SplitCheckHost {
     const float* claimed; const float* ref; long ldy, strideY; double alpha, eps_rel; tao_profile* out;
 };
 
-static int split_run(const float* A, const float* W, const float* bias, float* tau,
-                     long M, long N, long K, long lda, long ldw, long ldt, int trans_w,
-                     long batch, long strideA, long strideW, long strideT,
-                     const tao_fp_model* model, void* ws, size_t ws_bytes, void* stream, const SplitCheckHost* chk) {
-    tao_fp_model md;
-    int rc = resolve_model(model, &md);
-    if (rc != TAO_OK) return rc;
-    if (M < 0 || N < 0 || K < 0 || batch < 0) return TAO_ERR_SHAPE;
-    if (lda < K || ldw < (trans_w ? N : K)) return TAO_ERR_SHAPE;
-    if (strideA < 0 || strideW < 0) return TAO_ERR_SHAPE;
-    if (tau || !chk) {
-        if (ldt < N || strideT < 0) return TAO_ERR_SHAPE;
-        if (batch > 1 && strideT < M * ldt - (ldt - N)) return TAO_ERR_SHAPE;   // outputs would overlap
+// Launches split3_bf16 for one operand: src [batch][rows][K] with row stride ld (trans == 0) or
+// [batch][K][rows] (trans != 0) -> image.  zero_ptr / zero_n: the side job described at the kernel.
+static void launch_split3(const float* src, long rows, long K, long ld, int trans, long batch, long stride,
+                          unsigned short* image, unsigned int* zero_ptr, long zero_n, hipStream_t st) {
+    const long Kp = (K + SBK - 1) / SBK * SBK;
+    // work items of split3_bf16: (row, chunk) pairs, or whole 64-row x 256-k patches of 2048
+    long b = trans ? (rows * (Kp >> 3) + 255) / 256 : ((rows + 63) / 64) * ((Kp + 255) / 256) * 8;
+    const unsigned blocks = (unsigned)(b < 1 ? 1 : (b > 256L * 64 ? 256L * 64 : b));
+    if (trans) {
+        hipLaunchKernelGGL((split3_bf16<true>), dim3(blocks, (unsigned)batch), dim3(256), 0, st,
+                           src, rows, K, ld, stride, image, Kp, 0, zero_ptr, zero_n);
+    } else {
+        const int vec = aligned(src, 16) && (ld % 4 == 0) && (stride % 4 == 0);
+        hipLaunchKernelGGL((split3_bf16<false>), dim3(blocks, (unsigned)batch), dim3(256), 0, st,
+                           src, rows, K, ld, stride, image, Kp, vec, zero_ptr, zero_n);
     }
+}
+
+// The product on prepared images.  ws: what core_workspace_bytes(M, N, K, batch, chk != NULL) asks for.
+// cleared: the check's partial results in ws are zero already (the caller's pre-pass cleared them).
+// tau / ldt / strideT: the caller's layout (validated by the caller); with a check they describe y_ref and
+// claimed as well when tau is stored.
+static int split_core(const unsigned short* A3, const unsigned short* W3, const float* bias, float* tau,
+                      long M, long N, long K, long ldt, long batch, long strideT, bool shared_w,
+                      const tao_fp_model& md, void* ws, void* stream, const SplitCheckHost* chk, bool cleared) {
     const long Kp_ = K + (bias ? 1 : 0);
     const double c = gamma_up(Kp_, md);
     if (!(c == c)) return TAO_ERR_K_RANGE;
     hipStream_t st = (hipStream_t)stream;
-    const size_t need_split = K > 0 ? round_up_256(tao_linear_split_workspace_bytes(M, N, K, batch,
-                                                   ((strideW == 0) || batch == 1) ? 1 : 0)) : 0;
+    const int parts = split_k_parts(M, N, K, batch);
+    char* wsb = static_cast<char*>(ws);
+    const size_t partial_bytes = parts >= 2 ? round_up_256((size_t)parts * (size_t)batch * (size_t)M * (size_t)N * sizeof(double)) : 0;
     CheckWorkspace cw = {};
     bool two_pass = false;
+    void* check_ws = nullptr;
     if (chk) {
-        if (!chk->out) return TAO_ERR_NULL;
-        if (!aligned(chk->out, 8)) return TAO_ERR_ALIGN;
-        if (chk->ldy < N || chk->strideY < 0 || !(chk->alpha >= 0.0) || !std::isfinite(chk->alpha) ||
-            !(chk->eps_rel >= 0.0) || !std::isfinite(chk->eps_rel)) return TAO_ERR_SHAPE;
-        if ((__int128)M * N * batch >= ((__int128)1 << 36)) return TAO_ERR_SHAPE;   // 32-bit partial counters
-        if (!ws || !aligned(ws, 256) || ws_bytes < need_split + check_workspace_bytes()) return TAO_ERR_WORKSPACE;
-        cw = carve_check_workspace(static_cast<char*>(ws) + need_split);
+        check_ws = wsb + partial_bytes;
+        cw = carve_check_workspace(check_ws);
         // Short reductions: in the epilogue the check is arithmetic that nothing overlaps (about 70
         // instructions per element on a compute unit whose matrix cores idle meanwhile), while the
         // streaming check spends the same arithmetic under its loads and the plain bound walks its
@@ -729,64 +766,16 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
         // saves the traffic of the stored bound.
         two_pass = K < kEpilogueCheckMinK && !(md.flags & TAO_FLAG_CHECK_IN_EPILOGUE) &&
                    chk->ldy == N && (batch == 1 || chk->strideY == M * N);
-        if (two_pass && !tau && M > 0 && N > 0 && batch > 0) {
-            const size_t off = need_split + round_up_256(check_workspace_bytes());
-            const size_t stored = round_up_256((size_t)M * N * batch * 4);      // (M N batch < 2^36, checked above)
-            if (stored > ws_bytes || ws_bytes - stored < off) return TAO_ERR_WORKSPACE;
-            tau = reinterpret_cast<float*>(static_cast<char*>(ws) + off);
+        if (two_pass && !tau) {
+            tau = reinterpret_cast<float*>(wsb + partial_bytes + round_up_256(check_workspace_bytes()));
             ldt = N; strideT = M * N;
         }
     }
-    if (M == 0 || N == 0 || batch == 0) {
-        if (chk) {                                           // the profile of an empty tensor
-            hipLaunchKernelGGL(zero_words, dim3(8), dim3(256), 0, st, cw.hist, (long)(check_workspace_bytes() / 4));
-            launch_profile_reduce(cw, 1, 0ull, chk->out, st);
-            return launch_status();
-        }
-        return TAO_OK;
-    }
-    if ((!chk && !tau) || (K > 0 && (!A || !W))) return TAO_ERR_NULL;
-    if (chk && (!chk->claimed || !chk->ref)) return TAO_ERR_NULL;
-    if (!aligned(A, 4) || !aligned(W, 4) || !aligned(bias, 4) || !aligned(tau, 4)) return TAO_ERR_ALIGN;
-    if (chk && (!aligned(chk->claimed, 4) || !aligned(chk->ref, 4))) return TAO_ERR_ALIGN;
     const long Kp = (K + SBK - 1) / SBK * SBK;
-    const bool shared_w = (strideW == 0) || batch == 1;
-    // descriptor ranges (128 rows of a plane) and the per-thread offsets must fit 32 bits
-    if ((__int128)STILE * Kp * 2 >= ((__int128)1 << 31)) return TAO_ERR_SHAPE;
-    const size_t need = tao_linear_split_workspace_bytes(M, N, K, batch, shared_w ? 1 : 0);
-    if (K > 0 && (need == 0 || !ws || ws_bytes < need || !aligned(ws, 256))) return TAO_ERR_WORKSPACE;
     const long tiles_n = (N + STILE - 1) / STILE, tiles_m = (M + STILE - 1) / STILE;
     const long ntiles = tiles_n * tiles_m * batch;
     if (ntiles >= (1L << 31)) return TAO_ERR_SHAPE;
-
-    unsigned short* A3 = static_cast<unsigned short*>(ws);
     const long blocksA = (M + STILE - 1) / STILE, blocksW = (N + STILE - 1) / STILE;
-    const size_t bytesA = (size_t)(Kp / SBK) * blocksA * kBlock * batch;          // a multiple of 256
-    unsigned short* W3 = reinterpret_cast<unsigned short*>(static_cast<char*>(ws) + bytesA);
-    const size_t bytesW3 = (size_t)(Kp / SBK) * blocksW * kBlock * (shared_w ? 1 : batch);
-    bool cleared = false;                                    // the check's partial results are zero already
-    if (K > 0) {
-        auto blocks_for = [](long rows, long kp, bool trans) {
-            // work items of split3_bf16: (row, chunk) pairs, or whole 64-row x 256-k patches of 2048
-            long b = trans ? (rows * (kp >> 3) + 255) / 256 : ((rows + 63) / 64) * ((kp + 255) / 256) * 8;
-            return (unsigned)(b < 1 ? 1 : (b > 256L * 64 ? 256L * 64 : b));
-        };
-        const int vecA = aligned(A, 16) && (lda % 4 == 0) && (strideA % 4 == 0);
-        // the operand pre-pass also clears the partial results of an epilogue check (no parts: those
-        // are checked by the combining pass, which needs none)
-        cleared = chk && !two_pass && split_k_parts(M, N, K, batch) < 2;
-        hipLaunchKernelGGL((split3_bf16<false>), dim3(blocks_for(M, Kp, false), (unsigned)batch), dim3(256), 0, st,
-                           A, M, K, lda, strideA, A3, Kp, vecA, cleared ? cw.hist : nullptr, (long)(check_workspace_bytes() / 4));
-        const unsigned wb = shared_w ? 1u : (unsigned)batch;
-        if (trans_w) {
-            hipLaunchKernelGGL((split3_bf16<true>), dim3(blocks_for(N, Kp, true), wb), dim3(256), 0, st,
-                               W, N, K, ldw, strideW, W3, Kp, 0, nullptr, 0L);
-        } else {
-            const int vecW = aligned(W, 16) && (ldw % 4 == 0) && (strideW % 4 == 0);
-            hipLaunchKernelGGL((split3_bf16<false>), dim3(blocks_for(N, Kp, false), wb), dim3(256), 0, st,
-                               W, N, K, ldw, strideW, W3, Kp, vecW, nullptr, 0L);
-        }
-    }
 
     SplitArgs p;
     p.A3 = A3; p.W3 = W3; p.bias = bias; p.tau = tau;
@@ -853,15 +842,14 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
         const int lrc = launch_status();
         if (lrc != TAO_OK || !two_pass) return lrc;
         return tao_check_and_profile(chk->claimed, chk->ref, tau, M * N * batch, chk->alpha, chk->eps_rel, chk->out,
-                                     static_cast<char*>(ws) + need_split, check_workspace_bytes(), stream);
+                                     check_ws, check_workspace_bytes(), stream);
     };
-    const int parts = split_k_parts(M, N, K, batch);
     if (parts >= 2) {
         // the reduction in parts, then one pass that adds them and forms (and checks) the bound
         const long groups = Kp / SBK;
         p.ksplit = parts; p.gpp = (groups + parts - 1) / parts;
         p.ksplit = (int)((groups + p.gpp - 1) / p.gpp);             // no empty part
-        p.partial = reinterpret_cast<double*>(static_cast<char*>(ws) + round_up_256((size_t)bytesA + bytesW3 + 512));
+        p.partial = reinterpret_cast<double*>(wsb);
         hipLaunchKernelGGL((absgemm_split<false, true>), dim3(p.ntiles * (unsigned)p.ksplit), dim3(kSplitThreads), lds_bytes, st, p);
         const long total = M * N * batch;
         long want = (total + (long)kCheckThreads * 8 - 1) / ((long)kCheckThreads * 8);
@@ -894,9 +882,146 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
     launch_profile_reduce(cw, slots, (unsigned long long)((__int128)M * N * batch), chk->out, st);
     return launch_status();
 }
+
+// Does split_core, with a check, clear the check's partial results itself (false) or expect them
+// cleared (an epilogue check without parts: the caller's pre-pass can do it on the side)?
+static bool epilogue_check_without_parts(long M, long N, long K, long batch, const tao_fp_model& md, const SplitCheckHost* chk) {
+    if (!chk) return false;
+    const bool two_pass = K < kEpilogueCheckMinK && !(md.flags & TAO_FLAG_CHECK_IN_EPILOGUE) &&
+                          chk->ldy == N && (batch == 1 || chk->strideY == M * N);
+    return !two_pass && split_k_parts(M, N, K, batch) < 2;
+}
+
+// Validation shared by the entry points below (everything but the operands themselves).
+static int split_validate(const float* bias, float* tau, long M, long N, long K, long ldt, long batch, long strideT,
+                          const tao_fp_model& md, const SplitCheckHost* chk) {
+    if (M < 0 || N < 0 || K < 0 || batch < 0) return TAO_ERR_SHAPE;
+    if (tau || !chk) {
+        if (ldt < N || strideT < 0) return TAO_ERR_SHAPE;
+        if (batch > 1 && strideT < M * ldt - (ldt - N)) return TAO_ERR_SHAPE;   // outputs would overlap
+    }
+    const double c = gamma_up(K + (bias ? 1 : 0), md);
+    if (!(c == c)) return TAO_ERR_K_RANGE;
+    if (chk) {
+        if (!chk->out) return TAO_ERR_NULL;
+        if (!aligned(chk->out, 8)) return TAO_ERR_ALIGN;
+        if (chk->ldy < N || chk->strideY < 0 || !(chk->alpha >= 0.0) || !std::isfinite(chk->alpha) ||
+            !(chk->eps_rel >= 0.0) || !std::isfinite(chk->eps_rel)) return TAO_ERR_SHAPE;
+        if ((__int128)M * N * batch >= ((__int128)1 << 36)) return TAO_ERR_SHAPE;   // 32-bit partial counters
+    }
+    // descriptor ranges (128 rows of a plane) and the per-thread offsets must fit 32 bits
+    const long Kp = (K + SBK - 1) / SBK * SBK;
+    if ((__int128)STILE * Kp * 2 >= ((__int128)1 << 31)) return TAO_ERR_SHAPE;
+    return TAO_OK;
+}
+
+// An empty product: nothing to bound; with a check, the profile of an empty tensor.
+static int split_empty(const SplitCheckHost* chk, void* check_ws, void* stream) {
+    if (!chk) return TAO_OK;
+    hipStream_t st = (hipStream_t)stream;
+    const CheckWorkspace cw = carve_check_workspace(check_ws);
+    hipLaunchKernelGGL(zero_words, dim3(8), dim3(256), 0, st, cw.hist, (long)(check_workspace_bytes() / 4));
+    launch_profile_reduce(cw, 1, 0ull, chk->out, st);
+    return launch_status();
+}
+
+static int split_run(const float* A, const float* W, const float* bias, float* tau,
+                     long M, long N, long K, long lda, long ldw, long ldt, int trans_w,
+                     long batch, long strideA, long strideW, long strideT,
+                     const tao_fp_model* model, void* ws, size_t ws_bytes, void* stream, const SplitCheckHost* chk) {
+    tao_fp_model md;
+    int rc = resolve_model(model, &md);
+    if (rc != TAO_OK) return rc;
+    if (M < 0 || N < 0 || K < 0 || batch < 0) return TAO_ERR_SHAPE;
+    if (lda < K || ldw < (trans_w ? N : K)) return TAO_ERR_SHAPE;
+    if (strideA < 0 || strideW < 0) return TAO_ERR_SHAPE;
+    rc = split_validate(bias, tau, M, N, K, ldt, batch, strideT, md, chk);
+    if (rc != TAO_OK) return rc;
+    const bool shared_w = (strideW == 0) || batch == 1;
+    const bool empty = M == 0 || N == 0 || batch == 0;
+    const size_t bytesA = (K > 0 && !empty) ? image_bytes(M, K, batch) : 0;
+    const size_t bytesW = (K > 0 && !empty) ? image_bytes(N, K, shared_w ? 1 : batch) : 0;
+    if (K > 0 && !empty && (bytesA == 0 || bytesW == 0)) return TAO_ERR_WORKSPACE;
+    const size_t need = bytesA + bytesW + core_workspace_bytes(M, N, K, batch, chk != nullptr);
+    if (need > 0 && (!ws || !aligned(ws, 256) || ws_bytes < need)) return TAO_ERR_WORKSPACE;
+    if (empty) return split_empty(chk, ws, stream);
+    if ((!chk && !tau) || (K > 0 && (!A || !W))) return TAO_ERR_NULL;
+    if (chk && (!chk->claimed || !chk->ref)) return TAO_ERR_NULL;
+    if (!aligned(A, 4) || !aligned(W, 4) || !aligned(bias, 4) || !aligned(tau, 4)) return TAO_ERR_ALIGN;
+    if (chk && (!aligned(chk->claimed, 4) || !aligned(chk->ref, 4))) return TAO_ERR_ALIGN;
+
+    char* wsb = static_cast<char*>(ws);
+    unsigned short* A3 = reinterpret_cast<unsigned short*>(wsb);
+    unsigned short* W3 = reinterpret_cast<unsigned short*>(wsb + bytesA);
+    void* rest = wsb + bytesA + bytesW;
+    hipStream_t st = (hipStream_t)stream;
+    bool cleared = false;
+    if (K > 0) {
+        // the operand pre-pass also clears the partial results of an epilogue check (no parts: those
+        // are checked by the combining pass, which needs none)
+        cleared = epilogue_check_without_parts(M, N, K, batch, md, chk);
+        unsigned int* zp = nullptr;
+        if (cleared) zp = carve_check_workspace(rest).hist;       // (no parts: the check's workspace comes first)
+        launch_split3(A, M, K, lda, 0, batch, strideA, A3, zp, (long)(check_workspace_bytes() / 4), st);
+        launch_split3(W, N, K, ldw, trans_w, shared_w ? 1 : batch, strideW, W3, nullptr, 0L, st);
+    }
+    return split_core(A3, W3, bias, tau, M, N, K, ldt, batch, strideT, shared_w, md, rest, stream, chk, cleared);
+}
+
+// The same on images the caller has prepared with tao_split_operand.
+static int images_run(const void* A_image, const void* W_image, const float* bias, float* tau,
+                      long M, long N, long K, long ldt, long batch, long strideT, int shared_w,
+                      const tao_fp_model* model, void* ws, size_t ws_bytes, void* stream, const SplitCheckHost* chk) {
+    tao_fp_model md;
+    int rc = resolve_model(model, &md);
+    if (rc != TAO_OK) return rc;
+    rc = split_validate(bias, tau, M, N, K, ldt, batch, strideT, md, chk);
+    if (rc != TAO_OK) return rc;
+    const bool sw = shared_w != 0 || batch == 1;
+    const size_t need = core_workspace_bytes(M, N, K, batch, chk != nullptr);
+    if (need > 0 && (!ws || !aligned(ws, 256) || ws_bytes < need)) return TAO_ERR_WORKSPACE;
+    if (M == 0 || N == 0 || batch == 0) return split_empty(chk, ws, stream);
+    if ((!chk && !tau) || (K > 0 && (!A_image || !W_image))) return TAO_ERR_NULL;
+    if (chk && (!chk->claimed || !chk->ref)) return TAO_ERR_NULL;
+    if (!aligned(A_image, 256) || !aligned(W_image, 256) || !aligned(bias, 4) || !aligned(tau, 4)) return TAO_ERR_ALIGN;
+    if (chk && (!aligned(chk->claimed, 4) || !aligned(chk->ref, 4))) return TAO_ERR_ALIGN;
+    return split_core(static_cast<const unsigned short*>(A_image), static_cast<const unsigned short*>(W_image), bias, tau,
+                      M, N, K, ldt, batch, strideT, sw, md, ws, stream, chk, false);
+}
 }  // namespace tao
 
 extern "C" {
+
+int tao_split_operand(const float* src, long rows, long K, long ld, int trans, long batch, long stride,
+                      void* image, size_t image_bytes, void* stream) {
+    using namespace tao;
+    if (rows < 0 || K < 0 || batch < 0 || stride < 0) return TAO_ERR_SHAPE;
+    if (ld < (trans ? rows : K)) return TAO_ERR_SHAPE;
+    if (rows == 0 || K == 0 || batch == 0) return TAO_OK;
+    const long Kp = (K + SBK - 1) / SBK * SBK;
+    if ((__int128)STILE * Kp * 2 >= ((__int128)1 << 31)) return TAO_ERR_SHAPE;
+    if (!src) return TAO_ERR_NULL;
+    if (!aligned(src, 4)) return TAO_ERR_ALIGN;
+    const size_t need = tao::image_bytes(rows, K, batch);
+    if (need == 0 || !image || !aligned(image, 256) || image_bytes < need) return TAO_ERR_WORKSPACE;
+    if (batch >= 65536) return TAO_ERR_SHAPE;                      // (second grid dimension)
+    launch_split3(src, rows, K, ld, trans, batch, stride, static_cast<unsigned short*>(image), nullptr, 0L, (hipStream_t)stream);
+    return launch_status();
+}
+
+int tao_bound_linear_images(const void* A_image, const void* W_image, const float* bias, float* tau,
+                            long M, long N, long K, long ldt, long batch, long strideT, int shared_w,
+                            const tao_fp_model* model, void* ws, size_t ws_bytes, void* stream) {
+    return tao::images_run(A_image, W_image, bias, tau, M, N, K, ldt, batch, strideT, shared_w, model, ws, ws_bytes, stream, nullptr);
+}
+
+int tao_bound_check_linear_images(const void* A_image, const void* W_image, const float* bias, const float* y_ref,
+                                  const float* claimed, float* tau, long M, long N, long K, long ldy, long batch,
+                                  long strideY, int shared_w, double alpha, double eps_rel, const tao_fp_model* model,
+                                  tao_profile* out, void* ws, size_t ws_bytes, void* stream) {
+    tao::SplitCheckHost chk = {claimed, y_ref, ldy, strideY, alpha, eps_rel, out};
+    return tao::images_run(A_image, W_image, bias, tau, M, N, K, ldy, batch, strideY, shared_w, model, ws, ws_bytes, stream, &chk);
+}
 
 int tao_bound_linear_split(const float* A, const float* W, const float* bias, float* tau,
                            long M, long N, long K, long lda, long ldw, long ldt, int trans_w,
@@ -907,11 +1032,12 @@ int tao_bound_linear_split(const float* A, const float* W, const float* bias, fl
 }
 
 size_t tao_bound_check_linear_workspace_bytes(long M, long N, long K, long batch, int shared_w) {
-    const size_t split = K > 0 ? tao_linear_split_workspace_bytes(M, N, K, batch, shared_w) : 0;
-    if (K > 0 && split == 0) return 0;
-    // (reductions shorter than kEpilogueCheckMinK: room for the stored bound behind the check's workspace)
-    const size_t stored = (K < tao::kEpilogueCheckMinK && M > 0 && N > 0 && batch > 0) ? tao::round_up_256((size_t)M * N * batch * 4) : 0;
-    return tao::round_up_256(split) + tao::round_up_256(tao::check_workspace_bytes()) + stored;
+    if (M < 0 || N < 0 || K < 0 || batch < 0) return 0;
+    const bool empty = M == 0 || N == 0 || batch == 0;
+    const size_t a = (K > 0 && !empty) ? tao::image_bytes(M, K, batch) : 0;
+    const size_t w = (K > 0 && !empty) ? tao::image_bytes(N, K, shared_w ? 1 : batch) : 0;
+    if (K > 0 && !empty && (a == 0 || w == 0)) return 0;
+    return a + w + tao::core_workspace_bytes(M, N, K, batch, true);
 }
 
 int tao_bound_check_linear_in_epilogue(long M, long N, long K, long batch) {

@@ -33,7 +33,7 @@ class Op:
     args: Dict[str, Optional[torch.Tensor]]
     y_ref: torch.Tensor
     claimed: torch.Tensor
-    attrs: Dict[str, object] = field(default_factory=dict)
+    attrs: Dict[str, object] = field(default_factory=dict)   # "weight": W is a committed model weight (constant across inputs)
 
 
 def _gen(seed, device):
@@ -189,7 +189,7 @@ def config2(device="cpu", seed=SEED0 + 2, scale=1):
         W = randn(g, (n_out, a.shape[-1]), 0.02)
         b = randn(g, (n_out,), 0.02)
         y = a @ W.t() + b
-        ops.append(Op(name, "linear", {"A": a, "W": W, "bias": b}, y, matmul_permuted_k(g, a, W) + b))
+        ops.append(Op(name, "linear", {"A": a, "W": W, "bias": b}, y, matmul_permuted_k(g, a, W) + b, {"weight": True}))
         return y
 
     def layernorm(name, a):
@@ -243,7 +243,7 @@ def config3(device="cpu", seed=SEED0 + 3, scale=1):
     def linear(name, a, n_out, si):
         W = randn(g, (n_out, a.shape[-1]), 0.02)
         y = a @ W.t()
-        ops.append(Op(name, "linear", {"A": a, "W": W, "bias": None}, y, matmul_split_k(a, W, slabs[si % 3])))
+        ops.append(Op(name, "linear", {"A": a, "W": W, "bias": None}, y, matmul_split_k(a, W, slabs[si % 3]), {"weight": True}))
         return y
 
     def rmsnorm(name, a):
@@ -310,7 +310,7 @@ def config4(device="cpu", seed=SEED0 + 4, scale=1):
     A = cols.transpose(1, 2).reshape(B * HW * HW, C * 9).contiguous()
     W = randn(g, (CO, C * 9), math.sqrt(2.0 / (C * 9)))
     y = A @ W.t()
-    ops = [Op("conv_im2col", "linear", {"A": A, "W": W, "bias": None}, y, matmul_permuted_k(g, A, W))]
+    ops = [Op("conv_im2col", "linear", {"A": A, "W": W, "bias": None}, y, matmul_permuted_k(g, A, W), {"weight": True})]
     # the same convolution in the layout of the native entry point: channels-last input and
     # filters [Cout][R][S][C] (the patch matrix above orders its columns (c, r, s) instead)
     ops[0].attrs["conv"] = {"x": x.permute(0, 2, 3, 1).contiguous(),

@@ -148,14 +148,14 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_bound_linear(nul, nul, nul, nul, *args(0, 4, 8, 8, 8, 4), None, None) == tao.OK
     # the same through the BF16 path: needs a workspace
     wsb = L.tao_linear_split_workspace_bytes(4, 4, 8, 1, 1)
-    assert wsb == 2 * 24576 + 512 and L.tao_linear_split_workspace_bytes(0, 4, 8, 1, 1) == 0
-    assert L.tao_linear_split_workspace_bytes(300, 129, 33, 2, 0) == 2 * (3 + 2) * 2 * 24576 + 512
+    assert wsb == 2 * (24576 + 512) and L.tao_linear_split_workspace_bytes(0, 4, 8, 1, 1) == 0
+    assert L.tao_linear_split_workspace_bytes(300, 129, 33, 2, 0) == 2 * (3 + 2) * 2 * 24576 + 2 * 512
     # fewer tiles than compute units (256 assumed without a device) and a long reduction: the reduction is
     # cut into parts whose binary64 partial sums follow the operands in the workspace
-    operands = (4096 // 32) * (16 + 8) * 24576 + 512
+    operands = (4096 // 32) * (16 + 8) * 24576 + 2 * 512       # two images, 512 bytes of slack each
     assert L.tao_linear_split_workspace_bytes(2048, 1024, 4096, 1, 1) == (operands + 255) // 256 * 256 + 2 * 2048 * 1024 * 8
-    assert L.tao_linear_split_workspace_bytes(2048, 4096, 4096, 1, 1) == (4096 // 32) * (16 + 32) * 24576 + 512   # 512 tiles: one part
-    assert L.tao_linear_split_workspace_bytes(2048, 1024, 256, 1, 1) == (256 // 32) * (16 + 8) * 24576 + 512     # too short to cut
+    assert L.tao_linear_split_workspace_bytes(2048, 4096, 4096, 1, 1) == (4096 // 32) * (16 + 32) * 24576 + 2 * 512   # 512 tiles: one part
+    assert L.tao_linear_split_workspace_bytes(2048, 1024, 256, 1, 1) == (256 // 32) * (16 + 8) * 24576 + 2 * 512     # too short to cut
     L.tao_linear_split_preferred.restype = ctypes.c_int
     assert L.tao_linear_split_preferred(2048, 1024, 4096, 1) == 1 and L.tao_linear_split_preferred(2048, 4096, 4096, 1) == 1
     assert L.tao_linear_split_preferred(8192, 128, 2048, 8) == 0 and L.tao_linear_split_preferred(512, 1024, 1024, 1) == 0
@@ -189,6 +189,38 @@ def test_argument_validation_without_a_gpu(tao):
     assert fc(p, p, p, p, nul, ok, 1.0, p, big, cwb - 1) == tao.ERR_WORKSPACE
     assert fc(p, p, p, p, nul, args(4, 4, K, K, K, 4), 1.0, p, big, 1 << 40) == tao.ERR_K_RANGE
     assert fc(p, p, p, p, nul, args(1 << 18, 1 << 18, 8, 8, 8, 1 << 18), 1.0, p, big, 1 << 50) == tao.ERR_SHAPE   # 2^36 outputs
+    # prepared operands: the image of an operand, and the products on two images
+    L.tao_split_image_bytes.restype = ctypes.c_size_t
+    ib = L.tao_split_image_bytes(4, 8, 1)
+    assert ib == 24576 + 512 and L.tao_split_image_bytes(300, 33, 2) == 3 * 2 * 2 * 24576 + 512 and L.tao_split_image_bytes(0, 8, 1) == 0
+    so = lambda src, rows, K_, ld, tr, img, nbytes: L.tao_split_operand(src, rows, K_, ld, tr, 1, 0, img, nbytes, None)
+    assert so(p, 4, 8, 4, 0, big, ib) == tao.ERR_SHAPE                 # ld < K
+    assert so(p, 4, 8, 2, 1, big, ib) == tao.ERR_SHAPE                 # transposed: ld < rows
+    assert so(nul, 4, 8, 8, 0, big, ib) == tao.ERR_NULL
+    assert so(odd, 4, 8, 8, 0, big, ib) == tao.ERR_ALIGN
+    assert so(p, 4, 8, 8, 0, nul, ib) == tao.ERR_WORKSPACE
+    assert so(p, 4, 8, 8, 0, big, ib - 1) == tao.ERR_WORKSPACE
+    assert so(p, 4, 8, 8, 0, ctypes.c_void_p(0x100010), ib) == tao.ERR_WORKSPACE
+    assert so(nul, 0, 8, 8, 0, nul, 0) == tao.OK
+    L.tao_linear_images_workspace_bytes.restype = ctypes.c_size_t
+    L.tao_check_linear_images_workspace_bytes.restype = ctypes.c_size_t
+    assert L.tao_linear_images_workspace_bytes(2048, 4096, 4096, 1) == 0
+    assert L.tao_linear_images_workspace_bytes(2048, 1024, 4096, 1) == 2 * 2048 * 1024 * 8
+    assert L.tao_check_linear_images_workspace_bytes(4, 4, 8, 1) == L.tao_check_workspace_bytes(16) + 256
+    fi = lambda a, w, t, M, N, K_, ldt, wsp, wsn: L.tao_bound_linear_images(a, w, nul, t, M, N, K_, ldt, 1, 0, 1, None, wsp, wsn, None)
+    assert fi(big, big, p, 4, 4, 8, 2, nul, 0) == tao.ERR_SHAPE        # ldt < N
+    assert fi(big, big, p, 4, 4, K, 4, nul, 0) == tao.ERR_K_RANGE
+    assert fi(nul, big, p, 4, 4, 8, 4, nul, 0) == tao.ERR_NULL
+    assert fi(big, big, nul, 4, 4, 8, 4, nul, 0) == tao.ERR_NULL
+    assert fi(ctypes.c_void_p(0x100010), big, p, 4, 4, 8, 4, nul, 0) == tao.ERR_ALIGN
+    assert fi(big, big, p, 2048, 1024, 4096, 1024, nul, 0) == tao.ERR_WORKSPACE      # parts: needs the partial sums
+    assert fi(nul, nul, nul, 0, 4, 8, 4, nul, 0) == tao.OK
+    ciw = L.tao_check_linear_images_workspace_bytes(4, 4, 8, 1)
+    fci = lambda a, w, y, c, o, wsp, wsn: L.tao_bound_check_linear_images(a, w, nul, y, c, nul, 4, 4, 8, 4, 1, 0, 1, 1.0, 0.0, None, o, wsp, wsn, None)
+    assert fci(big, big, p, p, nul, big, ciw) == tao.ERR_NULL
+    assert fci(big, big, nul, p, p, big, ciw) == tao.ERR_NULL
+    assert fci(big, big, p, p, p, big, ciw - 1) == tao.ERR_WORKSPACE
+    assert fci(big, big, p, p, p, nul, ciw) == tao.ERR_WORKSPACE
     # conv2d: (batch, H, W, C, Cout, R, S, stride h/w, pad h/w, dilation h/w)
     cargs = lambda B=1, H=8, W=8, C=4, Co=4, R=3, S=3, sh=1, sw=1, ph=1, pw=1, dh=1, dw=1: \
         (B, H, W, C, Co, R, S, sh, sw, ph, pw, dh, dw)

@@ -673,6 +673,74 @@ def test_matmul_bound_checked_in_the_epilogue(tao, oracle_mod, M, N, K, bias, tr
         assert again["violations"] >= 3 and again["nan_count"] >= 1
 
 
+@pytest.mark.parametrize("M,N,K,bias,trans_w,batch,shared", [
+    (1, 1, 1, False, False, 1, True), (129, 257, 49, True, False, 1, True), (130, 64, 601, False, True, 1, True),
+    (33, 200, 48, True, True, 3, False), (96, 160, 320, False, False, 3, True), (5, 3, 0, True, False, 1, True),
+    (2048, 1024, 4096, False, False, 1, True),      # reduction cut into parts: partial sums in the workspace
+    (2100, 1500, 100, True, False, 6, False),       # tile walk
+    (512, 384, 2048, True, False, 1, True), (300, 260, 1000, False, True, 2, False), (0, 16, 8, False, False, 1, True)])
+def test_products_on_prepared_operand_images(tao, oracle_mod, M, N, K, bias, trans_w, batch, shared):
+    """tao_split_operand + tao_bound_linear_images / tao_bound_check_linear_images: the bits of
+    tao_bound_linear_split and the profile of tao_bound_check_linear, with the images built once and
+    used twice (a second product on the same W image after other work has used the scratch memory)."""
+    g = torch.Generator().manual_seed(M * 11 + N * 5 + K + batch)
+    A = torch.randn((batch, M, K), generator=g)
+    wb = 1 if shared else batch
+    W = torch.randn((wb, K, N) if trans_w else (wb, N, K), generator=g)
+    b = torch.randn((N,), generator=g).cuda() if bias else None
+    if batch == 1:
+        A = A[0]
+    if wb == 1:
+        W = W[0]
+    Ag, Wg = A.cuda(), W.cuda()
+    Wfull = Wg if (W.dim() == A.dim()) else Wg[None].expand((batch,) + tuple(Wg.shape))     # what the unprepared entry takes
+    want = tao.tao_bound_linear_split(Ag, Wfull, b, trans_w=trans_w)
+    A_img = tao.tao_split_operand(Ag) if M * K > 0 else Ag.new_empty(256, dtype=torch.uint8)
+    W_img = tao.tao_split_operand(Wg, trans=trans_w) if N * K > 0 else Ag.new_empty(256, dtype=torch.uint8)
+    sh = shared or batch == 1
+    got = tao.tao_bound_linear_images(A_img, W_img, M, N, K, bias=b, batch=batch, shared_w=sh)
+    assert torch.equal(got.view(torch.int32).reshape(-1), want.view(torch.int32).reshape(-1)), "images vs pre-pass inside the call"
+    if M * N * batch > 0:
+        assert_bound_parity(_np(got).reshape(-1), oracle_mod.bound_linear(_np(A), _np(Wfull), None if b is None else _np(b), trans_w=trans_w).reshape(-1),
+                            "images vs oracle %s" % ((M, N, K, batch),))
+    # the checked product on the same images
+    Wnk = Wfull.transpose(-1, -2) if trans_w else Wfull
+    ref = (Ag @ Wnk.transpose(-1, -2)) if K > 0 else torch.zeros(tuple(Ag.shape[:-1]) + (N,), device="cuda")
+    if b is not None:
+        ref = ref + b
+    ref = ref.contiguous()
+    claimed = tao_inputs.ulp_noise(torch.Generator(device="cuda").manual_seed(5), ref, max_ulps=2) if ref.numel() else ref.clone()
+    if ref.numel() > 40:
+        claimed.view(-1)[3] += 1.0
+        claimed.view(-1)[9] = float("nan")
+    for model in (None, tao.FpModel(flags=tao.FLAG_CHECK_IN_EPILOGUE)):
+        one = tao.tao_bound_check_linear(Ag, Wfull, b, ref, claimed, trans_w=trans_w, alpha=2.0, model=model)
+        tau2 = torch.full_like(want, -1.0)
+        img = tao.tao_bound_check_linear_images(A_img, W_img, M, N, K, ref, claimed, bias=b, batch=batch, shared_w=sh, alpha=2.0,
+                                                model=model, tau_out=tau2)
+        assert_profile_equal(img, one, "checked product on images %s" % ((M, N, K, batch, model is None),))
+        assert torch.equal(tau2.view(torch.int32).reshape(-1), want.view(torch.int32).reshape(-1))
+    # the images are read only: a second product on them gives the same bits
+    again = tao.tao_bound_linear_images(A_img, W_img, M, N, K, bias=b, batch=batch, shared_w=sh)
+    assert torch.equal(again.view(torch.int32), got.view(torch.int32))
+
+
+def test_one_activation_image_feeds_several_projections(tao, oracle_mod):
+    """An activation split once and multiplied with three weight images (the q / k / v pattern), and a
+    weight image reused for a second activation."""
+    g = torch.Generator().manual_seed(31)
+    x = torch.randn((300, 520), generator=g).cuda()
+    x_img = tao.tao_split_operand(x)
+    ws = [torch.randn((n, 520), generator=g).cuda() * 0.02 for n in (520, 130, 129)]
+    imgs = [tao.tao_split_operand(w) for w in ws]
+    for w, wi in zip(ws, imgs):
+        got = tao.tao_bound_linear_images(x_img, wi, 300, w.shape[0], 520)
+        assert_bound_parity(_np(got), oracle_mod.bound_linear(_np(x), _np(w)), "shared activation image")
+    x2 = torch.randn((77, 520), generator=g).cuda()
+    got = tao.tao_bound_linear_images(tao.tao_split_operand(x2), imgs[0], 77, 520, 520)
+    assert_bound_parity(_np(got), oracle_mod.bound_linear(_np(x2), _np(ws[0])), "shared weight image")
+
+
 @pytest.mark.parametrize("N,C,spatial,G,affine", [
     (2, 32, (16, 16), 8, True),       # rows of 1024: cached, one wavefront per row
     (3, 12, (5, 7), 4, True),         # 105 columns: ragged, channel boundaries inside a vector
