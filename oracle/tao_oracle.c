@@ -328,11 +328,18 @@ static int rsqrt_tail(double v_lo, double v_up, double E_v, double eps, const ta
  *   (App. A.2 Eq. det-sum): sum: Gamma(n-1) sum|x|;
  *   mean: Gamma(n-1) sum|x| / n + |y| c_div u / (1 - c_div u).
  * `eps_in` is rounded to the binary32 value the operator actually adds.
- * g == NULL means g = 1; the additive term b never enters a bound. */
+ * g == NULL means g = 1.
+ * y == NULL (the caller has no re-executed output at hand): the fresh-rounding term u|y| of
+ * Sec. 3.1 is taken at an upper bound Y >= |y| of every canonical execution instead, formed from
+ * the exact intermediates and their error bounds:
+ *   LAYERNORM  Y = (|d*| r* |g| + E_p + |b|)(1+u)      (y = fl(p^ + b), |p^ - p*| <= E_p)
+ *   RMSNORM    Y = |x g| R (1+u)^2                      (y = fl(g fl(x r^)), r^ <= R)
+ *   BN_AFFINE  Y = (|x s|(1+u) + |t|)(1+u)              (y = fl(fl(x s) + t), or one fused rounding)
+ *   MEAN       Y = (sum|x| / n)(1 + Gamma(n-1))(1 + c_div u)
+ * b (the additive term) enters a bound only through this Y. */
 int taoo_bound_norm(int kind, const float *x, const float *y, const float *g, const float *b,
                     double eps_in, float *tau, long rows, long cols, long ld,
                     const taoo_model *md) {
-    (void)b;
     const long n = cols;
     double G = taoo_gamma(n - 1, md);
     if (!(G == G)) return -4;
@@ -348,18 +355,24 @@ int taoo_bound_norm(int kind, const float *x, const float *y, const float *g, co
             volatile double t = G * sa;
             if (kind == TAOO_MEAN) {
                 volatile double cu = md->c_div * u;
-                t = t / (double)n + fabs((double)y[r]) * (cu / one_minus_lo(cu));
+                volatile double Y;
+                if (y) Y = fabs((double)y[r]);
+                else Y = (sa / (double)n) * (1.0 + G) * (1.0 + cu);
+                t = t / (double)n + Y * (cu / one_minus_lo(cu));
             }
             tau[r] = (float)t;
         } else if (kind == TAOO_BN_AFFINE) {
-            const float *yr = y + r * ld; float *tr = tau + r * ld;
+            const float *yr = y ? y + r * ld : NULL; float *tr = tau + r * ld;
             for (long i = 0; i < n; ++i) {
                 double xs = fabs((double)xr[i] * (double)g[i]);           /* exact product */
-                volatile double t = u * xs * (1.0 + u) + u * fabs((double)yr[i]);
+                volatile double Y;
+                if (yr) Y = fabs((double)yr[i]);
+                else Y = (xs * (1.0 + u) + (b ? fabs((double)b[i]) : 0.0)) * (1.0 + u);
+                volatile double t = u * xs * (1.0 + u) + u * Y;
                 tr[i] = (float)t;
             }
         } else if (kind == TAOO_RMSNORM) {
-            const float *yr = y + r * ld; float *tr = tau + r * ld;
+            const float *yr = y ? y + r * ld : NULL; float *tr = tau + r * ld;
             volatile double s2_up = 0.0, ns2 = 0.0;    /* upper sum, negated lower sum of x^2 */
             for (long i = 0; i < n; ++i) {
                 double xi = (double)xr[i];
@@ -379,12 +392,15 @@ int taoo_bound_norm(int kind, const float *x, const float *y, const float *g, co
                 for (long i = 0; i < n; ++i) {
                     double gi = g ? (double)g[i] : 1.0;
                     double xg = fabs((double)xr[i] * gi);                 /* exact */
-                    volatile double t = xg * (E_r + u * R) + u * fabs((double)yr[i]);
+                    volatile double Y;
+                    if (yr) Y = fabs((double)yr[i]);
+                    else Y = xg * R * (1.0 + u) * (1.0 + u);
+                    volatile double t = xg * (E_r + u * R) + u * Y;
                     tr[i] = (float)t;
                 }
             }
         } else { /* LAYERNORM */
-            const float *yr = y + r * ld; float *tr = tau + r * ld;
+            const float *yr = y ? y + r * ld : NULL; float *tr = tau + r * ld;
             volatile double s_up = 0.0, ns = 0.0, sabs = 0.0;
             for (long i = 0; i < n; ++i) {
                 double xi = (double)xr[i];
@@ -431,7 +447,10 @@ int taoo_bound_norm(int kind, const float *x, const float *y, const float *g, co
                     volatile double H = ad_up * rs + E_h;
                     double ag = g ? fabs((double)g[i]) : 1.0;
                     volatile double E_p = ag * E_h + u * ag * H;
-                    volatile double t = E_p + u * fabs((double)yr[i]);
+                    volatile double Y;
+                    if (yr) Y = fabs((double)yr[i]);
+                    else Y = (ad_up * rs * ag + E_p + (b ? fabs((double)b[i]) : 0.0)) * (1.0 + u);
+                    volatile double t = E_p + u * Y;
                     tr[i] = (float)t;
                 }
             }

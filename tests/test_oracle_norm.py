@@ -91,6 +91,10 @@ def test_layernorm_bound_is_sound(oracle_mod, n):
             runs += 1
             for i in range(n):
                 assert abs(_mpf(y[i]) - ystar[i]) <= _mpf(tau[i]), (x, g, b, eps, y, i)
+            # without the re-executed output the fresh-rounding term is taken at an upper bound of
+            # |y| over all canonical executions: never below the bound that knows y
+            tau0 = oracle_mod.bound_norm(oracle_mod.LAYERNORM, x[None], y=None, g=g, b=b, eps=eps)[0]
+            assert np.all(tau0 >= tau)
             # not absurdly loose: a few hundred u relative to the scale of the output
             scale = np.abs(g).max() * np.sqrt(n) + np.abs(b).max()
             assert np.all(tau < 2000 * U * scale)
@@ -181,6 +185,8 @@ def test_rmsnorm_bound_is_sound(oracle_mod, n):
             for i in range(n):
                 assert abs(_mpf(y[i]) - ystar[i]) <= _mpf(tau[i])
             assert np.all(tau <= (n + 12) * 2 * U * np.abs(y) + 1e-30)
+            tau0 = oracle_mod.bound_norm(oracle_mod.RMSNORM, x[None], y=None, g=g, eps=eps)[0]
+            assert np.all(tau0 >= tau) and np.all(tau0 <= tau * (1 + 8 * U) + 1e-30)
 
 
 def test_rmsnorm_constant_magnitude_closed_form(oracle_mod):
@@ -205,6 +211,11 @@ def test_rmsnorm_constant_magnitude_closed_form(oracle_mod):
     for i in range(n):
         want = mp.mpf(c) * (E_r + u * R) + u * abs(_mpf(y[0, i]))
         assert want <= _mpf(tau[i]) <= want * (1 + mp.mpf(2) ** -22)
+    # the same row without y: the fresh-rounding term at Y = |x g| R (1+u)^2
+    tau0 = oracle_mod.bound_norm(oracle_mod.RMSNORM, x, y=None, g=g, eps=eps)[0]
+    for i in range(n):
+        want = mp.mpf(c) * (E_r + u * R) + u * mp.mpf(c) * R * (1 + u) ** 2
+        assert want <= _mpf(tau0[i]) <= want * (1 + mp.mpf(2) ** -22)
     # first-order size: |y| (gamma_n/2 + (c_rsqrt + c_div/2 + 2.5) u), about (n/2 + 5.5) u |y|
     assert np.all(np.abs(tau / np.abs(y[0]) / U - (n / 2 + 5.5)) < 1.0)
 
@@ -231,6 +242,64 @@ def test_bn_affine_sound_fused_and_unfused(oracle_mod):
                 want = Fraction(1, 2 ** 24) * abs(frac(x[i, c]) * frac(s[c])) * (1 + Fraction(1, 2 ** 24)) \
                     + Fraction(1, 2 ** 24) * abs(frac(y[i, c]))
                 assert want <= frac(tau[i, c]) <= want * (1 + Fraction(1, 2 ** 22))
+
+
+def test_bounds_without_the_reexecuted_output(oracle_mod):
+    """y = None: the term u|y| of the primitive rule (Sec. 3.1) is evaluated at an upper bound Y of
+    |y| built from exact intermediates: closed forms in exact rationals (BatchNorm-affine, mean) and
+    against 60-digit intermediates (LayerNorm)."""
+    rng = _rng(77)
+    u = Fraction(1, 2 ** 24)
+    C = 9
+    x = rng.standard_normal((4, C)).astype(f32)
+    s = (rng.standard_normal(C) * 2).astype(f32)
+    t = rng.standard_normal(C).astype(f32)
+    for shift in (t, None):
+        tau = oracle_mod.bound_norm(oracle_mod.BN_AFFINE, x, y=None, g=s, b=shift)
+        for i in range(4):
+            for c in range(C):
+                xs = abs(frac(x[i, c]) * frac(s[c]))
+                at = abs(frac(shift[c])) if shift is not None else 0
+                want = u * xs * (1 + u) + u * (xs * (1 + u) + at) * (1 + u)
+                assert want <= frac(tau[i, c]) <= want * (1 + Fraction(1, 2 ** 22))
+    # mean of n terms: Gamma(n-1) sum|x| / n + Y c u/(1 - c u), Y = (sum|x|/n)(1 + Gamma(n-1))(1 + c u), c = c_div = 2
+    for n in (1, 3, 17):
+        xr = rng.standard_normal((2, n)).astype(f32)
+        tau = oracle_mod.bound_norm(oracle_mod.MEAN, xr, y=None)
+        for r in range(2):
+            sa = sum(abs(frac(v)) for v in xr[r])
+            G = (n - 1) * u / (1 - (n - 1) * u)
+            cu = 2 * u
+            want = G * sa / n + (sa / n) * (1 + G) * (1 + cu) * cu / (1 - cu)
+            assert want <= frac(tau[r]) <= want * (1 + Fraction(1, 2 ** 22)) + Fraction(1, 2 ** 149)
+            # and it covers the bound of any actual mean
+            y = np.array([f32(np.sum(xr[r], dtype=f32) / f32(n))], f32)
+            assert tau[r] >= oracle_mod.bound_norm(oracle_mod.MEAN, xr[r:r + 1], y=y)[0]
+    # LayerNorm: tau(None) = E_p + u (|d*| r* |g| + E_p + |b|)(1+u) with E_p = tau(y) - u|y| of the branch
+    # pinned above and d*, r* from 60-digit arithmetic
+    n = 12
+    xl = (rng.standard_normal((3, n)) * 2 + 1).astype(f32)
+    g = (rng.standard_normal(n) + 1).astype(f32)
+    b = rng.standard_normal(n).astype(f32)
+    eps = 1e-5
+    um = mp.mpf(2) ** -24
+    for use_b in (True, False):
+        bb = b if use_b else None
+        y = np.array([[f32(float(v)) for v in _layernorm_exact(row, g, b if use_b else np.zeros(n, f32), eps)] for row in xl], f32)
+        t_y = oracle_mod.bound_norm(oracle_mod.LAYERNORM, xl, y=y, g=g, b=bb, eps=eps)
+        t_0 = oracle_mod.bound_norm(oracle_mod.LAYERNORM, xl, y=None, g=g, b=bb, eps=eps)
+        for r in range(3):
+            xs = [_mpf(v) for v in xl[r]]
+            mu = mp.fsum(xs) / n
+            d = [v - mu for v in xs]
+            rs = 1 / mp.sqrt(mp.fsum([v * v for v in d]) / n + _mpf(f32(eps)))
+            for i in range(n):
+                E_p = _mpf(t_y[r, i]) - um * abs(_mpf(y[r, i]))
+                want = E_p + um * (abs(d[i]) * rs * abs(_mpf(g[i])) + E_p + (abs(_mpf(b[i])) if use_b else 0)) * (1 + um)
+                assert want * (1 - mp.mpf(2) ** -22) <= _mpf(t_0[r, i]) <= want * (1 + mp.mpf(2) ** -21)
+    # a planted mistake would show: leaving |b| out of Y changes the LayerNorm bound
+    assert np.any(oracle_mod.bound_norm(oracle_mod.LAYERNORM, xl, y=None, g=g, b=b, eps=eps) >
+                  oracle_mod.bound_norm(oracle_mod.LAYERNORM, xl, y=None, g=g, b=None, eps=eps))
 
 
 # ---- GroupNorm (App. A.3 operator list): LayerNorm over each (sample, group) -------------------
