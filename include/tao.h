@@ -16,7 +16,8 @@
  *    written, everything else is read only.  Nothing is retained after return.
  *  - `stream` is the caller's hipStream_t passed as void* (NULL = the null
  *    stream).  All work is enqueued asynchronously on it; no entry point
- *    synchronises and none allocates device memory.
+ *    allocates device memory and none synchronises, except the two device self
+ *    tests, which copy their findings back to the host.
  *  - `model` is a HOST pointer (NULL selects tao_default_model()).
  *  - Return value: TAO_OK or a negative TAO_ERR_* code; on error nothing has
  *    been enqueued.  Data-dependent failures (a row for which a template has
@@ -214,11 +215,17 @@ size_t tao_check_linear_images_workspace_bytes(long M, long N, long K, long batc
  * kernel's epilogue, 0 if it stores the bound and runs the streaming check.  Host only: for callers
  * that time or schedule the two kernels separately. */
 int tao_bound_check_linear_in_epilogue(long M, long N, long K, long batch);
-/* Probes v_mfma_f32_32x32x16_bf16 with 3072 seeded non-negative cases and compares every result
- * with the exact integer model the inflation of tao_bound_linear_split rests on.  *report (HOST):
- * bit 0 every case reproduced bit for bit; bit 1 every result from a zero accumulator within
- * [S(1 - 10u), S(1 + 2u)] of the exact sum S.  Synchronises the stream. */
-int tao_selftest_matrix_core_bf16(unsigned *report, void *stream);
+/* Probes v_mfma_f32_32x32x16_bf16 with `cases` seeded non-negative cases (0 = 3072; the model was
+ * fitted on 280 000 of the same generator's kind, which a caller may ask for) and compares every
+ * result with the exact integer model the inflation of tao_bound_linear_split rests on.  *report
+ * (HOST): bit 0 every case of the three normal-range families reproduced bit for bit; bit 1 every
+ * result from a zero accumulator within [S(1 - 10u), S(1 + 2u)] of the exact sum S; bit 2 every result
+ * of the fourth family (products and sums between 2^-150 and 2^-124: the subnormal range) within two
+ * steps of 2^-149 of the exact sum, the absolute term the bound carries for that range.
+ * ws / ws_bytes: DEVICE scratch of tao_selftest_workspace_bytes(cases) bytes, 256-byte aligned (the
+ * self tests allocate nothing on the device).  Synchronises the stream. */
+int tao_selftest_matrix_core_bf16(unsigned *report, long cases, void *ws, size_t ws_bytes, void *stream);
+size_t tao_selftest_workspace_bytes(long cases);
 
 /* 2-D convolution bound without a stored patch matrix (Sec. 3.1: conv is a
  * reduction with gamma_k of the output element; Conv2D of the operator list,
@@ -257,9 +264,13 @@ int tao_bound_softmax(const float *x, const float *y_ref, float *tau, long rows,
 /* Row-wise normalisations and reductions over the last dimension (operators of
  * App. A.3; templates follow the primitive rule of Sec. 3.1).  x: [rows][cols],
  * row stride ld.  y_ref: the verifier's binary32 output ([rows][cols] with row
- * stride ld; [rows] for MEAN; unused and may be NULL for SUM).
+ * stride ld; [rows] for MEAN; unused for SUM), or NULL: the fresh-rounding term
+ * u|y| of the primitive rule is then taken at an upper bound Y of |y| over every
+ * canonical execution, formed from the inputs (a bound that knows y is never larger):
+ *   LAYERNORM (|x - mean| r |g| + E_p + |b|)(1+u), E_p the bound before that term;  RMSNORM |x g| R (1+u)^2;
+ *   BN_AFFINE (|x s|(1+u) + |t|)(1+u);  MEAN (sum|x| / cols)(1 + Gamma(cols-1))(1 + c_div u).
  *  LAYERNORM  y = (x - mean) rsqrt(var + eps) g + b; g = gamma_or_scale[cols] or NULL (= 1),
- *             b = beta_or_shift[cols] or NULL (never enters the bound); two-pass algorithm.
+ *             b = beta_or_shift[cols] or NULL (= 0; enters a bound only through Y); two-pass algorithm.
  *  RMSNORM    y = g (x rsqrt(mean(x^2) + eps)); g as above.
  *  BN_AFFINE  y = x s_c + t_c per column c; s = gamma_or_scale (required), t = beta_or_shift.
  *  SUM, MEAN  tau: [rows];  Gamma(cols-1) sum|x|  (/cols + |y| c_div u/(1 - c_div u) for MEAN).
@@ -478,8 +489,9 @@ size_t tao_project_workspace_bytes(long n);   /* 0 for n <= 0 or n >= 2^31 */
  * linear bound's inflation hold on this device: bit 0 accumulation rounds to
  * nearest-even; bit 1 subnormal products are kept (no flush); bit 2 a 6-step
  * chain on random non-negative data stays within gamma_6 of the exact sum.
+ * ws / ws_bytes: DEVICE scratch of tao_selftest_workspace_bytes(0) bytes, 256-byte aligned.
  * Synchronises the stream.  For callers that want to verify the device once. */
-int tao_selftest_matrix_core(unsigned *report, void *stream);
+int tao_selftest_matrix_core(unsigned *report, void *ws, size_t ws_bytes, void *stream);
 
 /* hipError_t of the most recent TAO_ERR_LAUNCH on this thread (0 if none). */
 int tao_last_hip_error(void);

@@ -95,7 +95,7 @@ EXPORTS = ["tao_default_model", "tao_gamma", "tao_bound_linear", "tao_bound_line
            "tao_linear_split_workspace_bytes", "tao_linear_split_preferred",
            "tao_split_image_bytes", "tao_split_operand", "tao_bound_linear_images", "tao_linear_images_workspace_bytes",
            "tao_bound_check_linear_images", "tao_check_linear_images_workspace_bytes", "tao_bound_check_linear_in_epilogue",
-           "tao_bound_check_linear", "tao_bound_check_linear_workspace_bytes", "tao_selftest_matrix_core_bf16", "tao_bound_conv2d", "tao_bound_softmax",
+           "tao_bound_check_linear", "tao_bound_check_linear_workspace_bytes", "tao_selftest_matrix_core_bf16", "tao_selftest_workspace_bytes", "tao_bound_conv2d", "tao_bound_softmax",
            "tao_bound_norm", "tao_bound_groupnorm", "tao_groupnorm_workspace_bytes", "tao_bound_act", "tao_bound_check_act", "tao_bound_rope", "tao_bound_check_rope", "tao_bound_check_norm", "tao_check_and_profile",
            "tao_check_and_profile_static",
            "tao_check_workspace_bytes", "tao_bound_check_softmax", "tao_profile_errors", "tao_profile_workspace_bytes",
@@ -145,7 +145,9 @@ def lib():
     L.tao_check_linear_images_workspace_bytes.argtypes = [lg, lg, lg, lg]
     L.tao_check_linear_images_workspace_bytes.restype = ctypes.c_size_t
     L.tao_bound_check_linear_in_epilogue.argtypes = [lg, lg, lg, lg]
-    L.tao_selftest_matrix_core_bf16.argtypes = [ctypes.POINTER(ctypes.c_uint), vp]
+    L.tao_selftest_matrix_core_bf16.argtypes = [ctypes.POINTER(ctypes.c_uint), lg, vp, ctypes.c_size_t, vp]
+    L.tao_selftest_workspace_bytes.argtypes = [lg]
+    L.tao_selftest_workspace_bytes.restype = ctypes.c_size_t
     L.tao_bound_conv2d.argtypes = [vp, vp, vp, vp] + [lg] * 13 + [mp, vp]
     L.tao_bound_softmax.argtypes = [vp, vp, vp, lg, lg, lg, mp, vp]
     L.tao_bound_norm.argtypes = [ctypes.c_int, vp, vp, vp, vp, dbl, vp, lg, lg, lg, mp, vp]
@@ -172,7 +174,7 @@ def lib():
     L.tao_project_workspace_bytes.restype = ctypes.c_size_t
     L.tao_profile_workspace_bytes.argtypes = [lg]
     L.tao_profile_workspace_bytes.restype = ctypes.c_size_t
-    L.tao_selftest_matrix_core.argtypes = [ctypes.POINTER(ctypes.c_uint), vp]
+    L.tao_selftest_matrix_core.argtypes = [ctypes.POINTER(ctypes.c_uint), vp, ctypes.c_size_t, vp]
     L.tao_last_hip_error.restype = ctypes.c_int
     L.tao_status_string.argtypes = [ctypes.c_int]
     L.tao_status_string.restype = ctypes.c_char_p
@@ -289,10 +291,12 @@ def tao_linear_split_preferred(M, N, K, batch=1):
     return bool(lib().tao_linear_split_preferred(int(M), int(N), int(K), int(batch)))
 
 
-def tao_selftest_matrix_core_bf16():
-    _torch()
+def tao_selftest_matrix_core_bf16(cases=0):
+    torch = _torch()
     rep = ctypes.c_uint(0)
-    _check(lib().tao_selftest_matrix_core_bf16(ctypes.byref(rep), _stream()), "tao_selftest_matrix_core_bf16")
+    ws = _scratch(torch.device("cuda", torch.cuda.current_device()), lib().tao_selftest_workspace_bytes(int(cases)))
+    _check(lib().tao_selftest_matrix_core_bf16(ctypes.byref(rep), int(cases), _ptr(ws), ws.numel(), _stream()),
+           "tao_selftest_matrix_core_bf16")
     return int(rep.value)
 
 
@@ -813,6 +817,8 @@ def tao_check_workspace_bytes(n):
 
 def tao_selftest_matrix_core():
     """Bit mask: 1 accumulation rounds to nearest-even, 2 subnormals kept, 4 chain within gamma_6."""
+    torch = _torch()
     rep = ctypes.c_uint(0)
-    _check(lib().tao_selftest_matrix_core(ctypes.byref(rep), _stream()), "tao_selftest_matrix_core")
+    ws = _scratch(torch.device("cuda", torch.cuda.current_device()), lib().tao_selftest_workspace_bytes(0))
+    _check(lib().tao_selftest_matrix_core(ctypes.byref(rep), _ptr(ws), ws.numel(), _stream()), "tao_selftest_matrix_core")
     return int(rep.value)

@@ -720,18 +720,18 @@ int tao_bound_conv2d(const float* x, const float* w, const float* bias, float* t
     return launch_status();
 }
 
-int tao_selftest_matrix_core(unsigned* report, void* stream) {
+int tao_selftest_matrix_core(unsigned* report, void* ws, size_t ws_bytes, void* stream) {
     using namespace tao;
     if (!report) return TAO_ERR_NULL;
+    if (!ws || !aligned(ws, 256) || ws_bytes < 8192) return TAO_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     const int kSteps = 3;
     float ha[kSteps * 64], hb[kSteps * 64], hout[16 * 64];
-    float *da = nullptr, *db = nullptr, *dout = nullptr;
-    auto fail = [&](hipError_t e) { g_last_hip_error = (int)e; (void)hipFree(da); (void)hipFree(db); (void)hipFree(dout); return TAO_ERR_LAUNCH; };
+    float* da = static_cast<float*>(ws);
+    float* db = da + kSteps * 64;
+    float* dout = db + kSteps * 64;
+    auto fail = [&](hipError_t e) { g_last_hip_error = (int)e; return TAO_ERR_LAUNCH; };
     hipError_t e;
-    if ((e = hipMalloc(&da, sizeof(ha))) != hipSuccess) return fail(e);
-    if ((e = hipMalloc(&db, sizeof(hb))) != hipSuccess) return fail(e);
-    if ((e = hipMalloc(&dout, sizeof(hout))) != hipSuccess) return fail(e);
     auto run = [&](int steps) -> hipError_t {
         hipError_t r;
         if ((r = hipMemcpyAsync(da, ha, sizeof(ha), hipMemcpyHostToDevice, st)) != hipSuccess) return r;
@@ -775,7 +775,6 @@ int tao_selftest_matrix_core(unsigned* report, void* stream) {
             if (!(std::fabs((double)D(i, j) - s) <= g6 * s)) { within = false; break; }
         }
     if (within) rep |= 4u;
-    (void)hipFree(da); (void)hipFree(db); (void)hipFree(dout);
     *report = rep;
     return TAO_OK;
 }

@@ -31,6 +31,7 @@
 // epilogue adds a bound on it (see split_run), which is far below 1e-6 of any bound above 2^-120.
 #include <cstring>
 #include <type_traits>
+#include <vector>
 #include "tao_device.hpp"
 #include "tao_host.hpp"
 #include "tao_check.hpp"
@@ -565,39 +566,49 @@ static u128 model_step(u128 acc, const u128* prod, const int* pexp) {
 
 extern "C" {
 
-int tao_selftest_matrix_core_bf16(unsigned* report, void* stream) {
+size_t tao_selftest_workspace_bytes(long cases) {
+    if (cases <= 0) cases = 3072;
+    const size_t bf16 = (size_t)cases * (sizeof(tao::Bf16Case) + sizeof(float)) + 256;
+    return bf16 < 8192 ? 8192 : bf16;       // (the FP32 self test needs 5.6 KB)
+}
+
+int tao_selftest_matrix_core_bf16(unsigned* report, long cases, void* ws, size_t ws_bytes, void* stream) {
     using namespace tao;
     if (!report) return TAO_ERR_NULL;
+    if (cases < 0 || cases > (1L << 24)) return TAO_ERR_SHAPE;
+    if (cases == 0) cases = 3072;
+    if (!ws || !aligned(ws, 256) || ws_bytes < tao_selftest_workspace_bytes(cases)) return TAO_ERR_WORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    constexpr int kCases = 3072;
-    static Bf16Case hc[kCases];
-    static float hd[kCases];
+    const int kCases = (int)cases;
+    std::vector<Bf16Case> hc(kCases);
+    std::vector<float> hd(kCases);
     unsigned long long lcg = 0x2545F4914F6CDD1Dull;
     auto rnd = [&]() { lcg = lcg * 6364136223846793005ull + 1442695040888963407ull; return (unsigned)(lcg >> 33); };
     auto bf = [](int e, unsigned man7) { return (unsigned short)(((127 + e) << 7) | (man7 & 127u)); };
     auto f32 = [](int e, unsigned man23) { const unsigned u = ((unsigned)(127 + e) << 23) | (man23 & 0x7fffffu); float f; memcpy(&f, &u, 4); return f; };
+    // four seeded families of non-negative operands: narrow exponents; wide exponents; products far
+    // below an accumulator of the order of 1; products and sums in the binary32 subnormal range
     for (int i = 0; i < kCases; ++i) {
         Bf16Case& c = hc[i];
-        const int fam = i % 3;
+        const int fam = i % 4;
         const int shift = 20 + (int)(rnd() % 10);
         for (int k = 0; k < 16; ++k) {
             if (fam == 0)      { c.a[k] = bf((int)(rnd() % 3) - 1, rnd()); c.b[k] = bf((int)(rnd() % 3) - 1, rnd()); }     // narrow
             else if (fam == 1) { c.a[k] = bf((int)(rnd() % 25) - 12, rnd()); c.b[k] = bf((int)(rnd() % 25) - 12, rnd()); } // wide
-            else               { c.a[k] = bf(-(shift / 2) + (int)(rnd() % 3) - 1, rnd()); c.b[k] = bf(-(shift - shift / 2), rnd()); }  // far below c
+            else if (fam == 2) { c.a[k] = bf(-(shift / 2) + (int)(rnd() % 3) - 1, rnd()); c.b[k] = bf(-(shift - shift / 2), rnd()); }  // far below c
+            else               { c.a[k] = bf(-75 + (int)(rnd() % 11), rnd()); c.b[k] = bf(-75 + (int)(rnd() % 11), rnd()); }           // 2^-150 .. 2^-128
         }
-        c.c = fam == 2 ? f32(0, rnd()) : ((i & 1) ? f32((int)(rnd() % 25) - 12, rnd()) : 0.f);
+        c.c = fam == 3 ? 0.f : fam == 2 ? f32(0, rnd()) : ((i & 1) ? f32((int)(rnd() % 25) - 12, rnd()) : 0.f);
     }
-    Bf16Case* dc = nullptr; float* dd = nullptr;
-    auto fail = [&](hipError_t e) { g_last_hip_error = (int)e; (void)hipFree(dc); (void)hipFree(dd); return TAO_ERR_LAUNCH; };
+    Bf16Case* dc = static_cast<Bf16Case*>(ws);
+    float* dd = reinterpret_cast<float*>(static_cast<char*>(ws) + ((size_t)kCases * sizeof(Bf16Case) + 255) / 256 * 256);
+    auto fail = [&](hipError_t e) { g_last_hip_error = (int)e; return TAO_ERR_LAUNCH; };
     hipError_t e;
-    if ((e = hipMalloc(&dc, sizeof(hc))) != hipSuccess) return fail(e);
-    if ((e = hipMalloc(&dd, sizeof(hd))) != hipSuccess) return fail(e);
-    if ((e = hipMemcpyAsync(dc, hc, sizeof(hc), hipMemcpyHostToDevice, st)) != hipSuccess) return fail(e);
+    if ((e = hipMemcpyAsync(dc, hc.data(), (size_t)kCases * sizeof(Bf16Case), hipMemcpyHostToDevice, st)) != hipSuccess) return fail(e);
     hipLaunchKernelGGL(bf16_mfma_probe, dim3((kCases + 3) / 4), dim3(256), 0, st, dc, dd, kCases);
     if ((e = hipGetLastError()) != hipSuccess) return fail(e);
-    if ((e = hipMemcpyAsync(hd, dd, sizeof(hd), hipMemcpyDeviceToHost, st)) != hipSuccess) return fail(e);
+    if ((e = hipMemcpyAsync(hd.data(), dd, (size_t)kCases * sizeof(float), hipMemcpyDeviceToHost, st)) != hipSuccess) return fail(e);
     if ((e = hipStreamSynchronize(st)) != hipSuccess) return fail(e);
-    (void)hipFree(dc); (void)hipFree(dd);
 
     auto to_int = [](float f) -> u128 {                       // positive normal binary32 -> units of 2^-kScale
         unsigned u; memcpy(&u, &f, 4);
@@ -605,9 +616,20 @@ int tao_selftest_matrix_core_bf16(unsigned* report, void* stream) {
         const int ex = (int)((u >> 23) & 255) - 127;
         return (u128)((u & 0x7fffffu) | 0x800000u) << (kScale + ex - 23);
     };
-    bool exact = true, within = true;
+    bool exact = true, within = true, tiny = true;
     for (int i = 0; i < kCases; ++i) {
         const Bf16Case& c = hc[i];
+        if (i % 4 == 3) {
+            // subnormal range: the exact sum (16 products of 16 bits within 22 binades: exact in
+            // binary64) against the result, in steps of 2^-149
+            double sum = 0.0;
+            for (int k = 0; k < 16; ++k) {
+                const int ea = (int)((c.a[k] >> 7) & 255) - 127, eb = (int)((c.b[k] >> 7) & 255) - 127;
+                sum += std::ldexp((double)(((c.a[k] & 127u) | 128u) * ((c.b[k] & 127u) | 128u)), ea + eb - 14);
+            }
+            if (!(std::fabs((double)hd[i] - sum) <= 2.0 * 0x1p-149)) tiny = false;
+            continue;
+        }
         u128 prod[16]; int pexp[16];
         u128 sum = to_int(c.c);
         for (int k = 0; k < 16; ++k) {
@@ -628,7 +650,7 @@ int tao_selftest_matrix_core_bf16(unsigned* report, void* stream) {
             if (got < lo || got > hi) within = false;
         }
     }
-    *report = (exact ? 1u : 0u) | (within ? 2u : 0u);
+    *report = (exact ? 1u : 0u) | (within ? 2u : 0u) | (tiny ? 4u : 0u);
     return TAO_OK;
 }
 

@@ -317,7 +317,7 @@ __device__ __forceinline__ bool rsqrt_tail(double vstar, double E_v, const RowCo
 // binary64 rounding (a few 2^-53) is covered by the rounding margin of up32g.
 // From E_mu, sum|d|, sum d^2 to the per-element coefficients: E_p/|g| = K1 |d| + K0.
 __device__ __forceinline__ void layernorm_tail(double E_mu, double s_ad, double s_d2, double n, const RowConsts& k,
-                                               double& K1, double& K0, double& amp) {
+                                               double& K1, double& K0, double& amp, double* rs_out = nullptr) {
     const double up = k.u * k.inv1mu, Ep = E_mu * k.inv1mu;       // u', E'
     const double c1 = 1.0 + up;
     const double sD2 = c1 * c1 * s_d2 + 2.0 * c1 * Ep * s_ad + n * Ep * Ep;           // sum D^2
@@ -330,16 +330,21 @@ __device__ __forceinline__ void layernorm_tail(double E_mu, double s_ad, double 
     const double hc = E_r + k.u * R;                              // E_h = D hc + r E_d
     K1 = (1.0 + k.u) * (c1 * hc + rs * up) + k.u * rs;
     K0 = ok ? (1.0 + k.u) * Ep * (hc + rs) : NAN;                 // NaN row when the bound is not finite
+    if (rs_out) *rs_out = rs;
 }
 
 // GROUPED (GroupNorm): a row is one (sample, group) of a channel-major tensor, cols = channels per
 // group x positions; column c takes the affine scale of channel (row % groups) * cpg + c / hw.
 struct GroupGeom { unsigned hw, cpg, groups; };
-template <int TPR, int V, bool GROUPED>
+// NOY: the caller has no re-executed output; the fresh-rounding term u|y| is then taken at the upper
+// bound Y = (|d| r |g| + E_p + |b|)(1+u) of |y| over all canonical executions (b: the additive term,
+// which enters a bound only here).
+template <int TPR, int V, bool GROUPED, bool NOY = false>
 __device__ __forceinline__ void layernorm_body(
     const float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ g,
     float* __restrict__ tau, long rows, long cols, long ld, int vec_ok, int vec_g, const RowConsts& k,
-    GroupGeom gg) {
+    GroupGeom gg, const float* __restrict__ b = nullptr, int vec_b = 0) {
+    static_assert(!(NOY && GROUPED), "GroupNorm takes the re-executed output");
     TAO_ROW_PROLOGUE
     // the four scales of the vector that starts at column idx
     const float* gb = (GROUPED && g && active) ? g + (unsigned long)(row % (long)gg.groups) * gg.cpg : g;
@@ -364,7 +369,9 @@ __device__ __forceinline__ void layernorm_body(
         const float4 X = load4<CACHED>(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
         if (CACHED) {
             xv[v] = X;
-            yv[v] = load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+            // (without y the registers hold |b| instead)
+            yv[v] = NOY ? (b ? load4(b, TAO_VEC_INDEX(v), limit, vec_b, 0.f) : make_float4(0.f, 0.f, 0.f, 0.f))
+                        : load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
             gv[v] = scales(TAO_VEC_INDEX(v));
         }
         const float e[4] = {X.x, X.y, X.z, X.w};
@@ -388,12 +395,14 @@ __device__ __forceinline__ void layernorm_body(
         }
     }
     group_sum<TPR>(a2, 2, smem + 16);
-    double K1, K0, amp;
-    layernorm_tail(E_mu, a2[0], a2[1], n, k, K1, K0, amp);
+    double K1, K0, amp, rs;
+    layernorm_tail(E_mu, a2[0], a2[1], n, k, K1, K0, amp, &rs);
     const UpFactors up(k.m * (1.0 + 2.0 * amp));
     for (int v = 0; v < nv; ++v) {
         const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
-        const float4 Y = CACHED ? yv[v] : load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        const float4 Y = CACHED ? yv[v]
+                       : NOY ? (b ? load4(b, TAO_VEC_INDEX(v), limit, vec_b, 0.f) : make_float4(0.f, 0.f, 0.f, 0.f))
+                             : load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
         const float4 Gv = CACHED ? gv[v] : scales(TAO_VEC_INDEX(v));
         const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w};
         const float ge[4] = {Gv.x, Gv.y, Gv.z, Gv.w};
@@ -401,8 +410,11 @@ __device__ __forceinline__ void layernorm_body(
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const double ad = fabs((double)xe[c] - mu);
-            const double ep = (double)fabsf(ge[c]) * fma(K1, ad, K0);
-            te[c] = up32g(fma(k.u, (double)fabsf(ye[c]), ep), up.mul, up.sub);
+            const double ag = (double)fabsf(ge[c]);
+            const double ep = ag * fma(K1, ad, K0);
+            // |y|, or its upper bound (|d| r |g| + E_p + |b|)(1+u)
+            const double Yb = NOY ? (ad * rs * ag + ep + (double)fabsf(ye[c])) * (1.0 + k.u) : (double)fabsf(ye[c]);
+            te[c] = up32g(fma(k.u, Yb, ep), up.mul, up.sub);
         }
         store4(tau + roff, TAO_VEC_INDEX(v), limit, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
     }
@@ -412,6 +424,12 @@ __global__ __launch_bounds__(kRowThreads) void layernorm_bound(
     const float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ g,
     float* __restrict__ tau, long rows, long cols, long ld, int vec_ok, int vec_g, RowConsts k) {
     layernorm_body<TPR, V, false>(x, y, g, tau, rows, cols, ld, vec_ok, vec_g, k, GroupGeom());
+}
+template <int TPR, int V>
+__global__ __launch_bounds__(kRowThreads) void layernorm_bound_noy(
+    const float* __restrict__ x, const float* __restrict__ g, const float* __restrict__ b,
+    float* __restrict__ tau, long rows, long cols, long ld, int vec_ok, int vec_g, int vec_b, RowConsts k) {
+    layernorm_body<TPR, V, false, true>(x, nullptr, g, tau, rows, cols, ld, vec_ok, vec_g, k, GroupGeom(), b, vec_b);
 }
 template <int TPR, int V>
 __global__ __launch_bounds__(kRowThreads) void groupnorm_bound(
@@ -531,18 +549,19 @@ __global__ __launch_bounds__(kRowThreads) void groupnorm_apply(
 }
 
 // ------------------------------------------------------------------ RMSNorm
-template <int TPR, int V>
-__global__ __launch_bounds__(kRowThreads) void rmsnorm_bound(
+// NOY: no re-executed output; u|y| is taken at Y = |x g| R (1+u)^2 >= |y|.
+template <int TPR, int V, bool NOY>
+__device__ __forceinline__ void rmsnorm_body(
     const float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ g,
-    float* __restrict__ tau, long rows, long cols, long ld, int vec_ok, int vec_g, RowConsts k) {
+    float* __restrict__ tau, long rows, long cols, long ld, int vec_ok, int vec_g, const RowConsts& k) {
     TAO_ROW_PROLOGUE
-    float4 xv[CACHED ? V : 1], yv[CACHED ? V : 1], gv[CACHED ? V : 1];
+    float4 xv[CACHED ? V : 1], yv[(CACHED && !NOY) ? V : 1], gv[CACHED ? V : 1];
     double a1[1] = {0.0};
     for (int v = 0; v < nv; ++v) {
         const float4 X = load4<CACHED>(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
         if (CACHED) {
             xv[v] = X;
-            yv[v] = load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+            if (!NOY) yv[v] = load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
             gv[v] = g ? load4(g, TAO_VEC_INDEX(v), limit, vec_g, 1.f) : make_float4(1.f, 1.f, 1.f, 1.f);
         }
         const float e[4] = {X.x, X.y, X.z, X.w};
@@ -556,10 +575,12 @@ __global__ __launch_bounds__(kRowThreads) void rmsnorm_bound(
     double rs, E_r, R, amp;
     const bool ok = rsqrt_tail(vstar, E_v, k, rs, E_r, R, amp);
     const double f = E_r + k.u * R;
+    const double fy = k.u * R * (1.0 + k.u) * (1.0 + k.u);           // NOY: u Y / |x g|
     const UpFactors up(k.m * (1.0 + 2.0 * amp));
     for (int v = 0; v < nv; ++v) {
         const float4 X = CACHED ? xv[v] : load4(x + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
-        const float4 Y = CACHED ? yv[v] : load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f);
+        const float4 Y = NOY ? make_float4(0.f, 0.f, 0.f, 0.f)
+                             : (CACHED ? yv[v] : load4<true>(y + roff, TAO_VEC_INDEX(v), limit, vec_ok, 0.f));
         const float4 Gv = CACHED ? gv[v] : (g ? load4(g, TAO_VEC_INDEX(v), limit, vec_g, 1.f) : make_float4(1.f, 1.f, 1.f, 1.f));
         const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w};
         const float ge[4] = {Gv.x, Gv.y, Gv.z, Gv.w};
@@ -567,11 +588,23 @@ __global__ __launch_bounds__(kRowThreads) void rmsnorm_bound(
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const double xg = fabs((double)xe[c] * (double)ge[c]);
-            const double t = xg * f + k.u * fabs((double)ye[c]);
+            const double t = NOY ? xg * f + xg * fy : xg * f + k.u * fabs((double)ye[c]);
             te[c] = ok ? up32g(t, up.mul, up.sub) : NAN;
         }
         store4(tau + roff, TAO_VEC_INDEX(v), limit, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
     }
+}
+template <int TPR, int V>
+__global__ __launch_bounds__(kRowThreads) void rmsnorm_bound(
+    const float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ g,
+    float* __restrict__ tau, long rows, long cols, long ld, int vec_ok, int vec_g, RowConsts k) {
+    rmsnorm_body<TPR, V, false>(x, y, g, tau, rows, cols, ld, vec_ok, vec_g, k);
+}
+template <int TPR, int V>
+__global__ __launch_bounds__(kRowThreads) void rmsnorm_bound_noy(
+    const float* __restrict__ x, const float* __restrict__ g,
+    float* __restrict__ tau, long rows, long cols, long ld, int vec_ok, int vec_g, RowConsts k) {
+    rmsnorm_body<TPR, V, true>(x, nullptr, g, tau, rows, cols, ld, vec_ok, vec_g, k);
 }
 
 // LayerNorm / RMSNorm bounds checked on the spot: the structure of softmax_check (1024-thread
@@ -695,7 +728,8 @@ __global__ __launch_bounds__(kRowThreads) void summean_bound(
     group_sum<TPR>(a1, 1, smem);
     if (active && lt == 0) {
         double t = k.G * a1[0];
-        if (is_mean) t = t * k.inv_n + fabs((double)y[row]) * k.mean_f;
+        // (mean without y: |y| <= (sum|x| / n)(1 + Gamma)(1 + c_div u))
+        if (is_mean) t = t * k.inv_n + (y ? fabs((double)y[row]) : a1[0] * k.inv_n * (1.0 + k.G) * (1.0 + k.cd_u)) * k.mean_f;
         const UpFactors up(k.m);
         tau[row] = up32g(t, up.mul, up.sub);
     }
@@ -703,6 +737,9 @@ __global__ __launch_bounds__(kRowThreads) void summean_bound(
 
 // ------------------------------------------------------------------ BatchNorm-affine
 // tau = u |x s_c| (1+u) + u |y|, column c = flat index mod cols; one thread per 4 columns.
+// NOY: no re-executed output (y is then the shift t or NULL, indexed by column like s): u|y| is taken at
+// Y = (|x s|(1+u) + |t|)(1+u) >= |y|.
+template <bool NOY>
 __global__ __launch_bounds__(kRowThreads) void bn_affine_bound(
     const float* __restrict__ x, const float* __restrict__ y, const float* __restrict__ s,
     float* __restrict__ tau, long rows, long cols, long ld, int vec_ok, int vec_s, double u) {
@@ -718,14 +755,16 @@ __global__ __launch_bounds__(kRowThreads) void bn_affine_bound(
         if (jv >= vpr) { jv -= vpr; ++row; }
         const long j = jv * 4;
         const float4 X = load4<true>(x + row * ld, j, cols, vec_ok, 0.f);
-        const float4 Y = load4<true>(y + row * ld, j, cols, vec_ok, 0.f);
+        const float4 Y = NOY ? (y ? load4(y, j, cols, 0, 0.f) : make_float4(0.f, 0.f, 0.f, 0.f))
+                             : load4<true>(y + row * ld, j, cols, vec_ok, 0.f);
         const float4 S = load4(s, j, cols, vec_s, 0.f);
         const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w}, se[4] = {S.x, S.y, S.z, S.w};
         float te[4];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const double xs = fabs((double)xe[c] * (double)se[c]);
-            const double t = u * xs * (1.0 + u) + u * fabs((double)ye[c]);
+            const double Yb = NOY ? (xs * (1.0 + u) + fabs((double)ye[c])) * (1.0 + u) : fabs((double)ye[c]);
+            const double t = u * xs * (1.0 + u) + u * Yb;
             te[c] = up32g(t, kUpMul, 1.0 + 0x1p-48);
         }
         store4(tau + row * ld, j, cols, vec_ok, make_float4(te[0], te[1], te[2], te[3]));
@@ -807,7 +846,6 @@ int tao_bound_norm(int kind, const float* x, const float* y_ref, const float* ga
                    const float* beta_or_shift, double eps, float* tau, long rows, long cols, long ld,
                    const tao_fp_model* model, void* stream) {
     using namespace tao;
-    (void)beta_or_shift;
     tao_fp_model md;
     int rc = resolve_model(model, &md);
     if (rc != TAO_OK) return rc;
@@ -817,31 +855,36 @@ int tao_bound_norm(int kind, const float* x, const float* y_ref, const float* ga
     if (cols == 0 && kind != TAO_NORM_SUM && kind != TAO_NORM_MEAN) return TAO_OK;
     if (cols == 0) return TAO_ERR_SHAPE;
     if (!x || !tau) return TAO_ERR_NULL;
-    if (kind != TAO_NORM_SUM && !y_ref) return TAO_ERR_NULL;
     if (kind == TAO_NORM_BN_AFFINE && !gamma_or_scale) return TAO_ERR_NULL;
-    if (!aligned(x, 4) || !aligned(y_ref, 4) || !aligned(tau, 4) || !aligned(gamma_or_scale, 4)) return TAO_ERR_ALIGN;
+    if (!aligned(x, 4) || !aligned(y_ref, 4) || !aligned(tau, 4) || !aligned(gamma_or_scale, 4) || !aligned(beta_or_shift, 4))
+        return TAO_ERR_ALIGN;
     if (!(eps >= 0.0) || !std::isfinite(eps)) return TAO_ERR_SHAPE;
     RowConsts k;
     rc = make_consts(md, cols, eps, &k, kind == TAO_NORM_LAYERNORM || kind == TAO_NORM_RMSNORM);
     if (rc != TAO_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     const int vec_x = aligned(x, 16) && (ld % 4 == 0);
-    const int vec_ok = vec_x && aligned(y_ref, 16) && aligned(tau, 16);
-    const int vec_g = aligned(gamma_or_scale, 16);
+    const int vec_ok = vec_x && aligned(y_ref, 16) && aligned(tau, 16);      // (a NULL y_ref counts as aligned)
+    const int vec_g = aligned(gamma_or_scale, 16), vec_b = aligned(beta_or_shift, 16);
     const float* g = gamma_or_scale;
+    const float* b = beta_or_shift;
     switch (kind) {
         case TAO_NORM_LAYERNORM:
-            TAO_DISPATCH_ROWS(layernorm_bound, 1024, rows, cols, st, x, y_ref, g, tau, rows, cols, ld, vec_ok, vec_g, k);
+            if (y_ref) TAO_DISPATCH_ROWS(layernorm_bound, 1024, rows, cols, st, x, y_ref, g, tau, rows, cols, ld, vec_ok, vec_g, k);
+            else       TAO_DISPATCH_ROWS(layernorm_bound_noy, 1024, rows, cols, st, x, g, b, tau, rows, cols, ld, vec_ok, vec_g, vec_b, k);
             break;
         case TAO_NORM_RMSNORM:
-            TAO_DISPATCH_ROWS(rmsnorm_bound, 1024, rows, cols, st, x, y_ref, g, tau, rows, cols, ld, vec_ok, vec_g, k);
+            if (y_ref) TAO_DISPATCH_ROWS(rmsnorm_bound, 1024, rows, cols, st, x, y_ref, g, tau, rows, cols, ld, vec_ok, vec_g, k);
+            else       TAO_DISPATCH_ROWS(rmsnorm_bound_noy, 1024, rows, cols, st, x, g, tau, rows, cols, ld, vec_ok, vec_g, k);
             break;
         case TAO_NORM_BN_AFFINE: {
             const long total = rows * ((cols + 3) / 4);
             long blocks = (total + kRowThreads - 1) / kRowThreads;
             if (blocks > 256L * 64) blocks = 256L * 64;    // grid-stride beyond 64 workgroups per CU
-            hipLaunchKernelGGL(bn_affine_bound, dim3((unsigned)blocks), dim3(kRowThreads), 0, st, x, y_ref, g,
-                               tau, rows, cols, ld, vec_ok, vec_g, md.u);
+            if (y_ref) hipLaunchKernelGGL(bn_affine_bound<false>, dim3((unsigned)blocks), dim3(kRowThreads), 0, st, x, y_ref, g,
+                                          tau, rows, cols, ld, vec_ok, vec_g, md.u);
+            else       hipLaunchKernelGGL(bn_affine_bound<true>, dim3((unsigned)blocks), dim3(kRowThreads), 0, st, x, b, g,
+                                          tau, rows, cols, ld, vec_ok, vec_g, md.u);
             break;
         }
         default: {

@@ -76,7 +76,8 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_bound_softmax(p, p, p, 4, 4, 4, ctypes.byref(tao.FpModel(flags=8)), None) == tao.ERR_MODEL     # unknown flag bit
     # norm
     assert L.tao_bound_norm(9, p, p, p, p, 1e-5, p, 4, 4, 4, None, None) == tao.ERR_KIND
-    assert L.tao_bound_norm(0, p, nul, p, p, 1e-5, p, 4, 4, 4, None, None) == tao.ERR_NULL   # y_ref required
+    assert L.tao_bound_norm(0, nul, p, p, p, 1e-5, p, 4, 4, 4, None, None) == tao.ERR_NULL   # x required (y_ref may be NULL)
+    assert L.tao_bound_norm(0, p, nul, p, odd, 1e-5, p, 4, 4, 4, None, None) == tao.ERR_ALIGN  # the shift enters the bound without y_ref
     assert L.tao_bound_norm(2, p, p, nul, p, 0.0, p, 4, 4, 4, None, None) == tao.ERR_NULL    # scale required
     assert L.tao_bound_norm(0, p, p, p, p, -1.0, p, 4, 4, 4, None, None) == tao.ERR_SHAPE
     # groupnorm: (eps, tau, batch, channels, positions, groups)
@@ -297,7 +298,16 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_project_empirical(nul, nul, 1.0, nul, 0, nul, 0, None) == tao.OK
     for code in range(0, -9, -1):
         assert L.tao_status_string(code)
-    assert L.tao_selftest_matrix_core(None, None) == tao.ERR_NULL
+    L.tao_selftest_workspace_bytes.restype = ctypes.c_size_t
+    rep = ctypes.c_uint(0)
+    assert L.tao_selftest_matrix_core(None, big, 8192, None) == tao.ERR_NULL
+    assert L.tao_selftest_matrix_core(ctypes.byref(rep), nul, 8192, None) == tao.ERR_WORKSPACE     # scratch comes from the caller
+    assert L.tao_selftest_matrix_core(ctypes.byref(rep), big, 100, None) == tao.ERR_WORKSPACE
+    assert L.tao_selftest_matrix_core_bf16(None, 0, big, 1 << 20, None) == tao.ERR_NULL
+    assert L.tao_selftest_matrix_core_bf16(ctypes.byref(rep), 0, nul, 1 << 20, None) == tao.ERR_WORKSPACE
+    assert L.tao_selftest_matrix_core_bf16(ctypes.byref(rep), 280000, big, L.tao_selftest_workspace_bytes(280000) - 1, None) == tao.ERR_WORKSPACE
+    assert L.tao_selftest_matrix_core_bf16(ctypes.byref(rep), -1, big, 1 << 20, None) == tao.ERR_SHAPE
+    assert L.tao_selftest_workspace_bytes(0) == 3072 * 72 + 256 and L.tao_selftest_workspace_bytes(280000) == 280000 * 72 + 256
 
 
 def test_binding_refuses_to_run_without_a_gpu(tao):

@@ -57,6 +57,9 @@ def test_bf16_matrix_core_selftest(tao):
     print("bf16 matrix-core self test report:", rep, flush=True)
     assert rep & 1, "v_mfma_f32_32x32x16_bf16 does not follow the model the split bound's inflation rests on"
     assert rep & 2, "a zero-accumulator instruction left [S(1-10u), S(1+2u)]"
+    assert rep & 4, "a result in the subnormal range is more than two steps of 2^-149 from the exact sum"
+    # the larger run on request: 280 000 cases of the same generator
+    assert tao.tao_selftest_matrix_core_bf16(cases=280000) == 7
     assert tao.tao_linear_split_preferred(2048, 4096, 4096) and not tao.tao_linear_split_preferred(2048, 128, 2048, 8)
     assert not tao.tao_linear_split_preferred(512, 768, 768)
 
@@ -469,6 +472,37 @@ def test_linear_tiny_operands_stay_above_the_reference(tao, oracle_mod):
     t_or = oracle_mod.bound_linear(_np(A), _np(W), model=mo)
     for t_gpu in (_np(tao.tao_bound_linear(A.cuda(), W.cuda(), model=mg)), _np(tao.tao_bound_linear_split(A.cuda(), W.cuda(), model=mg))):
         assert np.all(t_gpu >= t_or) and np.all(t_gpu <= t_or + np.float32(2.0 ** -149))
+
+
+@pytest.mark.parametrize("kind", ["layernorm", "rmsnorm", "bn_affine", "mean"])
+@pytest.mark.parametrize("rows,cols", [(1, 1), (5, 3), (16, 256), (7, 768), (3, 1030), (4, 4096), (2, 8200), (3, 20000)])
+def test_norm_bounds_without_the_reexecuted_output(tao, oracle_mod, kind, rows, cols):
+    """y_ref = NULL: the fresh-rounding term at the template's own upper bound of |y|; against the
+    oracle, with and without scale and shift, and never below the bound that is given y."""
+    g = torch.Generator().manual_seed(rows * 977 + cols)
+    x = torch.randn((rows, cols), generator=g) * 2 + 0.5
+    gam = 1 + 0.1 * torch.randn((cols,), generator=g)
+    bet = 0.5 * torch.randn((cols,), generator=g)
+    code = {"layernorm": 0, "rmsnorm": 1, "bn_affine": 2, "mean": 4}[kind]
+    eps = 1e-5
+    variants = [(gam, bet), (gam, None)] + ([] if kind == "bn_affine" else [(None, None)])
+    for gg, bb in variants:
+        t_or = oracle_mod.bound_norm(code, _np(x), y=None, g=None if gg is None else _np(gg), b=None if bb is None else _np(bb), eps=eps)
+        t_gpu = tao.tao_bound_norm(code, x.cuda(), None, None if gg is None else gg.cuda(), None if bb is None else bb.cuda(), eps=eps)
+        assert_bound_parity(_np(t_gpu), t_or, "%s %dx%d without y" % (kind, rows, cols))
+    # the bound that knows an actual output is never larger
+    if kind == "layernorm":
+        y = tao_inputs.layernorm_f32(x, gam, bet, eps)
+    elif kind == "rmsnorm":
+        y = tao_inputs.rmsnorm_f32(x, gam, eps)
+    elif kind == "bn_affine":
+        y = x * gam + bet
+    else:
+        y = x.sum(-1) / cols
+    with_y = tao.tao_bound_norm(code, x.cuda(), y.cuda(), gam.cuda(), bet.cuda(), eps=eps)
+    without = tao.tao_bound_norm(code, x.cuda(), None, gam.cuda(), bet.cuda(), eps=eps)
+    ok = ~torch.isnan(with_y)
+    assert bool((without[ok] >= with_y[ok]).all())
 
 
 @pytest.mark.parametrize("kind", ["layernorm", "rmsnorm"])
