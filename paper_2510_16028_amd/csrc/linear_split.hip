@@ -158,6 +158,9 @@ struct SplitArgs {
     double* partial;
     // workgroup -> tile: slots per super-tile (8 patches of ph x pw tiles), per batch entry, patches side by side
     unsigned slots, slots_per_z, super_rows, pw, ph, npx;
+    // AREG instantiations: the binary32 A operand itself (row stride lda, batch stride strideA, in
+    // elements); A3 is then unused
+    const float* Af; long lda, strideA;
 };
 
 // check_one with the histogram layout of the CHECK instantiation below (16-bit counters, bin b in
@@ -183,10 +186,18 @@ __device__ __forceinline__ void check_one_packed(float c, float r, float t, doub
 // WALK: the plain bound as the host launches it.  A workgroup takes the slots blockIdx.x,
 // + gridDim.x, ... and its pipeline of slabs runs on across the tile boundaries: with a workgroup
 // per slot that is one tile, with a workgroup per compute unit (short reductions) a walk over many.
-template <bool CHECK, bool PARTIAL = false, bool WALK = false>
+// AREG: the A operand is not read from a prepared image but from its binary32 matrix: every thread
+// loads 8 consecutive k of one row of the slab two groups ahead, cuts them into the three pieces in
+// registers one group ahead and writes them to the stage in the image's layout.  For products
+// whose A operand is used by one or two column tiles only (a 128-column output, e.g. attention
+// probabilities times values), where a pre-pass over A (10 bytes per element written and read back)
+// costs more than the product.  One tile per workgroup (no walk), whole groups only (K a multiple
+// of 32), 16-byte aligned rows: the host checks all of it.
+template <bool CHECK, bool PARTIAL = false, bool WALK = false, bool AREG = false>
 __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
     static_assert(!(CHECK && PARTIAL), "the parts are checked by split_combine");
     static_assert(!(WALK && (CHECK || PARTIAL)), "only the plain bound walks tiles");
+    static_assert(!(AREG && (WALK || PARTIAL)), "the in-load split keeps one tile per workgroup and the whole reduction");
     extern __shared__ __attribute__((aligned(16))) char lds[];
     // CHECK: four copies of the 2048-bin histogram with 16-bit counters (a tile has 16384 elements, so
     // none overflows), two bins to a word and the four copies of a word in consecutive banks: 16 KB,
@@ -250,11 +261,40 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
             (unsigned)(size_t)(__attribute__((address_space(3))) char*)(stage) + (unsigned)wave * 1024u);
 #pragma unroll
         for (int i = 0; i < 3; ++i) {
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                         :: "s"(dst + (unsigned)(i * kSplitThreads * 16)), "v"(a + i * kSplitThreads * 16) : "memory");
+            if (!AREG)
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                             :: "s"(dst + (unsigned)(i * kSplitThreads * 16)), "v"(a + i * kSplitThreads * 16) : "memory");
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
                          :: "s"(dst + (unsigned)(kBlock + i * kSplitThreads * 16)), "v"(w + i * kSplitThreads * 16) : "memory");
         }
+    };
+    // AREG: thread -> row tid / 4 of the tile, k chunk tid % 4 of the group (8 consecutive k: 32
+    // bytes).  Ordinary loads, which the compiler tracks: it waits for them where their registers are
+    // first used (commit_a, one group after the request).  Rows beyond M read the last row instead
+    // (their outputs are never stored).
+    typedef float floatx4 __attribute__((ext_vector_type(4)));
+    auto fetch_a = [&](floatx4& lo4, floatx4& hi4, long g) __attribute__((always_inline)) {
+        long row = (long)m0 + (tid >> 2);
+        row = row < p.M ? row : p.M - 1;
+        const floatx4* src = reinterpret_cast<const floatx4*>(p.Af + (long)z * p.strideA + row * p.lda + (g0 + g) * SBK + (tid & 3) * 8);
+        lo4 = src[0];
+        hi4 = src[1];
+    };
+    auto commit_a = [&](char* stage, const floatx4& lo4, const floatx4& hi4) __attribute__((always_inline)) {
+        const float v[8] = {lo4[0], lo4[1], lo4[2], lo4[3], hi4[0], hi4[1], hi4[2], hi4[3]};
+        unsigned hh[8], mm[8], ll[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) split_one(v[j], hh[j], mm[j], ll[j]);
+        uintx4 H, Mi, L;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            H[j] = hh[2 * j] | (hh[2 * j + 1] << 16); Mi[j] = mm[2 * j] | (mm[2 * j + 1] << 16); L[j] = ll[2 * j] | (ll[2 * j + 1] << 16);
+        }
+        const int r = tid >> 2;
+        const int o = r * SROW + (((tid & 3) ^ ((r >> 2) & 3)) * 16);
+        *reinterpret_cast<uintx4*>(stage + o) = H;
+        *reinterpret_cast<uintx4*>(stage + kSlab + o) = Mi;
+        *reinterpret_cast<uintx4*>(stage + 2 * kSlab + o) = L;
     };
 
     double S[2][16];
@@ -332,8 +372,20 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
     // reads of stage (j + 2) % 3 (group j - 1) from its next fill.  The first group of a later tile
     // waits for everything instead: the epilogue before it has issued loads, stores and atomics of
     // its own, which count in the same counter.
-    if (ngroup > 0) request(lds, m0, n0, z, 0);
-    if (ngroup > 1) request(lds + kSplitStage, m0, n0, z, 1);
+    // AREG: slab j's A part is requested into registers at the top of group j - 2 (after the copies of
+    // slab j - 1's A part have been cut and written), cut into its pieces and written to stage j % 3 at
+    // the top of group j - 1, and used in group j.
+    floatx4 ar0[2], ar1[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) { ar0[i] = floatx4{0.f, 0.f, 0.f, 0.f}; ar1[i] = ar0[i]; }
+    if (AREG) {
+        if (ngroup > 0) { fetch_a(ar0[0], ar0[1], 0); request(lds, m0, n0, z, 0); }
+        if (ngroup > 1) { fetch_a(ar1[0], ar1[1], 1); request(lds + kSplitStage, m0, n0, z, 1); }
+        if (ngroup > 0) commit_a(lds, ar0[0], ar0[1]);
+    } else {
+        if (ngroup > 0) request(lds, m0, n0, z, 0);
+        if (ngroup > 1) request(lds + kSplitStage, m0, n0, z, 1);
+    }
     int cur = 0;
     bool first = true;
     ThreadAcc acc;
@@ -369,6 +421,26 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
         };
         // (the last group stands apart from the loop: the registers of the prefetched values are then
         // occupied in that copy of the arithmetic only)
+        if (AREG) {
+            // one group that is not the tile's last: slab g is used, slab g + 1 (register set `nset`,
+            // requested one group ago) is cut and written to its stage, slab g + 2 requested
+            auto body = [&](long g, floatx4 (&nset)[2], floatx4 (&fset)[2]) __attribute__((always_inline)) {
+                __builtin_amdgcn_s_waitcnt(0x0F75);               // vmcnt(5): all of slab g has landed
+                __syncthreads();
+                const int nxt2 = cur == 0 ? 2 : cur - 1, nxt1 = cur == 2 ? 0 : cur + 1;
+                commit_a(lds + nxt1 * kSplitStage, nset[0], nset[1]);     // (the compiler waits for nset's loads here)
+                if (g + 2 < ngroup) {
+                    fetch_a(fset[0], fset[1], g + 2);
+                    request(lds + nxt2 * kSplitStage, m0, n0, z, g + 2);
+                }
+                compute(lds + cur * kSplitStage);
+                cur = nxt1;
+            };
+            long g = 0;
+#pragma unroll 1
+            for (; g + 2 < ngroup; g += 2) { body(g, ar1, ar0); body(g + 1, ar0, ar1); }
+            if (g + 1 < ngroup) body(g, ar1, ar0);
+        } else {
 #pragma unroll 1
         for (long g = 0; g + 1 < ngroup; ++g) {
             if (g == 0 && !first) __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
@@ -379,6 +451,7 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
             else if (more)       request(lds + nxt2 * kSplitStage, m1, n1, z1, 0);
             compute(lds + cur * kSplitStage);
             cur = cur == 2 ? 0 : cur + 1;
+        }
         }
         float bias_c[2] = {0.f, 0.f};
         if (!PARTIAL && p.bias) {
@@ -730,7 +803,10 @@ int tao_linear_split_preferred(long M, long N, long K, long batch) {
     // parts fill the chip.
     if (M <= 0 || N <= 0 || K <= 0 || batch <= 0) return 0;
     const long tiles = ((M + tao::STILE - 1) / tao::STILE) * ((N + tao::STILE - 1) / tao::STILE) * batch;
-    return tiles * tao::split_k_parts(M, N, K, batch) >= tao::device_cus() && M >= 2 * tao::STILE && N >= 2 * tao::STILE && K >= 64;
+    // (a single column tile pays when its A operand can be split while it is loaded: a long reduction of whole groups)
+    const bool n_ok = N >= 2 * tao::STILE || (N >= tao::STILE && K % tao::SBK == 0 && K / tao::SBK > tao::kWalkMaxGroups &&
+                                              tao::split_k_parts(M, N, K, batch) < 2);
+    return tiles * tao::split_k_parts(M, N, K, batch) >= tao::device_cus() && M >= 2 * tao::STILE && n_ok && K >= 64;
 }
 
 }  // extern "C"
@@ -763,9 +839,12 @@ static void launch_split3(const float* src, long rows, long K, long ld, int tran
 // cleared: the check's partial results in ws are zero already (the caller's pre-pass cleared them).
 // tau / ldt / strideT: the caller's layout (validated by the caller); with a check they describe y_ref and
 // claimed as well when tau is stored.
+// Af != NULL: the A operand is split while it is loaded (AREG instantiations; the caller has
+// checked in_load_split_ok); A3 is then unused.
 static int split_core(const unsigned short* A3, const unsigned short* W3, const float* bias, float* tau,
                       long M, long N, long K, long ldt, long batch, long strideT, bool shared_w,
-                      const tao_fp_model& md, void* ws, void* stream, const SplitCheckHost* chk, bool cleared) {
+                      const tao_fp_model& md, void* ws, void* stream, const SplitCheckHost* chk, bool cleared,
+                      const float* Af = nullptr, long lda = 0, long strideA = 0) {
     const long Kp_ = K + (bias ? 1 : 0);
     const double c = gamma_up(Kp_, md);
     if (!(c == c)) return TAO_ERR_K_RANGE;
@@ -801,6 +880,7 @@ static int split_core(const unsigned short* A3, const unsigned short* W3, const 
 
     SplitArgs p;
     p.A3 = A3; p.W3 = W3; p.bias = bias; p.tau = tau;
+    p.Af = Af; p.lda = lda; p.strideA = strideA;
     p.M = M; p.N = N; p.Kp = Kp; p.ldt = ldt; p.strideT = strideT;
     p.batchA3 = (Kp / SBK) * blocksA * (kBlock / 2); p.batchW3 = shared_w ? 0 : (Kp / SBK) * blocksW * (kBlock / 2);
     p.tiles_n = (unsigned)tiles_n; p.tiles_m = (unsigned)tiles_m;
@@ -832,6 +912,12 @@ static int split_core(const unsigned short* A3, const unsigned short* W3, const 
                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
             if (r == hipSuccess)
                 r = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split<false, true>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            if (r == hipSuccess)
+                r = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split<false, false, false, true>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            if (r == hipSuccess)
+                r = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split<true, false, false, true>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
             return r;
         });
@@ -893,14 +979,16 @@ static int split_core(const unsigned short* A3, const unsigned short* W3, const 
         // cannot hide.)  The walk needs two groups per tile.
         const long groups = Kp / SBK;
         const unsigned cus = (unsigned)device_cus() & ~7u;
-        const bool walk = groups >= 2 && groups <= kWalkMaxGroups && cus >= 8 && (long)p.ntiles >= (long)kWalkMinTilesPerCu * cus;
+        const bool walk = !Af && groups >= 2 && groups <= kWalkMaxGroups && cus >= 8 && (long)p.ntiles >= (long)kWalkMinTilesPerCu * cus;
         // (one instantiation for both: with a workgroup per slot its walk ends after the first tile)
-        hipLaunchKernelGGL((absgemm_split<false, false, true>), dim3(walk ? cus : p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
+        if (Af) hipLaunchKernelGGL((absgemm_split<false, false, false, true>), dim3(p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
+        else    hipLaunchKernelGGL((absgemm_split<false, false, true>), dim3(walk ? cus : p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
         return then_check();
     }
     const int slots = kMaxCheckBlocks;                       // workgroup b adds to partial result b % 256
     if (!cleared) hipLaunchKernelGGL(zero_words, dim3(64), dim3(256), 0, st, cw.hist, (long)(check_workspace_bytes() / 4));
-    hipLaunchKernelGGL((absgemm_split<true>), dim3(p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
+    if (Af) hipLaunchKernelGGL((absgemm_split<true, false, false, true>), dim3(p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
+    else    hipLaunchKernelGGL((absgemm_split<true>), dim3(p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
     launch_profile_reduce(cw, slots, (unsigned long long)((__int128)M * N * batch), chk->out, st);
     return launch_status();
 }
@@ -978,16 +1066,24 @@ static int split_run(const float* A, const float* W, const float* bias, float* t
     void* rest = wsb + bytesA + bytesW;
     hipStream_t st = (hipStream_t)stream;
     bool cleared = false;
+    // An A operand that only one or two column tiles use is split while the product loads it (no
+    // pre-pass over it, no image): whole groups, 16-byte aligned rows, the reduction in one part, and
+    // not a launch whose short reduction is better served by the tile walk.
+    const bool in_load = K > 0 && K % SBK == 0 && N <= 2 * STILE && aligned(A, 16) && lda % 4 == 0 && strideA % 4 == 0 &&
+                         split_k_parts(M, N, K, batch) < 2 && K / SBK > kWalkMaxGroups &&
+                         (__int128)M * lda < ((__int128)1 << 40);
     if (K > 0) {
         // the operand pre-pass also clears the partial results of an epilogue check (no parts: those
         // are checked by the combining pass, which needs none)
         cleared = epilogue_check_without_parts(M, N, K, batch, md, chk);
         unsigned int* zp = nullptr;
         if (cleared) zp = carve_check_workspace(rest).hist;       // (no parts: the check's workspace comes first)
-        launch_split3(A, M, K, lda, 0, batch, strideA, A3, zp, (long)(check_workspace_bytes() / 4), st);
-        launch_split3(W, N, K, ldw, trans_w, shared_w ? 1 : batch, strideW, W3, nullptr, 0L, st);
+        const long zn = (long)(check_workspace_bytes() / 4);
+        if (!in_load) launch_split3(A, M, K, lda, 0, batch, strideA, A3, zp, zn, st);
+        launch_split3(W, N, K, ldw, trans_w, shared_w ? 1 : batch, strideW, W3, in_load ? zp : nullptr, in_load ? zn : 0L, st);
     }
-    return split_core(A3, W3, bias, tau, M, N, K, ldt, batch, strideT, shared_w, md, rest, stream, chk, cleared);
+    return split_core(A3, W3, bias, tau, M, N, K, ldt, batch, strideT, shared_w, md, rest, stream, chk, cleared,
+                      in_load ? A : nullptr, lda, strideA);
 }
 
 // The same on images the caller has prepared with tao_split_operand.

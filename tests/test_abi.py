@@ -159,7 +159,8 @@ def test_argument_validation_without_a_gpu(tao):
     assert L.tao_linear_split_workspace_bytes(2048, 1024, 256, 1, 1) == (256 // 32) * (16 + 8) * 24576 + 2 * 512     # too short to cut
     L.tao_linear_split_preferred.restype = ctypes.c_int
     assert L.tao_linear_split_preferred(2048, 1024, 4096, 1) == 1 and L.tao_linear_split_preferred(2048, 4096, 4096, 1) == 1
-    assert L.tao_linear_split_preferred(8192, 128, 2048, 8) == 0 and L.tao_linear_split_preferred(512, 1024, 1024, 1) == 0
+    assert L.tao_linear_split_preferred(8192, 128, 2048, 8) == 1 and L.tao_linear_split_preferred(512, 1024, 1024, 1) == 0
+    assert L.tao_linear_split_preferred(8192, 128, 1024, 8) == 0 and L.tao_linear_split_preferred(2048, 128, 2048, 8) == 0
     assert L.tao_bound_check_linear_in_epilogue(2048, 4096, 4096, 1) == 1 and L.tao_bound_check_linear_in_epilogue(8192, 2048, 128, 8) == 0
     assert L.tao_bound_check_linear_in_epilogue(64, 64, 1024, 1) == 0 and L.tao_bound_check_linear_in_epilogue(64, 64, 1025, 1) == 1
     big = ctypes.c_void_p(0x100000)

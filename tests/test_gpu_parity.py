@@ -61,6 +61,8 @@ def test_bf16_matrix_core_selftest(tao):
     # the larger run on request: 280 000 cases of the same generator
     assert tao.tao_selftest_matrix_core_bf16(cases=280000) == 7
     assert tao.tao_linear_split_preferred(2048, 4096, 4096) and not tao.tao_linear_split_preferred(2048, 128, 2048, 8)
+    # one column tile pays when A can be split while it is loaded (enough tiles, a long reduction of whole groups)
+    assert tao.tao_linear_split_preferred(8192, 128, 2048, 8) and not tao.tao_linear_split_preferred(8192, 128, 2040, 8)
     assert not tao.tao_linear_split_preferred(512, 768, 768)
 
 
@@ -757,6 +759,45 @@ def test_products_on_prepared_operand_images(tao, oracle_mod, M, N, K, bias, tra
     # the images are read only: a second product on them gives the same bits
     again = tao.tao_bound_linear_images(A_img, W_img, M, N, K, bias=b, batch=batch, shared_w=sh)
     assert torch.equal(again.view(torch.int32), got.view(torch.int32))
+
+
+@pytest.mark.parametrize("M,N,K,bias,trans_w,batch", [
+    (16640, 128, 1056, False, False, 1),     # 130 tiles, one column tile, 33 groups
+    (16700, 200, 1088, True, True, 1),       # ragged rows and columns, two column tiles, W stored K x N
+    (8900, 128, 1120, False, True, 2),       # batched (70 tiles each): the shape family of probabilities times values
+])
+def test_matmul_bound_with_the_a_operand_split_while_loaded(tao, oracle_mod, M, N, K, bias, trans_w, batch):
+    """Products whose A operand serves one or two column tiles skip the pre-pass over A: the kernel
+    cuts A into its pieces while loading it.  Same bits as the product on prepared images (which
+    cannot take that route), parity with the oracle, and the checked variant's profile."""
+    g = torch.Generator(device="cuda").manual_seed(M + N + K)
+    A = torch.randn((batch, M, K), generator=g, device="cuda")
+    W = torch.randn((batch, K, N) if trans_w else (batch, N, K), generator=g, device="cuda")
+    A[0, 5, 7] = 0.0; A[0, 6, :] = 0.0                       # zeros and a zero row
+    b = torch.randn((N,), generator=g, device="cuda") if bias else None
+    if batch == 1:
+        A, W = A[0], W[0]
+    got = tao.tao_bound_linear_split(A, W, b, trans_w=trans_w)
+    via_images = tao.tao_bound_linear_images(tao.tao_split_operand(A), tao.tao_split_operand(W, trans=trans_w), M, N, K,
+                                             bias=b, batch=batch, shared_w=False)
+    assert torch.equal(got.view(torch.int32).reshape(-1), via_images.view(torch.int32).reshape(-1))
+    # the oracle on a sample of rows (the whole product would take it minutes)
+    rows = torch.cat([torch.arange(0, 40), torch.arange(M - 140, M)])
+    Ar = A[..., rows, :]
+    t_or = oracle_mod.bound_linear(_np(Ar), _np(W), None if b is None else _np(b), trans_w=trans_w)
+    assert_bound_parity(_np(got[..., rows, :]), t_or, "in-load split %s" % ((M, N, K, batch),))
+    # checked in the epilogue (reductions beyond 1024): the profile of the two separate calls
+    Wnk = W.transpose(-1, -2) if trans_w else W
+    ref = A @ Wnk.transpose(-1, -2)
+    if b is not None:
+        ref = ref + b
+    ref = ref.contiguous()
+    claimed = tao_inputs.ulp_noise(g, ref, max_ulps=2)
+    claimed.view(-1)[11] += 1.0
+    one = tao.tao_bound_check_linear(A, W, b, ref, claimed, trans_w=trans_w)
+    two = tao.tao_check_and_profile(claimed, ref, got)
+    assert_profile_equal(one, two, "in-load split, checked in the epilogue")
+    assert one["violations"] >= 1
 
 
 def test_one_activation_image_feeds_several_projections(tao, oracle_mod):
