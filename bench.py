@@ -86,8 +86,20 @@ class PlannedOp:
             M, N = self.y_ref.shape[-2], self.y_ref.shape[-1]
             self.dims = (M, N, K, batch)
             self.conv = "conv" in op.attrs
+            if self.conv:
+                cv = op.attrs["conv"]
+                # the convolution on the BF16 matrix cores (patch matrix gathered and split while loaded),
+                # where the library serves the shape; else its FP32 implicit-GEMM kernel
+                self.split = use_split and tao.tao_conv2d_split_supported(cv["x"].shape, cv["w"].shape, 1, cv["padding"], 1)
+                self.fused = self.split and use_fused
+                if self.split:
+                    need = tao.lib().tao_conv2d_split_workspace_bytes(*cv["x"].shape, cv["w"].shape[0], cv["w"].shape[1], cv["w"].shape[2],
+                                                                      1, 1, cv["padding"], cv["padding"], 1, 1, 1)
+                    self.ws = torch.empty(max(int(need), 256), dtype=torch.uint8, device=A.device)
+                self.bound_events, self.check_events = [], []
+                return
             # the library's own rule picks the BF16-split or the FP32 matrix-core path per shape
-            self.split = (not self.conv) and use_split and tao.tao_linear_split_preferred(M, N, K, batch)
+            self.split = use_split and tao.tao_linear_split_preferred(M, N, K, batch)
             # ... and there the check runs in the matrix kernel's epilogue (tau is never stored)
             # (short reductions: the library itself would store the bound and run the streaming check; the
             # benchmark makes the two calls itself so that the matmul figure times the matmul kernels alone)
@@ -120,7 +132,7 @@ class PlannedOp:
     @property
     def path(self):
         if self.conv:
-            return "fp32 (implicit patch matrix)"
+            return ("bf16_split (patch matrix gathered while loaded)" + ("+check" if self.fused else "")) if self.split else "fp32 (implicit patch matrix)"
         if not self.split:
             return "fp32"
         return "bf16_split" + ("+prepared_w" if self.prepared else "") + ("+check" if self.fused else "")
@@ -129,7 +141,10 @@ class PlannedOp:
         tao, a, op = self.tao, self.op.args, self.op
         if self.kind == "linear" and self.conv:
             cv = op.attrs["conv"]
-            tao.tao_bound_conv2d(cv["x"], cv["w"], None, 1, cv["padding"], 1, out=self.tau.view(self.conv_shape()))
+            if self.split:
+                tao.tao_bound_conv2d_split(cv["x"], cv["w"], None, 1, cv["padding"], 1, out=self.tau.view(self.conv_shape()), ws=self.ws)
+            else:
+                tao.tao_bound_conv2d(cv["x"], cv["w"], None, 1, cv["padding"], 1, out=self.tau.view(self.conv_shape()))
         elif self.kind == "linear" and self.prepared:
             M, N, K, batch = self.dims
             if self.owns_image:
@@ -175,6 +190,11 @@ class PlannedOp:
         if self.kind != "linear":
             self.tao.tao_bound_check_act(_ACT[self.kind], a.get("x"), self.y_ref, self.claimed, x2=a.get("x2"),
                                          out=self.prof, ws=self.ws, readback=False)
+            return
+        if self.conv:
+            cv = op.attrs["conv"]
+            self.tao.tao_bound_check_conv2d(cv["x"], cv["w"], None, self.y_ref, self.claimed, 1, cv["padding"], 1,
+                                            out=self.prof, ws=self.ws, readback=False)
             return
         if self.prepared:
             M, N, K, batch = self.dims

@@ -250,6 +250,32 @@ int tao_bound_conv2d(const float *x, const float *w, const float *bias, float *t
                      long stride_h, long stride_w, long pad_h, long pad_w, long dil_h, long dil_w,
                      const tao_fp_model *model, void *stream);
 
+/* The same convolution bound on the BF16 matrix cores (the scheme of tao_bound_linear_split: three
+ * exact BF16 pieces per operand, same guarantee): the filters' image is written into ws by a small
+ * pre-pass, the implicit patch matrix is gathered from x and cut into its pieces while the product
+ * loads it, so no patch matrix and no image of it is ever stored.  Arguments as tao_bound_conv2d.
+ * Served when C is a multiple of 32, x is 16-byte aligned and the launch has enough 128 x 128 output
+ * tiles to keep the reduction in one part (tao_conv2d_split_supported returns 1; host only):
+ * TAO_ERR_SHAPE otherwise -- tao_bound_conv2d serves every shape.
+ * tao_bound_check_conv2d: the bound checked on the spot like tao_bound_check_linear (y_ref, claimed and
+ * the optional tau: [batch][OH][OW][Cout] contiguous; the result of tao_check_and_profile on the stored
+ * bound, field for field).  ws / ws_bytes: DEVICE scratch of tao_conv2d_split_workspace_bytes(...,
+ * with_check) bytes, 256-byte aligned. */
+int tao_conv2d_split_supported(long batch, long H, long W, long C, long Cout, long R, long S,
+                               long stride_h, long stride_w, long pad_h, long pad_w, long dil_h, long dil_w);
+size_t tao_conv2d_split_workspace_bytes(long batch, long H, long W, long C, long Cout, long R, long S,
+                                        long stride_h, long stride_w, long pad_h, long pad_w, long dil_h, long dil_w,
+                                        int with_check);
+int tao_bound_conv2d_split(const float *x, const float *w, const float *bias, float *tau,
+                           long batch, long H, long W, long C, long Cout, long R, long S,
+                           long stride_h, long stride_w, long pad_h, long pad_w, long dil_h, long dil_w,
+                           const tao_fp_model *model, void *ws, size_t ws_bytes, void *stream);
+int tao_bound_check_conv2d(const float *x, const float *w, const float *bias, const float *y_ref, const float *claimed,
+                           float *tau, long batch, long H, long W, long C, long Cout, long R, long S,
+                           long stride_h, long stride_w, long pad_h, long pad_w, long dil_h, long dil_w,
+                           double alpha, double eps_rel, const tao_fp_model *model, tao_profile *out,
+                           void *ws, size_t ws_bytes, void *stream);
+
 /* Softmax over the last dimension (Sec. 3.1 "Minimal example: softmax", closed
  * to second order).  x, y_ref, tau: [rows][cols] with row stride ld; y_ref is
  * the verifier's own binary32 softmax output.  Per row, with n = cols:

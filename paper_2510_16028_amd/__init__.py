@@ -95,7 +95,8 @@ EXPORTS = ["tao_default_model", "tao_gamma", "tao_bound_linear", "tao_bound_line
            "tao_linear_split_workspace_bytes", "tao_linear_split_preferred",
            "tao_split_image_bytes", "tao_split_operand", "tao_bound_linear_images", "tao_linear_images_workspace_bytes",
            "tao_bound_check_linear_images", "tao_check_linear_images_workspace_bytes", "tao_bound_check_linear_in_epilogue",
-           "tao_bound_check_linear", "tao_bound_check_linear_workspace_bytes", "tao_selftest_matrix_core_bf16", "tao_selftest_workspace_bytes", "tao_bound_conv2d", "tao_bound_softmax",
+           "tao_bound_check_linear", "tao_bound_check_linear_workspace_bytes", "tao_selftest_matrix_core_bf16", "tao_selftest_workspace_bytes", "tao_bound_conv2d",
+           "tao_conv2d_split_supported", "tao_conv2d_split_workspace_bytes", "tao_bound_conv2d_split", "tao_bound_check_conv2d", "tao_bound_softmax",
            "tao_bound_norm", "tao_bound_groupnorm", "tao_groupnorm_workspace_bytes", "tao_bound_act", "tao_bound_check_act", "tao_bound_rope", "tao_bound_check_rope", "tao_bound_check_norm", "tao_check_and_profile",
            "tao_check_and_profile_static",
            "tao_check_workspace_bytes", "tao_bound_check_softmax", "tao_profile_errors", "tao_profile_workspace_bytes",
@@ -149,6 +150,11 @@ def lib():
     L.tao_selftest_workspace_bytes.argtypes = [lg]
     L.tao_selftest_workspace_bytes.restype = ctypes.c_size_t
     L.tao_bound_conv2d.argtypes = [vp, vp, vp, vp] + [lg] * 13 + [mp, vp]
+    L.tao_conv2d_split_supported.argtypes = [lg] * 13
+    L.tao_conv2d_split_workspace_bytes.argtypes = [lg] * 13 + [ctypes.c_int]
+    L.tao_conv2d_split_workspace_bytes.restype = ctypes.c_size_t
+    L.tao_bound_conv2d_split.argtypes = [vp, vp, vp, vp] + [lg] * 13 + [mp, vp, ctypes.c_size_t, vp]
+    L.tao_bound_check_conv2d.argtypes = [vp, vp, vp, vp, vp, vp] + [lg] * 13 + [dbl, dbl, mp, vp, vp, ctypes.c_size_t, vp]
     L.tao_bound_softmax.argtypes = [vp, vp, vp, lg, lg, lg, mp, vp]
     L.tao_bound_norm.argtypes = [ctypes.c_int, vp, vp, vp, vp, dbl, vp, lg, lg, lg, mp, vp]
     L.tao_bound_groupnorm.argtypes = [vp, vp, vp, vp, dbl, vp, lg, lg, lg, lg, mp, vp, ctypes.c_size_t, vp]
@@ -445,6 +451,68 @@ def tao_bound_conv2d(x, w, bias=None, stride=1, padding=0, dilation=1, model=Non
                                 sh, sw, ph, pw, dh, dw, _mref(model), _stream())
     _check(rc, "tao_bound_conv2d")
     return out
+
+
+def _conv_args(x, w, bias, stride, padding, dilation):
+    x = _dev(x, "x"); w = _dev(w, "w"); bias = _dev(bias, "bias")
+    if x.dim() != 4 or w.dim() != 4 or not x.is_contiguous() or not w.is_contiguous():
+        raise ValueError("x [B, H, W, C] and w [Cout, R, S, C] must be contiguous 4-D tensors")
+    B, H, W, C = x.shape
+    Cout, R, S, C2 = w.shape
+    if C != C2:
+        raise ValueError("channel counts of x and w differ")
+    if bias is not None and (bias.dim() != 1 or bias.shape[0] != Cout or not bias.is_contiguous()):
+        raise ValueError("bias must be a contiguous [Cout] tensor")
+    sh, sw = _pair(stride, "stride"); ph, pw = _pair(padding, "padding"); dh, dw = _pair(dilation, "dilation")
+    if min(sh, sw, dh, dw) < 1 or min(ph, pw) < 0 or min(R, S) < 1:
+        raise ValueError("bad convolution geometry")
+    eh, ew = H + 2 * ph - dh * (R - 1) - 1, W + 2 * pw - dw * (S - 1) - 1
+    if eh < 0 or ew < 0:
+        raise ValueError("filter larger than the padded input")
+    geom = (B, H, W, C, Cout, R, S, sh, sw, ph, pw, dh, dw)
+    return x, w, bias, geom, (B, eh // sh + 1, ew // sw + 1, Cout)
+
+
+def tao_conv2d_split_supported(x_shape, w_shape, stride=1, padding=0, dilation=1):
+    """Whether tao_bound_conv2d_split / tao_bound_check_conv2d serve this convolution (else: tao_bound_conv2d)."""
+    B, H, W, C = x_shape; Cout, R, S, _ = w_shape
+    sh, sw = _pair(stride, "stride"); ph, pw = _pair(padding, "padding"); dh, dw = _pair(dilation, "dilation")
+    return bool(lib().tao_conv2d_split_supported(B, H, W, C, Cout, R, S, sh, sw, ph, pw, dh, dw))
+
+
+def tao_bound_conv2d_split(x, w, bias=None, stride=1, padding=0, dilation=1, model=None, out=None, ws=None):
+    """tao_bound_conv2d on the BF16 matrix cores (patch matrix gathered and split while loaded)."""
+    torch = _torch()
+    x, w, bias, geom, shape = _conv_args(x, w, bias, stride, padding, dilation)
+    if out is None:
+        out = torch.empty(shape, dtype=torch.float32, device=x.device)
+    elif tuple(out.shape) != shape or not out.is_contiguous() or out.dtype != torch.float32:
+        raise ValueError("out must be a contiguous float32 tensor of shape %s" % (shape,))
+    if ws is None:
+        ws = _scratch(x.device, lib().tao_conv2d_split_workspace_bytes(*geom, 0))
+    rc = lib().tao_bound_conv2d_split(_ptr(x), _ptr(w), _ptr(bias), _ptr(out), *geom, _mref(model), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "tao_bound_conv2d_split")
+    return out
+
+
+def tao_bound_check_conv2d(x, w, bias, y_ref, claimed, stride=1, padding=0, dilation=1, alpha=1.0, eps_rel=1e-12, model=None,
+                           tau_out=None, out=None, ws=None, readback=True):
+    """The convolution bound of tao_bound_conv2d_split checked on the spot against `claimed` and `y_ref`
+    ([B, OH, OW, Cout], contiguous); tau is stored only into `tau_out` if given."""
+    x, w, bias, geom, shape = _conv_args(x, w, bias, stride, padding, dilation)
+    y_ref = _dev(y_ref, "y_ref"); claimed = _dev(claimed, "claimed")
+    n = shape[0] * shape[1] * shape[2] * shape[3]
+    for t, nm in ((y_ref, "y_ref"), (claimed, "claimed"), (tau_out, "tau_out")):
+        if t is not None and (t.numel() != n or not t.is_contiguous()):
+            raise ValueError("%s must be contiguous with %d elements" % (nm, n))
+    if out is None:
+        out = new_profile_buffer(x.device)
+    if ws is None:
+        ws = _scratch(x.device, lib().tao_conv2d_split_workspace_bytes(*geom, 1))
+    rc = lib().tao_bound_check_conv2d(_ptr(x), _ptr(w), _ptr(bias), _ptr(y_ref), _ptr(claimed), _ptr(tau_out), *geom,
+                                      float(alpha), float(eps_rel), _mref(model), _ptr(out), _ptr(ws), ws.numel(), _stream())
+    _check(rc, "tao_bound_check_conv2d")
+    return read_profile(out) if readback else out
 
 
 def tao_bound_softmax(x, y_ref, model=None, out=None):

@@ -60,18 +60,31 @@ constexpr int kWalkMinTilesPerCu = 4;   // ... when a compute unit has at least 
 
 // ---- pre-pass: binary32 -> BF16 blocks [k / 32][row / 128][piece][row % 128][32] with the 16-byte units of
 // a row swizzled: the LDS image of a workgroup's slab; zero-padded to Kp columns ----------------------
-__device__ __forceinline__ void split_one(float v, unsigned& h, unsigned& m, unsigned& l) {
+// The three pieces of |v| as binary32 bit patterns whose upper halves are the BF16 pieces: hi by
+// masking, mid by masking the exact remainder, lo = the exact second remainder (at most 8 significant
+// bits), rounded up to a BF16 value by adding 0xffff before the upper half is taken (exact unless the
+// remainder lies below BF16's subnormal step: then up).  An infinite or NaN operand leaves pieces that
+// are infinite or NaN (inf - inf), so its outputs are never finite.
+__device__ __forceinline__ void split_bits(float v, unsigned& h, unsigned& m, unsigned& l) {
     const float a = fabsf(v);
-    const unsigned hb = __float_as_uint(a) & 0xffff0000u;
-    if (!(a < INFINITY)) {                       // infinity stays one piece; NaN stays NaN
-        h = (a != a) ? 0x7fc0u : 0x7f80u; m = 0; l = 0;
-        return;
+    h = __float_as_uint(a) & 0xffff0000u;
+    const float r1 = a - __uint_as_float(h);                           // exact
+    m = __float_as_uint(r1) & 0xffff0000u;
+    const float r2 = r1 - __uint_as_float(m);                          // exact
+    l = __float_as_uint(r2) + 0xffffu;
+}
+// Eight consecutive values -> the three 16-byte units of BF16 pieces (upper halves packed in pairs).
+__device__ __forceinline__ void split_pack8(const float (&v)[8], uintx4& H, uintx4& Mi, uintx4& L) {
+    unsigned h[8], m[8], l[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) split_bits(v[j], h[j], m[j], l[j]);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        // bytes 2, 3 of the even element, then bytes 2, 3 of the odd one
+        H[j] = __builtin_amdgcn_perm(h[2 * j + 1], h[2 * j], 0x07060302u);
+        Mi[j] = __builtin_amdgcn_perm(m[2 * j + 1], m[2 * j], 0x07060302u);
+        L[j] = __builtin_amdgcn_perm(l[2 * j + 1], l[2 * j], 0x07060302u);
     }
-    const float r1 = a - __uint_as_float(hb);                          // exact
-    const unsigned mb = __float_as_uint(r1) & 0xffff0000u;
-    const float r2 = r1 - __uint_as_float(mb);                         // exact, at most 8 significant bits
-    h = hb >> 16; m = mb >> 16;
-    l = (__float_as_uint(r2) + 0xffffu) >> 16;                         // exact unless below BF16's subnormal step: then up
 }
 
 // One thread per 8 consecutive k of one row.  TRANS: the source is [K][ld] with the row index
@@ -120,14 +133,8 @@ __global__ __launch_bounds__(256) void split3_bf16(const float* __restrict__ src
                 v[j] = (k < K) ? (TRANS ? s[k * ld + row] : s[row * ld + k]) : 0.f;
             }
         }
-        unsigned h[8], m[8], l[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) split_one(v[j], h[j], m[j], l[j]);
         uintx4 H, Mi, L;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            H[j] = h[2 * j] | (h[2 * j + 1] << 16); Mi[j] = m[2 * j] | (m[2 * j + 1] << 16); L[j] = l[2 * j] | (l[2 * j + 1] << 16);
-        }
+        split_pack8(v, H, Mi, L);
         const long r = row & (STILE - 1);
         const long unit = ((k0 & (SBK - 1)) >> 3) ^ ((r >> 2) & 3);
         const long o = ((k0 >> 5) * rblocks + (row >> 7)) * (kBlock / 2) + r * (SROW / 2) + unit * 8;
@@ -161,6 +168,10 @@ struct SplitArgs {
     // AREG instantiations: the binary32 A operand itself (row stride lda, batch stride strideA, in
     // elements); A3 is then unused
     const float* Af; long lda, strideA;
+    // CONV instantiations: Af is the channels-last input x[batch][H][W][C] of a convolution and row m of
+    // the implicit patch matrix is output pixel (image, oh, ow); a 32-wide k slab is 32 consecutive
+    // channels of one filter tap (C a multiple of 32)
+    int cH, cW, cC, cOW, cS, csh, csw, cph, cpw, cdh, cdw; unsigned cohow;
 };
 
 // check_one with the histogram layout of the CHECK instantiation below (16-bit counters, bin b in
@@ -193,8 +204,11 @@ __device__ __forceinline__ void check_one_packed(float c, float r, float t, doub
 // probabilities times values), where a pre-pass over A (10 bytes per element written and read back)
 // costs more than the product.  One tile per workgroup (no walk), whole groups only (K a multiple
 // of 32), 16-byte aligned rows: the host checks all of it.
-template <bool CHECK, bool PARTIAL = false, bool WALK = false, bool AREG = false>
+// CONV (with AREG): the A operand is the implicit patch matrix of a convolution, gathered from the
+// channels-last input while loading; taps in the zero padding contribute zeros.
+template <bool CHECK, bool PARTIAL = false, bool WALK = false, bool AREG = false, bool CONV = false>
 __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
+    static_assert(!CONV || AREG, "the patch matrix exists only as a gather");
     static_assert(!(CHECK && PARTIAL), "the parts are checked by split_combine");
     static_assert(!(WALK && (CHECK || PARTIAL)), "only the plain bound walks tiles");
     static_assert(!(AREG && (WALK || PARTIAL)), "the in-load split keeps one tile per workgroup and the whole reduction");
@@ -273,23 +287,46 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
     // first used (commit_a, one group after the request).  Rows beyond M read the last row instead
     // (their outputs are never stored).
     typedef float floatx4 __attribute__((ext_vector_type(4)));
-    auto fetch_a = [&](floatx4& lo4, floatx4& hi4, long g) __attribute__((always_inline)) {
-        long row = (long)m0 + (tid >> 2);
-        row = row < p.M ? row : p.M - 1;
-        const floatx4* src = reinterpret_cast<const floatx4*>(p.Af + (long)z * p.strideA + row * p.lda + (g0 + g) * SBK + (tid & 3) * 8);
-        lo4 = src[0];
-        hi4 = src[1];
-    };
-    auto commit_a = [&](char* stage, const floatx4& lo4, const floatx4& hi4) __attribute__((always_inline)) {
-        const float v[8] = {lo4[0], lo4[1], lo4[2], lo4[3], hi4[0], hi4[1], hi4[2], hi4[3]};
-        unsigned hh[8], mm[8], ll[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) split_one(v[j], hh[j], mm[j], ll[j]);
-        uintx4 H, Mi, L;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            H[j] = hh[2 * j] | (hh[2 * j + 1] << 16); Mi[j] = mm[2 * j] | (mm[2 * j + 1] << 16); L[j] = ll[2 * j] | (ll[2 * j + 1] << 16);
+    // CONV: input coordinates of filter tap (0, 0) for this thread's patch row and the offset of that
+    // pixel's first channel (a row beyond M never has a tap inside)
+    int cv_ih0 = 0, cv_iw0 = 0; long cv_base = 0;
+    if (CONV) {
+        const long m = (long)m0 + (tid >> 2);
+        const unsigned mm = m < p.M ? (unsigned)m : 0u;
+        const unsigned img = mm / p.cohow, rem = mm - img * p.cohow;
+        const unsigned oh = rem / (unsigned)p.cOW, ow = rem - oh * (unsigned)p.cOW;
+        cv_ih0 = (int)oh * p.csh - p.cph; cv_iw0 = (int)ow * p.csw - p.cpw;
+        cv_base = (((long)img * p.cH + cv_ih0) * p.cW + cv_iw0) * p.cC;
+        if (m >= p.M) cv_ih0 = -(1 << 30);
+    }
+    // `inside`: CONV only, whether the slab's tap lies inside the input for this row (else the loaded
+    // values are replaced by zeros when the slab is cut)
+    auto fetch_a = [&](floatx4& lo4, floatx4& hi4, bool& inside, long g) __attribute__((always_inline)) {
+        const float* src;
+        if (CONV) {
+            const unsigned k0 = (unsigned)(g * SBK);
+            const unsigned tap = k0 / (unsigned)p.cC, c0 = k0 - tap * (unsigned)p.cC;
+            const unsigned r = tap / (unsigned)p.cS, sx = tap - r * (unsigned)p.cS;
+            const int dr = (int)r * p.cdh, ds = (int)sx * p.cdw;
+            inside = (unsigned)(cv_ih0 + dr) < (unsigned)p.cH && (unsigned)(cv_iw0 + ds) < (unsigned)p.cW;
+            src = p.Af + (inside ? cv_base + ((long)dr * p.cW + ds) * p.cC + c0 : 0L) + (tid & 3) * 8;
+        } else {
+            inside = true;
+            long row = (long)m0 + (tid >> 2);
+            row = row < p.M ? row : p.M - 1;
+            src = p.Af + (long)z * p.strideA + row * p.lda + (g0 + g) * SBK + (tid & 3) * 8;
         }
+        lo4 = reinterpret_cast<const floatx4*>(src)[0];
+        hi4 = reinterpret_cast<const floatx4*>(src)[1];
+    };
+    auto commit_a = [&](char* stage, const floatx4& lo4, const floatx4& hi4, bool inside) __attribute__((always_inline)) {
+        float v[8] = {lo4[0], lo4[1], lo4[2], lo4[3], hi4[0], hi4[1], hi4[2], hi4[3]};
+        if (CONV) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = inside ? v[j] : 0.f;
+        }
+        uintx4 H, Mi, L;
+        split_pack8(v, H, Mi, L);
         const int r = tid >> 2;
         const int o = r * SROW + (((tid & 3) ^ ((r >> 2) & 3)) * 16);
         *reinterpret_cast<uintx4*>(stage + o) = H;
@@ -378,10 +415,11 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
     floatx4 ar0[2], ar1[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) { ar0[i] = floatx4{0.f, 0.f, 0.f, 0.f}; ar1[i] = ar0[i]; }
+    bool in0 = true, in1 = true;
     if (AREG) {
-        if (ngroup > 0) { fetch_a(ar0[0], ar0[1], 0); request(lds, m0, n0, z, 0); }
-        if (ngroup > 1) { fetch_a(ar1[0], ar1[1], 1); request(lds + kSplitStage, m0, n0, z, 1); }
-        if (ngroup > 0) commit_a(lds, ar0[0], ar0[1]);
+        if (ngroup > 0) { fetch_a(ar0[0], ar0[1], in0, 0); request(lds, m0, n0, z, 0); }
+        if (ngroup > 1) { fetch_a(ar1[0], ar1[1], in1, 1); request(lds + kSplitStage, m0, n0, z, 1); }
+        if (ngroup > 0) commit_a(lds, ar0[0], ar0[1], in0);
     } else {
         if (ngroup > 0) request(lds, m0, n0, z, 0);
         if (ngroup > 1) request(lds + kSplitStage, m0, n0, z, 1);
@@ -424,13 +462,13 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
         if (AREG) {
             // one group that is not the tile's last: slab g is used, slab g + 1 (register set `nset`,
             // requested one group ago) is cut and written to its stage, slab g + 2 requested
-            auto body = [&](long g, floatx4 (&nset)[2], floatx4 (&fset)[2]) __attribute__((always_inline)) {
+            auto body = [&](long g, floatx4 (&nset)[2], bool& nin, floatx4 (&fset)[2], bool& fin) __attribute__((always_inline)) {
                 __builtin_amdgcn_s_waitcnt(0x0F75);               // vmcnt(5): all of slab g has landed
                 __syncthreads();
                 const int nxt2 = cur == 0 ? 2 : cur - 1, nxt1 = cur == 2 ? 0 : cur + 1;
-                commit_a(lds + nxt1 * kSplitStage, nset[0], nset[1]);     // (the compiler waits for nset's loads here)
+                commit_a(lds + nxt1 * kSplitStage, nset[0], nset[1], nin);     // (the compiler waits for nset's loads here)
                 if (g + 2 < ngroup) {
-                    fetch_a(fset[0], fset[1], g + 2);
+                    fetch_a(fset[0], fset[1], fin, g + 2);
                     request(lds + nxt2 * kSplitStage, m0, n0, z, g + 2);
                 }
                 compute(lds + cur * kSplitStage);
@@ -438,8 +476,8 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
             };
             long g = 0;
 #pragma unroll 1
-            for (; g + 2 < ngroup; g += 2) { body(g, ar1, ar0); body(g + 1, ar0, ar1); }
-            if (g + 1 < ngroup) body(g, ar1, ar0);
+            for (; g + 2 < ngroup; g += 2) { body(g, ar1, in1, ar0, in0); body(g + 1, ar0, in0, ar1, in1); }
+            if (g + 1 < ngroup) body(g, ar1, in1, ar0, in0);
         } else {
 #pragma unroll 1
         for (long g = 0; g + 1 < ngroup; ++g) {
@@ -841,10 +879,12 @@ static void launch_split3(const float* src, long rows, long K, long ld, int tran
 // claimed as well when tau is stored.
 // Af != NULL: the A operand is split while it is loaded (AREG instantiations; the caller has
 // checked in_load_split_ok); A3 is then unused.
+struct ConvHost { int H, W, C, OW, S, sh, sw, ph, pw, dh, dw; unsigned ohow; };
+// cv != NULL (with Af): Af is a convolution's channels-last input and A its implicit patch matrix.
 static int split_core(const unsigned short* A3, const unsigned short* W3, const float* bias, float* tau,
                       long M, long N, long K, long ldt, long batch, long strideT, bool shared_w,
                       const tao_fp_model& md, void* ws, void* stream, const SplitCheckHost* chk, bool cleared,
-                      const float* Af = nullptr, long lda = 0, long strideA = 0) {
+                      const float* Af = nullptr, long lda = 0, long strideA = 0, const ConvHost* cv = nullptr) {
     const long Kp_ = K + (bias ? 1 : 0);
     const double c = gamma_up(Kp_, md);
     if (!(c == c)) return TAO_ERR_K_RANGE;
@@ -881,6 +921,11 @@ static int split_core(const unsigned short* A3, const unsigned short* W3, const 
     SplitArgs p;
     p.A3 = A3; p.W3 = W3; p.bias = bias; p.tau = tau;
     p.Af = Af; p.lda = lda; p.strideA = strideA;
+    p.cH = p.cW = p.cC = p.cOW = p.cS = p.csh = p.csw = p.cph = p.cpw = p.cdh = p.cdw = 0; p.cohow = 1;
+    if (cv) {
+        p.cH = cv->H; p.cW = cv->W; p.cC = cv->C; p.cOW = cv->OW; p.cS = cv->S; p.csh = cv->sh; p.csw = cv->sw;
+        p.cph = cv->ph; p.cpw = cv->pw; p.cdh = cv->dh; p.cdw = cv->dw; p.cohow = cv->ohow;
+    }
     p.M = M; p.N = N; p.Kp = Kp; p.ldt = ldt; p.strideT = strideT;
     p.batchA3 = (Kp / SBK) * blocksA * (kBlock / 2); p.batchW3 = shared_w ? 0 : (Kp / SBK) * blocksW * (kBlock / 2);
     p.tiles_n = (unsigned)tiles_n; p.tiles_m = (unsigned)tiles_m;
@@ -918,6 +963,12 @@ static int split_core(const unsigned short* A3, const unsigned short* W3, const 
                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
             if (r == hipSuccess)
                 r = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split<true, false, false, true>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            if (r == hipSuccess)
+                r = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split<false, false, false, true, true>),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+            if (r == hipSuccess)
+                r = hipFuncSetAttribute(reinterpret_cast<const void*>(&absgemm_split<true, false, false, true, true>),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
             return r;
         });
@@ -981,14 +1032,16 @@ static int split_core(const unsigned short* A3, const unsigned short* W3, const 
         const unsigned cus = (unsigned)device_cus() & ~7u;
         const bool walk = !Af && groups >= 2 && groups <= kWalkMaxGroups && cus >= 8 && (long)p.ntiles >= (long)kWalkMinTilesPerCu * cus;
         // (one instantiation for both: with a workgroup per slot its walk ends after the first tile)
-        if (Af) hipLaunchKernelGGL((absgemm_split<false, false, false, true>), dim3(p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
-        else    hipLaunchKernelGGL((absgemm_split<false, false, true>), dim3(walk ? cus : p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
+        if (Af && cv) hipLaunchKernelGGL((absgemm_split<false, false, false, true, true>), dim3(p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
+        else if (Af)  hipLaunchKernelGGL((absgemm_split<false, false, false, true>), dim3(p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
+        else          hipLaunchKernelGGL((absgemm_split<false, false, true>), dim3(walk ? cus : p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
         return then_check();
     }
     const int slots = kMaxCheckBlocks;                       // workgroup b adds to partial result b % 256
     if (!cleared) hipLaunchKernelGGL(zero_words, dim3(64), dim3(256), 0, st, cw.hist, (long)(check_workspace_bytes() / 4));
-    if (Af) hipLaunchKernelGGL((absgemm_split<true, false, false, true>), dim3(p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
-    else    hipLaunchKernelGGL((absgemm_split<true>), dim3(p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
+    if (Af && cv) hipLaunchKernelGGL((absgemm_split<true, false, false, true, true>), dim3(p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
+    else if (Af)  hipLaunchKernelGGL((absgemm_split<true, false, false, true>), dim3(p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
+    else          hipLaunchKernelGGL((absgemm_split<true>), dim3(p.ntiles), dim3(kSplitThreads), lds_bytes, st, p);
     launch_profile_reduce(cw, slots, (unsigned long long)((__int128)M * N * batch), chk->out, st);
     return launch_status();
 }
@@ -1139,6 +1192,91 @@ int tao_bound_check_linear_images(const void* A_image, const void* W_image, cons
                                   tao_profile* out, void* ws, size_t ws_bytes, void* stream) {
     tao::SplitCheckHost chk = {claimed, y_ref, ldy, strideY, alpha, eps_rel, out};
     return tao::images_run(A_image, W_image, bias, tau, M, N, K, ldy, batch, strideY, shared_w, model, ws, ws_bytes, stream, &chk);
+}
+
+}  // extern "C"
+
+namespace tao {
+// The convolution bound on the BF16 matrix cores: the filters' image is written into ws by the
+// pre-pass, the patch matrix is gathered and cut into pieces while the product loads it.
+static bool conv_split_ok(long M, long N, long K, long C, long batch_hwc, const float* x) {
+    // whole 32-channel slabs inside one tap, the reduction in one part (enough tiles), 16-byte aligned
+    // pixels, 32-bit pixel arithmetic in the kernel
+    return C % SBK == 0 && K / SBK >= 1 && split_k_parts(M, N, K, 1) < 2 && aligned(x, 16) && batch_hwc < (1L << 40);
+}
+static int conv_split_run(const float* x, const float* w, const float* bias, float* tau,
+                          long batch, long H, long W, long C, long Cout, long R, long S,
+                          long stride_h, long stride_w, long pad_h, long pad_w, long dil_h, long dil_w,
+                          const tao_fp_model* model, void* ws, size_t ws_bytes, void* stream, const SplitCheckHost* chk) {
+    tao_fp_model md;
+    int rc = resolve_model(model, &md);
+    if (rc != TAO_OK) return rc;
+    long OH = 0, OW = 0, M = 0, K = 0;
+    rc = conv_geometry(batch, H, W, C, Cout, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, &OH, &OW, &M, &K);
+    if (rc != TAO_OK) return rc;
+    const long N = Cout;
+    rc = split_validate(bias, tau, M, N, K, N, 1, M * N, md, chk);
+    if (rc != TAO_OK) return rc;
+    const bool empty = M == 0 || N == 0;
+    if (!empty && !conv_split_ok(M, N, K, C, batch * H * W * C, x)) return TAO_ERR_SHAPE;
+    const size_t bytesW = empty ? 0 : image_bytes(N, K, 1);
+    const size_t need = bytesW + core_workspace_bytes(M, N, K, 1, chk != nullptr);
+    if (need > 0 && (!ws || !aligned(ws, 256) || ws_bytes < need)) return TAO_ERR_WORKSPACE;
+    if (empty) return split_empty(chk, ws, stream);
+    if ((!chk && !tau) || !x || !w) return TAO_ERR_NULL;
+    if (chk && (!chk->claimed || !chk->ref)) return TAO_ERR_NULL;
+    if (!aligned(w, 4) || !aligned(bias, 4) || !aligned(tau, 4)) return TAO_ERR_ALIGN;
+    if (chk && (!aligned(chk->claimed, 4) || !aligned(chk->ref, 4))) return TAO_ERR_ALIGN;
+    char* wsb = static_cast<char*>(ws);
+    unsigned short* W3 = reinterpret_cast<unsigned short*>(wsb);
+    void* rest = wsb + bytesW;
+    const bool cleared = epilogue_check_without_parts(M, N, K, 1, md, chk);
+    launch_split3(w, N, K, K, 0, 1, 0, W3, cleared ? carve_check_workspace(rest).hist : nullptr,
+                  cleared ? (long)(check_workspace_bytes() / 4) : 0L, (hipStream_t)stream);
+    ConvHost cv;
+    cv.H = (int)H; cv.W = (int)W; cv.C = (int)C; cv.OW = (int)OW; cv.S = (int)S;
+    cv.sh = (int)stride_h; cv.sw = (int)stride_w; cv.ph = (int)pad_h; cv.pw = (int)pad_w; cv.dh = (int)dil_h; cv.dw = (int)dil_w;
+    cv.ohow = (unsigned)(OH * OW);
+    return split_core(nullptr, W3, bias, tau, M, N, K, N, 1, M * N, true, md, rest, stream, chk, cleared, x, K, 0, &cv);
+}
+}  // namespace tao
+
+extern "C" {
+
+int tao_conv2d_split_supported(long batch, long H, long W, long C, long Cout, long R, long S,
+                               long stride_h, long stride_w, long pad_h, long pad_w, long dil_h, long dil_w) {
+    long OH = 0, OW = 0, M = 0, K = 0;
+    if (tao::conv_geometry(batch, H, W, C, Cout, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, &OH, &OW, &M, &K) != TAO_OK) return 0;
+    if (M == 0 || Cout == 0) return 1;
+    return tao::conv_split_ok(M, Cout, K, C, batch * H * W * C, nullptr) ? 1 : 0;
+}
+
+size_t tao_conv2d_split_workspace_bytes(long batch, long H, long W, long C, long Cout, long R, long S,
+                                        long stride_h, long stride_w, long pad_h, long pad_w, long dil_h, long dil_w,
+                                        int with_check) {
+    long OH = 0, OW = 0, M = 0, K = 0;
+    if (tao::conv_geometry(batch, H, W, C, Cout, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w, &OH, &OW, &M, &K) != TAO_OK) return 0;
+    const size_t img = (M == 0 || Cout == 0) ? 0 : tao::image_bytes(Cout, K, 1);
+    return img + tao::core_workspace_bytes(M, Cout, K, 1, with_check != 0);
+}
+
+int tao_bound_conv2d_split(const float* x, const float* w, const float* bias, float* tau,
+                           long batch, long H, long W, long C, long Cout, long R, long S,
+                           long stride_h, long stride_w, long pad_h, long pad_w, long dil_h, long dil_w,
+                           const tao_fp_model* model, void* ws, size_t ws_bytes, void* stream) {
+    return tao::conv_split_run(x, w, bias, tau, batch, H, W, C, Cout, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
+                               model, ws, ws_bytes, stream, nullptr);
+}
+
+int tao_bound_check_conv2d(const float* x, const float* w, const float* bias, const float* y_ref, const float* claimed,
+                           float* tau, long batch, long H, long W, long C, long Cout, long R, long S,
+                           long stride_h, long stride_w, long pad_h, long pad_w, long dil_h, long dil_w,
+                           double alpha, double eps_rel, const tao_fp_model* model, tao_profile* out,
+                           void* ws, size_t ws_bytes, void* stream) {
+    // (y_ref, claimed and tau are [batch][OH][OW][Cout] contiguous: rows of Cout, one batch entry in matrix terms)
+    tao::SplitCheckHost chk = {claimed, y_ref, Cout, 0, alpha, eps_rel, out};
+    return tao::conv_split_run(x, w, bias, tau, batch, H, W, C, Cout, R, S, stride_h, stride_w, pad_h, pad_w, dil_h, dil_w,
+                               model, ws, ws_bytes, stream, &chk);
 }
 
 int tao_bound_linear_split(const float* A, const float* W, const float* bias, float* tau,

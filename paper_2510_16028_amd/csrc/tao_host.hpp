@@ -43,6 +43,27 @@ int resolve_model(const tao_fp_model* m, tao_fp_model* out);
 double gamma_up(long k, const tao_fp_model& m);            // NaN when undefined
 inline double widen(double v) { return v * (1.0 + 0x1p-49); }   // for v >= 0
 
+// Shape checks of a 2-D convolution (channels-last input [batch][H][W][C], filters [Cout][R][S][C]) and the
+// shape of its implicit patch-matrix product: M = batch OH OW rows, K = R S C columns.
+inline int conv_geometry(long batch, long H, long W, long C, long Cout, long R, long S,
+                         long stride_h, long stride_w, long pad_h, long pad_w, long dil_h, long dil_w,
+                         long* OH, long* OW, long* M, long* K) {
+    if (batch < 0 || H < 0 || W < 0 || C < 0 || Cout < 0 || R < 1 || S < 1) return TAO_ERR_SHAPE;
+    if (stride_h < 1 || stride_w < 1 || dil_h < 1 || dil_w < 1 || pad_h < 0 || pad_w < 0) return TAO_ERR_SHAPE;
+    const long lim = 1L << 28;       // each extent, so that coordinate arithmetic stays in 32 bits
+    if (H >= lim || W >= lim || C >= lim || R >= lim || S >= lim || Cout >= lim || batch >= lim ||
+        stride_h >= lim || stride_w >= lim || dil_h >= lim || dil_w >= lim || pad_h >= lim || pad_w >= lim) return TAO_ERR_SHAPE;
+    if (dil_h * (R - 1) >= lim || dil_w * (S - 1) >= lim) return TAO_ERR_SHAPE;
+    const long eh = H + 2 * pad_h - dil_h * (R - 1) - 1, ew = W + 2 * pad_w - dil_w * (S - 1) - 1;
+    if (eh < 0 || ew < 0) return TAO_ERR_SHAPE;          // filter larger than the padded input
+    *OH = eh / stride_h + 1; *OW = ew / stride_w + 1;
+    const __int128 M128 = (__int128)batch * *OH * *OW, K128 = (__int128)R * S * C;
+    if (M128 >= (1L << 31) || K128 >= (1L << 31) || *OH * *OW >= (1L << 31)) return TAO_ERR_SHAPE;
+    *M = (long)M128; *K = (long)K128;
+    if ((__int128)batch * H * W * C >= ((__int128)1 << 61) || (__int128)*M * Cout >= ((__int128)1 << 61)) return TAO_ERR_SHAPE;
+    return TAO_OK;
+}
+
 // Every kernel evaluates its formula in round-to-nearest binary64; a margin that dominates the
 // accumulated binary64 rounding keeps the emitted bound at or above the real-number value.  The
 // matrix kernel multiplies by this factor and rounds up exactly (up32); the streaming kernels fold

@@ -296,6 +296,47 @@ def test_conv2d_random_geometries(tao, oracle_mod):
         assert_bound_parity(_np(t_gpu), t_or, what)
 
 
+@pytest.mark.parametrize("B,H,W,C,Cout,R,S,stride,pad,dil", [
+    (20, 40, 40, 32, 128, 3, 3, (1, 1), (1, 1), (1, 1)),      # 250 tiles of one column tile
+    (33, 33, 35, 64, 200, 3, 3, (1, 1), (1, 1), (1, 1)),      # ragged rows and columns, two column tiles
+    (40, 29, 31, 32, 130, 5, 3, (1, 2), (3, 0), (2, 1)),      # strides, asymmetric padding, dilation: taps in the padding
+    (36, 30, 30, 96, 64, 1, 1, (1, 1), (0, 0), (1, 1)),       # 1 x 1: a plain product with three groups
+])
+def test_conv2d_bound_on_the_bf16_matrix_cores(tao, oracle_mod, B, H, W, C, Cout, R, S, stride, pad, dil):
+    """tao_bound_conv2d_split / tao_bound_check_conv2d: parity with the oracle's direct loop (on a few
+    images), the bits of the BF16-split product on the explicit patch matrix, and the checked variant's
+    profile against the two separate calls."""
+    assert tao.tao_conv2d_split_supported((B, H, W, C), (Cout, R, S, C), stride, pad, dil)
+    g = torch.Generator(device="cuda").manual_seed(B * 31 + C + Cout)
+    x = torch.randn((B, H, W, C), generator=g, device="cuda").abs()
+    w = torch.randn((Cout, R, S, C), generator=g, device="cuda") * 0.05
+    b = torch.randn((Cout,), generator=g, device="cuda")
+    tau = tao.tao_bound_conv2d_split(x, w, b, stride, pad, dil)
+    for img in (0, B - 1):
+        t_or = oracle_mod.bound_conv2d(_np(x[img:img + 1]), _np(w), _np(b), stride, pad, dil)
+        assert_bound_parity(_np(tau[img:img + 1]), t_or, "conv on BF16 cores, image %d" % img)
+    # the explicit patch matrix (columns ordered (r, s, c) like the filters) through the matrix entry point
+    xp = torch.nn.functional.pad(x.permute(0, 3, 1, 2), (pad[1], pad[1], pad[0], pad[0]))
+    cols = torch.nn.functional.unfold(xp, kernel_size=(R, S), dilation=dil, stride=stride)          # [B, C*R*S, L], (c, r, s) order
+    L = cols.shape[-1]
+    A = cols.reshape(B, C, R * S, L).permute(0, 3, 2, 1).reshape(B * L, R * S * C).contiguous()
+    via_matrix = tao.tao_bound_linear_split(A, w.reshape(Cout, -1), b)
+    assert torch.equal(via_matrix.view(torch.int32).reshape(-1), tau.view(torch.int32).reshape(-1))
+    # checked on the spot
+    ref = (A @ w.reshape(Cout, -1).t() + b).contiguous()
+    claimed = tao_inputs.ulp_noise(g, ref, max_ulps=2)
+    claimed.view(-1)[5] += 1.0
+    tau2 = torch.empty_like(tau)
+    one = tao.tao_bound_check_conv2d(x, w, b, ref, claimed, stride, pad, dil, tau_out=tau2)
+    assert torch.equal(tau2.view(torch.int32), tau.view(torch.int32))
+    assert_profile_equal(one, tao.tao_check_and_profile(claimed.reshape(-1), ref.reshape(-1), tau.reshape(-1)), "conv checked on the spot")
+    assert one["violations"] >= 1
+    # shapes it does not serve are refused, not mangled
+    with pytest.raises(tao.TaoError) as ei:
+        tao.tao_bound_conv2d_split(x[:, :, :, :24].contiguous(), w[:, :, :, :24].contiguous(), b, stride, pad, dil)
+    assert ei.value.status == tao.ERR_SHAPE
+
+
 def test_linear_unaligned_views_and_modes(tao, oracle_mod):
     g = torch.Generator().manual_seed(77)
     Abig = torch.randn((150, 203), generator=g).cuda()
