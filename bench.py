@@ -239,6 +239,36 @@ def _event_time(torch, fn, reps, warm=2):
     return sum(_ms(ev)) / reps
 
 
+def shader_clock_under(torch, fn, samples=3):
+    """The shader clock (MHz) rocm-smi reports while `fn` keeps the GPU busy, or None if it cannot be read.
+    (The matrix cores' peaks are quoted at 2.4 GHz; the chip lowers its clock under dense BF16 MFMA work.)
+    rocm-smi takes a few hundred milliseconds to start: launches are queued, a few at a time, until it has
+    answered, so the clock it reads is the one under load."""
+    import re, subprocess
+    try:
+        seen = []
+        for _ in range(samples):
+            for _ in range(4):
+                fn()
+            torch.cuda.synchronize()
+            proc = subprocess.Popen(["rocm-smi", "--showclocks"], stdout=subprocess.PIPE, stderr=subprocess.DEVNULL, text=True)
+            t0 = time.perf_counter()
+            while proc.poll() is None and time.perf_counter() - t0 < 10.0:
+                for _ in range(4):
+                    fn()
+                torch.cuda.synchronize()
+            if proc.poll() is None:
+                proc.kill()
+                proc.communicate()
+                return None
+            m = re.search(r"sclk clock level: \d+: \((\d+)Mhz\)", proc.communicate()[0])
+            if m:
+                seen.append(int(m.group(1)))
+        return (sum(seen) / len(seen)) if seen else None
+    except Exception:
+        return None
+
+
 def make_plan(torch, tao, ops, args):
     images = {}
     return [PlannedOp(tao, torch, op, images, use_split=not args.fp32_only, use_fused=not args.no_fused_check,
@@ -418,6 +448,9 @@ def main():
                          "(side measurement; used for the committed kernel trace)")
     ap.add_argument("--only-config", type=int, default=0,
                     help="only time this configuration (1, 2 or 4) and exit (side measurement; used for the committed kernel traces)")
+    ap.add_argument("--only-product", type=int, default=0,
+                    help="only time the BF16-split product of an n x n x n problem on prepared operand images and exit "
+                         "(side measurement; used for the committed counter summary)")
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run three 1 GiB element-wise copy kernels (reference kernel for scaling FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
@@ -436,6 +469,17 @@ def main():
 
     if args.projection_elems > 0:
         print(json.dumps(projection_only(torch, tao, tao_inputs, dev, args.projection_elems, args.steps, args.warmup)))
+        return
+
+    if args.only_product > 0:
+        n = args.only_product
+        g, A, W = tao_inputs.config5_operands(dev, size=n)
+        a_img, w_img = tao.tao_split_operand(A), tao.tao_split_operand(W)
+        out = torch.empty((n, n), device=dev)
+        ms = _event_time(torch, lambda: tao.tao_bound_linear_images(a_img, w_img, n, n, n, out=out), args.steps, args.warmup)
+        tf = 2.0 * n ** 3 / (ms * 1e-3) / 1e12
+        print(json.dumps({"workload": "BF16-split product %d^3 on prepared operand images" % n, "ms": ms, "TFLOP/s": tf,
+                          "issued_frac_of_bf16_peak": 8.0 * tf / PEAK_BF16_MFMA_TFLOPS}))
         return
 
     other = {1: ("config 1: one 64x256 @ 256x128 linear and a 64x128 softmax", lambda: tao_inputs.config1(dev)),
@@ -546,6 +590,13 @@ def main():
         tf = 2.0 * 8192 ** 3 / (ms * 1e-3) / 1e12
         kernels["linear_8192^3_bf16_split_prepared_operands"] = {"ms": ms, "TFLOP/s": tf, "frac_mfma": tf / PEAK_FP32_MFMA_TFLOPS,
                                                                  "issued_frac_of_bf16_peak": 8.0 * tf / PEAK_BF16_MFMA_TFLOPS}
+        # the clock the chip holds under either path's kernel (the peaks assume 2400 MHz)
+        mhz = shader_clock_under(torch, lambda: tao.tao_bound_linear_images(a_img, w_img, 8192, 8192, 8192, out=out))
+        kernels["linear_8192^3_bf16_split_prepared_operands"]["sclk_mhz"] = mhz
+        if mhz:
+            kernels["linear_8192^3_bf16_split_prepared_operands"]["issued_frac_of_bf16_peak_at_that_clock"] = \
+                8.0 * tf / (PEAK_BF16_MFMA_TFLOPS * mhz / 2400.0)
+        kernels["linear_8192^3"]["sclk_mhz"] = shader_clock_under(torch, lambda: tao.tao_bound_linear(A, W, out=out))
         del ws5, a_img, w_img
         tao.tao_bound_linear(A, W, out=out)      # the stored bound of the check below: the FP32 path's
         ref = A @ W.t()
