@@ -141,8 +141,19 @@ def test_config3_matmuls_through_the_bf16_split_path(tao, oracle_mod):
         print("   sampled %d rows: max tau_gpu/tau_oracle - 1 = %.3e" % (len(rows), worst), flush=True)
         ref = gpu_tau(tao, op)
         assert float((tau / ref - 1).abs().max()) <= 1e-6
-        del tau, ref
-    assert taken >= 5
+        del ref
+        # as bench.py runs a projection: the weight's operand image prepared once, the activation's image
+        # shared; the bound and the profile are those of the calls above, bit for bit
+        if A.dim() == 2 and not op.attrs.get("trans_w", 0):
+            a_img, w_img = tao.tao_split_operand(A), tao.tao_split_operand(W)
+            via_images = tao.tao_bound_linear_images(a_img, w_img, M, N, K, bias=op.args.get("bias"))
+            assert torch.equal(via_images, tau), op.name + " (prepared images)"
+            fused_images = tao.tao_bound_check_linear_images(a_img, w_img, M, N, K, op.y_ref.contiguous(),
+                                                             op.claimed.contiguous(), bias=op.args.get("bias"))
+            assert_profile_equal(fused_images, p, op.name + " (prepared images, check in the epilogue)")
+            del a_img, w_img, via_images
+        del tau
+    assert taken >= 9
 
 
 def test_config2_bert_block_full_size(tao, oracle_mod):
@@ -176,6 +187,28 @@ def test_config4_native_convolution_full_size(tao, oracle_mod):
     ratio = (flat / via_patches - 1).abs().max().item()
     print("native vs patch-matrix bound: max relative difference %.3e" % ratio, flush=True)
     assert ratio <= 1e-6
+
+
+def test_config4_convolution_on_the_bf16_matrix_cores_full_size(tao, oracle_mod):
+    """The conv stage as bench.py runs it: tao_bound_check_conv2d (patch matrix gathered and cut into BF16
+    pieces while loaded, check in the epilogue).  The stored bound against the oracle's direct loop on two
+    whole images, the profile against the two-pass route field for field, the honest claim accepted."""
+    op = tao_inputs.config4("cuda", scale=1)[0]
+    cv = op.attrs["conv"]
+    x, w = cv["x"], cv["w"]
+    assert tao.tao_conv2d_split_supported(tuple(x.shape), tuple(w.shape), 1, cv["padding"], 1)
+    tau = tao.tao_bound_conv2d_split(x, w, None, 1, cv["padding"], 1)
+    B, H, W, Cout = tau.shape
+    for b in (0, B - 1):
+        t_or = oracle_mod.bound_conv2d(_np(x[b:b + 1]), _np(w), None, (1, 1), (1, 1), (1, 1))
+        worst = assert_bound_parity(_np(tau[b:b + 1]), t_or, "conv on the BF16 cores, image %d" % b)
+        print("image %d: max tau_gpu/tau_oracle - 1 = %.3e" % (b, worst), flush=True)
+    y_ref = op.y_ref.contiguous().reshape(B, H, W, Cout)
+    claimed = op.claimed.contiguous().reshape(B, H, W, Cout)
+    two_pass = tao.tao_check_and_profile(claimed, y_ref, tau)
+    assert two_pass["violations"] == 0 and two_pass["n"] == y_ref.numel()
+    fused = tao.tao_bound_check_conv2d(x, w, None, y_ref, claimed, 1, cv["padding"], 1)
+    assert_profile_equal(fused, two_pass, "conv stage, check in the epilogue")
 
 
 def test_config5_stress_full_size(tao, oracle_mod):
