@@ -289,6 +289,28 @@ def timed_passes(torch, plan, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def graph_replay_ms(torch, tao, plan, steps):
+    """One pass of the plan captured into a HIP graph (the entry points only enqueue kernels) and replayed:
+    (ms per replay, violations seen by the last replay).  For the small configurations, whose pass is a few
+    dozen launches of 4 - 80 us, this takes the launch spacing of the eager loop out."""
+    for p in plan:
+        p.run(torch, False)                                   # every cached scratch buffer exists before the capture
+    torch.cuda.synchronize()
+    gph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(gph):
+        for p in plan:
+            p.run(torch, False)
+    for _ in range(3):
+        gph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        gph.replay()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    return ms, sum(tao.read_profile(p.prof)["violations"] for p in plan)
+
+
 def plan_summary(tao, plan, ms_per_pass, what):
     """Whole-pass figures of one configuration: throughput, the matmul bound against the FP32 MFMA peak
     (algorithmic flop) and the streaming operators against the HBM peak (algorithmic bytes)."""
@@ -493,6 +515,9 @@ def main():
         cplan = make_plan(torch, tao, cops, args)
         ms = timed_passes(torch, cplan, args.steps, args.warmup)
         res = plan_summary(tao, cplan, ms, what)
+        if c in (1, 2):
+            gms, gviol = graph_replay_ms(torch, tao, cplan, max(args.steps, 20))
+            res["hip_graph_replay"] = {"ms_per_pass": gms, "GB/s_verified": res["elements"] * 4 / (gms * 1e-3) / 1e9, "violations": gviol}
         del cplan, cops
         torch.cuda.empty_cache()
         return res
