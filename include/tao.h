@@ -166,7 +166,7 @@ int tao_linear_split_preferred(long M, long N, long K, long batch);
  * tau that tao_bound_linear_split computes from the same operands, but tau is compared in registers
  * in the matrix kernel's epilogue and only stored when `tau` is not NULL (layout ldy / strideY, like
  * y_ref and claimed: M x N per batch entry, ldy >= N).  Where the epilogue would cost more than it
- * saves -- reductions up to 1024 long with contiguous outputs -- the bound is stored instead (into
+ * saves -- reductions up to 1024 long with contiguous outputs that are not cut into parts -- the bound is stored instead (into
  * `tau`, else into the workspace) and the streaming check reads it: the same result, sooner.
  * y_ref: the verifier's re-executed output, claimed: the proposer's.  out: DEVICE, fully overwritten,
  * valid once the stream has drained.  ws / ws_bytes: DEVICE scratch of at least
@@ -211,9 +211,10 @@ int tao_bound_check_linear_images(const void *A_image, const void *W_image, cons
                                   tao_profile *out, void *ws, size_t ws_bytes, void *stream);
 size_t tao_check_linear_images_workspace_bytes(long M, long N, long K, long batch);
 
-/* 1 if tao_bound_check_linear checks a product of this shape (contiguous outputs) in the matrix
- * kernel's epilogue, 0 if it stores the bound and runs the streaming check.  Host only: for callers
- * that time or schedule the two kernels separately. */
+/* 1 if tao_bound_check_linear checks a product of this shape (contiguous outputs) without storing the
+ * bound -- in the matrix kernel's epilogue, or in the pass that adds the parts of a reduction cut into
+ * parts --, 0 if it stores the bound and runs the streaming check.  Host only: for callers that time or
+ * schedule the two kernels separately. */
 int tao_bound_check_linear_in_epilogue(long M, long N, long K, long batch);
 /* Probes v_mfma_f32_32x32x16_bf16 with `cases` seeded non-negative cases (0 = 3072; the model was
  * fitted on 280 000 of the same generator's kind, which a caller may ask for) and compares every

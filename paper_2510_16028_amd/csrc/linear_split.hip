@@ -53,6 +53,7 @@ constexpr int kBlock = 3 * kSlab;       // one operand, three pieces: 24576 byte
 constexpr int kSplitStage = 2 * kBlock; // |A| hi, mid, lo, |W| hi, mid, lo: 49152 bytes
 constexpr int kSplitStages = 3;         // 144 KB of LDS
 constexpr long kEpilogueCheckMinK = 1025; // shorter reductions (up to 1024, as far as the plain bound walks its tiles): the bound is stored and the streaming check reads it (see split_run)
+constexpr long kMinGroupsPerPart = 4;   // a reduction cut into parts: at least 128 k-steps each
 constexpr long kWalkMaxGroups = 32;     // reductions up to 1024 k-steps walk their tiles ...
 constexpr int kWalkMinTilesPerCu = 4;   // ... when a compute unit has at least this many
 
@@ -602,8 +603,15 @@ __global__ __launch_bounds__(kCheckThreads) void split_combine(SplitArgs p, long
     ThreadAcc acc;
     const int rep = threadIdx.x & (kReplicas - 1);
     const long per = p.M * p.N, total = per * batch;
+    const bool narrow = total < (1L << 32);                   // (64-bit divisions cost an order of magnitude more)
     for (long i = (long)blockIdx.x * kCheckThreads + threadIdx.x; i < total; i += (long)gridDim.x * kCheckThreads) {
-        const long z = i / per, rc = i - z * per, row = rc / p.N, col = rc - row * p.N;
+        long z, row, col;
+        if (narrow) {
+            const unsigned ui = (unsigned)i, uz = ui / (unsigned)per, rc = ui - uz * (unsigned)per, ur = rc / (unsigned)p.N;
+            z = uz; row = ur; col = rc - ur * (unsigned)p.N;
+        } else {
+            z = i / per; const long rc = i - z * per; row = rc / p.N; col = rc - row * p.N;
+        }
         double sv = 0.0;
         for (int k = 0; k < p.ksplit; ++k) sv += p.partial[(long)k * total + i];
         const double ab = p.bias ? fabs((double)p.bias[col]) : 0.0;
@@ -775,7 +783,7 @@ static int device_cus() {
     return cus;
 }
 // Parts the reduction is cut into: launches with fewer 128 x 128 tiles than compute units take as
-// many parts as fill the chip, each at least 16 groups (512 k-steps) long.
+// many parts as fill the chip, each at least kMinGroupsPerPart groups long.
 static int split_k_parts(long M, long N, long K, long batch) {
     if (M <= 0 || N <= 0 || K <= 0 || batch <= 0) return 1;
     const long tiles = ((M + STILE - 1) / STILE) * ((N + STILE - 1) / STILE) * batch;
@@ -783,7 +791,7 @@ static int split_k_parts(long M, long N, long K, long batch) {
     const long cus = device_cus();
     if (tiles >= cus) return 1;
     long parts = cus / tiles;
-    if (parts > groups / 16) parts = groups / 16;
+    if (parts > groups / kMinGroupsPerPart) parts = groups / kMinGroupsPerPart;
     if (parts > 16) parts = 16;
     return parts < 2 ? 1 : (int)parts;
 }
@@ -910,7 +918,8 @@ static int split_core(const unsigned short* A3, const unsigned short* W3, const 
         // wants it) and checked by that pass: the same results, field for field, 1 - 8 % sooner
         // (measured at K = 128 ... 1024); beyond, the two routes take the same time and the epilogue
         // saves the traffic of the stored bound.
-        two_pass = K < kEpilogueCheckMinK && !(md.flags & TAO_FLAG_CHECK_IN_EPILOGUE) &&
+        // (A reduction cut into parts is checked by the pass that adds the parts, whatever its length.)
+        two_pass = parts < 2 && K < kEpilogueCheckMinK && !(md.flags & TAO_FLAG_CHECK_IN_EPILOGUE) &&
                    chk->ldy == N && (batch == 1 || chk->strideY == M * N);
         if (two_pass && !tau) {
             tau = reinterpret_cast<float*>(wsb + partial_bytes + round_up_256(check_workspace_bytes()));
@@ -1016,7 +1025,7 @@ static int split_core(const unsigned short* A3, const unsigned short* W3, const 
         p.partial = reinterpret_cast<double*>(wsb);
         hipLaunchKernelGGL((absgemm_split<false, true>), dim3(p.ntiles * (unsigned)p.ksplit), dim3(kSplitThreads), lds_bytes, st, p);
         const long total = M * N * batch;
-        long want = (total + (long)kCheckThreads * 8 - 1) / ((long)kCheckThreads * 8);
+        long want = (total + (long)kCheckThreads * 2 - 1) / ((long)kCheckThreads * 2);   // (a few elements per thread: outputs that need parts are small)
         const int nblocks = (int)(want < 1 ? 1 : (want > kMaxCheckBlocks ? kMaxCheckBlocks : want));
         if (epi) {
             hipLaunchKernelGGL(split_combine<true>, dim3(nblocks), dim3(kCheckThreads), 0, st, p, batch);
@@ -1302,8 +1311,7 @@ size_t tao_bound_check_linear_workspace_bytes(long M, long N, long K, long batch
 }
 
 int tao_bound_check_linear_in_epilogue(long M, long N, long K, long batch) {
-    (void)M; (void)N; (void)batch;
-    return K >= tao::kEpilogueCheckMinK ? 1 : 0;
+    return (K >= tao::kEpilogueCheckMinK || tao::split_k_parts(M, N, K, batch) >= 2) ? 1 : 0;
 }
 
 int tao_bound_check_linear(const float* A, const float* W, const float* bias, const float* y_ref,

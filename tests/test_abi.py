@@ -156,13 +156,16 @@ def test_argument_validation_without_a_gpu(tao):
     operands = (4096 // 32) * (16 + 8) * 24576 + 2 * 512       # two images, 512 bytes of slack each
     assert L.tao_linear_split_workspace_bytes(2048, 1024, 4096, 1, 1) == (operands + 255) // 256 * 256 + 2 * 2048 * 1024 * 8
     assert L.tao_linear_split_workspace_bytes(2048, 4096, 4096, 1, 1) == (4096 // 32) * (16 + 32) * 24576 + 2 * 512   # 512 tiles: one part
-    assert L.tao_linear_split_workspace_bytes(2048, 1024, 256, 1, 1) == (256 // 32) * (16 + 8) * 24576 + 2 * 512     # too short to cut
+    operands = (256 // 32) * (16 + 8) * 24576 + 2 * 512          # 8 groups: two parts of four
+    assert L.tao_linear_split_workspace_bytes(2048, 1024, 256, 1, 1) == (operands + 255) // 256 * 256 + 2 * 2048 * 1024 * 8
+    assert L.tao_linear_split_workspace_bytes(2048, 1024, 96, 1, 1) == (96 // 32) * (16 + 8) * 24576 + 2 * 512       # too short to cut
     L.tao_linear_split_preferred.restype = ctypes.c_int
     assert L.tao_linear_split_preferred(2048, 1024, 4096, 1) == 1 and L.tao_linear_split_preferred(2048, 4096, 4096, 1) == 1
-    assert L.tao_linear_split_preferred(8192, 128, 2048, 8) == 1 and L.tao_linear_split_preferred(512, 1024, 1024, 1) == 0
+    assert L.tao_linear_split_preferred(8192, 128, 2048, 8) == 1 and L.tao_linear_split_preferred(128, 1024, 1024, 1) == 0
     assert L.tao_linear_split_preferred(8192, 128, 1024, 8) == 0 and L.tao_linear_split_preferred(2048, 128, 2048, 8) == 0
     assert L.tao_bound_check_linear_in_epilogue(2048, 4096, 4096, 1) == 1 and L.tao_bound_check_linear_in_epilogue(8192, 2048, 128, 8) == 0
-    assert L.tao_bound_check_linear_in_epilogue(64, 64, 1024, 1) == 0 and L.tao_bound_check_linear_in_epilogue(64, 64, 1025, 1) == 1
+    assert L.tao_bound_check_linear_in_epilogue(64, 64, 96, 1) == 0 and L.tao_bound_check_linear_in_epilogue(64, 64, 1025, 1) == 1
+    assert L.tao_bound_check_linear_in_epilogue(64, 64, 1024, 1) == 1       # cut into parts: checked by the pass that adds them
     big = ctypes.c_void_p(0x100000)
     assert L.tao_bound_linear_split(p, p, nul, p, *args(4, 4, 8, 4, 8, 4), None, big, wsb, None) == tao.ERR_SHAPE
     assert L.tao_bound_linear_split(p, p, nul, p, *args(4, 4, 8, 8, 8, 4), None, nul, wsb, None) == tao.ERR_WORKSPACE

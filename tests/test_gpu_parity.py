@@ -63,7 +63,8 @@ def test_bf16_matrix_core_selftest(tao):
     assert tao.tao_linear_split_preferred(2048, 4096, 4096) and not tao.tao_linear_split_preferred(2048, 128, 2048, 8)
     # one column tile pays when A can be split while it is loaded (enough tiles, a long reduction of whole groups)
     assert tao.tao_linear_split_preferred(8192, 128, 2048, 8) and not tao.tao_linear_split_preferred(8192, 128, 2040, 8)
-    assert not tao.tao_linear_split_preferred(512, 768, 768)
+    # few tiles: preferred where the reduction, cut into parts, fills the chip
+    assert tao.tao_linear_split_preferred(512, 768, 768) and not tao.tao_linear_split_preferred(128, 768, 768)
 
 
 def test_config1_linear_and_softmax(tao, oracle_mod):
