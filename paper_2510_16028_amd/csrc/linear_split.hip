@@ -603,15 +603,11 @@ __global__ __launch_bounds__(kCheckThreads) void split_combine(SplitArgs p, long
     ThreadAcc acc;
     const int rep = threadIdx.x & (kReplicas - 1);
     const long per = p.M * p.N, total = per * batch;
-    const bool narrow = total < (1L << 32);                   // (64-bit divisions cost an order of magnitude more)
+    // (total < 2^32: a reduction is cut into parts only where the tiles are fewer than the compute units;
+    // 64-bit divisions would cost an order of magnitude more)
     for (long i = (long)blockIdx.x * kCheckThreads + threadIdx.x; i < total; i += (long)gridDim.x * kCheckThreads) {
-        long z, row, col;
-        if (narrow) {
-            const unsigned ui = (unsigned)i, uz = ui / (unsigned)per, rc = ui - uz * (unsigned)per, ur = rc / (unsigned)p.N;
-            z = uz; row = ur; col = rc - ur * (unsigned)p.N;
-        } else {
-            z = i / per; const long rc = i - z * per; row = rc / p.N; col = rc - row * p.N;
-        }
+        const unsigned ui = (unsigned)i, uz = ui / (unsigned)per, rc = ui - uz * (unsigned)per, ur = rc / (unsigned)p.N;
+        const long z = uz, row = ur, col = rc - ur * (unsigned)p.N;
         double sv = 0.0;
         for (int k = 0; k < p.ksplit; ++k) sv += p.partial[(long)k * total + i];
         const double ab = p.bias ? fabs((double)p.bias[col]) : 0.0;
@@ -1020,6 +1016,7 @@ static int split_core(const unsigned short* A3, const unsigned short* W3, const 
     if (parts >= 2) {
         // the reduction in parts, then one pass that adds them and forms (and checks) the bound
         const long groups = Kp / SBK;
+        if (M * N * batch >= (1L << 32)) return TAO_ERR_SHAPE;      // (cannot happen: fewer tiles than compute units)
         p.ksplit = parts; p.gpp = (groups + parts - 1) / parts;
         p.ksplit = (int)((groups + p.gpp - 1) / p.gpp);             // no empty part
         p.partial = reinterpret_cast<double*>(wsb);
