@@ -99,7 +99,7 @@ def test_config5_stress_scaled(tao, oracle_mod):
     assert po["violations"] == int((cls == 2).sum())            # the 1.01x class, known from the seed
     pg = tao.tao_check_and_profile(claimed.cuda(), ref.cuda(), torch.from_numpy(t_or).cuda())
     assert_profile_equal(pg, po, "c5 check")
-    # the GPU's own bound gives the same verdict counts: 1 % margins >> 1e-6 tolerance
+    # the GPU's own bound gives the same violation counts: 1 % margins >> 1e-6 tolerance
     pe = tao.tao_check_and_profile(claimed.cuda(), ref.cuda(), t_gpu)
     assert pe["violations"] == po["violations"]
 
