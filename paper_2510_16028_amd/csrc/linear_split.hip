@@ -165,7 +165,7 @@ struct SplitArgs {
     unsigned ntiles; int ksplit; long gpp;
     double* partial;
     // workgroup -> tile: slots per super-tile (8 patches of ph x pw tiles), per batch entry, patches side by side
-    unsigned slots, slots_per_z, super_rows, pw, ph, npx;
+    unsigned slots, slots_per_z, super_rows, pw, ph, npx, linear;
     // AREG instantiations: the binary32 A operand itself (row stride lda, batch stride strideA, in
     // elements); A3 is then unused
     const float* Af; long lda, strideA;
@@ -235,6 +235,11 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
     unsigned m0 = 0, n0 = 0, z = 0;                          // first row and column of the tile, batch entry
     auto locate = [&](unsigned t, unsigned& tm0, unsigned& tn0, unsigned& tz) __attribute__((always_inline)) -> bool {
         const unsigned zp = t / p.slots_per_z, bb = t - zp * p.slots_per_z;
+        if (p.linear) {                                      // fewer tiles than compute units: row by row, no empty slot
+            const unsigned ty = bb / p.tiles_n, tx = bb - ty * p.tiles_n;
+            tn0 = tx * STILE; tm0 = ty * STILE; tz = zp;
+            return true;
+        }
         const unsigned sup = bb / p.slots, w8 = bb - sup * p.slots;
         const unsigned xcd = w8 & 7u, j = w8 >> 3;
         const unsigned ly = (xcd / p.npx) * p.ph + j / p.pw, lx = (xcd % p.npx) * p.pw + j % p.pw;
@@ -995,7 +1000,12 @@ static int split_core(const unsigned short* A3, const unsigned short* W3, const 
         p.ph = (gh + npy - 1) / npy;
         p.slots = 8 * p.ph * p.pw;
         p.super_rows = (unsigned)((tiles_m + 15) / 16);
-        const long per_z = (long)p.super_rows * ((tiles_n + 15) / 16) * p.slots;
+        long per_z = (long)p.super_rows * ((tiles_n + 15) / 16) * p.slots;
+        // A patch pattern that leaves slots empty costs a launch of less than one round dearly (an empty
+        // workgroup still has to be given a compute unit's LDS before it can leave): such launches, whose
+        // tiles all run at once anyway, take their tiles row by row.
+        p.linear = (tiles_m * tiles_n < per_z && tiles_m * tiles_n < (long)device_cus()) ? 1u : 0u;
+        if (p.linear) per_z = tiles_m * tiles_n;
         if (per_z * batch * 16 >= (1L << 31)) return TAO_ERR_SHAPE;
         p.slots_per_z = (unsigned)per_z;
         p.ntiles = (unsigned)(per_z * batch);                        // workgroups of one part
