@@ -158,8 +158,10 @@ int tao_bound_linear_split(const float *A, const float *W, const float *bias, fl
                            long batch, long strideA, long strideW, long strideT,
                            const tao_fp_model *model, void *ws, size_t ws_bytes, void *stream);
 size_t tao_linear_split_workspace_bytes(long M, long N, long K, long batch, int shared_w);
-/* 1 when the BF16 path is expected to be the faster one for this shape on the current device
- * (enough 128 x 128 tiles to fill it, both output extents at least 256), else 0.  Host only. */
+/* 1 when the BF16 path is expected to be the faster one for this shape on the current device (its
+ * 128 x 128 tiles, times the parts a long reduction is cut into when they are few, fill the device;
+ * at least 256 rows; 256 columns, or 128 with a long reduction of whole 32-step groups, or 64 where
+ * the tiles are few enough for four parts), else 0.  Measured rule of thumb.  Host only. */
 int tao_linear_split_preferred(long M, long N, long K, long batch);
 /* The bound of tao_bound_linear_split checked on the spot (Sec. 5.4 leaf check, Sec. 5.3 profile):
  * *out receives exactly what tao_check_and_profile(claimed, y_ref, tau, ...) would return for the

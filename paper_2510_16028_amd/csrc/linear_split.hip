@@ -851,8 +851,13 @@ int tao_linear_split_preferred(long M, long N, long K, long batch) {
     if (M <= 0 || N <= 0 || K <= 0 || batch <= 0) return 0;
     const long tiles = ((M + tao::STILE - 1) / tao::STILE) * ((N + tao::STILE - 1) / tao::STILE) * batch;
     // (a single column tile pays when its A operand can be split while it is loaded: a long reduction of whole groups)
+    // (even half a column tile pays where the tiles are so few that the reduction is cut into four parts or more:
+    // bound and check of 12 x 512 x 64 outputs over K = 512 take 0.041 against 0.054 ms, of 4096 x 128 over K = 4096
+    // 0.087 against 0.208 ms; with 128 tiles in two parts -- 8 x 2048 x 128 over K = 2048 -- the pre-pass over A still
+    // outweighs the gain: 0.170 against 0.132 ms)
     const bool n_ok = N >= 2 * tao::STILE || (N >= tao::STILE && K % tao::SBK == 0 && K / tao::SBK > tao::kWalkMaxGroups &&
-                                              tao::split_k_parts(M, N, K, batch) < 2);
+                                              tao::split_k_parts(M, N, K, batch) < 2) ||
+                      (N >= tao::STILE / 2 && tao::split_k_parts(M, N, K, batch) >= 4);
     // (a long reduction cut into parts also pays on half the chip: the FP32 path would leave its few
     // tiles on as few compute units for the whole reduction -- measured 0.092 against 0.147 ms on
     // 512 x 768 x 3072, where shorter reductions of that size stay faster on the FP32 path)
