@@ -152,8 +152,10 @@ struct SplitArgs {
     long M, N, Kp, ldt, strideT;
     long batchA3, batchW3;            // elements between batch entries (0 for a shared W)
     unsigned tiles_n, tiles_m;
-    double c, infl, uflow;
-    double sabs, sabs0;               // absolute part of the accumulation's error, for a positive / an exactly zero sum
+    // tau = Gamma ((S + s) infl + |bias|) guard + underflow, with s the absolute part of the accumulation's
+    // error (for a positive / for an exactly zero sum), as host-folded constants, each rounded up:
+    // tau = fma(S, c1, fma(cg, (S > 0 ? si : si0) + |bias|, uflow))
+    double c1, cg, si, si0, uflow;
     // CHECK instantiation: the claimed and the re-executed output (layout ldy / strideY), the check's
     // parameters and the partial results of the leaf check in the caller's workspace
     const float* claimed; const float* ref;
@@ -174,6 +176,14 @@ struct SplitArgs {
     // channels of one filter tap (C a multiple of 32)
     int cH, cW, cC, cOW, cS, csh, csw, cph, cpw, cdh, cdw; unsigned cohow;
 };
+
+// The constant term of the bound for a column with |bias| = ab, and the bound of a sum S (SplitArgs).
+__device__ __forceinline__ double bound_offset(const SplitArgs& p, double s_abs, double ab) {
+    return fma(p.cg, s_abs + ab, p.uflow);
+}
+__device__ __forceinline__ double bound_of_sum(const SplitArgs& p, double sv, double off_pos, double off_zero) {
+    return fma(sv, p.c1, sv > 0.0 ? off_pos : off_zero);
+}
 
 // check_one with the histogram layout of the CHECK instantiation below (16-bit counters, bin b in
 // half b & 1 of word (b >> 1) * 4 + copy).
@@ -530,6 +540,7 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
         for (int tj = 0; tj < 2; ++tj) {
             const long col = (long)ne + ecol + tj * 32;
             const double ab = fabs((double)bias_c[tj]);
+            const double off_pos = bound_offset(p, p.si, ab), off_zero = bound_offset(p, p.si0, ab);
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const long row = (long)me + erow + 8 * (v >> 2) + (v & 3);
@@ -538,9 +549,7 @@ __global__ __launch_bounds__(kSplitThreads) void absgemm_split(SplitArgs p) {
                     continue;
                 }
                 if (row < p.M && col < p.N) {
-                    const double sv = S[tj][v];
-                    const double tt = p.c * ((sv + (sv > 0.0 ? p.sabs : p.sabs0)) * p.infl + ab) * kGuard + p.uflow;
-                    const float t32 = up32(tt);
+                    const float t32 = up32(bound_of_sum(p, S[tj][v], off_pos, off_zero));
                     if (!CHECK) {
                         T[row * p.ldt + col] = t32;
                     } else {
@@ -616,8 +625,7 @@ __global__ __launch_bounds__(kCheckThreads) void split_combine(SplitArgs p, long
         double sv = 0.0;
         for (int k = 0; k < p.ksplit; ++k) sv += p.partial[(long)k * total + i];
         const double ab = p.bias ? fabs((double)p.bias[col]) : 0.0;
-        const double tt = p.c * ((sv + (sv > 0.0 ? p.sabs : p.sabs0)) * p.infl + ab) * kGuard + p.uflow;
-        const float t32 = up32(tt);
+        const float t32 = up32(bound_of_sum(p, sv, bound_offset(p, p.si, ab), bound_offset(p, p.si0, ab)));
         if (p.tau) p.tau[z * p.strideT + row * p.ldt + col] = t32;
         if (CHECK) {
             const long y = z * p.strideY + row * p.ldy + col;
@@ -949,22 +957,26 @@ static int split_core(const unsigned short* A3, const unsigned short* W3, const 
     p.M = M; p.N = N; p.Kp = Kp; p.ldt = ldt; p.strideT = strideT;
     p.batchA3 = (Kp / SBK) * blocksA * (kBlock / 2); p.batchW3 = shared_w ? 0 : (Kp / SBK) * blocksW * (kBlock / 2);
     p.tiles_n = (unsigned)tiles_n; p.tiles_m = (unsigned)tiles_m;
-    p.c = c;
     const double u = md.u;
     // lower factor of the accumulation: (1 - 11.5u) for the matrix-core steps (10u main, 1.44u
     // cross, rounded up), 2^-53 per binary64 addition (three per 32 k-steps and output element)
     const double f64 = (double)(3 * (Kp / SBK) + 4 + 16);             // + the additions of up to 16 parts
     const double lower = (1.0 - 11.5 * u) * (1.0 - f64 * 0x1p-53);
-    p.infl = widen(1.0 / (lower * (1.0 - 0x1p-52)));
-    p.uflow = (md.flags & TAO_FLAG_UNDERFLOW_TERMS) ? (double)Kp_ * 0x1p-149 : 0.0;
+    const double infl = widen(1.0 / (lower * (1.0 - 0x1p-52)));
+    p.uflow = (md.flags & TAO_FLAG_UNDERFLOW_TERMS) ? widen((double)Kp_ * 0x1p-149) : 0.0;
     // Results in the binary32 subnormal range: the instruction keeps subnormal operands, products
     // and sums (gradual underflow) and then errs absolutely, by less than one step of 2^-149 per
     // instruction (probed like the model above: 160 000 cases with products between 2^-160 and
     // 2^-120); two steps are budgeted for each of the 16 instructions an output element sees per
     // 32 k-steps.  Added to every positive sum; to an exactly zero sum only when the caller asked for
     // underflow terms (otherwise such a sum is taken as the exact zero of zero operands).
-    p.sabs = K > 0 ? ((double)Kp + 32.0) * 0x1p-149 : 0.0;
-    p.sabs0 = (md.flags & TAO_FLAG_UNDERFLOW_TERMS) ? p.sabs : 0.0;
+    const double sabs = K > 0 ? ((double)Kp + 32.0) * 0x1p-149 : 0.0;
+    // The folded constants; every product is rounded up with room for the two or three roundings of its
+    // evaluation on the device, and the guard factor (2^-32) stays far above all of them.
+    p.c1 = widen(c * infl * kGuard);
+    p.cg = widen(c * kGuard);
+    p.si = widen(sabs * infl);
+    p.si0 = (md.flags & TAO_FLAG_UNDERFLOW_TERMS) ? p.si : 0.0;
 
     constexpr int lds_bytes = kSplitStages * kSplitStage;
     static OncePerDevice configured;      // the dynamic LDS limit of the three instantiations, once per device
