@@ -156,6 +156,39 @@ def test_config3_matmuls_through_the_bf16_split_path(tao, oracle_mod):
     assert taken >= 9
 
 
+def test_config2_matmuls_through_the_bf16_split_path(tao, oracle_mod):
+    """The BERT-sized products the library's rule sends to the BF16 path (few tiles: the reduction cut into
+    parts, tiles taken row by row, the check in the pass that adds the parts), as bench.py runs them: sampled
+    rows against the oracle, the profile against the stored bound and the streaming check."""
+    ops = [op for op in tao_inputs.config2("cuda", scale=1) if op.kind == "linear"]
+    taken = 0
+    for idx, op in enumerate(ops):
+        A, W = op.args["A"], op.args["W"]
+        batch = A.shape[0] if A.dim() == 3 else 1
+        M, N, K = op.y_ref.shape[-2], op.y_ref.shape[-1], A.shape[-1]
+        if not tao.tao_linear_split_preferred(M, N, K, batch):
+            continue
+        taken += 1
+        tw = bool(op.attrs.get("trans_w", 0))
+        print("op", op.name, (batch, M, N, K), flush=True)
+        tau = tao.tao_bound_linear_split(A, W, op.args.get("bias"), trans_w=tw)
+        p = tao.tao_check_and_profile(op.claimed.contiguous(), op.y_ref.contiguous(), tau)
+        assert p["violations"] == 0 and p["n"] == op.y_ref.numel(), op.name
+        fused = tao.tao_bound_check_linear(A, W, op.args.get("bias"), op.y_ref.contiguous(), op.claimed.contiguous(), trans_w=tw)
+        assert_profile_equal(fused, p, op.name + " (checked by the pass that adds the parts)")
+        rows = _sample_rows(M, 13, 900 + idx)
+        b = (idx % batch) if A.dim() == 3 else None
+        sub = _sub_op(op, rows, b)
+        t_or = oracle_tau(oracle_mod, sub)
+        worst = assert_bound_parity(_np(_tau_rows(tau, op, rows, b)), t_or, op.name + " (bf16 split, parts)")
+        print("   sampled %d rows: max tau_gpu/tau_oracle - 1 = %.3e" % (len(rows), worst), flush=True)
+        if A.dim() == 2 and not tw:
+            a_img, w_img = tao.tao_split_operand(A), tao.tao_split_operand(W)
+            assert torch.equal(tao.tao_bound_linear_images(a_img, w_img, M, N, K, bias=op.args.get("bias")), tau)
+        del tau
+    assert taken >= 4
+
+
 def test_config2_bert_block_full_size(tao, oracle_mod):
     ops = tao_inputs.config2("cuda", scale=1)
     _check_ops_sampled(tao, oracle_mod, ops, nsample=13, seed=200)
