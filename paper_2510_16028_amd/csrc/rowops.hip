@@ -271,6 +271,17 @@ __global__ __launch_bounds__(kCheckThreads) void softmax_check(
             const float4 Y = CACHED ? yv[v] : load4(y + roff, idx, limit, vec_ok, 0.f);
             const float4 C = load4<true>(claimed + roff, idx, limit, vec_ok, 0.f);
             const float xe[4] = {X.x, X.y, X.z, X.w}, ye[4] = {Y.x, Y.y, Y.z, Y.w}, ce[4] = {C.x, C.y, C.z, C.w};
+            if (idx + 3 < limit) {                           // a whole vector: four chains side by side
+                float te[4];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    double q, rho;
+                    q_rho(xe[c], ye[c], q, rho);
+                    te[c] = up32g(q * fma(rho, w1, w0), up.mul, up.sub);
+                }
+                check_four(ce, ye, te, alpha, eps_rel, hist, rep, acc_chk);
+                continue;
+            }
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 if (idx + c >= limit) break;

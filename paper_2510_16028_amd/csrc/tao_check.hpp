@@ -52,6 +52,35 @@ __device__ __forceinline__ CheckedElement check_arith(float c, float r, float t,
     return o;
 }
 
+// Four elements at once, as straight-line code: the four chains of dependent binary64 operations are
+// independent of one another, so the compiler interleaves them and a wavefront does not sit out the
+// latency of every operation of every element in turn (element by element, each behind its own test
+// for the shortcut, that is what happened).  The shortcut is taken for the four together or not at
+// all; the full arithmetic returns the shortcut's result for an element that qualifies (d = 0, e = 0 or
+// 0/0), so the profile does not depend on the route.
+template <int R = kReplicas>
+__device__ __forceinline__ void check_four(const float (&c)[4], const float (&r)[4], const float (&t)[4], double alpha,
+                                           double eps_rel, unsigned int* hist, int rep, ThreadAcc& acc) {
+    bool same = true;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) same = same && c[i] == r[i] && fabsf(c[i]) != INFINITY;
+    CheckedElement o[4];
+    if (same) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = check_arith<true>(c[i], r[i], t[i], alpha, eps_rel);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) o[i] = check_arith<false>(c[i], r[i], t[i], alpha, eps_rel);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        acc.violations += o[i].violation;
+        acc.nans += o[i].is_nan;
+        acc.max_bits = max(acc.max_bits, o[i].is_nan ? 0u : o[i].bits);
+        atomicAdd(&hist[o[i].bin * R + rep], 1u);
+    }
+}
+
 // R: copies of every bin in the LDS histogram `hist` (copy `rep` is used).
 template <int R = kReplicas>
 __device__ __forceinline__ void check_one(float c, float r, float t, double alpha, double eps_rel,
