@@ -484,7 +484,7 @@ __global__ __launch_bounds__(kRowThreads) void groupnorm_sums_a(const float* __r
     double a[2] = {0.0, 0.0};
 #pragma unroll
     for (int v = 0; v < kChunkVecs; ++v) {
-        const float4 X = load4<true>(xr, ((long)v * kRowThreads + threadIdx.x) * 4, p.limit, vec_ok, 0.f);
+        const float4 X = load4<false>(xr, ((long)v * kRowThreads + threadIdx.x) * 4, p.limit, vec_ok, 0.f);
         const float e[4] = {X.x, X.y, X.z, X.w};
 #pragma unroll
         for (int c = 0; c < 4; ++c) { a[0] += (double)e[c]; a[1] += (double)fabsf(e[c]); }
@@ -504,7 +504,7 @@ __global__ __launch_bounds__(kRowThreads) void groupnorm_sums_b(const float* __r
 #pragma unroll
     for (int v = 0; v < kChunkVecs; ++v) {
         const long idx = ((long)v * kRowThreads + threadIdx.x) * 4;
-        const float4 X = load4<true>(xr, idx, p.limit, vec_ok, 0.f);
+        const float4 X = load4<false>(xr, idx, p.limit, vec_ok, 0.f);
         const float e[4] = {X.x, X.y, X.z, X.w};
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
