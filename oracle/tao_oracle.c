@@ -27,8 +27,10 @@
  * templates, and an exact order-statistic cross-check of the histogram
  * percentiles.  Templates the paper names but does not print (LayerNorm,
  * RMSNorm, BatchNorm-affine, GELU, SiLU, mean) are derived from the primitive
- * rule of Sec. 3.1; they are pinned by soundness and closed-form special cases
- * only ("parity unpinned by the paper" for their exact constants).
+ * rule of Sec. 3.1: "parity unpinned by the paper" for their exact constants.
+ * They are pinned from below by soundness (brute force over executions) and
+ * from above by the first-order worst case of the canonical algorithm under the
+ * model of App. A.1, derived independently of the chains written here.
  */
 #include <fenv.h>
 #include <math.h>
