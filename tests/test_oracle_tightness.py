@@ -167,3 +167,32 @@ def test_gelu_and_silu_bounds_against_the_first_order_worst_case(oracle_mod):
         worst_s, best_s = max(worst_s, r), min(best_s, r)
     assert 1 - 1e-5 <= best_g <= 1.01 and worst_g <= 1.4, (best_g, worst_g)
     assert 1 - 1e-5 <= best_s <= 1.01 and worst_s <= 2.0 + 1e-3, (best_s, worst_s)
+
+
+def test_gelu_tanh_bound_against_the_first_order_worst_case(oracle_mod):
+    """GELU, tanh form: p = sqrt(2/pi)(x + 0.044715 x^3) through seven roundings (five operations, the two
+    constants), tanh within c_tanh u, fl(1 + tanh), fl(0.5 x . ).  The template charges all seven roundings
+    on |p| although the cubic term carries four of them at a small weight for small |x|, and bounds |tanh|
+    by min(1, |p|): ratio 1.00 - 1.51."""
+    o = oracle_mod
+    kap, c3 = mp.sqrt(2 / mp.pi), mp.mpf("0.044715")
+    worst, best = 0.0, 10.0
+    for xv in np.linspace(-5, 5, 51).astype(f32):
+        if xv == 0:
+            continue
+        x = _m(xv)
+
+        def gelu(d):
+            k, c = kap * (1 + d[0]), c3 * (1 + d[1])
+            x2 = (x * x) * (1 + d[2])
+            x3 = (x2 * x) * (1 + d[3])
+            t = (c * x3) * (1 + d[4])
+            s = (x + t) * (1 + d[5])
+            p = (k * s) * (1 + d[6])
+            th = mp.tanh(p) * (1 + d[7])
+            return [(x / 2 * ((1 + th) * (1 + d[8]))) * (1 + d[9])]
+        y = np.array([float(gelu([mp.mpf(0)] * 10)[0])], f32)
+        fo = _first_order(gelu, [1, 1, 1, 1, 1, 1, 1, 4, 1, 1], 1)[0]
+        r = float(_m(o.bound_act(o.GELU_TANH, np.array([xv], f32), y)[0]) / fo)
+        worst, best = max(worst, r), min(best, r)
+    assert 1 - 1e-5 <= best <= 1.01 and worst <= 1.56, (best, worst)
